@@ -1,0 +1,321 @@
+"""ctypes front end of the CPU oracle (oracle/ckks_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this
+package; the HIP library and its binding never do.  Besides thin wrappers of the C
+functions it holds the harness-side steps the key-switch path itself does not
+export: lifting a small signed polynomial to RNS limbs, switching-key
+generation (from random draws handed in by the caller) and the
+decrypt-and-bound noise check.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ckks_oracle.c")
+_LIB = os.path.join(_HERE, "libckks_oracle.so")
+
+_u64 = ctypes.c_uint64
+_u32 = ctypes.c_uint32
+_p = ctypes.c_void_p
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over limbs)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        for name in ("orc_mulmod", "orc_addmod", "orc_submod", "orc_powmod"):
+            f = getattr(_lib, name)
+            f.restype, f.argtypes = _u64, [_u64, _u64, _u64]
+        _lib.orc_invmod.restype, _lib.orc_invmod.argtypes = _u64, [_u64, _u64]
+        _lib.orc_min_psi.restype, _lib.orc_min_psi.argtypes = _u64, [_u64, _u32]
+        _lib.orc_ntt_def_at.restype = _u64
+        _lib.orc_ntt_def_at.argtypes = [_p, _u32, _u64, _u64, _u32]
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"], "oracle buffers must be contiguous"
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _arr_u64(v: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.array([int(x) for x in v], dtype=np.uint64))
+
+
+# ------------------------------------------------------------------ parameters
+class Params:
+    """Primes (q's then p's) and the minimal primitive 2N-th roots the oracle derives itself."""
+
+    def __init__(self, logN: int, L: int, K: int, dnum: int, primes: Sequence[int],
+                 psi: Optional[Sequence[int]] = None):
+        assert len(primes) == L + K
+        assert dnum >= 1 and L % dnum == 0
+        self.logN, self.L, self.K, self.dnum = logN, L, K, dnum
+        self.N = 1 << logN
+        self.alpha = L // dnum
+        self.primes = [int(p) for p in primes]
+        self.psi = [int(x) for x in psi] if psi is not None else [min_psi(p, logN) for p in self.primes]
+        self._primes = _arr_u64(self.primes)
+        self._psi = _arr_u64(self.psi)
+
+    @classmethod
+    def from_set(cls, ps) -> "Params":
+        return cls(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+
+    def _tail(self):
+        return (_u32(self.logN), _u32(self.L), _u32(self.K), _u32(self.dnum), _ptr(self._primes), _ptr(self._psi))
+
+
+# --------------------------------------------------------------------- scalars
+def mulmod(a, b, m):
+    return int(lib().orc_mulmod(int(a), int(b), int(m)))
+
+
+def powmod(a, e, m):
+    return int(lib().orc_powmod(int(a), int(e), int(m)))
+
+
+def invmod(a, m):
+    return int(lib().orc_invmod(int(a), int(m)))
+
+
+def min_psi(m: int, logN: int) -> int:
+    return int(lib().orc_min_psi(int(m), int(logN)))
+
+
+# ------------------------------------------------------------------ transforms
+def ntt_def(x: np.ndarray, logN: int, m: int, psi: int) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    out = np.empty_like(x)
+    lib().orc_ntt_def(_ptr(x), _ptr(out), _u32(logN), _u64(m), _u64(psi))
+    return out
+
+
+def ntt_def_at(x: np.ndarray, logN: int, m: int, psi: int, j: int) -> int:
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    return int(lib().orc_ntt_def_at(_ptr(x), logN, m, psi, j))
+
+
+def ntt(x: np.ndarray, logN: int, m: int, psi: int) -> np.ndarray:
+    out = np.array(x, dtype=np.uint64, copy=True, order="C")
+    lib().orc_ntt(_ptr(out), _u32(logN), _u64(m), _u64(psi))
+    return out
+
+
+def intt(x: np.ndarray, logN: int, m: int, psi: int) -> np.ndarray:
+    out = np.array(x, dtype=np.uint64, copy=True, order="C")
+    lib().orc_intt(_ptr(out), _u32(logN), _u64(m), _u64(psi))
+    return out
+
+
+def ntt_batch(x: np.ndarray, P: Params, prime_first: int, inverse: bool = False) -> np.ndarray:
+    """x: [batch][n_limbs][N] (or [n_limbs][N]); limb l uses prime prime_first + l."""
+    out = np.array(x, dtype=np.uint64, copy=True, order="C")
+    n_limbs = out.shape[-2]
+    batch = int(np.prod(out.shape[:-2])) if out.ndim > 2 else 1
+    pr = _arr_u64(P.primes[prime_first:prime_first + n_limbs])
+    ps = _arr_u64(P.psi[prime_first:prime_first + n_limbs])
+    lib().orc_ntt_batch(_ptr(out), _u32(P.logN), _u32(n_limbs), _u32(batch), _ptr(pr), _ptr(ps),
+                        ctypes.c_int(1 if inverse else 0))
+    return out
+
+
+# ------------------------------------------------------------- base conversion
+def conv(x: np.ndarray, src: Sequence[int], b: int) -> np.ndarray:
+    """x: [len(src)][N] -> [N] residues modulo b (uncorrected fast base conversion)."""
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    n = x.shape[-1]
+    out = np.empty(n, dtype=np.uint64)
+    s = _arr_u64(src)
+    lib().orc_conv(_ptr(x), ctypes.c_size_t(n), ctypes.c_size_t(n), _ptr(s), _u32(len(src)), _u64(b), _ptr(out))
+    return out
+
+
+def modup(x: np.ndarray, P: Params) -> np.ndarray:
+    """[L][N] coefficient form -> [dnum][L+K][N] coefficient form."""
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    out = np.empty((P.dnum, P.L + P.K, P.N), dtype=np.uint64)
+    lib().orc_modup(_ptr(x), _ptr(out), _u32(P.logN), _u32(P.L), _u32(P.K), _u32(P.dnum), _ptr(P._primes))
+    return out
+
+
+def moddown(x: np.ndarray, P: Params) -> np.ndarray:
+    """[L+K][N] coefficient form -> [L][N] coefficient form."""
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    out = np.empty((P.L, P.N), dtype=np.uint64)
+    lib().orc_moddown(_ptr(x), _ptr(out), _u32(P.logN), _u32(P.L), _u32(P.K), _ptr(P._primes))
+    return out
+
+
+# ---------------------------------------------------------------- automorphism
+def automorph_coeff(x: np.ndarray, logN: int, m: int, g: int) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    out = np.empty_like(x)
+    lib().orc_automorph_coeff(_ptr(x), _ptr(out), _u32(logN), _u64(m), _u32(g))
+    return out
+
+
+def automorph_eval(x: np.ndarray, logN: int, g: int) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    out = np.empty_like(x)
+    lib().orc_automorph_eval(_ptr(x), _ptr(out), _u32(logN), _u32(g))
+    return out
+
+
+def automorph_limbs(x: np.ndarray, P: Params, prime_first: int, g: int, eval_domain: bool) -> np.ndarray:
+    """Apply sigma_g to every limb of [..., n_limbs, N]; limb l uses prime prime_first + l."""
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    flat = x.reshape(-1, x.shape[-2], x.shape[-1])
+    out = np.empty_like(flat)
+    for b in range(flat.shape[0]):
+        for l in range(flat.shape[1]):
+            if eval_domain:
+                out[b, l] = automorph_eval(flat[b, l], P.logN, g)
+            else:
+                out[b, l] = automorph_coeff(flat[b, l], P.logN, P.primes[prime_first + l], g)
+    return out.reshape(x.shape)
+
+
+# ---------------------------------------------------------------- compositions
+def keyswitch(d: np.ndarray, key: np.ndarray, P: Params) -> np.ndarray:
+    """d [L][N] eval, key [dnum][2][L+K][N] eval -> [2][L][N] eval."""
+    d = np.ascontiguousarray(d, dtype=np.uint64)
+    key = np.ascontiguousarray(key, dtype=np.uint64)
+    assert d.shape == (P.L, P.N) and key.shape == (P.dnum, 2, P.L + P.K, P.N)
+    out = np.empty((2, P.L, P.N), dtype=np.uint64)
+    lib().orc_keyswitch(_ptr(d), _ptr(key), _ptr(out), *P._tail())
+    return out
+
+
+def hmult_relin(ct1: np.ndarray, ct2: np.ndarray, evk: np.ndarray, P: Params) -> np.ndarray:
+    ct1 = np.ascontiguousarray(ct1, dtype=np.uint64)
+    ct2 = np.ascontiguousarray(ct2, dtype=np.uint64)
+    evk = np.ascontiguousarray(evk, dtype=np.uint64)
+    assert ct1.shape == ct2.shape == (2, P.L, P.N) and evk.shape == (P.dnum, 2, P.L + P.K, P.N)
+    out = np.empty((2, P.L, P.N), dtype=np.uint64)
+    lib().orc_hmult_relin(_ptr(ct1), _ptr(ct2), _ptr(evk), _ptr(out), *P._tail())
+    return out
+
+
+def hrot(ct: np.ndarray, g: int, rk: np.ndarray, P: Params) -> np.ndarray:
+    ct = np.ascontiguousarray(ct, dtype=np.uint64)
+    rk = np.ascontiguousarray(rk, dtype=np.uint64)
+    assert ct.shape == (2, P.L, P.N) and rk.shape == (P.dnum, 2, P.L + P.K, P.N)
+    out = np.empty((2, P.L, P.N), dtype=np.uint64)
+    lib().orc_hrot(_ptr(ct), _u32(g), _ptr(rk), _ptr(out), *P._tail())
+    return out
+
+
+def hrot_hoisted_mac(ct: np.ndarray, galois: Sequence[int], rks: Sequence[np.ndarray], pt: np.ndarray,
+                     P: Params, want_per_rotation: bool = False):
+    """ct [2][L][N]; rks: one [dnum][2][L+K][N] key per rotation; pt [n_rot][L][N] -> [2][L][N]."""
+    ct = np.ascontiguousarray(ct, dtype=np.uint64)
+    pt = np.ascontiguousarray(pt, dtype=np.uint64)
+    n_rot = len(galois)
+    assert len(rks) == n_rot and pt.shape == (n_rot, P.L, P.N)
+    rks = [np.ascontiguousarray(k, dtype=np.uint64) for k in rks]
+    ptrs = (ctypes.c_void_p * n_rot)(*[k.ctypes.data for k in rks])
+    g = np.ascontiguousarray(np.array(galois, dtype=np.uint32))
+    out = np.empty((2, P.L, P.N), dtype=np.uint64)
+    per = np.empty((n_rot, 2, P.L, P.N), dtype=np.uint64) if want_per_rotation else None
+    lib().orc_hrot_hoisted_mac(_ptr(ct), _u32(n_rot), _ptr(g), ptrs, _ptr(pt), _ptr(out),
+                               _ptr(per) if per is not None else None, *P._tail())
+    return (out, per) if want_per_rotation else out
+
+
+# ------------------------------------------------------------- harness helpers
+def lift_signed(v: np.ndarray, primes: Sequence[int]) -> np.ndarray:
+    """Small signed coefficients [N] -> canonical residues [len(primes)][N]."""
+    v = np.asarray(v, dtype=np.int64)
+    out = np.empty((len(primes), v.shape[0]), dtype=np.uint64)
+    for i, p in enumerate(primes):
+        out[i] = np.where(v >= 0, v, v + int(p)).astype(np.uint64)
+    return out
+
+
+def secret_eval(s: np.ndarray, P: Params) -> np.ndarray:
+    """Ternary secret [N] (int8) -> evaluation form over all L+K limbs."""
+    return ntt_batch(lift_signed(s, P.primes), P, 0)
+
+
+def pointwise(op: str, a: np.ndarray, b: np.ndarray, primes: Sequence[int]) -> np.ndarray:
+    """Limb-wise a (op) b for [n_limbs][N] arrays, op in mul/add/sub."""
+    a = np.ascontiguousarray(a, dtype=np.uint64)
+    b = np.ascontiguousarray(b, dtype=np.uint64)
+    out = np.empty_like(a)
+    f = getattr(lib(), "orc_pointwise_" + op)
+    n = a.shape[-1]
+    for i, p in enumerate(primes):
+        f(_ptr(a[i]), _ptr(b[i]), _ptr(out[i]), ctypes.c_size_t(n), _u64(p))
+    return out
+
+
+def make_switch_key(s_hat: np.ndarray, sp_hat: np.ndarray, a: np.ndarray, e: np.ndarray, P: Params) -> np.ndarray:
+    """Switching key s' -> s.  a: uniform [dnum][L+K][N]; e: int64 [dnum][N]; returns [dnum][2][L+K][N]."""
+    s_hat = np.ascontiguousarray(s_hat, dtype=np.uint64)
+    sp_hat = np.ascontiguousarray(sp_hat, dtype=np.uint64)
+    a = np.ascontiguousarray(a, dtype=np.uint64)
+    e = np.ascontiguousarray(e, dtype=np.int64)
+    D = P.L + P.K
+    assert s_hat.shape == sp_hat.shape == (D, P.N) and a.shape == (P.dnum, D, P.N) and e.shape == (P.dnum, P.N)
+    key = np.empty((P.dnum, 2, D, P.N), dtype=np.uint64)
+    lib().orc_make_switch_key(_ptr(s_hat), _ptr(sp_hat), _ptr(a), _ptr(e), _ptr(key), *P._tail())
+    return key
+
+
+def centred_small(x_eval: np.ndarray, P: Params, n_limbs: int) -> np.ndarray:
+    """INTT the first n_limbs limbs of an evaluation-form value that is supposed to be SMALL, centre
+    every limb to (-q/2, q/2] and require all limbs to agree (then, by CRT, that common value is the
+    centred representative modulo the whole product).  Returns the int64 coefficient vector."""
+    c = ntt_batch(np.ascontiguousarray(x_eval[:n_limbs]), P, 0, inverse=True)
+    ref = None
+    for i in range(n_limbs):
+        q = P.primes[i]
+        v = c[i].astype(np.int64)
+        v = np.where(c[i] > np.uint64(q // 2), v - q, v)
+        if ref is None:
+            ref = v
+        elif not np.array_equal(ref, v):
+            raise AssertionError(f"limb {i} disagrees with limb 0: value is not small modulo the product")
+    return ref
+
+
+def keyswitch_noise(d: np.ndarray, ks: np.ndarray, s_hat: np.ndarray, sp_hat: np.ndarray, P: Params) -> np.ndarray:
+    """E = ks0 + ks1*s - d*s'  over the q-limbs, as centred integer coefficients (must be small)."""
+    q = P.primes[:P.L]
+    t = pointwise("add", ks[0], pointwise("mul", ks[1], s_hat[:P.L], q), q)
+    t = pointwise("sub", t, pointwise("mul", d, sp_hat[:P.L], q), q)
+    return centred_small(t, P, P.L)
+
+
+def keyswitch_noise_bound(P: Params, s_l1: int) -> int:
+    """ceil(dnum * N * alpha * max_j Q_j * 19 / P) + K * (1 + ||s||_1) + 1."""
+    qs, ps = P.primes[:P.L], P.primes[P.L:]
+    Pprod = 1
+    for p in ps:
+        Pprod *= p
+    maxQ = 0
+    for j in range(P.dnum):
+        Qj = 1
+        for q in qs[j * P.alpha:(j + 1) * P.alpha]:
+            Qj *= q
+        maxQ = max(maxQ, Qj)
+    first = -((-(P.dnum * P.N * P.alpha * maxQ * 19)) // Pprod)
+    return first + P.K * (1 + s_l1) + 1
