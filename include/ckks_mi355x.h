@@ -1,0 +1,187 @@
+/*
+ * ckks_mi355x.h -- C ABI of the MI355X (gfx950) RNS-CKKS key-switch library.
+ *
+ * Scope: the polynomial kernels of the GPU RNS-CKKS library described in the
+ * paper's Section 2 ("A GPU Library Supporting RNS-CKKS") -- NTT and base
+ * conversion, the kernels it names as the major ones -- and the thin slice of
+ * HE operations built from them (HMult with relinearisation, rotation; Table 1
+ * and Section 4).  The paper defers the definition of each step to the full-RNS
+ * CKKS scheme it cites; the definitions used here are restated with every
+ * entry point.
+ *
+ * Object (Section 2): a polynomial of Z_Q[X]/(X^N+1) is an L x N matrix of
+ * 64-bit words, one row ("limb") per RNS prime, stored limb-major.
+ *
+ * Conventions that hold for EVERY call
+ *   - every data pointer named d_* is DEVICE memory owned by the caller,
+ *     contiguous, 16-byte aligned, uint64 words, layout [...][limb][N];
+ *     pointers named h_* are HOST memory read during the call only.
+ *   - residues are canonical, in [0, prime), on entry and on exit.
+ *   - prime order: q_0 .. q_{L-1} (ciphertext limbs), then p_0 .. p_{K-1}
+ *     (special limbs).  D = L + K.  alpha = L / dnum; digit j owns the limbs
+ *     j*alpha .. (j+1)*alpha-1.
+ *   - a ciphertext is [2][L][N] in evaluation form: index 0 = c0 (b),
+ *     1 = c1 (a); it decrypts as c0 + c1*s.
+ *   - a switching key is [dnum][2][D][N] in evaluation form.
+ *   - evaluation form of limb i: slot j holds the polynomial evaluated at
+ *     psi_i^(2*bitrev(j)+1) (bit-reversed order), psi_i a primitive 2N-th root
+ *     of unity modulo prime i; coefficient form is natural order.
+ *   - all work is enqueued on `stream` (a hipStream_t passed as void*; NULL =
+ *     the default stream) and is asynchronous; the caller synchronises.
+ *   - input and output buffers must not overlap unless "in place" is stated.
+ *   - the library allocates no device memory: tables and workspace are caller
+ *     buffers sized by ckks_table_bytes / ckks_workspace_bytes, 256-byte aligned.
+ *   - return value: CKKS_OK or a negative error code; nothing throws or aborts.
+ *     ckks_last_error() gives a message for the last failing call on a context.
+ *   - only full-level operands are supported (all L limbs present, dnum | L).
+ */
+#ifndef CKKS_MI355X_H
+#define CKKS_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CKKS_OK 0
+#define CKKS_EINVAL (-1)       /* null / misaligned pointer, size out of range, bad Galois element */
+#define CKKS_EUNSUPPORTED (-2) /* shape outside what the kernels are built for */
+#define CKKS_EHIP (-3)         /* a HIP runtime call failed */
+#define CKKS_ENOMEM (-4)       /* caller's table / workspace buffer too small */
+
+/* selectors for ckks_workspace_bytes */
+#define CKKS_OP_NTT 0
+#define CKKS_OP_MODUP 1
+#define CKKS_OP_MODDOWN 2
+#define CKKS_OP_AUTOMORPH 3
+#define CKKS_OP_KEYSWITCH 4
+#define CKKS_OP_HMULT_RELIN 5
+#define CKKS_OP_HROT 6
+#define CKKS_OP_HROT_HOISTED_MAC 7
+
+/* limits of this build */
+#define CKKS_MIN_LOGN 12
+#define CKKS_MAX_LOGN 16
+#define CKKS_MAX_PRIMES 64 /* L + K */
+#define CKKS_MAX_DIGIT 8   /* alpha and K */
+#define CKKS_MAX_PRIME_BITS 61
+
+typedef struct ckks_ctx ckks_ctx;
+
+/* Bytes of device memory ckks_ctx_create needs for twiddle and constant tables. */
+int ckks_table_bytes(uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum, size_t* bytes);
+
+/*
+ * Build a context: validates the parameter set, derives on the host every
+ * per-prime table (powers of psi in bit-reversed order for the forward and the
+ * inverse transform, base-conversion constants for every digit and for the
+ * special basis) and copies them into d_tables.
+ *   h_primes : L+K primes, each = 1 mod 2N and < 2^61, pairwise distinct.
+ *   h_psi    : L+K primitive 2N-th roots, or NULL = the numerically smallest
+ *              psi with psi^N = -1 for every prime.
+ *   K may be 0 (transform-only context; key-switch calls then return
+ *   CKKS_EUNSUPPORTED).  Returns after the copy has completed.
+ * Ownership: the context keeps d_tables in use until ckks_ctx_destroy; the
+ * caller frees it afterwards.
+ */
+int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
+                    const uint64_t* h_primes, const uint64_t* h_psi, void* d_tables, size_t table_bytes,
+                    void* stream);
+
+/* Frees host state only. NULL is allowed. */
+void ckks_ctx_destroy(ckks_ctx* ctx);
+
+/* Message of the last error on this context (owned by the context; "" if none). */
+const char* ckks_last_error(const ckks_ctx* ctx);
+
+/* The root of unity in use for prime index i (0 on a bad index). */
+uint64_t ckks_ctx_psi(const ckks_ctx* ctx, uint32_t i);
+
+/* Bytes of workspace the given op needs for `batch_or_nrot` (batch size; number of rotations
+ * for CKKS_OP_HROT_HOISTED_MAC).  0 for ops that need none. */
+int ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t batch_or_nrot, size_t* bytes);
+
+/*
+ * Forward negacyclic NTT, in place, batched (Section 2: "NTT", a major kernel).
+ *   d_x : [batch][n_limbs][N]; limb l is reduced modulo prime (prime_first + l).
+ *   X^[j] = sum_t x_t * psi^(t*(2*bitrev(j)+1)) mod prime: natural-order coefficients in,
+ *   bit-reversed evaluation order out.
+ */
+int ckks_ntt(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uint32_t n_limbs, uint32_t batch, void* stream);
+
+/* Inverse of ckks_ntt (includes the factor N^-1): evaluation form in, natural-order coefficients out. */
+int ckks_intt(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uint32_t n_limbs, uint32_t batch, void* stream);
+
+/*
+ * ModUp: digit decomposition + fast base conversion (Section 2: "base conversion"), coefficient form.
+ *   d_in  : [batch][L][N]     d_out : [batch][dnum][D][N]
+ *   For digit j and coefficient n, with C_j the digit's primes and Q_j their product:
+ *     y_i = x_i * [(Q_j/q_i)^-1]_{q_i} mod q_i   (canonical),
+ *     out[j][t] = sum_{i in C_j} y_i * ((Q_j/q_i) mod m_t)  mod m_t    for every prime m_t outside C_j,
+ *     out[j][t] = x_t                                                   for t in C_j.
+ *   No correction of the overflow multiple of Q_j is applied.
+ */
+int ckks_modup(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, uint32_t batch, void* stream);
+
+/*
+ * ModDown: division by P = p_0*...*p_{K-1} with floor-type rounding, coefficient form.
+ *   d_in : [batch][D][N]      d_out : [batch][L][N]
+ *   out_i = (in_i - Conv_{P -> q_i}(in restricted to the special limbs)) * [P^-1]_{q_i}  mod q_i,
+ *   Conv being the same uncorrected fast base conversion as in ModUp with source basis p_0..p_{K-1}.
+ */
+int ckks_moddown(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, uint32_t batch, void* stream);
+
+/*
+ * Galois automorphism sigma_g : X -> X^g (the map behind homomorphic rotation, Section 4).
+ *   d_in, d_out : [batch][n_limbs][N], limb l modulo prime (prime_first + l); galois odd, < 2N.
+ *   eval_domain = 0: coefficient form, out[(t*g mod 2N) mod N] = +-in[t] (minus when t*g mod 2N >= N).
+ *   eval_domain = 1: evaluation form, out[j] = in[j'] with 2*bitrev(j')+1 = g*(2*bitrev(j)+1) mod 2N.
+ */
+int ckks_automorph(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, uint32_t prime_first, uint32_t n_limbs,
+                   uint32_t galois, int eval_domain, uint32_t batch, void* stream);
+
+/*
+ * Hybrid key switch (the step inside HMult and rotation; Table 1 measures HMult):
+ *   x = INTT(d);  dt = ModUp(x);  Dh_j = NTT(dt_j) on all D limbs;
+ *   c'_t[i] = sum_j Dh_j[i] * key[j][t][i] mod m_i  (t = 0,1);
+ *   out_t = NTT(ModDown(INTT(c'_t))).
+ *   d_d : [batch][L][N] eval;  d_key : [dnum][2][D][N] eval (shared by the batch);  d_out : [batch][2][L][N] eval.
+ */
+int ckks_keyswitch(ckks_ctx* ctx, const uint64_t* d_d, const uint64_t* d_key, uint64_t* d_out, uint32_t batch,
+                   void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * HMult with relinearisation, no rescale (Table 1 "HMult"):
+ *   d0 = b1*b2, d1 = a1*b2 + a2*b1, d2 = a1*a2 (limb-wise, evaluation form);
+ *   out = (d0 + ks_0, d1 + ks_1), ks = KeySwitch(d2, evk).
+ *   d_ct1, d_ct2, d_out : [batch][2][L][N];  d_evk : [dnum][2][D][N].
+ */
+int ckks_hmult_relin(ckks_ctx* ctx, const uint64_t* d_ct1, const uint64_t* d_ct2, const uint64_t* d_evk,
+                     uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Homomorphic rotation by the Galois element g (Section 4: rotations dominate convolution time):
+ *   out = (sigma_g(b) + ks_0, ks_1), ks = KeySwitch(sigma_g(a), rk_g), sigma_g on evaluation form.
+ *   d_ct, d_out : [batch][2][L][N];  d_rk : [dnum][2][D][N].
+ */
+int ckks_hrot(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t galois, const uint64_t* d_rk, uint64_t* d_out,
+              uint32_t batch, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Hoisted rotate-multiply-accumulate (the convolution / linear-transform shape of Section 4):
+ *   Dh_j = NTT(ModUp(INTT(a))_j) once; then for every rotation r
+ *     c'_t = sum_j sigma_{g_r}(Dh_j) * rk_r[j][t];  ks = NTT(ModDown(INTT(c')));
+ *     R_r = (sigma_{g_r}(b) + ks_0, ks_1);   out += pt_r * R_r  (both components).
+ *   d_ct : [2][L][N];  h_galois : n_rot Galois elements (host);  h_rk_ptrs : host array of n_rot device
+ *   pointers, each a [dnum][2][D][N] key;  d_pt : [n_rot][L][N] eval;  d_out : [2][L][N] (overwritten).
+ */
+int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, const uint32_t* h_galois,
+                          const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt, uint64_t* d_out, void* d_ws,
+                          size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKKS_MI355X_H */

@@ -1,0 +1,346 @@
+"""Parity of the HIP path against the CPU oracle, bit for bit, through the C ABI (needs an MI355X).
+
+Every comparison is exact (integer work): `np.array_equal` on the uint64 words.
+Sizes: reduced shapes of the same family that the oracle finishes in seconds (several
+workgroup tiles, every supported ring degree, digit sizes 1..7), then the full BASELINE
+shapes in the launch configuration the benchmark times.
+"""
+import numpy as np
+import pytest
+
+from paper_2310_16530_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def dev(a):
+    torch = _torch()
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int64)).to("cuda:0")
+
+
+def host(t):
+    return t.cpu().numpy().view(np.uint64)
+
+
+_CTX = {}
+
+
+def gpu_ctx(ps):
+    from paper_2310_16530_amd import binding
+    key = (ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+    if key not in _CTX:
+        _CTX[key] = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+    return _CTX[key]
+
+
+_ORC = {}
+
+
+def orc_params(orc, ps):
+    key = (ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+    if key not in _ORC:
+        _ORC[key] = orc.Params.from_set(ps)
+    return _ORC[key]
+
+
+def test_library_is_the_hip_one_and_roots_agree(orc):
+    from paper_2310_16530_amd import binding
+    lib = binding.load()
+    assert lib._name.endswith("libckks_mi355x.so")
+    ps = synth.CFG0
+    ctx = gpu_ctx(ps)
+    P = orc_params(orc, ps)
+    assert [ctx.psi(i) for i in range(ps.L + ps.K)] == P.psi
+
+
+# ------------------------------------------------------------------------------ NTT
+@pytest.mark.parametrize("logN", [12, 13, 14, 15, 16])
+def test_ntt_intt_parity_all_ring_degrees(orc, logN):
+    # 3 fifty-bit limbs + 2 sixty-bit limbs, batch 3: 15 limb jobs, up to 16 tiles each
+    ps = synth.small_params(logN, 3, 2, 3)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(100 + logN)
+    x = synth.uniform_residues(rng, ps.primes, ps.N, lead=(3,))
+    x[0, :, :7] = 0
+    for i, p in enumerate(ps.primes):       # edge values: zeros and q-1 runs
+        x[1, i, :] = p - 1
+    x[2, 0, :] = 0
+    fwd = host(ctx.ntt(dev(x)))
+    assert np.array_equal(fwd, orc.ntt_batch(x, P, 0))
+    inv = host(ctx.intt(dev(x)))
+    assert np.array_equal(inv, orc.ntt_batch(x, P, 0, inverse=True))
+    back = host(ctx.intt(ctx.ntt(dev(x))))
+    assert np.array_equal(back, x)
+    # sub-range of the chain: limbs 2..4 only (prime_first = 2), single batch, single limb
+    sub = np.ascontiguousarray(x[0, 2:5])
+    assert np.array_equal(host(ctx.ntt(dev(sub), prime_first=2)),
+                          np.stack([orc.ntt(sub[i], logN, ps.primes[2 + i], P.psi[2 + i]) for i in range(3)]))
+    one = np.ascontiguousarray(x[0, 4:5])
+    assert np.array_equal(host(ctx.intt(dev(one), prime_first=4))[0], orc.intt(one[0], logN, ps.primes[4], P.psi[4]))
+
+
+@pytest.mark.timeout(900)
+def test_ntt_config1_full_size(orc):
+    """BASELINE config 1: 16 polynomials x 24 fifty-bit limbs at N = 2^16, forward, inverse, round trip."""
+    ps = synth.CFG1
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    x = synth.uniform_residues(synth.rng_for(1, 0), ps.primes, ps.N, lead=(synth.CFG1_BATCH,))
+    d = dev(x)
+    ctx.ntt(d)
+    assert np.array_equal(host(d), orc.ntt_batch(x, P, 0))
+    # definition, sampled slots (independent of the oracle's fast network)
+    got = host(d)
+    for (b, l, j) in [(0, 0, 0), (3, 7, 12345), (15, 23, 65535)]:
+        assert int(got[b, l, j]) == orc.ntt_def_at(x[b, l], 16, ps.primes[l], P.psi[l], j)
+    ctx.intt(d)
+    assert np.array_equal(host(d), x)
+    d2 = dev(x)
+    ctx.intt(d2)
+    assert np.array_equal(host(d2), orc.ntt_batch(x, P, 0, inverse=True))
+
+
+# ------------------------------------------------------------------ base conversion
+CONV_SHAPES = [(12, 4, 2, 2), (12, 3, 1, 3), (13, 6, 3, 2), (12, 8, 8, 1), (14, 6, 6, 1), (12, 10, 5, 2),
+               (12, 7, 7, 1), (12, 8, 4, 2)]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_modup_moddown_parity(orc, shape):
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(sum(shape))
+    x = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    x[0, :, 0] = 0
+    for i, p in enumerate(ps.q_primes):
+        x[0, i, 1] = p - 1
+    up = host(ctx.modup(dev(x)))
+    for b in range(2):
+        assert np.array_equal(up[b], orc.modup(x[b], P))
+    y = synth.uniform_residues(rng, ps.primes, ps.N, lead=(2,))
+    for i, p in enumerate(ps.primes):
+        y[1, i, 5] = p - 1
+    down = host(ctx.moddown(dev(y)))
+    for b in range(2):
+        assert np.array_equal(down[b], orc.moddown(y[b], P))
+
+
+@pytest.mark.timeout(900)
+def test_modup_moddown_full_size(orc):
+    ps = synth.CFG2
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(2, 7)
+    x = synth.uniform_residues(rng, ps.q_primes, ps.N)
+    assert np.array_equal(host(ctx.modup(dev(x))), orc.modup(x, P))
+    y = synth.uniform_residues(rng, ps.primes, ps.N)
+    assert np.array_equal(host(ctx.moddown(dev(y))), orc.moddown(y, P))
+
+
+# --------------------------------------------------------------------- automorphism
+@pytest.mark.parametrize("logN", [12, 16])
+def test_automorph_parity(orc, logN):
+    ps = synth.small_params(logN, 2, 1, 2)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(logN)
+    x = synth.uniform_residues(rng, ps.primes, ps.N, lead=(2,))
+    x[0, 0, :3] = 0
+    for g in [1, 5, 25, synth.galois_element(-1, logN), synth.galois_element(7, logN), 2 * ps.N - 1, 3]:
+        for ev in (False, True):
+            got = host(ctx.automorph(dev(x), g, ev))
+            assert np.array_equal(got, orc.automorph_limbs(x, P, 0, g, ev)), (g, ev)
+
+
+# ------------------------------------------------- key switch, HMult, HRot (reduced shapes)
+def make_keys(orc, ps, P, rng, s_hat, sp_hat):
+    a = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum,))
+    e = synth.gaussian_error(rng, (ps.dnum, ps.N))
+    return orc.make_switch_key(s_hat, sp_hat, a, e, P)
+
+
+KS_SHAPES = [(12, 4, 2, 2), (12, 3, 1, 3), (13, 6, 3, 2), (12, 6, 6, 1), (14, 4, 2, 2), (12, 14, 7, 2), (12, 8, 8, 1)]
+
+
+@pytest.mark.parametrize("shape", KS_SHAPES)
+def test_keyswitch_hmult_hrot_parity_reduced(orc, shape):
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(1000 + sum(shape))
+    s = synth.ternary_hamming(rng, ps.N, 64)
+    s_hat = orc.secret_eval(s, P)
+    s2_hat = orc.pointwise("mul", s_hat, s_hat, ps.primes)
+    evk = make_keys(orc, ps, P, rng, s_hat, s2_hat)
+    d_evk = dev(evk)
+    B = 3
+    d = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B,))
+    d[2] = 0
+    ks = host(ctx.keyswitch(dev(d), d_evk))
+    for b in range(B):
+        assert np.array_equal(ks[b], orc.keyswitch(d[b], evk, P)), b
+    # decrypt-and-bound on the GPU result itself
+    bound = orc.keyswitch_noise_bound(P, int(np.abs(s).sum()))
+    assert np.abs(orc.keyswitch_noise(d[0], ks[0], s_hat, s2_hat, P)).max() <= bound
+
+    ct1 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
+    ct2 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
+    hm = host(ctx.hmult_relin(dev(ct1), dev(ct2), d_evk))
+    for b in range(B):
+        assert np.array_equal(hm[b], orc.hmult_relin(ct1[b], ct2[b], evk, P)), b
+
+    for rot in (1, -1):
+        g = synth.galois_element(rot, ps.logN)
+        sg_hat = orc.automorph_limbs(s_hat, P, 0, g, True)
+        rk = make_keys(orc, ps, P, rng, s_hat, sg_hat)
+        hr = host(ctx.hrot(dev(ct1), g, dev(rk)))
+        for b in range(B):
+            assert np.array_equal(hr[b], orc.hrot(ct1[b], g, rk, P)), (rot, b)
+
+
+@pytest.mark.parametrize("shape,n_rot", [((12, 4, 2, 2), 3), ((13, 6, 3, 2), 11), ((12, 3, 1, 3), 8), ((12, 6, 6, 1), 9)])
+def test_hoisted_mac_parity_reduced(orc, shape, n_rot):
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(2000 + sum(shape))
+    s = synth.ternary_hamming(rng, ps.N, 64)
+    s_hat = orc.secret_eval(s, P)
+    rots = [1, 2, 3, 4, 5, 6, 7, 8, 16, -1, 32][:n_rot]
+    gs = [synth.galois_element(r, ps.logN) for r in rots]
+    rks = [make_keys(orc, ps, P, rng, s_hat, orc.automorph_limbs(s_hat, P, 0, g, True)) for g in gs]
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    pt = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(n_rot,))
+    want, per = orc.hrot_hoisted_mac(ct, gs, rks, pt, P, want_per_rotation=True)
+    d_rks = [dev(k) for k in rks]
+    got = host(ctx.hrot_hoisted_mac(dev(ct), gs, d_rks, dev(pt)))
+    assert np.array_equal(got, want)
+    # unit plaintext on one rotation reproduces that rotated ciphertext; decrypt-and-bound it
+    r = n_rot - 1
+    unit = np.zeros_like(pt)
+    unit[r] = 1
+    Rr = host(ctx.hrot_hoisted_mac(dev(ct), gs, d_rks, dev(unit)))
+    assert np.array_equal(Rr, per[r])
+    q = ps.q_primes
+    sq = s_hat[:ps.L]
+
+    def dec(c):
+        return orc.pointwise("add", c[0], orc.pointwise("mul", c[1], sq, q), q)
+
+    E = orc.centred_small(orc.pointwise("sub", dec(Rr), orc.automorph_limbs(dec(ct), P, 0, gs[r], True), q), P, ps.L)
+    assert np.abs(E).max() <= orc.keyswitch_noise_bound(P, int(np.abs(s).sum()))
+
+
+# ------------------------------------------------------------- full BASELINE shapes
+def test_config0_hmult_exact_shape(orc):
+    ps = synth.CFG0
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(0, 0)
+    s = synth.ternary_iid(rng, ps.N)
+    s_hat = orc.secret_eval(s, P)
+    s2_hat = orc.pointwise("mul", s_hat, s_hat, ps.primes)
+    evk = make_keys(orc, ps, P, rng, s_hat, s2_hat)
+    ct1 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    ct2 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    got = host(ctx.hmult_relin(dev(ct1), dev(ct2), dev(evk)))
+    assert np.array_equal(got, orc.hmult_relin(ct1, ct2, evk, P))
+    q = ps.q_primes
+    sq = s_hat[:ps.L]
+
+    def dec(c):
+        return orc.pointwise("add", c[0], orc.pointwise("mul", c[1], sq, q), q)
+
+    E = orc.centred_small(orc.pointwise("sub", dec(got), orc.pointwise("mul", dec(ct1), dec(ct2), q), q), P, ps.L)
+    assert np.abs(E).max() <= orc.keyswitch_noise_bound(P, int(np.abs(s).sum()))
+
+
+@pytest.mark.timeout(900)
+def test_config2_hmult_batch8_full_size(orc):
+    """BASELINE config 2 in the benchmark's launch configuration (batch 8, shared evk).  The oracle
+    recomputes two of the eight products in full; all eight are checked by decrypt-and-bound."""
+    ps = synth.CFG2
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(2, 0)
+    s = synth.ternary_hamming(rng, ps.N, 192)
+    s_hat = orc.secret_eval(s, P)
+    s2_hat = orc.pointwise("mul", s_hat, s_hat, ps.primes)
+    evk = make_keys(orc, ps, P, rng, s_hat, s2_hat)
+    B = synth.CFG2_BATCH
+    ct1 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
+    ct2 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
+    got = host(ctx.hmult_relin(dev(ct1), dev(ct2), dev(evk)))
+    for b in (0, B - 1):
+        assert np.array_equal(got[b], orc.hmult_relin(ct1[b], ct2[b], evk, P)), b
+    q = ps.q_primes
+    sq = s_hat[:ps.L]
+    bound = orc.keyswitch_noise_bound(P, 192)
+    assert bound <= 1160  # ceil(2^-29) + 6*193 + 1
+
+    def dec(c):
+        return orc.pointwise("add", c[0], orc.pointwise("mul", c[1], sq, q), q)
+
+    for b in range(B):
+        E = orc.centred_small(orc.pointwise("sub", dec(got[b]), orc.pointwise("mul", dec(ct1[b]), dec(ct2[b]), q), q), P, ps.L)
+        assert np.abs(E).max() <= bound, b
+
+
+@pytest.mark.timeout(900)
+def test_config2_hrot_and_keyswitch_full_size(orc):
+    ps = synth.CFG2
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(2, 1)
+    B = synth.CFG2_BATCH
+    # parity needs no structured key: uniform residues stand in for the key limbs
+    rk = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
+    g = synth.galois_element(1, ps.logN)
+    got = host(ctx.hrot(dev(ct), g, dev(rk)))
+    for b in (1, B - 2):
+        assert np.array_equal(got[b], orc.hrot(ct[b], g, rk, P)), b
+    d = np.ascontiguousarray(ct[:2, 1])
+    ks = host(ctx.keyswitch(dev(d), dev(rk)))
+    assert np.array_equal(ks[1], orc.keyswitch(d[1], rk, P))
+
+
+@pytest.mark.timeout(900)
+def test_config3_rotate_and_sum_full_size(orc):
+    """BASELINE config 3: one ciphertext, the 17 listed offsets, hoisted ModUp, plaintext MAC."""
+    ps = synth.CFG3
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(3, 0)
+    gs = [synth.galois_element(r, ps.logN) for r in synth.CFG3_ROTATIONS]
+    n_rot = len(gs)
+    assert n_rot == 17
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    pt = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(n_rot,))
+    got = host(ctx.hrot_hoisted_mac(dev(ct), gs, [dev(k) for k in rks], dev(pt)))
+    assert np.array_equal(got, orc.hrot_hoisted_mac(ct, gs, rks, pt, P))
+
+
+@pytest.mark.timeout(900)
+def test_config4_coeff_to_slot_shape_full_size(orc):
+    """BASELINE config 4: L=35, K=7, dnum=5, 32 rotations +-2^i.  The oracle recomputes a 5-rotation
+    subset in full (including the identity element g = 1 from +-2^15); the 32-rotation call is then
+    checked by linearity: it must equal the sum of four 8-rotation calls."""
+    ps = synth.CFG4
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(4, 0)
+    gs = [synth.galois_element(r, ps.logN) for r in synth.CFG4_ROTATIONS]
+    assert len(gs) == 32 and gs[30] == 1 and gs[31] == 1
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    d_ct = dev(ct)
+    rks = [dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))) for _ in gs]
+    pt = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(32,))
+    d_pt = dev(pt)
+    full = host(ctx.hrot_hoisted_mac(d_ct, gs, rks, d_pt))
+    sub = [0, 1, 29, 30, 31]
+    want = orc.hrot_hoisted_mac(ct, [gs[i] for i in sub], [host(rks[i]) for i in sub], np.ascontiguousarray(pt[sub]), P)
+    got_sub = host(ctx.hrot_hoisted_mac(d_ct, [gs[i] for i in sub], [rks[i] for i in sub], dev(np.ascontiguousarray(pt[sub]))))
+    assert np.array_equal(got_sub, want)
+    acc = np.zeros_like(full)
+    for c in range(4):
+        part = host(ctx.hrot_hoisted_mac(d_ct, gs[8 * c:8 * c + 8], rks[8 * c:8 * c + 8], d_pt[8 * c:8 * c + 8].contiguous()))
+        for t in range(2):
+            acc[t] = orc.pointwise("add", acc[t], part[t], ps.q_primes)
+    assert np.array_equal(full, acc)
