@@ -23,7 +23,9 @@ EXPORTS = (
     "ckks_table_bytes", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error", "ckks_ctx_psi",
     "ckks_workspace_bytes", "ckks_ntt", "ckks_intt", "ckks_modup", "ckks_moddown", "ckks_automorph",
     "ckks_keyswitch", "ckks_hmult_relin", "ckks_hrot", "ckks_hrot_hoisted_mac",
+    "ckks_profile_enable", "ckks_profile_read",
 )
+PROF_KINDS = 10
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
 _lib = None
@@ -62,6 +64,9 @@ def load() -> ctypes.CDLL:
     lib.ckks_hmult_relin.argtypes = [_vp, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot.argtypes = [_vp, _vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_hoisted_mac.argtypes = [_vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.ckks_profile_enable.argtypes = [_vp, _int]
+    lib.ckks_profile_read.argtypes = [_vp, _u32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_u64),
+                                      ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_u64)]
     for name in EXPORTS:
         f = getattr(lib, name)
         if name not in ("ckks_ctx_destroy", "ckks_last_error", "ckks_ctx_psi"):
@@ -131,6 +136,19 @@ class Context:
             self._ws = None
             self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
         return self._ws
+
+    def profile_enable(self, on: bool) -> None:
+        self._check(load().ckks_profile_enable(self.handle, 1 if on else 0))
+
+    def profile_read(self) -> dict:
+        """{kernel name: (launches, total_ms, algorithmic_bytes)} since profile_enable(True)."""
+        out = {}
+        for kind in range(PROF_KINDS):
+            name, n, ms, nbytes = ctypes.c_char_p(), _u64(), ctypes.c_double(), _u64()
+            self._check(load().ckks_profile_read(self.handle, kind, ctypes.byref(name), ctypes.byref(n),
+                                                 ctypes.byref(ms), ctypes.byref(nbytes)))
+            out[name.value.decode()] = (n.value, ms.value, nbytes.value)
+        return out
 
     # -- entry points (same names as the C ABI, minus the prefix) ----------------------
     def ntt(self, x: torch.Tensor, prime_first: int = 0, inverse: bool = False) -> torch.Tensor:

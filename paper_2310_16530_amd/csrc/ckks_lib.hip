@@ -112,12 +112,72 @@ static TableLayout table_layout(u32 logN, u32 L, u32 K) {
     return t;
 }
 
+// per-kernel timing: when enabled, every launch is bracketed by two HIP events recorded on the
+// launch stream; ckks_profile_read waits for them and sums elapsed time per kernel.
+enum ProfKind {
+    PK_NTT_FWD_STRIDED = 0, PK_NTT_FWD_CONTIG, PK_NTT_INV_CONTIG, PK_NTT_INV_STRIDED, PK_MODUP, PK_MODDOWN,
+    PK_INNER, PK_PREP, PK_FINAL, PK_AUTOMORPH, PK_COUNT
+};
+static const char* const prof_names[PK_COUNT] = {
+    "ntt_fwd_strided_kernel", "ntt_fwd_contig_kernel", "ntt_inv_contig_kernel", "ntt_inv_strided_kernel",
+    "modup_kernel", "moddown_kernel", "inner_product_kernel", "prep_kernel", "final_kernel", "automorph_kernel"};
+static_assert(PK_COUNT == CKKS_PROF_KINDS, "header and library disagree on the number of kernel kinds");
+
+struct ProfRec {
+    int kind;
+    hipEvent_t a, b;
+};
+struct ProfState {
+    bool on = false;
+    std::vector<ProfRec> pending;
+    std::vector<hipEvent_t> pool;
+    double ms[PK_COUNT] = {0};
+    u64 launches[PK_COUNT] = {0}, bytes[PK_COUNT] = {0};
+};
+
 struct ckks_ctx {
     u32 logN, L, K, dnum, alpha, D;
     std::vector<u64> primes, psi;
     NttTables ntt;
     ConvTables conv;
     mutable std::string err;
+    mutable ProfState prof;
+};
+
+static hipEvent_t prof_event(ProfState& p) {
+    if (!p.pool.empty()) {
+        hipEvent_t e = p.pool.back();
+        p.pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct ProfScope {
+    ProfState* p = nullptr;
+    hipStream_t s;
+    ProfRec rec;
+    ProfScope(const ckks_ctx* c, int kind, u64 alg_bytes, hipStream_t stream) : s(stream) {
+        if (!c->prof.on) return;
+        p = &c->prof;
+        p->launches[kind]++;
+        p->bytes[kind] += alg_bytes;
+        rec.kind = kind;
+        rec.a = prof_event(*p);
+        rec.b = prof_event(*p);
+        if (!rec.a || !rec.b) {
+            p = nullptr;
+            return;
+        }
+        (void)hipEventRecord(rec.a, s);
+    }
+    ~ProfScope() {
+        if (!p) return;
+        (void)hipEventRecord(rec.b, s);
+        p->pending.push_back(rec);
+    }
 };
 
 static int fail(const ckks_ctx* c, int code, const char* msg) {
@@ -268,7 +328,41 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     return CKKS_OK;
 }
 
-extern "C" void ckks_ctx_destroy(ckks_ctx* ctx) { delete ctx; }
+static void prof_drain(ProfState& p) {
+    for (ProfRec& r : p.pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) p.ms[r.kind] += ms;
+        p.pool.push_back(r.a);
+        p.pool.push_back(r.b);
+    }
+    p.pending.clear();
+}
+
+extern "C" void ckks_ctx_destroy(ckks_ctx* ctx) {
+    if (!ctx) return;
+    prof_drain(ctx->prof);
+    for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+extern "C" int ckks_profile_enable(ckks_ctx* ctx, int on) {
+    if (!ctx) return CKKS_EINVAL;
+    prof_drain(ctx->prof);
+    ctx->prof.on = on != 0;
+    for (int k = 0; k < PK_COUNT; k++) ctx->prof.ms[k] = 0, ctx->prof.launches[k] = 0, ctx->prof.bytes[k] = 0;
+    return CKKS_OK;
+}
+
+extern "C" int ckks_profile_read(ckks_ctx* ctx, uint32_t kind, const char** name, uint64_t* launches,
+                                 double* total_ms, uint64_t* alg_bytes) {
+    if (!ctx || kind >= PK_COUNT) return CKKS_EINVAL;
+    prof_drain(ctx->prof);
+    if (name) *name = prof_names[kind];
+    if (launches) *launches = ctx->prof.launches[kind];
+    if (total_ms) *total_ms = ctx->prof.ms[kind];
+    if (alg_bytes) *alg_bytes = ctx->prof.bytes[kind];
+    return CKKS_OK;
+}
 
 extern "C" const char* ckks_last_error(const ckks_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
@@ -290,12 +384,25 @@ template <int A>
 static void launch_ntt_a(const ckks_ctx* c, u64* data, const LimbMap& map, u32 jobs, bool inverse, hipStream_t s) {
     const u32 tiles = (1u << A) / 16;
     const dim3 grid(jobs * tiles), block(256);
+    const u64 bytes = (u64)jobs * 2 * sizeof(u64) << c->logN;  // every limb read once and written once
     if (!inverse) {
-        hipLaunchKernelGGL(ntt_fwd_strided_kernel<A>, grid, block, 0, s, data, map, c->ntt);
-        hipLaunchKernelGGL(ntt_fwd_contig_kernel<A>, grid, block, 0, s, data, map, c->ntt);
+        {
+            ProfScope ps(c, PK_NTT_FWD_STRIDED, bytes, s);
+            hipLaunchKernelGGL(ntt_fwd_strided_kernel<A>, grid, block, 0, s, data, map, c->ntt);
+        }
+        {
+            ProfScope ps(c, PK_NTT_FWD_CONTIG, bytes, s);
+            hipLaunchKernelGGL(ntt_fwd_contig_kernel<A>, grid, block, 0, s, data, map, c->ntt);
+        }
     } else {
-        hipLaunchKernelGGL(ntt_inv_contig_kernel<A>, grid, block, 0, s, data, map, c->ntt);
-        hipLaunchKernelGGL(ntt_inv_strided_kernel<A>, grid, block, 0, s, data, map, c->ntt);
+        {
+            ProfScope ps(c, PK_NTT_INV_CONTIG, bytes, s);
+            hipLaunchKernelGGL(ntt_inv_contig_kernel<A>, grid, block, 0, s, data, map, c->ntt);
+        }
+        {
+            ProfScope ps(c, PK_NTT_INV_STRIDED, bytes, s);
+            hipLaunchKernelGGL(ntt_inv_strided_kernel<A>, grid, block, 0, s, data, map, c->ntt);
+        }
     }
 }
 
@@ -316,6 +423,8 @@ static LimbMap plain_map(u32 n_limbs, u32 prime_first) { return LimbMap{n_limbs,
 template <int AL>
 static void launch_modup_a(const ckks_ctx* c, const u64* in, u64* out, u32 batch, int write_own, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, c->dnum, batch), block(256);
+    const u64 limbs = (u64)batch * (c->L + (u64)c->dnum * (c->D - c->alpha) + (write_own ? c->L : 0));
+    ProfScope ps(c, PK_MODUP, limbs * sizeof(u64) << c->logN, s);
     hipLaunchKernelGGL(modup_kernel<AL>, grid, block, 0, s, in, out, c->conv, c->logN, c->L, c->D, c->dnum, write_own);
 }
 static void launch_modup(const ckks_ctx* c, const u64* in, u64* out, u32 batch, int write_own, hipStream_t s) {
@@ -334,6 +443,8 @@ static void launch_modup(const ckks_ctx* c, const u64* in, u64* out, u32 batch, 
 template <int KK, bool FUSE>
 static void launch_moddown_k(const ckks_ctx* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, groups), block(256);
+    const u64 limbs = (u64)groups * (c->K + c->L + (FUSE ? c->L : 0));
+    ProfScope ps(c, PK_MODDOWN, limbs * sizeof(u64) << c->logN, s);
     hipLaunchKernelGGL((moddown_kernel<KK, FUSE>), grid, block, 0, s, in, out, c->conv, c->logN, c->L, c->D);
 }
 template <bool FUSE>
@@ -467,6 +578,7 @@ extern "C" int ckks_automorph(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_o
     if (batch > 65535) return fail(ctx, CKKS_EINVAL, "batch too large");
     const dim3 grid((1u << ctx->logN) / 256, n_limbs, batch), block(256);
     hipStream_t s = (hipStream_t)stream;
+    ProfScope ps(ctx, PK_AUTOMORPH, (u64)batch * n_limbs * 2 * sizeof(u64) << ctx->logN, s);
     if (eval_domain) {
         hipLaunchKernelGGL(automorph_eval_kernel, grid, block, 0, s, d_in, d_out, ctx->logN, n_limbs, galois);
     } else {
@@ -515,6 +627,8 @@ template <int MODE>
 static void launch_prep(const ckks_ctx* c, const u64* in1, const u64* in2, const Workspace& w, u32 batch, u32 galois,
                         hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, c->L, batch), block(256);
+    const u64 limbs = (u64)batch * c->L * (MODE == PREP_TENSOR_D2 ? 4 : 3);
+    ProfScope ps(c, PK_PREP, limbs * sizeof(u64) << c->logN, s);
     hipLaunchKernelGGL(prep_kernel<MODE>, grid, block, 0, s, in1, in2, w.x, w.dt, c->ntt.pc, c->logN, c->L, c->D,
                        c->dnum, c->alpha, galois);
 }
@@ -525,6 +639,9 @@ static void launch_inner_shared_key(const ckks_ctx* c, const Workspace& w, const
     memset(&kp, 0, sizeof(kp));
     kp.key[0] = key;
     const dim3 grid((1u << c->logN) / 256, c->D, batch), block(256);
+    // extended digits read, c' written, the shared key read once
+    const u64 limbs = (u64)batch * (c->dnum + 2) * c->D + (u64)c->dnum * 2 * c->D;
+    ProfScope ps(c, PK_INNER, limbs * sizeof(u64) << c->logN, s);
     hipLaunchKernelGGL(inner_product_kernel<false>, grid, block, 0, s, (const u64*)w.dt, (size_t)c->dnum * c->D * N, kp,
                        w.cp, c->ntt.pc, c->logN, c->D, c->dnum);
 }
@@ -532,6 +649,10 @@ static void launch_inner_shared_key(const ckks_ctx* c, const Workspace& w, const
 template <int MODE>
 static void launch_final(const ckks_ctx* c, const FinalArgs& fa, u32 groups, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, c->L, MODE == FIN_HOISTED ? 2 : groups * 2), block(256);
+    u64 limbs;  // c' and conv read, output written, plus the mode's extra operands
+    if (MODE == FIN_HOISTED) limbs = (u64)fa.n_rot * c->L * (4 + 1 + 1) + (u64)c->L * (2 + (fa.accumulate ? 2 : 0));
+    else limbs = (u64)groups * c->L * (6 + (MODE == FIN_HMULT ? 4 : MODE == FIN_HROT ? 1 : 0));
+    ProfScope ps(c, PK_FINAL, limbs * sizeof(u64) << c->logN, s);
     hipLaunchKernelGGL(final_kernel<MODE>, grid, block, 0, s, fa, c->conv, c->logN, c->L, c->D);
 }
 
@@ -617,6 +738,7 @@ extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32
     // hoisted part: decompose a = ct[1] once
     {
         const dim3 grid((1u << ctx->logN) / 256, ctx->L, 1), block(256);
+        ProfScope ps(ctx, PK_PREP, (u64)ctx->L * 3 * sizeof(u64) << ctx->logN, s);
         hipLaunchKernelGGL(prep_kernel<PREP_COPY>, grid, block, 0, s, d_ct + (size_t)ctx->L * N, (const u64*)nullptr,
                            w.x, w.dt, ctx->ntt.pc, ctx->logN, ctx->L, ctx->D, ctx->dnum, ctx->alpha, 1u);
     }
@@ -633,8 +755,13 @@ extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32
             fa.galois[r] = h_galois[r0 + r];
         }
         const dim3 grid((1u << ctx->logN) / 256, ctx->D, nr), block(256);
-        hipLaunchKernelGGL(inner_product_kernel<true>, grid, block, 0, s, (const u64*)w.dt, (size_t)0, kp, w.cp,
-                           ctx->ntt.pc, ctx->logN, ctx->D, ctx->dnum);
+        {
+            // per rotation: the shared extended digits gathered, its key read, c' written
+            const u64 limbs = (u64)nr * ((u64)ctx->dnum * ctx->D + (u64)ctx->dnum * 2 * ctx->D + 2 * ctx->D);
+            ProfScope ps(ctx, PK_INNER, limbs * sizeof(u64) << ctx->logN, s);
+            hipLaunchKernelGGL(inner_product_kernel<true>, grid, block, 0, s, (const u64*)w.dt, (size_t)0, kp, w.cp,
+                               ctx->ntt.pc, ctx->logN, ctx->D, ctx->dnum);
+        }
         moddown_tail(ctx, w, nr, s);
         fa.cp = w.cp, fa.cv = w.cv, fa.out = d_out, fa.ct1 = d_ct, fa.pt = d_pt + (size_t)r0 * ctx->L * N;
         fa.n_rot = nr, fa.accumulate = r0 ? 1 : 0;
