@@ -190,7 +190,7 @@ int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, c
  * summed duration in milliseconds and their summed algorithmic bytes (the words each launch
  * must read and write once, tables excluded).  Any output pointer may be NULL.
  */
-#define CKKS_PROF_KINDS 10
+#define CKKS_PROF_KINDS 9
 int ckks_profile_enable(ckks_ctx* ctx, int on);
 int ckks_profile_read(ckks_ctx* ctx, uint32_t kind, const char** name, uint64_t* launches, double* total_ms,
                       uint64_t* alg_bytes);

@@ -25,7 +25,7 @@ EXPORTS = (
     "ckks_keyswitch", "ckks_hmult_relin", "ckks_hrot", "ckks_hrot_hoisted_mac",
     "ckks_profile_enable", "ckks_profile_read",
 )
-PROF_KINDS = 10
+PROF_KINDS = 9
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
 _lib = None

@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libckks_mi355x.so")
 SOURCES = ["ckks_lib.hip"]
-HEADERS = ["modarith.h", "ntt.h", "poly_kernels.h"]
+HEADERS = ["modarith.h", "ntt.h", "kernels.h"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

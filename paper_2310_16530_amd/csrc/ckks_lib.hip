@@ -10,7 +10,7 @@
 #include <vector>
 
 #include "../../include/ckks_mi355x.h"
-#include "poly_kernels.h"
+#include "kernels.h"
 
 typedef unsigned __int128 u128;
 
@@ -29,7 +29,6 @@ static u64 h_powmod(u64 b, u64 e, u64 m) {
 static inline u64 h_invmod(u64 a, u64 m) { return h_powmod(a % m, m - 2, m); }
 static inline u64 h_shoup(u64 w, u64 m) { return (u64)(((u128)w << 64) / m); }
 static inline u64 h_mont(u64 w, u64 m) { return (u64)(((u128)w << 64) % m); }
-static inline ShoupConst h_sc(u64 w, u64 m) { return ShoupConst{w, h_shoup(w, m)}; }
 static u64 h_neg_inv64(u64 q) {  // -q^-1 mod 2^64 by Newton iteration
     u64 x = q;                    // correct to 3 bits (q odd)
     for (int i = 0; i < 6; i++) x *= 2 - q * x;
@@ -87,27 +86,31 @@ static u64 h_min_root(u64 m, u32 logN) {
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct TableLayout {
-    size_t tw, pc, up_hatinv, up_chat, dn_hatinv, dn_chat, pinv, total;
+    size_t tw_int, tw_fp, pc, sc_plain, sc_up, sc_dn, up_hatinv, dn_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, pinv, total;
 };
 
 static TableLayout table_layout(u32 logN, u32 L, u32 K) {
-    const size_t N = (size_t)1 << logN, D = L + K;
+    const size_t N = (size_t)1 << logN, D = L + K, K1 = K ? K : 1;
     TableLayout t;
     size_t o = 0;
-    t.tw = o;
-    o += align256(D * 4 * N * sizeof(u64));
-    t.pc = o;
-    o += align256(D * sizeof(PrimeConst));
-    t.up_hatinv = o;
-    o += align256(L * sizeof(ShoupConst));
-    t.up_chat = o;
-    o += align256(L * D * sizeof(u64));
-    t.dn_hatinv = o;
-    o += align256((K ? K : 1) * sizeof(ShoupConst));
-    t.dn_chat = o;
-    o += align256((K ? K : 1) * L * sizeof(u64));
-    t.pinv = o;
-    o += align256(L * sizeof(ShoupConst));
+    auto take = [&o](size_t bytes) {
+        size_t at = o;
+        o += align256(bytes);
+        return at;
+    };
+    t.tw_int = take(D * 4 * N * sizeof(u64));
+    t.tw_fp = take(D * 2 * N * sizeof(double));
+    t.pc = take(D * sizeof(PrimeConst));
+    t.sc_plain = take(D * sizeof(InvScale));
+    t.sc_up = take(L * sizeof(InvScale));
+    t.sc_dn = take(K1 * sizeof(InvScale));
+    t.up_hatinv = take(L * 2 * sizeof(u64));
+    t.dn_hatinv = take(K1 * 2 * sizeof(u64));
+    t.up_chat = take(L * D * sizeof(u64));
+    t.up_chat_fp = take(L * D * sizeof(double));
+    t.up_fp_ok = take(L * D * sizeof(u32));
+    t.dn_chat = take(K1 * L * sizeof(u64));
+    t.pinv = take(L * sizeof(PinvConst));
     t.total = o;
     return t;
 }
@@ -115,12 +118,12 @@ static TableLayout table_layout(u32 logN, u32 L, u32 K) {
 // per-kernel timing: when enabled, every launch is bracketed by two HIP events recorded on the
 // launch stream; ckks_profile_read waits for them and sums elapsed time per kernel.
 enum ProfKind {
-    PK_NTT_FWD_STRIDED = 0, PK_NTT_FWD_CONTIG, PK_NTT_INV_CONTIG, PK_NTT_INV_STRIDED, PK_MODUP, PK_MODDOWN,
-    PK_INNER, PK_PREP, PK_FINAL, PK_AUTOMORPH, PK_COUNT
+    PK_INV_CONTIG = 0, PK_INV_STRIDED, PK_FWD_STRIDED, PK_FWD_CONTIG, PK_KS_INNER, PK_KS_FINAL, PK_MODUP, PK_MODDOWN,
+    PK_AUTOMORPH, PK_COUNT
 };
 static const char* const prof_names[PK_COUNT] = {
-    "ntt_fwd_strided_kernel", "ntt_fwd_contig_kernel", "ntt_inv_contig_kernel", "ntt_inv_strided_kernel",
-    "modup_kernel", "moddown_kernel", "inner_product_kernel", "prep_kernel", "final_kernel", "automorph_kernel"};
+    "inv_contig_kernel", "inv_strided_kernel", "fwd_strided_kernel", "fwd_contig_kernel", "ks_inner_kernel",
+    "ks_final_kernel", "modup_kernel", "moddown_kernel", "automorph_kernel"};
 static_assert(PK_COUNT == CKKS_PROF_KINDS, "header and library disagree on the number of kernel kinds");
 
 struct ProfRec {
@@ -138,8 +141,7 @@ struct ProfState {
 struct ckks_ctx {
     u32 logN, L, K, dnum, alpha, D;
     std::vector<u64> primes, psi;
-    NttTables ntt;
-    ConvTables conv;
+    Tables tb;
     mutable std::string err;
     mutable ProfState prof;
 };
@@ -159,11 +161,12 @@ struct ProfScope {
     ProfState* p = nullptr;
     hipStream_t s;
     ProfRec rec;
-    ProfScope(const ckks_ctx* c, int kind, u64 alg_bytes, hipStream_t stream) : s(stream) {
+    // alg_limbs: limbs (N words each) the launch must read plus write once
+    ProfScope(const ckks_ctx* c, int kind, u64 alg_limbs, hipStream_t stream) : s(stream) {
         if (!c->prof.on) return;
         p = &c->prof;
         p->launches[kind]++;
-        p->bytes[kind] += alg_bytes;
+        p->bytes[kind] += (alg_limbs * sizeof(u64)) << c->logN;
         rec.kind = kind;
         rec.a = prof_event(*p);
         rec.b = prof_event(*p);
@@ -179,6 +182,16 @@ struct ProfScope {
         p->pending.push_back(rec);
     }
 };
+
+static void prof_drain(ProfState& p) {
+    for (ProfRec& r : p.pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) p.ms[r.kind] += ms;
+        p.pool.push_back(r.a);
+        p.pool.push_back(r.b);
+    }
+    p.pending.clear();
+}
 
 static int fail(const ckks_ctx* c, int code, const char* msg) {
     if (c) c->err = msg;
@@ -201,6 +214,17 @@ extern "C" int ckks_table_bytes(uint32_t logN, uint32_t L, uint32_t K, uint32_t 
     if (rc) return rc;
     *bytes = table_layout(logN, L, K).total;
     return CKKS_OK;
+}
+
+static InvScale make_scale(u64 factor, u64 ninv, u64 wlast, u64 m, bool fp) {
+    InvScale s;
+    s.sx = h_mulmod(ninv, factor, m);
+    s.sx_p = h_shoup(s.sx, m);
+    s.sy = h_mulmod(h_mulmod(wlast, ninv, m), factor, m);
+    s.sy_p = h_shoup(s.sy, m);
+    s.sxd = fp ? (double)s.sx : 0.0;
+    s.syd = fp ? (double)s.sy : 0.0;
+    return s;
 }
 
 extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
@@ -232,15 +256,28 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     c->psi.resize(D);
 
     std::vector<unsigned char> host(lay.total, 0);
-    u64* tw = (u64*)(host.data() + lay.tw);
+    u64* tw = (u64*)(host.data() + lay.tw_int);
+    double* twf = (double*)(host.data() + lay.tw_fp);
     PrimeConst* pc = (PrimeConst*)(host.data() + lay.pc);
-    std::vector<u64> pw(N);
+    InvScale* sc_plain = (InvScale*)(host.data() + lay.sc_plain);
+    InvScale* sc_up = (InvScale*)(host.data() + lay.sc_up);
+    InvScale* sc_dn = (InvScale*)(host.data() + lay.sc_dn);
+    u64* up_hatinv = (u64*)(host.data() + lay.up_hatinv);
+    u64* dn_hatinv = (u64*)(host.data() + lay.dn_hatinv);
+    u64* up_chat = (u64*)(host.data() + lay.up_chat);
+    double* up_chat_fp = (double*)(host.data() + lay.up_chat_fp);
+    u32* up_fp_ok = (u32*)(host.data() + lay.up_fp_ok);
+    u64* dn_chat = (u64*)(host.data() + lay.dn_chat);
+    PinvConst* pinv = (PinvConst*)(host.data() + lay.pinv);
+    std::vector<u64> pw(N), ninv(D), wlast(D);
     for (u32 i = 0; i < D; i++) {
         const u64 m = c->primes[i];
+        const bool fp = m < CKKS_FP_PRIME_LIMIT;
         const u64 psi = h_psi ? h_psi[i] : h_min_root(m, logN);
         c->psi[i] = psi;
         const u64 psi_inv = h_invmod(psi, m);
         u64* fw = tw + (size_t)i * 4 * N;
+        double* ff = twf + (size_t)i * 2 * N;
         for (int dir = 0; dir < 2; dir++) {
             const u64 base = dir ? psi_inv : psi;
             pw[0] = 1;
@@ -249,21 +286,24 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
             for (size_t k = 0; k < N; k++) {
                 w[k] = pw[h_bitrev((u32)k, logN)];
                 w[N + k] = h_shoup(w[k], m);
+                if (fp) ff[(size_t)dir * N + k] = (double)w[k];
             }
         }
         PrimeConst& p = pc[i];
         p.q = m;
         p.qneg = h_neg_inv64(m);
-        p.r2 = (u64)((((u128)1 << 64) % m) * (((u128)1 << 64) % m) % m);
-        p.ninv = h_invmod(N % m, m);
-        p.ninv_p = h_shoup(p.ninv, m);
-        p.wlast = h_mulmod(fw[2 * N + 1], p.ninv, m);
-        p.wlast_p = h_shoup(p.wlast, m);
+        p.r1 = (u64)(((u128)1 << 64) % m);
+        p.r1_p = h_shoup(p.r1, m);
+        p.r2 = h_mulmod(p.r1, p.r1, m);
+        p.qd = fp ? (double)m : 0.0;
+        p.qinv = fp ? 1.0 / (double)m : 0.0;
+        p.fp = fp ? 1 : 0;
         p.pad = 0;
+        ninv[i] = h_invmod(N % m, m);
+        wlast[i] = fw[2 * N + 1];
+        sc_plain[i] = make_scale(1, ninv[i], wlast[i], m, fp);
     }
     // ModUp constants per digit
-    ShoupConst* up_hatinv = (ShoupConst*)(host.data() + lay.up_hatinv);
-    u64* up_chat = (u64*)(host.data() + lay.up_chat);
     for (u32 j = 0; j < dnum; j++) {
         for (u32 ii = 0; ii < alpha; ii++) {
             const u32 i = j * alpha + ii;
@@ -271,7 +311,10 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
             u64 hat = 1;
             for (u32 kk = 0; kk < alpha; kk++)
                 if (kk != ii) hat = h_mulmod(hat, c->primes[j * alpha + kk] % qi, qi);
-            up_hatinv[i] = h_sc(h_invmod(hat, qi), qi);
+            const u64 hinv = h_invmod(hat, qi);
+            up_hatinv[2 * i] = hinv;
+            up_hatinv[2 * i + 1] = h_shoup(hinv, qi);
+            sc_up[i] = make_scale(hinv, ninv[i], wlast[i], qi, pc[i].fp != 0);
             for (u32 t = 0; t < D; t++) {
                 if (t >= j * alpha && t < (j + 1) * alpha) continue;
                 const u64 mt = c->primes[t];
@@ -279,19 +322,28 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
                 for (u32 kk = 0; kk < alpha; kk++)
                     if (kk != ii) hb = h_mulmod(hb, c->primes[j * alpha + kk] % mt, mt);
                 up_chat[(size_t)i * D + t] = h_mont(hb, mt);
+                up_chat_fp[(size_t)i * D + t] = pc[t].fp ? (double)hb : 0.0;
             }
+        }
+        for (u32 t = 0; t < D; t++) {
+            bool ok = pc[t].fp != 0;
+            for (u32 ii = 0; ii < alpha; ii++) {
+                const u32 i = j * alpha + ii;
+                ok = ok && pc[i].fp && c->primes[i] <= 2 * c->primes[t];
+            }
+            up_fp_ok[(size_t)j * D + t] = ok ? 1 : 0;
         }
     }
     // ModDown constants
-    ShoupConst* dn_hatinv = (ShoupConst*)(host.data() + lay.dn_hatinv);
-    u64* dn_chat = (u64*)(host.data() + lay.dn_chat);
-    ShoupConst* pinv = (ShoupConst*)(host.data() + lay.pinv);
     for (u32 k = 0; k < K; k++) {
         const u64 pk = c->primes[L + k];
         u64 hat = 1;
         for (u32 kk = 0; kk < K; kk++)
             if (kk != k) hat = h_mulmod(hat, c->primes[L + kk] % pk, pk);
-        dn_hatinv[k] = h_sc(h_invmod(hat, pk), pk);
+        const u64 hinv = h_invmod(hat, pk);
+        dn_hatinv[2 * k] = hinv;
+        dn_hatinv[2 * k + 1] = h_shoup(hinv, pk);
+        sc_dn[k] = make_scale(hinv, ninv[L + k], wlast[L + k], pk, pc[L + k].fp != 0);
         for (u32 i = 0; i < L; i++) {
             const u64 qi = c->primes[i];
             u64 hb = 1;
@@ -304,7 +356,8 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         const u64 qi = c->primes[i];
         u64 P = 1;
         for (u32 k = 0; k < K; k++) P = h_mulmod(P, c->primes[L + k] % qi, qi);
-        pinv[i] = h_sc(h_invmod(P, qi), qi);
+        const u64 pi = h_invmod(P, qi);
+        pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
     }
 
     hipStream_t s = (hipStream_t)stream;
@@ -315,27 +368,23 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         return CKKS_EHIP;
     }
     unsigned char* dbase = (unsigned char*)d_tables;
-    c->ntt.tw = (const u64*)(dbase + lay.tw);
-    c->ntt.pc = (const PrimeConst*)(dbase + lay.pc);
-    c->ntt.logN = logN;
-    c->conv.pc = c->ntt.pc;
-    c->conv.up_hatinv = (const ShoupConst*)(dbase + lay.up_hatinv);
-    c->conv.up_chat = (const u64*)(dbase + lay.up_chat);
-    c->conv.dn_hatinv = (const ShoupConst*)(dbase + lay.dn_hatinv);
-    c->conv.dn_chat = (const u64*)(dbase + lay.dn_chat);
-    c->conv.pinv = (const ShoupConst*)(dbase + lay.pinv);
+    Tables& tb = c->tb;
+    tb.tw_int = (const u64*)(dbase + lay.tw_int);
+    tb.tw_fp = (const double*)(dbase + lay.tw_fp);
+    tb.pc = (const PrimeConst*)(dbase + lay.pc);
+    tb.sc_plain = (const InvScale*)(dbase + lay.sc_plain);
+    tb.sc_up = (const InvScale*)(dbase + lay.sc_up);
+    tb.sc_dn = (const InvScale*)(dbase + lay.sc_dn);
+    tb.up_hatinv = (const u64*)(dbase + lay.up_hatinv);
+    tb.dn_hatinv = (const u64*)(dbase + lay.dn_hatinv);
+    tb.up_chat = (const u64*)(dbase + lay.up_chat);
+    tb.up_chat_fp = (const double*)(dbase + lay.up_chat_fp);
+    tb.up_fp_ok = (const u32*)(dbase + lay.up_fp_ok);
+    tb.dn_chat = (const u64*)(dbase + lay.dn_chat);
+    tb.pinv = (const PinvConst*)(dbase + lay.pinv);
+    tb.logN = logN, tb.L = L, tb.K = K, tb.dnum = dnum, tb.alpha = alpha, tb.D = D;
     *out = c;
     return CKKS_OK;
-}
-
-static void prof_drain(ProfState& p) {
-    for (ProfRec& r : p.pending) {
-        float ms = 0.f;
-        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) p.ms[r.kind] += ms;
-        p.pool.push_back(r.a);
-        p.pool.push_back(r.b);
-    }
-    p.pending.clear();
 }
 
 extern "C" void ckks_ctx_destroy(ckks_ctx* ctx) {
@@ -380,105 +429,142 @@ static int hip_check(const ckks_ctx* c, const char* what) {
     return CKKS_OK;
 }
 
-template <int A>
-static void launch_ntt_a(const ckks_ctx* c, u64* data, const LimbMap& map, u32 jobs, bool inverse, hipStream_t s) {
-    const u32 tiles = (1u << A) / 16;
-    const dim3 grid(jobs * tiles), block(256);
-    const u64 bytes = (u64)jobs * 2 * sizeof(u64) << c->logN;  // every limb read once and written once
-    if (!inverse) {
-        {
-            ProfScope ps(c, PK_NTT_FWD_STRIDED, bytes, s);
-            hipLaunchKernelGGL(ntt_fwd_strided_kernel<A>, grid, block, 0, s, data, map, c->ntt);
-        }
-        {
-            ProfScope ps(c, PK_NTT_FWD_CONTIG, bytes, s);
-            hipLaunchKernelGGL(ntt_fwd_contig_kernel<A>, grid, block, 0, s, data, map, c->ntt);
-        }
+// grid of an XCD-aware launch: groups padded to a multiple of 8, times the instances per group
+static inline u32 xcd_grid(u32 groups, u32 inst) { return ((groups + 7) / 8) * 8 * inst; }
+static inline u32 tiles_of(const ckks_ctx* c) { return (1u << (c->logN - 8)) / 16; }
+
+#define DISPATCH_A(c, CALL)                    \
+    switch ((c)->logN - 8) {                   \
+        case 4: { constexpr int A = 4; CALL; } break; \
+        case 5: { constexpr int A = 5; CALL; } break; \
+        case 6: { constexpr int A = 6; CALL; } break; \
+        case 7: { constexpr int A = 7; CALL; } break; \
+        case 8: { constexpr int A = 8; CALL; } break; \
+    }
+
+template <int LOAD>
+static void launch_inv_contig(const ckks_ctx* c, const InvContigArgs& a, hipStream_t s) {
+    const u32 jobs = a.sel.n_l * a.sel.n_inst;
+    ProfScope ps(c, PK_INV_CONTIG, (u64)jobs * (LOAD == INV_TENSOR ? 3 : 2), s);
+    const dim3 grid(xcd_grid(a.sel.n_l * tiles_of(c), a.sel.n_inst)), block(256);
+    DISPATCH_A(c, hipLaunchKernelGGL((inv_contig_kernel<A, LOAD>), grid, block, 0, s, a, c->tb));
+}
+
+static void launch_inv_strided(const ckks_ctx* c, const InvStridedArgs& a, hipStream_t s) {
+    const u32 jobs = a.sel.n_l * a.sel.n_inst;
+    ProfScope ps(c, PK_INV_STRIDED, (u64)jobs * 2, s);
+    const dim3 grid(xcd_grid(a.sel.n_l * tiles_of(c), a.sel.n_inst)), block(256);
+    DISPATCH_A(c, hipLaunchKernelGGL((inv_strided_kernel<A>), grid, block, 0, s, a, c->tb));
+}
+
+template <int LOAD>
+static void launch_fwd_strided(const ckks_ctx* c, const FwdStridedArgs& a, hipStream_t s) {
+    u32 groups, inst;
+    u64 limbs;
+    if (LOAD == FWD_PLAIN) {
+        groups = a.sel.n_l * tiles_of(c), inst = a.sel.n_inst;
+        limbs = (u64)a.sel.n_l * a.sel.n_inst * 2;
+    } else if (LOAD == FWD_CONV_UP) {
+        groups = a.groups_outer * c->dnum * tiles_of(c), inst = c->D - c->alpha;
+        limbs = (u64)a.groups_outer * (c->L + (u64)c->dnum * (c->D - c->alpha));
     } else {
-        {
-            ProfScope ps(c, PK_NTT_INV_CONTIG, bytes, s);
-            hipLaunchKernelGGL(ntt_inv_contig_kernel<A>, grid, block, 0, s, data, map, c->ntt);
-        }
-        {
-            ProfScope ps(c, PK_NTT_INV_STRIDED, bytes, s);
-            hipLaunchKernelGGL(ntt_inv_strided_kernel<A>, grid, block, 0, s, data, map, c->ntt);
-        }
+        groups = a.groups_outer * tiles_of(c), inst = c->L;
+        limbs = (u64)a.groups_outer * (c->K + c->L);
     }
+    ProfScope ps(c, PK_FWD_STRIDED, limbs, s);
+    const dim3 grid(xcd_grid(groups, inst)), block(256);
+    DISPATCH_A(c, hipLaunchKernelGGL((fwd_strided_kernel<A, LOAD>), grid, block, 0, s, a, c->tb));
 }
 
-// jobs = number of limbs the map enumerates
-static void launch_ntt(const ckks_ctx* c, u64* data, const LimbMap& map, u32 jobs, bool inverse, hipStream_t s) {
-    if (jobs == 0) return;
-    switch (c->logN - 8) {
-        case 4: launch_ntt_a<4>(c, data, map, jobs, inverse, s); break;
-        case 5: launch_ntt_a<5>(c, data, map, jobs, inverse, s); break;
-        case 6: launch_ntt_a<6>(c, data, map, jobs, inverse, s); break;
-        case 7: launch_ntt_a<7>(c, data, map, jobs, inverse, s); break;
-        case 8: launch_ntt_a<8>(c, data, map, jobs, inverse, s); break;
-    }
+static void launch_fwd_contig(const ckks_ctx* c, const FwdContigArgs& a, hipStream_t s) {
+    const u32 jobs = a.sel.n_l * a.sel.n_inst;
+    ProfScope ps(c, PK_FWD_CONTIG, (u64)jobs * 2, s);
+    const dim3 grid(xcd_grid(a.sel.n_l * tiles_of(c), a.sel.n_inst)), block(256);
+    DISPATCH_A(c, hipLaunchKernelGGL((fwd_contig_kernel<A>), grid, block, 0, s, a, c->tb));
 }
 
-static LimbMap plain_map(u32 n_limbs, u32 prime_first) { return LimbMap{n_limbs, n_limbs, 0, prime_first, 0, 1}; }
+template <int OWN, bool HOISTED>
+static void launch_ks_inner(const ckks_ctx* c, const InnerArgs& a, hipStream_t s) {
+    const u64 per_inst = (u64)c->dnum * c->D - c->L              // extended digits outside their own limbs
+                         + (u64)c->L * (OWN == OWN_TENSOR ? 2 : 1)  // the switched polynomial on its own limbs
+                         + 2 * (u64)c->D;                         // c' written
+    const u64 key = (u64)c->dnum * 2 * c->D;
+    ProfScope ps(c, PK_KS_INNER, a.n_inst * per_inst + (HOISTED ? a.n_inst : 1) * key, s);
+    const dim3 grid(xcd_grid(c->D * tiles_of(c), a.n_inst)), block(256);
+    DISPATCH_A(c, hipLaunchKernelGGL((ks_inner_kernel<A, OWN, HOISTED>), grid, block, 0, s, a, c->tb));
+}
+
+template <int MODE>
+static void launch_ks_final(const ckks_ctx* c, const FinalArgs& a, hipStream_t s) {
+    u64 limbs;
+    if (MODE == FIN_HOISTED) limbs = (u64)a.n_rot * c->L * (2 + 2 + 1 + 1) + (u64)c->L * (2 + (a.accumulate ? 2 : 0));
+    else limbs = (u64)a.n_inst * c->L * (6 + (MODE == FIN_HMULT ? 4 : MODE == FIN_HROT ? 1 : 0));
+    ProfScope ps(c, PK_KS_FINAL, limbs, s);
+    const dim3 grid(xcd_grid(c->L * tiles_of(c), a.n_inst)), block(256);
+    DISPATCH_A(c, hipLaunchKernelGGL((ks_final_kernel<A, MODE>), grid, block, 0, s, a, c->tb));
+}
 
 template <int AL>
-static void launch_modup_a(const ckks_ctx* c, const u64* in, u64* out, u32 batch, int write_own, hipStream_t s) {
+static void launch_modup_a(const ckks_ctx* c, const u64* in, u64* out, u32 batch, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, c->dnum, batch), block(256);
-    const u64 limbs = (u64)batch * (c->L + (u64)c->dnum * (c->D - c->alpha) + (write_own ? c->L : 0));
-    ProfScope ps(c, PK_MODUP, limbs * sizeof(u64) << c->logN, s);
-    hipLaunchKernelGGL(modup_kernel<AL>, grid, block, 0, s, in, out, c->conv, c->logN, c->L, c->D, c->dnum, write_own);
+    ProfScope ps(c, PK_MODUP, (u64)batch * (2 * (u64)c->L + (u64)c->dnum * (c->D - c->alpha)), s);
+    hipLaunchKernelGGL(modup_kernel<AL>, grid, block, 0, s, in, out, c->tb);
 }
-static void launch_modup(const ckks_ctx* c, const u64* in, u64* out, u32 batch, int write_own, hipStream_t s) {
+static void launch_modup(const ckks_ctx* c, const u64* in, u64* out, u32 batch, hipStream_t s) {
     switch (c->alpha) {
-        case 1: launch_modup_a<1>(c, in, out, batch, write_own, s); break;
-        case 2: launch_modup_a<2>(c, in, out, batch, write_own, s); break;
-        case 3: launch_modup_a<3>(c, in, out, batch, write_own, s); break;
-        case 4: launch_modup_a<4>(c, in, out, batch, write_own, s); break;
-        case 5: launch_modup_a<5>(c, in, out, batch, write_own, s); break;
-        case 6: launch_modup_a<6>(c, in, out, batch, write_own, s); break;
-        case 7: launch_modup_a<7>(c, in, out, batch, write_own, s); break;
-        case 8: launch_modup_a<8>(c, in, out, batch, write_own, s); break;
+        case 1: launch_modup_a<1>(c, in, out, batch, s); break;
+        case 2: launch_modup_a<2>(c, in, out, batch, s); break;
+        case 3: launch_modup_a<3>(c, in, out, batch, s); break;
+        case 4: launch_modup_a<4>(c, in, out, batch, s); break;
+        case 5: launch_modup_a<5>(c, in, out, batch, s); break;
+        case 6: launch_modup_a<6>(c, in, out, batch, s); break;
+        case 7: launch_modup_a<7>(c, in, out, batch, s); break;
+        case 8: launch_modup_a<8>(c, in, out, batch, s); break;
     }
 }
 
-template <int KK, bool FUSE>
+template <int KK>
 static void launch_moddown_k(const ckks_ctx* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, groups), block(256);
-    const u64 limbs = (u64)groups * (c->K + c->L + (FUSE ? c->L : 0));
-    ProfScope ps(c, PK_MODDOWN, limbs * sizeof(u64) << c->logN, s);
-    hipLaunchKernelGGL((moddown_kernel<KK, FUSE>), grid, block, 0, s, in, out, c->conv, c->logN, c->L, c->D);
+    ProfScope ps(c, PK_MODDOWN, (u64)groups * (c->K + 2 * (u64)c->L), s);
+    hipLaunchKernelGGL(moddown_kernel<KK>, grid, block, 0, s, in, out, c->tb);
 }
-template <bool FUSE>
 static void launch_moddown(const ckks_ctx* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
     switch (c->K) {
-        case 1: launch_moddown_k<1, FUSE>(c, in, out, groups, s); break;
-        case 2: launch_moddown_k<2, FUSE>(c, in, out, groups, s); break;
-        case 3: launch_moddown_k<3, FUSE>(c, in, out, groups, s); break;
-        case 4: launch_moddown_k<4, FUSE>(c, in, out, groups, s); break;
-        case 5: launch_moddown_k<5, FUSE>(c, in, out, groups, s); break;
-        case 6: launch_moddown_k<6, FUSE>(c, in, out, groups, s); break;
-        case 7: launch_moddown_k<7, FUSE>(c, in, out, groups, s); break;
-        case 8: launch_moddown_k<8, FUSE>(c, in, out, groups, s); break;
+        case 1: launch_moddown_k<1>(c, in, out, groups, s); break;
+        case 2: launch_moddown_k<2>(c, in, out, groups, s); break;
+        case 3: launch_moddown_k<3>(c, in, out, groups, s); break;
+        case 4: launch_moddown_k<4>(c, in, out, groups, s); break;
+        case 5: launch_moddown_k<5>(c, in, out, groups, s); break;
+        case 6: launch_moddown_k<6>(c, in, out, groups, s); break;
+        case 7: launch_moddown_k<7>(c, in, out, groups, s); break;
+        case 8: launch_moddown_k<8>(c, in, out, groups, s); break;
     }
 }
 
 // ---------------------------------------------------------------------- workspace carving
+// x  [xg][L][N]        coefficients of the switched polynomial (raw after pass 1, then canonical * pre-factor)
+// dt [dg][dnum][D][N]  extended digits (first forward pass done; own-digit limbs unused)
+// cq [cg][2][L][N]     c' on the q-limbs, canonical evaluation form
+// cp [cg][2][K][N]     c' on the special limbs: raw after the first inverse pass, then coefficients * pre-factor
+// cv [cg][2][L][N]     Conv_{P->Q} of the special part, first forward pass done
 struct Workspace {
-    u64 *x, *dt, *cp, *cv;
+    u64 *x, *dt, *cq, *cp, *cv;
 };
 
-static size_t ks_workspace_words(const ckks_ctx* c, u32 x_groups, u32 dt_groups, u32 cp_groups) {
+static size_t ks_workspace_words(const ckks_ctx* c, u32 xg, u32 dg, u32 cg) {
     const size_t N = (size_t)1 << c->logN;
-    return ((size_t)x_groups * c->L + (size_t)dt_groups * c->dnum * c->D + (size_t)cp_groups * 2 * c->D +
-            (size_t)cp_groups * 2 * c->L) * N;
+    return ((size_t)xg * c->L + (size_t)dg * c->dnum * c->D + (size_t)cg * 2 * (2 * (size_t)c->L + c->K)) * N;
 }
 
-static Workspace carve(const ckks_ctx* c, void* ws, u32 x_groups, u32 dt_groups, u32 cp_groups) {
+static Workspace carve(const ckks_ctx* c, void* ws, u32 xg, u32 dg, u32 cg) {
     const size_t N = (size_t)1 << c->logN;
     Workspace w;
     w.x = (u64*)ws;
-    w.dt = w.x + (size_t)x_groups * c->L * N;
-    w.cp = w.dt + (size_t)dt_groups * c->dnum * c->D * N;
-    w.cv = w.cp + (size_t)cp_groups * 2 * c->D * N;
+    w.dt = w.x + (size_t)xg * c->L * N;
+    w.cq = w.dt + (size_t)dg * c->dnum * c->D * N;
+    w.cp = w.cq + (size_t)cg * 2 * c->L * N;
+    w.cv = w.cp + (size_t)cg * 2 * c->K * N;
     return w;
 }
 
@@ -520,7 +606,19 @@ static int ntt_entry(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uint32_
     if (!d_x || misaligned(d_x, 16)) return fail(ctx, CKKS_EINVAL, "d_x is null or not 16-byte aligned");
     int rc = check_limb_range(ctx, prime_first, n_limbs, batch);
     if (rc) return rc;
-    launch_ntt(ctx, d_x, plain_map(n_limbs, prime_first), n_limbs * batch, inverse, (hipStream_t)stream);
+    hipStream_t s = (hipStream_t)stream;
+    const LimbSel sel = {n_limbs, batch, n_limbs, 0, prime_first, 0};
+    if (!inverse) {
+        FwdStridedArgs a1 = {d_x, d_x, sel, 0};
+        launch_fwd_strided<FWD_PLAIN>(ctx, a1, s);
+        FwdContigArgs a2 = {d_x, sel};
+        launch_fwd_contig(ctx, a2, s);
+    } else {
+        InvContigArgs a1 = {d_x, nullptr, d_x, sel, sel, 1};
+        launch_inv_contig<INV_PLAIN>(ctx, a1, s);
+        InvStridedArgs a2 = {d_x, sel, SC_PLAIN, 0};
+        launch_inv_strided(ctx, a2, s);
+    }
     return hip_check(ctx, inverse ? "ckks_intt" : "ckks_ntt");
 }
 
@@ -546,7 +644,7 @@ extern "C" int ckks_modup(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, 
         return fail(ctx, CKKS_EINVAL, "null or misaligned buffer");
     int rc = check_ks_ctx(ctx, batch);
     if (rc) return rc;
-    launch_modup(ctx, d_in, d_out, batch, 1, (hipStream_t)stream);
+    launch_modup(ctx, d_in, d_out, batch, (hipStream_t)stream);
     return hip_check(ctx, "ckks_modup");
 }
 
@@ -556,7 +654,7 @@ extern "C" int ckks_moddown(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out
         return fail(ctx, CKKS_EINVAL, "null or misaligned buffer");
     int rc = check_ks_ctx(ctx, batch);
     if (rc) return rc;
-    launch_moddown<true>(ctx, d_in, d_out, batch, (hipStream_t)stream);
+    launch_moddown(ctx, d_in, d_out, batch, (hipStream_t)stream);
     return hip_check(ctx, "ckks_moddown");
 }
 
@@ -578,7 +676,7 @@ extern "C" int ckks_automorph(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_o
     if (batch > 65535) return fail(ctx, CKKS_EINVAL, "batch too large");
     const dim3 grid((1u << ctx->logN) / 256, n_limbs, batch), block(256);
     hipStream_t s = (hipStream_t)stream;
-    ProfScope ps(ctx, PK_AUTOMORPH, (u64)batch * n_limbs * 2 * sizeof(u64) << ctx->logN, s);
+    ProfScope ps(ctx, PK_AUTOMORPH, (u64)batch * n_limbs * 2, s);
     if (eval_domain) {
         hipLaunchKernelGGL(automorph_eval_kernel, grid, block, 0, s, d_in, d_out, ctx->logN, n_limbs, galois);
     } else {
@@ -586,27 +684,10 @@ extern "C" int ckks_automorph(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_o
         u32 inv = galois;
         for (int i = 0; i < 5; i++) inv *= 2 - galois * inv;
         inv &= (2u << ctx->logN) - 1;
-        hipLaunchKernelGGL(automorph_coeff_kernel, grid, block, 0, s, d_in, d_out, ctx->ntt.pc, ctx->logN, n_limbs,
+        hipLaunchKernelGGL(automorph_coeff_kernel, grid, block, 0, s, d_in, d_out, ctx->tb.pc, ctx->logN, n_limbs,
                            prime_first, inv);
     }
     return hip_check(ctx, "ckks_automorph");
-}
-
-// Shared tail of every key switch.  On entry w.x holds the evaluation-form polynomial(s) to
-// switch, [x_groups][L][N], and the own-digit limbs of w.dt already hold the same values.
-// Leaves c' in w.cp ([cp_groups][2][D][N]) and NTT(Conv_{P->Q}(INTT(c'|P))) in w.cv.
-static void decompose_extend(const ckks_ctx* c, const Workspace& w, u32 groups, hipStream_t s) {
-    launch_ntt(c, w.x, plain_map(c->L, 0), groups * c->L, true, s);
-    launch_modup(c, w.x, w.dt, groups, 0, s);
-    const LimbMap ext = {c->D - c->alpha, c->D, 0, 0, c->alpha, c->dnum};
-    launch_ntt(c, w.dt, ext, groups * c->dnum * (c->D - c->alpha), false, s);
-}
-
-static void moddown_tail(const ckks_ctx* c, const Workspace& w, u32 cp_groups, hipStream_t s) {
-    const LimbMap special = {c->K, c->D, c->L, 0, 0, 1};
-    launch_ntt(c, w.cp, special, cp_groups * 2 * c->K, true, s);
-    launch_moddown<false>(c, w.cp, w.cv, cp_groups * 2, s);
-    launch_ntt(c, w.cv, plain_map(c->L, 0), cp_groups * 2 * c->L, false, s);
 }
 
 static int check_ks_args(const ckks_ctx* c, const void* a, const void* b, const void* out, u32 batch, int op,
@@ -623,37 +704,44 @@ static int check_ks_args(const ckks_ctx* c, const void* a, const void* b, const 
     return CKKS_OK;
 }
 
-template <int MODE>
-static void launch_prep(const ckks_ctx* c, const u64* in1, const u64* in2, const Workspace& w, u32 batch, u32 galois,
-                        hipStream_t s) {
-    const dim3 grid((1u << c->logN) / 256, c->L, batch), block(256);
-    const u64 limbs = (u64)batch * c->L * (MODE == PREP_TENSOR_D2 ? 4 : 3);
-    ProfScope ps(c, PK_PREP, limbs * sizeof(u64) << c->logN, s);
-    hipLaunchKernelGGL(prep_kernel<MODE>, grid, block, 0, s, in1, in2, w.x, w.dt, c->ntt.pc, c->logN, c->L, c->D,
-                       c->dnum, c->alpha, galois);
+// ModUp side shared by every key switch: w.x holds the first inverse pass of the polynomial(s).
+// Second inverse pass (scaled by the conversion pre-factor), then conversion fused into the
+// first forward pass of every extended limb.
+static void decompose_extend(const ckks_ctx* c, const Workspace& w, u32 groups, hipStream_t s) {
+    const LimbSel sel = {c->L, groups, c->L, 0, 0, 0};
+    InvStridedArgs a2 = {w.x, sel, SC_UP, 1};
+    launch_inv_strided(c, a2, s);
+    FwdStridedArgs a3 = {w.x, w.dt, sel, groups};
+    launch_fwd_strided<FWD_CONV_UP>(c, a3, s);
 }
 
-static void launch_inner_shared_key(const ckks_ctx* c, const Workspace& w, const u64* key, u32 batch, hipStream_t s) {
-    const size_t N = (size_t)1 << c->logN;
-    KeyPtrs kp;
-    memset(&kp, 0, sizeof(kp));
-    kp.key[0] = key;
-    const dim3 grid((1u << c->logN) / 256, c->D, batch), block(256);
-    // extended digits read, c' written, the shared key read once
-    const u64 limbs = (u64)batch * (c->dnum + 2) * c->D + (u64)c->dnum * 2 * c->D;
-    ProfScope ps(c, PK_INNER, limbs * sizeof(u64) << c->logN, s);
-    hipLaunchKernelGGL(inner_product_kernel<false>, grid, block, 0, s, (const u64*)w.dt, (size_t)c->dnum * c->D * N, kp,
-                       w.cp, c->ntt.pc, c->logN, c->D, c->dnum);
+// ModDown side: w.cp holds the first inverse pass of c' on the special limbs.
+static void moddown_convert(const ckks_ctx* c, const Workspace& w, u32 cg, hipStream_t s) {
+    const LimbSel sel = {c->K, cg * 2, c->K, 0, c->L, 0};
+    InvStridedArgs a6 = {w.cp, sel, SC_DN, 0};
+    launch_inv_strided(c, a6, s);
+    FwdStridedArgs a7 = {w.cp, w.cv, sel, cg * 2};
+    launch_fwd_strided<FWD_CONV_DN>(c, a7, s);
 }
 
-template <int MODE>
-static void launch_final(const ckks_ctx* c, const FinalArgs& fa, u32 groups, hipStream_t s) {
-    const dim3 grid((1u << c->logN) / 256, c->L, MODE == FIN_HOISTED ? 2 : groups * 2), block(256);
-    u64 limbs;  // c' and conv read, output written, plus the mode's extra operands
-    if (MODE == FIN_HOISTED) limbs = (u64)fa.n_rot * c->L * (4 + 1 + 1) + (u64)c->L * (2 + (fa.accumulate ? 2 : 0));
-    else limbs = (u64)groups * c->L * (6 + (MODE == FIN_HMULT ? 4 : MODE == FIN_HROT ? 1 : 0));
-    ProfScope ps(c, PK_FINAL, limbs * sizeof(u64) << c->logN, s);
-    hipLaunchKernelGGL(final_kernel<MODE>, grid, block, 0, s, fa, c->conv, c->logN, c->L, c->D);
+template <int LOAD, int OWN, int FIN>
+static void keyswitch_pipeline(const ckks_ctx* c, const u64* in1, const u64* in2, const u64* key, u64* out, u32 batch,
+                               u32 galois, void* ws, hipStream_t s) {
+    const Workspace w = carve(c, ws, batch, batch, batch);
+    const LimbSel sel = {c->L, batch, c->L, 0, 0, 0};
+    InvContigArgs a1 = {in1, in2, w.x, sel, sel, galois};
+    launch_inv_contig<LOAD>(c, a1, s);
+    decompose_extend(c, w, batch, s);
+    InnerArgs ia;
+    memset(&ia, 0, sizeof(ia));
+    ia.dt = w.dt, ia.own = in1, ia.own2 = in2, ia.key[0] = key, ia.galois[0] = galois;
+    ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = batch;
+    launch_ks_inner<OWN, false>(c, ia, s);
+    moddown_convert(c, w, batch, s);
+    FinalArgs fa;
+    memset(&fa, 0, sizeof(fa));
+    fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = in1, fa.ct2 = in2, fa.out = out, fa.galois[0] = galois, fa.n_inst = batch;
+    launch_ks_final<FIN>(c, fa, s);
 }
 
 extern "C" int ckks_keyswitch(ckks_ctx* ctx, const uint64_t* d_d, const uint64_t* d_key, uint64_t* d_out,
@@ -661,16 +749,8 @@ extern "C" int ckks_keyswitch(ckks_ctx* ctx, const uint64_t* d_d, const uint64_t
     if (!ctx) return CKKS_EINVAL;
     int rc = check_ks_args(ctx, d_d, d_key, d_out, batch, CKKS_OP_KEYSWITCH, d_ws, ws_bytes);
     if (rc) return rc;
-    hipStream_t s = (hipStream_t)stream;
-    const Workspace w = carve(ctx, d_ws, batch, batch, batch);
-    launch_prep<PREP_COPY>(ctx, d_d, nullptr, w, batch, 1, s);
-    decompose_extend(ctx, w, batch, s);
-    launch_inner_shared_key(ctx, w, d_key, batch, s);
-    moddown_tail(ctx, w, batch, s);
-    FinalArgs fa;
-    memset(&fa, 0, sizeof(fa));
-    fa.cp = w.cp, fa.cv = w.cv, fa.out = d_out;
-    launch_final<FIN_KS>(ctx, fa, batch, s);
+    keyswitch_pipeline<INV_PLAIN, OWN_COPY, FIN_KS>(ctx, d_d, nullptr, d_key, d_out, batch, 1, d_ws,
+                                                    (hipStream_t)stream);
     return hip_check(ctx, "ckks_keyswitch");
 }
 
@@ -680,16 +760,8 @@ extern "C" int ckks_hmult_relin(ckks_ctx* ctx, const uint64_t* d_ct1, const uint
     if (!d_ct2 || misaligned(d_ct2, 16)) return fail(ctx, CKKS_EINVAL, "null or misaligned buffer");
     int rc = check_ks_args(ctx, d_ct1, d_evk, d_out, batch, CKKS_OP_HMULT_RELIN, d_ws, ws_bytes);
     if (rc) return rc;
-    hipStream_t s = (hipStream_t)stream;
-    const Workspace w = carve(ctx, d_ws, batch, batch, batch);
-    launch_prep<PREP_TENSOR_D2>(ctx, d_ct1, d_ct2, w, batch, 1, s);
-    decompose_extend(ctx, w, batch, s);
-    launch_inner_shared_key(ctx, w, d_evk, batch, s);
-    moddown_tail(ctx, w, batch, s);
-    FinalArgs fa;
-    memset(&fa, 0, sizeof(fa));
-    fa.cp = w.cp, fa.cv = w.cv, fa.out = d_out, fa.ct1 = d_ct1, fa.ct2 = d_ct2;
-    launch_final<FIN_HMULT>(ctx, fa, batch, s);
+    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT>(ctx, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
+                                                          (hipStream_t)stream);
     return hip_check(ctx, "ckks_hmult_relin");
 }
 
@@ -700,16 +772,8 @@ extern "C" int ckks_hrot(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t galois, c
     if (rc) return rc;
     rc = check_galois(ctx, galois);
     if (rc) return rc;
-    hipStream_t s = (hipStream_t)stream;
-    const Workspace w = carve(ctx, d_ws, batch, batch, batch);
-    launch_prep<PREP_ROT_A>(ctx, d_ct, nullptr, w, batch, galois, s);
-    decompose_extend(ctx, w, batch, s);
-    launch_inner_shared_key(ctx, w, d_rk, batch, s);
-    moddown_tail(ctx, w, batch, s);
-    FinalArgs fa;
-    memset(&fa, 0, sizeof(fa));
-    fa.cp = w.cp, fa.cv = w.cv, fa.out = d_out, fa.ct1 = d_ct, fa.galois[0] = galois;
-    launch_final<FIN_HROT>(ctx, fa, batch, s);
+    keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(ctx, d_ct, nullptr, d_rk, d_out, batch, galois, d_ws,
+                                                   (hipStream_t)stream);
     return hip_check(ctx, "ckks_hrot");
 }
 
@@ -731,41 +795,42 @@ extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32
         rc = check_galois(ctx, h_galois[r]);
         if (rc) return rc;
     }
+    const ckks_ctx* c = ctx;
     hipStream_t s = (hipStream_t)stream;
-    const size_t N = (size_t)1 << ctx->logN;
+    const size_t N = (size_t)1 << c->logN;
     const u32 chunk_max = n_rot < CKKS_ROT_CHUNK ? n_rot : CKKS_ROT_CHUNK;
-    const Workspace w = carve(ctx, d_ws, 1, 1, chunk_max);
-    // hoisted part: decompose a = ct[1] once
+    const Workspace w = carve(c, d_ws, 1, 1, chunk_max);
+    // hoisted part: decompose a = ct[1] once and finish the transform of every extended limb
     {
-        const dim3 grid((1u << ctx->logN) / 256, ctx->L, 1), block(256);
-        ProfScope ps(ctx, PK_PREP, (u64)ctx->L * 3 * sizeof(u64) << ctx->logN, s);
-        hipLaunchKernelGGL(prep_kernel<PREP_COPY>, grid, block, 0, s, d_ct + (size_t)ctx->L * N, (const u64*)nullptr,
-                           w.x, w.dt, ctx->ntt.pc, ctx->logN, ctx->L, ctx->D, ctx->dnum, ctx->alpha, 1u);
+        const LimbSel src = {c->L, 1, c->L, c->L, 0, 0};  // limbs L .. 2L-1 of ct, primes 0 .. L-1
+        const LimbSel dst = {c->L, 1, c->L, 0, 0, 0};
+        InvContigArgs a1 = {d_ct, nullptr, w.x, src, dst, 1};
+        launch_inv_contig<INV_PLAIN>(c, a1, s);
+        decompose_extend(c, w, 1, s);
+        if (c->dnum > 1) {
+            FwdContigArgs q = {w.dt, LimbSel{c->L, c->dnum - 1, c->D, 0, 0, c->alpha}};
+            launch_fwd_contig(c, q, s);
+        }
+        FwdContigArgs p = {w.dt, LimbSel{c->K, c->dnum, c->D, c->L, c->L, 0}};
+        launch_fwd_contig(c, p, s);
     }
-    decompose_extend(ctx, w, 1, s);
     for (u32 r0 = 0; r0 < n_rot; r0 += CKKS_ROT_CHUNK) {
         const u32 nr = (n_rot - r0) < CKKS_ROT_CHUNK ? (n_rot - r0) : CKKS_ROT_CHUNK;
-        KeyPtrs kp;
-        memset(&kp, 0, sizeof(kp));
+        InnerArgs ia;
+        memset(&ia, 0, sizeof(ia));
         FinalArgs fa;
         memset(&fa, 0, sizeof(fa));
         for (u32 r = 0; r < nr; r++) {
-            kp.key[r] = h_rk_ptrs[r0 + r];
-            kp.galois[r] = h_galois[r0 + r];
+            ia.key[r] = h_rk_ptrs[r0 + r];
+            ia.galois[r] = h_galois[r0 + r];
             fa.galois[r] = h_galois[r0 + r];
         }
-        const dim3 grid((1u << ctx->logN) / 256, ctx->D, nr), block(256);
-        {
-            // per rotation: the shared extended digits gathered, its key read, c' written
-            const u64 limbs = (u64)nr * ((u64)ctx->dnum * ctx->D + (u64)ctx->dnum * 2 * ctx->D + 2 * ctx->D);
-            ProfScope ps(ctx, PK_INNER, limbs * sizeof(u64) << ctx->logN, s);
-            hipLaunchKernelGGL(inner_product_kernel<true>, grid, block, 0, s, (const u64*)w.dt, (size_t)0, kp, w.cp,
-                               ctx->ntt.pc, ctx->logN, ctx->D, ctx->dnum);
-        }
-        moddown_tail(ctx, w, nr, s);
-        fa.cp = w.cp, fa.cv = w.cv, fa.out = d_out, fa.ct1 = d_ct, fa.pt = d_pt + (size_t)r0 * ctx->L * N;
-        fa.n_rot = nr, fa.accumulate = r0 ? 1 : 0;
-        launch_final<FIN_HOISTED>(ctx, fa, 1, s);
+        ia.dt = w.dt, ia.own = d_ct, ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = nr;
+        launch_ks_inner<OWN_COPY, true>(c, ia, s);
+        moddown_convert(c, w, nr, s);
+        fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = d_ct, fa.pt = d_pt + (size_t)r0 * c->L * N, fa.out = d_out;
+        fa.n_inst = 2, fa.n_rot = nr, fa.accumulate = r0 ? 1 : 0;
+        launch_ks_final<FIN_HOISTED>(c, fa, s);
     }
     return hip_check(ctx, "ckks_hrot_hoisted_mac");
 }

@@ -1,0 +1,640 @@
+// Kernels of the key-switch path.  The paper (Section 2) names the NTT and the base conversion as
+// the major, memory-bound kernels and fuses several jobs into each memory load; here every
+// producer and consumer of a transform is fused into one of the two NTT passes:
+//
+//   inv_contig_kernel   load (copy | a1*a2 | sigma_g gather) -> first inverse pass
+//   inv_strided_kernel  second inverse pass -> scale by N^-1 (* base-conversion pre-factor)
+//   fwd_strided_kernel  load (plain | base conversion from the digit / special limbs) -> first forward pass
+//   fwd_contig_kernel   second forward pass -> canonical store
+//   ks_inner_kernel     second forward pass of every extended digit -> key inner product accumulated over
+//                       the digits in registers -> (special limbs) first inverse pass of ModDown
+//   ks_final_kernel     second forward pass of the converted special part -> (c' - .) * P^-1 + operand
+//                       (HMult tensor terms, sigma_g(b), or plaintext multiply-accumulate over rotations)
+//   modup_kernel / moddown_kernel / automorph kernels: the stand-alone coefficient-form entry points.
+//
+// Every kernel picks its arithmetic per limb: FpAr for primes below 3*2^48, IntAr otherwise.
+#pragma once
+#include "ntt.h"
+
+struct PinvConst {
+    u64 w, wp;
+    double d;
+};
+
+struct Tables {
+    const u64* tw_int;         // [D][4][N]  fwd w, fwd w', inv w, inv w'
+    const double* tw_fp;       // [D][2][N]  fwd w, inv w (FpAr primes only)
+    const PrimeConst* pc;      // [D]
+    const InvScale* sc_plain;  // [D]  N^-1
+    const InvScale* sc_up;     // [L]  N^-1 * [(Q_j/q_i)^-1]_{q_i}
+    const InvScale* sc_dn;     // [K]  N^-1 * [(P/p_k)^-1]_{p_k}
+    const u64* up_hatinv;      // [L][2]  [(Q_j/q_i)^-1]_{q_i} and Shoup companion (stand-alone ModUp)
+    const u64* dn_hatinv;      // [K][2]
+    const u64* up_chat;        // [L][D]  (Q_j/q_i) * 2^64 mod m_t   (0 inside the digit)
+    const double* up_chat_fp;  // [L][D]  (Q_j/q_i) mod m_t as a double (FpAr targets)
+    const u32* up_fp_ok;       // [dnum][D] 1 if target t of digit j may convert on the FP64 pipe: target and
+                               //           all sources FpAr primes, largest source <= 2 * target
+    const u64* dn_chat;        // [K][L]  (P/p_k) * 2^64 mod q_i
+    const PinvConst* pinv;     // [L]     P^-1 mod q_i
+    u32 logN, L, K, dnum, alpha, D;
+};
+
+// slot j of sigma_g(f) in evaluation form reads slot eval_perm(j) of f
+__device__ __forceinline__ u32 eval_perm(u32 j, u32 g, u32 logN) {
+    const u32 two_n_mask = (2u << logN) - 1;
+    u32 e = (g * (2 * (__brev(j) >> (32 - logN)) + 1)) & two_n_mask;
+    return __brev((e - 1) >> 1) >> (32 - logN);
+}
+
+// Limb addressing of the plain transform passes: instance `inst`, limb l of n_l:
+//   word offset (inst'*gs + first + l) * N, prime index prime_base + l, where inst' = inst unless
+//   skip_alpha != 0: then instances enumerate the digits that do NOT own limb first + l
+//   (inst' = inst + 1 from the owning digit (first + l) / skip_alpha on).
+struct LimbSel {
+    u32 n_l, n_inst, gs, first, prime_base, skip_alpha;
+};
+__device__ __forceinline__ size_t limb_offset(const LimbSel& s, u32 inst, u32 l) {
+    if (s.skip_alpha && inst >= (s.first + l) / s.skip_alpha) inst++;
+    return (size_t)inst * s.gs + s.first + l;
+}
+
+// ============================================================ inverse transform, first pass
+enum InvLoad { INV_PLAIN = 0, INV_TENSOR = 1, INV_ROT = 2 };
+struct InvContigArgs {
+    const u64* src;   // PLAIN: canonical eval-form limbs addressed by sel; TENSOR: ct1; ROT: ct
+    const u64* src2;  // TENSOR: ct2
+    u64* dst;         // raw inverse-lazy words, addressed by dsel
+    LimbSel sel, dsel;
+    u32 galois;
+};
+
+template <class AR, int A, int LOAD>
+__device__ __forceinline__ void inv_contig_body(const InvContigArgs& a, const Tables& tb, u64* lds, u32 l, u32 tile,
+                                                u32 inst) {
+    typedef typename AR::T T;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x, e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
+    const u32 pi = a.sel.prime_base + l;
+    const PrimeConst pc = tb.pc[pi];
+    const typename AR::Mod m = AR::mod(pc);
+    const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
+    const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
+    u64* lrow = lds + ch * 272;
+    T x[16];
+    if (LOAD == INV_PLAIN) {
+        const u64* p = a.src + limb_offset(a.sel, inst, l) * N + (size_t)r * 256;
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = AR::round_reduce(AR::from_canon(p[k * 16 + e0], m), m);
+    } else if (LOAD == INV_TENSOR) {  // d2 = a1 * a2 on limb l of pair `inst`
+        const size_t off = (((size_t)inst * 2 + 1) * tb.L + l) * N + (size_t)r * 256;
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const u64 v = mulmod_var(a.src[off + k * 16 + e0], a.src2[off + k * 16 + e0], pc.q, pc.qneg, pc.r2);
+            x[k] = AR::round_reduce(AR::from_canon(v, m), m);
+        }
+    } else {  // sigma_g(a) on limb l of ciphertext `inst`
+        const u64* p = a.src + (((size_t)inst * 2 + 1) * tb.L + l) * N;
+#pragma unroll
+        for (int k = 0; k < 16; k++)
+            x[k] = AR::round_reduce(AR::from_canon(p[eval_perm(r * 256 + k * 16 + e0, a.galois, tb.logN)], m), m);
+    }
+    exchange_ca_to_cb<AR>(x, lrow, e0);
+    NttCore<AR, A>::inv_contig(x, lrow, e0, r, ti, tf, N, m);
+    u64* o = a.dst + limb_offset(a.dsel, inst, l) * N + (size_t)r * 256;
+#pragma unroll
+    for (int k = 0; k < 16; k++) o[k * 16 + e0] = AR::to_raw(AR::round_reduce(x[k], m));
+}
+
+template <int A, int LOAD>
+__global__ __launch_bounds__(256) void inv_contig_kernel(InvContigArgs a, Tables tb) {
+    __shared__ u64 lds[NTT_LDS_WORDS];
+    constexpr u32 TILES = (1u << A) / 16;
+    u32 group, inst;
+    if (!xcd_decode(blockIdx.x, a.sel.n_inst, a.sel.n_l * TILES, group, inst)) return;
+    const u32 l = group / TILES, tile = group % TILES;
+    if (tb.pc[a.sel.prime_base + l].fp) inv_contig_body<FpAr, A, LOAD>(a, tb, lds, l, tile, inst);
+    else inv_contig_body<IntAr, A, LOAD>(a, tb, lds, l, tile, inst);
+}
+
+// =========================================================== inverse transform, second pass
+enum InvScaleSel { SC_PLAIN = 0, SC_UP = 1, SC_DN = 2 };
+struct InvStridedArgs {
+    u64* data;  // in place: raw inverse-lazy words in, canonical coefficients (times the scale) out
+    LimbSel sel;
+    u32 scale;   // InvScaleSel
+    u32 fp_out;  // 1: limbs of FpAr primes are stored as doubles (same canonical integer values)
+};
+
+template <class AR, int A>
+__device__ __forceinline__ void inv_strided_body(const InvStridedArgs& a, const Tables& tb, u64* lds, u32 l, u32 tile,
+                                                 u32 inst) {
+    typedef typename AR::T T;
+    typedef NttCore<AR, A> C;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x;
+    const u32 pi = a.sel.prime_base + l;
+    const typename AR::Mod m = AR::mod(tb.pc[pi]);
+    const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
+    const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
+    const InvScale sc = a.scale == SC_PLAIN ? tb.sc_plain[pi] : a.scale == SC_UP ? tb.sc_up[pi] : tb.sc_dn[pi - tb.L];
+    const u32 c = tid % C::TC, r0 = tid / C::TC, col = tile * C::TC + c;
+    u64* base = a.data + limb_offset(a.sel, inst, l) * N;
+    T x[16];
+    if constexpr (A > 4) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = AR::from_raw(base[(size_t)(r0 * 16 + k) * 256 + col]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = AR::from_raw(base[(size_t)(k * C::RB + r0) * 256 + col]);
+    }
+    C::inv_strided_but_last(x, lds, tid, ti, tf, N, m);
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+        u64 ox, oy;
+        AR::bfly_inv_last(x[k], x[k + 8], sc, m, a.fp_out != 0, ox, oy);
+        base[(size_t)(k * C::RB + r0) * 256 + col] = ox;
+        base[(size_t)((k + 8) * C::RB + r0) * 256 + col] = oy;
+    }
+}
+
+template <int A>
+__global__ __launch_bounds__(256) void inv_strided_kernel(InvStridedArgs a, Tables tb) {
+    __shared__ u64 lds[4096];
+    constexpr u32 TILES = (1u << A) / 16;
+    u32 group, inst;
+    if (!xcd_decode(blockIdx.x, a.sel.n_inst, a.sel.n_l * TILES, group, inst)) return;
+    const u32 l = group / TILES, tile = group % TILES;
+    if (tb.pc[a.sel.prime_base + l].fp) inv_strided_body<FpAr, A>(a, tb, lds, l, tile, inst);
+    else inv_strided_body<IntAr, A>(a, tb, lds, l, tile, inst);
+}
+
+// ============================================================ forward transform, first pass
+// FWD_PLAIN  : canonical coefficients addressed by sel (in place when dst == src).
+// FWD_CONV_UP: group = (b, digit j, tile), instance = target slot s of the D - alpha limbs outside the
+//              digit; sources y [b][L][N] (coefficients already times [(Q_j/q_i)^-1]); dst dt [b][dnum][D][N].
+// FWD_CONV_DN: group = (g, tile), instance = target q-limb i; sources y = special limbs [g][K][N];
+//              dst cv [g][L][N].
+enum FwdLoad { FWD_PLAIN = 0, FWD_CONV_UP = 1, FWD_CONV_DN = 2 };
+struct FwdStridedArgs {
+    const u64* src;
+    u64* dst;  // raw forward-lazy words
+    LimbSel sel;
+    u32 groups_outer;  // CONV_UP: batch; CONV_DN: number of g
+};
+
+// base-conversion operands of one target limb (workgroup-uniform)
+struct ConvSel {
+    const u64* chat;        // Montgomery-form constants, stride chat_stride per source
+    const double* chat_fp;  // the same constants as plain doubles
+    u32 chat_stride, ns;    // number of source limbs
+    u32 src_prime;          // prime index of source 0
+    u32 src_fp_fmt;         // sources of FpAr primes are stored as doubles
+    u32 fp_ok;              // the FP64 conversion path is valid for this target
+};
+
+template <class AR, int A, int LOAD>
+__device__ __forceinline__ void fwd_strided_body(const FwdStridedArgs& a, const Tables& tb, u64* lds, u32 pi,
+                                                 const u64* src, u64* dst, const ConvSel& cv, u32 tile) {
+    typedef typename AR::T T;
+    typedef NttCore<AR, A> C;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x;
+    const PrimeConst pc = tb.pc[pi];
+    const typename AR::Mod m = AR::mod(pc);
+    const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
+    const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
+    const u32 c = tid % C::TC, r0 = tid / C::TC, col = tile * C::TC + c;
+    T x[16];
+    if (LOAD == FWD_PLAIN) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = AR::from_canon(src[(size_t)(k * C::RB + r0) * 256 + col], m);
+    } else if (AR::is_fp && cv.fp_ok) {
+        // sources are doubles holding canonical residues; accumulate lazily reduced products
+        double acc[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) acc[k] = 0.0;
+        for (u32 i = 0; i < cv.ns; i++) {
+            const double cf = cv.chat_fp[(size_t)i * cv.chat_stride];
+            const u64* si = src + (size_t)i * N;
+#pragma unroll
+            for (int k = 0; k < 16; k++)
+                acc[k] += FpAr::mulmod_lazy(FpAr::from_raw(si[(size_t)(k * C::RB + r0) * 256 + col]), cf, FpAr::mod(pc));
+        }
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = AR::from_f64_lazy(acc[k], m);
+    } else {
+        u128w acc[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) acc[k] = u128w{0, 0};
+        for (u32 i = 0; i < cv.ns; i++) {
+            const u64 cc = cv.chat[(size_t)i * cv.chat_stride];
+            const u64* si = src + (size_t)i * N;
+            const bool src_fp = cv.src_fp_fmt && tb.pc[cv.src_prime + i].fp;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
+                if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+                mac128(acc[k], y, cc);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = AR::from_canon(redc(acc[k], pc.q, pc.qneg), m);
+    }
+    C::fwd_strided(x, lds, tid, ti, tf, N, m);
+    if constexpr (A > 4) {
+#pragma unroll
+        for (int k = 0; k < 16; k++) dst[(size_t)(r0 * 16 + k) * 256 + col] = AR::to_raw(AR::round_reduce(x[k], m));
+    } else {
+#pragma unroll
+        for (int k = 0; k < 16; k++)
+            dst[(size_t)(k * C::RB + r0) * 256 + col] = AR::to_raw(AR::round_reduce(x[k], m));
+    }
+}
+
+template <int A, int LOAD>
+__global__ __launch_bounds__(256) void fwd_strided_kernel(FwdStridedArgs a, Tables tb) {
+    __shared__ u64 lds[4096];
+    constexpr u32 TILES = (1u << A) / 16;
+    const u32 N = 1u << tb.logN;
+    u32 group, inst, pi, tile;
+    const u64* src;
+    u64* dst;
+    ConvSel cv = {nullptr, nullptr, 0, 0, 0, 0, 0};
+    if (LOAD == FWD_PLAIN) {
+        if (!xcd_decode(blockIdx.x, a.sel.n_inst, a.sel.n_l * TILES, group, inst)) return;
+        const u32 l = group / TILES;
+        tile = group % TILES;
+        pi = a.sel.prime_base + l;
+        const size_t off = limb_offset(a.sel, inst, l) * N;
+        src = a.src + off;
+        dst = a.dst + off;
+    } else if (LOAD == FWD_CONV_UP) {
+        const u32 n_t = tb.D - tb.alpha;
+        if (!xcd_decode(blockIdx.x, n_t, a.groups_outer * tb.dnum * TILES, group, inst)) return;
+        tile = group % TILES;
+        const u32 bj = group / TILES, j = bj % tb.dnum, b = bj / tb.dnum;
+        pi = inst < j * tb.alpha ? inst : inst + tb.alpha;
+        src = a.src + ((size_t)b * tb.L + (size_t)j * tb.alpha) * N;
+        dst = a.dst + (((size_t)b * tb.dnum + j) * tb.D + pi) * N;
+        cv.chat = tb.up_chat + (size_t)j * tb.alpha * tb.D + pi;
+        cv.chat_fp = tb.up_chat_fp + (size_t)j * tb.alpha * tb.D + pi;
+        cv.chat_stride = tb.D;
+        cv.ns = tb.alpha;
+        cv.src_prime = j * tb.alpha;
+        cv.src_fp_fmt = 1;
+        cv.fp_ok = tb.up_fp_ok[j * tb.D + pi];
+    } else {
+        if (!xcd_decode(blockIdx.x, tb.L, a.groups_outer * TILES, group, inst)) return;
+        tile = group % TILES;
+        const u32 g = group / TILES;
+        pi = inst;
+        src = a.src + (size_t)g * tb.K * N;
+        dst = a.dst + ((size_t)g * tb.L + pi) * N;
+        cv.chat = tb.dn_chat + pi;
+        cv.chat_stride = tb.L;
+        cv.ns = tb.K;
+        cv.src_prime = tb.L;
+    }
+    if (tb.pc[pi].fp) fwd_strided_body<FpAr, A, LOAD>(a, tb, lds, pi, src, dst, cv, tile);
+    else fwd_strided_body<IntAr, A, LOAD>(a, tb, lds, pi, src, dst, cv, tile);
+}
+
+// =========================================================== forward transform, second pass
+struct FwdContigArgs {
+    u64* data;  // in place: raw forward-lazy words in, canonical evaluation form out
+    LimbSel sel;
+};
+
+template <class AR, int A>
+__device__ __forceinline__ void fwd_contig_body(const FwdContigArgs& a, const Tables& tb, u64* lds, u32 l, u32 tile,
+                                                u32 inst) {
+    typedef typename AR::T T;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x, e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
+    const u32 pi = a.sel.prime_base + l;
+    const typename AR::Mod m = AR::mod(tb.pc[pi]);
+    const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
+    const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
+    u64* lrow = lds + ch * 272;
+    u64* p = a.data + limb_offset(a.sel, inst, l) * N + (size_t)r * 256;
+    T x[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = AR::from_raw(p[k * 16 + e0]);
+    NttCore<AR, A>::fwd_contig(x, lrow, e0, r, ti, tf, N, m);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) lrow[pad16(e0 * 16 + k)] = AR::canon_fwd(x[k], m);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) p[k * 16 + e0] = lrow[pad16(k * 16 + e0)];
+}
+
+template <int A>
+__global__ __launch_bounds__(256) void fwd_contig_kernel(FwdContigArgs a, Tables tb) {
+    __shared__ u64 lds[NTT_LDS_WORDS];
+    constexpr u32 TILES = (1u << A) / 16;
+    u32 group, inst;
+    if (!xcd_decode(blockIdx.x, a.sel.n_inst, a.sel.n_l * TILES, group, inst)) return;
+    const u32 l = group / TILES, tile = group % TILES;
+    if (tb.pc[a.sel.prime_base + l].fp) fwd_contig_body<FpAr, A>(a, tb, lds, l, tile, inst);
+    else fwd_contig_body<IntAr, A>(a, tb, lds, l, tile, inst);
+}
+
+// ==================================================================== key inner product
+// Work item = (limb i of D, tile, instance).  For every digit j the evaluation-form value of the
+// extended digit on limb i is produced in registers -- the second forward pass of dt[.][j][i]
+// (NTT_INSIDE), or a gather from the already transformed digits (hoisted rotations), or, on the
+// digit's own limbs, the switched polynomial itself (copy | a1*a2 | sigma_g(a)) -- multiplied by
+// the two key components and accumulated.  q-limbs: c' is stored canonical.  Special limbs: the
+// first inverse pass of ModDown runs on the accumulators and raw words are stored.
+#define CKKS_ROT_CHUNK 8
+enum OwnLoad { OWN_COPY = 0, OWN_TENSOR = 1, OWN_ROT = 2 };
+struct InnerArgs {
+    const u64* dt;    // [inst or 1][dnum][D][N]: raw forward-lazy (NTT_INSIDE) or canonical eval (hoisted)
+    const u64* own;   // COPY: d [inst][L][N]; TENSOR: ct1; ROT: ct ([inst][2][L][N]); hoisted: ct [2][L][N]
+    const u64* own2;  // TENSOR: ct2
+    const u64* key[CKKS_ROT_CHUNK];  // one shared key (index 0) or one per instance (hoisted)
+    u32 galois[CKKS_ROT_CHUNK];      // ROT: [0]; hoisted: per instance
+    u64* cq;                         // [inst][2][L][N] canonical
+    u64* cp;                         // [inst][2][K][N] raw inverse-lazy after the first inverse pass
+    u32 n_inst;
+};
+
+template <class AR, int A, int OWN, bool HOISTED>
+__device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile,
+                                              u32 inst) {
+    typedef typename AR::T T;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x, e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
+    const u32 L = tb.L, D = tb.D;
+    const PrimeConst pc = tb.pc[i];
+    const typename AR::Mod m = AR::mod(pc);
+    const u64* ti = tb.tw_int + (size_t)i * 4 * N;
+    const double* tf = tb.tw_fp + (size_t)i * 2 * N;
+    u64* lrow = lds + ch * 272;
+    const u32 row_off = r * 256;
+    const u64* key = a.key[HOISTED ? inst : 0] + (size_t)i * N + row_off;
+    const u32 gal = HOISTED ? a.galois[inst] : a.galois[0];
+    const u32 own_digit = i < L ? i / tb.alpha : 0xffffffffu;
+    T acc0[16], acc1[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
+    for (u32 j = 0; j < tb.dnum; j++) {
+        T v[16];
+        if (j == own_digit) {
+            if (HOISTED) {
+                const u64* p = a.own + ((size_t)L + i) * N;
+#pragma unroll
+                for (int k = 0; k < 16; k++)
+                    v[k] = AR::round_reduce(AR::from_canon(p[eval_perm(row_off + k * 16 + e0, gal, tb.logN)], m), m);
+            } else if (OWN == OWN_COPY) {
+                const u64* p = a.own + ((size_t)inst * L + i) * N + row_off;
+#pragma unroll
+                for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(AR::from_canon(p[k * 16 + e0], m), m);
+            } else if (OWN == OWN_TENSOR) {
+                const size_t off = (((size_t)inst * 2 + 1) * L + i) * N + row_off;
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    const u64 t = mulmod_var(a.own[off + k * 16 + e0], a.own2[off + k * 16 + e0], pc.q, pc.qneg, pc.r2);
+                    v[k] = AR::round_reduce(AR::from_canon(t, m), m);
+                }
+            } else {
+                const u64* p = a.own + (((size_t)inst * 2 + 1) * L + i) * N;
+#pragma unroll
+                for (int k = 0; k < 16; k++)
+                    v[k] = AR::round_reduce(AR::from_canon(p[eval_perm(row_off + k * 16 + e0, gal, tb.logN)], m), m);
+            }
+        } else if (HOISTED) {
+            const u64* p = a.dt + ((size_t)j * D + i) * N;
+#pragma unroll
+            for (int k = 0; k < 16; k++)
+                v[k] = AR::round_reduce(AR::from_canon(p[eval_perm(row_off + k * 16 + e0, gal, tb.logN)], m), m);
+        } else {
+            const u64* p = a.dt + (((size_t)inst * tb.dnum + j) * D + i) * N + row_off;
+#pragma unroll
+            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+            NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
+#pragma unroll
+            for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(v[k], m);
+            exchange_cb_to_ca<AR>(v, lrow, e0);
+        }
+        const u64* k0 = key + ((size_t)j * 2 + 0) * D * N;
+        const u64* k1 = key + ((size_t)j * 2 + 1) * D * N;
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            AR::acc_mac(acc0[k], v[k], k0[k * 16 + e0], m);
+            AR::acc_mac(acc1[k], v[k], k1[k * 16 + e0], m);
+        }
+    }
+    if (i < L) {
+        u64* o0 = a.cq + (((size_t)inst * 2 + 0) * L + i) * N + row_off;
+        u64* o1 = a.cq + (((size_t)inst * 2 + 1) * L + i) * N + row_off;
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            o0[k * 16 + e0] = AR::acc_canon(AR::acc_finish(acc0[k], m), m);
+            o1[k * 16 + e0] = AR::acc_canon(AR::acc_finish(acc1[k], m), m);
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            T x[16];
+#pragma unroll
+            for (int k = 0; k < 16; k++) x[k] = AR::acc_finish(t ? acc1[k] : acc0[k], m);
+            exchange_ca_to_cb<AR>(x, lrow, e0);
+            NttCore<AR, A>::inv_contig(x, lrow, e0, r, ti, tf, N, m);
+            u64* o = a.cp + (((size_t)inst * 2 + t) * tb.K + (i - L)) * N + row_off;
+#pragma unroll
+            for (int k = 0; k < 16; k++) o[k * 16 + e0] = AR::to_raw(AR::round_reduce(x[k], m));
+        }
+    }
+}
+
+template <int A, int OWN, bool HOISTED>
+__global__ __launch_bounds__(256) void ks_inner_kernel(InnerArgs a, Tables tb) {
+    __shared__ u64 lds[NTT_LDS_WORDS];
+    constexpr u32 TILES = (1u << A) / 16;
+    u32 group, inst;
+    if (!xcd_decode(blockIdx.x, a.n_inst, tb.D * TILES, group, inst)) return;
+    const u32 i = group / TILES, tile = group % TILES;
+    if (tb.pc[i].fp) ks_inner_body<FpAr, A, OWN, HOISTED>(a, tb, lds, i, tile, inst);
+    else ks_inner_body<IntAr, A, OWN, HOISTED>(a, tb, lds, i, tile, inst);
+}
+
+// ======================================================================== final combine
+// ks_t[i] = (c'_t[i] - NTT(conv_t)[i]) * P^-1 mod q_i, the NTT's second pass done here, then
+//   FIN_KS     : out[inst][t][i] = ks
+//   FIN_HMULT  : out = ks + (t == 0 ? b1*b2 : a1*b2 + a2*b1)
+//   FIN_HROT   : out = ks + (t == 0 ? sigma_g(b) : 0)
+//   FIN_HOISTED: out[t][i] (+)= sum_r pt_r[i] * (ks_r + (t == 0 ? sigma_{g_r}(b) : 0)); work item (i, tile, t)
+enum FinalMode { FIN_KS = 0, FIN_HMULT = 1, FIN_HROT = 2, FIN_HOISTED = 3 };
+struct FinalArgs {
+    const u64* cq;   // [g][2][L][N] canonical
+    const u64* cv;   // [g][2][L][N] raw forward-lazy (first pass done)
+    const u64* ct1;  // HMULT: ct1; HROT / HOISTED: ct
+    const u64* ct2;  // HMULT: ct2
+    const u64* pt;   // HOISTED: plaintexts of this chunk [n_rot][L][N]
+    u64* out;
+    u32 galois[CKKS_ROT_CHUNK];
+    u32 n_inst;      // batch (or 2 for HOISTED: the component t)
+    u32 n_rot;       // HOISTED
+    u32 accumulate;  // HOISTED: add to what out already holds
+};
+
+template <class AR, int A, int MODE>
+__device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile, u32 inst) {
+    typedef typename AR::T T;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x, e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
+    const u32 L = tb.L;
+    const PrimeConst pc = tb.pc[i];
+    const typename AR::Mod m = AR::mod(pc);
+    const PinvConst pinv = tb.pinv[i];
+    const u64* ti = tb.tw_int + (size_t)i * 4 * N;
+    const double* tf = tb.tw_fp + (size_t)i * 2 * N;
+    u64* lrow = lds + ch * 272;
+    const u32 row_off = r * 256;
+    const u64 q = pc.q;
+    if (MODE == FIN_HOISTED) {
+        const u32 t = inst;
+        u128w acc[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) acc[k] = u128w{0, 0};
+        for (u32 rr = 0; rr < a.n_rot; rr++) {
+            T v[16];
+            const u64* p = a.cv + (((size_t)rr * 2 + t) * L + i) * N + row_off;
+#pragma unroll
+            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+            NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
+            exchange_cb_to_ca<AR>(v, lrow, e0);
+            const u64* c = a.cq + (((size_t)rr * 2 + t) * L + i) * N + row_off;
+            const u64* ptp = a.pt + ((size_t)rr * L + i) * N + row_off;
+            const u64* bp = a.ct1 + (size_t)i * N;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                u64 ks = mul_shoup(submod(c[k * 16 + e0], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
+                if (t == 0) ks = addmod(ks, bp[eval_perm(row_off + k * 16 + e0, a.galois[rr], tb.logN)], q);
+                mac128(acc[k], ks, ptp[k * 16 + e0]);
+            }
+        }
+        u64* o = a.out + ((size_t)t * L + i) * N + row_off;
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            u64 res = reduce128(acc[k], q, pc.qneg, pc.r2);
+            if (a.accumulate) res = addmod(res, o[k * 16 + e0], q);
+            o[k * 16 + e0] = res;
+        }
+        return;
+    }
+#pragma unroll
+    for (int t = 0; t < 2; t++) {
+        T v[16];
+        const u64* p = a.cv + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+#pragma unroll
+        for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+        NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
+        exchange_cb_to_ca<AR>(v, lrow, e0);
+        const u64* c = a.cq + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+        u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+        const size_t o0 = (((size_t)inst * 2 + 0) * L + i) * N + row_off, o1 = o0 + (size_t)L * N;
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const u32 e = k * 16 + e0;
+            u64 ks = mul_shoup(submod(c[e], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
+            if (MODE == FIN_HMULT) {
+                u128w s = {0, 0};
+                if (t == 0) {
+                    mac128(s, a.ct1[o0 + e], a.ct2[o0 + e]);
+                } else {
+                    mac128(s, a.ct1[o1 + e], a.ct2[o0 + e]);
+                    mac128(s, a.ct2[o1 + e], a.ct1[o0 + e]);
+                }
+                ks = addmod(ks, reduce128(s, q, pc.qneg, pc.r2), q);
+            } else if (MODE == FIN_HROT) {
+                if (t == 0) ks = addmod(ks, a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[0], tb.logN)], q);
+            }
+            o[e] = ks;
+        }
+    }
+}
+
+template <int A, int MODE>
+__global__ __launch_bounds__(256) void ks_final_kernel(FinalArgs a, Tables tb) {
+    __shared__ u64 lds[NTT_LDS_WORDS];
+    constexpr u32 TILES = (1u << A) / 16;
+    u32 group, inst;
+    if (!xcd_decode(blockIdx.x, a.n_inst, tb.L * TILES, group, inst)) return;
+    const u32 i = group / TILES, tile = group % TILES;
+    if (tb.pc[i].fp) ks_final_body<FpAr, A, MODE>(a, tb, lds, i, tile, inst);
+    else ks_final_body<IntAr, A, MODE>(a, tb, lds, i, tile, inst);
+}
+
+// ================================================== stand-alone coefficient-form base conversions
+// in [b][L][N] coeff -> out [b][dnum][D][N].  grid (N/256, dnum, batch).
+template <int ALPHA>
+__global__ __launch_bounds__(256) void modup_kernel(const u64* __restrict__ in, u64* __restrict__ out, Tables tb) {
+    const u32 N = 1u << tb.logN, L = tb.L, D = tb.D;
+    const u32 n = blockIdx.x * 256 + threadIdx.x, j = blockIdx.y, b = blockIdx.z;
+    const u64* src = in + ((size_t)b * L + (size_t)j * ALPHA) * N + n;
+    u64* dst = out + ((size_t)b * tb.dnum + j) * D * N + n;
+    u64 y[ALPHA];
+#pragma unroll
+    for (int ii = 0; ii < ALPHA; ii++) {
+        const u32 i = j * ALPHA + ii;
+        const u64 x = src[(size_t)ii * N];
+        dst[(size_t)i * N] = x;
+        y[ii] = mul_shoup(x, tb.up_hatinv[2 * i], tb.up_hatinv[2 * i + 1], tb.pc[i].q);
+    }
+    const u64* chat = tb.up_chat + (size_t)j * ALPHA * D;
+    for (u32 t = 0; t < D; t++) {
+        if (t >= j * ALPHA && t < (j + 1) * ALPHA) continue;
+        u128w acc = {0, 0};
+#pragma unroll
+        for (int ii = 0; ii < ALPHA; ii++) mac128(acc, y[ii], chat[(size_t)ii * D + t]);
+        const PrimeConst pc = tb.pc[t];
+        dst[(size_t)t * N] = redc(acc, pc.q, pc.qneg);
+    }
+}
+
+// in [g][D][N] coeff -> out [g][L][N] = (in_i - conv_i) * P^-1.  grid (N/256, groups).
+template <int KK>
+__global__ __launch_bounds__(256) void moddown_kernel(const u64* __restrict__ in, u64* __restrict__ out, Tables tb) {
+    const u32 N = 1u << tb.logN, L = tb.L, D = tb.D;
+    const u32 n = blockIdx.x * 256 + threadIdx.x, g = blockIdx.y;
+    const u64* src = in + (size_t)g * D * N + n;
+    u64* dst = out + (size_t)g * L * N + n;
+    u64 y[KK];
+#pragma unroll
+    for (int k = 0; k < KK; k++)
+        y[k] = mul_shoup(src[(size_t)(L + k) * N], tb.dn_hatinv[2 * k], tb.dn_hatinv[2 * k + 1], tb.pc[L + k].q);
+    for (u32 i = 0; i < L; i++) {
+        u128w acc = {0, 0};
+#pragma unroll
+        for (int k = 0; k < KK; k++) mac128(acc, y[k], tb.dn_chat[(size_t)k * L + i]);
+        const PrimeConst pc = tb.pc[i];
+        const u64 conv = redc(acc, pc.q, pc.qneg);
+        const PinvConst pi = tb.pinv[i];
+        dst[(size_t)i * N] = mul_shoup(submod(src[(size_t)i * N], conv, pc.q), pi.w, pi.wp, pc.q);
+    }
+}
+
+// ------------------------------------------------------------------------ automorphism
+__global__ __launch_bounds__(256) void automorph_eval_kernel(const u64* __restrict__ in, u64* __restrict__ out, u32 logN,
+                                                             u32 n_limbs, u32 galois) {
+    const u32 N = 1u << logN;
+    const u32 n = blockIdx.x * 256 + threadIdx.x;
+    const size_t limb = ((size_t)blockIdx.z * n_limbs + blockIdx.y) * N;
+    out[limb + n] = in[limb + eval_perm(n, galois, logN)];
+}
+
+// coefficient form, as a gather: out[u] = +-in[t] with t*g = u (mod 2N) or t*g = u + N (mod 2N)
+__global__ __launch_bounds__(256) void automorph_coeff_kernel(const u64* __restrict__ in, u64* __restrict__ out,
+                                                              const PrimeConst* pcs, u32 logN, u32 n_limbs,
+                                                              u32 prime_first, u32 galois_inv) {
+    const u32 N = 1u << logN;
+    const u32 u = blockIdx.x * 256 + threadIdx.x;
+    const size_t limb = ((size_t)blockIdx.z * n_limbs + blockIdx.y) * N;
+    const u64 q = pcs[prime_first + blockIdx.y].q;
+    const u32 tp = (u * galois_inv) & (2 * N - 1);
+    u64 v;
+    if (tp < N) {
+        v = in[limb + tp];
+    } else {
+        v = in[limb + tp - N];
+        v = v ? q - v : 0;
+    }
+    out[limb + u] = v;
+}

@@ -1,295 +1,186 @@
-// Two-pass negacyclic NTT / inverse NTT over limb batches (paper, Section 2: the NTT is one of
-// the two major, memory-bound kernels of the RNS-CKKS GPU library).
+// Building blocks of the two-pass negacyclic NTT / inverse NTT (paper, Section 2: the NTT is one
+// of the two major, memory-bound kernels of the RNS-CKKS GPU library).
 //
 // N = 2^logN = R1 * 256 with R1 = 2^A rows (A = logN - 8).  A limb is viewed as an R1 x 256
-// matrix in row-major order.  The forward transform (natural order in, bit-reversed order out)
-// runs its first A butterfly stages down the columns ("strided" pass) and the last 8 stages
-// inside each 256-word row ("contiguous" pass); the inverse runs the mirror image.  Every
-// workgroup of 256 threads owns 4096 words; each thread keeps 16 words in registers, performs up
-// to 4 radix-2 stages on them, exchanges through LDS once and performs the remaining stages.
-// Global accesses are segments of >= 128 contiguous bytes.
+// row-major matrix.  The forward transform (natural order in, bit-reversed order out) runs its
+// first A butterfly stages down the columns ("strided" pass) and the last 8 stages inside each
+// 256-word row ("contiguous" pass); the inverse runs the mirror image.  A workgroup of 256
+// threads owns 4096 words; a thread keeps 16 words in registers, performs up to 4 radix-2 stages
+// on them, exchanges through LDS once and performs the remaining stages.  The passes are written
+// as device functions over the register array so that producers (base conversion, tensor
+// product, automorphism) and consumers (key inner product, final combine) fuse into them.
 //
-// Twiddle convention: W[k] = psi^bitrev(k), k < N, so that the stage with `g` groups uses
-// W[g + i] for group i; the inverse uses the same layout built from psi^-1.
+// Register layouts of the 16 words x[k] of thread `tid`:
+//   strided pass, tile = all R1 rows x TC = 4096/R1 columns, c = tid % TC, r0 = tid / TC:
+//     layout SA: row k*(R1/16) + r0, column c        layout SB: row r0*16 + k, column c
+//   contiguous pass, tile = 16 rows, e0 = tid % 16, ch = tid / 16 (row within the tile):
+//     layout CA: word k*16 + e0 of the row            layout CB: word e0*16 + k of the row
+// CA and SA/SB are the coalesced layouts (>= 128 contiguous bytes per 16 lanes).
+//
+// Twiddle convention: W[k] = psi^bitrev(k), k < N: the stage with g groups uses W[g + i] for
+// group i; the inverse uses the same layout built from psi^-1.
 #pragma once
 #include "modarith.h"
 
-struct PrimeConst {
-    u64 q;        // the prime
-    u64 qneg;     // -q^-1 mod 2^64
-    u64 r2;       // 2^128 mod q
-    u64 ninv;     // N^-1 mod q
-    u64 ninv_p;   // its Shoup companion
-    u64 wlast;    // psi^-bitrev(1) * N^-1 mod q  (twiddle of the last inverse stage, pre-scaled)
-    u64 wlast_p;  // its Shoup companion
-    u64 pad;
-};
-
-struct NttTables {
-    const u64* tw;         // [n_primes][4][N]: forward w, forward w', inverse w, inverse w'
-    const PrimeConst* pc;  // [n_primes]
-    u32 logN;
-};
-
-// Which limbs of a buffer a launch works on.  Job `id` -> group g = id / cnt, l' = id % cnt,
-// limb-in-group l = first + l' (plus alpha if skip_alpha and l >= (g % dnum) * alpha, which
-// skips the limbs owned by digit g % dnum); word offset (g*gs + l) * N; prime prime_base + l.
-struct LimbMap {
-    u32 cnt, gs, first, prime_base, skip_alpha, dnum;
-};
-
-__device__ __forceinline__ void resolve_limb(const LimbMap& m, u32 id, u32& limb_off, u32& prime) {
-    u32 g = id / m.cnt;
-    u32 l = m.first + id % m.cnt;
-    if (m.skip_alpha) {
-        u32 j = g % m.dnum;
-        if (l >= j * m.skip_alpha) l += m.skip_alpha;
-    }
-    limb_off = g * m.gs + l;
-    prime = m.prime_base + l;
-}
-
-__device__ __forceinline__ void bfly_fwd(u64& X, u64& Y, u64 w, u64 wp, u64 q, u64 q2) {
-    u64 x = X >= q2 ? X - q2 : X;
-    u64 t = mul_shoup_lazy(Y, w, wp, q);
-    X = x + t;
-    Y = x - t + q2;
-}
-
-__device__ __forceinline__ void bfly_inv(u64& X, u64& Y, u64 w, u64 wp, u64 q, u64 q2) {
-    u64 s = X + Y;
-    u64 d = X - Y + q2;
-    X = s >= q2 ? s - q2 : s;
-    Y = mul_shoup_lazy(d, w, wp, q);
-}
-
-#define NTT_LDS_CHUNK 272  // 256 words + one pad word per 16
+#define NTT_LDS_WORDS (16 * 272)  // 16 rows of 256 words + one pad word per 16
 __device__ __forceinline__ u32 pad16(u32 e) { return e + (e >> 4); }
 
-// ------------------------------------------------------------------ forward, strided pass
-template <int A>
-__global__ __launch_bounds__(256) void ntt_fwd_strided_kernel(u64* __restrict__ data, LimbMap map, NttTables tb) {
-    constexpr int R1 = 1 << A, TC = 4096 / R1, RB = R1 / 16, TILES = R1 / 16;
-    __shared__ u64 lds[4096];
-    const u32 N = 1u << tb.logN;
-    const u32 tid = threadIdx.x;
-    const u32 tile = blockIdx.x % TILES, job = blockIdx.x / TILES;
-    u32 limb_off, pi;
-    resolve_limb(map, job, limb_off, pi);
-    u64* base = data + (size_t)limb_off * N;
-    const u64* W = tb.tw + (size_t)pi * 4 * N;
-    const u64* Wp = W + N;
-    const u64 q = tb.pc[pi].q, q2 = 2 * q;
-    const u32 c = tid % TC, r0 = tid / TC, col = tile * TC + c;
+template <class AR, int A>
+struct NttCore {
+    typedef typename AR::T T;
+    typedef typename AR::Mod Mod;
+    static constexpr int R1 = 1 << A, TC = 4096 / R1, RB = R1 / 16;
 
-    u64 x[16];
+    // ---- forward strided pass: x in layout SA -> all A stages -> layout SB (A > 4) or SA (A == 4)
+    static __device__ __forceinline__ void fwd_strided(T (&x)[16], u64* lds, u32 tid, const u64* ti, const double* tf,
+                                                       u32 N, const Mod& m) {
 #pragma unroll
-    for (int k = 0; k < 16; k++) x[k] = base[(size_t)(k * RB + r0) * 256 + col];
-#pragma unroll
-    for (int s = 0; s < 4; s++) {
-        const int d = 8 >> s;
-#pragma unroll
-        for (int k = 0; k < 16; k++) {
-            if (k & d) continue;
-            const u32 ti = (1u << s) + (k >> (4 - s));
-            bfly_fwd(x[k], x[k + d], W[ti], Wp[ti], q, q2);
-        }
-    }
-    if constexpr (A == 4) {
-#pragma unroll
-        for (int k = 0; k < 16; k++) base[(size_t)(k * RB + r0) * 256 + col] = x[k];
-    } else {
-#pragma unroll
-        for (int k = 0; k < 16; k++) lds[k * 256 + tid] = x[k];
-        __syncthreads();
-        const u32 r1 = r0;
-#pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = lds[(r1 * 16 + k) * TC + c];
-#pragma unroll
-        for (int s = 4; s < A; s++) {
-            const int d = 1 << (A - s - 1);
+        for (int s = 0; s < 4; s++) {
+            const int d = 8 >> s;
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 if (k & d) continue;
-                const u32 ti = (1u << s) + ((r1 * 16 + k) >> (A - s));
-                bfly_fwd(x[k], x[k + d], W[ti], Wp[ti], q, q2);
+                AR::bfly_fwd(x[k], x[k + d], AR::tw(ti, tf, (1u << s) + (k >> (4 - s)), N, false), m);
             }
         }
+        if constexpr (A > 4) {
+            const u32 c = tid % TC, r1 = tid / TC;
 #pragma unroll
-        for (int k = 0; k < 16; k++) base[(size_t)(r1 * 16 + k) * 256 + col] = x[k];
-    }
-}
-
-// --------------------------------------------------------------- forward, contiguous pass
-// Input values in [0, 4q); output canonical.
-template <int A>
-__global__ __launch_bounds__(256) void ntt_fwd_contig_kernel(u64* __restrict__ data, LimbMap map, NttTables tb) {
-    constexpr int R1 = 1 << A, TILES = R1 / 16;
-    __shared__ u64 lds[16 * NTT_LDS_CHUNK];
-    const u32 N = 1u << tb.logN;
-    const u32 tid = threadIdx.x;
-    const u32 tile = blockIdx.x % TILES, job = blockIdx.x / TILES;
-    u32 limb_off, pi;
-    resolve_limb(map, job, limb_off, pi);
-    const u64* W = tb.tw + (size_t)pi * 4 * N;
-    const u64* Wp = W + N;
-    const u64 q = tb.pc[pi].q, q2 = 2 * q;
-    const u32 e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
-    u64* ptr = data + (size_t)limb_off * N + (size_t)r * 256;
-    u64* l = lds + ch * NTT_LDS_CHUNK;
-
-    u64 x[16];
+            for (int k = 0; k < 16; k++) lds[k * 256 + tid] = AR::to_raw(AR::round_reduce(x[k], m));
+            __syncthreads();
 #pragma unroll
-    for (int k = 0; k < 16; k++) x[k] = ptr[k * 16 + e0];
+            for (int k = 0; k < 16; k++) x[k] = AR::from_raw(lds[(r1 * 16 + k) * TC + c]);
 #pragma unroll
-    for (int u = 0; u < 4; u++) {
-        const int d = 8 >> u;
+            for (int s = 4; s < A; s++) {
+                const int d = 1 << (A - s - 1);
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            if (k & d) continue;
-            const u32 ti = (1u << (A + u)) + (r << u) + (k >> (4 - u));
-            bfly_fwd(x[k], x[k + d], W[ti], Wp[ti], q, q2);
+                for (int k = 0; k < 16; k++) {
+                    if (k & d) continue;
+                    AR::bfly_fwd(x[k], x[k + d], AR::tw(ti, tf, (1u << s) + ((r1 * 16 + k) >> (A - s)), N, false), m);
+                }
+            }
         }
     }
-#pragma unroll
-    for (int k = 0; k < 16; k++) l[pad16(k * 16 + e0)] = x[k];
-    __syncthreads();
-    const u32 e1 = e0;
-#pragma unroll
-    for (int k = 0; k < 16; k++) x[k] = l[pad16(e1 * 16 + k)];
-#pragma unroll
-    for (int u = 4; u < 8; u++) {
-        const int d = 8 >> (u - 4);
-#pragma unroll
-        for (int k = 0; k < 16; k++) {
-            if (k & d) continue;
-            const u32 ti = (1u << (A + u)) + (r << u) + ((e1 * 16 + k) >> (8 - u));
-            bfly_fwd(x[k], x[k + d], W[ti], Wp[ti], q, q2);
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) l[pad16(e1 * 16 + k)] = csub(csub(x[k], q2), q);
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) ptr[k * 16 + e0] = l[pad16(k * 16 + e0)];
-}
 
-// --------------------------------------------------------------- inverse, contiguous pass
-// Input canonical (evaluation form); output in [0, 2q).
-template <int A>
-__global__ __launch_bounds__(256) void ntt_inv_contig_kernel(u64* __restrict__ data, LimbMap map, NttTables tb) {
-    constexpr int R1 = 1 << A, TILES = R1 / 16;
-    __shared__ u64 lds[16 * NTT_LDS_CHUNK];
-    const u32 N = 1u << tb.logN;
-    const u32 tid = threadIdx.x;
-    const u32 tile = blockIdx.x % TILES, job = blockIdx.x / TILES;
-    u32 limb_off, pi;
-    resolve_limb(map, job, limb_off, pi);
-    const u64* W = tb.tw + (size_t)pi * 4 * N + 2 * (size_t)N;
-    const u64* Wp = W + N;
-    const u64 q = tb.pc[pi].q, q2 = 2 * q;
-    const u32 e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
-    u64* ptr = data + (size_t)limb_off * N + (size_t)r * 256;
-    u64* l = lds + ch * NTT_LDS_CHUNK;
-
-    u64 x[16];
+    // ---- forward contiguous pass: x in layout CA (row r of the limb) -> 8 stages -> layout CB
+    static __device__ __forceinline__ void fwd_contig(T (&x)[16], u64* l, u32 e0, u32 r, const u64* ti,
+                                                      const double* tf, u32 N, const Mod& m) {
 #pragma unroll
-    for (int k = 0; k < 16; k++) l[pad16(k * 16 + e0)] = ptr[k * 16 + e0];
-    __syncthreads();
-    const u32 e1 = e0;
-#pragma unroll
-    for (int k = 0; k < 16; k++) x[k] = l[pad16(e1 * 16 + k)];
-#pragma unroll
-    for (int v = 0; v < 4; v++) {
-        const int d = 1 << v;
-#pragma unroll
-        for (int k = 0; k < 16; k++) {
-            if (k & d) continue;
-            const u32 ti = (N >> (v + 1)) + ((r * 256 + e1 * 16 + k) >> (v + 1));
-            bfly_inv(x[k], x[k + d], W[ti], Wp[ti], q, q2);
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) l[pad16(e1 * 16 + k)] = x[k];
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 16; k++) x[k] = l[pad16(k * 16 + e0)];
-#pragma unroll
-    for (int v = 4; v < 8; v++) {
-        const int d = 1 << (v - 4);
-#pragma unroll
-        for (int k = 0; k < 16; k++) {
-            if (k & d) continue;
-            const u32 ti = (N >> (v + 1)) + ((r * 256 + k * 16) >> (v + 1));
-            bfly_inv(x[k], x[k + d], W[ti], Wp[ti], q, q2);
-        }
-    }
-#pragma unroll
-    for (int k = 0; k < 16; k++) ptr[k * 16 + e0] = x[k];
-}
-
-// ------------------------------------------------------------------ inverse, strided pass
-// Input in [0, 2q); output canonical, scaled by N^-1 (natural-order coefficients).
-template <int A>
-__global__ __launch_bounds__(256) void ntt_inv_strided_kernel(u64* __restrict__ data, LimbMap map, NttTables tb) {
-    constexpr int R1 = 1 << A, TC = 4096 / R1, RB = R1 / 16, TILES = R1 / 16;
-    __shared__ u64 lds[4096];
-    const u32 N = 1u << tb.logN;
-    const u32 tid = threadIdx.x;
-    const u32 tile = blockIdx.x % TILES, job = blockIdx.x / TILES;
-    u32 limb_off, pi;
-    resolve_limb(map, job, limb_off, pi);
-    u64* base = data + (size_t)limb_off * N;
-    const u64* W = tb.tw + (size_t)pi * 4 * N + 2 * (size_t)N;
-    const u64* Wp = W + N;
-    const PrimeConst pc = tb.pc[pi];
-    const u64 q = pc.q, q2 = 2 * q;
-    const u32 c = tid % TC, r0 = tid / TC, col = tile * TC + c;
-
-    u64 x[16];
-    if constexpr (A > 4) {
-        const u32 r1 = r0;
-#pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = base[(size_t)(r1 * 16 + k) * 256 + col];
-#pragma unroll
-        for (int w = 0; w < A - 4; w++) {
-            const int d = 1 << w;
+        for (int u = 0; u < 4; u++) {
+            const int d = 8 >> u;
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 if (k & d) continue;
-                const u32 ti = (N >> (9 + w)) + ((r1 * 16 + k) >> (w + 1));
-                bfly_inv(x[k], x[k + d], W[ti], Wp[ti], q, q2);
+                AR::bfly_fwd(x[k], x[k + d], AR::tw(ti, tf, (1u << (A + u)) + (r << u) + (k >> (4 - u)), N, false), m);
             }
         }
 #pragma unroll
-        for (int k = 0; k < 16; k++) lds[(r1 * 16 + k) * TC + c] = x[k];
+        for (int k = 0; k < 16; k++) l[pad16(k * 16 + e0)] = AR::to_raw(AR::round_reduce(x[k], m));
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = lds[k * 256 + tid];
-    } else {
+        for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(e0 * 16 + k)]);
 #pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = base[(size_t)(k * RB + r0) * 256 + col];
-    }
+        for (int u = 4; u < 8; u++) {
+            const int d = 8 >> (u - 4);
 #pragma unroll
-    for (int w = A - 4; w < A - 1; w++) {
-        const int d = 1 << (w - A + 4);
-#pragma unroll
-        for (int k = 0; k < 16; k++) {
-            if (k & d) continue;
-            const u32 ti = (1u << (A - 1 - w)) + (k >> (w - A + 5));
-            bfly_inv(x[k], x[k + d], W[ti], Wp[ti], q, q2);
+            for (int k = 0; k < 16; k++) {
+                if (k & d) continue;
+                AR::bfly_fwd(x[k], x[k + d],
+                             AR::tw(ti, tf, (1u << (A + u)) + (r << u) + ((e0 * 16 + k) >> (8 - u)), N, false), m);
+            }
         }
     }
-    // last stage (one group, twiddle index 1) merged with the factor N^-1
+
+    // ---- inverse contiguous pass: x in layout CB (inverse-lazy range) -> 8 stages -> layout CA
+    static __device__ __forceinline__ void inv_contig(T (&x)[16], u64* l, u32 e0, u32 r, const u64* ti,
+                                                      const double* tf, u32 N, const Mod& m) {
 #pragma unroll
-    for (int k = 0; k < 8; k++) {
-        u64 s = x[k] + x[k + 8];
-        u64 d = x[k] - x[k + 8] + q2;
-        x[k] = mul_shoup(s, pc.ninv, pc.ninv_p, q);
-        x[k + 8] = mul_shoup(d, pc.wlast, pc.wlast_p, q);
+        for (int v = 0; v < 4; v++) {
+            const int d = 1 << v;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                if (k & d) continue;
+                AR::bfly_inv(x[k], x[k + d],
+                             AR::tw(ti, tf, (N >> (v + 1)) + ((r * 256 + e0 * 16 + k) >> (v + 1)), N, true), m);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 16; k++) l[pad16(e0 * 16 + k)] = AR::to_raw(AR::round_reduce(x[k], m));
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(k * 16 + e0)]);
+#pragma unroll
+        for (int v = 4; v < 8; v++) {
+            const int d = 1 << (v - 4);
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                if (k & d) continue;
+                AR::bfly_inv(x[k], x[k + d], AR::tw(ti, tf, (N >> (v + 1)) + ((r * 256 + k * 16) >> (v + 1)), N, true),
+                             m);
+            }
+        }
     }
+
+    // ---- inverse strided pass: x in layout SB (A > 4) or SA (A == 4) -> all stages but the last
+    //      -> layout SA.  The caller applies the last stage (pairs x[k], x[k+8]) with its scaling.
+    static __device__ __forceinline__ void inv_strided_but_last(T (&x)[16], u64* lds, u32 tid, const u64* ti,
+                                                                const double* tf, u32 N, const Mod& m) {
+        if constexpr (A > 4) {
+            const u32 c = tid % TC, r1 = tid / TC;
 #pragma unroll
-    for (int k = 0; k < 16; k++) base[(size_t)(k * RB + r0) * 256 + col] = x[k];
+            for (int w = 0; w < A - 4; w++) {
+                const int d = 1 << w;
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    if (k & d) continue;
+                    AR::bfly_inv(x[k], x[k + d], AR::tw(ti, tf, (N >> (9 + w)) + ((r1 * 16 + k) >> (w + 1)), N, true), m);
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 16; k++) lds[(r1 * 16 + k) * TC + c] = AR::to_raw(AR::round_reduce(x[k], m));
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < 16; k++) x[k] = AR::from_raw(lds[k * 256 + tid]);
+        }
+#pragma unroll
+        for (int w = A - 4; w < A - 1; w++) {
+            const int d = 1 << (w - A + 4);
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                if (k & d) continue;
+                AR::bfly_inv(x[k], x[k + d], AR::tw(ti, tf, (1u << (A - 1 - w)) + (k >> (w - A + 5)), N, true), m);
+            }
+        }
+    }
+};
+
+// exchange between the two contiguous-pass layouts through the row's LDS slice
+template <class AR>
+__device__ __forceinline__ void exchange_cb_to_ca(typename AR::T (&x)[16], u64* l, u32 e0) {
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) l[pad16(e0 * 16 + k)] = AR::to_raw(x[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(k * 16 + e0)]);
+}
+template <class AR>
+__device__ __forceinline__ void exchange_ca_to_cb(typename AR::T (&x)[16], u64* l, u32 e0) {
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) l[pad16(k * 16 + e0)] = AR::to_raw(x[k]);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(e0 * 16 + k)]);
+}
+
+// XCD-aware decode of a linear workgroup id.  Workgroups are handed to the 8 XCDs round-robin,
+// so ids congruent modulo 8 share an L2.  Work is organised as `groups` groups of `S` instances
+// that read the same tables / sources; all instances of a group get ids on one XCD, adjacent
+// in dispatch order.  The grid must hold ceil(groups/8)*8*S workgroups; returns false for padding.
+__device__ __forceinline__ bool xcd_decode(u32 bid, u32 S, u32 groups, u32& group, u32& inst) {
+    const u32 xcd = bid & 7, pos = bid >> 3;
+    inst = pos % S;
+    group = (pos / S) * 8 + xcd;
+    return group < groups;
 }

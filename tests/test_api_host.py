@@ -37,8 +37,8 @@ def test_every_declared_symbol_is_exported(lib):
 def test_table_bytes_and_shape_validation(lib):
     n = ctypes.c_size_t()
     assert lib.ckks_table_bytes(16, 24, 6, 4, ctypes.byref(n)) == 0
-    # 30 primes x 4 tables x 2^16 words dominate
-    assert 30 * 4 * 65536 * 8 <= n.value <= 30 * 4 * 65536 * 8 + (1 << 20)
+    # 30 primes x (4 integer + 2 floating-point) twiddle tables x 2^16 words dominate
+    assert 30 * 6 * 65536 * 8 <= n.value <= 30 * 6 * 65536 * 8 + (1 << 20)
     assert lib.ckks_table_bytes(16, 24, 6, 4, None) == -1
     assert lib.ckks_table_bytes(11, 24, 6, 4, ctypes.byref(n)) == -2      # ring too small
     assert lib.ckks_table_bytes(17, 24, 6, 4, ctypes.byref(n)) == -2      # ring too large

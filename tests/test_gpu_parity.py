@@ -393,6 +393,6 @@ def test_repeat_runs_are_bit_identical_and_profile_counts_launches(orc):
         assert np.array_equal(host(ctx.hrot(ct, g, rk)), first)
     prof = ctx.profile_read()
     ctx.profile_enable(False)
-    assert prof["inner_product_kernel"][0] == 3 and prof["modup_kernel"][0] == 3
-    assert prof["ntt_fwd_contig_kernel"][0] == 6 and prof["ntt_inv_strided_kernel"][0] == 6
+    assert prof["ks_inner_kernel"][0] == 3 and prof["ks_final_kernel"][0] == 3 and prof["inv_contig_kernel"][0] == 3
+    assert prof["fwd_strided_kernel"][0] == 6 and prof["inv_strided_kernel"][0] == 6
     assert all(ms > 0 for n, ms, b in prof.values() if n)
