@@ -86,7 +86,7 @@ static u64 h_min_root(u64 m, u32 logN) {
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct TableLayout {
-    size_t tw_int, tw_fp, pc, sc_plain, sc_up, sc_dn, up_hatinv, dn_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, pinv, total;
+    size_t tw_int, tw_fp, pc, sc_plain, sc_up, sc_dn, up_hatinv, dn_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, dn_chat_fp, dn_fp_ok, pinv, total;
 };
 
 static TableLayout table_layout(u32 logN, u32 L, u32 K) {
@@ -110,6 +110,8 @@ static TableLayout table_layout(u32 logN, u32 L, u32 K) {
     t.up_chat_fp = take(L * D * sizeof(double));
     t.up_fp_ok = take(L * D * sizeof(u32));
     t.dn_chat = take(K1 * L * sizeof(u64));
+    t.dn_chat_fp = take(K1 * L * 2 * sizeof(double));
+    t.dn_fp_ok = take(L * sizeof(u32));
     t.pinv = take(L * sizeof(PinvConst));
     t.total = o;
     return t;
@@ -268,6 +270,8 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     double* up_chat_fp = (double*)(host.data() + lay.up_chat_fp);
     u32* up_fp_ok = (u32*)(host.data() + lay.up_fp_ok);
     u64* dn_chat = (u64*)(host.data() + lay.dn_chat);
+    double* dn_chat_fp = (double*)(host.data() + lay.dn_chat_fp);
+    u32* dn_fp_ok = (u32*)(host.data() + lay.dn_fp_ok);
     PinvConst* pinv = (PinvConst*)(host.data() + lay.pinv);
     std::vector<u64> pw(N), ninv(D), wlast(D);
     for (u32 i = 0; i < D; i++) {
@@ -350,8 +354,12 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
             for (u32 kk = 0; kk < K; kk++)
                 if (kk != k) hb = h_mulmod(hb, c->primes[L + kk] % qi, qi);
             dn_chat[(size_t)k * L + i] = h_mont(hb, qi);
+            // chat_stride of the conversion kernel is L entries, i.e. 2L doubles: index (k*L + i)*2
+            dn_chat_fp[((size_t)k * L + i) * 2] = pc[i].fp ? (double)hb : 0.0;
+            dn_chat_fp[((size_t)k * L + i) * 2 + 1] = pc[i].fp ? (double)h_mulmod(hb, (1ull << 30) % qi, qi) : 0.0;
         }
     }
+    for (u32 i = 0; i < L; i++) dn_fp_ok[i] = (pc[i].fp && c->primes[i] >= (1ull << 28)) ? 1 : 0;
     for (u32 i = 0; i < L; i++) {
         const u64 qi = c->primes[i];
         u64 P = 1;
@@ -381,6 +389,8 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     tb.up_chat_fp = (const double*)(dbase + lay.up_chat_fp);
     tb.up_fp_ok = (const u32*)(dbase + lay.up_fp_ok);
     tb.dn_chat = (const u64*)(dbase + lay.dn_chat);
+    tb.dn_chat_fp = (const double*)(dbase + lay.dn_chat_fp);
+    tb.dn_fp_ok = (const u32*)(dbase + lay.dn_fp_ok);
     tb.pinv = (const PinvConst*)(dbase + lay.pinv);
     tb.logN = logN, tb.L = L, tb.K = K, tb.dnum = dnum, tb.alpha = alpha, tb.D = D;
     *out = c;
@@ -433,54 +443,125 @@ static int hip_check(const ckks_ctx* c, const char* what) {
 static inline u32 xcd_grid(u32 groups, u32 inst) { return ((groups + 7) / 8) * 8 * inst; }
 static inline u32 tiles_of(const ckks_ctx* c) { return (1u << (c->logN - 8)) / 16; }
 
-#define DISPATCH_A(c, CALL)                    \
-    switch ((c)->logN - 8) {                   \
-        case 4: { constexpr int A = 4; CALL; } break; \
-        case 5: { constexpr int A = 5; CALL; } break; \
-        case 6: { constexpr int A = 6; CALL; } break; \
-        case 7: { constexpr int A = 7; CALL; } break; \
-        case 8: { constexpr int A = 8; CALL; } break; \
+// Maximal runs of consecutive primes [lo, hi) that share an arithmetic (FpAr / IntAr).
+struct ClassRun {
+    u32 first, count;
+    bool fp;
+};
+static std::vector<ClassRun> class_runs(const ckks_ctx* c, u32 lo, u32 hi) {
+    std::vector<ClassRun> r;
+    for (u32 i = lo; i < hi; i++) {
+        const bool fp = c->primes[i] < CKKS_FP_PRIME_LIMIT;
+        if (!r.empty() && r.back().fp == fp) r.back().count++;
+        else r.push_back(ClassRun{i, 1, fp});
     }
+    return r;
+}
+
+// A launcher type L provides  template <class AR, int A> static void go(grid, stream, args, tables, run).
+template <class L, class ArgT>
+static void dispatch_kernel(const ckks_ctx* c, bool fp, dim3 grid, hipStream_t s, const ArgT& a, LimbRun run) {
+#define CKKS_CASE_A(AV)                                               \
+    case AV:                                                          \
+        if (fp) L::template go<FpAr, AV>(grid, s, a, c->tb, run);     \
+        else L::template go<IntAr, AV>(grid, s, a, c->tb, run);       \
+        break;
+    switch (c->logN - 8) {
+        CKKS_CASE_A(4)
+        CKKS_CASE_A(5)
+        CKKS_CASE_A(6)
+        CKKS_CASE_A(7)
+        CKKS_CASE_A(8)
+    }
+#undef CKKS_CASE_A
+}
+
+// One launch per arithmetic run of the primes [lo, hi).  limb_base converts a prime index into the
+// kernel's limb index.  by_limb: groups = run limbs x groups_n, instances = inst_n;
+// otherwise (conversion targets): groups = groups_n, instances = the run's limbs x inst_n.
+template <class L, class ArgT>
+static void launch_runs(const ckks_ctx* c, u32 lo, u32 hi, u32 limb_base, bool by_limb, u32 groups_n, u32 inst_n,
+                        const ArgT& a, hipStream_t s) {
+    for (const ClassRun& cr : class_runs(c, lo, hi)) {
+        const LimbRun run = {cr.first - limb_base, cr.count};
+        const dim3 grid(by_limb ? xcd_grid(cr.count * groups_n, inst_n) : xcd_grid(groups_n, cr.count * inst_n));
+        dispatch_kernel<L>(c, cr.fp, grid, s, a, run);
+    }
+}
+
+template <int LOAD>
+struct InvContigL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const InvContigArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((inv_contig_kernel<AR, A, LOAD>), g, dim3(256), 0, s, a, tb, run);
+    }
+};
+struct InvStridedL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const InvStridedArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((inv_strided_kernel<AR, A>), g, dim3(256), 0, s, a, tb, run);
+    }
+};
+template <int LOAD>
+struct FwdStridedL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const FwdStridedArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((fwd_strided_kernel<AR, A, LOAD>), g, dim3(256), 0, s, a, tb, run);
+    }
+};
+struct FwdContigL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const FwdContigArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((fwd_contig_kernel<AR, A>), g, dim3(256), 0, s, a, tb, run);
+    }
+};
+template <int OWN, bool HOISTED>
+struct KsInnerL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const InnerArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((ks_inner_kernel<AR, A, OWN, HOISTED>), g, dim3(256), 0, s, a, tb, run);
+    }
+};
+template <int MODE>
+struct KsFinalL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const FinalArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((ks_final_kernel<AR, A, MODE>), g, dim3(256), 0, s, a, tb, run);
+    }
+};
 
 template <int LOAD>
 static void launch_inv_contig(const ckks_ctx* c, const InvContigArgs& a, hipStream_t s) {
-    const u32 jobs = a.sel.n_l * a.sel.n_inst;
-    ProfScope ps(c, PK_INV_CONTIG, (u64)jobs * (LOAD == INV_TENSOR ? 3 : 2), s);
-    const dim3 grid(xcd_grid(a.sel.n_l * tiles_of(c), a.sel.n_inst)), block(256);
-    DISPATCH_A(c, hipLaunchKernelGGL((inv_contig_kernel<A, LOAD>), grid, block, 0, s, a, c->tb));
+    ProfScope ps(c, PK_INV_CONTIG, (u64)a.sel.n_l * a.sel.n_inst * (LOAD == INV_TENSOR ? 3 : 2), s);
+    const u32 pb = a.sel.prime_base;
+    launch_runs<InvContigL<LOAD>>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s);
 }
 
 static void launch_inv_strided(const ckks_ctx* c, const InvStridedArgs& a, hipStream_t s) {
-    const u32 jobs = a.sel.n_l * a.sel.n_inst;
-    ProfScope ps(c, PK_INV_STRIDED, (u64)jobs * 2, s);
-    const dim3 grid(xcd_grid(a.sel.n_l * tiles_of(c), a.sel.n_inst)), block(256);
-    DISPATCH_A(c, hipLaunchKernelGGL((inv_strided_kernel<A>), grid, block, 0, s, a, c->tb));
+    ProfScope ps(c, PK_INV_STRIDED, (u64)a.sel.n_l * a.sel.n_inst * 2, s);
+    const u32 pb = a.sel.prime_base;
+    launch_runs<InvStridedL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s);
 }
 
 template <int LOAD>
 static void launch_fwd_strided(const ckks_ctx* c, const FwdStridedArgs& a, hipStream_t s) {
-    u32 groups, inst;
-    u64 limbs;
     if (LOAD == FWD_PLAIN) {
-        groups = a.sel.n_l * tiles_of(c), inst = a.sel.n_inst;
-        limbs = (u64)a.sel.n_l * a.sel.n_inst * 2;
-    } else if (LOAD == FWD_CONV_UP) {
-        groups = a.groups_outer * c->dnum * tiles_of(c), inst = c->D - c->alpha;
-        limbs = (u64)a.groups_outer * (c->L + (u64)c->dnum * (c->D - c->alpha));
-    } else {
-        groups = a.groups_outer * tiles_of(c), inst = c->L;
-        limbs = (u64)a.groups_outer * (c->K + c->L);
+        ProfScope ps(c, PK_FWD_STRIDED, (u64)a.sel.n_l * a.sel.n_inst * 2, s);
+        const u32 pb = a.sel.prime_base;
+        launch_runs<FwdStridedL<LOAD>>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s);
+    } else if (LOAD == FWD_CONV_UP) {  // groups = (batch, digit, tile); instances = the run's target primes
+        ProfScope ps(c, PK_FWD_STRIDED, (u64)a.groups_outer * (c->L + (u64)c->dnum * (c->D - c->alpha)), s);
+        launch_runs<FwdStridedL<LOAD>>(c, 0, c->D, 0, false, a.groups_outer * c->dnum * tiles_of(c), 1, a, s);
+    } else {  // groups = (g, tile); instances = the run's target q-limbs
+        ProfScope ps(c, PK_FWD_STRIDED, (u64)a.groups_outer * (c->K + c->L), s);
+        launch_runs<FwdStridedL<LOAD>>(c, 0, c->L, 0, false, a.groups_outer * tiles_of(c), 1, a, s);
     }
-    ProfScope ps(c, PK_FWD_STRIDED, limbs, s);
-    const dim3 grid(xcd_grid(groups, inst)), block(256);
-    DISPATCH_A(c, hipLaunchKernelGGL((fwd_strided_kernel<A, LOAD>), grid, block, 0, s, a, c->tb));
 }
 
 static void launch_fwd_contig(const ckks_ctx* c, const FwdContigArgs& a, hipStream_t s) {
-    const u32 jobs = a.sel.n_l * a.sel.n_inst;
-    ProfScope ps(c, PK_FWD_CONTIG, (u64)jobs * 2, s);
-    const dim3 grid(xcd_grid(a.sel.n_l * tiles_of(c), a.sel.n_inst)), block(256);
-    DISPATCH_A(c, hipLaunchKernelGGL((fwd_contig_kernel<A>), grid, block, 0, s, a, c->tb));
+    ProfScope ps(c, PK_FWD_CONTIG, (u64)a.sel.n_l * a.sel.n_inst * 2, s);
+    const u32 pb = a.sel.prime_base;
+    launch_runs<FwdContigL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s);
 }
 
 template <int OWN, bool HOISTED>
@@ -490,8 +571,7 @@ static void launch_ks_inner(const ckks_ctx* c, const InnerArgs& a, hipStream_t s
                          + 2 * (u64)c->D;                         // c' written
     const u64 key = (u64)c->dnum * 2 * c->D;
     ProfScope ps(c, PK_KS_INNER, a.n_inst * per_inst + (HOISTED ? a.n_inst : 1) * key, s);
-    const dim3 grid(xcd_grid(c->D * tiles_of(c), a.n_inst)), block(256);
-    DISPATCH_A(c, hipLaunchKernelGGL((ks_inner_kernel<A, OWN, HOISTED>), grid, block, 0, s, a, c->tb));
+    launch_runs<KsInnerL<OWN, HOISTED>>(c, 0, c->D, 0, true, tiles_of(c), a.n_inst, a, s);
 }
 
 template <int MODE>
@@ -500,8 +580,7 @@ static void launch_ks_final(const ckks_ctx* c, const FinalArgs& a, hipStream_t s
     if (MODE == FIN_HOISTED) limbs = (u64)a.n_rot * c->L * (2 + 2 + 1 + 1) + (u64)c->L * (2 + (a.accumulate ? 2 : 0));
     else limbs = (u64)a.n_inst * c->L * (6 + (MODE == FIN_HMULT ? 4 : MODE == FIN_HROT ? 1 : 0));
     ProfScope ps(c, PK_KS_FINAL, limbs, s);
-    const dim3 grid(xcd_grid(c->L * tiles_of(c), a.n_inst)), block(256);
-    DISPATCH_A(c, hipLaunchKernelGGL((ks_final_kernel<A, MODE>), grid, block, 0, s, a, c->tb));
+    launch_runs<KsFinalL<MODE>>(c, 0, c->L, 0, true, tiles_of(c), a.n_inst, a, s);
 }
 
 template <int AL>
@@ -547,14 +626,16 @@ static void launch_moddown(const ckks_ctx* c, const u64* in, u64* out, u32 group
 // dt [dg][dnum][D][N]  extended digits (first forward pass done; own-digit limbs unused)
 // cq [cg][2][L][N]     c' on the q-limbs, canonical evaluation form
 // cp [cg][2][K][N]     c' on the special limbs: raw after the first inverse pass, then coefficients * pre-factor
+//                      (split: high 30-bit halves here, low halves in cl, both as doubles)
+// cl [cg][2][K][N]     low halves of the special-limb coefficients
 // cv [cg][2][L][N]     Conv_{P->Q} of the special part, first forward pass done
 struct Workspace {
-    u64 *x, *dt, *cq, *cp, *cv;
+    u64 *x, *dt, *cq, *cp, *cl, *cv;
 };
 
 static size_t ks_workspace_words(const ckks_ctx* c, u32 xg, u32 dg, u32 cg) {
     const size_t N = (size_t)1 << c->logN;
-    return ((size_t)xg * c->L + (size_t)dg * c->dnum * c->D + (size_t)cg * 2 * (2 * (size_t)c->L + c->K)) * N;
+    return ((size_t)xg * c->L + (size_t)dg * c->dnum * c->D + (size_t)cg * 2 * (2 * (size_t)c->L + 2 * (size_t)c->K)) * N;
 }
 
 static Workspace carve(const ckks_ctx* c, void* ws, u32 xg, u32 dg, u32 cg) {
@@ -564,7 +645,8 @@ static Workspace carve(const ckks_ctx* c, void* ws, u32 xg, u32 dg, u32 cg) {
     w.dt = w.x + (size_t)xg * c->L * N;
     w.cq = w.dt + (size_t)dg * c->dnum * c->D * N;
     w.cp = w.cq + (size_t)cg * 2 * c->L * N;
-    w.cv = w.cp + (size_t)cg * 2 * c->K * N;
+    w.cl = w.cp + (size_t)cg * 2 * c->K * N;
+    w.cv = w.cl + (size_t)cg * 2 * c->K * N;
     return w;
 }
 
@@ -609,14 +691,14 @@ static int ntt_entry(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uint32_
     hipStream_t s = (hipStream_t)stream;
     const LimbSel sel = {n_limbs, batch, n_limbs, 0, prime_first, 0};
     if (!inverse) {
-        FwdStridedArgs a1 = {d_x, d_x, sel, 0};
+        FwdStridedArgs a1 = {d_x, nullptr, d_x, sel, 0};
         launch_fwd_strided<FWD_PLAIN>(ctx, a1, s);
         FwdContigArgs a2 = {d_x, sel};
         launch_fwd_contig(ctx, a2, s);
     } else {
         InvContigArgs a1 = {d_x, nullptr, d_x, sel, sel, 1};
         launch_inv_contig<INV_PLAIN>(ctx, a1, s);
-        InvStridedArgs a2 = {d_x, sel, SC_PLAIN, 0};
+        InvStridedArgs a2 = {d_x, sel, SC_PLAIN, 0, nullptr};
         launch_inv_strided(ctx, a2, s);
     }
     return hip_check(ctx, inverse ? "ckks_intt" : "ckks_ntt");
@@ -709,18 +791,18 @@ static int check_ks_args(const ckks_ctx* c, const void* a, const void* b, const 
 // first forward pass of every extended limb.
 static void decompose_extend(const ckks_ctx* c, const Workspace& w, u32 groups, hipStream_t s) {
     const LimbSel sel = {c->L, groups, c->L, 0, 0, 0};
-    InvStridedArgs a2 = {w.x, sel, SC_UP, 1};
+    InvStridedArgs a2 = {w.x, sel, SC_UP, 1, nullptr};
     launch_inv_strided(c, a2, s);
-    FwdStridedArgs a3 = {w.x, w.dt, sel, groups};
+    FwdStridedArgs a3 = {w.x, nullptr, w.dt, sel, groups};
     launch_fwd_strided<FWD_CONV_UP>(c, a3, s);
 }
 
 // ModDown side: w.cp holds the first inverse pass of c' on the special limbs.
 static void moddown_convert(const ckks_ctx* c, const Workspace& w, u32 cg, hipStream_t s) {
     const LimbSel sel = {c->K, cg * 2, c->K, 0, c->L, 0};
-    InvStridedArgs a6 = {w.cp, sel, SC_DN, 0};
+    InvStridedArgs a6 = {w.cp, sel, SC_DN, 0, w.cl};
     launch_inv_strided(c, a6, s);
-    FwdStridedArgs a7 = {w.cp, w.cv, sel, cg * 2};
+    FwdStridedArgs a7 = {w.cp, w.cl, w.cv, sel, cg * 2};
     launch_fwd_strided<FWD_CONV_DN>(c, a7, s);
 }
 

@@ -35,6 +35,8 @@ struct Tables {
     const u32* up_fp_ok;       // [dnum][D] 1 if target t of digit j may convert on the FP64 pipe: target and
                                //           all sources FpAr primes, largest source <= 2 * target
     const u64* dn_chat;        // [K][L]  (P/p_k) * 2^64 mod q_i
+    const double* dn_chat_fp;  // [K][L][2]  (P/p_k) mod q_i and (P/p_k) * 2^30 mod q_i as doubles
+    const u32* dn_fp_ok;       // [L]  1 if q_i may convert on the FP64 pipe (FpAr prime, at least 2^28)
     const PinvConst* pinv;     // [L]     P^-1 mod q_i
     u32 logN, L, K, dnum, alpha, D;
 };
@@ -88,8 +90,7 @@ __device__ __forceinline__ void inv_contig_body(const InvContigArgs& a, const Ta
         const size_t off = (((size_t)inst * 2 + 1) * tb.L + l) * N + (size_t)r * 256;
 #pragma unroll
         for (int k = 0; k < 16; k++) {
-            const u64 v = mulmod_var(a.src[off + k * 16 + e0], a.src2[off + k * 16 + e0], pc.q, pc.qneg, pc.r2);
-            x[k] = AR::round_reduce(AR::from_canon(v, m), m);
+            x[k] = AR::round_reduce(AR::mul_canon(a.src[off + k * 16 + e0], a.src2[off + k * 16 + e0], pc, m), m);
         }
     } else {  // sigma_g(a) on limb l of ciphertext `inst`
         const u64* p = a.src + (((size_t)inst * 2 + 1) * tb.L + l) * N;
@@ -104,15 +105,19 @@ __device__ __forceinline__ void inv_contig_body(const InvContigArgs& a, const Ta
     for (int k = 0; k < 16; k++) o[k * 16 + e0] = AR::to_raw(AR::round_reduce(x[k], m));
 }
 
-template <int A, int LOAD>
-__global__ __launch_bounds__(256) void inv_contig_kernel(InvContigArgs a, Tables tb) {
+// Every transform kernel is compiled once per arithmetic and launched on a run of consecutive
+// limbs [run.first, run.first + run.count) whose primes all use that arithmetic.
+struct LimbRun {
+    u32 first, count;
+};
+
+template <class AR, int A, int LOAD>
+__global__ __launch_bounds__(256) void inv_contig_kernel(InvContigArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[NTT_LDS_WORDS];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;
-    if (!xcd_decode(blockIdx.x, a.sel.n_inst, a.sel.n_l * TILES, group, inst)) return;
-    const u32 l = group / TILES, tile = group % TILES;
-    if (tb.pc[a.sel.prime_base + l].fp) inv_contig_body<FpAr, A, LOAD>(a, tb, lds, l, tile, inst);
-    else inv_contig_body<IntAr, A, LOAD>(a, tb, lds, l, tile, inst);
+    if (!xcd_decode(blockIdx.x, a.sel.n_inst, run.count * TILES, group, inst)) return;
+    inv_contig_body<AR, A, LOAD>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
 }
 
 // =========================================================== inverse transform, second pass
@@ -122,6 +127,8 @@ struct InvStridedArgs {
     LimbSel sel;
     u32 scale;   // InvScaleSel
     u32 fp_out;  // 1: limbs of FpAr primes are stored as doubles (same canonical integer values)
+    u64* lo_out; // not NULL: every value y is stored split, double(y >> 30) in place and
+                 //           double(y mod 2^30) at the same offset of lo_out
 };
 
 template <class AR, int A>
@@ -150,20 +157,27 @@ __device__ __forceinline__ void inv_strided_body(const InvStridedArgs& a, const 
     for (int k = 0; k < 8; k++) {
         u64 ox, oy;
         AR::bfly_inv_last(x[k], x[k + 8], sc, m, a.fp_out != 0, ox, oy);
-        base[(size_t)(k * C::RB + r0) * 256 + col] = ox;
-        base[(size_t)((k + 8) * C::RB + r0) * 256 + col] = oy;
+        const size_t ix = (size_t)(k * C::RB + r0) * 256 + col, iy = (size_t)((k + 8) * C::RB + r0) * 256 + col;
+        if (a.lo_out) {
+            u64* lo = a.lo_out + limb_offset(a.sel, inst, l) * N;
+            base[ix] = FpAr::to_raw((double)(u32)(ox >> 30));
+            lo[ix] = FpAr::to_raw((double)(u32)(ox & 0x3fffffffu));
+            base[iy] = FpAr::to_raw((double)(u32)(oy >> 30));
+            lo[iy] = FpAr::to_raw((double)(u32)(oy & 0x3fffffffu));
+        } else {
+            base[ix] = ox;
+            base[iy] = oy;
+        }
     }
 }
 
-template <int A>
-__global__ __launch_bounds__(256) void inv_strided_kernel(InvStridedArgs a, Tables tb) {
+template <class AR, int A>
+__global__ __launch_bounds__(256) void inv_strided_kernel(InvStridedArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[4096];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;
-    if (!xcd_decode(blockIdx.x, a.sel.n_inst, a.sel.n_l * TILES, group, inst)) return;
-    const u32 l = group / TILES, tile = group % TILES;
-    if (tb.pc[a.sel.prime_base + l].fp) inv_strided_body<FpAr, A>(a, tb, lds, l, tile, inst);
-    else inv_strided_body<IntAr, A>(a, tb, lds, l, tile, inst);
+    if (!xcd_decode(blockIdx.x, a.sel.n_inst, run.count * TILES, group, inst)) return;
+    inv_strided_body<AR, A>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
 }
 
 // ============================================================ forward transform, first pass
@@ -175,7 +189,8 @@ __global__ __launch_bounds__(256) void inv_strided_kernel(InvStridedArgs a, Tabl
 enum FwdLoad { FWD_PLAIN = 0, FWD_CONV_UP = 1, FWD_CONV_DN = 2 };
 struct FwdStridedArgs {
     const u64* src;
-    u64* dst;  // raw forward-lazy words
+    const u64* src_lo;  // CONV_DN: the low 30-bit halves (src holds the high halves), both as doubles
+    u64* dst;           // raw forward-lazy words
     LimbSel sel;
     u32 groups_outer;  // CONV_UP: batch; CONV_DN: number of g
 };
@@ -183,11 +198,13 @@ struct FwdStridedArgs {
 // base-conversion operands of one target limb (workgroup-uniform)
 struct ConvSel {
     const u64* chat;        // Montgomery-form constants, stride chat_stride per source
-    const double* chat_fp;  // the same constants as plain doubles
+    const double* chat_fp;  // the same constants as plain doubles (CONV_DN: pairs c, c * 2^30)
+    const u64* src_lo;      // CONV_DN: low halves of the sources
     u32 chat_stride, ns;    // number of source limbs
     u32 src_prime;          // prime index of source 0
     u32 src_fp_fmt;         // sources of FpAr primes are stored as doubles
     u32 fp_ok;              // the FP64 conversion path is valid for this target
+    u32 rot;                // first source visited: targets that share sources walk them in different orders
 };
 
 template <class AR, int A, int LOAD>
@@ -205,12 +222,13 @@ __device__ __forceinline__ void fwd_strided_body(const FwdStridedArgs& a, const 
     if (LOAD == FWD_PLAIN) {
 #pragma unroll
         for (int k = 0; k < 16; k++) x[k] = AR::from_canon(src[(size_t)(k * C::RB + r0) * 256 + col], m);
-    } else if (AR::is_fp && cv.fp_ok) {
+    } else if (LOAD == FWD_CONV_UP && AR::is_fp && cv.fp_ok) {
         // sources are doubles holding canonical residues; accumulate lazily reduced products
         double acc[16];
 #pragma unroll
         for (int k = 0; k < 16; k++) acc[k] = 0.0;
-        for (u32 i = 0; i < cv.ns; i++) {
+        for (u32 i0 = 0; i0 < cv.ns; i0++) {
+            const u32 i = i0 + cv.rot < cv.ns ? i0 + cv.rot : i0 + cv.rot - cv.ns;
             const double cf = cv.chat_fp[(size_t)i * cv.chat_stride];
             const u64* si = src + (size_t)i * N;
 #pragma unroll
@@ -219,18 +237,43 @@ __device__ __forceinline__ void fwd_strided_body(const FwdStridedArgs& a, const 
         }
 #pragma unroll
         for (int k = 0; k < 16; k++) x[k] = AR::from_f64_lazy(acc[k], m);
+    } else if (LOAD == FWD_CONV_DN && AR::is_fp && cv.fp_ok) {
+        // sources are split y = yh * 2^30 + yl (two doubles): y * c = yh * (c * 2^30) + yl * c  (mod q)
+        double acc[16];
+#pragma unroll
+        for (int k = 0; k < 16; k++) acc[k] = 0.0;
+        for (u32 i0 = 0; i0 < cv.ns; i0++) {
+            const u32 i = i0 + cv.rot < cv.ns ? i0 + cv.rot : i0 + cv.rot - cv.ns;
+            const double cl = cv.chat_fp[(size_t)i * cv.chat_stride * 2], ch = cv.chat_fp[(size_t)i * cv.chat_stride * 2 + 1];
+            const u64* sh = src + (size_t)i * N;
+            const u64* sl = cv.src_lo + (size_t)i * N;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const size_t off = (size_t)(k * C::RB + r0) * 256 + col;
+                acc[k] += FpAr::mulmod_lazy(FpAr::from_raw(sh[off]), ch, FpAr::mod(pc)) +
+                          FpAr::mulmod_lazy(FpAr::from_raw(sl[off]), cl, FpAr::mod(pc));
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 16; k++) x[k] = AR::from_f64_lazy(acc[k], m);
     } else {
         u128w acc[16];
 #pragma unroll
         for (int k = 0; k < 16; k++) acc[k] = u128w{0, 0};
-        for (u32 i = 0; i < cv.ns; i++) {
+        for (u32 i0 = 0; i0 < cv.ns; i0++) {
+            const u32 i = i0 + cv.rot < cv.ns ? i0 + cv.rot : i0 + cv.rot - cv.ns;
             const u64 cc = cv.chat[(size_t)i * cv.chat_stride];
             const u64* si = src + (size_t)i * N;
             const bool src_fp = cv.src_fp_fmt && tb.pc[cv.src_prime + i].fp;
 #pragma unroll
             for (int k = 0; k < 16; k++) {
-                u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
-                if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+                const size_t off = (size_t)(k * C::RB + r0) * 256 + col;
+                u64 y = si[off];
+                if (LOAD == FWD_CONV_DN) {
+                    y = ((u64)(u32)FpAr::from_raw(y) << 30) | (u32)FpAr::from_raw(cv.src_lo[(size_t)i * N + off]);
+                } else if (src_fp) {
+                    y = f64_to_u64(FpAr::from_raw(y));
+                }
                 mac128(acc[k], y, cc);
             }
         }
@@ -248,29 +291,31 @@ __device__ __forceinline__ void fwd_strided_body(const FwdStridedArgs& a, const 
     }
 }
 
-template <int A, int LOAD>
-__global__ __launch_bounds__(256) void fwd_strided_kernel(FwdStridedArgs a, Tables tb) {
+// run: FWD_PLAIN limbs of sel; FWD_CONV_UP / FWD_CONV_DN target primes (targets inside the source digit
+// are skipped).
+template <class AR, int A, int LOAD>
+__global__ __launch_bounds__(256) void fwd_strided_kernel(FwdStridedArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[4096];
     constexpr u32 TILES = (1u << A) / 16;
     const u32 N = 1u << tb.logN;
     u32 group, inst, pi, tile;
     const u64* src;
     u64* dst;
-    ConvSel cv = {nullptr, nullptr, 0, 0, 0, 0, 0};
+    ConvSel cv = {nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
     if (LOAD == FWD_PLAIN) {
-        if (!xcd_decode(blockIdx.x, a.sel.n_inst, a.sel.n_l * TILES, group, inst)) return;
-        const u32 l = group / TILES;
+        if (!xcd_decode(blockIdx.x, a.sel.n_inst, run.count * TILES, group, inst)) return;
+        const u32 l = run.first + group / TILES;
         tile = group % TILES;
         pi = a.sel.prime_base + l;
         const size_t off = limb_offset(a.sel, inst, l) * N;
         src = a.src + off;
         dst = a.dst + off;
     } else if (LOAD == FWD_CONV_UP) {
-        const u32 n_t = tb.D - tb.alpha;
-        if (!xcd_decode(blockIdx.x, n_t, a.groups_outer * tb.dnum * TILES, group, inst)) return;
+        if (!xcd_decode(blockIdx.x, run.count, a.groups_outer * tb.dnum * TILES, group, inst)) return;
         tile = group % TILES;
         const u32 bj = group / TILES, j = bj % tb.dnum, b = bj / tb.dnum;
-        pi = inst < j * tb.alpha ? inst : inst + tb.alpha;
+        pi = run.first + inst;
+        if (pi >= j * tb.alpha && pi < (j + 1) * tb.alpha) return;  // the digit's own limbs need no conversion
         src = a.src + ((size_t)b * tb.L + (size_t)j * tb.alpha) * N;
         dst = a.dst + (((size_t)b * tb.dnum + j) * tb.D + pi) * N;
         cv.chat = tb.up_chat + (size_t)j * tb.alpha * tb.D + pi;
@@ -281,19 +326,22 @@ __global__ __launch_bounds__(256) void fwd_strided_kernel(FwdStridedArgs a, Tabl
         cv.src_fp_fmt = 1;
         cv.fp_ok = tb.up_fp_ok[j * tb.D + pi];
     } else {
-        if (!xcd_decode(blockIdx.x, tb.L, a.groups_outer * TILES, group, inst)) return;
+        if (!xcd_decode(blockIdx.x, run.count, a.groups_outer * TILES, group, inst)) return;
         tile = group % TILES;
         const u32 g = group / TILES;
-        pi = inst;
+        pi = run.first + inst;
         src = a.src + (size_t)g * tb.K * N;
         dst = a.dst + ((size_t)g * tb.L + pi) * N;
         cv.chat = tb.dn_chat + pi;
+        cv.chat_fp = tb.dn_chat_fp + 2 * (size_t)pi;
+        cv.src_lo = a.src_lo + (size_t)g * tb.K * N;
         cv.chat_stride = tb.L;
         cv.ns = tb.K;
         cv.src_prime = tb.L;
+        cv.fp_ok = tb.dn_fp_ok[pi];
     }
-    if (tb.pc[pi].fp) fwd_strided_body<FpAr, A, LOAD>(a, tb, lds, pi, src, dst, cv, tile);
-    else fwd_strided_body<IntAr, A, LOAD>(a, tb, lds, pi, src, dst, cv, tile);
+    cv.rot = cv.ns ? pi % cv.ns : 0;
+    fwd_strided_body<AR, A, LOAD>(a, tb, lds, pi, src, dst, cv, tile);
 }
 
 // =========================================================== forward transform, second pass
@@ -317,23 +365,21 @@ __device__ __forceinline__ void fwd_contig_body(const FwdContigArgs& a, const Ta
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = AR::from_raw(p[k * 16 + e0]);
     NttCore<AR, A>::fwd_contig(x, lrow, e0, r, ti, tf, N, m);
-    __syncthreads();
+    row_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) lrow[pad16(e0 * 16 + k)] = AR::canon_fwd(x[k], m);
-    __syncthreads();
+    row_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) p[k * 16 + e0] = lrow[pad16(k * 16 + e0)];
 }
 
-template <int A>
-__global__ __launch_bounds__(256) void fwd_contig_kernel(FwdContigArgs a, Tables tb) {
+template <class AR, int A>
+__global__ __launch_bounds__(256) void fwd_contig_kernel(FwdContigArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[NTT_LDS_WORDS];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;
-    if (!xcd_decode(blockIdx.x, a.sel.n_inst, a.sel.n_l * TILES, group, inst)) return;
-    const u32 l = group / TILES, tile = group % TILES;
-    if (tb.pc[a.sel.prime_base + l].fp) fwd_contig_body<FpAr, A>(a, tb, lds, l, tile, inst);
-    else fwd_contig_body<IntAr, A>(a, tb, lds, l, tile, inst);
+    if (!xcd_decode(blockIdx.x, a.sel.n_inst, run.count * TILES, group, inst)) return;
+    fwd_contig_body<AR, A>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
 }
 
 // ==================================================================== key inner product
@@ -375,6 +421,14 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
 #pragma unroll
     for (int k = 0; k < 16; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
     for (u32 j = 0; j < tb.dnum; j++) {
+        // issue the key loads first so that they are in flight while the digit is transformed
+        const u64* k0 = key + ((size_t)j * 2 + 0) * D * N;
+        const u64* k1 = key + ((size_t)j * 2 + 1) * D * N;
+        u64 kv0[16], kv1[16];
+        if constexpr (AR::is_fp) {  // IntAr has no registers to spare: it loads the key at its use
+#pragma unroll
+            for (int k = 0; k < 16; k++) kv0[k] = k0[k * 16 + e0], kv1[k] = k1[k * 16 + e0];
+        }
         T v[16];
         if (j == own_digit) {
             if (HOISTED) {
@@ -390,8 +444,7 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
                 const size_t off = (((size_t)inst * 2 + 1) * L + i) * N + row_off;
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
-                    const u64 t = mulmod_var(a.own[off + k * 16 + e0], a.own2[off + k * 16 + e0], pc.q, pc.qneg, pc.r2);
-                    v[k] = AR::round_reduce(AR::from_canon(t, m), m);
+                    v[k] = AR::round_reduce(AR::mul_canon(a.own[off + k * 16 + e0], a.own2[off + k * 16 + e0], pc, m), m);
                 }
             } else {
                 const u64* p = a.own + (((size_t)inst * 2 + 1) * L + i) * N;
@@ -413,12 +466,11 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(v[k], m);
             exchange_cb_to_ca<AR>(v, lrow, e0);
         }
-        const u64* k0 = key + ((size_t)j * 2 + 0) * D * N;
-        const u64* k1 = key + ((size_t)j * 2 + 1) * D * N;
 #pragma unroll
         for (int k = 0; k < 16; k++) {
-            AR::acc_mac(acc0[k], v[k], k0[k * 16 + e0], m);
-            AR::acc_mac(acc1[k], v[k], k1[k * 16 + e0], m);
+            if constexpr (!AR::is_fp) kv0[k] = k0[k * 16 + e0], kv1[k] = k1[k * 16 + e0];
+            AR::acc_mac(acc0[k], v[k], kv0[k], m);
+            AR::acc_mac(acc1[k], v[k], kv1[k], m);
         }
     }
     if (i < L) {
@@ -444,15 +496,13 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
     }
 }
 
-template <int A, int OWN, bool HOISTED>
-__global__ __launch_bounds__(256) void ks_inner_kernel(InnerArgs a, Tables tb) {
+template <class AR, int A, int OWN, bool HOISTED>
+__global__ __launch_bounds__(256) void ks_inner_kernel(InnerArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[NTT_LDS_WORDS];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;
-    if (!xcd_decode(blockIdx.x, a.n_inst, tb.D * TILES, group, inst)) return;
-    const u32 i = group / TILES, tile = group % TILES;
-    if (tb.pc[i].fp) ks_inner_body<FpAr, A, OWN, HOISTED>(a, tb, lds, i, tile, inst);
-    else ks_inner_body<IntAr, A, OWN, HOISTED>(a, tb, lds, i, tile, inst);
+    if (!xcd_decode(blockIdx.x, a.n_inst, run.count * TILES, group, inst)) return;
+    ks_inner_body<AR, A, OWN, HOISTED>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
 }
 
 // ======================================================================== final combine
@@ -551,15 +601,13 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
     }
 }
 
-template <int A, int MODE>
-__global__ __launch_bounds__(256) void ks_final_kernel(FinalArgs a, Tables tb) {
+template <class AR, int A, int MODE>
+__global__ __launch_bounds__(256) void ks_final_kernel(FinalArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[NTT_LDS_WORDS];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;
-    if (!xcd_decode(blockIdx.x, a.n_inst, tb.L * TILES, group, inst)) return;
-    const u32 i = group / TILES, tile = group % TILES;
-    if (tb.pc[i].fp) ks_final_body<FpAr, A, MODE>(a, tb, lds, i, tile, inst);
-    else ks_final_body<IntAr, A, MODE>(a, tb, lds, i, tile, inst);
+    if (!xcd_decode(blockIdx.x, a.n_inst, run.count * TILES, group, inst)) return;
+    ks_final_body<AR, A, MODE>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
 }
 
 // ================================================== stand-alone coefficient-form base conversions

@@ -114,6 +114,8 @@ struct IntAr {
     static HD T from_raw(u64 v) { return v; }
     static HD u64 to_raw(T v) { return v; }
     static HD T from_f64_lazy(double, const Mod&) { return 0; }  // FP64 conversion path is FpAr-only
+    // product of two canonical residues, as a value the transforms accept
+    static HD T mul_canon(u64 a, u64 b, const PrimeConst& p, const Mod&) { return mulmod_var(a, b, p.q, p.qneg, p.r2); }
     // forward: values in [0, 4q)
     static HD void bfly_fwd(T& X, T& Y, const Tw& t, const Mod& m) {
         u64 x = X >= m.q2 ? X - m.q2 : X;
@@ -190,6 +192,9 @@ struct FpAr {
     static HD T from_raw(u64 v) { return __builtin_bit_cast(double, v); }
     static HD u64 to_raw(T v) { return __builtin_bit_cast(u64, v); }
     static HD T from_f64_lazy(double v, const Mod& m) { return reduce(v, m); }
+    static HD T mul_canon(u64 a, u64 b, const PrimeConst&, const Mod& m) {
+        return mulmod_lazy(u64_to_f64(a), u64_to_f64(b), m);  // |result| <= 0.875 q
+    }
     static HD void bfly_fwd(T& X, T& Y, const Tw& t, const Mod& m) {
         double r = mulmod_lazy(Y, t.w, m);
         double x = X;

@@ -25,6 +25,14 @@
 #define NTT_LDS_WORDS (16 * 272)  // 16 rows of 256 words + one pad word per 16
 __device__ __forceinline__ u32 pad16(u32 e) { return e + (e >> 4); }
 
+// In the contiguous pass the 16 lanes that own a row are part of one wavefront and no other
+// wavefront touches that row's LDS slice, so exchanges need no workgroup barrier: LDS operations
+// of one wavefront execute in issue order; the fence keeps the compiler from reordering them.
+__device__ __forceinline__ void row_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 template <class AR, int A>
 struct NttCore {
     typedef typename AR::T T;
@@ -76,7 +84,7 @@ struct NttCore {
         }
 #pragma unroll
         for (int k = 0; k < 16; k++) l[pad16(k * 16 + e0)] = AR::to_raw(AR::round_reduce(x[k], m));
-        __syncthreads();
+        row_sync();
 #pragma unroll
         for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(e0 * 16 + k)]);
 #pragma unroll
@@ -106,7 +114,7 @@ struct NttCore {
         }
 #pragma unroll
         for (int k = 0; k < 16; k++) l[pad16(e0 * 16 + k)] = AR::to_raw(AR::round_reduce(x[k], m));
-        __syncthreads();
+        row_sync();
 #pragma unroll
         for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(k * 16 + e0)]);
 #pragma unroll
@@ -157,19 +165,19 @@ struct NttCore {
 // exchange between the two contiguous-pass layouts through the row's LDS slice
 template <class AR>
 __device__ __forceinline__ void exchange_cb_to_ca(typename AR::T (&x)[16], u64* l, u32 e0) {
-    __syncthreads();
+    row_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) l[pad16(e0 * 16 + k)] = AR::to_raw(x[k]);
-    __syncthreads();
+    row_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(k * 16 + e0)]);
 }
 template <class AR>
 __device__ __forceinline__ void exchange_ca_to_cb(typename AR::T (&x)[16], u64* l, u32 e0) {
-    __syncthreads();
+    row_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) l[pad16(k * 16 + e0)] = AR::to_raw(x[k]);
-    __syncthreads();
+    row_sync();
 #pragma unroll
     for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(e0 * 16 + k)]);
 }
