@@ -185,14 +185,15 @@ int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, c
  * Measurement support (no part of the method): per-kernel timing with HIP events.
  * ckks_profile_enable(ctx, 1) clears the counters and makes every later kernel launch of this
  * context be bracketed by two HIP events recorded on the launch stream; (ctx, 0) stops that.
- * ckks_profile_read waits for the recorded events and returns, for kernel kind
- * 0 <= kind < CKKS_PROF_KINDS: the kernel's name (static string), the number of launches, their
- * summed duration in milliseconds and their summed algorithmic bytes (the words each launch
- * must read and write once, tables excluded).  Any output pointer may be NULL.
+ * ckks_profile_read waits for the recorded events and returns, for the index-th kernel
+ * instantiation seen since the counters were cleared: its name as a profiler prints it (owned by
+ * the context, valid until the next ckks_profile_enable), the number of launches, their summed
+ * duration in milliseconds and their summed algorithmic bytes (the words each launch must read
+ * and write once, tables excluded).  Returns CKKS_EINVAL once index is past the last entry.
+ * Any output pointer may be NULL.
  */
-#define CKKS_PROF_KINDS 9
 int ckks_profile_enable(ckks_ctx* ctx, int on);
-int ckks_profile_read(ckks_ctx* ctx, uint32_t kind, const char** name, uint64_t* launches, double* total_ms,
+int ckks_profile_read(ckks_ctx* ctx, uint32_t index, const char** name, uint64_t* launches, double* total_ms,
                       uint64_t* alg_bytes);
 
 #ifdef __cplusplus

@@ -25,7 +25,6 @@ EXPORTS = (
     "ckks_keyswitch", "ckks_hmult_relin", "ckks_hrot", "ckks_hrot_hoisted_mac",
     "ckks_profile_enable", "ckks_profile_read",
 )
-PROF_KINDS = 9
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
 _lib = None
@@ -143,11 +142,15 @@ class Context:
     def profile_read(self) -> dict:
         """{kernel name: (launches, total_ms, algorithmic_bytes)} since profile_enable(True)."""
         out = {}
-        for kind in range(PROF_KINDS):
+        index = 0
+        while True:
             name, n, ms, nbytes = ctypes.c_char_p(), _u64(), ctypes.c_double(), _u64()
-            self._check(load().ckks_profile_read(self.handle, kind, ctypes.byref(name), ctypes.byref(n),
-                                                 ctypes.byref(ms), ctypes.byref(nbytes)))
+            rc = load().ckks_profile_read(self.handle, index, ctypes.byref(name), ctypes.byref(n),
+                                          ctypes.byref(ms), ctypes.byref(nbytes))
+            if rc:
+                break
             out[name.value.decode()] = (n.value, ms.value, nbytes.value)
+            index += 1
         return out
 
     # -- entry points (same names as the C ABI, minus the prefix) ----------------------

@@ -21,7 +21,8 @@ HIPCC_FLAGS = [
 def build(verbose: bool = False) -> str:
     """Always compiles (the driver uses this as its build check)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB_PATH]
+    extra = os.environ.get("CKKS_EXTRA_HIPCC_FLAGS", "").split()
+    cmd = [hipcc] + HIPCC_FLAGS + extra + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB_PATH]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

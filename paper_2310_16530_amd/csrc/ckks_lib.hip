@@ -118,26 +118,29 @@ static TableLayout table_layout(u32 logN, u32 L, u32 K) {
 }
 
 // per-kernel timing: when enabled, every launch is bracketed by two HIP events recorded on the
-// launch stream; ckks_profile_read waits for them and sums elapsed time per kernel.
-enum ProfKind {
-    PK_INV_CONTIG = 0, PK_INV_STRIDED, PK_FWD_STRIDED, PK_FWD_CONTIG, PK_KS_INNER, PK_KS_FINAL, PK_MODUP, PK_MODDOWN,
-    PK_AUTOMORPH, PK_COUNT
-};
-static const char* const prof_names[PK_COUNT] = {
-    "inv_contig_kernel", "inv_strided_kernel", "fwd_strided_kernel", "fwd_contig_kernel", "ks_inner_kernel",
-    "ks_final_kernel", "modup_kernel", "moddown_kernel", "automorph_kernel"};
-static_assert(PK_COUNT == CKKS_PROF_KINDS, "header and library disagree on the number of kernel kinds");
-
+// launch stream; ckks_profile_read waits for them and sums elapsed time per kernel instantiation
+// (named as the profiler names it, e.g. "fwd_strided_kernel<FpAr, 8, 1>").
 struct ProfRec {
     int kind;
     hipEvent_t a, b;
+};
+struct ProfKindStat {
+    std::string name;
+    double ms = 0;
+    u64 launches = 0, bytes = 0;
 };
 struct ProfState {
     bool on = false;
     std::vector<ProfRec> pending;
     std::vector<hipEvent_t> pool;
-    double ms[PK_COUNT] = {0};
-    u64 launches[PK_COUNT] = {0}, bytes[PK_COUNT] = {0};
+    std::vector<ProfKindStat> kinds;
+    int kind_of(const std::string& name) {
+        for (size_t i = 0; i < kinds.size(); i++)
+            if (kinds[i].name == name) return (int)i;
+        kinds.emplace_back();
+        kinds.back().name = name;
+        return (int)kinds.size() - 1;
+    }
 };
 
 struct ckks_ctx {
@@ -164,12 +167,12 @@ struct ProfScope {
     hipStream_t s;
     ProfRec rec;
     // alg_limbs: limbs (N words each) the launch must read plus write once
-    ProfScope(const ckks_ctx* c, int kind, u64 alg_limbs, hipStream_t stream) : s(stream) {
+    ProfScope(const ckks_ctx* c, const std::string& name, u64 alg_limbs, hipStream_t stream) : s(stream) {
         if (!c->prof.on) return;
         p = &c->prof;
-        p->launches[kind]++;
-        p->bytes[kind] += (alg_limbs * sizeof(u64)) << c->logN;
-        rec.kind = kind;
+        rec.kind = p->kind_of(name);
+        p->kinds[rec.kind].launches++;
+        p->kinds[rec.kind].bytes += (alg_limbs * sizeof(u64)) << c->logN;
         rec.a = prof_event(*p);
         rec.b = prof_event(*p);
         if (!rec.a || !rec.b) {
@@ -188,7 +191,7 @@ struct ProfScope {
 static void prof_drain(ProfState& p) {
     for (ProfRec& r : p.pending) {
         float ms = 0.f;
-        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) p.ms[r.kind] += ms;
+        if (hipEventSynchronize(r.b) == hipSuccess && hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) p.kinds[r.kind].ms += ms;
         p.pool.push_back(r.a);
         p.pool.push_back(r.b);
     }
@@ -408,18 +411,20 @@ extern "C" int ckks_profile_enable(ckks_ctx* ctx, int on) {
     if (!ctx) return CKKS_EINVAL;
     prof_drain(ctx->prof);
     ctx->prof.on = on != 0;
-    for (int k = 0; k < PK_COUNT; k++) ctx->prof.ms[k] = 0, ctx->prof.launches[k] = 0, ctx->prof.bytes[k] = 0;
+    ctx->prof.kinds.clear();
     return CKKS_OK;
 }
 
-extern "C" int ckks_profile_read(ckks_ctx* ctx, uint32_t kind, const char** name, uint64_t* launches,
+extern "C" int ckks_profile_read(ckks_ctx* ctx, uint32_t index, const char** name, uint64_t* launches,
                                  double* total_ms, uint64_t* alg_bytes) {
-    if (!ctx || kind >= PK_COUNT) return CKKS_EINVAL;
+    if (!ctx) return CKKS_EINVAL;
     prof_drain(ctx->prof);
-    if (name) *name = prof_names[kind];
-    if (launches) *launches = ctx->prof.launches[kind];
-    if (total_ms) *total_ms = ctx->prof.ms[kind];
-    if (alg_bytes) *alg_bytes = ctx->prof.bytes[kind];
+    if (index >= ctx->prof.kinds.size()) return CKKS_EINVAL;
+    const ProfKindStat& k = ctx->prof.kinds[index];
+    if (name) *name = k.name.c_str();
+    if (launches) *launches = k.launches;
+    if (total_ms) *total_ms = k.ms;
+    if (alg_bytes) *alg_bytes = k.bytes;
     return CKKS_OK;
 }
 
@@ -458,7 +463,9 @@ static std::vector<ClassRun> class_runs(const ckks_ctx* c, u32 lo, u32 hi) {
     return r;
 }
 
-// A launcher type L provides  template <class AR, int A> static void go(grid, stream, args, tables, run).
+// A launcher type L provides
+//   template <class AR, int A> static void go(grid, stream, args, tables, run)   the launch
+//   static std::string name(const char* ar, int A)                               the profiler's kernel name
 template <class L, class ArgT>
 static void dispatch_kernel(const ckks_ctx* c, bool fp, dim3 grid, hipStream_t s, const ArgT& a, LimbRun run) {
 #define CKKS_CASE_A(AV)                                               \
@@ -476,15 +483,23 @@ static void dispatch_kernel(const ckks_ctx* c, bool fp, dim3 grid, hipStream_t s
 #undef CKKS_CASE_A
 }
 
+static std::string kname(const char* base, const char* ar, int A, const char* tail) {
+    return std::string(base) + "<" + ar + ", " + std::to_string(A) + tail + ">";
+}
+
 // One launch per arithmetic run of the primes [lo, hi).  limb_base converts a prime index into the
-// kernel's limb index.  by_limb: groups = run limbs x groups_n, instances = inst_n;
-// otherwise (conversion targets): groups = groups_n, instances = the run's limbs x inst_n.
-template <class L, class ArgT>
+// kernel's limb index.  by_limb: groups = run limbs x groups_n, instances = inst_n; otherwise
+// (conversion targets): groups = groups_n, instances = the run's limbs in blocks of inst_n.  alg(first, count) gives
+// the algorithmic limbs (read + written once) of the launch covering primes [first, first+count).
+template <class L, class ArgT, class AlgFn>
 static void launch_runs(const ckks_ctx* c, u32 lo, u32 hi, u32 limb_base, bool by_limb, u32 groups_n, u32 inst_n,
-                        const ArgT& a, hipStream_t s) {
+                        const ArgT& a, hipStream_t s, AlgFn alg) {
     for (const ClassRun& cr : class_runs(c, lo, hi)) {
         const LimbRun run = {cr.first - limb_base, cr.count};
-        const dim3 grid(by_limb ? xcd_grid(cr.count * groups_n, inst_n) : xcd_grid(groups_n, cr.count * inst_n));
+        const dim3 grid(by_limb ? xcd_grid(cr.count * groups_n, inst_n)
+                                : xcd_grid(groups_n, (cr.count + inst_n - 1) / inst_n));
+        ProfScope ps(c, c->prof.on ? L::name(cr.fp ? "FpAr" : "IntAr", (int)c->logN - 8) : std::string(),
+                     c->prof.on ? alg(cr.first, cr.count) : 0, s);
         dispatch_kernel<L>(c, cr.fp, grid, s, a, run);
     }
 }
@@ -495,18 +510,41 @@ struct InvContigL {
     static void go(dim3 g, hipStream_t s, const InvContigArgs& a, const Tables& tb, LimbRun run) {
         hipLaunchKernelGGL((inv_contig_kernel<AR, A, LOAD>), g, dim3(256), 0, s, a, tb, run);
     }
+    static std::string name(const char* ar, int A) {
+        return kname("inv_contig_kernel", ar, A, LOAD == 0 ? ", 0" : LOAD == 1 ? ", 1" : ", 2");
+    }
 };
 struct InvStridedL {
     template <class AR, int A>
     static void go(dim3 g, hipStream_t s, const InvStridedArgs& a, const Tables& tb, LimbRun run) {
         hipLaunchKernelGGL((inv_strided_kernel<AR, A>), g, dim3(256), 0, s, a, tb, run);
     }
+    static std::string name(const char* ar, int A) { return kname("inv_strided_kernel", ar, A, ""); }
 };
-template <int LOAD>
 struct FwdStridedL {
     template <class AR, int A>
     static void go(dim3 g, hipStream_t s, const FwdStridedArgs& a, const Tables& tb, LimbRun run) {
-        hipLaunchKernelGGL((fwd_strided_kernel<AR, A, LOAD>), g, dim3(256), 0, s, a, tb, run);
+        hipLaunchKernelGGL((fwd_strided_kernel<AR, A>), g, dim3(256), 0, s, a, tb, run);
+    }
+    static std::string name(const char* ar, int A) { return kname("fwd_strided_kernel", ar, A, ""); }
+};
+// target limbs converted per workgroup
+#ifndef CKKS_CONV_TB_UP
+#define CKKS_CONV_TB_UP 1
+#endif
+#ifndef CKKS_CONV_TB_DN
+#define CKKS_CONV_TB_DN 3
+#endif
+template <int DIR>
+struct ConvL {
+    static constexpr int TB = DIR == CONV_UP ? CKKS_CONV_TB_UP : CKKS_CONV_TB_DN;
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const ConvArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((conv_fwd_strided_kernel<AR, A, DIR, TB>), g, dim3(256), 0, s, a, tb, run);
+    }
+    static std::string name(const char* ar, int A) {
+        return kname("conv_fwd_strided_kernel", ar, A,
+                     (std::string(", ") + std::to_string(DIR) + ", " + std::to_string(TB)).c_str());
     }
 };
 struct FwdContigL {
@@ -514,12 +552,17 @@ struct FwdContigL {
     static void go(dim3 g, hipStream_t s, const FwdContigArgs& a, const Tables& tb, LimbRun run) {
         hipLaunchKernelGGL((fwd_contig_kernel<AR, A>), g, dim3(256), 0, s, a, tb, run);
     }
+    static std::string name(const char* ar, int A) { return kname("fwd_contig_kernel", ar, A, ""); }
 };
 template <int OWN, bool HOISTED>
 struct KsInnerL {
     template <class AR, int A>
     static void go(dim3 g, hipStream_t s, const InnerArgs& a, const Tables& tb, LimbRun run) {
         hipLaunchKernelGGL((ks_inner_kernel<AR, A, OWN, HOISTED>), g, dim3(256), 0, s, a, tb, run);
+    }
+    static std::string name(const char* ar, int A) {
+        return kname("ks_inner_kernel", ar, A,
+                     (std::string(", ") + std::to_string(OWN) + (HOISTED ? ", true" : ", false")).c_str());
     }
 };
 template <int MODE>
@@ -528,65 +571,85 @@ struct KsFinalL {
     static void go(dim3 g, hipStream_t s, const FinalArgs& a, const Tables& tb, LimbRun run) {
         hipLaunchKernelGGL((ks_final_kernel<AR, A, MODE>), g, dim3(256), 0, s, a, tb, run);
     }
+    static std::string name(const char* ar, int A) {
+        return kname("ks_final_kernel", ar, A, (std::string(", ") + std::to_string(MODE)).c_str());
+    }
 };
 
 template <int LOAD>
 static void launch_inv_contig(const ckks_ctx* c, const InvContigArgs& a, hipStream_t s) {
-    ProfScope ps(c, PK_INV_CONTIG, (u64)a.sel.n_l * a.sel.n_inst * (LOAD == INV_TENSOR ? 3 : 2), s);
     const u32 pb = a.sel.prime_base;
-    launch_runs<InvContigL<LOAD>>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s);
+    const u64 per = (u64)a.sel.n_inst * (LOAD == INV_TENSOR ? 3 : 2);
+    launch_runs<InvContigL<LOAD>>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s,
+                                  [per](u32, u32 n) { return per * n; });
 }
 
 static void launch_inv_strided(const ckks_ctx* c, const InvStridedArgs& a, hipStream_t s) {
-    ProfScope ps(c, PK_INV_STRIDED, (u64)a.sel.n_l * a.sel.n_inst * 2, s);
     const u32 pb = a.sel.prime_base;
-    launch_runs<InvStridedL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s);
+    const u64 per = (u64)a.sel.n_inst * 2;
+    launch_runs<InvStridedL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s,
+                             [per](u32, u32 n) { return per * n; });
 }
 
-template <int LOAD>
 static void launch_fwd_strided(const ckks_ctx* c, const FwdStridedArgs& a, hipStream_t s) {
-    if (LOAD == FWD_PLAIN) {
-        ProfScope ps(c, PK_FWD_STRIDED, (u64)a.sel.n_l * a.sel.n_inst * 2, s);
-        const u32 pb = a.sel.prime_base;
-        launch_runs<FwdStridedL<LOAD>>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s);
-    } else if (LOAD == FWD_CONV_UP) {  // groups = (batch, digit, tile); instances = the run's target primes
-        ProfScope ps(c, PK_FWD_STRIDED, (u64)a.groups_outer * (c->L + (u64)c->dnum * (c->D - c->alpha)), s);
-        launch_runs<FwdStridedL<LOAD>>(c, 0, c->D, 0, false, a.groups_outer * c->dnum * tiles_of(c), 1, a, s);
-    } else {  // groups = (g, tile); instances = the run's target q-limbs
-        ProfScope ps(c, PK_FWD_STRIDED, (u64)a.groups_outer * (c->K + c->L), s);
-        launch_runs<FwdStridedL<LOAD>>(c, 0, c->L, 0, false, a.groups_outer * tiles_of(c), 1, a, s);
+    const u32 pb = a.sel.prime_base;
+    const u64 per = (u64)a.sel.n_inst * 2;
+    launch_runs<FwdStridedL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s,
+                             [per](u32, u32 n) { return per * n; });
+}
+
+template <int DIR>
+static void launch_conv(const ckks_ctx* c, const ConvArgs& a, hipStream_t s) {
+    const u64 outer = a.groups_outer;
+    if (DIR == CONV_UP) {  // groups = (batch, digit, tile); instances = blocks of the run's target primes
+        launch_runs<ConvL<DIR>>(c, 0, c->D, 0, false, a.groups_outer * c->dnum * tiles_of(c), ConvL<DIR>::TB, a, s,
+                                [c, outer](u32 first, u32 n) {
+                                    u64 w = 0;  // every target limb is written for each digit that does not own it
+                                    for (u32 t = first; t < first + n; t++) w += c->dnum - (t < c->L ? 1 : 0);
+                                    return outer * (w + c->L);  // plus the source coefficients, read once
+                                });
+    } else {  // groups = (g, tile); instances = blocks of the run's target q-limbs
+        launch_runs<ConvL<DIR>>(c, 0, c->L, 0, false, a.groups_outer * tiles_of(c), ConvL<DIR>::TB, a, s,
+                                [c, outer](u32, u32 n) { return outer * (n + (u64)c->K); });
     }
 }
 
 static void launch_fwd_contig(const ckks_ctx* c, const FwdContigArgs& a, hipStream_t s) {
-    ProfScope ps(c, PK_FWD_CONTIG, (u64)a.sel.n_l * a.sel.n_inst * 2, s);
     const u32 pb = a.sel.prime_base;
-    launch_runs<FwdContigL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s);
+    const u64 per = (u64)a.sel.n_inst * 2;
+    launch_runs<FwdContigL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s,
+                            [per](u32, u32 n) { return per * n; });
 }
 
 template <int OWN, bool HOISTED>
 static void launch_ks_inner(const ckks_ctx* c, const InnerArgs& a, hipStream_t s) {
-    const u64 per_inst = (u64)c->dnum * c->D - c->L              // extended digits outside their own limbs
-                         + (u64)c->L * (OWN == OWN_TENSOR ? 2 : 1)  // the switched polynomial on its own limbs
-                         + 2 * (u64)c->D;                         // c' written
-    const u64 key = (u64)c->dnum * 2 * c->D;
-    ProfScope ps(c, PK_KS_INNER, a.n_inst * per_inst + (HOISTED ? a.n_inst : 1) * key, s);
-    launch_runs<KsInnerL<OWN, HOISTED>>(c, 0, c->D, 0, true, tiles_of(c), a.n_inst, a, s);
+    const u64 n_inst = a.n_inst;
+    launch_runs<KsInnerL<OWN, HOISTED>>(
+        c, 0, c->D, 0, true, tiles_of(c), a.n_inst, a, s, [c, n_inst](u32 first, u32 n) {
+            u64 limbs = 0;
+            for (u32 i = first; i < first + n; i++) {
+                const bool q = i < c->L;
+                limbs += n_inst * ((u64)c->dnum - (q ? 1 : 0)            // extended digits outside their own limbs
+                                   + (q ? (OWN == OWN_TENSOR ? 2 : 1) : 0)  // the switched polynomial on its own limb
+                                   + 2)                                    // c' written
+                         + (HOISTED ? n_inst : 1) * 2 * (u64)c->dnum;      // key limbs
+            }
+            return limbs;
+        });
 }
 
 template <int MODE>
 static void launch_ks_final(const ckks_ctx* c, const FinalArgs& a, hipStream_t s) {
-    u64 limbs;
-    if (MODE == FIN_HOISTED) limbs = (u64)a.n_rot * c->L * (2 + 2 + 1 + 1) + (u64)c->L * (2 + (a.accumulate ? 2 : 0));
-    else limbs = (u64)a.n_inst * c->L * (6 + (MODE == FIN_HMULT ? 4 : MODE == FIN_HROT ? 1 : 0));
-    ProfScope ps(c, PK_KS_FINAL, limbs, s);
-    launch_runs<KsFinalL<MODE>>(c, 0, c->L, 0, true, tiles_of(c), a.n_inst, a, s);
+    u64 per;  // algorithmic limbs per q-limb
+    if (MODE == FIN_HOISTED) per = (u64)a.n_rot * (2 + 2 + 1 + 1) + (2 + (a.accumulate ? 2 : 0));
+    else per = (u64)a.n_inst * (6 + (MODE == FIN_HMULT ? 4 : MODE == FIN_HROT ? 1 : 0));
+    launch_runs<KsFinalL<MODE>>(c, 0, c->L, 0, true, tiles_of(c), a.n_inst, a, s, [per](u32, u32 n) { return per * n; });
 }
 
 template <int AL>
 static void launch_modup_a(const ckks_ctx* c, const u64* in, u64* out, u32 batch, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, c->dnum, batch), block(256);
-    ProfScope ps(c, PK_MODUP, (u64)batch * (2 * (u64)c->L + (u64)c->dnum * (c->D - c->alpha)), s);
+    ProfScope ps(c, std::string("modup_kernel"), (u64)batch * (2 * (u64)c->L + (u64)c->dnum * (c->D - c->alpha)), s);
     hipLaunchKernelGGL(modup_kernel<AL>, grid, block, 0, s, in, out, c->tb);
 }
 static void launch_modup(const ckks_ctx* c, const u64* in, u64* out, u32 batch, hipStream_t s) {
@@ -605,7 +668,7 @@ static void launch_modup(const ckks_ctx* c, const u64* in, u64* out, u32 batch, 
 template <int KK>
 static void launch_moddown_k(const ckks_ctx* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, groups), block(256);
-    ProfScope ps(c, PK_MODDOWN, (u64)groups * (c->K + 2 * (u64)c->L), s);
+    ProfScope ps(c, std::string("moddown_kernel"), (u64)groups * (c->K + 2 * (u64)c->L), s);
     hipLaunchKernelGGL(moddown_kernel<KK>, grid, block, 0, s, in, out, c->tb);
 }
 static void launch_moddown(const ckks_ctx* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
@@ -626,16 +689,14 @@ static void launch_moddown(const ckks_ctx* c, const u64* in, u64* out, u32 group
 // dt [dg][dnum][D][N]  extended digits (first forward pass done; own-digit limbs unused)
 // cq [cg][2][L][N]     c' on the q-limbs, canonical evaluation form
 // cp [cg][2][K][N]     c' on the special limbs: raw after the first inverse pass, then coefficients * pre-factor
-//                      (split: high 30-bit halves here, low halves in cl, both as doubles)
-// cl [cg][2][K][N]     low halves of the special-limb coefficients
 // cv [cg][2][L][N]     Conv_{P->Q} of the special part, first forward pass done
 struct Workspace {
-    u64 *x, *dt, *cq, *cp, *cl, *cv;
+    u64 *x, *dt, *cq, *cp, *cv;
 };
 
 static size_t ks_workspace_words(const ckks_ctx* c, u32 xg, u32 dg, u32 cg) {
     const size_t N = (size_t)1 << c->logN;
-    return ((size_t)xg * c->L + (size_t)dg * c->dnum * c->D + (size_t)cg * 2 * (2 * (size_t)c->L + 2 * (size_t)c->K)) * N;
+    return ((size_t)xg * c->L + (size_t)dg * c->dnum * c->D + (size_t)cg * 2 * (2 * (size_t)c->L + c->K)) * N;
 }
 
 static Workspace carve(const ckks_ctx* c, void* ws, u32 xg, u32 dg, u32 cg) {
@@ -645,8 +706,7 @@ static Workspace carve(const ckks_ctx* c, void* ws, u32 xg, u32 dg, u32 cg) {
     w.dt = w.x + (size_t)xg * c->L * N;
     w.cq = w.dt + (size_t)dg * c->dnum * c->D * N;
     w.cp = w.cq + (size_t)cg * 2 * c->L * N;
-    w.cl = w.cp + (size_t)cg * 2 * c->K * N;
-    w.cv = w.cl + (size_t)cg * 2 * c->K * N;
+    w.cv = w.cp + (size_t)cg * 2 * c->K * N;
     return w;
 }
 
@@ -691,14 +751,14 @@ static int ntt_entry(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uint32_
     hipStream_t s = (hipStream_t)stream;
     const LimbSel sel = {n_limbs, batch, n_limbs, 0, prime_first, 0};
     if (!inverse) {
-        FwdStridedArgs a1 = {d_x, nullptr, d_x, sel, 0};
-        launch_fwd_strided<FWD_PLAIN>(ctx, a1, s);
+        FwdStridedArgs a1 = {d_x, d_x, sel};
+        launch_fwd_strided(ctx, a1, s);
         FwdContigArgs a2 = {d_x, sel};
         launch_fwd_contig(ctx, a2, s);
     } else {
         InvContigArgs a1 = {d_x, nullptr, d_x, sel, sel, 1};
         launch_inv_contig<INV_PLAIN>(ctx, a1, s);
-        InvStridedArgs a2 = {d_x, sel, SC_PLAIN, 0, nullptr};
+        InvStridedArgs a2 = {d_x, sel, SC_PLAIN, 0};
         launch_inv_strided(ctx, a2, s);
     }
     return hip_check(ctx, inverse ? "ckks_intt" : "ckks_ntt");
@@ -758,7 +818,7 @@ extern "C" int ckks_automorph(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_o
     if (batch > 65535) return fail(ctx, CKKS_EINVAL, "batch too large");
     const dim3 grid((1u << ctx->logN) / 256, n_limbs, batch), block(256);
     hipStream_t s = (hipStream_t)stream;
-    ProfScope ps(ctx, PK_AUTOMORPH, (u64)batch * n_limbs * 2, s);
+    ProfScope ps(ctx, std::string(eval_domain ? "automorph_eval_kernel" : "automorph_coeff_kernel"), (u64)batch * n_limbs * 2, s);
     if (eval_domain) {
         hipLaunchKernelGGL(automorph_eval_kernel, grid, block, 0, s, d_in, d_out, ctx->logN, n_limbs, galois);
     } else {
@@ -791,19 +851,19 @@ static int check_ks_args(const ckks_ctx* c, const void* a, const void* b, const 
 // first forward pass of every extended limb.
 static void decompose_extend(const ckks_ctx* c, const Workspace& w, u32 groups, hipStream_t s) {
     const LimbSel sel = {c->L, groups, c->L, 0, 0, 0};
-    InvStridedArgs a2 = {w.x, sel, SC_UP, 1, nullptr};
+    InvStridedArgs a2 = {w.x, sel, SC_UP, 1};
     launch_inv_strided(c, a2, s);
-    FwdStridedArgs a3 = {w.x, nullptr, w.dt, sel, groups};
-    launch_fwd_strided<FWD_CONV_UP>(c, a3, s);
+    ConvArgs a3 = {w.x, w.dt, groups};
+    launch_conv<CONV_UP>(c, a3, s);
 }
 
 // ModDown side: w.cp holds the first inverse pass of c' on the special limbs.
 static void moddown_convert(const ckks_ctx* c, const Workspace& w, u32 cg, hipStream_t s) {
     const LimbSel sel = {c->K, cg * 2, c->K, 0, c->L, 0};
-    InvStridedArgs a6 = {w.cp, sel, SC_DN, 0, w.cl};
+    InvStridedArgs a6 = {w.cp, sel, SC_DN, 0};
     launch_inv_strided(c, a6, s);
-    FwdStridedArgs a7 = {w.cp, w.cl, w.cv, sel, cg * 2};
-    launch_fwd_strided<FWD_CONV_DN>(c, a7, s);
+    ConvArgs a7 = {w.cp, w.cv, cg * 2};
+    launch_conv<CONV_DN>(c, a7, s);
 }
 
 template <int LOAD, int OWN, int FIN>

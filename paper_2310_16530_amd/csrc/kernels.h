@@ -127,8 +127,6 @@ struct InvStridedArgs {
     LimbSel sel;
     u32 scale;   // InvScaleSel
     u32 fp_out;  // 1: limbs of FpAr primes are stored as doubles (same canonical integer values)
-    u64* lo_out; // not NULL: every value y is stored split, double(y >> 30) in place and
-                 //           double(y mod 2^30) at the same offset of lo_out
 };
 
 template <class AR, int A>
@@ -157,17 +155,8 @@ __device__ __forceinline__ void inv_strided_body(const InvStridedArgs& a, const 
     for (int k = 0; k < 8; k++) {
         u64 ox, oy;
         AR::bfly_inv_last(x[k], x[k + 8], sc, m, a.fp_out != 0, ox, oy);
-        const size_t ix = (size_t)(k * C::RB + r0) * 256 + col, iy = (size_t)((k + 8) * C::RB + r0) * 256 + col;
-        if (a.lo_out) {
-            u64* lo = a.lo_out + limb_offset(a.sel, inst, l) * N;
-            base[ix] = FpAr::to_raw((double)(u32)(ox >> 30));
-            lo[ix] = FpAr::to_raw((double)(u32)(ox & 0x3fffffffu));
-            base[iy] = FpAr::to_raw((double)(u32)(oy >> 30));
-            lo[iy] = FpAr::to_raw((double)(u32)(oy & 0x3fffffffu));
-        } else {
-            base[ix] = ox;
-            base[iy] = oy;
-        }
+        base[(size_t)(k * C::RB + r0) * 256 + col] = ox;
+        base[(size_t)((k + 8) * C::RB + r0) * 256 + col] = oy;
     }
 }
 
@@ -181,105 +170,22 @@ __global__ __launch_bounds__(256) void inv_strided_kernel(InvStridedArgs a, Tabl
 }
 
 // ============================================================ forward transform, first pass
-// FWD_PLAIN  : canonical coefficients addressed by sel (in place when dst == src).
-// FWD_CONV_UP: group = (b, digit j, tile), instance = target slot s of the D - alpha limbs outside the
-//              digit; sources y [b][L][N] (coefficients already times [(Q_j/q_i)^-1]); dst dt [b][dnum][D][N].
-// FWD_CONV_DN: group = (g, tile), instance = target q-limb i; sources y = special limbs [g][K][N];
-//              dst cv [g][L][N].
-enum FwdLoad { FWD_PLAIN = 0, FWD_CONV_UP = 1, FWD_CONV_DN = 2 };
 struct FwdStridedArgs {
-    const u64* src;
-    const u64* src_lo;  // CONV_DN: the low 30-bit halves (src holds the high halves), both as doubles
-    u64* dst;           // raw forward-lazy words
+    const u64* src;  // canonical coefficients addressed by sel
+    u64* dst;        // raw forward-lazy words, same addressing (in place when dst == src)
     LimbSel sel;
-    u32 groups_outer;  // CONV_UP: batch; CONV_DN: number of g
 };
 
-// base-conversion operands of one target limb (workgroup-uniform)
-struct ConvSel {
-    const u64* chat;        // Montgomery-form constants, stride chat_stride per source
-    const double* chat_fp;  // the same constants as plain doubles (CONV_DN: pairs c, c * 2^30)
-    const u64* src_lo;      // CONV_DN: low halves of the sources
-    u32 chat_stride, ns;    // number of source limbs
-    u32 src_prime;          // prime index of source 0
-    u32 src_fp_fmt;         // sources of FpAr primes are stored as doubles
-    u32 fp_ok;              // the FP64 conversion path is valid for this target
-    u32 rot;                // first source visited: targets that share sources walk them in different orders
-};
-
-template <class AR, int A, int LOAD>
-__device__ __forceinline__ void fwd_strided_body(const FwdStridedArgs& a, const Tables& tb, u64* lds, u32 pi,
-                                                 const u64* src, u64* dst, const ConvSel& cv, u32 tile) {
-    typedef typename AR::T T;
+// stages + store shared by the plain and the conversion-fused first pass; x in layout SA
+template <class AR, int A>
+__device__ __forceinline__ void fwd_strided_finish(typename AR::T (&x)[16], const Tables& tb, u64* lds, u32 pi,
+                                                   u64* dst, u32 tile) {
     typedef NttCore<AR, A> C;
     const u32 N = 1u << tb.logN, tid = threadIdx.x;
-    const PrimeConst pc = tb.pc[pi];
-    const typename AR::Mod m = AR::mod(pc);
+    const typename AR::Mod m = AR::mod(tb.pc[pi]);
     const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
     const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
     const u32 c = tid % C::TC, r0 = tid / C::TC, col = tile * C::TC + c;
-    T x[16];
-    if (LOAD == FWD_PLAIN) {
-#pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = AR::from_canon(src[(size_t)(k * C::RB + r0) * 256 + col], m);
-    } else if (LOAD == FWD_CONV_UP && AR::is_fp && cv.fp_ok) {
-        // sources are doubles holding canonical residues; accumulate lazily reduced products
-        double acc[16];
-#pragma unroll
-        for (int k = 0; k < 16; k++) acc[k] = 0.0;
-        for (u32 i0 = 0; i0 < cv.ns; i0++) {
-            const u32 i = i0 + cv.rot < cv.ns ? i0 + cv.rot : i0 + cv.rot - cv.ns;
-            const double cf = cv.chat_fp[(size_t)i * cv.chat_stride];
-            const u64* si = src + (size_t)i * N;
-#pragma unroll
-            for (int k = 0; k < 16; k++)
-                acc[k] += FpAr::mulmod_lazy(FpAr::from_raw(si[(size_t)(k * C::RB + r0) * 256 + col]), cf, FpAr::mod(pc));
-        }
-#pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = AR::from_f64_lazy(acc[k], m);
-    } else if (LOAD == FWD_CONV_DN && AR::is_fp && cv.fp_ok) {
-        // sources are split y = yh * 2^30 + yl (two doubles): y * c = yh * (c * 2^30) + yl * c  (mod q)
-        double acc[16];
-#pragma unroll
-        for (int k = 0; k < 16; k++) acc[k] = 0.0;
-        for (u32 i0 = 0; i0 < cv.ns; i0++) {
-            const u32 i = i0 + cv.rot < cv.ns ? i0 + cv.rot : i0 + cv.rot - cv.ns;
-            const double cl = cv.chat_fp[(size_t)i * cv.chat_stride * 2], ch = cv.chat_fp[(size_t)i * cv.chat_stride * 2 + 1];
-            const u64* sh = src + (size_t)i * N;
-            const u64* sl = cv.src_lo + (size_t)i * N;
-#pragma unroll
-            for (int k = 0; k < 16; k++) {
-                const size_t off = (size_t)(k * C::RB + r0) * 256 + col;
-                acc[k] += FpAr::mulmod_lazy(FpAr::from_raw(sh[off]), ch, FpAr::mod(pc)) +
-                          FpAr::mulmod_lazy(FpAr::from_raw(sl[off]), cl, FpAr::mod(pc));
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = AR::from_f64_lazy(acc[k], m);
-    } else {
-        u128w acc[16];
-#pragma unroll
-        for (int k = 0; k < 16; k++) acc[k] = u128w{0, 0};
-        for (u32 i0 = 0; i0 < cv.ns; i0++) {
-            const u32 i = i0 + cv.rot < cv.ns ? i0 + cv.rot : i0 + cv.rot - cv.ns;
-            const u64 cc = cv.chat[(size_t)i * cv.chat_stride];
-            const u64* si = src + (size_t)i * N;
-            const bool src_fp = cv.src_fp_fmt && tb.pc[cv.src_prime + i].fp;
-#pragma unroll
-            for (int k = 0; k < 16; k++) {
-                const size_t off = (size_t)(k * C::RB + r0) * 256 + col;
-                u64 y = si[off];
-                if (LOAD == FWD_CONV_DN) {
-                    y = ((u64)(u32)FpAr::from_raw(y) << 30) | (u32)FpAr::from_raw(cv.src_lo[(size_t)i * N + off]);
-                } else if (src_fp) {
-                    y = f64_to_u64(FpAr::from_raw(y));
-                }
-                mac128(acc[k], y, cc);
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = AR::from_canon(redc(acc[k], pc.q, pc.qneg), m);
-    }
     C::fwd_strided(x, lds, tid, ti, tf, N, m);
     if constexpr (A > 4) {
 #pragma unroll
@@ -291,57 +197,199 @@ __device__ __forceinline__ void fwd_strided_body(const FwdStridedArgs& a, const 
     }
 }
 
-// run: FWD_PLAIN limbs of sel; FWD_CONV_UP / FWD_CONV_DN target primes (targets inside the source digit
-// are skipped).
-template <class AR, int A, int LOAD>
+template <class AR, int A>
 __global__ __launch_bounds__(256) void fwd_strided_kernel(FwdStridedArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[4096];
+    typedef NttCore<AR, A> C;
     constexpr u32 TILES = (1u << A) / 16;
-    const u32 N = 1u << tb.logN;
-    u32 group, inst, pi, tile;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x;
+    u32 group, inst;
+    if (!xcd_decode(blockIdx.x, a.sel.n_inst, run.count * TILES, group, inst)) return;
+    const u32 l = run.first + group / TILES, tile = group % TILES, pi = a.sel.prime_base + l;
+    const size_t off = limb_offset(a.sel, inst, l) * N;
+    const typename AR::Mod m = AR::mod(tb.pc[pi]);
+    const u32 c = tid % C::TC, r0 = tid / C::TC, col = tile * C::TC + c;
+    typename AR::T x[16];
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = AR::from_canon(a.src[off + (size_t)(k * C::RB + r0) * 256 + col], m);
+    fwd_strided_finish<AR, A>(x, tb, lds, pi, a.dst + off, tile);
+}
+
+// ============================== base conversion fused into the first forward pass of its targets
+// CONV_UP: group = (b, digit j, tile); sources y [b][L][N] = coefficients times [(Q_j/q_i)^-1], limbs of
+//          FpAr primes stored as doubles; targets = the primes outside digit j; dst dt [b][dnum][D][N].
+// CONV_DN: group = (g, tile); sources y = special limbs [g][K][N] (canonical words); targets = q-limbs;
+//          dst cv [g][L][N].
+// A workgroup converts TB consecutive target primes of the run from one load of the sources (the
+// sources come from L2, whose bandwidth is what bounds a one-target-per-workgroup version), then
+// runs the first forward pass of each target in turn.
+enum ConvDir { CONV_UP = 1, CONV_DN = 2 };
+struct ConvArgs {
     const u64* src;
     u64* dst;
-    ConvSel cv = {nullptr, nullptr, nullptr, 0, 0, 0, 0, 0, 0};
-    if (LOAD == FWD_PLAIN) {
-        if (!xcd_decode(blockIdx.x, a.sel.n_inst, run.count * TILES, group, inst)) return;
-        const u32 l = run.first + group / TILES;
-        tile = group % TILES;
-        pi = a.sel.prime_base + l;
-        const size_t off = limb_offset(a.sel, inst, l) * N;
-        src = a.src + off;
-        dst = a.dst + off;
-    } else if (LOAD == FWD_CONV_UP) {
-        if (!xcd_decode(blockIdx.x, run.count, a.groups_outer * tb.dnum * TILES, group, inst)) return;
+    u32 groups_outer;  // CONV_UP: batch; CONV_DN: number of g
+};
+
+template <class AR, int A, int DIR, int TB>
+__global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kernel(ConvArgs a, Tables tb, LimbRun run) {
+    __shared__ u64 lds[4096];
+    typedef NttCore<AR, A> C;
+    typedef typename AR::T T;
+    constexpr u32 TILES = (1u << A) / 16;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x;
+    const u32 n_inst = (run.count + TB - 1) / TB;
+    u32 group, inst, tile, ns, src_prime, chat_stride;
+    const u64* src;
+    u64* dst0;  // limb 0 of the destination group
+    const u64* chat;
+    const double* chat_fp;
+    const u32* fp_ok;
+    u32 own_lo = 0xffffffffu, own_hi = 0xffffffffu;  // target primes in [own_lo, own_hi) are skipped
+    if (DIR == CONV_UP) {
+        if (!xcd_decode(blockIdx.x, n_inst, a.groups_outer * tb.dnum * TILES, group, inst)) return;
         tile = group % TILES;
         const u32 bj = group / TILES, j = bj % tb.dnum, b = bj / tb.dnum;
-        pi = run.first + inst;
-        if (pi >= j * tb.alpha && pi < (j + 1) * tb.alpha) return;  // the digit's own limbs need no conversion
         src = a.src + ((size_t)b * tb.L + (size_t)j * tb.alpha) * N;
-        dst = a.dst + (((size_t)b * tb.dnum + j) * tb.D + pi) * N;
-        cv.chat = tb.up_chat + (size_t)j * tb.alpha * tb.D + pi;
-        cv.chat_fp = tb.up_chat_fp + (size_t)j * tb.alpha * tb.D + pi;
-        cv.chat_stride = tb.D;
-        cv.ns = tb.alpha;
-        cv.src_prime = j * tb.alpha;
-        cv.src_fp_fmt = 1;
-        cv.fp_ok = tb.up_fp_ok[j * tb.D + pi];
+        dst0 = a.dst + ((size_t)b * tb.dnum + j) * tb.D * N;
+        chat = tb.up_chat + (size_t)j * tb.alpha * tb.D;
+        chat_fp = tb.up_chat_fp + (size_t)j * tb.alpha * tb.D;
+        fp_ok = tb.up_fp_ok + (size_t)j * tb.D;
+        chat_stride = tb.D, ns = tb.alpha, src_prime = j * tb.alpha;
+        own_lo = j * tb.alpha, own_hi = (j + 1) * tb.alpha;
     } else {
-        if (!xcd_decode(blockIdx.x, run.count, a.groups_outer * TILES, group, inst)) return;
+        if (!xcd_decode(blockIdx.x, n_inst, a.groups_outer * TILES, group, inst)) return;
         tile = group % TILES;
         const u32 g = group / TILES;
-        pi = run.first + inst;
         src = a.src + (size_t)g * tb.K * N;
-        dst = a.dst + ((size_t)g * tb.L + pi) * N;
-        cv.chat = tb.dn_chat + pi;
-        cv.chat_fp = tb.dn_chat_fp + 2 * (size_t)pi;
-        cv.src_lo = a.src_lo + (size_t)g * tb.K * N;
-        cv.chat_stride = tb.L;
-        cv.ns = tb.K;
-        cv.src_prime = tb.L;
-        cv.fp_ok = tb.dn_fp_ok[pi];
+        dst0 = a.dst + (size_t)g * tb.L * N;
+        chat = tb.dn_chat;
+        chat_fp = tb.dn_chat_fp;
+        fp_ok = tb.dn_fp_ok;
+        chat_stride = tb.L, ns = tb.K, src_prime = tb.L;
     }
-    cv.rot = cv.ns ? pi % cv.ns : 0;
-    fwd_strided_body<AR, A, LOAD>(a, tb, lds, pi, src, dst, cv, tile);
+    u32 pi[TB];
+    bool valid[TB], any = false, all_fp = AR::is_fp;
+#pragma unroll
+    for (int t = 0; t < TB; t++) {
+        pi[t] = run.first + inst * TB + t;
+        valid[t] = pi[t] < run.first + run.count && !(pi[t] >= own_lo && pi[t] < own_hi);
+        if (!valid[t]) pi[t] = run.first;  // any prime of the run: its result is dropped
+        any = any || valid[t];
+        all_fp = all_fp && (!valid[t] || fp_ok[pi[t]]);
+    }
+    if (!any) return;
+    const u32 c = tid % C::TC, r0 = tid / C::TC, col = tile * C::TC + c;
+    const u32 rot = ns ? (inst + tile) % ns : 0;  // workgroups sharing sources walk them in different orders
+    T x[TB][16];
+    if (all_fp) {
+        // FP64 pipe: every product reduced lazily (|.| <= 1.25 q), at most 16 of them accumulated
+        double acc[TB][16];
+        FpAr::Mod fm[TB];
+#pragma unroll
+        for (int t = 0; t < TB; t++) {
+            fm[t] = FpAr::mod(tb.pc[pi[t]]);
+#pragma unroll
+            for (int k = 0; k < 16; k++) acc[t][k] = 0.0;
+        }
+#pragma unroll 1
+        for (u32 i0 = 0; i0 < ns; i0++) {
+            const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
+            const u64* si = src + (size_t)i * N;
+            if (DIR == CONV_UP) {  // sources are doubles holding canonical residues of ~the targets' size
+                double cf[TB];
+#pragma unroll
+                for (int t = 0; t < TB; t++) cf[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    const double y = FpAr::from_raw(si[(size_t)(k * C::RB + r0) * 256 + col]);
+#pragma unroll
+                    for (int t = 0; t < TB; t++) acc[t][k] += FpAr::mulmod_lazy(y, cf[t], fm[t]);
+                }
+            } else {  // sources are words below 2^61: y = yh * 2^30 + yl, y*c = yh * (c * 2^30) + yl * c (mod q)
+                double cl[TB], ch[TB];
+#pragma unroll
+                for (int t = 0; t < TB; t++) {
+                    cl[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2];
+                    ch[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2 + 1];
+                }
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    const u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
+                    const double yh = (double)(u32)(y >> 30), yl = (double)(u32)(y & 0x3fffffffu);
+#pragma unroll
+                    for (int t = 0; t < TB; t++)
+                        acc[t][k] += FpAr::mulmod_lazy(yh, ch[t], fm[t]) + FpAr::mulmod_lazy(yl, cl[t], fm[t]);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < TB; t++) {
+            const typename AR::Mod m = AR::mod(tb.pc[pi[t]]);
+#pragma unroll
+            for (int k = 0; k < 16; k++) x[t][k] = AR::from_f64_lazy(acc[t][k], m);
+        }
+    } else if (!AR::is_fp) {
+        // integer pipe: 128-bit accumulation against Montgomery-form constants, one reduction per target
+        u128w acc[TB][16];
+#pragma unroll
+        for (int t = 0; t < TB; t++)
+#pragma unroll
+            for (int k = 0; k < 16; k++) acc[t][k] = u128w{0, 0};
+        for (u32 i0 = 0; i0 < ns; i0++) {
+            const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
+            const u64* si = src + (size_t)i * N;
+            const bool src_fp = DIR == CONV_UP && tb.pc[src_prime + i].fp;
+            u64 cc[TB];
+#pragma unroll
+            for (int t = 0; t < TB; t++) cc[t] = chat[(size_t)i * chat_stride + pi[t]];
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
+                if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+#pragma unroll
+                for (int t = 0; t < TB; t++) mac128(acc[t][k], y, cc[t]);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < TB; t++) {
+            const PrimeConst pc = tb.pc[pi[t]];
+            const typename AR::Mod m = AR::mod(pc);
+#pragma unroll
+            for (int k = 0; k < 16; k++) x[t][k] = AR::from_canon(redc(acc[t][k], pc.q, pc.qneg), m);
+        }
+    } else {
+        // FpAr targets whose sources do not fit the FP64 bounds: integer conversion, one target at a time
+        for (int t = 0; t < TB; t++) {
+            const PrimeConst pc = tb.pc[pi[t]];
+            const typename AR::Mod m = AR::mod(pc);
+            u128w acc[16];
+#pragma unroll
+            for (int k = 0; k < 16; k++) acc[k] = u128w{0, 0};
+            for (u32 i = 0; i < ns; i++) {
+                const u64* si = src + (size_t)i * N;
+                const bool src_fp = DIR == CONV_UP && tb.pc[src_prime + i].fp;
+                const u64 cc = chat[(size_t)i * chat_stride + pi[t]];
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
+                    if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+                    mac128(acc[k], y, cc);
+                }
+            }
+#pragma unroll
+            for (int tt = 0; tt < TB; tt++)
+                if (tt == t) {
+#pragma unroll
+                    for (int k = 0; k < 16; k++) x[tt][k] = AR::from_canon(redc(acc[k], pc.q, pc.qneg), m);
+                }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TB; t++) {
+        if (t) __syncthreads();  // the previous target's exchange must have been read
+        if (valid[t]) fwd_strided_finish<AR, A>(x[t], tb, lds, pi[t], dst0 + (size_t)pi[t] * N, tile);
+        else if (A > 4) __syncthreads();  // keep barrier counts equal (fwd_strided holds one barrier)
+    }
 }
 
 // =========================================================== forward transform, second pass

@@ -393,6 +393,9 @@ def test_repeat_runs_are_bit_identical_and_profile_counts_launches(orc):
         assert np.array_equal(host(ctx.hrot(ct, g, rk)), first)
     prof = ctx.profile_read()
     ctx.profile_enable(False)
-    assert prof["ks_inner_kernel"][0] == 3 and prof["ks_final_kernel"][0] == 3 and prof["inv_contig_kernel"][0] == 3
-    assert prof["fwd_strided_kernel"][0] == 6 and prof["inv_strided_kernel"][0] == 6
-    assert all(ms > 0 for n, ms, b in prof.values() if n)
+    # kernels are named as a profiler prints them; q-limbs run on the FP64 arithmetic, special limbs on integers
+    assert prof["ks_inner_kernel<FpAr, 5, 2, false>"][0] == 3 and prof["ks_inner_kernel<IntAr, 5, 2, false>"][0] == 3
+    assert prof["ks_final_kernel<FpAr, 5, 2>"][0] == 3 and prof["inv_contig_kernel<FpAr, 5, 2>"][0] == 3
+    assert prof["conv_fwd_strided_kernel<FpAr, 5, 1, 1>"][0] == 3 and prof["conv_fwd_strided_kernel<FpAr, 5, 2, 3>"][0] == 3
+    assert prof["inv_strided_kernel<FpAr, 5>"][0] == 3 and prof["inv_strided_kernel<IntAr, 5>"][0] == 3
+    assert all(n > 0 and ms > 0 and b > 0 for n, ms, b in prof.values())
