@@ -24,9 +24,25 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
-# copy kernel of known size); filled from profiles/ for the default workload, None when not measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for the default workload,
+# taken from profiles/keyswitch_step_n16_l24_d4_hbm_traffic.txt (FETCH_SIZE scaled by 2, the factor a plain
+# copy of known size shows); None for kernels or workloads that were not measured.
+_MIB = 1 << 20
+MEASURED_TRAFFIC_BYTES = {
+    "conv_fwd_strided_kernel<FpAr, 8, 1, 1>": int((97.5 + 288.0) * _MIB),
+    "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": int((78.1 + 194.0) * _MIB),
+    "conv_fwd_strided_kernel<IntAr, 8, 1, 1>": int((156.0 + 96.0) * _MIB),
+    "inv_contig_kernel<FpAr, 8, 1>": int((204.1 + 96.0) * _MIB),
+    "inv_contig_kernel<FpAr, 8, 2>": int((108.1 + 96.0) * _MIB),
+    "inv_strided_kernel<FpAr, 8>": int((96.6 + 96.0) * _MIB),
+    "inv_strided_kernel<IntAr, 8>": int((48.5 + 48.0) * _MIB),
+    "ks_final_kernel<FpAr, 8, 1>": int((984.7 + 192.0) * _MIB),
+    "ks_final_kernel<FpAr, 8, 2>": int((504.3 + 192.0) * _MIB),
+    "ks_inner_kernel<FpAr, 8, 1, false>": int((594.9 + 192.0) * _MIB),
+    "ks_inner_kernel<FpAr, 8, 2, false>": int((497.5 + 192.0) * _MIB),
+    "ks_inner_kernel<IntAr, 8, 1, false>": int((133.3 + 48.0) * _MIB),
+    "ks_inner_kernel<IntAr, 8, 2, false>": int((133.5 + 48.0) * _MIB),
+}
 
 
 def main():
@@ -101,7 +117,7 @@ def main():
     dom = max(prof.items(), key=lambda kv: kv[1][1])
     dname, (dn, dms, dbytes) = dom
     achieved = dbytes / dms / 1e6  # GB/s
-    traffic = MEASURED_TRAFFIC_BYTES.get(dname)
+    traffic = MEASURED_TRAFFIC_BYTES.get(dname) if (args.steps and B == synth.CFG2_BATCH) else None
     roofline = {"bound": "hbm", "kernel": dname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "alg_bytes_per_launch": dbytes // dn, "avg_launch_us": round(1e3 * dms / dn, 2),
