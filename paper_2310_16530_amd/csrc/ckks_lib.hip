@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -143,13 +144,67 @@ struct ProfState {
     }
 };
 
+// Overlap of the two arithmetic classes: between fork() and join() the launches on IntAr limbs
+// (integer-VALU bound) go to a side stream and run concurrently with the launches on FpAr limbs
+// (memory bound) of the caller's stream.  Ordering is by events only; both streams have default priority.
+struct SideStream {
+    bool enabled = true;  // CKKS_NO_OVERLAP=1 in the environment at context creation disables it
+    bool active = false;
+    hipStream_t stream = nullptr;
+    std::vector<hipEvent_t> events;
+    size_t next = 0;
+};
+
 struct ckks_ctx {
     u32 logN, L, K, dnum, alpha, D;
     std::vector<u64> primes, psi;
     Tables tb;
+    bool mixed_classes = false;  // both FpAr and IntAr primes present
     mutable std::string err;
     mutable ProfState prof;
+    mutable SideStream side;
 };
+
+static hipEvent_t side_event(SideStream& sd) {
+    if (sd.events.size() < 16) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        sd.events.push_back(e);
+        return e;
+    }
+    return sd.events[sd.next++ % sd.events.size()];
+}
+
+// From here on IntAr launches go to the side stream, ordered after everything enqueued on s so far.
+static void fork_side(const ckks_ctx* c, hipStream_t s) {
+    SideStream& sd = c->side;
+    if (!sd.enabled || !c->mixed_classes || sd.active) return;
+    if (!sd.stream && hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) != hipSuccess) {
+        sd.stream = nullptr;
+        sd.enabled = false;
+        (void)hipGetLastError();
+        return;
+    }
+    hipEvent_t e = side_event(sd);
+    if (!e || hipEventRecord(e, s) != hipSuccess || hipStreamWaitEvent(sd.stream, e, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+    }
+    sd.active = true;
+}
+
+// s waits for everything the side stream was given; IntAr launches return to s.
+static void join_side(const ckks_ctx* c, hipStream_t s) {
+    SideStream& sd = c->side;
+    if (!sd.active) return;
+    sd.active = false;
+    hipEvent_t e = side_event(sd);
+    if (!e || hipEventRecord(e, sd.stream) != hipSuccess || hipStreamWaitEvent(s, e, 0) != hipSuccess) {
+        // cannot order by event: fall back to a full wait so that correctness never depends on it
+        (void)hipGetLastError();
+        (void)hipStreamSynchronize(sd.stream);
+    }
+}
 
 static hipEvent_t prof_event(ProfState& p) {
     if (!p.pool.empty()) {
@@ -259,6 +314,13 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     c->logN = logN, c->L = L, c->K = K, c->dnum = dnum, c->alpha = alpha, c->D = D;
     c->primes.assign(h_primes, h_primes + D);
     c->psi.resize(D);
+    {
+        bool any_fp = false, any_int = false;
+        for (u32 i = 0; i < D; i++) (h_primes[i] < CKKS_FP_PRIME_LIMIT ? any_fp : any_int) = true;
+        c->mixed_classes = any_fp && any_int;
+        const char* e = getenv("CKKS_NO_OVERLAP");
+        c->side.enabled = !(e && e[0] == '1');
+    }
 
     std::vector<unsigned char> host(lay.total, 0);
     u64* tw = (u64*)(host.data() + lay.tw_int);
@@ -404,6 +466,11 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* ctx) {
     if (!ctx) return;
     prof_drain(ctx->prof);
     for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
+    if (ctx->side.stream) {
+        (void)hipStreamSynchronize(ctx->side.stream);
+        (void)hipStreamDestroy(ctx->side.stream);
+    }
+    for (hipEvent_t e : ctx->side.events) (void)hipEventDestroy(e);
     delete ctx;
 }
 
@@ -498,9 +565,10 @@ static void launch_runs(const ckks_ctx* c, u32 lo, u32 hi, u32 limb_base, bool b
         const LimbRun run = {cr.first - limb_base, cr.count};
         const dim3 grid(by_limb ? xcd_grid(cr.count * groups_n, inst_n)
                                 : xcd_grid(groups_n, (cr.count + inst_n - 1) / inst_n));
+        hipStream_t rs = (!cr.fp && c->side.active) ? c->side.stream : s;
         ProfScope ps(c, c->prof.on ? L::name(cr.fp ? "FpAr" : "IntAr", (int)c->logN - 8) : std::string(),
-                     c->prof.on ? alg(cr.first, cr.count) : 0, s);
-        dispatch_kernel<L>(c, cr.fp, grid, s, a, run);
+                     c->prof.on ? alg(cr.first, cr.count) : 0, rs);
+        dispatch_kernel<L>(c, cr.fp, grid, rs, a, run);
     }
 }
 
@@ -853,6 +921,7 @@ static void decompose_extend(const ckks_ctx* c, const Workspace& w, u32 groups, 
     const LimbSel sel = {c->L, groups, c->L, 0, 0, 0};
     InvStridedArgs a2 = {w.x, sel, SC_UP, 1};
     launch_inv_strided(c, a2, s);
+    fork_side(c, s);  // from here the special-limb (IntAr) chain runs beside the q-limb chain
     ConvArgs a3 = {w.x, w.dt, groups};
     launch_conv<CONV_UP>(c, a3, s);
 }
@@ -862,6 +931,7 @@ static void moddown_convert(const ckks_ctx* c, const Workspace& w, u32 cg, hipSt
     const LimbSel sel = {c->K, cg * 2, c->K, 0, c->L, 0};
     InvStridedArgs a6 = {w.cp, sel, SC_DN, 0};
     launch_inv_strided(c, a6, s);
+    join_side(c, s);  // the conversion reads every special limb
     ConvArgs a7 = {w.cp, w.cv, cg * 2};
     launch_conv<CONV_DN>(c, a7, s);
 }
@@ -956,8 +1026,11 @@ extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32
         FwdContigArgs p = {w.dt, LimbSel{c->K, c->dnum, c->D, c->L, c->L, 0}};
         launch_fwd_contig(c, p, s);
     }
-    for (u32 r0 = 0; r0 < n_rot; r0 += CKKS_ROT_CHUNK) {
-        const u32 nr = (n_rot - r0) < CKKS_ROT_CHUNK ? (n_rot - r0) : CKKS_ROT_CHUNK;
+    // rotations go through the ModDown side in chunks of at most CKKS_ROT_CHUNK, sized evenly
+    const u32 n_chunks = (n_rot + CKKS_ROT_CHUNK - 1) / CKKS_ROT_CHUNK;
+    const u32 chunk = (n_rot + n_chunks - 1) / n_chunks;
+    for (u32 r0 = 0; r0 < n_rot; r0 += chunk) {
+        const u32 nr = (n_rot - r0) < chunk ? (n_rot - r0) : chunk;
         InnerArgs ia;
         memset(&ia, 0, sizeof(ia));
         FinalArgs fa;
@@ -968,6 +1041,7 @@ extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32
             fa.galois[r] = h_galois[r0 + r];
         }
         ia.dt = w.dt, ia.own = d_ct, ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = nr;
+        fork_side(c, s);  // no-op in the first chunk (still forked); later chunks wait for the previous ModDown
         launch_ks_inner<OWN_COPY, true>(c, ia, s);
         moddown_convert(c, w, nr, s);
         fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = d_ct, fa.pt = d_pt + (size_t)r0 * c->L * N, fa.out = d_out;

@@ -586,6 +586,73 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
     u64* lrow = lds + ch * 272;
     const u32 row_off = r * 256;
     const u64 q = pc.q;
+    if constexpr (AR::is_fp) {
+        // FP64 pipe (magnitudes in units of q): v <= 5.2, c' - v <= 6.2, ks = (c' - v) * P^-1 <= 2.9,
+        // every added product of canonical operands <= 0.875; everything is canonicalised before the store.
+        const FpAr::Mod fm = FpAr::mod(pc);
+        if (MODE == FIN_HOISTED) {
+            const u32 t = inst;
+            double acc[16];
+#pragma unroll
+            for (int k = 0; k < 16; k++) acc[k] = 0.0;
+            for (u32 rr = 0; rr < a.n_rot; rr++) {
+                T v[16];
+                const u64* p = a.cv + (((size_t)rr * 2 + t) * L + i) * N + row_off;
+#pragma unroll
+                for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+                NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
+                exchange_cb_to_ca<AR>(v, lrow, e0);
+                const u64* c = a.cq + (((size_t)rr * 2 + t) * L + i) * N + row_off;
+                const u64* ptp = a.pt + ((size_t)rr * L + i) * N + row_off;
+                const u64* bp = a.ct1 + (size_t)i * N;
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    double ks = FpAr::mulmod_lazy(u64_to_f64(c[k * 16 + e0]) - v[k], pinv.d, fm);
+                    if (t == 0) ks += u64_to_f64(bp[eval_perm(row_off + k * 16 + e0, a.galois[rr], tb.logN)]);
+                    // reduced to <= q/2 so that the at most 8 accumulated products stay below 5.5 q
+                    acc[k] += FpAr::mulmod_lazy(FpAr::reduce(ks, fm), u64_to_f64(ptp[k * 16 + e0]), fm);
+                }
+            }
+            u64* o = a.out + ((size_t)t * L + i) * N + row_off;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                double res = acc[k];
+                if (a.accumulate) res += u64_to_f64(o[k * 16 + e0]);
+                o[k * 16 + e0] = FpAr::canon(res, fm);
+            }
+            return;
+        }
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            T v[16];
+            const u64* p = a.cv + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+#pragma unroll
+            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+            NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
+            exchange_cb_to_ca<AR>(v, lrow, e0);
+            const u64* c = a.cq + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+            u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+            const size_t o0 = (((size_t)inst * 2 + 0) * L + i) * N + row_off, o1 = o0 + (size_t)L * N;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const u32 e = k * 16 + e0;
+                double ks = FpAr::mulmod_lazy(u64_to_f64(c[e]) - v[k], pinv.d, fm);
+                if (MODE == FIN_HMULT) {
+                    if (t == 0) {
+                        ks += FpAr::mulmod_lazy(u64_to_f64(a.ct1[o0 + e]), u64_to_f64(a.ct2[o0 + e]), fm);
+                    } else {
+                        const double b1 = u64_to_f64(a.ct1[o0 + e]), b2 = u64_to_f64(a.ct2[o0 + e]);
+                        ks += FpAr::mulmod_lazy(u64_to_f64(a.ct1[o1 + e]), b2, fm) +
+                              FpAr::mulmod_lazy(u64_to_f64(a.ct2[o1 + e]), b1, fm);
+                    }
+                } else if (MODE == FIN_HROT) {
+                    if (t == 0) ks += u64_to_f64(a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[0], tb.logN)]);
+                }
+                o[e] = FpAr::canon(ks, fm);
+            }
+        }
+        return;
+    }
     if (MODE == FIN_HOISTED) {
         const u32 t = inst;
         u128w acc[16];
