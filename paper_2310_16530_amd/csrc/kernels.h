@@ -520,6 +520,10 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             AR::acc_mac(acc0[k], v[k], kv0[k], m);
             AR::acc_mac(acc1[k], v[k], kv1[k], m);
         }
+        if ((j & 7) == 7) {  // FpAr sums at most 8 lazily reduced products (0.69 q each) between reductions
+#pragma unroll
+            for (int k = 0; k < 16; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
+        }
     }
     if (i < L) {
         u64* o0 = a.cq + (((size_t)inst * 2 + 0) * L + i) * N + row_off;

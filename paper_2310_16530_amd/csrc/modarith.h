@@ -148,6 +148,7 @@ struct IntAr {
         u64 s = acc + r;
         acc = s >= m.q2 ? s - m.q2 : s;
     }
+    static HD T acc_fold(T acc, const Mod&) { return acc; }  // already kept in [0, 2q)
     static HD T acc_finish(T acc, const Mod& m) {  // remove the 2^-64: result in [0, 2q), valid as inverse-lazy
         return mul_shoup_lazy(acc, m.r1, m.r1_p, m.q);
     }
@@ -227,6 +228,7 @@ struct FpAr {
     }
     static HD T acc_zero() { return 0.0; }
     static HD void acc_mac(T& acc, T v, u64 key, const Mod& m) { acc += mulmod_lazy(v, u64_to_f64(key), m); }
+    static HD T acc_fold(T acc, const Mod& m) { return reduce(acc, m); }
     static HD T acc_finish(T acc, const Mod& m) { return reduce(acc, m); }
     static HD u64 acc_canon(T fin, const Mod& m) {
         double r = fin < 0.0 ? fin + m.q : fin;

@@ -161,7 +161,8 @@ def make_keys(orc, ps, P, rng, s_hat, sp_hat):
     return orc.make_switch_key(s_hat, sp_hat, a, e, P)
 
 
-KS_SHAPES = [(12, 4, 2, 2), (12, 3, 1, 3), (13, 6, 3, 2), (12, 6, 6, 1), (14, 4, 2, 2), (12, 14, 7, 2), (12, 8, 8, 1)]
+KS_SHAPES = [(12, 4, 2, 2), (12, 3, 1, 3), (13, 6, 3, 2), (12, 6, 6, 1), (14, 4, 2, 2), (12, 14, 7, 2), (12, 8, 8, 1),
+             (12, 20, 1, 20), (15, 2, 2, 1)]
 
 
 @pytest.mark.parametrize("shape", KS_SHAPES)

@@ -1,0 +1,44 @@
+"""Planted mistakes in the CPU oracle must be caught by its pins (CPU only, nothing touches a GPU).
+
+Each mutation is a single-line change of oracle/ckks_oracle.c (swapped operands, a dropped factor, a
+wrong index map ...), compiled into a scratch library; the named pin test is then run against it in a
+subprocess and must fail.
+"""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "ckks_oracle.c")
+
+MUTATIONS = [
+    ("x[j + t] = orc_submod(u, v, m);", "x[j + t] = orc_submod(v, u, m);", "test_ntt_equals_bigint_definition"),
+    ("uint64_t y = orc_mulmod(x[i * stride + n], hat_inv[i], src[i]);", "uint64_t y = x[i * stride + n];", "test_modup_vs_bigint_crt"),
+    ("orc_mulmod(orc_submod(in[(size_t)i * N + n], conv[n], q), Pinv, q)", "orc_mulmod(orc_submod(conv[n], in[(size_t)i * N + n], q), Pinv, q)", "test_moddown_vs_bigint"),
+    ("uint64_t e = ((uint64_t)g * (2ull * bitrev(j, logN) + 1)) % (2 * N);", "uint64_t e = ((uint64_t)g * (2ull * j + 1)) % (2 * N);", "test_automorphism_coeff_by_substitution_and_eval_consistency"),
+    ("else out[u - N] = (m - in[t]) % m;", "else out[u - N] = in[t];", "test_automorphism_coeff_by_substitution_and_eval_consistency"),
+    ("if (i >= j * alpha && i < (j + 1) * alpha) {\n            Pm = 1;", "if (i < L) {\n            Pm = 1;", "test_switch_key_structure"),
+    ("orc_keyswitch(rot + (size_t)L * N, rk, out", "orc_keyswitch(ct + (size_t)L * N, rk, out", "test_hrot_decrypts_to_rotated"),
+    ("orc_addmod(orc_mulmod(a1[n], b2[n], m), orc_mulmod(a2[n], b1[n], m), m);", "orc_addmod(orc_mulmod(a1[n], b2[n], m), orc_mulmod(a2[n], b2[n], m), m);", "test_hmult_relin_decrypts_to_product"),
+    ("if (galois != 1) { orc_automorph_eval(src, perm, p->logN, galois); src = perm; }", "", "test_hoisted_mac_per_rotation_and_linearity"),
+    ("limbs_ntt(cp, p, 0, D, 2, D, 1);", "limbs_ntt(cp, p, 0, D, 2, D, 0);", "test_keyswitch_decrypt_and_bound"),
+    ("uint64_t n_inv = orc_invmod(N % m, m);", "uint64_t n_inv = 1;", "test_ntt_equals_bigint_definition"),
+    ("memcpy(dst, in + (size_t)t * N, N * sizeof(uint64_t));", "memset(dst, 0, N * sizeof(uint64_t));", "test_modup_vs_bigint_crt"),
+]
+
+
+@pytest.mark.parametrize("idx", range(len(MUTATIONS)))
+def test_planted_mistake_is_caught(idx, tmp_path):
+    old, new, victim = MUTATIONS[idx]
+    text = open(SRC).read()
+    assert text.count(old) >= 1, "mutation target not found: the oracle source changed"
+    mutated = tmp_path / "ckks_oracle.c"
+    mutated.write_text(text.replace(old, new, 1))
+    lib = tmp_path / "libckks_oracle_mut.so"
+    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(lib), str(mutated)])
+    env = dict(os.environ, CKKS_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+                        "-k", victim, "-p", "no:cacheprovider"], capture_output=True, text=True, env=env, cwd=ROOT)
+    assert r.returncode != 0 and "failed" in r.stdout, "the pins did not notice: " + new
