@@ -85,12 +85,12 @@ __device__ __forceinline__ void inv_contig_body(const InvContigArgs& a, const Ta
     if (LOAD == INV_PLAIN) {
         const u64* p = a.src + limb_offset(a.sel, inst, l) * N + (size_t)r * 256;
 #pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = AR::round_reduce(AR::from_canon(p[k * 16 + e0], m), m);
+        for (int k = 0; k < 16; k++) x[k] = AR::round_reduce(AR::from_canon(__builtin_nontemporal_load(&p[k * 16 + e0]), m), m);
     } else if (LOAD == INV_TENSOR) {  // d2 = a1 * a2 on limb l of pair `inst`
         const size_t off = (((size_t)inst * 2 + 1) * tb.L + l) * N + (size_t)r * 256;
 #pragma unroll
         for (int k = 0; k < 16; k++) {
-            x[k] = AR::round_reduce(AR::mul_canon(a.src[off + k * 16 + e0], a.src2[off + k * 16 + e0], pc, m), m);
+            x[k] = AR::round_reduce(AR::mul_canon(__builtin_nontemporal_load(&a.src[off + k * 16 + e0]), __builtin_nontemporal_load(&a.src2[off + k * 16 + e0]), pc, m), m);
         }
     } else {  // sigma_g(a) on limb l of ciphertext `inst`
         const u64* p = a.src + (((size_t)inst * 2 + 1) * tb.L + l) * N;
@@ -189,7 +189,7 @@ __device__ __forceinline__ void fwd_strided_finish(typename AR::T (&x)[16], cons
     C::fwd_strided(x, lds, tid, ti, tf, N, m);
     if constexpr (A > 4) {
 #pragma unroll
-        for (int k = 0; k < 16; k++) dst[(size_t)(r0 * 16 + k) * 256 + col] = AR::to_raw(AR::round_reduce(x[k], m));
+        for (int k = 0; k < 16; k++) __builtin_nontemporal_store(AR::to_raw(AR::round_reduce(x[k], m)), &dst[(size_t)(r0 * 16 + k) * 256 + col]);
     } else {
 #pragma unroll
         for (int k = 0; k < 16; k++)
@@ -492,7 +492,7 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
                 const size_t off = (((size_t)inst * 2 + 1) * L + i) * N + row_off;
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
-                    v[k] = AR::round_reduce(AR::mul_canon(a.own[off + k * 16 + e0], a.own2[off + k * 16 + e0], pc, m), m);
+                    v[k] = AR::round_reduce(AR::mul_canon(__builtin_nontemporal_load(&a.own[off + k * 16 + e0]), __builtin_nontemporal_load(&a.own2[off + k * 16 + e0]), pc, m), m);
                 }
             } else {
                 const u64* p = a.own + (((size_t)inst * 2 + 1) * L + i) * N;
@@ -508,7 +508,7 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
         } else {
             const u64* p = a.dt + (((size_t)inst * tb.dnum + j) * D + i) * N + row_off;
 #pragma unroll
-            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
             NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
 #pragma unroll
             for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(v[k], m);
@@ -530,8 +530,8 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
         u64* o1 = a.cq + (((size_t)inst * 2 + 1) * L + i) * N + row_off;
 #pragma unroll
         for (int k = 0; k < 16; k++) {
-            o0[k * 16 + e0] = AR::acc_canon(AR::acc_finish(acc0[k], m), m);
-            o1[k * 16 + e0] = AR::acc_canon(AR::acc_finish(acc1[k], m), m);
+            __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc0[k], m), m), &o0[k * 16 + e0]);
+            __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc1[k], m), m), &o1[k * 16 + e0]);
         }
     } else {
 #pragma unroll
@@ -603,7 +603,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                 T v[16];
                 const u64* p = a.cv + (((size_t)rr * 2 + t) * L + i) * N + row_off;
 #pragma unroll
-                for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+                for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
                 NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
                 exchange_cb_to_ca<AR>(v, lrow, e0);
                 const u64* c = a.cq + (((size_t)rr * 2 + t) * L + i) * N + row_off;
@@ -611,10 +611,10 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                 const u64* bp = a.ct1 + (size_t)i * N;
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
-                    double ks = FpAr::mulmod_lazy(u64_to_f64(c[k * 16 + e0]) - v[k], pinv.d, fm);
+                    double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[k * 16 + e0])) - v[k], pinv.d, fm);
                     if (t == 0) ks += u64_to_f64(bp[eval_perm(row_off + k * 16 + e0, a.galois[rr], tb.logN)]);
                     // reduced to <= q/2 so that the at most 8 accumulated products stay below 5.5 q
-                    acc[k] += FpAr::mulmod_lazy(FpAr::reduce(ks, fm), u64_to_f64(ptp[k * 16 + e0]), fm);
+                    acc[k] += FpAr::mulmod_lazy(FpAr::reduce(ks, fm), u64_to_f64(__builtin_nontemporal_load(&ptp[k * 16 + e0])), fm);
                 }
             }
             u64* o = a.out + ((size_t)t * L + i) * N + row_off;
@@ -622,7 +622,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             for (int k = 0; k < 16; k++) {
                 double res = acc[k];
                 if (a.accumulate) res += u64_to_f64(o[k * 16 + e0]);
-                o[k * 16 + e0] = FpAr::canon(res, fm);
+                __builtin_nontemporal_store(FpAr::canon(res, fm), &o[k * 16 + e0]);
             }
             return;
         }
@@ -631,7 +631,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             T v[16];
             const u64* p = a.cv + (((size_t)inst * 2 + t) * L + i) * N + row_off;
 #pragma unroll
-            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
             NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
             exchange_cb_to_ca<AR>(v, lrow, e0);
             const u64* c = a.cq + (((size_t)inst * 2 + t) * L + i) * N + row_off;
@@ -640,7 +640,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 const u32 e = k * 16 + e0;
-                double ks = FpAr::mulmod_lazy(u64_to_f64(c[e]) - v[k], pinv.d, fm);
+                double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[e])) - v[k], pinv.d, fm);
                 if (MODE == FIN_HMULT) {
                     if (t == 0) {
                         ks += FpAr::mulmod_lazy(u64_to_f64(a.ct1[o0 + e]), u64_to_f64(a.ct2[o0 + e]), fm);
@@ -652,7 +652,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                 } else if (MODE == FIN_HROT) {
                     if (t == 0) ks += u64_to_f64(a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[0], tb.logN)]);
                 }
-                o[e] = FpAr::canon(ks, fm);
+                __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[e]);
             }
         }
         return;
@@ -666,7 +666,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             T v[16];
             const u64* p = a.cv + (((size_t)rr * 2 + t) * L + i) * N + row_off;
 #pragma unroll
-            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
             NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
             exchange_cb_to_ca<AR>(v, lrow, e0);
             const u64* c = a.cq + (((size_t)rr * 2 + t) * L + i) * N + row_off;
@@ -693,7 +693,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
         T v[16];
         const u64* p = a.cv + (((size_t)inst * 2 + t) * L + i) * N + row_off;
 #pragma unroll
-        for (int k = 0; k < 16; k++) v[k] = AR::from_raw(p[k * 16 + e0]);
+        for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
         NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
         exchange_cb_to_ca<AR>(v, lrow, e0);
         const u64* c = a.cq + (((size_t)inst * 2 + t) * L + i) * N + row_off;
