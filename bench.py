@@ -23,25 +23,30 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# VALU issue peak: 256 CUs x 4 SIMDs, one wave64 instruction per 4 cycles at 2.4 GHz = 39.3 T lane-instructions/s
+# (the same units and clock that give the published 78.6 TFLOP/s fp64 figure, an FMA counting two flops).
+VALU_PEAK_TINSTR = 256 * 64 * 2.4e9 / 1e12
 
-# HBM bytes per launch (read + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for the default workload,
-# taken from profiles/keyswitch_step_n16_l24_d4_hbm_traffic.txt (FETCH_SIZE scaled by 2, the factor a plain
-# copy of known size shows); None for kernels or workloads that were not measured.
+# Per-launch counters of the default workload from rocprofv3 --pmc, copied from
+# profiles/keyswitch_step_n16_l24_d4_hbm_traffic.txt: HBM bytes (FETCH_SIZE scaled by 2, the factor a plain copy
+# of known size shows, plus WRITE_SIZE) and wave-level VALU instructions (SQ_INSTS_VALU).  Kernels or workloads
+# that were not measured report null.
 _MIB = 1 << 20
-MEASURED_TRAFFIC_BYTES = {
-    "conv_fwd_strided_kernel<FpAr, 8, 1, 1>": int((97.5 + 288.0) * _MIB),
-    "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": int((78.1 + 194.0) * _MIB),
-    "conv_fwd_strided_kernel<IntAr, 8, 1, 1>": int((156.0 + 96.0) * _MIB),
-    "inv_contig_kernel<FpAr, 8, 1>": int((204.1 + 96.0) * _MIB),
-    "inv_contig_kernel<FpAr, 8, 2>": int((108.1 + 96.0) * _MIB),
-    "inv_strided_kernel<FpAr, 8>": int((96.6 + 96.0) * _MIB),
-    "inv_strided_kernel<IntAr, 8>": int((48.5 + 48.0) * _MIB),
-    "ks_final_kernel<FpAr, 8, 1>": int((984.7 + 192.0) * _MIB),
-    "ks_final_kernel<FpAr, 8, 2>": int((504.3 + 192.0) * _MIB),
-    "ks_inner_kernel<FpAr, 8, 1, false>": int((594.9 + 192.0) * _MIB),
-    "ks_inner_kernel<FpAr, 8, 2, false>": int((497.5 + 192.0) * _MIB),
-    "ks_inner_kernel<IntAr, 8, 1, false>": int((133.3 + 48.0) * _MIB),
-    "ks_inner_kernel<IntAr, 8, 2, false>": int((133.5 + 48.0) * _MIB),
+MEASURED = {
+    # kernel: (read MiB, write MiB, VALU wave-instructions)
+    "conv_fwd_strided_kernel<FpAr, 8, 1, 1>": (96.7, 288.0, 58736640),
+    "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": (49.7, 194.0, 55205888),
+    "conv_fwd_strided_kernel<IntAr, 8, 1, 1>": (114.8, 96.0, 58097664),
+    "inv_contig_kernel<FpAr, 8, 1>": (204.1, 96.0, 11341824),
+    "inv_contig_kernel<FpAr, 8, 2>": (108.1, 96.0, 11476992),
+    "inv_strided_kernel<FpAr, 8>": (96.6, 96.0, 9891840),
+    "inv_strided_kernel<IntAr, 8>": (48.5, 48.0, 13197312),
+    "ks_final_kernel<FpAr, 8, 1>": (984.3, 192.0, 32305152),
+    "ks_final_kernel<FpAr, 8, 2>": (499.6, 192.0, 26652672),
+    "ks_inner_kernel<FpAr, 8, 1, false>": (588.2, 192.0, 49041408),
+    "ks_inner_kernel<FpAr, 8, 2, false>": (492.2, 192.0, 49188864),
+    "ks_inner_kernel<IntAr, 8, 1, false>": (132.8, 48.0, 50257920),
+    "ks_inner_kernel<IntAr, 8, 2, false>": (132.9, 48.0, 50789376),
 }
 
 
@@ -112,16 +117,35 @@ def main():
     total_ms = sum(v[1] for v in prof.values()) or 1.0
     for name, (n, ms, nbytes) in prof.items():
         if n:
-            kernels[name] = {"launches_per_step": n / args.steps, "avg_us": 1e3 * ms / n,
-                             "share": ms / total_ms, "alg_GBps": nbytes / ms / 1e6}
+            k = {"launches_per_step": n / args.steps, "avg_us": round(1e3 * ms / n, 2),
+                 "share": round(ms / total_ms, 4), "alg_GBps": round(nbytes / ms / 1e6, 1)}
+            mk = MEASURED.get(name) if B == synth.CFG2_BATCH else None
+            if mk:
+                k["hbm_traffic_GBps"] = round((mk[0] + mk[1]) * _MIB / (ms / n * 1e-3) / 1e9, 1)
+                k["valu_issue_frac"] = round(mk[2] * 64 / (ms / n * 1e-3) / 1e12 / VALU_PEAK_TINSTR, 3)
+            kernels[name] = k
     dom = max(prof.items(), key=lambda kv: kv[1][1])
     dname, (dn, dms, dbytes) = dom
-    achieved = dbytes / dms / 1e6  # GB/s
-    traffic = MEASURED_TRAFFIC_BYTES.get(dname) if (args.steps and B == synth.CFG2_BATCH) else None
-    roofline = {"bound": "hbm", "kernel": dname, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "alg_bytes_per_launch": dbytes // dn, "avg_launch_us": round(1e3 * dms / dn, 2),
-                "share_of_step": round(dms / total_ms, 3)}
+    dur_s = dms / dn * 1e-3
+    hbm_gbs = dbytes / dms / 1e6
+    meas = MEASURED.get(dname) if B == synth.CFG2_BATCH else None
+    traffic = int((meas[0] + meas[1]) * _MIB) if meas else None
+    valu_tinstr = meas[2] * 64 / dur_s / 1e12 if meas else None
+    hbm_frac = hbm_gbs / HBM_PEAK_GBS
+    alu_frac = valu_tinstr / VALU_PEAK_TINSTR if meas else None
+    roofline = {"kernel": dname, "traffic": traffic, "alg_bytes_per_launch": dbytes // dn,
+                "avg_launch_us": round(1e6 * dur_s, 2), "share_of_step": round(dms / total_ms, 3),
+                "hbm": {"achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_frac, 4)},
+                "alu": None if alu_frac is None else {
+                    "achieved": round(valu_tinstr, 2), "peak": round(VALU_PEAK_TINSTR, 2),
+                    "unit": "T VALU lane-instructions/s (peak = 256 CU x 64 lanes x 2.4 GHz = fp64 78.6 TFLOP/s / 2)",
+                    "frac": round(alu_frac, 4)}}
+    if alu_frac is not None and alu_frac > hbm_frac:
+        roofline.update({"bound": "alu", "achieved": round(valu_tinstr, 2), "peak": round(VALU_PEAK_TINSTR, 2),
+                         "unit": "Tinstr/s", "frac": round(alu_frac, 4)})
+    else:
+        roofline.update({"bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round(hbm_frac, 4)})
 
     extra = {"hmult_relin_per_s": None, "hrot_per_s": None}
     # split of the step (separately timed, same launch configuration)
@@ -135,6 +159,19 @@ def main():
         extra[name] = round(B * args.steps / (time.perf_counter() - a), 1)
 
     if not args.no_extras:
+        # the same step with the optional two-stream execution inside each call (integer special-limb launches
+        # beside the floating-point launches)
+        ctx.set_overlap(True)
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        extra["key_switches_per_s_with_overlap"] = round(ks_per_step * args.steps / (time.perf_counter() - a), 1)
+        ctx.set_overlap(False)
+
         # config 1: 16 polynomials x 24 limbs, forward and inverse
         x = dev(synth.uniform_residues(rng, ps.q_primes, N, lead=(synth.CFG1_BATCH,)))
         limbs = synth.CFG1_BATCH * L
@@ -150,6 +187,8 @@ def main():
             extra[name] = round(limbs / dt, 1)
             # one transform reads and writes every limb once: 2 * 8N bytes per limb (compulsory)
             extra[name.replace("limbs_per_s", "effective_GBps")] = round(limbs * 2 * 8 * N / dt / 1e9, 1)
+            # the two passes together move every limb four times
+            extra[name.replace("limbs_per_s", "pass_traffic_GBps")] = round(limbs * 4 * 8 * N / dt / 1e9, 1)
         del x
         # config 3: 17 hoisted rotations with plaintext MAC (keys are rolled copies of one uniform key)
         rots = synth.CFG3_ROTATIONS

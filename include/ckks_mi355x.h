@@ -182,6 +182,16 @@ int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, c
                           size_t ws_bytes, void* stream);
 
 /*
+ * Optional two-stream execution inside one call.  Off by default: every kernel of a call runs on the
+ * caller's stream in order.  With on != 0 the key-switch entry points run the launches that work on
+ * integer-arithmetic limbs (primes of 50 bits and more, normally the special limbs) on a second stream
+ * owned by the context, beside the launches on floating-point-arithmetic limbs, ordered by events
+ * (both streams at default priority).  Results are identical; the call still completes in stream order
+ * on the caller's stream.  Not to be changed while a call of this context is being issued.
+ */
+int ckks_set_overlap(ckks_ctx* ctx, int on);
+
+/*
  * Measurement support (no part of the method): per-kernel timing with HIP events.
  * ckks_profile_enable(ctx, 1) clears the counters and makes every later kernel launch of this
  * context be bracketed by two HIP events recorded on the launch stream; (ctx, 0) stops that.

@@ -23,7 +23,7 @@ EXPORTS = (
     "ckks_table_bytes", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error", "ckks_ctx_psi",
     "ckks_workspace_bytes", "ckks_ntt", "ckks_intt", "ckks_modup", "ckks_moddown", "ckks_automorph",
     "ckks_keyswitch", "ckks_hmult_relin", "ckks_hrot", "ckks_hrot_hoisted_mac",
-    "ckks_profile_enable", "ckks_profile_read",
+    "ckks_profile_enable", "ckks_profile_read", "ckks_set_overlap",
 )
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
@@ -63,6 +63,7 @@ def load() -> ctypes.CDLL:
     lib.ckks_hmult_relin.argtypes = [_vp, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot.argtypes = [_vp, _vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_hoisted_mac.argtypes = [_vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.ckks_set_overlap.argtypes = [_vp, _int]
     lib.ckks_profile_enable.argtypes = [_vp, _int]
     lib.ckks_profile_read.argtypes = [_vp, _u32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_u64),
                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_u64)]
@@ -135,6 +136,9 @@ class Context:
             self._ws = None
             self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
         return self._ws
+
+    def set_overlap(self, on: bool) -> None:
+        self._check(load().ckks_set_overlap(self.handle, 1 if on else 0))
 
     def profile_enable(self, on: bool) -> None:
         self._check(load().ckks_profile_enable(self.handle, 1 if on else 0))

@@ -4,7 +4,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdio.h>
-#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -148,7 +147,7 @@ struct ProfState {
 // (integer-VALU bound) go to a side stream and run concurrently with the launches on FpAr limbs
 // (memory bound) of the caller's stream.  Ordering is by events only; both streams have default priority.
 struct SideStream {
-    bool enabled = true;  // CKKS_NO_OVERLAP=1 in the environment at context creation disables it
+    bool enabled = false;  // off by default; ckks_set_overlap switches it
     bool active = false;
     hipStream_t stream = nullptr;
     std::vector<hipEvent_t> events;
@@ -318,8 +317,6 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         bool any_fp = false, any_int = false;
         for (u32 i = 0; i < D; i++) (h_primes[i] < CKKS_FP_PRIME_LIMIT ? any_fp : any_int) = true;
         c->mixed_classes = any_fp && any_int;
-        const char* e = getenv("CKKS_NO_OVERLAP");
-        c->side.enabled = !(e && e[0] == '1');
     }
 
     std::vector<unsigned char> host(lay.total, 0);
@@ -495,6 +492,13 @@ extern "C" int ckks_profile_read(ckks_ctx* ctx, uint32_t index, const char** nam
     return CKKS_OK;
 }
 
+extern "C" int ckks_set_overlap(ckks_ctx* ctx, int on) {
+    if (!ctx) return CKKS_EINVAL;
+    if (ctx->side.active) return fail(ctx, CKKS_EINVAL, "cannot change overlap inside an operation");
+    ctx->side.enabled = on != 0;
+    return CKKS_OK;
+}
+
 extern "C" const char* ckks_last_error(const ckks_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
 extern "C" uint64_t ckks_ctx_psi(const ckks_ctx* ctx, uint32_t i) { return (ctx && i < ctx->D) ? ctx->psi[i] : 0; }
@@ -563,8 +567,11 @@ static void launch_runs(const ckks_ctx* c, u32 lo, u32 hi, u32 limb_base, bool b
                         const ArgT& a, hipStream_t s, AlgFn alg) {
     for (const ClassRun& cr : class_runs(c, lo, hi)) {
         const LimbRun run = {cr.first - limb_base, cr.count};
+        // conversion launches: inst_n holds the targets per workgroup of FpAr runs in its low half and of
+        // IntAr runs in its high half
+        const u32 tbn = cr.fp ? (inst_n & 0xffff) : (inst_n >> 16);
         const dim3 grid(by_limb ? xcd_grid(cr.count * groups_n, inst_n)
-                                : xcd_grid(groups_n, (cr.count + inst_n - 1) / inst_n));
+                                : xcd_grid(groups_n, (cr.count + tbn - 1) / tbn));
         hipStream_t rs = (!cr.fp && c->side.active) ? c->side.stream : s;
         ProfScope ps(c, c->prof.on ? L::name(cr.fp ? "FpAr" : "IntAr", (int)c->logN - 8) : std::string(),
                      c->prof.on ? alg(cr.first, cr.count) : 0, rs);
@@ -596,23 +603,29 @@ struct FwdStridedL {
     }
     static std::string name(const char* ar, int A) { return kname("fwd_strided_kernel", ar, A, ""); }
 };
-// target limbs converted per workgroup
-#ifndef CKKS_CONV_TB_UP
-#define CKKS_CONV_TB_UP 1
+// target limbs converted per workgroup, per direction and arithmetic (measured optimum: more targets save L2
+// reads of the sources but cost registers, which the integer kernels do not have)
+#ifndef CKKS_CONV_TB_UP_FP
+#define CKKS_CONV_TB_UP_FP 2
 #endif
-#ifndef CKKS_CONV_TB_DN
-#define CKKS_CONV_TB_DN 3
+#ifndef CKKS_CONV_TB_DN_FP
+#define CKKS_CONV_TB_DN_FP 3
 #endif
+template <int DIR, bool FP>
+struct ConvTB {
+    static constexpr int value = FP ? (DIR == CONV_UP ? CKKS_CONV_TB_UP_FP : CKKS_CONV_TB_DN_FP) : 1;
+};
 template <int DIR>
 struct ConvL {
-    static constexpr int TB = DIR == CONV_UP ? CKKS_CONV_TB_UP : CKKS_CONV_TB_DN;
     template <class AR, int A>
     static void go(dim3 g, hipStream_t s, const ConvArgs& a, const Tables& tb, LimbRun run) {
-        hipLaunchKernelGGL((conv_fwd_strided_kernel<AR, A, DIR, TB>), g, dim3(256), 0, s, a, tb, run);
+        hipLaunchKernelGGL((conv_fwd_strided_kernel<AR, A, DIR, ConvTB<DIR, AR::is_fp>::value>), g, dim3(256), 0, s, a, tb,
+                           run);
     }
     static std::string name(const char* ar, int A) {
+        const int tbv = ar[0] == 'F' ? ConvTB<DIR, true>::value : ConvTB<DIR, false>::value;
         return kname("conv_fwd_strided_kernel", ar, A,
-                     (std::string(", ") + std::to_string(DIR) + ", " + std::to_string(TB)).c_str());
+                     (std::string(", ") + std::to_string(DIR) + ", " + std::to_string(tbv)).c_str());
     }
 };
 struct FwdContigL {
@@ -670,14 +683,16 @@ template <int DIR>
 static void launch_conv(const ckks_ctx* c, const ConvArgs& a, hipStream_t s) {
     const u64 outer = a.groups_outer;
     if (DIR == CONV_UP) {  // groups = (batch, digit, tile); instances = blocks of the run's target primes
-        launch_runs<ConvL<DIR>>(c, 0, c->D, 0, false, a.groups_outer * c->dnum * tiles_of(c), ConvL<DIR>::TB, a, s,
+        launch_runs<ConvL<DIR>>(c, 0, c->D, 0, false, a.groups_outer * c->dnum * tiles_of(c),
+                                ConvTB<DIR, true>::value | (ConvTB<DIR, false>::value << 16), a, s,
                                 [c, outer](u32 first, u32 n) {
                                     u64 w = 0;  // every target limb is written for each digit that does not own it
                                     for (u32 t = first; t < first + n; t++) w += c->dnum - (t < c->L ? 1 : 0);
                                     return outer * (w + c->L);  // plus the source coefficients, read once
                                 });
     } else {  // groups = (g, tile); instances = blocks of the run's target q-limbs
-        launch_runs<ConvL<DIR>>(c, 0, c->L, 0, false, a.groups_outer * tiles_of(c), ConvL<DIR>::TB, a, s,
+        launch_runs<ConvL<DIR>>(c, 0, c->L, 0, false, a.groups_outer * tiles_of(c),
+                                ConvTB<DIR, true>::value | (ConvTB<DIR, false>::value << 16), a, s,
                                 [c, outer](u32, u32 n) { return outer * (n + (u64)c->K); });
     }
 }

@@ -291,17 +291,28 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
 #pragma unroll
             for (int k = 0; k < 16; k++) acc[t][k] = 0.0;
         }
-#pragma unroll 1
+        // the loads of source i+1 are issued before the arithmetic on source i (software pipeline)
+        u64 cur[16], nxt[16];
+        {
+            const u64* s0 = src + (size_t)rot * N;
+#pragma unroll
+            for (int k = 0; k < 16; k++) cur[k] = s0[(size_t)(k * C::RB + r0) * 256 + col];
+        }
         for (u32 i0 = 0; i0 < ns; i0++) {
             const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
-            const u64* si = src + (size_t)i * N;
+            if (i0 + 1 < ns) {
+                const u32 in = i0 + 1 + rot < ns ? i0 + 1 + rot : i0 + 1 + rot - ns;
+                const u64* sn = src + (size_t)in * N;
+#pragma unroll
+                for (int k = 0; k < 16; k++) nxt[k] = sn[(size_t)(k * C::RB + r0) * 256 + col];
+            }
             if (DIR == CONV_UP) {  // sources are doubles holding canonical residues of ~the targets' size
                 double cf[TB];
 #pragma unroll
                 for (int t = 0; t < TB; t++) cf[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
-                    const double y = FpAr::from_raw(si[(size_t)(k * C::RB + r0) * 256 + col]);
+                    const double y = FpAr::from_raw(cur[k]);
 #pragma unroll
                     for (int t = 0; t < TB; t++) acc[t][k] += FpAr::mulmod_lazy(y, cf[t], fm[t]);
                 }
@@ -314,13 +325,15 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
                 }
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
-                    const u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
+                    const u64 y = cur[k];
                     const double yh = (double)(u32)(y >> 30), yl = (double)(u32)(y & 0x3fffffffu);
 #pragma unroll
                     for (int t = 0; t < TB; t++)
                         acc[t][k] += FpAr::mulmod_lazy(yh, ch[t], fm[t]) + FpAr::mulmod_lazy(yl, cl[t], fm[t]);
                 }
             }
+#pragma unroll
+            for (int k = 0; k < 16; k++) cur[k] = nxt[k];
         }
 #pragma unroll
         for (int t = 0; t < TB; t++) {

@@ -91,6 +91,7 @@ def test_null_context_calls_fail_cleanly(lib):
     assert lib.ckks_hrot_hoisted_mac(None, fake, 1, fake, fake, fake, fake, fake, 0, None) == -1
     assert lib.ckks_workspace_bytes(None, 4, 1, ctypes.byref(n)) == -1
     assert lib.ckks_profile_enable(None, 1) == -1
+    assert lib.ckks_set_overlap(None, 1) == -1
     assert lib.ckks_last_error(None) == b"null context"
     assert lib.ckks_ctx_psi(None, 0) == 0
     lib.ckks_ctx_destroy(None)

@@ -397,6 +397,29 @@ def test_repeat_runs_are_bit_identical_and_profile_counts_launches(orc):
     # kernels are named as a profiler prints them; q-limbs run on the FP64 arithmetic, special limbs on integers
     assert prof["ks_inner_kernel<FpAr, 5, 2, false>"][0] == 3 and prof["ks_inner_kernel<IntAr, 5, 2, false>"][0] == 3
     assert prof["ks_final_kernel<FpAr, 5, 2>"][0] == 3 and prof["inv_contig_kernel<FpAr, 5, 2>"][0] == 3
-    assert prof["conv_fwd_strided_kernel<FpAr, 5, 1, 1>"][0] == 3 and prof["conv_fwd_strided_kernel<FpAr, 5, 2, 3>"][0] == 3
+    assert prof["conv_fwd_strided_kernel<FpAr, 5, 1, 2>"][0] == 3 and prof["conv_fwd_strided_kernel<FpAr, 5, 2, 3>"][0] == 3
     assert prof["inv_strided_kernel<FpAr, 5>"][0] == 3 and prof["inv_strided_kernel<IntAr, 5>"][0] == 3
     assert all(n > 0 and ms > 0 and b > 0 for n, ms, b in prof.values())
+
+
+def test_two_stream_overlap_gives_identical_results(orc):
+    ps = synth.small_params(13, 6, 3, 2)
+    ctx = gpu_ctx(ps)
+    rng = np.random.default_rng(19)
+    ct1 = dev(synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(3, 2)))
+    ct2 = dev(synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(3, 2)))
+    key = dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)))
+    gs = [synth.galois_element(r, ps.logN) for r in range(1, 12)]
+    rks = [dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))) for _ in gs]
+    pt = dev(synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(len(gs),)))
+    ref = [host(ctx.hmult_relin(ct1, ct2, key)), host(ctx.hrot(ct1, gs[2], key)),
+           host(ctx.hrot_hoisted_mac(ct1[0].contiguous(), gs, rks, pt))]
+    ctx.set_overlap(True)
+    try:
+        for _ in range(3):
+            got = [host(ctx.hmult_relin(ct1, ct2, key)), host(ctx.hrot(ct1, gs[2], key)),
+                   host(ctx.hrot_hoisted_mac(ct1[0].contiguous(), gs, rks, pt))]
+            for a, b in zip(ref, got):
+                assert np.array_equal(a, b)
+    finally:
+        ctx.set_overlap(False)
