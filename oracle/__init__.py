@@ -244,6 +244,82 @@ def hrot_hoisted_mac(ct: np.ndarray, galois: Sequence[int], rks: Sequence[np.nda
     return (out, per) if want_per_rotation else out
 
 
+# ----------------------------------------------------- levels below L, rescale
+def _level_tail(P: Params, level: int):
+    assert 1 <= level <= P.L
+    return (_u32(level),) + P._tail()
+
+
+def rescale(x: np.ndarray, P: Params) -> np.ndarray:
+    """[..., ell, N] eval -> [..., ell-1, N] eval: every polynomial divided by q_{ell-1} (floor type)."""
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    ell = x.shape[-2]
+    assert 2 <= ell <= P.L and x.shape[-1] == P.N
+    flat = x.reshape(-1, ell, P.N)
+    out = np.empty((flat.shape[0], ell - 1, P.N), dtype=np.uint64)
+    for b in range(flat.shape[0]):
+        lib().orc_rescale(_ptr(flat[b]), _ptr(out[b]), _u32(P.logN), _u32(ell), _ptr(P._primes), _ptr(P._psi))
+    return out.reshape(x.shape[:-2] + (ell - 1, P.N))
+
+
+def modup_level(x: np.ndarray, P: Params) -> np.ndarray:
+    """[ell][N] coefficient form -> [ceil(ell/alpha)][ell+K][N] on the basis q_0..q_{ell-1}, p_0..p_{K-1}."""
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    ell = x.shape[0]
+    vp = _arr_u64(P.primes[:ell] + P.primes[P.L:])
+    beta = -(-ell // P.alpha)
+    out = np.empty((beta, ell + P.K, P.N), dtype=np.uint64)
+    lib().orc_modup_level(_ptr(x), _ptr(out), _u32(P.logN), _u32(ell), _u32(P.K), _u32(P.alpha), _ptr(vp))
+    return out
+
+
+def keyswitch_level(d: np.ndarray, key: np.ndarray, P: Params) -> np.ndarray:
+    """d [ell][N] eval, full-level key [dnum][2][L+K][N] -> [2][ell][N] eval."""
+    d = np.ascontiguousarray(d, dtype=np.uint64)
+    key = np.ascontiguousarray(key, dtype=np.uint64)
+    ell = d.shape[0]
+    assert d.shape == (ell, P.N) and key.shape == (P.dnum, 2, P.L + P.K, P.N)
+    out = np.empty((2, ell, P.N), dtype=np.uint64)
+    lib().orc_keyswitch_level(_ptr(d), _ptr(key), _ptr(out), *_level_tail(P, ell))
+    return out
+
+
+def hmult_relin_level(ct1: np.ndarray, ct2: np.ndarray, evk: np.ndarray, P: Params) -> np.ndarray:
+    ct1 = np.ascontiguousarray(ct1, dtype=np.uint64)
+    ct2 = np.ascontiguousarray(ct2, dtype=np.uint64)
+    evk = np.ascontiguousarray(evk, dtype=np.uint64)
+    ell = ct1.shape[1]
+    assert ct1.shape == ct2.shape == (2, ell, P.N) and evk.shape == (P.dnum, 2, P.L + P.K, P.N)
+    out = np.empty((2, ell, P.N), dtype=np.uint64)
+    lib().orc_hmult_relin_level(_ptr(ct1), _ptr(ct2), _ptr(evk), _ptr(out), *_level_tail(P, ell))
+    return out
+
+
+def hrot_level(ct: np.ndarray, g: int, rk: np.ndarray, P: Params) -> np.ndarray:
+    ct = np.ascontiguousarray(ct, dtype=np.uint64)
+    rk = np.ascontiguousarray(rk, dtype=np.uint64)
+    ell = ct.shape[1]
+    assert ct.shape == (2, ell, P.N) and rk.shape == (P.dnum, 2, P.L + P.K, P.N)
+    out = np.empty((2, ell, P.N), dtype=np.uint64)
+    lib().orc_hrot_level(_ptr(ct), _u32(g), _ptr(rk), _ptr(out), *_level_tail(P, ell))
+    return out
+
+
+def hrot_hoisted_mac_level(ct: np.ndarray, galois: Sequence[int], rks: Sequence[np.ndarray], pt: np.ndarray,
+                           P: Params) -> np.ndarray:
+    """ct [2][ell][N]; full-level keys; pt [n_rot][ell][N] -> [2][ell][N]."""
+    ct = np.ascontiguousarray(ct, dtype=np.uint64)
+    pt = np.ascontiguousarray(pt, dtype=np.uint64)
+    n_rot, ell = len(galois), ct.shape[1]
+    assert len(rks) == n_rot and pt.shape == (n_rot, ell, P.N) and ct.shape == (2, ell, P.N)
+    rks = [np.ascontiguousarray(k, dtype=np.uint64) for k in rks]
+    ptrs = (ctypes.c_void_p * n_rot)(*[k.ctypes.data for k in rks])
+    g = np.ascontiguousarray(np.array(galois, dtype=np.uint32))
+    out = np.empty((2, ell, P.N), dtype=np.uint64)
+    lib().orc_hrot_hoisted_mac_level(_ptr(ct), _u32(n_rot), _ptr(g), ptrs, _ptr(pt), _ptr(out), *_level_tail(P, ell))
+    return out
+
+
 # ------------------------------------------------------------- harness helpers
 def lift_signed(v: np.ndarray, primes: Sequence[int]) -> np.ndarray:
     """Small signed coefficients [N] -> canonical residues [len(primes)][N]."""
@@ -301,25 +377,29 @@ def centred_small(x_eval: np.ndarray, P: Params, n_limbs: int) -> np.ndarray:
     return ref
 
 
-def keyswitch_noise(d: np.ndarray, ks: np.ndarray, s_hat: np.ndarray, sp_hat: np.ndarray, P: Params) -> np.ndarray:
-    """E = ks0 + ks1*s - d*s'  over the q-limbs, as centred integer coefficients (must be small)."""
-    q = P.primes[:P.L]
-    t = pointwise("add", ks[0], pointwise("mul", ks[1], s_hat[:P.L], q), q)
-    t = pointwise("sub", t, pointwise("mul", d, sp_hat[:P.L], q), q)
-    return centred_small(t, P, P.L)
+def keyswitch_noise(d: np.ndarray, ks: np.ndarray, s_hat: np.ndarray, sp_hat: np.ndarray, P: Params,
+                    level: Optional[int] = None) -> np.ndarray:
+    """E = ks0 + ks1*s - d*s'  over the (active) q-limbs, as centred integer coefficients (must be small)."""
+    ell = P.L if level is None else level
+    q = P.primes[:ell]
+    t = pointwise("add", ks[0], pointwise("mul", ks[1], s_hat[:ell], q), q)
+    t = pointwise("sub", t, pointwise("mul", d, sp_hat[:ell], q), q)
+    return centred_small(t, P, ell)
 
 
-def keyswitch_noise_bound(P: Params, s_l1: int) -> int:
-    """ceil(dnum * N * alpha * max_j Q_j * 19 / P) + K * (1 + ||s||_1) + 1."""
-    qs, ps = P.primes[:P.L], P.primes[P.L:]
+def keyswitch_noise_bound(P: Params, s_l1: int, level: Optional[int] = None) -> int:
+    """ceil(beta * N * alpha * max_j Q_j * 19 / P) + K * (1 + ||s||_1) + 1 over the beta digits of the level."""
+    ell = P.L if level is None else level
+    qs, ps = P.primes[:ell], P.primes[P.L:]
     Pprod = 1
     for p in ps:
         Pprod *= p
+    beta = -(-ell // P.alpha)
     maxQ = 0
-    for j in range(P.dnum):
+    for j in range(beta):
         Qj = 1
         for q in qs[j * P.alpha:(j + 1) * P.alpha]:
             Qj *= q
         maxQ = max(maxQ, Qj)
-    first = -((-(P.dnum * P.N * P.alpha * maxQ * 19)) // Pprod)
+    first = -((-(beta * P.N * P.alpha * maxQ * 19)) // Pprod)
     return first + P.K * (1 + s_l1) + 1

@@ -411,6 +411,219 @@ void orc_hrot_hoisted_mac(const uint64_t* ct, uint32_t n_rot, const uint32_t* ga
     free(sb);
 }
 
+/* ------------------------------------------------- levels below L and rescale */
+/* A ciphertext at level ell (1 <= ell <= L) lives on the limbs q_0..q_{ell-1}: [2][ell][N].
+ * The paper's CNN consumes one level per multiplication (Section 4: each layer's "multiplicative
+ * level consumption"), i.e. every HMult is followed by a rescale and later operations run on
+ * fewer limbs.  Definitions evaluated here:
+ *
+ * Rescale (floor type, like ModDown): with X the value in [0, Q_ell) of a coefficient and
+ * q = q_{ell-1}, the result is (X - [X]_q) / q modulo Q_{ell-1}, limb by limb
+ *     out_i = (in_i - NTT_i([INTT(in_{ell-1})] mod q_i)) * [q^-1]_{q_i}  mod q_i,   i < ell-1,
+ * [.] the canonical representative in [0, q).
+ *
+ * Key switch at level ell with the full-level key: the extended basis is q_0..q_{ell-1},
+ * p_0..p_{K-1}; digit j holds the active limbs j*alpha .. min((j+1)*alpha, ell)-1 (the last digit
+ * may be partial, and its conversion constants are those of the limbs it really has); there are
+ * beta = ceil(ell/alpha) digits; the key is read on the active limbs and the special limbs of
+ * its first beta digits.  (The gadget of digit j is P on the digit's own limbs and 0 elsewhere,
+ * which stays the CRT idempotent of the digit's active part modulo Q_ell, so the same key works.) */
+
+void orc_rescale(const uint64_t* in, uint64_t* out, uint32_t logN, uint32_t ell, const uint64_t* primes,
+                 const uint64_t* psi) {
+    size_t N = (size_t)1 << logN;
+    uint64_t qlast = primes[ell - 1];
+    uint64_t* x = (uint64_t*)malloc(sizeof(uint64_t) * N);
+    memcpy(x, in + (size_t)(ell - 1) * N, sizeof(uint64_t) * N);
+    orc_intt(x, logN, qlast, psi[ell - 1]);
+#pragma omp parallel for schedule(dynamic)
+    for (long i = 0; i < (long)ell - 1; i++) {
+        uint64_t q = primes[i];
+        uint64_t qinv = orc_invmod(qlast % q, q);
+        uint64_t* r = (uint64_t*)malloc(sizeof(uint64_t) * N);
+        for (size_t n = 0; n < N; n++) r[n] = x[n] % q;
+        orc_ntt(r, logN, q, psi[i]);
+        for (size_t n = 0; n < N; n++)
+            out[(size_t)i * N + n] = orc_mulmod(orc_submod(in[(size_t)i * N + n], r[n], q), qinv, q);
+        free(r);
+    }
+    free(x);
+}
+
+/* ModUp with digits of alpha limbs over ell active limbs (last digit possibly partial).
+ * in: [ell][N] coefficient form; vprimes: the ell + K primes of the extended basis in order;
+ * out: [beta][ell+K][N]. */
+void orc_modup_level(const uint64_t* in, uint64_t* out, uint32_t logN, uint32_t ell, uint32_t K, uint32_t alpha,
+                     const uint64_t* vprimes) {
+    size_t N = (size_t)1 << logN;
+    uint32_t D = ell + K, beta = (ell + alpha - 1) / alpha;
+    long total = (long)beta * D;
+#pragma omp parallel for schedule(dynamic)
+    for (long id = 0; id < total; id++) {
+        uint32_t j = (uint32_t)(id / D), t = (uint32_t)(id % D);
+        uint32_t lo = j * alpha, hi = (j + 1) * alpha < ell ? (j + 1) * alpha : ell;
+        uint64_t* dst = out + ((size_t)j * D + t) * N;
+        if (t >= lo && t < hi) memcpy(dst, in + (size_t)t * N, N * sizeof(uint64_t));
+        else orc_conv(in + (size_t)lo * N, N, N, vprimes + lo, hi - lo, vprimes[t], dst);
+    }
+}
+
+/* Everything a level-ell operation needs: the primes/roots of the extended basis at that level and
+ * the key restricted to it ([beta][2][ell+K][N], gathered from [dnum][2][L+K][N]). */
+typedef struct {
+    orc_params p; /* L = ell, dnum = beta, primes/psi = the arrays below */
+    uint32_t alpha;
+    uint64_t *vprimes, *vpsi;
+} orc_level;
+
+static void level_open(orc_level* v, uint32_t ell, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
+                       const uint64_t* primes, const uint64_t* psi) {
+    uint32_t D = ell + K;
+    v->alpha = L / dnum;
+    v->vprimes = (uint64_t*)malloc(sizeof(uint64_t) * D);
+    v->vpsi = (uint64_t*)malloc(sizeof(uint64_t) * D);
+    for (uint32_t i = 0; i < D; i++) {
+        uint32_t src = i < ell ? i : L + (i - ell);
+        v->vprimes[i] = primes[src];
+        v->vpsi[i] = psi[src];
+    }
+    orc_params p = {logN, ell, K, (ell + v->alpha - 1) / v->alpha, v->vprimes, v->vpsi};
+    v->p = p;
+}
+
+static void level_close(orc_level* v) {
+    free(v->vprimes);
+    free(v->vpsi);
+}
+
+static uint64_t* level_key(const orc_level* v, const uint64_t* key, uint32_t L) {
+    size_t N = (size_t)1 << v->p.logN;
+    uint32_t ell = v->p.L, K = v->p.K, D = ell + K, Dfull = L + K;
+    uint64_t* kc = (uint64_t*)malloc(sizeof(uint64_t) * v->p.dnum * 2 * D * N);
+    for (uint32_t j = 0; j < v->p.dnum; j++)
+        for (uint32_t t = 0; t < 2; t++)
+            for (uint32_t i = 0; i < D; i++) {
+                uint32_t src = i < ell ? i : L + (i - ell);
+                memcpy(kc + (((size_t)j * 2 + t) * D + i) * N, key + (((size_t)j * 2 + t) * Dfull + src) * N,
+                       sizeof(uint64_t) * N);
+            }
+    return kc;
+}
+
+/* dhat = NTT(ModUp(INTT(d))) at a level: d [ell][N] eval -> dhat [beta][ell+K][N] eval. */
+static void decompose_extend_level(const uint64_t* d, uint64_t* dhat, const orc_level* v) {
+    const orc_params* p = &v->p;
+    size_t N = (size_t)1 << p->logN;
+    uint32_t D = p->L + p->K;
+    uint64_t* x = (uint64_t*)malloc(sizeof(uint64_t) * p->L * N);
+    memcpy(x, d, sizeof(uint64_t) * p->L * N);
+    limbs_ntt(x, p, 0, p->L, 1, p->L, 1);
+    orc_modup_level(x, dhat, p->logN, p->L, p->K, v->alpha, p->primes);
+    limbs_ntt(dhat, p, 0, D, p->dnum, D, 0);
+    free(x);
+}
+
+/* d [ell][N] eval, key [dnum][2][L+K][N] eval (full level) -> out [2][ell][N] eval. */
+void orc_keyswitch_level(const uint64_t* d, const uint64_t* key, uint64_t* out, uint32_t ell, uint32_t logN,
+                         uint32_t L, uint32_t K, uint32_t dnum, const uint64_t* primes, const uint64_t* psi) {
+    orc_level v;
+    level_open(&v, ell, logN, L, K, dnum, primes, psi);
+    size_t N = (size_t)1 << logN;
+    uint32_t D = ell + K;
+    uint64_t* kc = level_key(&v, key, L);
+    uint64_t* dhat = (uint64_t*)malloc(sizeof(uint64_t) * v.p.dnum * D * N);
+    uint64_t* cp = (uint64_t*)malloc(sizeof(uint64_t) * 2 * D * N);
+    decompose_extend_level(d, dhat, &v);
+    key_inner_product(dhat, kc, cp, &v.p, 1);
+    moddown_eval(cp, out, &v.p);
+    free(dhat);
+    free(cp);
+    free(kc);
+    level_close(&v);
+}
+
+/* HMult + relinearisation of two level-ell ciphertexts [2][ell][N] (no rescale). */
+void orc_hmult_relin_level(const uint64_t* ct1, const uint64_t* ct2, const uint64_t* evk, uint64_t* out,
+                           uint32_t ell, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
+                           const uint64_t* primes, const uint64_t* psi) {
+    size_t N = (size_t)1 << logN;
+    uint64_t* d2 = (uint64_t*)malloc(sizeof(uint64_t) * ell * N);
+    uint64_t* ks = (uint64_t*)malloc(sizeof(uint64_t) * 2 * ell * N);
+    for (uint32_t i = 0; i < ell; i++) {
+        const uint64_t *a1 = ct1 + ((size_t)ell + i) * N, *a2 = ct2 + ((size_t)ell + i) * N;
+        for (size_t n = 0; n < N; n++) d2[(size_t)i * N + n] = orc_mulmod(a1[n], a2[n], primes[i]);
+    }
+    orc_keyswitch_level(d2, evk, ks, ell, logN, L, K, dnum, primes, psi);
+    for (uint32_t i = 0; i < ell; i++) {
+        uint64_t m = primes[i];
+        const uint64_t *b1 = ct1 + (size_t)i * N, *a1 = ct1 + ((size_t)ell + i) * N;
+        const uint64_t *b2 = ct2 + (size_t)i * N, *a2 = ct2 + ((size_t)ell + i) * N;
+        for (size_t n = 0; n < N; n++) {
+            uint64_t d0 = orc_mulmod(b1[n], b2[n], m);
+            uint64_t d1 = orc_addmod(orc_mulmod(a1[n], b2[n], m), orc_mulmod(a2[n], b1[n], m), m);
+            out[(size_t)i * N + n] = orc_addmod(d0, ks[(size_t)i * N + n], m);
+            out[((size_t)ell + i) * N + n] = orc_addmod(d1, ks[((size_t)ell + i) * N + n], m);
+        }
+    }
+    free(d2);
+    free(ks);
+}
+
+/* Rotation of a level-ell ciphertext: (sigma_g(b) + ks0, ks1), ks = KeySwitch_ell(sigma_g(a), rk_g). */
+void orc_hrot_level(const uint64_t* ct, uint32_t g, const uint64_t* rk, uint64_t* out, uint32_t ell,
+                    uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum, const uint64_t* primes,
+                    const uint64_t* psi) {
+    size_t N = (size_t)1 << logN;
+    uint64_t* rot = (uint64_t*)malloc(sizeof(uint64_t) * 2 * ell * N);
+    for (uint32_t i = 0; i < 2 * ell; i++) orc_automorph_eval(ct + (size_t)i * N, rot + (size_t)i * N, logN, g);
+    orc_keyswitch_level(rot + (size_t)ell * N, rk, out, ell, logN, L, K, dnum, primes, psi);
+    for (uint32_t i = 0; i < ell; i++)
+        for (size_t n = 0; n < N; n++)
+            out[(size_t)i * N + n] = orc_addmod(out[(size_t)i * N + n], rot[(size_t)i * N + n], primes[i]);
+    free(rot);
+}
+
+/* Hoisted rotate-multiply-accumulate at level ell: as orc_hrot_hoisted_mac on the level's basis.
+ * ct [2][ell][N], pt [n_rot][ell][N], out [2][ell][N]; keys are full-level. */
+void orc_hrot_hoisted_mac_level(const uint64_t* ct, uint32_t n_rot, const uint32_t* galois,
+                                const uint64_t* const* rk, const uint64_t* pt, uint64_t* out, uint32_t ell,
+                                uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum, const uint64_t* primes,
+                                const uint64_t* psi) {
+    orc_level v;
+    level_open(&v, ell, logN, L, K, dnum, primes, psi);
+    size_t N = (size_t)1 << logN;
+    uint32_t D = ell + K;
+    uint64_t* dhat = (uint64_t*)malloc(sizeof(uint64_t) * v.p.dnum * D * N);
+    uint64_t* cp = (uint64_t*)malloc(sizeof(uint64_t) * 2 * D * N);
+    uint64_t* ks = (uint64_t*)malloc(sizeof(uint64_t) * 2 * ell * N);
+    uint64_t* sb = (uint64_t*)malloc(sizeof(uint64_t) * N);
+    decompose_extend_level(ct + (size_t)ell * N, dhat, &v);
+    memset(out, 0, sizeof(uint64_t) * 2 * ell * N);
+    for (uint32_t r = 0; r < n_rot; r++) {
+        uint64_t* kc = level_key(&v, rk[r], L);
+        key_inner_product(dhat, kc, cp, &v.p, galois[r]);
+        moddown_eval(cp, ks, &v.p);
+        free(kc);
+        for (uint32_t i = 0; i < ell; i++) {
+            uint64_t m = primes[i];
+            orc_automorph_eval(ct + (size_t)i * N, sb, logN, galois[r]);
+            const uint64_t* ptr = pt + ((size_t)r * ell + i) * N;
+            for (size_t n = 0; n < N; n++) {
+                uint64_t r0 = orc_addmod(sb[n], ks[(size_t)i * N + n], m);
+                uint64_t r1 = ks[((size_t)ell + i) * N + n];
+                out[(size_t)i * N + n] = orc_addmod(out[(size_t)i * N + n], orc_mulmod(ptr[n], r0, m), m);
+                out[((size_t)ell + i) * N + n] =
+                    orc_addmod(out[((size_t)ell + i) * N + n], orc_mulmod(ptr[n], r1, m), m);
+            }
+        }
+    }
+    free(dhat);
+    free(cp);
+    free(ks);
+    free(sb);
+    level_close(&v);
+}
+
 /* --------------------------------------------------------- harness: key gen */
 /* Switching key from s to s' under the RNS gadget (P on digit j's own limbs):
  *   key[j][1][i] = a_j[i]                                   (uniform, evaluation form, given)

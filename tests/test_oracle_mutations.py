@@ -26,6 +26,14 @@ MUTATIONS = [
     ("limbs_ntt(cp, p, 0, D, 2, D, 1);", "limbs_ntt(cp, p, 0, D, 2, D, 0);", "test_keyswitch_decrypt_and_bound"),
     ("uint64_t n_inv = orc_invmod(N % m, m);", "uint64_t n_inv = 1;", "test_ntt_equals_bigint_definition"),
     ("memcpy(dst, in + (size_t)t * N, N * sizeof(uint64_t));", "memset(dst, 0, N * sizeof(uint64_t));", "test_modup_vs_bigint_crt"),
+    ("out[(size_t)i * N + n] = orc_mulmod(orc_submod(in[(size_t)i * N + n], r[n], q), qinv, q);", "out[(size_t)i * N + n] = orc_mulmod(orc_addmod(in[(size_t)i * N + n], r[n], q), qinv, q);", "test_rescale_vs_bigint_floor_division"),
+    ("uint64_t qinv = orc_invmod(qlast % q, q);", "uint64_t qinv = orc_invmod(q % qlast, qlast);", "test_rescale_decryption_identity"),
+    ("for (size_t n = 0; n < N; n++) r[n] = x[n] % q;", "for (size_t n = 0; n < N; n++) r[n] = (x[n] + qlast / 2) % q;", "test_rescale_vs_bigint_floor_division"),
+    ("else orc_conv(in + (size_t)lo * N, N, N, vprimes + lo, hi - lo, vprimes[t], dst);", "else orc_conv(in + (size_t)lo * N, N, N, vprimes + lo, alpha, vprimes[t], dst);", "test_modup_level_vs_bigint_crt"),
+    ("        uint32_t src = i < ell ? i : L + (i - ell);\n        v->vprimes[i] = primes[src];", "        uint32_t src = i;\n        v->vprimes[i] = primes[src];", "test_keyswitch_level_decrypt_and_bound"),
+    ("key_inner_product(dhat, kc, cp, &v.p, 1);", "key_inner_product(dhat, key, cp, &v.p, 1);", "test_keyswitch_level_decrypt_and_bound"),
+    ("orc_keyswitch_level(rot + (size_t)ell * N, rk, out", "orc_keyswitch_level(ct + (size_t)ell * N, rk, out", "test_hmult_hrot_level_decrypt"),
+    ("        key_inner_product(dhat, kc, cp, &v.p, galois[r]);", "        key_inner_product(dhat, kc, cp, &v.p, 1);", "test_hoisted_mac_level"),
 ]
 
 

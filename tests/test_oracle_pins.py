@@ -456,3 +456,192 @@ def test_config0_exact_shape_hmult(orc):
     bound = orc.keyswitch_noise_bound(P, int(np.abs(s).sum()))
     assert bound <= 116736 + 4097 + 1
     assert 0 < np.abs(E).max() <= bound
+
+
+# ------------------------------------------------------ levels below L and rescale
+def _negacyclic_int(a, b):
+    """Integer negacyclic product (no modulus) of two integer lists."""
+    n = len(a)
+    out = [0] * n
+    for i, ai in enumerate(a):
+        if ai == 0:
+            continue
+        for j, bj in enumerate(b):
+            k = i + j
+            if k < n:
+                out[k] += ai * bj
+            else:
+                out[k - n] -= ai * bj
+    return out
+
+
+def _coeff(orc, x, P, n_limbs):
+    return orc.ntt_batch(np.ascontiguousarray(x[:n_limbs]), P, 0, inverse=True)
+
+
+@pytest.mark.parametrize("ell", [5, 4, 2])
+def test_rescale_vs_bigint_floor_division(orc, ell):
+    ps = _small_set(4, 5, 1, 5, 30, 31)
+    P = orc.Params.from_set(ps)
+    q = list(ps.q_primes[:ell])
+    rng = np.random.default_rng(71 + ell)
+    c = synth.uniform_residues(rng, q, ps.N)
+    Qe = 1
+    for m in q:
+        Qe *= m
+    big = (123456789123456789 * 987654321987 % (Qe // q[-1])) * q[-1]       # coefficient 0: exact multiple
+    small = q[-1] - 1                                                         # coefficient 1: below the divisor
+    for i, m in enumerate(q):
+        c[i, 0], c[i, 1] = big % m, small % m
+    x = orc.ntt_batch(c, P, 0)
+    out = orc.rescale(x, P)
+    assert out.shape == (ell - 1, ps.N)
+    oc = _coeff(orc, out, P, ell - 1)
+    for n in range(ps.N):
+        X, _ = crt([c[i, n] for i in range(ell)], q)
+        want = (X - X % q[-1]) // q[-1]
+        assert [int(oc[i, n]) for i in range(ell - 1)] == [want % m for m in q[:-1]]
+    assert all(int(oc[i, 0]) == (big // q[-1]) % q[i] for i in range(ell - 1))
+    assert all(int(oc[i, 1]) == 0 for i in range(ell - 1))
+
+
+def test_rescale_decryption_identity(orc):
+    """q_last * Dec(rescale(ct)) - Dec(ct) = -([b]_q + [a]_q * s) exactly (mod Q_ell), [.]_q in [0, q_last)."""
+    ps = _small_set(5, 4, 2, 2, 24, 26)
+    P, rng, s, s_hat = _setup(orc, ps, 73)
+    for ell in (4, 3):
+        q = list(ps.q_primes[:ell])
+        ct = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        out = orc.rescale(ct, P)
+        assert out.shape == (2, ell - 1, ps.N)
+
+        def dec(c, n_l):
+            qq = q[:n_l]
+            return orc.pointwise("add", c[0], orc.pointwise("mul", c[1], s_hat[:n_l], qq), qq)
+
+        m_c = _coeff(orc, dec(ct, ell), P, ell)
+        m2_c = _coeff(orc, dec(out, ell - 1), P, ell - 1)
+        r0 = orc.intt(ct[0, ell - 1], ps.logN, q[-1], P.psi[ell - 1]).tolist()
+        r1 = orc.intt(ct[1, ell - 1], ps.logN, q[-1], P.psi[ell - 1]).tolist()
+        r1s = _negacyclic_int([int(v) for v in r1], [int(v) for v in s])
+        Qe = 1
+        for m in q:
+            Qe *= m
+        worst = 0
+        for n in range(ps.N):
+            M, _ = crt([m_c[i, n] for i in range(ell)], q)
+            M2, _ = crt([m2_c[i, n] for i in range(ell - 1)], q[:-1])
+            E = (q[-1] * M2 - M) % Qe
+            E = E - Qe if E > Qe // 2 else E
+            assert E == -(int(r0[n]) + r1s[n])
+            worst = max(worst, abs(E))
+        assert worst <= q[-1] * (1 + int(np.abs(s).sum())) < Qe // 4
+
+
+LEVEL_SHAPES = [(5, 6, 2, 3, 20, 22), (5, 6, 3, 2, 20, 24), (4, 8, 2, 4, 49, 59)]
+
+
+@pytest.mark.parametrize("shape", LEVEL_SHAPES)
+def test_modup_level_vs_bigint_crt(orc, shape):
+    ps = _small_set(*shape)
+    P = orc.Params.from_set(ps)
+    rng = np.random.default_rng(75)
+    a = ps.alpha
+    for ell in range(1, ps.L + 1):
+        x = synth.uniform_residues(rng, ps.q_primes[:ell], ps.N)
+        out = orc.modup_level(x, P)
+        beta = -(-ell // a)
+        basis = list(ps.q_primes[:ell]) + list(ps.p_primes)
+        assert out.shape == (beta, ell + ps.K, ps.N)
+        for j in range(beta):
+            lo, hi = j * a, min((j + 1) * a, ell)
+            digit = basis[lo:hi]
+            for n in range(0, ps.N, 3):
+                xi, Qj = crt([x[i, n] for i in range(lo, hi)], digit)
+                us = set()
+                for t, b in enumerate(basis):
+                    if lo <= t < hi:
+                        assert out[j, t, n] == x[t, n]
+                        continue
+                    us.add((int(out[j, t, n]) - xi) * pow(Qj, -1, b) % b)
+                assert len(us) == 1 and 0 <= us.pop() < hi - lo
+        if ell == ps.L:
+            assert np.array_equal(out, orc.modup(x, P))
+
+
+@pytest.mark.parametrize("shape", LEVEL_SHAPES[:2] + [(6, 4, 4, 1, 30, 31)])
+def test_keyswitch_level_decrypt_and_bound(orc, shape):
+    ps = _small_set(*shape)
+    P, rng, s, s_hat = _setup(orc, ps, 77)
+    s2_hat = orc.pointwise("mul", s_hat, s_hat, ps.primes)
+    key, _ = _keys(orc, ps, P, rng, s2_hat, s_hat)
+    for ell in range(1, ps.L + 1):
+        d = synth.uniform_residues(rng, ps.q_primes[:ell], ps.N)
+        ks = orc.keyswitch_level(d, key, P)
+        assert ks.shape == (2, ell, ps.N)
+        E = orc.keyswitch_noise(d, ks, s_hat, s2_hat, P, level=ell)
+        bound = orc.keyswitch_noise_bound(P, int(np.abs(s).sum()), level=ell)
+        assert np.abs(E).max() <= bound
+        assert ell == 1 or bound < min(ps.q_primes) // 4
+        if ell == ps.L:
+            assert np.array_equal(ks, orc.keyswitch(d, key, P))     # the full level is the special case
+
+
+@pytest.mark.parametrize("shape", LEVEL_SHAPES[:2])
+def test_hmult_hrot_level_decrypt(orc, shape):
+    ps = _small_set(*shape)
+    P, rng, s, s_hat = _setup(orc, ps, 79)
+    s2_hat = orc.pointwise("mul", s_hat, s_hat, ps.primes)
+    evk, _ = _keys(orc, ps, P, rng, s2_hat, s_hat)
+    g = synth.galois_element(3, ps.logN)
+    sg_hat = orc.automorph_limbs(s_hat, P, 0, g, True)
+    rk, _ = _keys(orc, ps, P, rng, sg_hat, s_hat)
+    for ell in (ps.L, ps.L - 1, ps.alpha + 1, 1):
+        q = list(ps.q_primes[:ell])
+        sq = s_hat[:ell]
+
+        def dec(c):
+            return orc.pointwise("add", c[0], orc.pointwise("mul", c[1], sq, q), q)
+
+        bound = orc.keyswitch_noise_bound(P, int(np.abs(s).sum()), level=ell)
+        ct1 = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        ct2 = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        out = orc.hmult_relin_level(ct1, ct2, evk, P)
+        E = orc.centred_small(orc.pointwise("sub", dec(out), orc.pointwise("mul", dec(ct1), dec(ct2), q), q), P, ell)
+        assert np.abs(E).max() <= bound
+        rot = orc.hrot_level(ct1, g, rk, P)
+        E = orc.centred_small(orc.pointwise("sub", dec(rot), orc.automorph_limbs(dec(ct1), P, 0, g, True), q), P, ell)
+        assert np.abs(E).max() <= bound
+        if ell == ps.L:
+            assert np.array_equal(out, orc.hmult_relin(ct1, ct2, evk, P))
+            assert np.array_equal(rot, orc.hrot(ct1, g, rk, P))
+
+
+def test_hoisted_mac_level(orc):
+    ps = _small_set(5, 6, 2, 3, 20, 22)
+    P, rng, s, s_hat = _setup(orc, ps, 81)
+    rots = [1, -2, 4]
+    gs = [synth.galois_element(r, ps.logN) for r in rots]
+    rks = [_keys(orc, ps, P, rng, orc.automorph_limbs(s_hat, P, 0, g, True), s_hat)[0] for g in gs]
+    for ell in (ps.L, 5, 3):
+        q = list(ps.q_primes[:ell])
+        sq = s_hat[:ell]
+
+        def dec(c):
+            return orc.pointwise("add", c[0], orc.pointwise("mul", c[1], sq, q), q)
+
+        ct = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        pt = synth.uniform_residues(rng, q, ps.N, lead=(len(rots),))
+        out = orc.hrot_hoisted_mac_level(ct, gs, rks, pt, P)
+        if ell == ps.L:
+            assert np.array_equal(out, orc.hrot_hoisted_mac(ct, gs, rks, pt, P))
+        bound = orc.keyswitch_noise_bound(P, int(np.abs(s).sum()), level=ell)
+        acc = np.zeros_like(out)
+        for r, g in enumerate(gs):
+            unit = np.ones((1, ell, ps.N), dtype=np.uint64)            # NTT(1): rotation r alone, unscaled
+            one = orc.hrot_hoisted_mac_level(ct, [g], [rks[r]], unit, P)
+            E = orc.centred_small(orc.pointwise("sub", dec(one), orc.automorph_limbs(dec(ct), P, 0, g, True), q), P, ell)
+            assert np.abs(E).max() <= bound
+            for t in range(2):
+                acc[t] = orc.pointwise("add", acc[t], orc.pointwise("mul", pt[r], one[t], q), q)
+        assert np.array_equal(acc, out)                               # linear in the per-rotation results
