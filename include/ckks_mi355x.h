@@ -60,6 +60,7 @@ extern "C" {
 #define CKKS_OP_HMULT_RELIN 5
 #define CKKS_OP_HROT 6
 #define CKKS_OP_HROT_HOISTED_MAC 7
+#define CKKS_OP_RESCALE 8
 
 /* limits of this build */
 #define CKKS_MIN_LOGN 12
@@ -102,6 +103,10 @@ uint64_t ckks_ctx_psi(const ckks_ctx* ctx, uint32_t i);
 /* Bytes of workspace the given op needs for `batch_or_nrot` (batch size; number of rotations
  * for CKKS_OP_HROT_HOISTED_MAC).  0 for ops that need none. */
 int ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t batch_or_nrot, size_t* bytes);
+
+/* The same for an operation at `level` active q-limbs (1 <= level <= L; for CKKS_OP_RESCALE the level of
+ * the input).  Never more than the full-level figure, so one full-level workspace serves every level. */
+int ckks_workspace_bytes_at(const ckks_ctx* ctx, int op, uint32_t level, uint32_t batch_or_nrot, size_t* bytes);
 
 /*
  * Forward negacyclic NTT, in place, batched (Section 2: "NTT", a major kernel).
@@ -180,6 +185,41 @@ int ckks_hrot(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t galois, const uint64
 int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, const uint32_t* h_galois,
                           const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt, uint64_t* d_out, void* d_ws,
                           size_t ws_bytes, void* stream);
+
+/*
+ * Levels below L (Section 4: every layer of the CNN consumes multiplicative levels, so most
+ * operations run on ciphertexts that have already lost limbs).  A ciphertext at `level` = ell
+ * (1 <= ell <= L) holds the limbs q_0..q_{ell-1}: [batch][2][ell][N].  The `_at` calls are the
+ * operations above on that basis with the SAME full-level keys [dnum][2][L+K][N]:
+ *   extended basis q_0..q_{ell-1}, p_0..p_{K-1};  ceil(ell/alpha) digits, digit j = limbs
+ *   j*alpha .. min((j+1)*alpha, ell)-1, the last digit possibly partial (its conversion constants are
+ *   those of the limbs it really has);  the key is read on the active and the special limbs of these
+ *   digits only;  ModDown divides by P as before.
+ * level = L gives exactly ckks_keyswitch / ckks_hmult_relin / ckks_hrot / ckks_hrot_hoisted_mac.
+ * Shapes: as the full-level calls with L replaced by ell everywhere except in the keys
+ * (d_pt : [n_rot][ell][N]).  level outside 1..L: CKKS_EINVAL.
+ */
+int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_d, const uint64_t* d_key, uint64_t* d_out,
+                      uint32_t batch, void* d_ws, size_t ws_bytes, void* stream);
+int ckks_hmult_relin_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct1, const uint64_t* d_ct2,
+                        const uint64_t* d_evk, uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes,
+                        void* stream);
+int ckks_hrot_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t galois, const uint64_t* d_rk,
+                 uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes, void* stream);
+int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
+                             const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt,
+                             uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Rescale (the step that consumes a level, Section 4): divide by the last active prime q = q_{level-1}
+ * and drop its limb, floor type like ModDown.  With X in [0, Q_level) the value of a coefficient the
+ * result is (X - [X]_q) / q modulo Q_{level-1}, [.]_q the canonical representative in [0, q):
+ *   out_i = (in_i - NTT_i([INTT(in_{level-1})]_q mod q_i)) * [q^-1]_{q_i}  mod q_i,   i < level-1.
+ *   d_ct : [batch][2][level][N] eval;  d_out : [batch][2][level-1][N] eval (must not overlap d_ct);
+ *   2 <= level <= L.  Works on contexts without special primes as well.
+ */
+int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch, void* d_ws,
+                 size_t ws_bytes, void* stream);
 
 /*
  * Optional two-stream execution inside one call.  Off by default: every kernel of a call runs on the

@@ -17,13 +17,16 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libckks_mi355x.so")
 
 CKKS_OK, CKKS_EINVAL, CKKS_EUNSUPPORTED, CKKS_EHIP, CKKS_ENOMEM = 0, -1, -2, -3, -4
-OP_NTT, OP_MODUP, OP_MODDOWN, OP_AUTOMORPH, OP_KEYSWITCH, OP_HMULT_RELIN, OP_HROT, OP_HROT_HOISTED_MAC = range(8)
+(OP_NTT, OP_MODUP, OP_MODDOWN, OP_AUTOMORPH, OP_KEYSWITCH, OP_HMULT_RELIN, OP_HROT, OP_HROT_HOISTED_MAC,
+ OP_RESCALE) = range(9)
 
 EXPORTS = (
     "ckks_table_bytes", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error", "ckks_ctx_psi",
     "ckks_workspace_bytes", "ckks_ntt", "ckks_intt", "ckks_modup", "ckks_moddown", "ckks_automorph",
     "ckks_keyswitch", "ckks_hmult_relin", "ckks_hrot", "ckks_hrot_hoisted_mac",
     "ckks_profile_enable", "ckks_profile_read", "ckks_set_overlap",
+    "ckks_workspace_bytes_at", "ckks_keyswitch_at", "ckks_hmult_relin_at", "ckks_hrot_at",
+    "ckks_hrot_hoisted_mac_at", "ckks_rescale",
 )
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
@@ -64,6 +67,12 @@ def load() -> ctypes.CDLL:
     lib.ckks_hrot.argtypes = [_vp, _vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_hoisted_mac.argtypes = [_vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_set_overlap.argtypes = [_vp, _int]
+    lib.ckks_workspace_bytes_at.argtypes = [_vp, _int, _u32, _u32, ctypes.POINTER(_sz)]
+    lib.ckks_keyswitch_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
+    lib.ckks_hmult_relin_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
+    lib.ckks_hrot_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
+    lib.ckks_hrot_hoisted_mac_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.ckks_rescale.argtypes = [_vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_profile_enable.argtypes = [_vp, _int]
     lib.ckks_profile_read.argtypes = [_vp, _u32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_u64),
                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_u64)]
@@ -130,8 +139,14 @@ class Context:
         self._check(load().ckks_workspace_bytes(self.handle, op, batch_or_nrot, ctypes.byref(n)))
         return n.value
 
-    def workspace(self, op: int, batch_or_nrot: int) -> torch.Tensor:
-        need = self.workspace_bytes(op, batch_or_nrot)
+    def workspace_bytes_at(self, op: int, level: int, batch_or_nrot: int) -> int:
+        n = _sz()
+        self._check(load().ckks_workspace_bytes_at(self.handle, op, level, batch_or_nrot, ctypes.byref(n)))
+        return n.value
+
+    def workspace(self, op: int, batch_or_nrot: int, level: Optional[int] = None) -> torch.Tensor:
+        need = (self.workspace_bytes(op, batch_or_nrot) if level is None
+                else self.workspace_bytes_at(op, level, batch_or_nrot))
         if self._ws is None or self._ws.numel() < need:
             self._ws = None
             self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
@@ -230,4 +245,60 @@ class Context:
         self._check(load().ckks_hrot_hoisted_mac(self.handle, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
                                                  ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out),
                                                  ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    # -- levels below L: tensors carry `level` limbs instead of L; keys stay full-level ----------
+    def keyswitch_at(self, level: int, d: torch.Tensor, key: torch.Tensor,
+                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        batch = d.numel() // (level * self.N)
+        if out is None:
+            out = torch.empty(tuple(d.shape[:-2]) + (2, level, self.N), dtype=d.dtype, device=d.device)
+        ws = self.workspace(OP_KEYSWITCH, batch, level)
+        self._check(load().ckks_keyswitch_at(self.handle, level, _dev_ptr(d), _dev_ptr(key), _dev_ptr(out), batch,
+                                             ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def hmult_relin_at(self, level: int, ct1: torch.Tensor, ct2: torch.Tensor, evk: torch.Tensor,
+                       out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        batch = ct1.numel() // (2 * level * self.N)
+        if out is None:
+            out = torch.empty_like(ct1)
+        ws = self.workspace(OP_HMULT_RELIN, batch, level)
+        self._check(load().ckks_hmult_relin_at(self.handle, level, _dev_ptr(ct1), _dev_ptr(ct2), _dev_ptr(evk),
+                                               _dev_ptr(out), batch, ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def hrot_at(self, level: int, ct: torch.Tensor, galois: int, rk: torch.Tensor,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        batch = ct.numel() // (2 * level * self.N)
+        if out is None:
+            out = torch.empty_like(ct)
+        ws = self.workspace(OP_HROT, batch, level)
+        self._check(load().ckks_hrot_at(self.handle, level, _dev_ptr(ct), galois, _dev_ptr(rk), _dev_ptr(out), batch,
+                                        ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def hrot_hoisted_mac_at(self, level: int, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor],
+                            pt: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        n_rot = len(galois)
+        if len(rks) != n_rot or pt.numel() != n_rot * level * self.N:
+            raise ValueError("one key and one plaintext per rotation")
+        if out is None:
+            out = torch.empty_like(ct)
+        g = (ctypes.c_uint32 * n_rot)(*[int(x) for x in galois])
+        ptrs = (ctypes.c_void_p * n_rot)(*[_dev_ptr(k) for k in rks])
+        ws = self.workspace(OP_HROT_HOISTED_MAC, n_rot, level)
+        self._check(load().ckks_hrot_hoisted_mac_at(self.handle, level, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
+                                                    ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out),
+                                                    ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def rescale(self, level: int, ct: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """ct [batch...][2][level][N] -> [batch...][2][level-1][N]."""
+        batch = ct.numel() // (2 * level * self.N)
+        if out is None:
+            out = torch.empty(tuple(ct.shape[:-2]) + (level - 1, self.N), dtype=ct.dtype, device=ct.device)
+        ws = self.workspace(OP_RESCALE, batch, level)
+        self._check(load().ckks_rescale(self.handle, level, _dev_ptr(ct), _dev_ptr(out), batch,
+                                        ws.data_ptr(), ws.numel(), _stream()))
         return out

@@ -85,36 +85,78 @@ static u64 h_min_root(u64 m, u32 logN) {
 // ------------------------------------------------------------------------------ context
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-struct TableLayout {
-    size_t tw_int, tw_fp, pc, sc_plain, sc_up, sc_dn, up_hatinv, dn_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, dn_chat_fp, dn_fp_ok, pinv, total;
+// The caller's table buffer holds one block shared by every level (per-prime twiddles and
+// constants over the whole chain), one block of conversion constants per level ell = 1..L (basis
+// q_0..q_{ell-1}, p_0..p_{K-1}) and one small block per rescale step ell -> ell-1 (ell = 2..L).
+struct SharedLayout {
+    size_t tw_int, tw_fp, pc, sc_plain, sc_dn, dn_hatinv, end;
+};
+struct LevelLayout {
+    size_t sc_up, up_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, dn_chat_fp, dn_fp_ok, pinv, end;
+};
+struct RescaleLayout {
+    size_t sc_dn, dn_chat, dn_chat_fp, dn_fp_ok, pinv, end;
 };
 
-static TableLayout table_layout(u32 logN, u32 L, u32 K) {
-    const size_t N = (size_t)1 << logN, D = L + K, K1 = K ? K : 1;
-    TableLayout t;
-    size_t o = 0;
-    auto take = [&o](size_t bytes) {
+struct Taker {
+    size_t o;
+    size_t take(size_t bytes) {
         size_t at = o;
         o += align256(bytes);
         return at;
-    };
-    t.tw_int = take(D * 4 * N * sizeof(u64));
-    t.tw_fp = take(D * 2 * N * sizeof(double));
-    t.pc = take(D * sizeof(PrimeConst));
-    t.sc_plain = take(D * sizeof(InvScale));
-    t.sc_up = take(L * sizeof(InvScale));
-    t.sc_dn = take(K1 * sizeof(InvScale));
-    t.up_hatinv = take(L * 2 * sizeof(u64));
-    t.dn_hatinv = take(K1 * 2 * sizeof(u64));
-    t.up_chat = take(L * D * sizeof(u64));
-    t.up_chat_fp = take(L * D * sizeof(double));
-    t.up_fp_ok = take(L * D * sizeof(u32));
-    t.dn_chat = take(K1 * L * sizeof(u64));
-    t.dn_chat_fp = take(K1 * L * 2 * sizeof(double));
-    t.dn_fp_ok = take(L * sizeof(u32));
-    t.pinv = take(L * sizeof(PinvConst));
-    t.total = o;
-    return t;
+    }
+};
+
+static SharedLayout shared_layout(u32 logN, u32 L, u32 K) {
+    const size_t N = (size_t)1 << logN, D = L + K, K1 = K ? K : 1;
+    Taker t{0};
+    SharedLayout l;
+    l.tw_int = t.take(D * 4 * N * sizeof(u64));
+    l.tw_fp = t.take(D * 2 * N * sizeof(double));
+    l.pc = t.take(D * sizeof(PrimeConst));
+    l.sc_plain = t.take(D * sizeof(InvScale));
+    l.sc_dn = t.take(K1 * sizeof(InvScale));
+    l.dn_hatinv = t.take(K1 * 2 * sizeof(u64));
+    l.end = t.o;
+    return l;
+}
+
+static LevelLayout level_layout(size_t base, u32 ell, u32 K, u32 alpha) {
+    const size_t D = ell + K, K1 = K ? K : 1, beta = (ell + alpha - 1) / alpha;
+    Taker t{base};
+    LevelLayout l;
+    l.sc_up = t.take(ell * sizeof(InvScale));
+    l.up_hatinv = t.take(ell * 2 * sizeof(u64));
+    l.up_chat = t.take(ell * D * sizeof(u64));
+    l.up_chat_fp = t.take(ell * D * sizeof(double));
+    l.up_fp_ok = t.take(beta * D * sizeof(u32));
+    l.dn_chat = t.take(K1 * ell * sizeof(u64));
+    l.dn_chat_fp = t.take(K1 * ell * 2 * sizeof(double));
+    l.dn_fp_ok = t.take(ell * sizeof(u32));
+    l.pinv = t.take(ell * sizeof(PinvConst));
+    l.end = t.o;
+    return l;
+}
+
+// rescale from ell limbs to ell - 1: one source prime (q_{ell-1}), targets q_0..q_{ell-2}
+static RescaleLayout rescale_layout(size_t base, u32 ell) {
+    const size_t T = ell - 1;
+    Taker t{base};
+    RescaleLayout l;
+    l.sc_dn = t.take(sizeof(InvScale));
+    l.dn_chat = t.take(T * sizeof(u64));
+    l.dn_chat_fp = t.take(T * 2 * sizeof(double));
+    l.dn_fp_ok = t.take(T * sizeof(u32));
+    l.pinv = t.take(T * sizeof(PinvConst));
+    l.end = t.o;
+    return l;
+}
+
+static size_t table_total(u32 logN, u32 L, u32 K, u32 dnum) {
+    size_t o = shared_layout(logN, L, K).end;
+    for (u32 ell = 1; ell <= L; ell++) o = level_layout(o, ell, K, L / dnum).end;
+    for (u32 ell = 2; ell <= L; ell++) o = rescale_layout(o, ell).end;
+    return o;
 }
 
 // per-kernel timing: when enabled, every launch is bracketed by two HIP events recorded on the
@@ -154,14 +196,28 @@ struct SideStream {
     size_t next = 0;
 };
 
+struct Shared {
+    std::string err;
+    ProfState prof;
+    SideStream side;
+};
+
+// One level of the context: everything a launch needs.  `primes` is the level's basis in limb order.
+struct View {
+    u32 logN = 0, L = 0, K = 0, dnum = 0, alpha = 0, D = 0;
+    std::vector<u64> primes;
+    Tables tb;
+    bool mixed_classes = false;  // both FpAr and IntAr primes present
+    Shared* sh = nullptr;
+};
+
 struct ckks_ctx {
     u32 logN, L, K, dnum, alpha, D;
     std::vector<u64> primes, psi;
-    Tables tb;
-    bool mixed_classes = false;  // both FpAr and IntAr primes present
-    mutable std::string err;
-    mutable ProfState prof;
-    mutable SideStream side;
+    std::vector<View> level;    // [ell], 1 <= ell <= L: key switching at ell active q-limbs; level[L] is the full one
+    std::vector<View> rescale;  // [ell], 2 <= ell <= L: the step from ell limbs to ell - 1 (K = 1, "special" prime q_{ell-1})
+    mutable Shared sh;
+    const View* full() const { return &level[L]; }
 };
 
 static hipEvent_t side_event(SideStream& sd) {
@@ -175,8 +231,8 @@ static hipEvent_t side_event(SideStream& sd) {
 }
 
 // From here on IntAr launches go to the side stream, ordered after everything enqueued on s so far.
-static void fork_side(const ckks_ctx* c, hipStream_t s) {
-    SideStream& sd = c->side;
+static void fork_side(const View* c, hipStream_t s) {
+    SideStream& sd = c->sh->side;
     if (!sd.enabled || !c->mixed_classes || sd.active) return;
     if (!sd.stream && hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) != hipSuccess) {
         sd.stream = nullptr;
@@ -193,8 +249,8 @@ static void fork_side(const ckks_ctx* c, hipStream_t s) {
 }
 
 // s waits for everything the side stream was given; IntAr launches return to s.
-static void join_side(const ckks_ctx* c, hipStream_t s) {
-    SideStream& sd = c->side;
+static void join_side(const View* c, hipStream_t s) {
+    SideStream& sd = c->sh->side;
     if (!sd.active) return;
     sd.active = false;
     hipEvent_t e = side_event(sd);
@@ -221,9 +277,9 @@ struct ProfScope {
     hipStream_t s;
     ProfRec rec;
     // alg_limbs: limbs (N words each) the launch must read plus write once
-    ProfScope(const ckks_ctx* c, const std::string& name, u64 alg_limbs, hipStream_t stream) : s(stream) {
-        if (!c->prof.on) return;
-        p = &c->prof;
+    ProfScope(const View* c, const std::string& name, u64 alg_limbs, hipStream_t stream) : s(stream) {
+        if (!c->sh->prof.on) return;
+        p = &c->sh->prof;
         rec.kind = p->kind_of(name);
         p->kinds[rec.kind].launches++;
         p->kinds[rec.kind].bytes += (alg_limbs * sizeof(u64)) << c->logN;
@@ -253,7 +309,11 @@ static void prof_drain(ProfState& p) {
 }
 
 static int fail(const ckks_ctx* c, int code, const char* msg) {
-    if (c) c->err = msg;
+    if (c) c->sh.err = msg;
+    return code;
+}
+static int fail(const View* c, int code, const char* msg) {
+    if (c) c->sh->err = msg;
     return code;
 }
 
@@ -271,7 +331,7 @@ extern "C" int ckks_table_bytes(uint32_t logN, uint32_t L, uint32_t K, uint32_t 
     if (!bytes) return CKKS_EINVAL;
     int rc = check_shape(logN, L, K, dnum);
     if (rc) return rc;
-    *bytes = table_layout(logN, L, K).total;
+    *bytes = table_total(logN, L, K, dnum);
     return CKKS_OK;
 }
 
@@ -286,6 +346,14 @@ static InvScale make_scale(u64 factor, u64 ninv, u64 wlast, u64 m, bool fp) {
     return s;
 }
 
+// (prod of src[k], k != skip) mod m
+static u64 prod_except(const std::vector<u64>& src, size_t skip, u64 m) {
+    u64 r = 1 % m;
+    for (size_t k = 0; k < src.size(); k++)
+        if (k != skip) r = h_mulmod(r, src[k] % m, m);
+    return r;
+}
+
 extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
                                const uint64_t* h_primes, const uint64_t* h_psi, void* d_tables, size_t table_bytes,
                                void* stream) {
@@ -295,8 +363,9 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     int rc = check_shape(logN, L, K, dnum);
     if (rc) return rc;
     if (((uintptr_t)d_tables) & 255) return CKKS_EINVAL;
-    const TableLayout lay = table_layout(logN, L, K);
-    if (table_bytes < lay.total) return CKKS_ENOMEM;
+    const size_t total = table_total(logN, L, K, dnum);
+    if (table_bytes < total) return CKKS_ENOMEM;
+    const SharedLayout lay = shared_layout(logN, L, K);
     const u32 D = L + K, alpha = L / dnum;
     const size_t N = (size_t)1 << logN;
     for (u32 i = 0; i < D; i++) {
@@ -313,28 +382,18 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     c->logN = logN, c->L = L, c->K = K, c->dnum = dnum, c->alpha = alpha, c->D = D;
     c->primes.assign(h_primes, h_primes + D);
     c->psi.resize(D);
-    {
-        bool any_fp = false, any_int = false;
-        for (u32 i = 0; i < D; i++) (h_primes[i] < CKKS_FP_PRIME_LIMIT ? any_fp : any_int) = true;
-        c->mixed_classes = any_fp && any_int;
-    }
+    const std::vector<u64> specials(c->primes.begin() + L, c->primes.end());
 
-    std::vector<unsigned char> host(lay.total, 0);
-    u64* tw = (u64*)(host.data() + lay.tw_int);
-    double* twf = (double*)(host.data() + lay.tw_fp);
-    PrimeConst* pc = (PrimeConst*)(host.data() + lay.pc);
-    InvScale* sc_plain = (InvScale*)(host.data() + lay.sc_plain);
-    InvScale* sc_up = (InvScale*)(host.data() + lay.sc_up);
-    InvScale* sc_dn = (InvScale*)(host.data() + lay.sc_dn);
-    u64* up_hatinv = (u64*)(host.data() + lay.up_hatinv);
-    u64* dn_hatinv = (u64*)(host.data() + lay.dn_hatinv);
-    u64* up_chat = (u64*)(host.data() + lay.up_chat);
-    double* up_chat_fp = (double*)(host.data() + lay.up_chat_fp);
-    u32* up_fp_ok = (u32*)(host.data() + lay.up_fp_ok);
-    u64* dn_chat = (u64*)(host.data() + lay.dn_chat);
-    double* dn_chat_fp = (double*)(host.data() + lay.dn_chat_fp);
-    u32* dn_fp_ok = (u32*)(host.data() + lay.dn_fp_ok);
-    PinvConst* pinv = (PinvConst*)(host.data() + lay.pinv);
+    std::vector<unsigned char> host(total, 0);
+    unsigned char* hb = host.data();
+    unsigned char* dbase = (unsigned char*)d_tables;
+    // ---- block shared by every level
+    u64* tw = (u64*)(hb + lay.tw_int);
+    double* twf = (double*)(hb + lay.tw_fp);
+    PrimeConst* pc = (PrimeConst*)(hb + lay.pc);
+    InvScale* sc_plain = (InvScale*)(hb + lay.sc_plain);
+    InvScale* sc_dn = (InvScale*)(hb + lay.sc_dn);
+    u64* dn_hatinv = (u64*)(hb + lay.dn_hatinv);
     std::vector<u64> pw(N), ninv(D), wlast(D);
     for (u32 i = 0; i < D; i++) {
         const u64 m = c->primes[i];
@@ -369,122 +428,174 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         wlast[i] = fw[2 * N + 1];
         sc_plain[i] = make_scale(1, ninv[i], wlast[i], m, fp);
     }
-    // ModUp constants per digit
-    for (u32 j = 0; j < dnum; j++) {
-        for (u32 ii = 0; ii < alpha; ii++) {
-            const u32 i = j * alpha + ii;
-            const u64 qi = c->primes[i];
-            u64 hat = 1;
-            for (u32 kk = 0; kk < alpha; kk++)
-                if (kk != ii) hat = h_mulmod(hat, c->primes[j * alpha + kk] % qi, qi);
-            const u64 hinv = h_invmod(hat, qi);
-            up_hatinv[2 * i] = hinv;
-            up_hatinv[2 * i + 1] = h_shoup(hinv, qi);
-            sc_up[i] = make_scale(hinv, ninv[i], wlast[i], qi, pc[i].fp != 0);
-            for (u32 t = 0; t < D; t++) {
-                if (t >= j * alpha && t < (j + 1) * alpha) continue;
-                const u64 mt = c->primes[t];
-                u64 hb = 1;
-                for (u32 kk = 0; kk < alpha; kk++)
-                    if (kk != ii) hb = h_mulmod(hb, c->primes[j * alpha + kk] % mt, mt);
-                up_chat[(size_t)i * D + t] = h_mont(hb, mt);
-                up_chat_fp[(size_t)i * D + t] = pc[t].fp ? (double)hb : 0.0;
-            }
-        }
-        for (u32 t = 0; t < D; t++) {
-            bool ok = pc[t].fp != 0;
-            for (u32 ii = 0; ii < alpha; ii++) {
-                const u32 i = j * alpha + ii;
-                ok = ok && pc[i].fp && c->primes[i] <= 2 * c->primes[t];
-            }
-            up_fp_ok[(size_t)j * D + t] = ok ? 1 : 0;
-        }
-    }
-    // ModDown constants
-    for (u32 k = 0; k < K; k++) {
-        const u64 pk = c->primes[L + k];
-        u64 hat = 1;
-        for (u32 kk = 0; kk < K; kk++)
-            if (kk != k) hat = h_mulmod(hat, c->primes[L + kk] % pk, pk);
-        const u64 hinv = h_invmod(hat, pk);
+    for (u32 k = 0; k < K; k++) {  // sources of ModDown: the special limbs, the same at every level
+        const u64 pk = specials[k];
+        const u64 hinv = h_invmod(prod_except(specials, k, pk), pk);
         dn_hatinv[2 * k] = hinv;
         dn_hatinv[2 * k + 1] = h_shoup(hinv, pk);
         sc_dn[k] = make_scale(hinv, ninv[L + k], wlast[L + k], pk, pc[L + k].fp != 0);
-        for (u32 i = 0; i < L; i++) {
-            const u64 qi = c->primes[i];
-            u64 hb = 1;
-            for (u32 kk = 0; kk < K; kk++)
-                if (kk != k) hb = h_mulmod(hb, c->primes[L + kk] % qi, qi);
-            dn_chat[(size_t)k * L + i] = h_mont(hb, qi);
-            // chat_stride of the conversion kernel is L entries, i.e. 2L doubles: index (k*L + i)*2
-            dn_chat_fp[((size_t)k * L + i) * 2] = pc[i].fp ? (double)hb : 0.0;
-            dn_chat_fp[((size_t)k * L + i) * 2 + 1] = pc[i].fp ? (double)h_mulmod(hb, (1ull << 30) % qi, qi) : 0.0;
-        }
     }
-    for (u32 i = 0; i < L; i++) dn_fp_ok[i] = (pc[i].fp && c->primes[i] >= (1ull << 28)) ? 1 : 0;
-    for (u32 i = 0; i < L; i++) {
-        const u64 qi = c->primes[i];
-        u64 P = 1;
-        for (u32 k = 0; k < K; k++) P = h_mulmod(P, c->primes[L + k] % qi, qi);
-        const u64 pi = h_invmod(P, qi);
-        pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
+    auto shared_tables = [&](Tables& tb) {
+        tb.tw_int = (const u64*)(dbase + lay.tw_int);
+        tb.tw_fp = (const double*)(dbase + lay.tw_fp);
+        tb.pc = (const PrimeConst*)(dbase + lay.pc);
+        tb.sc_plain = (const InvScale*)(dbase + lay.sc_plain);
+        tb.sc_dn = (const InvScale*)(dbase + lay.sc_dn);
+        tb.dn_hatinv = (const u64*)(dbase + lay.dn_hatinv);
+        tb.logN = logN;
+    };
+    auto classes_mixed = [](const std::vector<u64>& pr) {
+        bool any_fp = false, any_int = false;
+        for (u64 m : pr) (m < CKKS_FP_PRIME_LIMIT ? any_fp : any_int) = true;
+        return any_fp && any_int;
+    };
+
+    // ---- one block per level: limb index i of the level is prime ph(i) of the chain
+    size_t off = lay.end;
+    c->level.resize(L + 1);
+    for (u32 ell = 1; ell <= L; ell++) {
+        const LevelLayout ll = level_layout(off, ell, K, alpha);
+        off = ll.end;
+        const u32 Dl = ell + K, beta = (ell + alpha - 1) / alpha;
+        auto ph = [&](u32 i) { return i < ell ? i : L + (i - ell); };
+        InvScale* sc_up = (InvScale*)(hb + ll.sc_up);
+        u64* up_hatinv = (u64*)(hb + ll.up_hatinv);
+        u64* up_chat = (u64*)(hb + ll.up_chat);
+        double* up_chat_fp = (double*)(hb + ll.up_chat_fp);
+        u32* up_fp_ok = (u32*)(hb + ll.up_fp_ok);
+        u64* dn_chat = (u64*)(hb + ll.dn_chat);
+        double* dn_chat_fp = (double*)(hb + ll.dn_chat_fp);
+        u32* dn_fp_ok = (u32*)(hb + ll.dn_fp_ok);
+        PinvConst* pinv = (PinvConst*)(hb + ll.pinv);
+        for (u32 j = 0; j < beta; j++) {  // ModUp constants of digit j = limbs [lo, hi)
+            const u32 lo = j * alpha, hi = (j + 1) * alpha < ell ? (j + 1) * alpha : ell;
+            const std::vector<u64> digit(c->primes.begin() + lo, c->primes.begin() + hi);
+            for (u32 i = lo; i < hi; i++) {
+                const u64 qi = c->primes[i];
+                const u64 hinv = h_invmod(prod_except(digit, i - lo, qi), qi);
+                up_hatinv[2 * i] = hinv;
+                up_hatinv[2 * i + 1] = h_shoup(hinv, qi);
+                sc_up[i] = make_scale(hinv, ninv[i], wlast[i], qi, pc[i].fp != 0);
+                for (u32 t = 0; t < Dl; t++) {
+                    if (t >= lo && t < hi) continue;
+                    const u64 mt = c->primes[ph(t)];
+                    const u64 hatb = prod_except(digit, i - lo, mt);
+                    up_chat[(size_t)i * Dl + t] = h_mont(hatb, mt);
+                    up_chat_fp[(size_t)i * Dl + t] = pc[ph(t)].fp ? (double)hatb : 0.0;
+                }
+            }
+            for (u32 t = 0; t < Dl; t++) {
+                bool ok = pc[ph(t)].fp != 0;
+                for (u32 i = lo; i < hi; i++) ok = ok && pc[i].fp && c->primes[i] <= 2 * c->primes[ph(t)];
+                up_fp_ok[(size_t)j * Dl + t] = ok ? 1 : 0;
+            }
+        }
+        for (u32 i = 0; i < ell; i++) {  // ModDown constants of target q_i
+            const u64 qi = c->primes[i];
+            for (u32 k = 0; k < K; k++) {
+                const u64 hatb = prod_except(specials, k, qi);
+                dn_chat[(size_t)k * ell + i] = h_mont(hatb, qi);
+                // the conversion kernel strides by ell entries, i.e. 2*ell doubles: index (k*ell + i)*2
+                dn_chat_fp[((size_t)k * ell + i) * 2] = pc[i].fp ? (double)hatb : 0.0;
+                dn_chat_fp[((size_t)k * ell + i) * 2 + 1] = pc[i].fp ? (double)h_mulmod(hatb, (1ull << 30) % qi, qi) : 0.0;
+            }
+            dn_fp_ok[i] = (pc[i].fp && qi >= (1ull << 28)) ? 1 : 0;
+            const u64 pi = h_invmod(prod_except(specials, specials.size(), qi), qi);
+            pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
+        }
+        View& v = c->level[ell];
+        v.logN = logN, v.L = ell, v.K = K, v.dnum = beta, v.alpha = alpha, v.D = Dl, v.sh = &c->sh;
+        v.primes.resize(Dl);
+        for (u32 i = 0; i < Dl; i++) v.primes[i] = c->primes[ph(i)];
+        v.mixed_classes = classes_mixed(v.primes);
+        Tables& tb = v.tb;
+        shared_tables(tb);
+        tb.sc_up = (const InvScale*)(dbase + ll.sc_up);
+        tb.up_hatinv = (const u64*)(dbase + ll.up_hatinv);
+        tb.up_chat = (const u64*)(dbase + ll.up_chat);
+        tb.up_chat_fp = (const double*)(dbase + ll.up_chat_fp);
+        tb.up_fp_ok = (const u32*)(dbase + ll.up_fp_ok);
+        tb.dn_chat = (const u64*)(dbase + ll.dn_chat);
+        tb.dn_chat_fp = (const double*)(dbase + ll.dn_chat_fp);
+        tb.dn_fp_ok = (const u32*)(dbase + ll.dn_fp_ok);
+        tb.pinv = (const PinvConst*)(dbase + ll.pinv);
+        tb.L = ell, tb.K = K, tb.dnum = beta, tb.alpha = alpha, tb.D = Dl, tb.Lfull = L;
+    }
+    // ---- one block per rescale step: a ModDown whose only "special" prime is q_{ell-1}
+    c->rescale.resize(L + 1);
+    for (u32 ell = 2; ell <= L; ell++) {
+        const RescaleLayout rl = rescale_layout(off, ell);
+        off = rl.end;
+        const u32 T = ell - 1;
+        const u64 ql = c->primes[T];
+        InvScale* rsc = (InvScale*)(hb + rl.sc_dn);
+        u64* dn_chat = (u64*)(hb + rl.dn_chat);
+        double* dn_chat_fp = (double*)(hb + rl.dn_chat_fp);
+        u32* dn_fp_ok = (u32*)(hb + rl.dn_fp_ok);
+        PinvConst* pinv = (PinvConst*)(hb + rl.pinv);
+        rsc[0] = make_scale(1, ninv[T], wlast[T], ql, pc[T].fp != 0);
+        for (u32 i = 0; i < T; i++) {
+            const u64 qi = c->primes[i];
+            dn_chat[i] = h_mont(1, qi);
+            dn_chat_fp[2 * i] = pc[i].fp ? 1.0 : 0.0;
+            dn_chat_fp[2 * i + 1] = pc[i].fp ? (double)((1ull << 30) % qi) : 0.0;
+            dn_fp_ok[i] = (pc[i].fp && qi >= (1ull << 28)) ? 1 : 0;
+            const u64 pi = h_invmod(ql % qi, qi);
+            pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
+        }
+        View& v = c->rescale[ell];
+        v.logN = logN, v.L = T, v.K = 1, v.dnum = 1, v.alpha = T, v.D = ell, v.sh = &c->sh;
+        v.primes.assign(c->primes.begin(), c->primes.begin() + ell);
+        v.mixed_classes = classes_mixed(v.primes);
+        Tables& tb = v.tb;
+        memset(&tb, 0, sizeof(tb));
+        shared_tables(tb);
+        tb.sc_dn = (const InvScale*)(dbase + rl.sc_dn);
+        tb.dn_hatinv = nullptr;
+        tb.dn_chat = (const u64*)(dbase + rl.dn_chat);
+        tb.dn_chat_fp = (const double*)(dbase + rl.dn_chat_fp);
+        tb.dn_fp_ok = (const u32*)(dbase + rl.dn_fp_ok);
+        tb.pinv = (const PinvConst*)(dbase + rl.pinv);
+        tb.L = T, tb.K = 1, tb.dnum = 1, tb.alpha = T, tb.D = ell, tb.Lfull = T;  // phys() is the identity here
     }
 
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = hipMemcpyAsync(d_tables, host.data(), lay.total, hipMemcpyHostToDevice, s);
+    hipError_t e = hipMemcpyAsync(d_tables, host.data(), total, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         delete c;
         return CKKS_EHIP;
     }
-    unsigned char* dbase = (unsigned char*)d_tables;
-    Tables& tb = c->tb;
-    tb.tw_int = (const u64*)(dbase + lay.tw_int);
-    tb.tw_fp = (const double*)(dbase + lay.tw_fp);
-    tb.pc = (const PrimeConst*)(dbase + lay.pc);
-    tb.sc_plain = (const InvScale*)(dbase + lay.sc_plain);
-    tb.sc_up = (const InvScale*)(dbase + lay.sc_up);
-    tb.sc_dn = (const InvScale*)(dbase + lay.sc_dn);
-    tb.up_hatinv = (const u64*)(dbase + lay.up_hatinv);
-    tb.dn_hatinv = (const u64*)(dbase + lay.dn_hatinv);
-    tb.up_chat = (const u64*)(dbase + lay.up_chat);
-    tb.up_chat_fp = (const double*)(dbase + lay.up_chat_fp);
-    tb.up_fp_ok = (const u32*)(dbase + lay.up_fp_ok);
-    tb.dn_chat = (const u64*)(dbase + lay.dn_chat);
-    tb.dn_chat_fp = (const double*)(dbase + lay.dn_chat_fp);
-    tb.dn_fp_ok = (const u32*)(dbase + lay.dn_fp_ok);
-    tb.pinv = (const PinvConst*)(dbase + lay.pinv);
-    tb.logN = logN, tb.L = L, tb.K = K, tb.dnum = dnum, tb.alpha = alpha, tb.D = D;
     *out = c;
     return CKKS_OK;
 }
 
 extern "C" void ckks_ctx_destroy(ckks_ctx* ctx) {
     if (!ctx) return;
-    prof_drain(ctx->prof);
-    for (hipEvent_t e : ctx->prof.pool) (void)hipEventDestroy(e);
-    if (ctx->side.stream) {
-        (void)hipStreamSynchronize(ctx->side.stream);
-        (void)hipStreamDestroy(ctx->side.stream);
+    prof_drain(ctx->sh.prof);
+    for (hipEvent_t e : ctx->sh.prof.pool) (void)hipEventDestroy(e);
+    if (ctx->sh.side.stream) {
+        (void)hipStreamSynchronize(ctx->sh.side.stream);
+        (void)hipStreamDestroy(ctx->sh.side.stream);
     }
-    for (hipEvent_t e : ctx->side.events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->sh.side.events) (void)hipEventDestroy(e);
     delete ctx;
 }
 
 extern "C" int ckks_profile_enable(ckks_ctx* ctx, int on) {
     if (!ctx) return CKKS_EINVAL;
-    prof_drain(ctx->prof);
-    ctx->prof.on = on != 0;
-    ctx->prof.kinds.clear();
+    prof_drain(ctx->sh.prof);
+    ctx->sh.prof.on = on != 0;
+    ctx->sh.prof.kinds.clear();
     return CKKS_OK;
 }
 
 extern "C" int ckks_profile_read(ckks_ctx* ctx, uint32_t index, const char** name, uint64_t* launches,
                                  double* total_ms, uint64_t* alg_bytes) {
     if (!ctx) return CKKS_EINVAL;
-    prof_drain(ctx->prof);
-    if (index >= ctx->prof.kinds.size()) return CKKS_EINVAL;
-    const ProfKindStat& k = ctx->prof.kinds[index];
+    prof_drain(ctx->sh.prof);
+    if (index >= ctx->sh.prof.kinds.size()) return CKKS_EINVAL;
+    const ProfKindStat& k = ctx->sh.prof.kinds[index];
     if (name) *name = k.name.c_str();
     if (launches) *launches = k.launches;
     if (total_ms) *total_ms = k.ms;
@@ -494,22 +605,22 @@ extern "C" int ckks_profile_read(ckks_ctx* ctx, uint32_t index, const char** nam
 
 extern "C" int ckks_set_overlap(ckks_ctx* ctx, int on) {
     if (!ctx) return CKKS_EINVAL;
-    if (ctx->side.active) return fail(ctx, CKKS_EINVAL, "cannot change overlap inside an operation");
-    ctx->side.enabled = on != 0;
+    if (ctx->sh.side.active) return fail(ctx, CKKS_EINVAL, "cannot change overlap inside an operation");
+    ctx->sh.side.enabled = on != 0;
     return CKKS_OK;
 }
 
-extern "C" const char* ckks_last_error(const ckks_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+extern "C" const char* ckks_last_error(const ckks_ctx* ctx) { return ctx ? ctx->sh.err.c_str() : "null context"; }
 
 extern "C" uint64_t ckks_ctx_psi(const ckks_ctx* ctx, uint32_t i) { return (ctx && i < ctx->D) ? ctx->psi[i] : 0; }
 
 // ----------------------------------------------------------------------------- launches
 static inline bool misaligned(const void* p, size_t a) { return ((uintptr_t)p & (a - 1)) != 0; }
 
-static int hip_check(const ckks_ctx* c, const char* what) {
+static int hip_check(const View* c, const char* what) {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
-        c->err = std::string(what) + ": " + hipGetErrorString(e);
+        c->sh->err = std::string(what) + ": " + hipGetErrorString(e);
         return CKKS_EHIP;
     }
     return CKKS_OK;
@@ -517,14 +628,14 @@ static int hip_check(const ckks_ctx* c, const char* what) {
 
 // grid of an XCD-aware launch: groups padded to a multiple of 8, times the instances per group
 static inline u32 xcd_grid(u32 groups, u32 inst) { return ((groups + 7) / 8) * 8 * inst; }
-static inline u32 tiles_of(const ckks_ctx* c) { return (1u << (c->logN - 8)) / 16; }
+static inline u32 tiles_of(const View* c) { return (1u << (c->logN - 8)) / 16; }
 
 // Maximal runs of consecutive primes [lo, hi) that share an arithmetic (FpAr / IntAr).
 struct ClassRun {
     u32 first, count;
     bool fp;
 };
-static std::vector<ClassRun> class_runs(const ckks_ctx* c, u32 lo, u32 hi) {
+static std::vector<ClassRun> class_runs(const View* c, u32 lo, u32 hi) {
     std::vector<ClassRun> r;
     for (u32 i = lo; i < hi; i++) {
         const bool fp = c->primes[i] < CKKS_FP_PRIME_LIMIT;
@@ -538,7 +649,7 @@ static std::vector<ClassRun> class_runs(const ckks_ctx* c, u32 lo, u32 hi) {
 //   template <class AR, int A> static void go(grid, stream, args, tables, run)   the launch
 //   static std::string name(const char* ar, int A)                               the profiler's kernel name
 template <class L, class ArgT>
-static void dispatch_kernel(const ckks_ctx* c, bool fp, dim3 grid, hipStream_t s, const ArgT& a, LimbRun run) {
+static void dispatch_kernel(const View* c, bool fp, dim3 grid, hipStream_t s, const ArgT& a, LimbRun run) {
 #define CKKS_CASE_A(AV)                                               \
     case AV:                                                          \
         if (fp) L::template go<FpAr, AV>(grid, s, a, c->tb, run);     \
@@ -563,7 +674,7 @@ static std::string kname(const char* base, const char* ar, int A, const char* ta
 // (conversion targets): groups = groups_n, instances = the run's limbs in blocks of inst_n.  alg(first, count) gives
 // the algorithmic limbs (read + written once) of the launch covering primes [first, first+count).
 template <class L, class ArgT, class AlgFn>
-static void launch_runs(const ckks_ctx* c, u32 lo, u32 hi, u32 limb_base, bool by_limb, u32 groups_n, u32 inst_n,
+static void launch_runs(const View* c, u32 lo, u32 hi, u32 limb_base, bool by_limb, u32 groups_n, u32 inst_n,
                         const ArgT& a, hipStream_t s, AlgFn alg) {
     for (const ClassRun& cr : class_runs(c, lo, hi)) {
         const LimbRun run = {cr.first - limb_base, cr.count};
@@ -572,9 +683,9 @@ static void launch_runs(const ckks_ctx* c, u32 lo, u32 hi, u32 limb_base, bool b
         const u32 tbn = cr.fp ? (inst_n & 0xffff) : (inst_n >> 16);
         const dim3 grid(by_limb ? xcd_grid(cr.count * groups_n, inst_n)
                                 : xcd_grid(groups_n, (cr.count + tbn - 1) / tbn));
-        hipStream_t rs = (!cr.fp && c->side.active) ? c->side.stream : s;
-        ProfScope ps(c, c->prof.on ? L::name(cr.fp ? "FpAr" : "IntAr", (int)c->logN - 8) : std::string(),
-                     c->prof.on ? alg(cr.first, cr.count) : 0, rs);
+        hipStream_t rs = (!cr.fp && c->sh->side.active) ? c->sh->side.stream : s;
+        ProfScope ps(c, c->sh->prof.on ? L::name(cr.fp ? "FpAr" : "IntAr", (int)c->logN - 8) : std::string(),
+                     c->sh->prof.on ? alg(cr.first, cr.count) : 0, rs);
         dispatch_kernel<L>(c, cr.fp, grid, rs, a, run);
     }
 }
@@ -658,21 +769,21 @@ struct KsFinalL {
 };
 
 template <int LOAD>
-static void launch_inv_contig(const ckks_ctx* c, const InvContigArgs& a, hipStream_t s) {
+static void launch_inv_contig(const View* c, const InvContigArgs& a, hipStream_t s) {
     const u32 pb = a.sel.prime_base;
     const u64 per = (u64)a.sel.n_inst * (LOAD == INV_TENSOR ? 3 : 2);
     launch_runs<InvContigL<LOAD>>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s,
                                   [per](u32, u32 n) { return per * n; });
 }
 
-static void launch_inv_strided(const ckks_ctx* c, const InvStridedArgs& a, hipStream_t s) {
+static void launch_inv_strided(const View* c, const InvStridedArgs& a, hipStream_t s) {
     const u32 pb = a.sel.prime_base;
     const u64 per = (u64)a.sel.n_inst * 2;
     launch_runs<InvStridedL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s,
                              [per](u32, u32 n) { return per * n; });
 }
 
-static void launch_fwd_strided(const ckks_ctx* c, const FwdStridedArgs& a, hipStream_t s) {
+static void launch_fwd_strided(const View* c, const FwdStridedArgs& a, hipStream_t s) {
     const u32 pb = a.sel.prime_base;
     const u64 per = (u64)a.sel.n_inst * 2;
     launch_runs<FwdStridedL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s,
@@ -680,7 +791,7 @@ static void launch_fwd_strided(const ckks_ctx* c, const FwdStridedArgs& a, hipSt
 }
 
 template <int DIR>
-static void launch_conv(const ckks_ctx* c, const ConvArgs& a, hipStream_t s) {
+static void launch_conv(const View* c, const ConvArgs& a, hipStream_t s) {
     const u64 outer = a.groups_outer;
     if (DIR == CONV_UP) {  // groups = (batch, digit, tile); instances = blocks of the run's target primes
         launch_runs<ConvL<DIR>>(c, 0, c->D, 0, false, a.groups_outer * c->dnum * tiles_of(c),
@@ -697,7 +808,7 @@ static void launch_conv(const ckks_ctx* c, const ConvArgs& a, hipStream_t s) {
     }
 }
 
-static void launch_fwd_contig(const ckks_ctx* c, const FwdContigArgs& a, hipStream_t s) {
+static void launch_fwd_contig(const View* c, const FwdContigArgs& a, hipStream_t s) {
     const u32 pb = a.sel.prime_base;
     const u64 per = (u64)a.sel.n_inst * 2;
     launch_runs<FwdContigL>(c, pb, pb + a.sel.n_l, pb, true, tiles_of(c), a.sel.n_inst, a, s,
@@ -705,7 +816,7 @@ static void launch_fwd_contig(const ckks_ctx* c, const FwdContigArgs& a, hipStre
 }
 
 template <int OWN, bool HOISTED>
-static void launch_ks_inner(const ckks_ctx* c, const InnerArgs& a, hipStream_t s) {
+static void launch_ks_inner(const View* c, const InnerArgs& a, hipStream_t s) {
     const u64 n_inst = a.n_inst;
     launch_runs<KsInnerL<OWN, HOISTED>>(
         c, 0, c->D, 0, true, tiles_of(c), a.n_inst, a, s, [c, n_inst](u32 first, u32 n) {
@@ -722,7 +833,7 @@ static void launch_ks_inner(const ckks_ctx* c, const InnerArgs& a, hipStream_t s
 }
 
 template <int MODE>
-static void launch_ks_final(const ckks_ctx* c, const FinalArgs& a, hipStream_t s) {
+static void launch_ks_final(const View* c, const FinalArgs& a, hipStream_t s) {
     u64 per;  // algorithmic limbs per q-limb
     if (MODE == FIN_HOISTED) per = (u64)a.n_rot * (2 + 2 + 1 + 1) + (2 + (a.accumulate ? 2 : 0));
     else per = (u64)a.n_inst * (6 + (MODE == FIN_HMULT ? 4 : MODE == FIN_HROT ? 1 : 0));
@@ -730,12 +841,12 @@ static void launch_ks_final(const ckks_ctx* c, const FinalArgs& a, hipStream_t s
 }
 
 template <int AL>
-static void launch_modup_a(const ckks_ctx* c, const u64* in, u64* out, u32 batch, hipStream_t s) {
+static void launch_modup_a(const View* c, const u64* in, u64* out, u32 batch, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, c->dnum, batch), block(256);
     ProfScope ps(c, std::string("modup_kernel"), (u64)batch * (2 * (u64)c->L + (u64)c->dnum * (c->D - c->alpha)), s);
     hipLaunchKernelGGL(modup_kernel<AL>, grid, block, 0, s, in, out, c->tb);
 }
-static void launch_modup(const ckks_ctx* c, const u64* in, u64* out, u32 batch, hipStream_t s) {
+static void launch_modup(const View* c, const u64* in, u64* out, u32 batch, hipStream_t s) {
     switch (c->alpha) {
         case 1: launch_modup_a<1>(c, in, out, batch, s); break;
         case 2: launch_modup_a<2>(c, in, out, batch, s); break;
@@ -749,12 +860,12 @@ static void launch_modup(const ckks_ctx* c, const u64* in, u64* out, u32 batch, 
 }
 
 template <int KK>
-static void launch_moddown_k(const ckks_ctx* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
+static void launch_moddown_k(const View* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
     const dim3 grid((1u << c->logN) / 256, groups), block(256);
     ProfScope ps(c, std::string("moddown_kernel"), (u64)groups * (c->K + 2 * (u64)c->L), s);
     hipLaunchKernelGGL(moddown_kernel<KK>, grid, block, 0, s, in, out, c->tb);
 }
-static void launch_moddown(const ckks_ctx* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
+static void launch_moddown(const View* c, const u64* in, u64* out, u32 groups, hipStream_t s) {
     switch (c->K) {
         case 1: launch_moddown_k<1>(c, in, out, groups, s); break;
         case 2: launch_moddown_k<2>(c, in, out, groups, s); break;
@@ -777,12 +888,12 @@ struct Workspace {
     u64 *x, *dt, *cq, *cp, *cv;
 };
 
-static size_t ks_workspace_words(const ckks_ctx* c, u32 xg, u32 dg, u32 cg) {
+static size_t ks_workspace_words(const View* c, u32 xg, u32 dg, u32 cg) {
     const size_t N = (size_t)1 << c->logN;
     return ((size_t)xg * c->L + (size_t)dg * c->dnum * c->D + (size_t)cg * 2 * (2 * (size_t)c->L + c->K)) * N;
 }
 
-static Workspace carve(const ckks_ctx* c, void* ws, u32 xg, u32 dg, u32 cg) {
+static Workspace carve(const View* c, void* ws, u32 xg, u32 dg, u32 cg) {
     const size_t N = (size_t)1 << c->logN;
     Workspace w;
     w.x = (u64*)ws;
@@ -793,9 +904,8 @@ static Workspace carve(const ckks_ctx* c, void* ws, u32 xg, u32 dg, u32 cg) {
     return w;
 }
 
-extern "C" int ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t batch_or_nrot, size_t* bytes) {
-    if (!ctx || !bytes) return CKKS_EINVAL;
-    if (batch_or_nrot == 0) return fail(ctx, CKKS_EINVAL, "batch must be positive");
+static int view_workspace_bytes(const View* v, int op, uint32_t batch_or_nrot, size_t* bytes) {
+    if (batch_or_nrot == 0) return fail(v, CKKS_EINVAL, "batch must be positive");
     switch (op) {
         case CKKS_OP_NTT:
         case CKKS_OP_MODUP:
@@ -804,21 +914,46 @@ extern "C" int ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t batch_
         case CKKS_OP_KEYSWITCH:
         case CKKS_OP_HMULT_RELIN:
         case CKKS_OP_HROT:
-            if (ctx->K == 0) return fail(ctx, CKKS_EUNSUPPORTED, "context has no special primes");
-            *bytes = ks_workspace_words(ctx, batch_or_nrot, batch_or_nrot, batch_or_nrot) * sizeof(u64);
+            if (v->K == 0) return fail(v, CKKS_EUNSUPPORTED, "context has no special primes");
+            *bytes = ks_workspace_words(v, batch_or_nrot, batch_or_nrot, batch_or_nrot) * sizeof(u64);
             return CKKS_OK;
         case CKKS_OP_HROT_HOISTED_MAC: {
-            if (ctx->K == 0) return fail(ctx, CKKS_EUNSUPPORTED, "context has no special primes");
+            if (v->K == 0) return fail(v, CKKS_EUNSUPPORTED, "context has no special primes");
             const u32 chunk = batch_or_nrot < CKKS_ROT_CHUNK ? batch_or_nrot : CKKS_ROT_CHUNK;
-            *bytes = ks_workspace_words(ctx, 1, 1, chunk) * sizeof(u64);
+            *bytes = ks_workspace_words(v, 1, 1, chunk) * sizeof(u64);
             return CKKS_OK;
         }
+        case CKKS_OP_RESCALE:  // last-limb coefficients [b][2][N] + converted part [b][2][ell-1][N]
+            if (v->L < 2) return fail(v, CKKS_EINVAL, "rescale needs at least two limbs");
+            *bytes = ((size_t)batch_or_nrot * 2 * v->L * sizeof(u64)) << v->logN;
+            return CKKS_OK;
     }
-    return fail(ctx, CKKS_EINVAL, "unknown op selector");
+    return fail(v, CKKS_EINVAL, "unknown op selector");
+}
+
+static const View* view_at(const ckks_ctx* ctx, uint32_t level) {
+    if (level == 0 || level > ctx->L) {
+        ctx->sh.err = "level must be between 1 and L";
+        return nullptr;
+    }
+    return &ctx->level[level];
+}
+
+extern "C" int ckks_workspace_bytes_at(const ckks_ctx* ctx, int op, uint32_t level, uint32_t batch_or_nrot,
+                                       size_t* bytes) {
+    if (!ctx || !bytes) return CKKS_EINVAL;
+    const View* v = view_at(ctx, level);
+    if (!v) return CKKS_EINVAL;
+    return view_workspace_bytes(v, op, batch_or_nrot, bytes);
+}
+
+extern "C" int ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t batch_or_nrot, size_t* bytes) {
+    if (!ctx) return CKKS_EINVAL;
+    return ckks_workspace_bytes_at(ctx, op, ctx->L, batch_or_nrot, bytes);
 }
 
 // --------------------------------------------------------------------------- entry points
-static int check_limb_range(const ckks_ctx* c, u32 prime_first, u32 n_limbs, u32 batch) {
+static int check_limb_range(const View* c, u32 prime_first, u32 n_limbs, u32 batch) {
     if (n_limbs == 0 || batch == 0) return fail(c, CKKS_EINVAL, "n_limbs and batch must be positive");
     if ((u64)prime_first + n_limbs > c->D) return fail(c, CKKS_EINVAL, "limb range exceeds the prime chain");
     if ((u64)n_limbs * batch > (1u << 20)) return fail(c, CKKS_EINVAL, "batch too large");
@@ -828,23 +963,24 @@ static int check_limb_range(const ckks_ctx* c, u32 prime_first, u32 n_limbs, u32
 static int ntt_entry(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uint32_t n_limbs, uint32_t batch,
                      void* stream, bool inverse) {
     if (!ctx) return CKKS_EINVAL;
-    if (!d_x || misaligned(d_x, 16)) return fail(ctx, CKKS_EINVAL, "d_x is null or not 16-byte aligned");
-    int rc = check_limb_range(ctx, prime_first, n_limbs, batch);
+    const View* c = ctx->full();
+    if (!d_x || misaligned(d_x, 16)) return fail(c, CKKS_EINVAL, "d_x is null or not 16-byte aligned");
+    int rc = check_limb_range(c, prime_first, n_limbs, batch);
     if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     const LimbSel sel = {n_limbs, batch, n_limbs, 0, prime_first, 0};
     if (!inverse) {
         FwdStridedArgs a1 = {d_x, d_x, sel};
-        launch_fwd_strided(ctx, a1, s);
+        launch_fwd_strided(c, a1, s);
         FwdContigArgs a2 = {d_x, sel};
-        launch_fwd_contig(ctx, a2, s);
+        launch_fwd_contig(c, a2, s);
     } else {
         InvContigArgs a1 = {d_x, nullptr, d_x, sel, sel, 1};
-        launch_inv_contig<INV_PLAIN>(ctx, a1, s);
+        launch_inv_contig<INV_PLAIN>(c, a1, s);
         InvStridedArgs a2 = {d_x, sel, SC_PLAIN, 0};
-        launch_inv_strided(ctx, a2, s);
+        launch_inv_strided(c, a2, s);
     }
-    return hip_check(ctx, inverse ? "ckks_intt" : "ckks_ntt");
+    return hip_check(c, inverse ? "ckks_intt" : "ckks_ntt");
 }
 
 extern "C" int ckks_ntt(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uint32_t n_limbs, uint32_t batch,
@@ -857,7 +993,7 @@ extern "C" int ckks_intt(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uin
     return ntt_entry(ctx, d_x, prime_first, n_limbs, batch, stream, true);
 }
 
-static int check_ks_ctx(const ckks_ctx* c, u32 batch) {
+static int check_ks_ctx(const View* c, u32 batch) {
     if (c->K == 0) return fail(c, CKKS_EUNSUPPORTED, "context has no special primes");
     if (batch == 0 || batch > 4096) return fail(c, CKKS_EINVAL, "batch out of range");
     return CKKS_OK;
@@ -865,25 +1001,27 @@ static int check_ks_ctx(const ckks_ctx* c, u32 batch) {
 
 extern "C" int ckks_modup(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, uint32_t batch, void* stream) {
     if (!ctx) return CKKS_EINVAL;
+    const View* c = ctx->full();
     if (!d_in || !d_out || misaligned(d_in, 16) || misaligned(d_out, 16))
-        return fail(ctx, CKKS_EINVAL, "null or misaligned buffer");
-    int rc = check_ks_ctx(ctx, batch);
+        return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    int rc = check_ks_ctx(c, batch);
     if (rc) return rc;
-    launch_modup(ctx, d_in, d_out, batch, (hipStream_t)stream);
-    return hip_check(ctx, "ckks_modup");
+    launch_modup(c, d_in, d_out, batch, (hipStream_t)stream);
+    return hip_check(c, "ckks_modup");
 }
 
 extern "C" int ckks_moddown(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, uint32_t batch, void* stream) {
     if (!ctx) return CKKS_EINVAL;
+    const View* c = ctx->full();
     if (!d_in || !d_out || misaligned(d_in, 16) || misaligned(d_out, 16))
-        return fail(ctx, CKKS_EINVAL, "null or misaligned buffer");
-    int rc = check_ks_ctx(ctx, batch);
+        return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    int rc = check_ks_ctx(c, batch);
     if (rc) return rc;
-    launch_moddown(ctx, d_in, d_out, batch, (hipStream_t)stream);
-    return hip_check(ctx, "ckks_moddown");
+    launch_moddown(c, d_in, d_out, batch, (hipStream_t)stream);
+    return hip_check(c, "ckks_moddown");
 }
 
-static int check_galois(const ckks_ctx* c, u32 g) {
+static int check_galois(const View* c, u32 g) {
     if ((g & 1) == 0 || g >= (2u << c->logN)) return fail(c, CKKS_EINVAL, "Galois element must be odd and below 2N");
     return CKKS_OK;
 }
@@ -891,31 +1029,32 @@ static int check_galois(const ckks_ctx* c, u32 g) {
 extern "C" int ckks_automorph(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, uint32_t prime_first,
                               uint32_t n_limbs, uint32_t galois, int eval_domain, uint32_t batch, void* stream) {
     if (!ctx) return CKKS_EINVAL;
+    const View* c = ctx->full();
     if (!d_in || !d_out || misaligned(d_in, 16) || misaligned(d_out, 16))
-        return fail(ctx, CKKS_EINVAL, "null or misaligned buffer");
-    if (d_in == d_out) return fail(ctx, CKKS_EINVAL, "automorphism cannot run in place");
-    int rc = check_limb_range(ctx, prime_first, n_limbs, batch);
+        return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    if (d_in == d_out) return fail(c, CKKS_EINVAL, "automorphism cannot run in place");
+    int rc = check_limb_range(c, prime_first, n_limbs, batch);
     if (rc) return rc;
-    rc = check_galois(ctx, galois);
+    rc = check_galois(c, galois);
     if (rc) return rc;
-    if (batch > 65535) return fail(ctx, CKKS_EINVAL, "batch too large");
-    const dim3 grid((1u << ctx->logN) / 256, n_limbs, batch), block(256);
+    if (batch > 65535) return fail(c, CKKS_EINVAL, "batch too large");
+    const dim3 grid((1u << c->logN) / 256, n_limbs, batch), block(256);
     hipStream_t s = (hipStream_t)stream;
-    ProfScope ps(ctx, std::string(eval_domain ? "automorph_eval_kernel" : "automorph_coeff_kernel"), (u64)batch * n_limbs * 2, s);
+    ProfScope ps(c, std::string(eval_domain ? "automorph_eval_kernel" : "automorph_coeff_kernel"), (u64)batch * n_limbs * 2, s);
     if (eval_domain) {
-        hipLaunchKernelGGL(automorph_eval_kernel, grid, block, 0, s, d_in, d_out, ctx->logN, n_limbs, galois);
+        hipLaunchKernelGGL(automorph_eval_kernel, grid, block, 0, s, d_in, d_out, c->logN, n_limbs, galois);
     } else {
         // inverse of g modulo 2N (a power of two): Newton iteration on 32-bit words, then mask
         u32 inv = galois;
         for (int i = 0; i < 5; i++) inv *= 2 - galois * inv;
-        inv &= (2u << ctx->logN) - 1;
-        hipLaunchKernelGGL(automorph_coeff_kernel, grid, block, 0, s, d_in, d_out, ctx->tb.pc, ctx->logN, n_limbs,
+        inv &= (2u << c->logN) - 1;
+        hipLaunchKernelGGL(automorph_coeff_kernel, grid, block, 0, s, d_in, d_out, c->tb.pc, c->logN, n_limbs,
                            prime_first, inv);
     }
-    return hip_check(ctx, "ckks_automorph");
+    return hip_check(c, "ckks_automorph");
 }
 
-static int check_ks_args(const ckks_ctx* c, const void* a, const void* b, const void* out, u32 batch, int op,
+static int check_ks_args(const View* c, const void* a, const void* b, const void* out, u32 batch, int op,
                          const void* ws, size_t ws_bytes) {
     if (!a || !b || !out || misaligned(a, 16) || misaligned(b, 16) || misaligned(out, 16))
         return fail(c, CKKS_EINVAL, "null or misaligned buffer");
@@ -923,7 +1062,7 @@ static int check_ks_args(const ckks_ctx* c, const void* a, const void* b, const 
     if (rc) return rc;
     if (!ws || misaligned(ws, 256)) return fail(c, CKKS_EINVAL, "workspace is null or not 256-byte aligned");
     size_t need = 0;
-    rc = ckks_workspace_bytes(c, op, batch, &need);
+    rc = view_workspace_bytes(c, op, batch, &need);
     if (rc) return rc;
     if (ws_bytes < need) return fail(c, CKKS_ENOMEM, "workspace too small");
     return CKKS_OK;
@@ -932,7 +1071,7 @@ static int check_ks_args(const ckks_ctx* c, const void* a, const void* b, const 
 // ModUp side shared by every key switch: w.x holds the first inverse pass of the polynomial(s).
 // Second inverse pass (scaled by the conversion pre-factor), then conversion fused into the
 // first forward pass of every extended limb.
-static void decompose_extend(const ckks_ctx* c, const Workspace& w, u32 groups, hipStream_t s) {
+static void decompose_extend(const View* c, const Workspace& w, u32 groups, hipStream_t s) {
     const LimbSel sel = {c->L, groups, c->L, 0, 0, 0};
     InvStridedArgs a2 = {w.x, sel, SC_UP, 1};
     launch_inv_strided(c, a2, s);
@@ -942,7 +1081,7 @@ static void decompose_extend(const ckks_ctx* c, const Workspace& w, u32 groups, 
 }
 
 // ModDown side: w.cp holds the first inverse pass of c' on the special limbs.
-static void moddown_convert(const ckks_ctx* c, const Workspace& w, u32 cg, hipStream_t s) {
+static void moddown_convert(const View* c, const Workspace& w, u32 cg, hipStream_t s) {
     const LimbSel sel = {c->K, cg * 2, c->K, 0, c->L, 0};
     InvStridedArgs a6 = {w.cp, sel, SC_DN, 0};
     launch_inv_strided(c, a6, s);
@@ -952,7 +1091,7 @@ static void moddown_convert(const ckks_ctx* c, const Workspace& w, u32 cg, hipSt
 }
 
 template <int LOAD, int OWN, int FIN>
-static void keyswitch_pipeline(const ckks_ctx* c, const u64* in1, const u64* in2, const u64* key, u64* out, u32 batch,
+static void keyswitch_pipeline(const View* c, const u64* in1, const u64* in2, const u64* key, u64* out, u32 batch,
                                u32 galois, void* ws, hipStream_t s) {
     const Workspace w = carve(c, ws, batch, batch, batch);
     const LimbSel sel = {c->L, batch, c->L, 0, 0, 0};
@@ -968,61 +1107,118 @@ static void keyswitch_pipeline(const ckks_ctx* c, const u64* in1, const u64* in2
     FinalArgs fa;
     memset(&fa, 0, sizeof(fa));
     fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = in1, fa.ct2 = in2, fa.out = out, fa.galois[0] = galois, fa.n_inst = batch;
+    fa.cq_L = c->L;
     launch_ks_final<FIN>(c, fa, s);
+}
+
+extern "C" int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_d, const uint64_t* d_key,
+                                 uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    int rc = check_ks_args(c, d_d, d_key, d_out, batch, CKKS_OP_KEYSWITCH, d_ws, ws_bytes);
+    if (rc) return rc;
+    keyswitch_pipeline<INV_PLAIN, OWN_COPY, FIN_KS>(c, d_d, nullptr, d_key, d_out, batch, 1, d_ws, (hipStream_t)stream);
+    return hip_check(c, "ckks_keyswitch");
+}
+
+extern "C" int ckks_hmult_relin_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct1, const uint64_t* d_ct2,
+                                   const uint64_t* d_evk, uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes,
+                                   void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    if (!d_ct2 || misaligned(d_ct2, 16)) return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    int rc = check_ks_args(c, d_ct1, d_evk, d_out, batch, CKKS_OP_HMULT_RELIN, d_ws, ws_bytes);
+    if (rc) return rc;
+    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT>(c, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
+                                                          (hipStream_t)stream);
+    return hip_check(c, "ckks_hmult_relin");
+}
+
+extern "C" int ckks_hrot_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t galois, const uint64_t* d_rk,
+                            uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    int rc = check_ks_args(c, d_ct, d_rk, d_out, batch, CKKS_OP_HROT, d_ws, ws_bytes);
+    if (rc) return rc;
+    rc = check_galois(c, galois);
+    if (rc) return rc;
+    keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, d_ct, nullptr, d_rk, d_out, batch, galois, d_ws,
+                                                   (hipStream_t)stream);
+    return hip_check(c, "ckks_hrot");
 }
 
 extern "C" int ckks_keyswitch(ckks_ctx* ctx, const uint64_t* d_d, const uint64_t* d_key, uint64_t* d_out,
                               uint32_t batch, void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx) return CKKS_EINVAL;
-    int rc = check_ks_args(ctx, d_d, d_key, d_out, batch, CKKS_OP_KEYSWITCH, d_ws, ws_bytes);
-    if (rc) return rc;
-    keyswitch_pipeline<INV_PLAIN, OWN_COPY, FIN_KS>(ctx, d_d, nullptr, d_key, d_out, batch, 1, d_ws,
-                                                    (hipStream_t)stream);
-    return hip_check(ctx, "ckks_keyswitch");
+    return ckks_keyswitch_at(ctx, ctx->L, d_d, d_key, d_out, batch, d_ws, ws_bytes, stream);
 }
 
 extern "C" int ckks_hmult_relin(ckks_ctx* ctx, const uint64_t* d_ct1, const uint64_t* d_ct2, const uint64_t* d_evk,
                                 uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx) return CKKS_EINVAL;
-    if (!d_ct2 || misaligned(d_ct2, 16)) return fail(ctx, CKKS_EINVAL, "null or misaligned buffer");
-    int rc = check_ks_args(ctx, d_ct1, d_evk, d_out, batch, CKKS_OP_HMULT_RELIN, d_ws, ws_bytes);
-    if (rc) return rc;
-    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT>(ctx, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
-                                                          (hipStream_t)stream);
-    return hip_check(ctx, "ckks_hmult_relin");
+    return ckks_hmult_relin_at(ctx, ctx->L, d_ct1, d_ct2, d_evk, d_out, batch, d_ws, ws_bytes, stream);
 }
 
 extern "C" int ckks_hrot(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t galois, const uint64_t* d_rk, uint64_t* d_out,
                          uint32_t batch, void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx) return CKKS_EINVAL;
-    int rc = check_ks_args(ctx, d_ct, d_rk, d_out, batch, CKKS_OP_HROT, d_ws, ws_bytes);
-    if (rc) return rc;
-    rc = check_galois(ctx, galois);
-    if (rc) return rc;
-    keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(ctx, d_ct, nullptr, d_rk, d_out, batch, galois, d_ws,
-                                                   (hipStream_t)stream);
-    return hip_check(ctx, "ckks_hrot");
+    return ckks_hrot_at(ctx, ctx->L, d_ct, galois, d_rk, d_out, batch, d_ws, ws_bytes, stream);
 }
 
-extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, const uint32_t* h_galois,
-                                     const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt, uint64_t* d_out,
-                                     void* d_ws, size_t ws_bytes, void* stream) {
+// Rescale = a ModDown whose only special prime is the last active limb: inverse transform of that
+// limb, reduction modulo every remaining prime fused into their first forward pass, second forward
+// pass fused with (c_i - .) * q_last^-1.
+extern "C" int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch,
+                            void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx) return CKKS_EINVAL;
-    if (!h_galois || !h_rk_ptrs) return fail(ctx, CKKS_EINVAL, "null host array");
-    if (n_rot == 0 || n_rot > 65535) return fail(ctx, CKKS_EINVAL, "n_rot out of range");
+    if (level < 2 || level > ctx->L) return fail(ctx, CKKS_EINVAL, "rescale needs a level between 2 and L");
+    const View* c = &ctx->rescale[level];  // c->L = level - 1 targets, c->K = 1
+    if (!d_ct || !d_out || misaligned(d_ct, 16) || misaligned(d_out, 16))
+        return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    if (batch == 0 || batch > 4096) return fail(c, CKKS_EINVAL, "batch out of range");
+    if (!d_ws || misaligned(d_ws, 256)) return fail(c, CKKS_EINVAL, "workspace is null or not 256-byte aligned");
+    const size_t N = (size_t)1 << c->logN;
+    if (ws_bytes < (size_t)batch * 2 * level * N * sizeof(u64)) return fail(c, CKKS_ENOMEM, "workspace too small");
+    hipStream_t s = (hipStream_t)stream;
+    Workspace w;
+    w.x = w.dt = w.cq = nullptr;
+    w.cp = (u64*)d_ws;                    // [b][2][1][N]
+    w.cv = w.cp + (size_t)batch * 2 * N;  // [b][2][level-1][N]
+    const LimbSel src = {1, batch * 2, level, level - 1, level - 1, 0};  // limb level-1 of every component
+    const LimbSel dst = {1, batch * 2, 1, 0, level - 1, 0};
+    InvContigArgs a1 = {d_ct, nullptr, w.cp, src, dst, 1};
+    launch_inv_contig<INV_PLAIN>(c, a1, s);
+    moddown_convert(c, w, batch, s);
+    FinalArgs fa;
+    memset(&fa, 0, sizeof(fa));
+    fa.cq = d_ct, fa.cq_L = level, fa.cv = w.cv, fa.out = d_out, fa.n_inst = batch;
+    launch_ks_final<FIN_KS>(c, fa, s);
+    return hip_check(c, "ckks_rescale");
+}
+
+extern "C" int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
+                                        const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt,
+                                        uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    if (!h_galois || !h_rk_ptrs) return fail(c, CKKS_EINVAL, "null host array");
+    if (n_rot == 0 || n_rot > 65535) return fail(c, CKKS_EINVAL, "n_rot out of range");
     if (!d_ct || !d_pt || !d_out || misaligned(d_ct, 16) || misaligned(d_pt, 16) || misaligned(d_out, 16))
-        return fail(ctx, CKKS_EINVAL, "null or misaligned buffer");
-    if (!d_ws || misaligned(d_ws, 256)) return fail(ctx, CKKS_EINVAL, "workspace is null or not 256-byte aligned");
+        return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    if (!d_ws || misaligned(d_ws, 256)) return fail(c, CKKS_EINVAL, "workspace is null or not 256-byte aligned");
     size_t need = 0;
-    int rc = ckks_workspace_bytes(ctx, CKKS_OP_HROT_HOISTED_MAC, n_rot, &need);
+    int rc = view_workspace_bytes(c, CKKS_OP_HROT_HOISTED_MAC, n_rot, &need);
     if (rc) return rc;
-    if (ws_bytes < need) return fail(ctx, CKKS_ENOMEM, "workspace too small");
+    if (ws_bytes < need) return fail(c, CKKS_ENOMEM, "workspace too small");
     for (u32 r = 0; r < n_rot; r++) {
-        if (!h_rk_ptrs[r] || misaligned(h_rk_ptrs[r], 16)) return fail(ctx, CKKS_EINVAL, "null or misaligned key");
-        rc = check_galois(ctx, h_galois[r]);
+        if (!h_rk_ptrs[r] || misaligned(h_rk_ptrs[r], 16)) return fail(c, CKKS_EINVAL, "null or misaligned key");
+        rc = check_galois(c, h_galois[r]);
         if (rc) return rc;
     }
-    const ckks_ctx* c = ctx;
     hipStream_t s = (hipStream_t)stream;
     const size_t N = (size_t)1 << c->logN;
     const u32 chunk_max = n_rot < CKKS_ROT_CHUNK ? n_rot : CKKS_ROT_CHUNK;
@@ -1059,9 +1255,16 @@ extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32
         fork_side(c, s);  // no-op in the first chunk (still forked); later chunks wait for the previous ModDown
         launch_ks_inner<OWN_COPY, true>(c, ia, s);
         moddown_convert(c, w, nr, s);
-        fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = d_ct, fa.pt = d_pt + (size_t)r0 * c->L * N, fa.out = d_out;
+        fa.cq = w.cq, fa.cq_L = c->L, fa.cv = w.cv, fa.ct1 = d_ct, fa.pt = d_pt + (size_t)r0 * c->L * N, fa.out = d_out;
         fa.n_inst = 2, fa.n_rot = nr, fa.accumulate = r0 ? 1 : 0;
         launch_ks_final<FIN_HOISTED>(c, fa, s);
     }
-    return hip_check(ctx, "ckks_hrot_hoisted_mac");
+    return hip_check(c, "ckks_hrot_hoisted_mac");
+}
+
+extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, const uint32_t* h_galois,
+                                     const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt, uint64_t* d_out,
+                                     void* d_ws, size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    return ckks_hrot_hoisted_mac_at(ctx, ctx->L, d_ct, n_rot, h_galois, h_rk_ptrs, d_pt, d_out, d_ws, ws_bytes, stream);
 }

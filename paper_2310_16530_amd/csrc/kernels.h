@@ -39,6 +39,13 @@ struct Tables {
     const u32* dn_fp_ok;       // [L]  1 if q_i may convert on the FP64 pipe (FpAr prime, at least 2^28)
     const PinvConst* pinv;     // [L]     P^-1 mod q_i
     u32 logN, L, K, dnum, alpha, D;
+    u32 Lfull;  // q-limbs of the whole prime chain (>= L)
+    // A Tables value describes one level: the basis q_0..q_{L-1}, p_0..p_{K-1} with L <= Lfull active
+    // q-limbs, dnum = ceil(L/alpha) digits (the last one possibly partial) and limb indices 0..D-1 over
+    // that basis.  The per-prime tables (tw_int, tw_fp, pc, sc_plain) and switching keys are laid out
+    // over the whole chain of Lfull + K primes: phys() maps a limb index of the level to them.  All
+    // other tables are per level and indexed by the level's limb indices.
+    __host__ __device__ __forceinline__ u32 phys(u32 i) const { return i < L ? i : i + (Lfull - L); }
 };
 
 // slot j of sigma_g(f) in evaluation form reads slot eval_perm(j) of f
@@ -75,7 +82,7 @@ __device__ __forceinline__ void inv_contig_body(const InvContigArgs& a, const Ta
                                                 u32 inst) {
     typedef typename AR::T T;
     const u32 N = 1u << tb.logN, tid = threadIdx.x, e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
-    const u32 pi = a.sel.prime_base + l;
+    const u32 pi = tb.phys(a.sel.prime_base + l);
     const PrimeConst pc = tb.pc[pi];
     const typename AR::Mod m = AR::mod(pc);
     const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
@@ -135,11 +142,11 @@ __device__ __forceinline__ void inv_strided_body(const InvStridedArgs& a, const 
     typedef typename AR::T T;
     typedef NttCore<AR, A> C;
     const u32 N = 1u << tb.logN, tid = threadIdx.x;
-    const u32 pi = a.sel.prime_base + l;
+    const u32 vi = a.sel.prime_base + l, pi = tb.phys(vi);
     const typename AR::Mod m = AR::mod(tb.pc[pi]);
     const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
     const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
-    const InvScale sc = a.scale == SC_PLAIN ? tb.sc_plain[pi] : a.scale == SC_UP ? tb.sc_up[pi] : tb.sc_dn[pi - tb.L];
+    const InvScale sc = a.scale == SC_PLAIN ? tb.sc_plain[pi] : a.scale == SC_UP ? tb.sc_up[vi] : tb.sc_dn[vi - tb.L];
     const u32 c = tid % C::TC, r0 = tid / C::TC, col = tile * C::TC + c;
     u64* base = a.data + limb_offset(a.sel, inst, l) * N;
     T x[16];
@@ -178,10 +185,10 @@ struct FwdStridedArgs {
 
 // stages + store shared by the plain and the conversion-fused first pass; x in layout SA
 template <class AR, int A>
-__device__ __forceinline__ void fwd_strided_finish(typename AR::T (&x)[16], const Tables& tb, u64* lds, u32 pi,
+__device__ __forceinline__ void fwd_strided_finish(typename AR::T (&x)[16], const Tables& tb, u64* lds, u32 vi,
                                                    u64* dst, u32 tile) {
     typedef NttCore<AR, A> C;
-    const u32 N = 1u << tb.logN, tid = threadIdx.x;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x, pi = tb.phys(vi);
     const typename AR::Mod m = AR::mod(tb.pc[pi]);
     const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
     const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
@@ -207,7 +214,7 @@ __global__ __launch_bounds__(256) void fwd_strided_kernel(FwdStridedArgs a, Tabl
     if (!xcd_decode(blockIdx.x, a.sel.n_inst, run.count * TILES, group, inst)) return;
     const u32 l = run.first + group / TILES, tile = group % TILES, pi = a.sel.prime_base + l;
     const size_t off = limb_offset(a.sel, inst, l) * N;
-    const typename AR::Mod m = AR::mod(tb.pc[pi]);
+    const typename AR::Mod m = AR::mod(tb.pc[tb.phys(pi)]);
     const u32 c = tid % C::TC, r0 = tid / C::TC, col = tile * C::TC + c;
     typename AR::T x[16];
 #pragma unroll
@@ -254,8 +261,9 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
         chat = tb.up_chat + (size_t)j * tb.alpha * tb.D;
         chat_fp = tb.up_chat_fp + (size_t)j * tb.alpha * tb.D;
         fp_ok = tb.up_fp_ok + (size_t)j * tb.D;
-        chat_stride = tb.D, ns = tb.alpha, src_prime = j * tb.alpha;
-        own_lo = j * tb.alpha, own_hi = (j + 1) * tb.alpha;
+        // the last digit of a level may hold fewer than alpha limbs
+        own_lo = j * tb.alpha, own_hi = (j + 1) * tb.alpha < tb.L ? (j + 1) * tb.alpha : tb.L;
+        chat_stride = tb.D, ns = own_hi - own_lo, src_prime = own_lo;
     } else {
         if (!xcd_decode(blockIdx.x, n_inst, a.groups_outer * TILES, group, inst)) return;
         tile = group % TILES;
@@ -287,7 +295,7 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
         FpAr::Mod fm[TB];
 #pragma unroll
         for (int t = 0; t < TB; t++) {
-            fm[t] = FpAr::mod(tb.pc[pi[t]]);
+            fm[t] = FpAr::mod(tb.pc[tb.phys(pi[t])]);
 #pragma unroll
             for (int k = 0; k < 16; k++) acc[t][k] = 0.0;
         }
@@ -337,7 +345,7 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
         }
 #pragma unroll
         for (int t = 0; t < TB; t++) {
-            const typename AR::Mod m = AR::mod(tb.pc[pi[t]]);
+            const typename AR::Mod m = AR::mod(tb.pc[tb.phys(pi[t])]);
 #pragma unroll
             for (int k = 0; k < 16; k++) x[t][k] = AR::from_f64_lazy(acc[t][k], m);
         }
@@ -351,7 +359,7 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
         for (u32 i0 = 0; i0 < ns; i0++) {
             const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
             const u64* si = src + (size_t)i * N;
-            const bool src_fp = DIR == CONV_UP && tb.pc[src_prime + i].fp;
+            const bool src_fp = DIR == CONV_UP && tb.pc[tb.phys(src_prime + i)].fp;
             u64 cc[TB];
 #pragma unroll
             for (int t = 0; t < TB; t++) cc[t] = chat[(size_t)i * chat_stride + pi[t]];
@@ -365,7 +373,7 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
         }
 #pragma unroll
         for (int t = 0; t < TB; t++) {
-            const PrimeConst pc = tb.pc[pi[t]];
+            const PrimeConst pc = tb.pc[tb.phys(pi[t])];
             const typename AR::Mod m = AR::mod(pc);
 #pragma unroll
             for (int k = 0; k < 16; k++) x[t][k] = AR::from_canon(redc(acc[t][k], pc.q, pc.qneg), m);
@@ -373,14 +381,14 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
     } else {
         // FpAr targets whose sources do not fit the FP64 bounds: integer conversion, one target at a time
         for (int t = 0; t < TB; t++) {
-            const PrimeConst pc = tb.pc[pi[t]];
+            const PrimeConst pc = tb.pc[tb.phys(pi[t])];
             const typename AR::Mod m = AR::mod(pc);
             u128w acc[16];
 #pragma unroll
             for (int k = 0; k < 16; k++) acc[k] = u128w{0, 0};
             for (u32 i = 0; i < ns; i++) {
                 const u64* si = src + (size_t)i * N;
-                const bool src_fp = DIR == CONV_UP && tb.pc[src_prime + i].fp;
+                const bool src_fp = DIR == CONV_UP && tb.pc[tb.phys(src_prime + i)].fp;
                 const u64 cc = chat[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
@@ -416,7 +424,7 @@ __device__ __forceinline__ void fwd_contig_body(const FwdContigArgs& a, const Ta
                                                 u32 inst) {
     typedef typename AR::T T;
     const u32 N = 1u << tb.logN, tid = threadIdx.x, e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
-    const u32 pi = a.sel.prime_base + l;
+    const u32 pi = tb.phys(a.sel.prime_base + l);
     const typename AR::Mod m = AR::mod(tb.pc[pi]);
     const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
     const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
@@ -469,13 +477,14 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
     typedef typename AR::T T;
     const u32 N = 1u << tb.logN, tid = threadIdx.x, e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
     const u32 L = tb.L, D = tb.D;
-    const PrimeConst pc = tb.pc[i];
+    const u32 pi = tb.phys(i), Dkey = tb.Lfull + tb.K;  // keys are laid out over the whole chain
+    const PrimeConst pc = tb.pc[pi];
     const typename AR::Mod m = AR::mod(pc);
-    const u64* ti = tb.tw_int + (size_t)i * 4 * N;
-    const double* tf = tb.tw_fp + (size_t)i * 2 * N;
+    const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
+    const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
     u64* lrow = lds + ch * 272;
     const u32 row_off = r * 256;
-    const u64* key = a.key[HOISTED ? inst : 0] + (size_t)i * N + row_off;
+    const u64* key = a.key[HOISTED ? inst : 0] + (size_t)pi * N + row_off;
     const u32 gal = HOISTED ? a.galois[inst] : a.galois[0];
     const u32 own_digit = i < L ? i / tb.alpha : 0xffffffffu;
     T acc0[16], acc1[16];
@@ -483,8 +492,8 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
     for (int k = 0; k < 16; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
     for (u32 j = 0; j < tb.dnum; j++) {
         // issue the key loads first so that they are in flight while the digit is transformed
-        const u64* k0 = key + ((size_t)j * 2 + 0) * D * N;
-        const u64* k1 = key + ((size_t)j * 2 + 1) * D * N;
+        const u64* k0 = key + ((size_t)j * 2 + 0) * Dkey * N;
+        const u64* k1 = key + ((size_t)j * 2 + 1) * Dkey * N;
         u64 kv0[16], kv1[16];
         if constexpr (AR::is_fp) {  // IntAr has no registers to spare: it loads the key at its use
 #pragma unroll
@@ -588,6 +597,7 @@ struct FinalArgs {
     u32 n_inst;      // batch (or 2 for HOISTED: the component t)
     u32 n_rot;       // HOISTED
     u32 accumulate;  // HOISTED: add to what out already holds
+    u32 cq_L;        // limbs per component of cq (L, or L + 1 when cq is a ciphertext about to lose its last limb)
 };
 
 template <class AR, int A, int MODE>
@@ -647,7 +657,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
             NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
             exchange_cb_to_ca<AR>(v, lrow, e0);
-            const u64* c = a.cq + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+            const u64* c = a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off;
             u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
             const size_t o0 = (((size_t)inst * 2 + 0) * L + i) * N + row_off, o1 = o0 + (size_t)L * N;
 #pragma unroll
@@ -709,7 +719,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
         for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
         NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
         exchange_cb_to_ca<AR>(v, lrow, e0);
-        const u64* c = a.cq + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+        const u64* c = a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off;
         u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
         const size_t o0 = (((size_t)inst * 2 + 0) * L + i) * N + row_off, o1 = o0 + (size_t)L * N;
 #pragma unroll

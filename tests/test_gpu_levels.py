@@ -1,0 +1,179 @@
+"""Parity of the level-aware entry points and of rescale against the CPU oracle, bit for bit (needs an MI355X).
+
+Covers every level of several reduced shapes (full digits, a partial last digit, a single limb),
+integer-arithmetic q-limbs as well as floating-point ones, a multiply-rescale chain, and the
+benchmark shape N = 2^16, L = 24, dnum = 4 at a level whose last digit is partial.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2310_16530_amd import synth
+
+from test_gpu_parity import dev, gpu_ctx, host, make_keys, orc_params
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# (logN, L, K, dnum, q bits, p bits): 49-bit q-limbs use the FP64 arithmetic, 55-bit ones the integer one
+RESCALE_SHAPES = [(12, 4, 2, 2, 49, 59), (13, 6, 3, 2, 49, 59), (12, 3, 1, 3, 35, 36), (14, 5, 0, 1, 49, 59),
+                  (12, 4, 2, 2, 55, 59), (16, 3, 1, 3, 49, 59)]
+
+
+@pytest.mark.parametrize("shape", RESCALE_SHAPES)
+def test_rescale_parity_every_level(orc, shape):
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(3000 + sum(shape))
+    B = 3
+    for ell in range(ps.L, 1, -1):
+        _say("rescale", shape, "level", ell)
+        ct = synth.uniform_residues(rng, ps.q_primes[:ell], ps.N, lead=(B, 2))
+        ct[1, 0] = 0
+        for i in range(ell):
+            ct[2, 1, i, :] = ps.q_primes[i] - 1
+        got = host(ctx.rescale(ell, dev(ct)))
+        assert got.shape == (B, 2, ell - 1, ps.N)
+        assert np.array_equal(got, orc.rescale(ct, P)), ell
+
+
+LEVEL_SHAPES = [(12, 6, 2, 3, 49, 59), (13, 6, 3, 2, 49, 59), (12, 8, 8, 1, 49, 59), (12, 3, 1, 3, 35, 36),
+                (12, 6, 3, 2, 55, 59), (12, 14, 7, 2, 49, 59)]
+
+
+@pytest.mark.parametrize("shape", LEVEL_SHAPES)
+def test_keyswitch_hmult_hrot_parity_at_levels(orc, shape):
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(4000 + sum(shape))
+    s = synth.ternary_hamming(rng, ps.N, 64)
+    s_hat = orc.secret_eval(s, P)
+    s2_hat = orc.pointwise("mul", s_hat, s_hat, ps.primes)
+    evk = make_keys(orc, ps, P, rng, s_hat, s2_hat)
+    g = synth.galois_element(-3, ps.logN)
+    rk = make_keys(orc, ps, P, rng, s_hat, orc.automorph_limbs(s_hat, P, 0, g, True))
+    d_evk, d_rk = dev(evk), dev(rk)
+    levels = sorted({ps.L, ps.L - 1, ps.alpha + 1, ps.alpha, max(ps.alpha - 1, 1), 1} & set(range(1, ps.L + 1)))
+    B = 2
+    for ell in levels:
+        _say("levels", shape, "level", ell)
+        q = ps.q_primes[:ell]
+        d = synth.uniform_residues(rng, q, ps.N, lead=(B,))
+        ks = host(ctx.keyswitch_at(ell, dev(d), d_evk))
+        for b in range(B):
+            assert np.array_equal(ks[b], orc.keyswitch_level(d[b], evk, P)), (ell, b)
+        bound = orc.keyswitch_noise_bound(P, int(np.abs(s).sum()), level=ell)
+        assert np.abs(orc.keyswitch_noise(d[0], ks[0], s_hat, s2_hat, P, level=ell)).max() <= bound
+        ct1 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
+        ct2 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
+        hm = host(ctx.hmult_relin_at(ell, dev(ct1), dev(ct2), d_evk))
+        hr = host(ctx.hrot_at(ell, dev(ct1), g, d_rk))
+        for b in range(B):
+            assert np.array_equal(hm[b], orc.hmult_relin_level(ct1[b], ct2[b], evk, P)), (ell, b)
+            assert np.array_equal(hr[b], orc.hrot_level(ct1[b], g, rk, P)), (ell, b)
+    # the full level through the level-aware entry equals the plain entry
+    ct = dev(synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2)))
+    assert np.array_equal(host(ctx.hrot_at(ps.L, ct, g, d_rk)), host(ctx.hrot(ct, g, d_rk)))
+
+
+@pytest.mark.parametrize("shape,n_rot", [((12, 6, 2, 3, 49, 59), 3), ((13, 6, 3, 2, 49, 59), 11)])
+def test_hoisted_mac_parity_at_levels(orc, shape, n_rot):
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(5000 + sum(shape))
+    rots = [1, 2, 3, 4, 5, 6, 7, 8, 16, -1, 32][:n_rot]
+    gs = [synth.galois_element(r, ps.logN) for r in rots]
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    d_rks = [dev(k) for k in rks]
+    for ell in (ps.L - 1, ps.alpha + 1, 1):
+        _say("hoisted", shape, "level", ell)
+        q = ps.q_primes[:ell]
+        ct = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        pt = synth.uniform_residues(rng, q, ps.N, lead=(n_rot,))
+        got = host(ctx.hrot_hoisted_mac_at(ell, dev(ct), gs, d_rks, dev(pt)))
+        assert np.array_equal(got, orc.hrot_hoisted_mac_level(ct, gs, rks, pt, P)), ell
+
+
+def test_multiply_rescale_chain(orc):
+    """(ct1 * ct2 -> rescale) * ct3 -> rescale, every intermediate compared with the oracle."""
+    ps = synth.small_params(13, 6, 2, 3)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(6000)
+    evk = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    d_evk = dev(evk)
+    L = ps.L
+    ct1 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    ct2 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    ct3 = synth.uniform_residues(rng, ps.q_primes[:L - 1], ps.N, lead=(2,))
+    g1 = ctx.hmult_relin_at(L, dev(ct1), dev(ct2), d_evk)
+    w1 = orc.hmult_relin_level(ct1, ct2, evk, P)
+    assert np.array_equal(host(g1), w1)
+    g2 = ctx.rescale(L, g1)
+    w2 = orc.rescale(w1, P)
+    assert np.array_equal(host(g2), w2)
+    g3 = ctx.hmult_relin_at(L - 1, g2, dev(ct3), d_evk)
+    w3 = orc.hmult_relin_level(w2, ct3, evk, P)
+    assert np.array_equal(host(g3), w3)
+    g4 = host(ctx.rescale(L - 1, g3))
+    assert np.array_equal(g4, orc.rescale(w3, P))
+
+
+@pytest.mark.timeout(900)
+def test_config2_shape_at_a_partial_level_full_size(orc):
+    """N = 2^16, L = 24, K = 6, dnum = 4 at level 13 (digits of 6, 6 and 1 limbs), batch 8: HMult, rescale, HRot."""
+    ps = synth.CFG2
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(2, 7)
+    ell, B = 13, synth.CFG2_BATCH
+    evk = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    q = ps.q_primes[:ell]
+    ct1 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
+    ct2 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
+    d_evk = dev(evk)
+    _say("cfg2 level 13: hmult")
+    hm_d = ctx.hmult_relin_at(ell, dev(ct1), dev(ct2), d_evk)
+    hm = host(hm_d)
+    for b in (0, B - 1):
+        assert np.array_equal(hm[b], orc.hmult_relin_level(ct1[b], ct2[b], evk, P)), b
+    _say("cfg2 level 13: rescale")
+    rs = host(ctx.rescale(ell, hm_d))
+    assert np.array_equal(rs, orc.rescale(hm, P))
+    _say("cfg2 level 13: hrot")
+    g = synth.galois_element(5, ps.logN)
+    hr = host(ctx.hrot_at(ell, dev(ct1), g, d_evk))
+    assert np.array_equal(hr[3], orc.hrot_level(ct1[3], g, evk, P))
+
+
+def test_level_error_paths(orc):
+    from paper_2310_16530_amd import binding
+    import torch
+    lib = binding.load()
+    ps = synth.small_params(12, 4, 2, 2)
+    ctx = gpu_ctx(ps)
+    x = torch.zeros((1, 2, ps.L, ps.N), dtype=torch.int64, device="cuda:0")
+    out = torch.empty_like(x)
+    key = torch.zeros((ps.dnum, 2, ps.L + ps.K, ps.N), dtype=torch.int64, device="cuda:0")
+    ws = ctx.workspace(binding.OP_HROT, 1)
+    h, p, o, k, w = ctx.handle, x.data_ptr(), out.data_ptr(), key.data_ptr(), ws.data_ptr()
+    for bad in (0, ps.L + 1):
+        assert lib.ckks_keyswitch_at(h, bad, p, k, o, 1, w, ws.numel(), None) == binding.CKKS_EINVAL
+        assert lib.ckks_hmult_relin_at(h, bad, p, p, k, o, 1, w, ws.numel(), None) == binding.CKKS_EINVAL
+        assert lib.ckks_hrot_at(h, bad, p, 5, k, o, 1, w, ws.numel(), None) == binding.CKKS_EINVAL
+        assert lib.ckks_rescale(h, bad, p, o, 1, w, ws.numel(), None) == binding.CKKS_EINVAL
+    assert b"level" in lib.ckks_last_error(h)
+    assert lib.ckks_rescale(h, 1, p, o, 1, w, ws.numel(), None) == binding.CKKS_EINVAL
+    assert lib.ckks_rescale(h, 3, p, o, 1, w, 64, None) == binding.CKKS_ENOMEM
+    assert lib.ckks_rescale(h, 3, p, None, 1, w, ws.numel(), None) == binding.CKKS_EINVAL
+    n = ctypes.c_size_t()
+    assert lib.ckks_workspace_bytes_at(h, binding.OP_KEYSWITCH, 9, 1, ctypes.byref(n)) == binding.CKKS_EINVAL
+    sizes = []
+    for ell in range(1, ps.L + 1):
+        assert lib.ckks_workspace_bytes_at(h, binding.OP_HMULT_RELIN, ell, 2, ctypes.byref(n)) == 0
+        sizes.append(n.value)
+    assert sizes == sorted(sizes) and sizes[-1] == ctx.workspace_bytes(binding.OP_HMULT_RELIN, 2)
+    torch.cuda.synchronize()
