@@ -207,6 +207,37 @@ def main():
         extra["hoisted_rot_mac_per_s"] = round(len(rots) * reps / (time.perf_counter() - a), 1)
         del rks, pt
 
+        # levels below L: rescale of the batch at level 24, and the HMult+relin -> rescale pair a CNN layer
+        # issues; then HMult+relin at level 13 (digits of 6, 6 and 1 limbs) with the same full-level key
+        def timed(fn):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            a0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - a0) / args.steps
+
+        rs_out = torch.empty((B, 2, L - 1, N), dtype=ct1.dtype, device=ct1.device)
+        dt = timed(lambda: ctx.rescale(L, ct1, rs_out))
+        extra["rescale_per_s"] = round(B / dt, 1)
+        # compulsory bytes of a rescale: read 2L limbs, write 2(L-1)
+        extra["rescale_effective_GBps"] = round(B * (4 * L - 2) * 8 * N / dt / 1e9, 1)
+
+        def mult_rescale():
+            ctx.hmult_relin(ct1, ct2, evk, out1)
+            ctx.rescale(L, out1, rs_out)
+
+        extra["hmult_relin_rescale_per_s"] = round(B / timed(mult_rescale), 1)
+        lv = 13
+        a13 = ct1[:, :, :lv].contiguous()
+        b13 = ct2[:, :, :lv].contiguous()
+        o13 = torch.empty_like(a13)
+        extra["hmult_relin_level13_per_s"] = round(B / timed(lambda: ctx.hmult_relin_at(lv, a13, b13, evk, o13)), 1)
+        extra["hrot_level13_per_s"] = round(B / timed(lambda: ctx.hrot_at(lv, a13, g, rk, o13)), 1)
+        del a13, b13, o13, rs_out
+
     cpu = None
     if not args.no_cpu:
         import oracle
