@@ -320,6 +320,40 @@ def hrot_hoisted_mac_level(ct: np.ndarray, galois: Sequence[int], rks: Sequence[
     return out
 
 
+def hrot_dh_mac_level(ct: np.ndarray, galois: Sequence[int], rks: Sequence[np.ndarray], pt: np.ndarray,
+                      P: Params) -> np.ndarray:
+    """Double-hoisted rotate-MAC.  ct [2][ell][N]; full-level keys; pt [n_rot][ell+K][N] (the level's
+    extended basis: q_0..q_{ell-1}, p_0..p_{K-1}) -> [2][ell][N]."""
+    ct = np.ascontiguousarray(ct, dtype=np.uint64)
+    pt = np.ascontiguousarray(pt, dtype=np.uint64)
+    n_rot, ell = len(galois), ct.shape[1]
+    assert len(rks) == n_rot and pt.shape == (n_rot, ell + P.K, P.N) and ct.shape == (2, ell, P.N)
+    rks = [np.ascontiguousarray(k, dtype=np.uint64) for k in rks]
+    ptrs = (ctypes.c_void_p * n_rot)(*[k.ctypes.data for k in rks])
+    g = np.ascontiguousarray(np.array(galois, dtype=np.uint32))
+    out = np.empty((2, ell, P.N), dtype=np.uint64)
+    lib().orc_hrot_dh_mac_level(_ptr(ct), _u32(n_rot), _ptr(g), ptrs, _ptr(pt), _ptr(out), *_level_tail(P, ell))
+    return out
+
+
+def dh_mac_noise_bound(P: Params, s_l1: int, pt_l1_sum: int, level: Optional[int] = None) -> int:
+    """ceil(sum_r ||pt_r||_1 * beta * N * alpha * max_j Q_j * 19 / P) + K * (1 + ||s||_1) + 1."""
+    ell = P.L if level is None else level
+    qs, ps = P.primes[:ell], P.primes[P.L:]
+    Pprod = 1
+    for p in ps:
+        Pprod *= p
+    beta = -(-ell // P.alpha)
+    maxQ = 0
+    for j in range(beta):
+        Qj = 1
+        for q in qs[j * P.alpha:(j + 1) * P.alpha]:
+            Qj *= q
+        maxQ = max(maxQ, Qj)
+    first = -((-(pt_l1_sum * beta * P.N * P.alpha * maxQ * 19)) // Pprod)
+    return first + P.K * (1 + s_l1) + 1
+
+
 # ------------------------------------------------------------- harness helpers
 def lift_signed(v: np.ndarray, primes: Sequence[int]) -> np.ndarray:
     """Small signed coefficients [N] -> canonical residues [len(primes)][N]."""

@@ -624,6 +624,62 @@ void orc_hrot_hoisted_mac_level(const uint64_t* ct, uint32_t n_rot, const uint32
     level_close(&v);
 }
 
+/* Double-hoisted rotate-multiply-accumulate (the linear-transform evaluation of the bootstrapping
+ * work the paper builds on): besides sharing the decomposition, the plaintext products are summed in
+ * the extended basis and ONE ModDown is applied to the sum,
+ *     C_t[i]  = sum_r pt_r[i] * c'_{r,t}[i]        on all ell+K limbs,  c'_r as in the hoisted version,
+ *     out_t   = NTT(ModDown(INTT(C_t))) + (t == 0 ? sum_r pt_r * sigma_{g_r}(b) : 0).
+ * pt: [n_rot][ell+K][N], the plaintext polynomial reduced modulo every prime of the level's extended
+ * basis (q_0..q_{ell-1}, p_0..p_{K-1}), evaluation form.  The result differs from the singly hoisted
+ * one bit for bit (ModDown of a sum is not the sum of ModDowns) and carries less rounding noise. */
+void orc_hrot_dh_mac_level(const uint64_t* ct, uint32_t n_rot, const uint32_t* galois, const uint64_t* const* rk,
+                           const uint64_t* pt, uint64_t* out, uint32_t ell, uint32_t logN, uint32_t L, uint32_t K,
+                           uint32_t dnum, const uint64_t* primes, const uint64_t* psi) {
+    orc_level v;
+    level_open(&v, ell, logN, L, K, dnum, primes, psi);
+    size_t N = (size_t)1 << logN;
+    uint32_t D = ell + K;
+    uint64_t* dhat = (uint64_t*)malloc(sizeof(uint64_t) * v.p.dnum * D * N);
+    uint64_t* cp = (uint64_t*)malloc(sizeof(uint64_t) * 2 * D * N);
+    uint64_t* C = (uint64_t*)calloc(2 * D * N, sizeof(uint64_t));
+    uint64_t* sb = (uint64_t*)malloc(sizeof(uint64_t) * N);
+    decompose_extend_level(ct + (size_t)ell * N, dhat, &v);
+    memset(out, 0, sizeof(uint64_t) * 2 * ell * N);
+    for (uint32_t r = 0; r < n_rot; r++) {
+        uint64_t* kc = level_key(&v, rk[r], L);
+        key_inner_product(dhat, kc, cp, &v.p, galois[r]);
+        free(kc);
+        for (uint32_t t = 0; t < 2; t++)
+            for (uint32_t i = 0; i < D; i++) {
+                uint64_t m = v.vprimes[i];
+                const uint64_t* ptr = pt + ((size_t)r * D + i) * N;
+                const uint64_t* src = cp + ((size_t)t * D + i) * N;
+                uint64_t* dst = C + ((size_t)t * D + i) * N;
+                for (size_t n = 0; n < N; n++) dst[n] = orc_addmod(dst[n], orc_mulmod(ptr[n], src[n], m), m);
+            }
+        for (uint32_t i = 0; i < ell; i++) { /* the b part never leaves the q-limbs */
+            uint64_t m = primes[i];
+            orc_automorph_eval(ct + (size_t)i * N, sb, logN, galois[r]);
+            const uint64_t* ptr = pt + ((size_t)r * D + i) * N;
+            for (size_t n = 0; n < N; n++)
+                out[(size_t)i * N + n] = orc_addmod(out[(size_t)i * N + n], orc_mulmod(ptr[n], sb[n], m), m);
+        }
+    }
+    uint64_t* ks = (uint64_t*)malloc(sizeof(uint64_t) * 2 * ell * N);
+    moddown_eval(C, ks, &v.p);
+    for (uint32_t i = 0; i < 2 * ell; i++) {
+        uint64_t m = primes[i % ell];
+        for (size_t n = 0; n < N; n++)
+            out[(size_t)i * N + n] = orc_addmod(out[(size_t)i * N + n], ks[(size_t)i * N + n], m);
+    }
+    free(ks);
+    free(dhat);
+    free(cp);
+    free(C);
+    free(sb);
+    level_close(&v);
+}
+
 /* --------------------------------------------------------- harness: key gen */
 /* Switching key from s to s' under the RNS gadget (P on digit j's own limbs):
  *   key[j][1][i] = a_j[i]                                   (uniform, evaluation form, given)

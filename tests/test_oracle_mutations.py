@@ -34,6 +34,9 @@ MUTATIONS = [
     ("key_inner_product(dhat, kc, cp, &v.p, 1);", "key_inner_product(dhat, key, cp, &v.p, 1);", "test_keyswitch_level_decrypt_and_bound"),
     ("orc_keyswitch_level(rot + (size_t)ell * N, rk, out", "orc_keyswitch_level(ct + (size_t)ell * N, rk, out", "test_hmult_hrot_level_decrypt"),
     ("        key_inner_product(dhat, kc, cp, &v.p, galois[r]);", "        key_inner_product(dhat, kc, cp, &v.p, 1);", "test_hoisted_mac_level"),
+    ("                const uint64_t* ptr = pt + ((size_t)r * D + i) * N;\n                const uint64_t* src = cp", "                const uint64_t* ptr = pt + ((size_t)r * D + (i % ell)) * N;\n                const uint64_t* src = cp", "test_double_hoisted_mac"),
+    ("            orc_automorph_eval(ct + (size_t)i * N, sb, logN, galois[r]);\n            const uint64_t* ptr = pt + ((size_t)r * D + i) * N;", "            orc_automorph_eval(ct + (size_t)i * N, sb, logN, 1);\n            const uint64_t* ptr = pt + ((size_t)r * D + i) * N;", "test_double_hoisted_mac"),
+    ("    moddown_eval(C, ks, &v.p);", "    moddown_eval(cp, ks, &v.p);", "test_double_hoisted_mac"),
 ]
 
 

@@ -645,3 +645,55 @@ def test_hoisted_mac_level(orc):
             for t in range(2):
                 acc[t] = orc.pointwise("add", acc[t], orc.pointwise("mul", pt[r], one[t], q), q)
         assert np.array_equal(acc, out)                               # linear in the per-rotation results
+
+
+# ------------------------------------------------------------- double hoisting
+def _small_plaintexts(orc, rng, P, n_rot, ell, amp=4):
+    """Plaintext polynomials with coefficients in [-amp, amp], reduced modulo every prime of the level's
+    extended basis and transformed: [n_rot][ell+K][N], plus their l1 norms."""
+    basis = list(P.primes[:ell]) + list(P.primes[P.L:])
+    psis = list(P.psi[:ell]) + list(P.psi[P.L:])
+    coeffs = rng.integers(-amp, amp + 1, size=(n_rot, P.N))
+    out = np.empty((n_rot, len(basis), P.N), dtype=np.uint64)
+    for r in range(n_rot):
+        lifted = orc.lift_signed(coeffs[r], basis)
+        for i, (m, w) in enumerate(zip(basis, psis)):
+            out[r, i] = orc.ntt(lifted[i], P.logN, m, w)
+    return out, [int(np.abs(c).sum()) for c in coeffs]
+
+
+@pytest.mark.parametrize("shape", LEVEL_SHAPES[:2] + [(6, 4, 4, 1, 30, 31)])
+def test_double_hoisted_mac_decrypts_and_reduces_to_single_rotation(orc, shape):
+    ps = _small_set(*shape)
+    P, rng, s, s_hat = _setup(orc, ps, 91)
+    rots = [1, -2, 4, 7]
+    gs = [synth.galois_element(r, ps.logN) for r in rots]
+    rks = [_keys(orc, ps, P, rng, orc.automorph_limbs(s_hat, P, 0, g, True), s_hat)[0] for g in gs]
+    h = int(np.abs(s).sum())
+    for ell in sorted({ps.L, ps.L - 1, min(ps.alpha + 1, ps.L), 1}):
+        q = list(ps.q_primes[:ell])
+        sq = s_hat[:ell]
+
+        def dec(c):
+            return orc.pointwise("add", c[0], orc.pointwise("mul", c[1], sq, q), q)
+
+        ct = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        pt, l1 = _small_plaintexts(orc, rng, P, len(rots), ell)
+        out = orc.hrot_dh_mac_level(ct, gs, rks, pt, P)
+        want = np.zeros((ell, ps.N), dtype=np.uint64)
+        for r, g in enumerate(gs):
+            want = orc.pointwise("add", want, orc.pointwise("mul", pt[r, :ell], orc.automorph_limbs(dec(ct), P, 0, g, True), q), q)
+        E = orc.centred_small(orc.pointwise("sub", dec(out), want, q), P, ell)
+        bound = orc.dh_mac_noise_bound(P, h, sum(l1), level=ell)
+        assert np.abs(E).max() <= bound
+        assert ell == 1 or bound < min(q) // 4
+        # one rotation with the unit plaintext is exactly the singly hoisted rotation
+        unit = np.ones((1, ell + ps.K, ps.N), dtype=np.uint64)
+        for r in (0, 3):
+            one = orc.hrot_dh_mac_level(ct, [gs[r]], [rks[r]], unit, P)
+            assert np.array_equal(one, orc.hrot_hoisted_mac_level(ct, [gs[r]], [rks[r]], unit[:, :ell], P))
+        # ... but the sum over rotations is not the sum of singly hoisted terms bit for bit
+        single = orc.hrot_hoisted_mac_level(ct, gs, rks, np.ascontiguousarray(pt[:, :ell]), P)
+        assert ell == 1 or not np.array_equal(single, out)
+        Es = orc.centred_small(orc.pointwise("sub", dec(single), dec(out), q), P, ell)
+        assert np.abs(Es).max() <= bound + sum(l1) * (ps.K * (1 + h) + 1) + sum(l1)
