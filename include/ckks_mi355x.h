@@ -61,6 +61,7 @@ extern "C" {
 #define CKKS_OP_HROT 6
 #define CKKS_OP_HROT_HOISTED_MAC 7
 #define CKKS_OP_RESCALE 8
+#define CKKS_OP_HROT_DH_MAC 9
 
 /* limits of this build */
 #define CKKS_MIN_LOGN 12
@@ -220,6 +221,24 @@ int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct
  */
 int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch, void* d_ws,
                  size_t ws_bytes, void* stream);
+
+/*
+ * Double-hoisted rotate-multiply-accumulate (the linear-transform evaluation of the bootstrapping
+ * the paper adopts, Section 2 / Table 1 "Boot"): besides sharing the decomposition, the plaintext
+ * products are summed in the extended basis and ONE ModDown is applied to the sum:
+ *   Dh_j as in ckks_hrot_hoisted_mac;  c'_{r,t} = sum_j sigma_{g_r}(Dh_j) * rk_r[j][t]  on all ell+K limbs;
+ *   C_t = sum_r pt_r * c'_{r,t};   out_t = NTT(ModDown(INTT(C_t))) + (t == 0 ? sum_r pt_r * sigma_{g_r}(b) : 0).
+ *   d_pt : [n_rot][ell+K][N] eval, the plaintext modulo every prime of the level's extended basis
+ *   (q_0..q_{ell-1}, then p_0..p_{K-1});  everything else as ckks_hrot_hoisted_mac(_at).
+ * Not bit-identical to the singly hoisted call (ModDown of a sum is not the sum of ModDowns); one
+ * rotation with the all-ones plaintext gives exactly that rotation's singly hoisted result.
+ */
+int ckks_hrot_dh_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, const uint32_t* h_galois,
+                     const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt, uint64_t* d_out, void* d_ws,
+                     size_t ws_bytes, void* stream);
+int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot, const uint32_t* h_galois,
+                        const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt, uint64_t* d_out, void* d_ws,
+                        size_t ws_bytes, void* stream);
 
 /*
  * Optional two-stream execution inside one call.  Off by default: every kernel of a call runs on the

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libckks_mi355x.so")
 
 CKKS_OK, CKKS_EINVAL, CKKS_EUNSUPPORTED, CKKS_EHIP, CKKS_ENOMEM = 0, -1, -2, -3, -4
 (OP_NTT, OP_MODUP, OP_MODDOWN, OP_AUTOMORPH, OP_KEYSWITCH, OP_HMULT_RELIN, OP_HROT, OP_HROT_HOISTED_MAC,
- OP_RESCALE) = range(9)
+ OP_RESCALE, OP_HROT_DH_MAC) = range(10)
 
 EXPORTS = (
     "ckks_table_bytes", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error", "ckks_ctx_psi",
@@ -26,7 +26,7 @@ EXPORTS = (
     "ckks_keyswitch", "ckks_hmult_relin", "ckks_hrot", "ckks_hrot_hoisted_mac",
     "ckks_profile_enable", "ckks_profile_read", "ckks_set_overlap",
     "ckks_workspace_bytes_at", "ckks_keyswitch_at", "ckks_hmult_relin_at", "ckks_hrot_at",
-    "ckks_hrot_hoisted_mac_at", "ckks_rescale",
+    "ckks_hrot_hoisted_mac_at", "ckks_rescale", "ckks_hrot_dh_mac", "ckks_hrot_dh_mac_at",
 )
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
@@ -73,6 +73,8 @@ def load() -> ctypes.CDLL:
     lib.ckks_hrot_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_hoisted_mac_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_rescale.argtypes = [_vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
+    lib.ckks_hrot_dh_mac.argtypes = [_vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.ckks_hrot_dh_mac_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_profile_enable.argtypes = [_vp, _int]
     lib.ckks_profile_read.argtypes = [_vp, _u32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_u64),
                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_u64)]
@@ -301,4 +303,26 @@ class Context:
         ws = self.workspace(OP_RESCALE, batch, level)
         self._check(load().ckks_rescale(self.handle, level, _dev_ptr(ct), _dev_ptr(out), batch,
                                         ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def hrot_dh_mac(self, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor], pt: torch.Tensor,
+                    out: Optional[torch.Tensor] = None, level: Optional[int] = None) -> torch.Tensor:
+        """Double-hoisted rotate-MAC; pt [n_rot][level+K][N] on the level's extended basis."""
+        ell = self.L if level is None else level
+        n_rot = len(galois)
+        if len(rks) != n_rot or pt.numel() != n_rot * (ell + self.K) * self.N:
+            raise ValueError("one key and one extended-basis plaintext per rotation")
+        if out is None:
+            out = torch.empty_like(ct)
+        g = (ctypes.c_uint32 * n_rot)(*[int(x) for x in galois])
+        ptrs = (ctypes.c_void_p * n_rot)(*[_dev_ptr(k) for k in rks])
+        ws = self.workspace(OP_HROT_DH_MAC, n_rot, ell)
+        if level is None:
+            rc = load().ckks_hrot_dh_mac(self.handle, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp), ctypes.cast(ptrs, _vp),
+                                         _dev_ptr(pt), _dev_ptr(out), ws.data_ptr(), ws.numel(), _stream())
+        else:
+            rc = load().ckks_hrot_dh_mac_at(self.handle, ell, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
+                                            ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out), ws.data_ptr(),
+                                            ws.numel(), _stream())
+        self._check(rc)
         return out

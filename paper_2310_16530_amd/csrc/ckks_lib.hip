@@ -92,7 +92,7 @@ struct SharedLayout {
     size_t tw_int, tw_fp, pc, sc_plain, sc_dn, dn_hatinv, end;
 };
 struct LevelLayout {
-    size_t sc_up, up_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, dn_chat_fp, dn_fp_ok, pinv, end;
+    size_t sc_up, up_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, dn_chat_fp, dn_fp_ok, pinv, pmod, end;
 };
 struct RescaleLayout {
     size_t sc_dn, dn_chat, dn_chat_fp, dn_fp_ok, pinv, end;
@@ -134,6 +134,7 @@ static LevelLayout level_layout(size_t base, u32 ell, u32 K, u32 alpha) {
     l.dn_chat_fp = t.take(K1 * ell * 2 * sizeof(double));
     l.dn_fp_ok = t.take(ell * sizeof(u32));
     l.pinv = t.take(ell * sizeof(PinvConst));
+    l.pmod = t.take(ell * sizeof(u64));
     l.end = t.o;
     return l;
 }
@@ -467,6 +468,7 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         double* dn_chat_fp = (double*)(hb + ll.dn_chat_fp);
         u32* dn_fp_ok = (u32*)(hb + ll.dn_fp_ok);
         PinvConst* pinv = (PinvConst*)(hb + ll.pinv);
+        u64* pmod = (u64*)(hb + ll.pmod);
         for (u32 j = 0; j < beta; j++) {  // ModUp constants of digit j = limbs [lo, hi)
             const u32 lo = j * alpha, hi = (j + 1) * alpha < ell ? (j + 1) * alpha : ell;
             const std::vector<u64> digit(c->primes.begin() + lo, c->primes.begin() + hi);
@@ -500,7 +502,8 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
                 dn_chat_fp[((size_t)k * ell + i) * 2 + 1] = pc[i].fp ? (double)h_mulmod(hatb, (1ull << 30) % qi, qi) : 0.0;
             }
             dn_fp_ok[i] = (pc[i].fp && qi >= (1ull << 28)) ? 1 : 0;
-            const u64 pi = h_invmod(prod_except(specials, specials.size(), qi), qi);
+            pmod[i] = prod_except(specials, specials.size(), qi);
+            const u64 pi = h_invmod(pmod[i], qi);
             pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
         }
         View& v = c->level[ell];
@@ -519,6 +522,7 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         tb.dn_chat_fp = (const double*)(dbase + ll.dn_chat_fp);
         tb.dn_fp_ok = (const u32*)(dbase + ll.dn_fp_ok);
         tb.pinv = (const PinvConst*)(dbase + ll.pinv);
+        tb.pmod = (const u64*)(dbase + ll.pmod);
         tb.L = ell, tb.K = K, tb.dnum = beta, tb.alpha = alpha, tb.D = Dl, tb.Lfull = L;
     }
     // ---- one block per rescale step: a ModDown whose only "special" prime is q_{ell-1}
@@ -757,6 +761,13 @@ struct KsInnerL {
                      (std::string(", ") + std::to_string(OWN) + (HOISTED ? ", true" : ", false")).c_str());
     }
 };
+struct DhInnerL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const DhInnerArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((dh_inner_kernel<AR, A>), g, dim3(256), 0, s, a, tb, run);
+    }
+    static std::string name(const char* ar, int A) { return kname("dh_inner_kernel", ar, A, ""); }
+};
 template <int MODE>
 struct KsFinalL {
     template <class AR, int A>
@@ -830,6 +841,33 @@ static void launch_ks_inner(const View* c, const InnerArgs& a, hipStream_t s) {
             }
             return limbs;
         });
+}
+
+#define CKKS_DH_EPT 4
+struct DhAccumQL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const DhInnerArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((dh_accum_q_kernel<AR, CKKS_DH_EPT>), g, dim3(256), 0, s, a, tb, run);
+    }
+    static std::string name(const char* ar, int) {
+        return std::string("dh_accum_q_kernel<") + ar + ", " + std::to_string(CKKS_DH_EPT) + ">";
+    }
+};
+
+static void launch_dh_inner(const View* c, const DhInnerArgs& a, hipStream_t s) {
+    const u64 n_rot = a.n_rot, acc = a.accumulate ? 2 : 0, dnum = c->dnum;
+    // per limb and rotation: the digits, the plaintext and both key components (and b on q-limbs); C_t written
+    // q-limbs, element-parallel: one workgroup per 256 * CKKS_DH_EPT slots of a limb
+    const u32 chunks = (1u << c->logN) / (256 * CKKS_DH_EPT);
+    for (const ClassRun& cr : class_runs(c, 0, c->L)) {
+        const LimbRun run = {cr.first, cr.count};
+        ProfScope ps(c, c->sh->prof.on ? DhAccumQL::name(cr.fp ? "FpAr" : "IntAr", 0) : std::string(),
+                     (n_rot * (3 * dnum + 2) + 2 + acc) * cr.count, s);
+        dispatch_kernel<DhAccumQL>(c, cr.fp, dim3(cr.count * chunks), s, a, run);
+    }
+    // special limbs: tiles, continuing with the first inverse pass of ModDown
+    launch_runs<DhInnerL>(c, c->L, c->D, 0, true, tiles_of(c), 1, a, s,
+                          [n_rot, acc, dnum](u32, u32 n) { return (n_rot * (3 * dnum + 1) + 2 + acc) * (u64)n; });
 }
 
 template <int MODE>
@@ -923,6 +961,10 @@ static int view_workspace_bytes(const View* v, int op, uint32_t batch_or_nrot, s
             *bytes = ks_workspace_words(v, 1, 1, chunk) * sizeof(u64);
             return CKKS_OK;
         }
+        case CKKS_OP_HROT_DH_MAC:
+            if (v->K == 0) return fail(v, CKKS_EUNSUPPORTED, "context has no special primes");
+            *bytes = ks_workspace_words(v, 1, 1, 1) * sizeof(u64);
+            return CKKS_OK;
         case CKKS_OP_RESCALE:  // last-limb coefficients [b][2][N] + converted part [b][2][ell-1][N]
             if (v->L < 2) return fail(v, CKKS_EINVAL, "rescale needs at least two limbs");
             *bytes = ((size_t)batch_or_nrot * 2 * v->L * sizeof(u64)) << v->logN;
@@ -1267,4 +1309,67 @@ extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32
                                      void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx) return CKKS_EINVAL;
     return ckks_hrot_hoisted_mac_at(ctx, ctx->L, d_ct, n_rot, h_galois, h_rk_ptrs, d_pt, d_out, d_ws, ws_bytes, stream);
+}
+
+// Double-hoisted variant: the plaintext products are accumulated in the extended basis over all
+// rotations (CKKS_DH_CHUNK of them per launch) and a single ModDown follows.
+extern "C" int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
+                                   const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt,
+                                   uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    if (!h_galois || !h_rk_ptrs) return fail(c, CKKS_EINVAL, "null host array");
+    if (n_rot == 0 || n_rot > 65535) return fail(c, CKKS_EINVAL, "n_rot out of range");
+    if (!d_ct || !d_pt || !d_out || misaligned(d_ct, 16) || misaligned(d_pt, 16) || misaligned(d_out, 16))
+        return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    if (!d_ws || misaligned(d_ws, 256)) return fail(c, CKKS_EINVAL, "workspace is null or not 256-byte aligned");
+    size_t need = 0;
+    int rc = view_workspace_bytes(c, CKKS_OP_HROT_DH_MAC, n_rot, &need);
+    if (rc) return rc;
+    if (ws_bytes < need) return fail(c, CKKS_ENOMEM, "workspace too small");
+    for (u32 r = 0; r < n_rot; r++) {
+        if (!h_rk_ptrs[r] || misaligned(h_rk_ptrs[r], 16)) return fail(c, CKKS_EINVAL, "null or misaligned key");
+        rc = check_galois(c, h_galois[r]);
+        if (rc) return rc;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const size_t N = (size_t)1 << c->logN;
+    const Workspace w = carve(c, d_ws, 1, 1, 1);
+    {  // hoisted part, as in ckks_hrot_hoisted_mac
+        const LimbSel src = {c->L, 1, c->L, c->L, 0, 0};
+        const LimbSel dst = {c->L, 1, c->L, 0, 0, 0};
+        InvContigArgs a1 = {d_ct, nullptr, w.x, src, dst, 1};
+        launch_inv_contig<INV_PLAIN>(c, a1, s);
+        decompose_extend(c, w, 1, s);
+        if (c->dnum > 1) {
+            FwdContigArgs q = {w.dt, LimbSel{c->L, c->dnum - 1, c->D, 0, 0, c->alpha}};
+            launch_fwd_contig(c, q, s);
+        }
+        FwdContigArgs p = {w.dt, LimbSel{c->K, c->dnum, c->D, c->L, c->L, 0}};
+        launch_fwd_contig(c, p, s);
+        join_side(c, s);  // the accumulation reads every limb of every digit
+    }
+    for (u32 r0 = 0; r0 < n_rot; r0 += CKKS_DH_CHUNK) {
+        const u32 nr = (n_rot - r0) < CKKS_DH_CHUNK ? (n_rot - r0) : CKKS_DH_CHUNK;
+        DhInnerArgs ia;
+        memset(&ia, 0, sizeof(ia));
+        for (u32 r = 0; r < nr; r++) ia.key[r] = h_rk_ptrs[r0 + r], ia.galois[r] = h_galois[r0 + r];
+        ia.dt = w.dt, ia.ct = d_ct, ia.pt = d_pt + (size_t)r0 * c->D * N, ia.cq = w.cq, ia.cp = w.cp;
+        ia.n_rot = nr, ia.accumulate = r0 ? 1 : 0;
+        launch_dh_inner(c, ia, s);
+    }
+    moddown_convert(c, w, 1, s);
+    FinalArgs fa;
+    memset(&fa, 0, sizeof(fa));
+    fa.cq = w.cq, fa.cq_L = c->L, fa.cv = w.cv, fa.out = d_out, fa.n_inst = 1;
+    launch_ks_final<FIN_KS>(c, fa, s);
+    return hip_check(c, "ckks_hrot_dh_mac");
+}
+
+extern "C" int ckks_hrot_dh_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, const uint32_t* h_galois,
+                                const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt, uint64_t* d_out, void* d_ws,
+                                size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    return ckks_hrot_dh_mac_at(ctx, ctx->L, d_ct, n_rot, h_galois, h_rk_ptrs, d_pt, d_out, d_ws, ws_bytes, stream);
 }

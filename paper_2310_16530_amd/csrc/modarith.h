@@ -153,6 +153,21 @@ struct IntAr {
         return mul_shoup_lazy(acc, m.r1, m.r1_p, m.q);
     }
     static HD u64 acc_canon(T fin, const Mod& m) { return csub(fin, m.q); }
+    // product of two canonical residues as an acc_mac operand carrying one more factor 2^-64 (in [0, 2q))
+    static HD T premul(u64 a, u64 b, const Mod& m) {
+        u128w p = {0, 0};
+        mac128(p, a, b);
+        return redc_lazy(p, m.q, m.qneg);
+    }
+    // finish of an accumulation whose operands came from premul: removes 2^-128
+    static HD T acc_finish2(T acc, const Mod& m) {
+        return mul_shoup_lazy(mul_shoup_lazy(acc, m.r1, m.r1_p, m.q), m.r1, m.r1_p, m.q);
+    }
+    // sum of two inverse-lazy words (both in [0, 2q))
+    static HD T lazy_add(T a, T b, const Mod& m) {
+        u64 s = a + b;
+        return s >= m.q2 ? s - m.q2 : s;
+    }
 };
 
 // ------------------------------------------------------------------------------- FpAr
@@ -234,4 +249,7 @@ struct FpAr {
         double r = fin < 0.0 ? fin + m.q : fin;
         return f64_to_u64(r);
     }
+    static HD T premul(u64 a, u64 b, const Mod& m) { return mulmod_lazy(u64_to_f64(a), u64_to_f64(b), m); }  // <= 0.875 q
+    static HD T acc_finish2(T acc, const Mod& m) { return reduce(acc, m); }
+    static HD T lazy_add(T a, T b, const Mod& m) { return reduce(a + b, m); }
 };

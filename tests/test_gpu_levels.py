@@ -177,3 +177,47 @@ def test_level_error_paths(orc):
         sizes.append(n.value)
     assert sizes == sorted(sizes) and sizes[-1] == ctx.workspace_bytes(binding.OP_HMULT_RELIN, 2)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ double hoisting
+@pytest.mark.parametrize("shape,n_rot", [((12, 6, 2, 3, 49, 59), 3), ((13, 6, 3, 2, 49, 59), 11), ((12, 4, 2, 2, 55, 59), 5),
+                                         ((12, 3, 1, 3, 35, 36), 37), ((12, 20, 1, 20, 49, 59), 4)])
+def test_double_hoisted_mac_parity(orc, shape, n_rot):
+    """Full level, a partial-digit level and a single limb; 37 rotations exceed one launch's chunk of 32."""
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(7000 + sum(shape))
+    gs = [synth.galois_element(r, ps.logN) for r in range(1, n_rot + 1)]
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    d_rks = [dev(k) for k in rks]
+    for ell in sorted({ps.L, max(ps.L - 1, 1), min(ps.alpha + 1, ps.L), 1}, reverse=True):
+        _say("double hoisting", shape, "level", ell)
+        basis = list(ps.q_primes[:ell]) + list(ps.p_primes)
+        ct = synth.uniform_residues(rng, basis[:ell], ps.N, lead=(2,))
+        pt = synth.uniform_residues(rng, basis, ps.N, lead=(n_rot,))
+        want = orc.hrot_dh_mac_level(ct, gs, rks, pt, P)
+        got = host(ctx.hrot_dh_mac(dev(ct), gs, d_rks, dev(pt), level=ell))
+        assert np.array_equal(got, want), ell
+        if ell == ps.L:
+            assert np.array_equal(host(ctx.hrot_dh_mac(dev(ct), gs, d_rks, dev(pt))), want)
+    # one rotation with the all-ones plaintext is that rotation of the singly hoisted path
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    unit = np.ones((1, ps.L + ps.K, ps.N), dtype=np.uint64)
+    one = host(ctx.hrot_dh_mac(dev(ct), gs[-1:], d_rks[-1:], dev(unit)))
+    assert np.array_equal(one, host(ctx.hrot_hoisted_mac(dev(ct), gs[-1:], d_rks[-1:], dev(unit[:, :ps.L]))))
+
+
+@pytest.mark.timeout(900)
+def test_config3_double_hoisted_full_size(orc):
+    """BASELINE config 3's shape (17 rotations, N = 2^16, L = 24, dnum = 4) through the double-hoisted call."""
+    ps = synth.CFG3
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(3, 5)
+    gs = [synth.galois_element(r, ps.logN) for r in synth.CFG3_ROTATIONS]
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    pt = synth.uniform_residues(rng, ps.primes, ps.N, lead=(len(gs),))
+    _say("cfg3 double hoisting: gpu")
+    got = host(ctx.hrot_dh_mac(dev(ct), gs, [dev(k) for k in rks], dev(pt)))
+    _say("cfg3 double hoisting: oracle")
+    assert np.array_equal(got, orc.hrot_dh_mac_level(ct, gs, rks, pt, P))
