@@ -205,7 +205,19 @@ def main():
             ctx.hrot_hoisted_mac(ct, gs, rks, pt, o)
         torch.cuda.synchronize()
         extra["hoisted_rot_mac_per_s"] = round(len(rots) * reps / (time.perf_counter() - a), 1)
-        del rks, pt
+        # the same 17 rotations double-hoisted: plaintexts on the extended basis, one ModDown for the sum
+        ptx = torch.stack([torch.roll(evk[0, 0], shifts=i, dims=-1) for i in range(len(rots))]).contiguous()
+        ctx.hrot_dh_mac(ct, gs, rks, ptx, o)
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for _ in range(reps):
+            ctx.hrot_dh_mac(ct, gs, rks, ptx, o)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - a) / reps
+        extra["double_hoisted_rot_mac_per_s"] = round(len(rots) / dt, 1)
+        # bytes that must come from HBM per rotation: the key (2*dnum*(L+K) limbs) and the plaintext (L+K limbs)
+        extra["double_hoisted_key_stream_GBps"] = round(len(rots) * (2 * dnum + 1) * D * 8 * N / dt / 1e9, 1)
+        del rks, pt, ptx
 
         # levels below L: rescale of the batch at level 24, and the HMult+relin -> rescale pair a CNN layer
         # issues; then HMult+relin at level 13 (digits of 6, 6 and 1 limbs) with the same full-level key

@@ -761,13 +761,6 @@ struct KsInnerL {
                      (std::string(", ") + std::to_string(OWN) + (HOISTED ? ", true" : ", false")).c_str());
     }
 };
-struct DhInnerL {
-    template <class AR, int A>
-    static void go(dim3 g, hipStream_t s, const DhInnerArgs& a, const Tables& tb, LimbRun run) {
-        hipLaunchKernelGGL((dh_inner_kernel<AR, A>), g, dim3(256), 0, s, a, tb, run);
-    }
-    static std::string name(const char* ar, int A) { return kname("dh_inner_kernel", ar, A, ""); }
-};
 template <int MODE>
 struct KsFinalL {
     template <class AR, int A>
@@ -844,30 +837,28 @@ static void launch_ks_inner(const View* c, const InnerArgs& a, hipStream_t s) {
 }
 
 #define CKKS_DH_EPT 4
-struct DhAccumQL {
+struct DhAccumL {
     template <class AR, int A>
     static void go(dim3 g, hipStream_t s, const DhInnerArgs& a, const Tables& tb, LimbRun run) {
-        hipLaunchKernelGGL((dh_accum_q_kernel<AR, CKKS_DH_EPT>), g, dim3(256), 0, s, a, tb, run);
+        hipLaunchKernelGGL((dh_accum_kernel<AR, CKKS_DH_EPT>), g, dim3(256), 0, s, a, tb, run);
     }
     static std::string name(const char* ar, int) {
-        return std::string("dh_accum_q_kernel<") + ar + ", " + std::to_string(CKKS_DH_EPT) + ">";
+        return std::string("dh_accum_kernel<") + ar + ", " + std::to_string(CKKS_DH_EPT) + ">";
     }
 };
 
-static void launch_dh_inner(const View* c, const DhInnerArgs& a, hipStream_t s) {
+// one workgroup per 256 * CKKS_DH_EPT slots of a limb, all limbs of the extended basis
+static void launch_dh_accum(const View* c, const DhInnerArgs& a, hipStream_t s) {
     const u64 n_rot = a.n_rot, acc = a.accumulate ? 2 : 0, dnum = c->dnum;
-    // per limb and rotation: the digits, the plaintext and both key components (and b on q-limbs); C_t written
-    // q-limbs, element-parallel: one workgroup per 256 * CKKS_DH_EPT slots of a limb
     const u32 chunks = (1u << c->logN) / (256 * CKKS_DH_EPT);
-    for (const ClassRun& cr : class_runs(c, 0, c->L)) {
+    for (const ClassRun& cr : class_runs(c, 0, c->D)) {
         const LimbRun run = {cr.first, cr.count};
-        ProfScope ps(c, c->sh->prof.on ? DhAccumQL::name(cr.fp ? "FpAr" : "IntAr", 0) : std::string(),
-                     (n_rot * (3 * dnum + 2) + 2 + acc) * cr.count, s);
-        dispatch_kernel<DhAccumQL>(c, cr.fp, dim3(cr.count * chunks), s, a, run);
+        u64 limbs = 0;  // per limb and rotation: the digits, the plaintext, both key components (and b on q-limbs); C_t written
+        for (u32 i = cr.first; i < cr.first + cr.count; i++) limbs += n_rot * (3 * dnum + 1 + (i < c->L ? 1 : 0)) + 2 + acc;
+        hipStream_t rs = (!cr.fp && c->sh->side.active) ? c->sh->side.stream : s;
+        ProfScope ps(c, c->sh->prof.on ? DhAccumL::name(cr.fp ? "FpAr" : "IntAr", 0) : std::string(), limbs, rs);
+        dispatch_kernel<DhAccumL>(c, cr.fp, dim3(cr.count * chunks), rs, a, run);
     }
-    // special limbs: tiles, continuing with the first inverse pass of ModDown
-    launch_runs<DhInnerL>(c, c->L, c->D, 0, true, tiles_of(c), 1, a, s,
-                          [n_rot, acc, dnum](u32, u32 n) { return (n_rot * (3 * dnum + 1) + 2 + acc) * (u64)n; });
 }
 
 template <int MODE>
@@ -1348,8 +1339,8 @@ extern "C" int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t
         }
         FwdContigArgs p = {w.dt, LimbSel{c->K, c->dnum, c->D, c->L, c->L, 0}};
         launch_fwd_contig(c, p, s);
-        join_side(c, s);  // the accumulation reads every limb of every digit
     }
+    // the special-limb chain (still on the side stream when overlap is on) only reads its own limbs
     for (u32 r0 = 0; r0 < n_rot; r0 += CKKS_DH_CHUNK) {
         const u32 nr = (n_rot - r0) < CKKS_DH_CHUNK ? (n_rot - r0) : CKKS_DH_CHUNK;
         DhInnerArgs ia;
@@ -1357,7 +1348,12 @@ extern "C" int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t
         for (u32 r = 0; r < nr; r++) ia.key[r] = h_rk_ptrs[r0 + r], ia.galois[r] = h_galois[r0 + r];
         ia.dt = w.dt, ia.ct = d_ct, ia.pt = d_pt + (size_t)r0 * c->D * N, ia.cq = w.cq, ia.cp = w.cp;
         ia.n_rot = nr, ia.accumulate = r0 ? 1 : 0;
-        launch_dh_inner(c, ia, s);
+        launch_dh_accum(c, ia, s);
+    }
+    {  // ModDown of the sum: first inverse pass of its special limbs, then the shared tail
+        const LimbSel sel = {c->K, 2, c->K, 0, c->L, 0};
+        InvContigArgs ic = {w.cp, nullptr, w.cp, sel, sel, 1};
+        launch_inv_contig<INV_PLAIN>(c, ic, s);
     }
     moddown_convert(c, w, 1, s);
     FinalArgs fa;

@@ -581,13 +581,12 @@ __global__ __launch_bounds__(256) void ks_inner_kernel(InnerArgs a, Tables tb, L
 }
 
 // ===================================================== double-hoisted rotate-multiply-accumulate
-// dh_inner_kernel: work item = (special limb i >= L, tile); dh_accum_q_kernel: the q-limbs.  Over the
-// rotations r of the launch and the digits j:
+// Over the rotations r of the launch and the digits j, on every limb i of the extended basis:
 //   C_t[i] += (pt_r[i] * sigma_{g_r}(Dh_j)[i]) * rk_r[j][t][i],   t = 0, 1,
 // with Dh_j read by gather from the transformed digits (the polynomial's own limb on the digit that
 // owns limb i).  On q-limbs the term pt_r * sigma_{g_r}(b) * P is added to C_0: ModDown divides it by
 // P exactly, which gives the same words as adding pt_r * sigma_{g_r}(b) after ModDown.
-// q-limbs: C_t stored canonical; special limbs: first inverse pass of the one ModDown that follows.
+// C_t is stored canonical, evaluation form: q-limbs in cq, special limbs in cp (ModDown follows).
 #define CKKS_DH_CHUNK 32
 struct DhInnerArgs {
     const u64* dt;   // [dnum][D][N] canonical evaluation form
@@ -596,126 +595,34 @@ struct DhInnerArgs {
     const u64* key[CKKS_DH_CHUNK];
     u32 galois[CKKS_DH_CHUNK];
     u64* cq;         // [2][L][N]
-    u64* cp;         // [2][K][N]
+    u64* cp;         // [2][K][N]  (evaluation form here; the inverse transform is a separate launch)
     u32 n_rot;
     u32 accumulate;  // add to what cq / cp already hold (a call with more rotations than one launch takes)
 };
 
-template <class AR, int A>
-__device__ __forceinline__ void dh_inner_body(const DhInnerArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile) {
-    typedef typename AR::T T;
-    const u32 N = 1u << tb.logN, tid = threadIdx.x, e0 = tid % 16, ch = tid / 16, r = tile * 16 + ch;
-    const u32 L = tb.L, D = tb.D;
-    const u32 pi = tb.phys(i), Dkey = tb.Lfull + tb.K;
-    const PrimeConst pc = tb.pc[pi];
-    const typename AR::Mod m = AR::mod(pc);
-    const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
-    const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
-    u64* lrow = lds + ch * 272;
-    const u32 row_off = r * 256;
-    const u32 own_digit = i < L ? i / tb.alpha : 0xffffffffu;
-    const u64 pmod = i < L ? tb.pmod[i] : 0;
-    T acc0[16], acc1[16];
-#pragma unroll
-    for (int k = 0; k < 16; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
-    u32 terms = 0;  // products added since the last fold (FpAr sums at most 8 of them, each <= 0.875 q)
-    for (u32 rr = 0; rr < a.n_rot; rr++) {
-        const u64* key = a.key[rr] + (size_t)pi * N + row_off;
-        const u32 gal = a.galois[rr];
-        const u64* ptp = a.pt + ((size_t)rr * D + i) * N + row_off;
-        u64 ptv[16];
-        u32 idx[16];
-#pragma unroll
-        for (int k = 0; k < 16; k++) {
-            ptv[k] = __builtin_nontemporal_load(&ptp[k * 16 + e0]);
-            idx[k] = eval_perm(row_off + k * 16 + e0, gal, tb.logN);
-        }
-        for (u32 j = 0; j < tb.dnum; j++) {
-            const u64* k0 = key + ((size_t)j * 2 + 0) * Dkey * N;
-            const u64* k1 = key + ((size_t)j * 2 + 1) * Dkey * N;
-            u64 kv0[16], kv1[16];
-            if constexpr (AR::is_fp) {  // key loads in flight during the gather and the plaintext product
-#pragma unroll
-                for (int k = 0; k < 16; k++)
-                    kv0[k] = __builtin_nontemporal_load(&k0[k * 16 + e0]), kv1[k] = __builtin_nontemporal_load(&k1[k * 16 + e0]);
-            }
-            const u64* src = j == own_digit ? a.ct + ((size_t)L + i) * N : a.dt + ((size_t)j * D + i) * N;
-            T w[16];
-#pragma unroll
-            for (int k = 0; k < 16; k++) w[k] = AR::premul(src[idx[k]], ptv[k], m);
-#pragma unroll
-            for (int k = 0; k < 16; k++) {
-                if constexpr (!AR::is_fp)
-                    kv0[k] = __builtin_nontemporal_load(&k0[k * 16 + e0]), kv1[k] = __builtin_nontemporal_load(&k1[k * 16 + e0]);
-                AR::acc_mac(acc0[k], w[k], kv0[k], m);
-                AR::acc_mac(acc1[k], w[k], kv1[k], m);
-            }
-            if ((++terms & 7) == 0) {
-#pragma unroll
-                for (int k = 0; k < 16; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
-            }
-        }
-        if (i < L) {
-            const u64* bp = a.ct + (size_t)i * N;
-#pragma unroll
-            for (int k = 0; k < 16; k++) AR::acc_mac(acc0[k], AR::premul(bp[idx[k]], ptv[k], m), pmod, m);
-            if ((++terms & 7) == 0) {
-#pragma unroll
-                for (int k = 0; k < 16; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
-            }
-        }
-    }
-    if (i < L) {
-        u64* o0 = a.cq + ((size_t)0 * L + i) * N + row_off;
-        u64* o1 = a.cq + ((size_t)1 * L + i) * N + row_off;
-#pragma unroll
-        for (int k = 0; k < 16; k++) {
-            u64 r0 = AR::acc_canon(AR::acc_finish2(acc0[k], m), m), r1 = AR::acc_canon(AR::acc_finish2(acc1[k], m), m);
-            if (a.accumulate) r0 = addmod(r0, o0[k * 16 + e0], pc.q), r1 = addmod(r1, o1[k * 16 + e0], pc.q);
-            o0[k * 16 + e0] = r0;
-            o1[k * 16 + e0] = r1;
-        }
-    } else {
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-            T x[16];
-#pragma unroll
-            for (int k = 0; k < 16; k++) x[k] = AR::acc_finish2(t ? acc1[k] : acc0[k], m);
-            exchange_ca_to_cb<AR>(x, lrow, e0);
-            NttCore<AR, A>::inv_contig(x, lrow, e0, r, ti, tf, N, m);
-            u64* o = a.cp + ((size_t)t * tb.K + (i - L)) * N + row_off;
-#pragma unroll
-            for (int k = 0; k < 16; k++) {
-                T v = AR::round_reduce(x[k], m);
-                if (a.accumulate) v = AR::lazy_add(v, AR::from_raw(o[k * 16 + e0]), m);
-                o[k * 16 + e0] = AR::to_raw(v);
-            }
-        }
-    }
-}
-
-// The q-limbs need no transform here, so they run element-parallel with few registers per lane
-// (many waves in flight hide the gather and key-load latency): work item = (limb i < L, 256 * EPT
-// consecutive slots), lane `tid` owns slots base + k * 256 + tid.
+// No transform is involved, so the work is element-parallel with few registers per lane (many waves in
+// flight hide the gather and key-load latency): work item = (limb i, 256 * EPT consecutive slots), lane
+// `tid` owns slots base + k * 256 + tid.
 template <class AR, int EPT>
-__global__ __launch_bounds__(256) void dh_accum_q_kernel(DhInnerArgs a, Tables tb, LimbRun run) {
+__global__ __launch_bounds__(256) void dh_accum_kernel(DhInnerArgs a, Tables tb, LimbRun run) {
     typedef typename AR::T T;
     const u32 N = 1u << tb.logN, tid = threadIdx.x, L = tb.L, D = tb.D;
     const u32 chunks = N / (256 * EPT);
     const u32 i = run.first + blockIdx.x / chunks, base = (blockIdx.x % chunks) * (256 * EPT) + tid;
     if (i >= run.first + run.count) return;
-    const u32 Dkey = tb.Lfull + tb.K;
-    const PrimeConst pc = tb.pc[i];
+    const u32 Dkey = tb.Lfull + tb.K, pi = tb.phys(i);
+    const bool is_q = i < L;
+    const PrimeConst pc = tb.pc[pi];
     const typename AR::Mod m = AR::mod(pc);
-    const u32 own_digit = i / tb.alpha;
-    const u64 pmod = tb.pmod[i];
-    const u64* bp = a.ct + (size_t)i * N;
+    const u32 own_digit = is_q ? i / tb.alpha : 0xffffffffu;
+    const u64 pmod = is_q ? tb.pmod[i] : 0;
+    const u64* bp = a.ct + (size_t)(is_q ? i : 0) * N;
     T acc0[EPT], acc1[EPT];
 #pragma unroll
     for (int k = 0; k < EPT; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
     u32 terms = 0;
     for (u32 rr = 0; rr < a.n_rot; rr++) {
-        const u64* key = a.key[rr] + (size_t)i * N + base;
+        const u64* key = a.key[rr] + (size_t)pi * N + base;
         const u32 gal = a.galois[rr];
         const u64* ptp = a.pt + ((size_t)rr * D + i) * N + base;
         u64 ptv[EPT];
@@ -747,15 +654,17 @@ __global__ __launch_bounds__(256) void dh_accum_q_kernel(DhInnerArgs a, Tables t
                 for (int k = 0; k < EPT; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
             }
         }
+        if (is_q) {
 #pragma unroll
-        for (int k = 0; k < EPT; k++) AR::acc_mac(acc0[k], AR::premul(bp[idx[k]], ptv[k], m), pmod, m);
-        if ((++terms & 7) == 0) {
+            for (int k = 0; k < EPT; k++) AR::acc_mac(acc0[k], AR::premul(bp[idx[k]], ptv[k], m), pmod, m);
+            if ((++terms & 7) == 0) {
 #pragma unroll
-            for (int k = 0; k < EPT; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
+                for (int k = 0; k < EPT; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
+            }
         }
     }
-    u64* o0 = a.cq + (size_t)i * N + base;
-    u64* o1 = a.cq + ((size_t)L + i) * N + base;
+    u64* o0 = (is_q ? a.cq + (size_t)i * N : a.cp + (size_t)(i - L) * N) + base;
+    u64* o1 = (is_q ? a.cq + ((size_t)L + i) * N : a.cp + ((size_t)tb.K + (i - L)) * N) + base;
 #pragma unroll
     for (int k = 0; k < EPT; k++) {
         u64 r0 = AR::acc_canon(AR::acc_finish2(acc0[k], m), m), r1 = AR::acc_canon(AR::acc_finish2(acc1[k], m), m);
@@ -763,15 +672,6 @@ __global__ __launch_bounds__(256) void dh_accum_q_kernel(DhInnerArgs a, Tables t
         o0[k * 256] = r0;
         o1[k * 256] = r1;
     }
-}
-
-template <class AR, int A>
-__global__ __launch_bounds__(256) void dh_inner_kernel(DhInnerArgs a, Tables tb, LimbRun run) {
-    __shared__ u64 lds[NTT_LDS_WORDS];
-    constexpr u32 TILES = (1u << A) / 16;
-    u32 group, inst;
-    if (!xcd_decode(blockIdx.x, 1, run.count * TILES, group, inst)) return;
-    dh_inner_body<AR, A>(a, tb, lds, run.first + group / TILES, group % TILES);
 }
 
 // ======================================================================== final combine

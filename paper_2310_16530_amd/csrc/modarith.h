@@ -163,11 +163,6 @@ struct IntAr {
     static HD T acc_finish2(T acc, const Mod& m) {
         return mul_shoup_lazy(mul_shoup_lazy(acc, m.r1, m.r1_p, m.q), m.r1, m.r1_p, m.q);
     }
-    // sum of two inverse-lazy words (both in [0, 2q))
-    static HD T lazy_add(T a, T b, const Mod& m) {
-        u64 s = a + b;
-        return s >= m.q2 ? s - m.q2 : s;
-    }
 };
 
 // ------------------------------------------------------------------------------- FpAr
@@ -251,5 +246,4 @@ struct FpAr {
     }
     static HD T premul(u64 a, u64 b, const Mod& m) { return mulmod_lazy(u64_to_f64(a), u64_to_f64(b), m); }  // <= 0.875 q
     static HD T acc_finish2(T acc, const Mod& m) { return reduce(acc, m); }
-    static HD T lazy_add(T a, T b, const Mod& m) { return reduce(a + b, m); }
 };
