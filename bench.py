@@ -55,7 +55,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--no-extras", action="store_true", help="skip the NTT and hoisted-rotation extras")
+    ap.add_argument("--no-extras", action="store_true", help="skip every extra measurement")
+    ap.add_argument("--extras", default="overlap,ntt,hoisted,levels",
+                    help="comma-separated extra measurements: overlap (two-stream step), ntt (config 1), hoisted "
+                         "(config 3 rotations, singly and doubly hoisted), levels (rescale, level-13 operations)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -158,38 +161,58 @@ def main():
         torch.cuda.synchronize()
         extra[name] = round(B * args.steps / (time.perf_counter() - a), 1)
 
-    if not args.no_extras:
+    EXTRA_GROUPS = ("overlap", "ntt", "hoisted", "levels")
+    groups = () if args.no_extras else tuple(g for g in args.extras.split(",") if g)
+    for gname in groups:
+        if gname not in EXTRA_GROUPS:
+            print("bench.py: unknown --extras group %r (choose from %s)" % (gname, ", ".join(EXTRA_GROUPS)), file=sys.stderr)
+            sys.exit(2)
+    extra_kernels = {}
+
+    def timed(fn, reps=None, label=None):
+        """Seconds per call over `reps` calls after 2 warm-up calls; with a label, a second event-timed pass
+        records the per-kernel averages of that operation."""
+        reps = reps or args.steps
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        a0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        per = (time.perf_counter() - a0) / reps
+        if label:
+            ctx.profile_enable(True)
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            pr = ctx.profile_read()
+            ctx.profile_enable(False)
+            extra_kernels[label] = {k: {"launches_per_call": n / reps, "avg_us": round(1e3 * ms / n, 2),
+                                        "alg_GBps": round(nb / ms / 1e6, 1)} for k, (n, ms, nb) in pr.items() if n}
+        return per
+
+    if "overlap" in groups:
         # the same step with the optional two-stream execution inside each call (integer special-limb launches
         # beside the floating-point launches)
         ctx.set_overlap(True)
-        for _ in range(2):
-            step()
-        torch.cuda.synchronize()
-        a = time.perf_counter()
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        extra["key_switches_per_s_with_overlap"] = round(ks_per_step * args.steps / (time.perf_counter() - a), 1)
+        extra["key_switches_per_s_with_overlap"] = round(ks_per_step / timed(step), 1)
         ctx.set_overlap(False)
 
+    if "ntt" in groups:
         # config 1: 16 polynomials x 24 limbs, forward and inverse
         x = dev(synth.uniform_residues(rng, ps.q_primes, N, lead=(synth.CFG1_BATCH,)))
         limbs = synth.CFG1_BATCH * L
         for name, inv in (("ntt_fwd_limbs_per_s", False), ("ntt_inv_limbs_per_s", True)):
-            for _ in range(2):
-                ctx.ntt(x, 0, inverse=inv)
-            torch.cuda.synchronize()
-            a = time.perf_counter()
-            for _ in range(args.steps):
-                ctx.ntt(x, 0, inverse=inv)
-            torch.cuda.synchronize()
-            dt = (time.perf_counter() - a) / args.steps
+            dt = timed(lambda: ctx.ntt(x, 0, inverse=inv), label="ntt_inv" if inv else "ntt_fwd")
             extra[name] = round(limbs / dt, 1)
             # one transform reads and writes every limb once: 2 * 8N bytes per limb (compulsory)
             extra[name.replace("limbs_per_s", "effective_GBps")] = round(limbs * 2 * 8 * N / dt / 1e9, 1)
             # the two passes together move every limb four times
             extra[name.replace("limbs_per_s", "pass_traffic_GBps")] = round(limbs * 4 * 8 * N / dt / 1e9, 1)
         del x
+
+    if "hoisted" in groups:
         # config 3: 17 hoisted rotations with plaintext MAC (keys are rolled copies of one uniform key)
         rots = synth.CFG3_ROTATIONS
         gs = [synth.galois_element(r, ps.logN) for r in rots]
@@ -197,42 +220,22 @@ def main():
         pt = torch.stack([torch.roll(ct1[0, 0], shifts=i, dims=-1) for i in range(len(rots))]).contiguous()
         ct = ct1[0].contiguous()
         o = torch.empty_like(ct)
-        ctx.hrot_hoisted_mac(ct, gs, rks, pt, o)
-        torch.cuda.synchronize()
-        a = time.perf_counter()
         reps = max(1, args.steps // 4)
-        for _ in range(reps):
-            ctx.hrot_hoisted_mac(ct, gs, rks, pt, o)
-        torch.cuda.synchronize()
-        extra["hoisted_rot_mac_per_s"] = round(len(rots) * reps / (time.perf_counter() - a), 1)
+        dt = timed(lambda: ctx.hrot_hoisted_mac(ct, gs, rks, pt, o), reps, "hoisted_rot_mac")
+        extra["hoisted_rot_mac_per_s"] = round(len(rots) / dt, 1)
         # the same 17 rotations double-hoisted: plaintexts on the extended basis, one ModDown for the sum
         ptx = torch.stack([torch.roll(evk[0, 0], shifts=i, dims=-1) for i in range(len(rots))]).contiguous()
-        ctx.hrot_dh_mac(ct, gs, rks, ptx, o)
-        torch.cuda.synchronize()
-        a = time.perf_counter()
-        for _ in range(reps):
-            ctx.hrot_dh_mac(ct, gs, rks, ptx, o)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - a) / reps
+        dt = timed(lambda: ctx.hrot_dh_mac(ct, gs, rks, ptx, o), reps, "double_hoisted_rot_mac")
         extra["double_hoisted_rot_mac_per_s"] = round(len(rots) / dt, 1)
         # bytes that must come from HBM per rotation: the key (2*dnum*(L+K) limbs) and the plaintext (L+K limbs)
         extra["double_hoisted_key_stream_GBps"] = round(len(rots) * (2 * dnum + 1) * D * 8 * N / dt / 1e9, 1)
         del rks, pt, ptx
 
+    if "levels" in groups:
         # levels below L: rescale of the batch at level 24, and the HMult+relin -> rescale pair a CNN layer
         # issues; then HMult+relin at level 13 (digits of 6, 6 and 1 limbs) with the same full-level key
-        def timed(fn):
-            for _ in range(2):
-                fn()
-            torch.cuda.synchronize()
-            a0 = time.perf_counter()
-            for _ in range(args.steps):
-                fn()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - a0) / args.steps
-
         rs_out = torch.empty((B, 2, L - 1, N), dtype=ct1.dtype, device=ct1.device)
-        dt = timed(lambda: ctx.rescale(L, ct1, rs_out))
+        dt = timed(lambda: ctx.rescale(L, ct1, rs_out), label="rescale")
         extra["rescale_per_s"] = round(B / dt, 1)
         # compulsory bytes of a rescale: read 2L limbs, write 2(L-1)
         extra["rescale_effective_GBps"] = round(B * (4 * L - 2) * 8 * N / dt / 1e9, 1)
@@ -288,6 +291,7 @@ def main():
         "cpu_baseline": cpu,
         "kernels": kernels,
         "extra": extra,
+        "extra_kernels": extra_kernels,
     }
     print(json.dumps(line))
 
