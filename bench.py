@@ -56,8 +56,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-extras", action="store_true", help="skip every extra measurement")
-    ap.add_argument("--extras", default="overlap,ntt,hoisted,levels",
-                    help="comma-separated extra measurements: overlap (two-stream step), ntt (config 1), hoisted "
+    ap.add_argument("--extras", default="overlap,concurrent,ntt,hoisted,levels",
+                    help="comma-separated extra measurements: overlap (two streams inside each call), concurrent "
+                         "(HMult and HRot batches on two caller streams), ntt (config 1), hoisted "
                          "(config 3 rotations, singly and doubly hoisted), levels (rescale, level-13 operations)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
@@ -161,7 +162,7 @@ def main():
         torch.cuda.synchronize()
         extra[name] = round(B * args.steps / (time.perf_counter() - a), 1)
 
-    EXTRA_GROUPS = ("overlap", "ntt", "hoisted", "levels")
+    EXTRA_GROUPS = ("overlap", "concurrent", "ntt", "hoisted", "levels")
     groups = () if args.no_extras else tuple(g for g in args.extras.split(",") if g)
     for gname in groups:
         if gname not in EXTRA_GROUPS:
@@ -198,6 +199,26 @@ def main():
         ctx.set_overlap(True)
         extra["key_switches_per_s_with_overlap"] = round(ks_per_step / timed(step), 1)
         ctx.set_overlap(False)
+
+    if "concurrent" in groups:
+        # the two halves of the step are independent: HMult batch and HRot batch issued on two streams, each with
+        # its own context (tables and workspace), so that compute-bound and memory-bound kernels of the two
+        # operations overlap
+        ctx2 = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+        st = [torch.cuda.Stream(), torch.cuda.Stream()]
+
+        def step2():
+            for q_ in st:
+                q_.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(st[0]):
+                ctx.hmult_relin(ct1, ct2, evk, out1)
+            with torch.cuda.stream(st[1]):
+                ctx2.hrot(ct1, g, rk, out2)
+            for q_ in st:
+                torch.cuda.current_stream().wait_stream(q_)
+
+        extra["key_switches_per_s_two_op_streams"] = round(ks_per_step / timed(step2), 1)
+        del ctx2
 
     if "ntt" in groups:
         # config 1: 16 polynomials x 24 limbs, forward and inverse

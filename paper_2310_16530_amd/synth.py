@@ -103,6 +103,56 @@ class ParamSet:
         return self.q_primes + self.p_primes
 
 
+@dataclass(frozen=True)
+class ExplicitParamSet:
+    """A parameter set given by its primes (same attributes as ParamSet), for chains that mix prime sizes."""
+    name: str
+    logN: int
+    dnum: int
+    q_primes: Tuple[int, ...]
+    p_primes: Tuple[int, ...]
+
+    @property
+    def N(self) -> int:
+        return 1 << self.logN
+
+    @property
+    def L(self) -> int:
+        return len(self.q_primes)
+
+    @property
+    def K(self) -> int:
+        return len(self.p_primes)
+
+    @property
+    def alpha(self) -> int:
+        return self.L // self.dnum
+
+    @property
+    def primes(self) -> Tuple[int, ...]:
+        return self.q_primes + self.p_primes
+
+
+def mixed_params(logN: int, q_floors: Sequence[int], p_floors: Sequence[int], dnum: int,
+                 name: str = "mixed") -> ExplicitParamSet:
+    """Limb i is the next unused prime = 1 mod 2N above floor i; a floor below 64 means 2**floor."""
+    used: List[int] = []
+
+    def pick(floor: int) -> int:
+        bound = (1 << floor) if floor < 64 else floor
+        k = 1
+        while True:
+            cand = primes_above(bound, 2 << logN, k)[-1]
+            if cand not in used:
+                used.append(cand)
+                return cand
+            k += 1
+
+    q = tuple(pick(f) for f in q_floors)
+    pp = tuple(pick(f) for f in p_floors)
+    return ExplicitParamSet(name, logN, dnum, q, pp)
+
+
 # The five workload shapes (BASELINE configs 0..4).
 CFG0 = ParamSet("cfg0_hmult_n12", 12, 3, 1, 3, 35, 36)
 CFG1 = ParamSet("cfg1_ntt_n16_l24", 16, 24, 0, 1, 49, 59)

@@ -1,0 +1,101 @@
+"""Parity on prime chains that mix sizes and arithmetic classes (needs an MI355X).
+
+The benchmark chains are uniform (50-bit q-limbs, 60-bit special limbs).  Here neighbouring limbs
+alternate between the FP64 and the integer arithmetic, some conversion targets are too small for
+their sources to be converted on the FP64 pipe (the library then converts them with integers), one
+prime lies below 2^28, and two pairs straddle the bound between the two arithmetics.  Everything is
+compared bit for bit with the oracle; nothing here depends on noise being small.
+"""
+import numpy as np
+import pytest
+
+from paper_2310_16530_amd import synth
+
+from test_gpu_parity import dev, gpu_ctx, host, orc_params
+
+pytestmark = pytest.mark.gpu
+
+FP_LIMIT = 3 << 48
+CHAINS = {
+    "alternating": (12, [36, 50, 30, 27, 55, 49], [59, 40], 3),
+    "big_small": (13, [60, 28, 49, 49], [36, 36, 60], 2),
+    "class_boundary": (12, [FP_LIMIT - (1 << 20), FP_LIMIT - (1 << 20), FP_LIMIT, FP_LIMIT], [FP_LIMIT - (1 << 22), 59], 2),
+    "small_special": (14, [50, 50, 50], [30, 31, 32], 1),
+}
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+@pytest.mark.parametrize("name", sorted(CHAINS))
+def test_every_entry_point_on_a_mixed_chain(orc, name):
+    logN, qf, pf, dnum = CHAINS[name]
+    ps = synth.mixed_params(logN, qf, pf, dnum, name)
+    if name == "class_boundary":
+        assert [p < FP_LIMIT for p in ps.primes] == [True, True, False, False, True, False]
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(len(name) * 1000 + logN)
+    L, K, N, D = ps.L, ps.K, ps.N, ps.L + ps.K
+    _say(name, "transforms")
+    x = synth.uniform_residues(rng, ps.primes, N, lead=(2,))
+    for i, p in enumerate(ps.primes):
+        x[1, i, :5] = p - 1
+    assert np.array_equal(host(ctx.ntt(dev(x))), orc.ntt_batch(x, P, 0))
+    assert np.array_equal(host(ctx.intt(dev(x))), orc.ntt_batch(x, P, 0, inverse=True))
+    _say(name, "conversions")
+    c = synth.uniform_residues(rng, ps.q_primes, N, lead=(2,))
+    up = host(ctx.modup(dev(c)))
+    for b in range(2):
+        assert np.array_equal(up[b], orc.modup(c[b], P))
+    assert np.array_equal(host(ctx.moddown(dev(x)))[0], orc.moddown(x[0], P))
+    key = synth.uniform_residues(rng, ps.primes, N, lead=(ps.dnum, 2))
+    d_key = dev(key)
+    g = synth.galois_element(7, logN)
+    gs = [synth.galois_element(r, logN) for r in (1, -1, 5)]
+    rks = [synth.uniform_residues(rng, ps.primes, N, lead=(ps.dnum, 2)) for _ in gs]
+    d_rks = [dev(k) for k in rks]
+    for ell in range(L, 0, -1):
+        _say(name, "level", ell)
+        q = ps.q_primes[:ell]
+        ct1 = synth.uniform_residues(rng, q, N, lead=(2, 2))
+        ct2 = synth.uniform_residues(rng, q, N, lead=(2, 2))
+        ks = host(ctx.keyswitch_at(ell, dev(ct1[:, 0]), d_key))
+        hm = host(ctx.hmult_relin_at(ell, dev(ct1), dev(ct2), d_key))
+        hr = host(ctx.hrot_at(ell, dev(ct1), g, d_key))
+        for b in range(2):
+            assert np.array_equal(ks[b], orc.keyswitch_level(ct1[b, 0], key, P)), (ell, b)
+            assert np.array_equal(hm[b], orc.hmult_relin_level(ct1[b], ct2[b], key, P)), (ell, b)
+            assert np.array_equal(hr[b], orc.hrot_level(ct1[b], g, key, P)), (ell, b)
+        basis = list(q) + list(ps.p_primes)
+        pt = synth.uniform_residues(rng, basis, N, lead=(len(gs),))
+        ho = host(ctx.hrot_hoisted_mac_at(ell, dev(ct1[0]), gs, d_rks, dev(pt[:, :ell])))
+        assert np.array_equal(ho, orc.hrot_hoisted_mac_level(ct1[0], gs, rks, np.ascontiguousarray(pt[:, :ell]), P)), ell
+        dh = host(ctx.hrot_dh_mac(dev(ct1[0]), gs, d_rks, dev(pt), level=ell))
+        assert np.array_equal(dh, orc.hrot_dh_mac_level(ct1[0], gs, rks, pt, P)), ell
+        if ell >= 2:
+            assert np.array_equal(host(ctx.rescale(ell, dev(ct1))), orc.rescale(ct1, P)), ell
+
+
+def test_largest_supported_chain(orc):
+    """L + K = 64 primes (the limit), digits of 8 limbs and 8 special limbs (both limits), N = 2^12."""
+    ps = synth.small_params(12, 56, 8, 7)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(64)
+    key = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    d_key = dev(key)
+    g = synth.galois_element(3, ps.logN)
+    for ell in (56, 51, 9):
+        _say("largest chain, level", ell)
+        q = ps.q_primes[:ell]
+        ct1 = synth.uniform_residues(rng, q, ps.N, lead=(2, 2))
+        ct2 = synth.uniform_residues(rng, q, ps.N, lead=(2, 2))
+        hm = host(ctx.hmult_relin_at(ell, dev(ct1), dev(ct2), d_key))
+        hr = host(ctx.hrot_at(ell, dev(ct1), g, d_key))
+        for b in range(2):
+            assert np.array_equal(hm[b], orc.hmult_relin_level(ct1[b], ct2[b], key, P)), (ell, b)
+            assert np.array_equal(hr[b], orc.hrot_level(ct1[b], g, key, P)), (ell, b)
+        pt = synth.uniform_residues(rng, list(q) + list(ps.p_primes), ps.N, lead=(2,))
+        dh = host(ctx.hrot_dh_mac(dev(ct1[0]), [g, 1], [d_key, d_key], dev(pt), level=ell))
+        assert np.array_equal(dh, orc.hrot_dh_mac_level(ct1[0], [g, 1], [key, key], pt, P)), ell
+        assert np.array_equal(host(ctx.rescale(ell, dev(ct1))), orc.rescale(ct1, P)), ell
