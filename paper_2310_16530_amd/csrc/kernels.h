@@ -744,6 +744,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             }
             return;
         }
+        double b1v[16], b2v[16];  // HMult: b1, b2 are read once and serve both components
 #pragma unroll
         for (int t = 0; t < 2; t++) {
             T v[16];
@@ -761,11 +762,12 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                 double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[e])) - v[k], pinv.d, fm);
                 if (MODE == FIN_HMULT) {
                     if (t == 0) {
-                        ks += FpAr::mulmod_lazy(u64_to_f64(a.ct1[o0 + e]), u64_to_f64(a.ct2[o0 + e]), fm);
+                        b1v[k] = u64_to_f64(__builtin_nontemporal_load(&a.ct1[o0 + e]));
+                        b2v[k] = u64_to_f64(__builtin_nontemporal_load(&a.ct2[o0 + e]));
+                        ks += FpAr::mulmod_lazy(b1v[k], b2v[k], fm);
                     } else {
-                        const double b1 = u64_to_f64(a.ct1[o0 + e]), b2 = u64_to_f64(a.ct2[o0 + e]);
-                        ks += FpAr::mulmod_lazy(u64_to_f64(a.ct1[o1 + e]), b2, fm) +
-                              FpAr::mulmod_lazy(u64_to_f64(a.ct2[o1 + e]), b1, fm);
+                        ks += FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct1[o1 + e])), b2v[k], fm) +
+                              FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct2[o1 + e])), b1v[k], fm);
                     }
                 } else if (MODE == FIN_HROT) {
                     if (t == 0) ks += u64_to_f64(a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[0], tb.logN)]);
