@@ -354,6 +354,29 @@ def dh_mac_noise_bound(P: Params, s_l1: int, pt_l1_sum: int, level: Optional[int
     return first + P.K * (1 + s_l1) + 1
 
 
+def moddown_merged(x: np.ndarray, P: Params) -> np.ndarray:
+    """[ell+K][N] coefficient form on the level's extended basis -> [ell-1][N]: division by P*q_{ell-1}."""
+    x = np.ascontiguousarray(x, dtype=np.uint64)
+    ell = x.shape[0] - P.K
+    assert 2 <= ell <= P.L
+    vp = _arr_u64(P.primes[:ell] + P.primes[P.L:])
+    out = np.empty((ell - 1, P.N), dtype=np.uint64)
+    lib().orc_moddown_merged(_ptr(x), _ptr(out), _u32(P.logN), _u32(ell), _u32(P.K), _ptr(vp))
+    return out
+
+
+def hmult_relin_rescale_level(ct1: np.ndarray, ct2: np.ndarray, evk: np.ndarray, P: Params) -> np.ndarray:
+    """[2][ell][N] x [2][ell][N] -> [2][ell-1][N]: HMult + relinearisation + rescale with one merged division."""
+    ct1 = np.ascontiguousarray(ct1, dtype=np.uint64)
+    ct2 = np.ascontiguousarray(ct2, dtype=np.uint64)
+    evk = np.ascontiguousarray(evk, dtype=np.uint64)
+    ell = ct1.shape[1]
+    assert ell >= 2 and ct1.shape == ct2.shape == (2, ell, P.N) and evk.shape == (P.dnum, 2, P.L + P.K, P.N)
+    out = np.empty((2, ell - 1, P.N), dtype=np.uint64)
+    lib().orc_hmult_relin_rescale_level(_ptr(ct1), _ptr(ct2), _ptr(evk), _ptr(out), *_level_tail(P, ell))
+    return out
+
+
 # ------------------------------------------------------------- harness helpers
 def lift_signed(v: np.ndarray, primes: Sequence[int]) -> np.ndarray:
     """Small signed coefficients [N] -> canonical residues [len(primes)][N]."""

@@ -680,6 +680,87 @@ void orc_hrot_dh_mac_level(const uint64_t* ct, uint32_t n_rot, const uint32_t* g
     level_close(&v);
 }
 
+/* ------------------------------------------- ModDown merged with the rescale that follows it */
+/* Division by P * q_last in ONE floor-type step: the last active limb is treated as one more special
+ * limb.  in: [ell+K][N] coefficient form on the level's extended basis vprimes = q_0..q_{ell-1},
+ * p_0..p_{K-1}; S = {q_{ell-1}, p_0, .., p_{K-1}} = vprimes[ell-1 ..], PS its product;  out: [ell-1][N]:
+ *   out_i = (in_i - Conv_{S -> q_i}(in restricted to S)) * [PS^-1]_{q_i}  mod q_i,   i < ell-1,
+ * Conv the same uncorrected fast base conversion as everywhere else.  As an integer the result is
+ * floor(X / PS) - u with 0 <= u <= K.  Not bit-identical to ModDown followed by rescale (two floors with
+ * two overshoots), but never further than K+1 from it. */
+void orc_moddown_merged(const uint64_t* in, uint64_t* out, uint32_t logN, uint32_t ell, uint32_t K,
+                        const uint64_t* vprimes) {
+    size_t N = (size_t)1 << logN;
+    uint32_t T = ell - 1, ns = K + 1;
+#pragma omp parallel for schedule(dynamic)
+    for (long i = 0; i < (long)T; i++) {
+        uint64_t q = vprimes[i];
+        uint64_t* conv = (uint64_t*)malloc(sizeof(uint64_t) * N);
+        orc_conv(in + (size_t)T * N, N, N, vprimes + T, ns, q, conv);
+        uint64_t PS = 1;
+        for (uint32_t k = 0; k < ns; k++) PS = orc_mulmod(PS, vprimes[T + k] % q, q);
+        uint64_t PSinv = orc_invmod(PS, q);
+        for (size_t n = 0; n < N; n++)
+            out[(size_t)i * N + n] = orc_mulmod(orc_submod(in[(size_t)i * N + n], conv[n], q), PSinv, q);
+        free(conv);
+    }
+}
+
+/* C: [2][ell+K][N] evaluation form on the level's extended basis -> out [2][ell-1][N] evaluation form. */
+static void moddown_merged_eval(uint64_t* C, uint64_t* out, const orc_level* v) {
+    const orc_params* p = &v->p;
+    size_t N = (size_t)1 << p->logN;
+    uint32_t ell = p->L, D = ell + p->K;
+    limbs_ntt(C, p, 0, D, 2, D, 1);
+    for (uint32_t t = 0; t < 2; t++)
+        orc_moddown_merged(C + (size_t)t * D * N, out + (size_t)t * (ell - 1) * N, p->logN, ell, p->K, p->primes);
+    limbs_ntt(out, p, 0, ell - 1, 2, ell - 1, 0);
+}
+
+/* HMult + relinearisation + rescale with the merged division: level ell in, level ell-1 out.
+ *   c' = inner product of the extended digits of d2 = a1*a2 with evk          ([2][ell+K][N]);
+ *   C_t = c'_t + P * d_t on the q-limbs (d_0 = b1*b2, d_1 = a1*b2 + a2*b1), C_t = c'_t on the special limbs;
+ *   out_t = NTT(ModDownMerged(INTT(C_t))).
+ * (ModDown(c') + d = ModDown(c' + P*d) exactly, so this is HMult+relin with its ModDown and the
+ * following rescale replaced by one division by P*q_{ell-1}.) */
+void orc_hmult_relin_rescale_level(const uint64_t* ct1, const uint64_t* ct2, const uint64_t* evk, uint64_t* out,
+                                   uint32_t ell, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
+                                   const uint64_t* primes, const uint64_t* psi) {
+    orc_level v;
+    level_open(&v, ell, logN, L, K, dnum, primes, psi);
+    size_t N = (size_t)1 << logN;
+    uint32_t D = ell + K;
+    uint64_t* kc = level_key(&v, evk, L);
+    uint64_t* d2 = (uint64_t*)malloc(sizeof(uint64_t) * ell * N);
+    uint64_t* dhat = (uint64_t*)malloc(sizeof(uint64_t) * v.p.dnum * D * N);
+    uint64_t* C = (uint64_t*)malloc(sizeof(uint64_t) * 2 * D * N);
+    for (uint32_t i = 0; i < ell; i++) {
+        const uint64_t *a1 = ct1 + ((size_t)ell + i) * N, *a2 = ct2 + ((size_t)ell + i) * N;
+        for (size_t n = 0; n < N; n++) d2[(size_t)i * N + n] = orc_mulmod(a1[n], a2[n], primes[i]);
+    }
+    decompose_extend_level(d2, dhat, &v);
+    key_inner_product(dhat, kc, C, &v.p, 1);
+    for (uint32_t i = 0; i < ell; i++) {
+        uint64_t m = primes[i], Pm = 1;
+        for (uint32_t k = 0; k < K; k++) Pm = orc_mulmod(Pm, primes[L + k] % m, m);
+        const uint64_t *b1 = ct1 + (size_t)i * N, *a1 = ct1 + ((size_t)ell + i) * N;
+        const uint64_t *b2 = ct2 + (size_t)i * N, *a2 = ct2 + ((size_t)ell + i) * N;
+        uint64_t *C0 = C + (size_t)i * N, *C1 = C + ((size_t)D + i) * N;
+        for (size_t n = 0; n < N; n++) {
+            uint64_t d0 = orc_mulmod(b1[n], b2[n], m);
+            uint64_t d1 = orc_addmod(orc_mulmod(a1[n], b2[n], m), orc_mulmod(a2[n], b1[n], m), m);
+            C0[n] = orc_addmod(C0[n], orc_mulmod(Pm, d0, m), m);
+            C1[n] = orc_addmod(C1[n], orc_mulmod(Pm, d1, m), m);
+        }
+    }
+    moddown_merged_eval(C, out, &v);
+    free(kc);
+    free(d2);
+    free(dhat);
+    free(C);
+    level_close(&v);
+}
+
 /* --------------------------------------------------------- harness: key gen */
 /* Switching key from s to s' under the RNS gadget (P on digit j's own limbs):
  *   key[j][1][i] = a_j[i]                                   (uniform, evaluation form, given)

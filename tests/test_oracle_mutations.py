@@ -37,6 +37,9 @@ MUTATIONS = [
     ("                const uint64_t* ptr = pt + ((size_t)r * D + i) * N;\n                const uint64_t* src = cp", "                const uint64_t* ptr = pt + ((size_t)r * D + (i % ell)) * N;\n                const uint64_t* src = cp", "test_double_hoisted_mac"),
     ("            orc_automorph_eval(ct + (size_t)i * N, sb, logN, galois[r]);\n            const uint64_t* ptr = pt + ((size_t)r * D + i) * N;", "            orc_automorph_eval(ct + (size_t)i * N, sb, logN, 1);\n            const uint64_t* ptr = pt + ((size_t)r * D + i) * N;", "test_double_hoisted_mac"),
     ("    moddown_eval(C, ks, &v.p);", "    moddown_eval(cp, ks, &v.p);", "test_double_hoisted_mac"),
+    ("orc_conv(in + (size_t)T * N, N, N, vprimes + T, ns, q, conv);", "orc_conv(in + (size_t)(T + 1) * N, N, N, vprimes + T + 1, ns - 1, q, conv);", "test_moddown_merged_vs_bigint"),
+    ("            C0[n] = orc_addmod(C0[n], orc_mulmod(Pm, d0, m), m);", "            C0[n] = orc_addmod(C0[n], d0, m);", "test_hmult_relin_rescale_merged"),
+    ("            C1[n] = orc_addmod(C1[n], orc_mulmod(Pm, d1, m), m);", "            C1[n] = orc_addmod(C1[n], orc_mulmod(Pm, d0, m), m);", "test_hmult_relin_rescale_merged"),
 ]
 
 

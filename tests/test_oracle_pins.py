@@ -697,3 +697,56 @@ def test_double_hoisted_mac_decrypts_and_reduces_to_single_rotation(orc, shape):
         assert ell == 1 or not np.array_equal(single, out)
         Es = orc.centred_small(orc.pointwise("sub", dec(single), dec(out), q), P, ell)
         assert np.abs(Es).max() <= bound + sum(l1) * (ps.K * (1 + h) + 1) + sum(l1)
+
+
+# ------------------------------------------------ ModDown merged with the rescale
+@pytest.mark.parametrize("shape", [(5, 4, 2, 2, 20, 24), (4, 6, 3, 2, 20, 22), (4, 3, 1, 3, 35, 36), (4, 8, 2, 4, 49, 59)])
+def test_moddown_merged_vs_bigint(orc, shape):
+    ps = _small_set(*shape)
+    P = orc.Params.from_set(ps)
+    rng = np.random.default_rng(93)
+    for ell in sorted({ps.L, ps.L - 1, 2}):
+        basis = list(ps.q_primes[:ell]) + list(ps.p_primes)
+        S = basis[ell - 1:]
+        PS = 1
+        for m in S:
+            PS *= m
+        Qt = 1
+        for m in basis[:ell - 1]:
+            Qt *= m
+        x = synth.uniform_residues(rng, basis, ps.N)
+        big = (rng.integers(0, 2**62, dtype=np.uint64).item() * 987654321987654321 % Qt) * PS   # exact multiple
+        for t, m in enumerate(basis):
+            x[t, 0] = big % m
+        out = orc.moddown_merged(x, P)
+        assert out.shape == (ell - 1, ps.N)
+        for n in range(ps.N):
+            c, _ = crt([x[t, n] for t in range(len(basis))], basis)
+            us = {(c // PS - int(out[i, n])) % q for i, q in enumerate(basis[:ell - 1])}
+            assert len(us) == 1
+            u = us.pop()
+            assert 0 <= u <= ps.K                                                     # K+1 sources
+            if n == 0:
+                assert u == 0 and all(int(out[i, 0]) == (big // PS) % q for i, q in enumerate(basis[:ell - 1]))
+
+
+@pytest.mark.parametrize("shape", LEVEL_SHAPES[:2] + [(6, 4, 4, 1, 30, 31)])
+def test_hmult_relin_rescale_merged_stays_next_to_the_two_step_result(orc, shape):
+    ps = _small_set(*shape)
+    P, rng, s, s_hat = _setup(orc, ps, 95)
+    s2_hat = orc.pointwise("mul", s_hat, s_hat, ps.primes)
+    evk, _ = _keys(orc, ps, P, rng, s2_hat, s_hat)
+    seen_different = False
+    for ell in range(ps.L, 1, -1):
+        q = list(ps.q_primes[:ell])
+        ct1 = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        ct2 = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        merged = orc.hmult_relin_rescale_level(ct1, ct2, evk, P)
+        two_step = orc.rescale(orc.hmult_relin_level(ct1, ct2, evk, P), P)
+        assert merged.shape == two_step.shape == (2, ell - 1, ps.N)
+        for t in range(2):
+            diff = orc.centred_small(orc.pointwise("sub", merged[t], two_step[t], q[:-1]), P, ell - 1)
+            # merged = floor(X/(P q)) - u2, u2 in [0, K]; two-step = that floor or one less: diff in [-K, 1]
+            assert -ps.K <= diff.min() and diff.max() <= 1
+        seen_different |= not np.array_equal(merged, two_step)
+    assert seen_different
