@@ -266,6 +266,9 @@ def main():
             ctx.rescale(L, out1, rs_out)
 
         extra["hmult_relin_rescale_per_s"] = round(B / timed(mult_rescale), 1)
+        # the same pair with the rescale merged into the ModDown (one division by P * q_last)
+        dt = timed(lambda: ctx.hmult_relin_rescale_at(L, ct1, ct2, evk, rs_out), label="hmult_relin_rescale_merged")
+        extra["hmult_relin_rescale_merged_per_s"] = round(B / dt, 1)
         lv = 13
         a13 = ct1[:, :, :lv].contiguous()
         b13 = ct2[:, :, :lv].contiguous()

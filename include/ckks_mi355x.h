@@ -241,6 +241,26 @@ int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uin
                         size_t ws_bytes, void* stream);
 
 /*
+ * ModDown merged with the rescale that follows it (Section 4: every multiplication of the CNN is followed
+ * by a rescale): one floor-type division by P * q_{level-1}.  The last active limb joins the special limbs
+ * as a source of the conversion:  S = {q_{level-1}, p_0..p_{K-1}}, PS its product,
+ *   out_i = (C_i - Conv_{S -> q_i}(C restricted to S)) * [PS^-1]_{q_i}  mod q_i,   i < level-1.
+ * ckks_hmult_relin_rescale_at:  C_t = c'_t + P * d_t on the q-limbs (d_0 = b1*b2, d_1 = a1*b2 + a2*b1, c' the
+ *   inner product of ckks_hmult_relin_at), C_t = c'_t on the special limbs;
+ *   d_ct1, d_ct2 : [batch][2][level][N];  d_out : [batch][2][level-1][N].
+ * ckks_hrot_dh_mac_rescale_at:  C_t of ckks_hrot_dh_mac_at with P * sum_r pt_r * sigma_{g_r}(b) added to C_0 on
+ *   the q-limbs;  d_out : [2][level-1][N];  everything else as ckks_hrot_dh_mac_at.
+ * As integers the results are floor(X / PS) - u, 0 <= u <= K: within K+1 of, but not bit-identical to, the
+ * un-merged call followed by ckks_rescale.  2 <= level <= L.  Workspace: as the un-merged call at that level.
+ */
+int ckks_hmult_relin_rescale_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct1, const uint64_t* d_ct2,
+                                const uint64_t* d_evk, uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes,
+                                void* stream);
+int ckks_hrot_dh_mac_rescale_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
+                                const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt,
+                                uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
  * Optional two-stream execution inside one call.  Off by default: every kernel of a call runs on the
  * caller's stream in order.  With on != 0 the key-switch entry points run the launches that work on
  * integer-arithmetic limbs (primes of 50 bits and more, normally the special limbs) on a second stream

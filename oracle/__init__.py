@@ -377,6 +377,22 @@ def hmult_relin_rescale_level(ct1: np.ndarray, ct2: np.ndarray, evk: np.ndarray,
     return out
 
 
+def hrot_dh_mac_rescale_level(ct: np.ndarray, galois: Sequence[int], rks: Sequence[np.ndarray], pt: np.ndarray,
+                              P: Params) -> np.ndarray:
+    """Double-hoisted rotate-MAC with the merged ModDown + rescale: [2][ell][N] -> [2][ell-1][N]."""
+    ct = np.ascontiguousarray(ct, dtype=np.uint64)
+    pt = np.ascontiguousarray(pt, dtype=np.uint64)
+    n_rot, ell = len(galois), ct.shape[1]
+    assert ell >= 2 and len(rks) == n_rot and pt.shape == (n_rot, ell + P.K, P.N) and ct.shape == (2, ell, P.N)
+    rks = [np.ascontiguousarray(k, dtype=np.uint64) for k in rks]
+    ptrs = (ctypes.c_void_p * n_rot)(*[k.ctypes.data for k in rks])
+    g = np.ascontiguousarray(np.array(galois, dtype=np.uint32))
+    out = np.empty((2, ell - 1, P.N), dtype=np.uint64)
+    lib().orc_hrot_dh_mac_rescale_level(_ptr(ct), _u32(n_rot), _ptr(g), ptrs, _ptr(pt), _ptr(out),
+                                        *_level_tail(P, ell))
+    return out
+
+
 # ------------------------------------------------------------- harness helpers
 def lift_signed(v: np.ndarray, primes: Sequence[int]) -> np.ndarray:
     """Small signed coefficients [N] -> canonical residues [len(primes)][N]."""

@@ -761,6 +761,52 @@ void orc_hmult_relin_rescale_level(const uint64_t* ct1, const uint64_t* ct2, con
     level_close(&v);
 }
 
+/* Double-hoisted rotate-multiply-accumulate followed by a rescale, with the merged division:
+ *   C_t as in orc_hrot_dh_mac_level, plus P * sum_r pt_r * sigma_{g_r}(b) added to C_0 on the q-limbs
+ *   (ModDown(C) + x = ModDown(C + P*x) exactly);   out_t = NTT(ModDownMerged(INTT(C_t))):  [2][ell-1][N]. */
+void orc_hrot_dh_mac_rescale_level(const uint64_t* ct, uint32_t n_rot, const uint32_t* galois,
+                                   const uint64_t* const* rk, const uint64_t* pt, uint64_t* out, uint32_t ell,
+                                   uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum, const uint64_t* primes,
+                                   const uint64_t* psi) {
+    orc_level v;
+    level_open(&v, ell, logN, L, K, dnum, primes, psi);
+    size_t N = (size_t)1 << logN;
+    uint32_t D = ell + K;
+    uint64_t* dhat = (uint64_t*)malloc(sizeof(uint64_t) * v.p.dnum * D * N);
+    uint64_t* cp = (uint64_t*)malloc(sizeof(uint64_t) * 2 * D * N);
+    uint64_t* C = (uint64_t*)calloc(2 * D * N, sizeof(uint64_t));
+    uint64_t* sb = (uint64_t*)malloc(sizeof(uint64_t) * N);
+    decompose_extend_level(ct + (size_t)ell * N, dhat, &v);
+    for (uint32_t r = 0; r < n_rot; r++) {
+        uint64_t* kc = level_key(&v, rk[r], L);
+        key_inner_product(dhat, kc, cp, &v.p, galois[r]);
+        free(kc);
+        for (uint32_t t = 0; t < 2; t++)
+            for (uint32_t i = 0; i < D; i++) {
+                uint64_t m = v.vprimes[i];
+                const uint64_t* ptr = pt + ((size_t)r * D + i) * N;
+                const uint64_t* src = cp + ((size_t)t * D + i) * N;
+                uint64_t* dst = C + ((size_t)t * D + i) * N;
+                for (size_t n = 0; n < N; n++) dst[n] = orc_addmod(dst[n], orc_mulmod(ptr[n], src[n], m), m);
+            }
+        for (uint32_t i = 0; i < ell; i++) {
+            uint64_t m = primes[i], Pm = 1;
+            for (uint32_t k = 0; k < K; k++) Pm = orc_mulmod(Pm, primes[L + k] % m, m);
+            orc_automorph_eval(ct + (size_t)i * N, sb, logN, galois[r]);
+            const uint64_t* ptr = pt + ((size_t)r * D + i) * N;
+            uint64_t* dst = C + (size_t)i * N;
+            for (size_t n = 0; n < N; n++)
+                dst[n] = orc_addmod(dst[n], orc_mulmod(Pm, orc_mulmod(ptr[n], sb[n], m), m), m);
+        }
+    }
+    moddown_merged_eval(C, out, &v);
+    free(dhat);
+    free(cp);
+    free(C);
+    free(sb);
+    level_close(&v);
+}
+
 /* --------------------------------------------------------- harness: key gen */
 /* Switching key from s to s' under the RNS gadget (P on digit j's own limbs):
  *   key[j][1][i] = a_j[i]                                   (uniform, evaluation form, given)

@@ -27,6 +27,7 @@ EXPORTS = (
     "ckks_profile_enable", "ckks_profile_read", "ckks_set_overlap",
     "ckks_workspace_bytes_at", "ckks_keyswitch_at", "ckks_hmult_relin_at", "ckks_hrot_at",
     "ckks_hrot_hoisted_mac_at", "ckks_rescale", "ckks_hrot_dh_mac", "ckks_hrot_dh_mac_at",
+    "ckks_hmult_relin_rescale_at", "ckks_hrot_dh_mac_rescale_at",
 )
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
@@ -75,6 +76,8 @@ def load() -> ctypes.CDLL:
     lib.ckks_rescale.argtypes = [_vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_dh_mac.argtypes = [_vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_hrot_dh_mac_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.ckks_hmult_relin_rescale_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
+    lib.ckks_hrot_dh_mac_rescale_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_profile_enable.argtypes = [_vp, _int]
     lib.ckks_profile_read.argtypes = [_vp, _u32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_u64),
                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_u64)]
@@ -325,4 +328,30 @@ class Context:
                                             ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out), ws.data_ptr(),
                                             ws.numel(), _stream())
         self._check(rc)
+        return out
+
+    # -- ModDown merged with the following rescale: outputs carry level - 1 limbs -----------------
+    def hmult_relin_rescale_at(self, level: int, ct1: torch.Tensor, ct2: torch.Tensor, evk: torch.Tensor,
+                               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        batch = ct1.numel() // (2 * level * self.N)
+        if out is None:
+            out = torch.empty(tuple(ct1.shape[:-2]) + (level - 1, self.N), dtype=ct1.dtype, device=ct1.device)
+        ws = self.workspace(OP_HMULT_RELIN, batch, level)
+        self._check(load().ckks_hmult_relin_rescale_at(self.handle, level, _dev_ptr(ct1), _dev_ptr(ct2), _dev_ptr(evk),
+                                                       _dev_ptr(out), batch, ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def hrot_dh_mac_rescale_at(self, level: int, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor],
+                               pt: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        n_rot = len(galois)
+        if len(rks) != n_rot or pt.numel() != n_rot * (level + self.K) * self.N:
+            raise ValueError("one key and one extended-basis plaintext per rotation")
+        if out is None:
+            out = torch.empty((2, level - 1, self.N), dtype=ct.dtype, device=ct.device)
+        g = (ctypes.c_uint32 * n_rot)(*[int(x) for x in galois])
+        ptrs = (ctypes.c_void_p * n_rot)(*[_dev_ptr(k) for k in rks])
+        ws = self.workspace(OP_HROT_DH_MAC, n_rot, level)
+        self._check(load().ckks_hrot_dh_mac_rescale_at(self.handle, level, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
+                                                       ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out),
+                                                       ws.data_ptr(), ws.numel(), _stream()))
         return out

@@ -153,10 +153,30 @@ static RescaleLayout rescale_layout(size_t base, u32 ell) {
     return l;
 }
 
+// ModDown merged with the rescale after it, from level ell: sources q_{ell-1}, p_0..p_{K-1}; targets q_0..q_{ell-2}
+struct MergedLayout {
+    size_t sc_dn, dn_chat, dn_chat_fp, dn_fp_ok, pinv, qlinv, end;
+};
+static MergedLayout merged_layout(size_t base, u32 ell, u32 K) {
+    const size_t T = ell - 1, S = K + 1;
+    Taker t{base};
+    MergedLayout l;
+    l.sc_dn = t.take(S * sizeof(InvScale));
+    l.dn_chat = t.take(S * T * sizeof(u64));
+    l.dn_chat_fp = t.take(S * T * 2 * sizeof(double));
+    l.dn_fp_ok = t.take(T * sizeof(u32));
+    l.pinv = t.take(T * sizeof(PinvConst));
+    l.qlinv = t.take(T * sizeof(PinvConst));
+    l.end = t.o;
+    return l;
+}
+
 static size_t table_total(u32 logN, u32 L, u32 K, u32 dnum) {
     size_t o = shared_layout(logN, L, K).end;
     for (u32 ell = 1; ell <= L; ell++) o = level_layout(o, ell, K, L / dnum).end;
     for (u32 ell = 2; ell <= L; ell++) o = rescale_layout(o, ell).end;
+    if (K)
+        for (u32 ell = 2; ell <= L; ell++) o = merged_layout(o, ell, K).end;
     return o;
 }
 
@@ -217,6 +237,7 @@ struct ckks_ctx {
     std::vector<u64> primes, psi;
     std::vector<View> level;    // [ell], 1 <= ell <= L: key switching at ell active q-limbs; level[L] is the full one
     std::vector<View> rescale;  // [ell], 2 <= ell <= L: the step from ell limbs to ell - 1 (K = 1, "special" prime q_{ell-1})
+    std::vector<View> merged;   // [ell], 2 <= ell <= L, K > 0: ModDown from level ell that also divides by q_{ell-1}
     mutable Shared sh;
     const View* full() const { return &level[L]; }
 };
@@ -523,7 +544,8 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         tb.dn_fp_ok = (const u32*)(dbase + ll.dn_fp_ok);
         tb.pinv = (const PinvConst*)(dbase + ll.pinv);
         tb.pmod = (const u64*)(dbase + ll.pmod);
-        tb.L = ell, tb.K = K, tb.dnum = beta, tb.alpha = alpha, tb.D = Dl, tb.Lfull = L;
+        tb.qlinv = nullptr;
+        tb.L = ell, tb.K = K, tb.dnum = beta, tb.alpha = alpha, tb.D = Dl, tb.Lfull = L, tb.Lq = ell;
     }
     // ---- one block per rescale step: a ModDown whose only "special" prime is q_{ell-1}
     c->rescale.resize(L + 1);
@@ -560,7 +582,57 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         tb.dn_chat_fp = (const double*)(dbase + rl.dn_chat_fp);
         tb.dn_fp_ok = (const u32*)(dbase + rl.dn_fp_ok);
         tb.pinv = (const PinvConst*)(dbase + rl.pinv);
-        tb.L = T, tb.K = 1, tb.dnum = 1, tb.alpha = T, tb.D = ell, tb.Lfull = T;  // phys() is the identity here
+        tb.L = T, tb.K = 1, tb.dnum = 1, tb.alpha = T, tb.D = ell, tb.Lfull = ell, tb.Lq = ell;  // phys() is the identity
+    }
+    // ---- one block per merged ModDown + rescale: sources q_{ell-1}, p_0..p_{K-1} (limbs ell-1 .. of level ell)
+    c->merged.resize(L + 1);
+    for (u32 ell = 2; K > 0 && ell <= L; ell++) {
+        const MergedLayout ml = merged_layout(off, ell, K);
+        off = ml.end;
+        const u32 T = ell - 1, S = K + 1;
+        std::vector<u64> src(1, c->primes[T]);
+        src.insert(src.end(), specials.begin(), specials.end());
+        auto sph = [&](u32 k) { return k == 0 ? T : L + (k - 1); };  // chain index of source k
+        InvScale* msc = (InvScale*)(hb + ml.sc_dn);
+        u64* dn_chat = (u64*)(hb + ml.dn_chat);
+        double* dn_chat_fp = (double*)(hb + ml.dn_chat_fp);
+        u32* dn_fp_ok = (u32*)(hb + ml.dn_fp_ok);
+        PinvConst* pinv = (PinvConst*)(hb + ml.pinv);
+        PinvConst* qlinv = (PinvConst*)(hb + ml.qlinv);
+        for (u32 k = 0; k < S; k++) {
+            const u64 sk = src[k];
+            const u64 hinv = h_invmod(prod_except(src, k, sk), sk);
+            msc[k] = make_scale(hinv, ninv[sph(k)], wlast[sph(k)], sk, pc[sph(k)].fp != 0);
+        }
+        for (u32 i = 0; i < T; i++) {
+            const u64 qi = c->primes[i];
+            for (u32 k = 0; k < S; k++) {
+                const u64 hatb = prod_except(src, k, qi);
+                dn_chat[(size_t)k * T + i] = h_mont(hatb, qi);
+                dn_chat_fp[((size_t)k * T + i) * 2] = pc[i].fp ? (double)hatb : 0.0;
+                dn_chat_fp[((size_t)k * T + i) * 2 + 1] = pc[i].fp ? (double)h_mulmod(hatb, (1ull << 30) % qi, qi) : 0.0;
+            }
+            dn_fp_ok[i] = (pc[i].fp && qi >= (1ull << 28)) ? 1 : 0;
+            const u64 pi = h_invmod(prod_except(src, src.size(), qi), qi);
+            pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
+            const u64 ql = h_invmod(src[0] % qi, qi);
+            qlinv[i] = PinvConst{ql, h_shoup(ql, qi), (double)ql};
+        }
+        View& v = c->merged[ell];
+        v.logN = logN, v.L = T, v.K = S, v.dnum = 1, v.alpha = T, v.D = ell + K, v.sh = &c->sh;
+        v.primes = c->level[ell].primes;  // same limb order as the level: q_0..q_{ell-1}, p_0..p_{K-1}
+        v.mixed_classes = c->level[ell].mixed_classes;
+        Tables& tb = v.tb;
+        memset(&tb, 0, sizeof(tb));
+        shared_tables(tb);
+        tb.sc_dn = (const InvScale*)(dbase + ml.sc_dn);
+        tb.dn_hatinv = nullptr;
+        tb.dn_chat = (const u64*)(dbase + ml.dn_chat);
+        tb.dn_chat_fp = (const double*)(dbase + ml.dn_chat_fp);
+        tb.dn_fp_ok = (const u32*)(dbase + ml.dn_fp_ok);
+        tb.pinv = (const PinvConst*)(dbase + ml.pinv);
+        tb.qlinv = (const PinvConst*)(dbase + ml.qlinv);
+        tb.L = T, tb.K = S, tb.dnum = 1, tb.alpha = T, tb.D = ell + K, tb.Lfull = L, tb.Lq = ell;
     }
 
     hipStream_t s = (hipStream_t)stream;
@@ -1123,10 +1195,17 @@ static void moddown_convert(const View* c, const Workspace& w, u32 cg, hipStream
     launch_conv<CONV_DN>(c, a7, s);
 }
 
+// cm: the view whose ModDown ends the pipeline: c itself, or the merged view of c's level (the ModDown then
+// also divides by the last q-limb: limb c->L - 1 joins the special limbs and the output has c->L - 1 limbs)
 template <int LOAD, int OWN, int FIN>
-static void keyswitch_pipeline(const View* c, const u64* in1, const u64* in2, const u64* key, u64* out, u32 batch,
-                               u32 galois, void* ws, hipStream_t s) {
-    const Workspace w = carve(c, ws, batch, batch, batch);
+static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, const u64* in2, const u64* key, u64* out,
+                               u32 batch, u32 galois, void* ws, hipStream_t s) {
+    Workspace w = carve(c, ws, batch, batch, batch);
+    if (cm != c) {  // cq and cv shrink by one limb per component, cp grows by one: still inside the level's workspace
+        const size_t N = (size_t)1 << c->logN;
+        w.cp = w.cq + (size_t)batch * 2 * cm->L * N;
+        w.cv = w.cp + (size_t)batch * 2 * cm->K * N;
+    }
     const LimbSel sel = {c->L, batch, c->L, 0, 0, 0};
     InvContigArgs a1 = {in1, in2, w.x, sel, sel, galois};
     launch_inv_contig<LOAD>(c, a1, s);
@@ -1134,14 +1213,14 @@ static void keyswitch_pipeline(const View* c, const u64* in1, const u64* in2, co
     InnerArgs ia;
     memset(&ia, 0, sizeof(ia));
     ia.dt = w.dt, ia.own = in1, ia.own2 = in2, ia.key[0] = key, ia.galois[0] = galois;
-    ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = batch;
+    ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = batch, ia.split = cm->L, ia.add_tensor = cm != c;
     launch_ks_inner<OWN, false>(c, ia, s);
-    moddown_convert(c, w, batch, s);
+    moddown_convert(cm, w, batch, s);
     FinalArgs fa;
     memset(&fa, 0, sizeof(fa));
     fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = in1, fa.ct2 = in2, fa.out = out, fa.galois[0] = galois, fa.n_inst = batch;
-    fa.cq_L = c->L;
-    launch_ks_final<FIN>(c, fa, s);
+    fa.cq_L = cm->L, fa.in_L = c->L;
+    launch_ks_final<FIN>(cm, fa, s);
 }
 
 extern "C" int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_d, const uint64_t* d_key,
@@ -1151,7 +1230,7 @@ extern "C" int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* 
     if (!c) return CKKS_EINVAL;
     int rc = check_ks_args(c, d_d, d_key, d_out, batch, CKKS_OP_KEYSWITCH, d_ws, ws_bytes);
     if (rc) return rc;
-    keyswitch_pipeline<INV_PLAIN, OWN_COPY, FIN_KS>(c, d_d, nullptr, d_key, d_out, batch, 1, d_ws, (hipStream_t)stream);
+    keyswitch_pipeline<INV_PLAIN, OWN_COPY, FIN_KS>(c, c, d_d, nullptr, d_key, d_out, batch, 1, d_ws, (hipStream_t)stream);
     return hip_check(c, "ckks_keyswitch");
 }
 
@@ -1164,9 +1243,24 @@ extern "C" int ckks_hmult_relin_at(ckks_ctx* ctx, uint32_t level, const uint64_t
     if (!d_ct2 || misaligned(d_ct2, 16)) return fail(c, CKKS_EINVAL, "null or misaligned buffer");
     int rc = check_ks_args(c, d_ct1, d_evk, d_out, batch, CKKS_OP_HMULT_RELIN, d_ws, ws_bytes);
     if (rc) return rc;
-    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT>(c, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
+    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT>(c, c, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
                                                           (hipStream_t)stream);
     return hip_check(c, "ckks_hmult_relin");
+}
+
+extern "C" int ckks_hmult_relin_rescale_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct1, const uint64_t* d_ct2,
+                                           const uint64_t* d_evk, uint64_t* d_out, uint32_t batch, void* d_ws,
+                                           size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    if (level < 2) return fail(c, CKKS_EINVAL, "rescale needs at least two limbs");
+    if (!d_ct2 || misaligned(d_ct2, 16)) return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    int rc = check_ks_args(c, d_ct1, d_evk, d_out, batch, CKKS_OP_HMULT_RELIN, d_ws, ws_bytes);
+    if (rc) return rc;
+    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT_RS>(c, &ctx->merged[level], d_ct1, d_ct2, d_evk, d_out, batch, 1,
+                                                             d_ws, (hipStream_t)stream);
+    return hip_check(c, "ckks_hmult_relin_rescale");
 }
 
 extern "C" int ckks_hrot_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t galois, const uint64_t* d_rk,
@@ -1178,7 +1272,7 @@ extern "C" int ckks_hrot_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct,
     if (rc) return rc;
     rc = check_galois(c, galois);
     if (rc) return rc;
-    keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, d_ct, nullptr, d_rk, d_out, batch, galois, d_ws,
+    keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, c, d_ct, nullptr, d_rk, d_out, batch, galois, d_ws,
                                                    (hipStream_t)stream);
     return hip_check(c, "ckks_hrot");
 }
@@ -1227,7 +1321,7 @@ extern "C" int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct,
     moddown_convert(c, w, batch, s);
     FinalArgs fa;
     memset(&fa, 0, sizeof(fa));
-    fa.cq = d_ct, fa.cq_L = level, fa.cv = w.cv, fa.out = d_out, fa.n_inst = batch;
+    fa.cq = d_ct, fa.cq_L = level, fa.in_L = c->L, fa.cv = w.cv, fa.out = d_out, fa.n_inst = batch;
     launch_ks_final<FIN_KS>(c, fa, s);
     return hip_check(c, "ckks_rescale");
 }
@@ -1284,12 +1378,12 @@ extern "C" int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uin
             ia.galois[r] = h_galois[r0 + r];
             fa.galois[r] = h_galois[r0 + r];
         }
-        ia.dt = w.dt, ia.own = d_ct, ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = nr;
+        ia.dt = w.dt, ia.own = d_ct, ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = nr, ia.split = c->L;
         fork_side(c, s);  // no-op in the first chunk (still forked); later chunks wait for the previous ModDown
         launch_ks_inner<OWN_COPY, true>(c, ia, s);
         moddown_convert(c, w, nr, s);
         fa.cq = w.cq, fa.cq_L = c->L, fa.cv = w.cv, fa.ct1 = d_ct, fa.pt = d_pt + (size_t)r0 * c->L * N, fa.out = d_out;
-        fa.n_inst = 2, fa.n_rot = nr, fa.accumulate = r0 ? 1 : 0;
+        fa.n_inst = 2, fa.n_rot = nr, fa.accumulate = r0 ? 1 : 0, fa.in_L = c->L;
         launch_ks_final<FIN_HOISTED>(c, fa, s);
     }
     return hip_check(c, "ckks_hrot_hoisted_mac");
@@ -1304,12 +1398,13 @@ extern "C" int ckks_hrot_hoisted_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32
 
 // Double-hoisted variant: the plaintext products are accumulated in the extended basis over all
 // rotations (CKKS_DH_CHUNK of them per launch) and a single ModDown follows.
-extern "C" int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
-                                   const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt,
-                                   uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream) {
+static int dh_mac_impl(ckks_ctx* ctx, uint32_t level, bool rescale, const uint64_t* d_ct, uint32_t n_rot,
+                       const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt,
+                       uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx) return CKKS_EINVAL;
     const View* c = view_at(ctx, level);
     if (!c) return CKKS_EINVAL;
+    if (rescale && level < 2) return fail(c, CKKS_EINVAL, "rescale needs at least two limbs");
     if (!h_galois || !h_rk_ptrs) return fail(c, CKKS_EINVAL, "null host array");
     if (n_rot == 0 || n_rot > 65535) return fail(c, CKKS_EINVAL, "n_rot out of range");
     if (!d_ct || !d_pt || !d_out || misaligned(d_ct, 16) || misaligned(d_pt, 16) || misaligned(d_out, 16))
@@ -1326,7 +1421,13 @@ extern "C" int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t
     }
     hipStream_t s = (hipStream_t)stream;
     const size_t N = (size_t)1 << c->logN;
-    const Workspace w = carve(c, d_ws, 1, 1, 1);
+    // cm: the view whose ModDown ends the call (the merged one also divides by the last q-limb)
+    const View* cm = rescale ? &ctx->merged[level] : c;
+    Workspace w = carve(c, d_ws, 1, 1, 1);
+    if (rescale) {
+        w.cp = w.cq + (size_t)2 * cm->L * N;
+        w.cv = w.cp + (size_t)2 * cm->K * N;
+    }
     {  // hoisted part, as in ckks_hrot_hoisted_mac
         const LimbSel src = {c->L, 1, c->L, c->L, 0, 0};
         const LimbSel dst = {c->L, 1, c->L, 0, 0, 0};
@@ -1347,20 +1448,33 @@ extern "C" int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t
         memset(&ia, 0, sizeof(ia));
         for (u32 r = 0; r < nr; r++) ia.key[r] = h_rk_ptrs[r0 + r], ia.galois[r] = h_galois[r0 + r];
         ia.dt = w.dt, ia.ct = d_ct, ia.pt = d_pt + (size_t)r0 * c->D * N, ia.cq = w.cq, ia.cp = w.cp;
-        ia.n_rot = nr, ia.accumulate = r0 ? 1 : 0;
+        ia.n_rot = nr, ia.accumulate = r0 ? 1 : 0, ia.split = cm->L;
         launch_dh_accum(c, ia, s);
     }
-    {  // ModDown of the sum: first inverse pass of its special limbs, then the shared tail
-        const LimbSel sel = {c->K, 2, c->K, 0, c->L, 0};
+    {  // ModDown of the sum: first inverse pass of its source limbs, then the shared tail
+        const LimbSel sel = {cm->K, 2, cm->K, 0, cm->L, 0};
         InvContigArgs ic = {w.cp, nullptr, w.cp, sel, sel, 1};
-        launch_inv_contig<INV_PLAIN>(c, ic, s);
+        launch_inv_contig<INV_PLAIN>(cm, ic, s);
     }
-    moddown_convert(c, w, 1, s);
+    moddown_convert(cm, w, 1, s);
     FinalArgs fa;
     memset(&fa, 0, sizeof(fa));
-    fa.cq = w.cq, fa.cq_L = c->L, fa.cv = w.cv, fa.out = d_out, fa.n_inst = 1;
-    launch_ks_final<FIN_KS>(c, fa, s);
+    fa.cq = w.cq, fa.cq_L = cm->L, fa.in_L = cm->L, fa.cv = w.cv, fa.out = d_out, fa.n_inst = 1;
+    launch_ks_final<FIN_KS>(cm, fa, s);
     return hip_check(c, "ckks_hrot_dh_mac");
+}
+
+extern "C" int ckks_hrot_dh_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
+                                   const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt,
+                                   uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream) {
+    return dh_mac_impl(ctx, level, false, d_ct, n_rot, h_galois, h_rk_ptrs, d_pt, d_out, d_ws, ws_bytes, stream);
+}
+
+extern "C" int ckks_hrot_dh_mac_rescale_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
+                                           const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs,
+                                           const uint64_t* d_pt, uint64_t* d_out, void* d_ws, size_t ws_bytes,
+                                           void* stream) {
+    return dh_mac_impl(ctx, level, true, d_ct, n_rot, h_galois, h_rk_ptrs, d_pt, d_out, d_ws, ws_bytes, stream);
 }
 
 extern "C" int ckks_hrot_dh_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_rot, const uint32_t* h_galois,

@@ -39,14 +39,19 @@ struct Tables {
     const u32* dn_fp_ok;       // [L]  1 if q_i may convert on the FP64 pipe (FpAr prime, at least 2^28)
     const PinvConst* pinv;     // [L]     P^-1 mod q_i
     const u64* pmod;           // [L]     P mod q_i
+    const PinvConst* qlinv;    // [L]     q_L^-1 mod q_i where limb L is the first source of a merged ModDown
     u32 logN, L, K, dnum, alpha, D;
-    u32 Lfull;  // q-limbs of the whole prime chain (>= L)
+    u32 Lfull;  // q-limbs of the whole prime chain
+    u32 Lq;     // limbs 0 .. Lq-1 of this basis are q-limbs of the chain, the rest its special limbs
     // A Tables value describes one level: the basis q_0..q_{L-1}, p_0..p_{K-1} with L <= Lfull active
     // q-limbs, dnum = ceil(L/alpha) digits (the last one possibly partial) and limb indices 0..D-1 over
     // that basis.  The per-prime tables (tw_int, tw_fp, pc, sc_plain) and switching keys are laid out
     // over the whole chain of Lfull + K primes: phys() maps a limb index of the level to them.  All
     // other tables are per level and indexed by the level's limb indices.
-    __host__ __device__ __forceinline__ u32 phys(u32 i) const { return i < L ? i : i + (Lfull - L); }
+    // Three kinds of Tables exist: a level (L active q-limbs, K special limbs, Lq = L); a rescale step
+    // (L targets, K = 1 source = q-limb L, Lq = L + 1); a ModDown merged with the rescale after it (L
+    // targets, K sources = q-limb L followed by the special limbs, Lq = L + 1).
+    __host__ __device__ __forceinline__ u32 phys(u32 i) const { return i < Lq ? i : i + (Lfull - Lq); }
 };
 
 // slot j of sigma_g(f) in evaluation form reads slot eval_perm(j) of f
@@ -468,8 +473,11 @@ struct InnerArgs {
     const u64* key[CKKS_ROT_CHUNK];  // one shared key (index 0) or one per instance (hoisted)
     u32 galois[CKKS_ROT_CHUNK];      // ROT: [0]; hoisted: per instance
     u64* cq;                         // [inst][2][L][N] canonical
-    u64* cp;                         // [inst][2][K][N] raw inverse-lazy after the first inverse pass
+    u64* cp;                         // [inst][2][D - split][N] raw inverse-lazy after the first inverse pass
     u32 n_inst;
+    u32 split;    // limbs below split are stored to cq ([inst][2][split][N]), the others continue to cp: the number
+                  // of q-limbs, or one less when the ModDown that follows also divides by the last q-limb
+    u32 add_tensor;  // OWN_TENSOR with split < L: add P * (b1*b2, a1*b2 + a2*b1) on limb `split` before its inverse pass
 };
 
 template <class AR, int A, int OWN, bool HOISTED>
@@ -548,9 +556,20 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             for (int k = 0; k < 16; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
         }
     }
-    if (i < L) {
-        u64* o0 = a.cq + (((size_t)inst * 2 + 0) * L + i) * N + row_off;
-        u64* o1 = a.cq + (((size_t)inst * 2 + 1) * L + i) * N + row_off;
+    if (OWN == OWN_TENSOR && a.add_tensor && i == a.split) {
+        const size_t o0 = (((size_t)inst * 2 + 0) * L + i) * N + row_off, o1 = o0 + (size_t)L * N;
+        const u64 pmod = tb.pmod[i];
+#pragma unroll
+        for (int k = 0; k < 16; k++) {
+            const u32 e = k * 16 + e0;
+            const u64 b1 = a.own[o0 + e], b2 = a.own2[o0 + e], a1 = a.own[o1 + e], a2 = a.own2[o1 + e];
+            AR::acc_mac(acc0[k], AR::mul_canon(b1, b2, pc, m), pmod, m);
+            AR::acc_mac(acc1[k], AR::mul_canon(a1, b2, pc, m) + AR::mul_canon(a2, b1, pc, m), pmod, m);
+        }
+    }
+    if (i < a.split) {
+        u64* o0 = a.cq + (((size_t)inst * 2 + 0) * a.split + i) * N + row_off;
+        u64* o1 = a.cq + (((size_t)inst * 2 + 1) * a.split + i) * N + row_off;
 #pragma unroll
         for (int k = 0; k < 16; k++) {
             __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc0[k], m), m), &o0[k * 16 + e0]);
@@ -564,7 +583,7 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             for (int k = 0; k < 16; k++) x[k] = AR::acc_finish(t ? acc1[k] : acc0[k], m);
             exchange_ca_to_cb<AR>(x, lrow, e0);
             NttCore<AR, A>::inv_contig(x, lrow, e0, r, ti, tf, N, m);
-            u64* o = a.cp + (((size_t)inst * 2 + t) * tb.K + (i - L)) * N + row_off;
+            u64* o = a.cp + (((size_t)inst * 2 + t) * (D - a.split) + (i - a.split)) * N + row_off;
 #pragma unroll
             for (int k = 0; k < 16; k++) o[k * 16 + e0] = AR::to_raw(AR::round_reduce(x[k], m));
         }
@@ -598,6 +617,7 @@ struct DhInnerArgs {
     u64* cp;         // [2][K][N]  (evaluation form here; the inverse transform is a separate launch)
     u32 n_rot;
     u32 accumulate;  // add to what cq / cp already hold (a call with more rotations than one launch takes)
+    u32 split;       // limbs below split go to cq ([2][split][N]), the others to cp ([2][D - split][N])
 };
 
 // No transform is involved, so the work is element-parallel with few registers per lane (many waves in
@@ -663,8 +683,9 @@ __global__ __launch_bounds__(256) void dh_accum_kernel(DhInnerArgs a, Tables tb,
             }
         }
     }
-    u64* o0 = (is_q ? a.cq + (size_t)i * N : a.cp + (size_t)(i - L) * N) + base;
-    u64* o1 = (is_q ? a.cq + ((size_t)L + i) * N : a.cp + ((size_t)tb.K + (i - L)) * N) + base;
+    const u32 sp = a.split;
+    u64* o0 = (i < sp ? a.cq + (size_t)i * N : a.cp + (size_t)(i - sp) * N) + base;
+    u64* o1 = (i < sp ? a.cq + ((size_t)sp + i) * N : a.cp + ((size_t)(D - sp) + (i - sp)) * N) + base;
 #pragma unroll
     for (int k = 0; k < EPT; k++) {
         u64 r0 = AR::acc_canon(AR::acc_finish2(acc0[k], m), m), r1 = AR::acc_canon(AR::acc_finish2(acc1[k], m), m);
@@ -680,7 +701,9 @@ __global__ __launch_bounds__(256) void dh_accum_kernel(DhInnerArgs a, Tables tb,
 //   FIN_HMULT  : out = ks + (t == 0 ? b1*b2 : a1*b2 + a2*b1)
 //   FIN_HROT   : out = ks + (t == 0 ? sigma_g(b) : 0)
 //   FIN_HOISTED: out[t][i] (+)= sum_r pt_r[i] * (ks_r + (t == 0 ? sigma_{g_r}(b) : 0)); work item (i, tile, t)
-enum FinalMode { FIN_KS = 0, FIN_HMULT = 1, FIN_HROT = 2, FIN_HOISTED = 3 };
+//   FIN_HMULT_RS: the ModDown also divides by the last q-limb of the inputs (merged rescale): out has L limbs,
+//                 ct1 / ct2 have in_L = L + 1, and the tensor terms enter divided by that limb's prime
+enum FinalMode { FIN_KS = 0, FIN_HMULT = 1, FIN_HROT = 2, FIN_HOISTED = 3, FIN_HMULT_RS = 4 };
 struct FinalArgs {
     const u64* cq;   // [g][2][L][N] canonical
     const u64* cv;   // [g][2][L][N] raw forward-lazy (first pass done)
@@ -693,6 +716,7 @@ struct FinalArgs {
     u32 n_rot;       // HOISTED
     u32 accumulate;  // HOISTED: add to what out already holds
     u32 cq_L;        // limbs per component of cq (L, or L + 1 when cq is a ciphertext about to lose its last limb)
+    u32 in_L;        // limbs per component of ct1 / ct2 (L, or L + 1 for FIN_HMULT_RS)
 };
 
 template <class AR, int A, int MODE>
@@ -755,20 +779,22 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             exchange_cb_to_ca<AR>(v, lrow, e0);
             const u64* c = a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off;
             u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
-            const size_t o0 = (((size_t)inst * 2 + 0) * L + i) * N + row_off, o1 = o0 + (size_t)L * N;
+            const size_t o0 = (((size_t)inst * 2 + 0) * a.in_L + i) * N + row_off, o1 = o0 + (size_t)a.in_L * N;
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 const u32 e = k * 16 + e0;
                 double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[e])) - v[k], pinv.d, fm);
-                if (MODE == FIN_HMULT) {
+                if (MODE == FIN_HMULT || MODE == FIN_HMULT_RS) {
+                    double d;
                     if (t == 0) {
                         b1v[k] = u64_to_f64(__builtin_nontemporal_load(&a.ct1[o0 + e]));
                         b2v[k] = u64_to_f64(__builtin_nontemporal_load(&a.ct2[o0 + e]));
-                        ks += FpAr::mulmod_lazy(b1v[k], b2v[k], fm);
+                        d = FpAr::mulmod_lazy(b1v[k], b2v[k], fm);
                     } else {
-                        ks += FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct1[o1 + e])), b2v[k], fm) +
-                              FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct2[o1 + e])), b1v[k], fm);
+                        d = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct1[o1 + e])), b2v[k], fm) +
+                            FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct2[o1 + e])), b1v[k], fm);
                     }
+                    ks += MODE == FIN_HMULT_RS ? FpAr::mulmod_lazy(d, tb.qlinv[i].d, fm) : d;  // |d| <= 1.75 q
                 } else if (MODE == FIN_HROT) {
                     if (t == 0) ks += u64_to_f64(a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[0], tb.logN)]);
                 }
@@ -818,12 +844,12 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
         exchange_cb_to_ca<AR>(v, lrow, e0);
         const u64* c = a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off;
         u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
-        const size_t o0 = (((size_t)inst * 2 + 0) * L + i) * N + row_off, o1 = o0 + (size_t)L * N;
+        const size_t o0 = (((size_t)inst * 2 + 0) * a.in_L + i) * N + row_off, o1 = o0 + (size_t)a.in_L * N;
 #pragma unroll
         for (int k = 0; k < 16; k++) {
             const u32 e = k * 16 + e0;
             u64 ks = mul_shoup(submod(c[e], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
-            if (MODE == FIN_HMULT) {
+            if (MODE == FIN_HMULT || MODE == FIN_HMULT_RS) {
                 u128w s = {0, 0};
                 if (t == 0) {
                     mac128(s, a.ct1[o0 + e], a.ct2[o0 + e]);
@@ -831,7 +857,9 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                     mac128(s, a.ct1[o1 + e], a.ct2[o0 + e]);
                     mac128(s, a.ct2[o1 + e], a.ct1[o0 + e]);
                 }
-                ks = addmod(ks, reduce128(s, q, pc.qneg, pc.r2), q);
+                u64 d = reduce128(s, q, pc.qneg, pc.r2);
+                if (MODE == FIN_HMULT_RS) d = mul_shoup(d, tb.qlinv[i].w, tb.qlinv[i].wp, q);
+                ks = addmod(ks, d, q);
             } else if (MODE == FIN_HROT) {
                 if (t == 0) ks = addmod(ks, a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[0], tb.logN)], q);
             }

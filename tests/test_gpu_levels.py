@@ -221,3 +221,90 @@ def test_config3_double_hoisted_full_size(orc):
     got = host(ctx.hrot_dh_mac(dev(ct), gs, [dev(k) for k in rks], dev(pt)))
     _say("cfg3 double hoisting: oracle")
     assert np.array_equal(got, orc.hrot_dh_mac_level(ct, gs, rks, pt, P))
+
+
+# ------------------------------------------- ModDown merged with the following rescale
+MERGED_SHAPES = [(12, 6, 2, 3, 49, 59), (13, 6, 3, 2, 49, 59), (12, 3, 1, 3, 35, 36), (12, 6, 3, 2, 55, 59),
+                 (12, 8, 8, 1, 49, 59), (14, 4, 2, 2, 49, 59)]
+
+
+@pytest.mark.parametrize("shape", MERGED_SHAPES)
+def test_hmult_relin_rescale_merged_parity_every_level(orc, shape):
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(8000 + sum(shape))
+    evk = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    d_evk = dev(evk)
+    B = 2
+    for ell in range(ps.L, 1, -1):
+        _say("merged hmult", shape, "level", ell)
+        q = ps.q_primes[:ell]
+        ct1 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
+        ct2 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
+        got = host(ctx.hmult_relin_rescale_at(ell, dev(ct1), dev(ct2), d_evk))
+        assert got.shape == (B, 2, ell - 1, ps.N)
+        for b in range(B):
+            assert np.array_equal(got[b], orc.hmult_relin_rescale_level(ct1[b], ct2[b], evk, P)), (ell, b)
+
+
+@pytest.mark.parametrize("shape,n_rot", [((12, 6, 2, 3, 49, 59), 3), ((13, 6, 3, 2, 49, 59), 11), ((12, 4, 2, 2, 55, 59), 5)])
+def test_double_hoisted_mac_rescale_merged_parity(orc, shape, n_rot):
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(9000 + sum(shape))
+    gs = [synth.galois_element(r, ps.logN) for r in range(1, n_rot + 1)]
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    d_rks = [dev(k) for k in rks]
+    for ell in sorted({ps.L, ps.L - 1, ps.alpha + 1, 2}, reverse=True):
+        _say("merged double hoisting", shape, "level", ell)
+        basis = list(ps.q_primes[:ell]) + list(ps.p_primes)
+        ct = synth.uniform_residues(rng, basis[:ell], ps.N, lead=(2,))
+        pt = synth.uniform_residues(rng, basis, ps.N, lead=(n_rot,))
+        got = host(ctx.hrot_dh_mac_rescale_at(ell, dev(ct), gs, d_rks, dev(pt)))
+        assert np.array_equal(got, orc.hrot_dh_mac_rescale_level(ct, gs, rks, pt, P)), ell
+
+
+@pytest.mark.timeout(900)
+def test_config2_shape_merged_rescale_full_size(orc):
+    """N = 2^16, L = 24, K = 6, dnum = 4, batch 8: HMult+relin+rescale at levels 24 and 13; 17 double-hoisted
+    rotations with rescale at level 24."""
+    ps = synth.CFG2
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(2, 9)
+    B = synth.CFG2_BATCH
+    evk = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    d_evk = dev(evk)
+    for ell, check in ((24, (0, 5)), (13, (7,))):
+        q = ps.q_primes[:ell]
+        ct1 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
+        ct2 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
+        _say("cfg2 merged hmult level", ell)
+        got = host(ctx.hmult_relin_rescale_at(ell, dev(ct1), dev(ct2), d_evk))
+        for b in check:
+            assert np.array_equal(got[b], orc.hmult_relin_rescale_level(ct1[b], ct2[b], evk, P)), (ell, b)
+    gs = [synth.galois_element(r, ps.logN) for r in synth.CFG3_ROTATIONS]
+    rks = [np.roll(evk, i + 1, axis=-1) for i in range(len(gs))]
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    pt = synth.uniform_residues(rng, ps.primes, ps.N, lead=(len(gs),))
+    _say("cfg3 merged double hoisting")
+    got = host(ctx.hrot_dh_mac_rescale_at(ps.L, dev(ct), gs, [dev(k) for k in rks], dev(pt)))
+    assert np.array_equal(got, orc.hrot_dh_mac_rescale_level(ct, gs, rks, pt, P))
+
+
+def test_merged_rescale_error_paths(orc):
+    from paper_2310_16530_amd import binding
+    import torch
+    lib = binding.load()
+    ps = synth.small_params(12, 4, 2, 2)
+    ctx = gpu_ctx(ps)
+    x = torch.zeros((1, 2, ps.L, ps.N), dtype=torch.int64, device="cuda:0")
+    out = torch.empty_like(x)
+    key = torch.zeros((ps.dnum, 2, ps.L + ps.K, ps.N), dtype=torch.int64, device="cuda:0")
+    ws = ctx.workspace(binding.OP_HROT, 1)
+    h, p, o, k, w = ctx.handle, x.data_ptr(), out.data_ptr(), key.data_ptr(), ws.data_ptr()
+    for bad in (0, 1, ps.L + 1):
+        assert lib.ckks_hmult_relin_rescale_at(h, bad, p, p, k, o, 1, w, ws.numel(), None) == binding.CKKS_EINVAL
+    assert lib.ckks_hmult_relin_rescale_at(h, 3, p, p, k, o, 1, w, 128, None) == binding.CKKS_ENOMEM
+    t_only = gpu_ctx(synth.small_params(12, 2, 0, 1))
+    assert lib.ckks_hmult_relin_rescale_at(t_only.handle, 2, p, p, k, o, 1, w, ws.numel(), None) == binding.CKKS_EUNSUPPORTED
+    torch.cuda.synchronize()

@@ -750,3 +750,23 @@ def test_hmult_relin_rescale_merged_stays_next_to_the_two_step_result(orc, shape
             assert -ps.K <= diff.min() and diff.max() <= 1
         seen_different |= not np.array_equal(merged, two_step)
     assert seen_different
+
+
+@pytest.mark.parametrize("shape", LEVEL_SHAPES[:2])
+def test_double_hoisted_mac_rescale_merged_stays_next_to_the_two_step_result(orc, shape):
+    ps = _small_set(*shape)
+    P, rng, s, s_hat = _setup(orc, ps, 97)
+    gs = [synth.galois_element(r, ps.logN) for r in (1, -2, 4)]
+    rks = [_keys(orc, ps, P, rng, orc.automorph_limbs(s_hat, P, 0, g, True), s_hat)[0] for g in gs]
+    seen_different = False
+    for ell in range(ps.L, 1, -1):
+        q = list(ps.q_primes[:ell])
+        ct = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        pt = synth.uniform_residues(rng, q + list(ps.p_primes), ps.N, lead=(len(gs),))
+        merged = orc.hrot_dh_mac_rescale_level(ct, gs, rks, pt, P)
+        two_step = orc.rescale(orc.hrot_dh_mac_level(ct, gs, rks, pt, P), P)
+        for t in range(2):
+            diff = orc.centred_small(orc.pointwise("sub", merged[t], two_step[t], q[:-1]), P, ell - 1)
+            assert -ps.K <= diff.min() and diff.max() <= 1
+        seen_different |= not np.array_equal(merged, two_step)
+    assert seen_different
