@@ -768,7 +768,6 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             }
             return;
         }
-        double b1v[16], b2v[16];  // HMult: b1, b2 are read once and serve both components
 #pragma unroll
         for (int t = 0; t < 2; t++) {
             T v[16];
@@ -785,14 +784,14 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                 const u32 e = k * 16 + e0;
                 double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[e])) - v[k], pinv.d, fm);
                 if (MODE == FIN_HMULT || MODE == FIN_HMULT_RS) {
+                    // b1, b2 are read again for t = 1 (from L2): holding them would cost a wave of occupancy
+                    const double b1 = u64_to_f64(a.ct1[o0 + e]), b2 = u64_to_f64(a.ct2[o0 + e]);
                     double d;
                     if (t == 0) {
-                        b1v[k] = u64_to_f64(__builtin_nontemporal_load(&a.ct1[o0 + e]));
-                        b2v[k] = u64_to_f64(__builtin_nontemporal_load(&a.ct2[o0 + e]));
-                        d = FpAr::mulmod_lazy(b1v[k], b2v[k], fm);
+                        d = FpAr::mulmod_lazy(b1, b2, fm);
                     } else {
-                        d = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct1[o1 + e])), b2v[k], fm) +
-                            FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct2[o1 + e])), b1v[k], fm);
+                        d = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct1[o1 + e])), b2, fm) +
+                            FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct2[o1 + e])), b1, fm);
                     }
                     ks += MODE == FIN_HMULT_RS ? FpAr::mulmod_lazy(d, tb.qlinv[i].d, fm) : d;  // |d| <= 1.75 q
                 } else if (MODE == FIN_HROT) {

@@ -166,13 +166,13 @@ struct IntAr {
 };
 
 // ------------------------------------------------------------------------------- FpAr
-HD double u64_to_f64(u64 x) {  // exact for x < 2^53
-    return __builtin_fma((double)(u32)(x >> 32), 4294967296.0, (double)(u32)x);
+// Conversions between residues and doubles through the bit pattern of 2^52 + x: for 0 <= x < 2^52 the
+// double 2^52 + x has exponent 2^52 and x itself as its 52 mantissa bits (FpAr residues are below 2^50).
+HD double u64_to_f64(u64 x) {  // exact for x < 2^52
+    return __builtin_bit_cast(double, x | 0x4330000000000000ull) - 4503599627370496.0;
 }
-HD u64 f64_to_u64(double d) {  // exact for integer-valued 0 <= d < 2^53
-    u32 hi = (u32)(d * (1.0 / 4294967296.0));
-    u32 lo = (u32)__builtin_fma(-(double)hi, 4294967296.0, d);
-    return ((u64)hi << 32) | lo;
+HD u64 f64_to_u64(double d) {  // exact for integer-valued 0 <= d < 2^52
+    return __builtin_bit_cast(u64, d + 4503599627370496.0) & 0x000fffffffffffffull;
 }
 
 struct FpAr {
