@@ -34,19 +34,19 @@ VALU_PEAK_TINSTR = 256 * 64 * 2.4e9 / 1e12
 _MIB = 1 << 20
 MEASURED = {
     # kernel: (read MiB, write MiB, VALU wave-instructions)
-    "conv_fwd_strided_kernel<FpAr, 8, 1, 2>": (97.5, 292.4, 55597056),
-    "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": (61.8, 223.4, 55484416),
-    "conv_fwd_strided_kernel<IntAr, 8, 1, 1>": (114.7, 96.0, 58097664),
-    "inv_contig_kernel<FpAr, 8, 1>": (204.1, 96.0, 11341824),
-    "inv_contig_kernel<FpAr, 8, 2>": (108.1, 96.0, 11476992),
+    "conv_fwd_strided_kernel<FpAr, 8, 1, 2>": (96.8, 288.0, 55615488),
+    "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": (62.0, 223.1, 55484416),
+    "conv_fwd_strided_kernel<IntAr, 8, 1, 1>": (114.9, 96.0, 55775232),
+    "inv_contig_kernel<FpAr, 8, 1>": (204.1, 96.0, 10543104),
+    "inv_contig_kernel<FpAr, 8, 2>": (108.1, 96.0, 11071488),
     "inv_strided_kernel<FpAr, 8>": (96.6, 96.0, 9891840),
-    "inv_strided_kernel<IntAr, 8>": (48.5, 48.0, 13197312),
-    "ks_final_kernel<FpAr, 8, 1>": (984.3, 192.0, 32305152),
-    "ks_final_kernel<FpAr, 8, 2>": (499.4, 192.0, 26652672),
-    "ks_inner_kernel<FpAr, 8, 1, false>": (588.2, 192.0, 49041408),
-    "ks_inner_kernel<FpAr, 8, 2, false>": (492.2, 192.0, 49188864),
-    "ks_inner_kernel<IntAr, 8, 1, false>": (132.8, 48.0, 50257920),
-    "ks_inner_kernel<IntAr, 8, 2, false>": (132.8, 48.0, 50789376),
+    "inv_strided_kernel<IntAr, 8>": (48.5, 48.0, 13221888),
+    "ks_final_kernel<FpAr, 8, 1>": (982.7, 192.0, 27979776),
+    "ks_final_kernel<FpAr, 8, 2>": (500.3, 192.0, 24293376),
+    "ks_inner_kernel<FpAr, 8, 1, false>": (588.2, 192.0, 43929600),
+    "ks_inner_kernel<FpAr, 8, 2, false>": (492.2, 192.0, 44457984),
+    "ks_inner_kernel<IntAr, 8, 1, false>": (132.9, 48.0, 49904640),
+    "ks_inner_kernel<IntAr, 8, 2, false>": (132.8, 48.0, 50408448),
 }
 
 
