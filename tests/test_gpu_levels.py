@@ -308,3 +308,35 @@ def test_merged_rescale_error_paths(orc):
     t_only = gpu_ctx(synth.small_params(12, 2, 0, 1))
     assert lib.ckks_hmult_relin_rescale_at(t_only.handle, 2, p, p, k, o, 1, w, ws.numel(), None) == binding.CKKS_EUNSUPPORTED
     torch.cuda.synchronize()
+
+
+def test_two_stream_overlap_on_level_and_merged_entry_points(orc):
+    """The optional two-stream execution must not change a single word of the newer entry points either."""
+    ps = synth.small_params(13, 6, 3, 2)
+    ctx = gpu_ctx(ps)
+    rng = np.random.default_rng(29)
+    ell = 5
+    q = ps.q_primes[:ell]
+    ct1 = dev(synth.uniform_residues(rng, q, ps.N, lead=(3, 2)))
+    ct2 = dev(synth.uniform_residues(rng, q, ps.N, lead=(3, 2)))
+    key = dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)))
+    gs = [synth.galois_element(r, ps.logN) for r in range(1, 6)]
+    rks = [dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))) for _ in gs]
+    pt = dev(synth.uniform_residues(rng, list(q) + list(ps.p_primes), ps.N, lead=(len(gs),)))
+    one = ct1[0].contiguous()
+
+    def run():
+        return [host(ctx.hmult_relin_at(ell, ct1, ct2, key)), host(ctx.hrot_at(ell, ct1, gs[1], key)),
+                host(ctx.rescale(ell, ct1)), host(ctx.hmult_relin_rescale_at(ell, ct1, ct2, key)),
+                host(ctx.hrot_hoisted_mac_at(ell, one, gs, rks, pt[:, :ell].contiguous())),
+                host(ctx.hrot_dh_mac(one, gs, rks, pt, level=ell)),
+                host(ctx.hrot_dh_mac_rescale_at(ell, one, gs, rks, pt))]
+
+    ref = run()
+    ctx.set_overlap(True)
+    try:
+        for _ in range(3):
+            for a, b in zip(ref, run()):
+                assert np.array_equal(a, b)
+    finally:
+        ctx.set_overlap(False)

@@ -40,6 +40,7 @@ MUTATIONS = [
     ("orc_conv(in + (size_t)T * N, N, N, vprimes + T, ns, q, conv);", "orc_conv(in + (size_t)(T + 1) * N, N, N, vprimes + T + 1, ns - 1, q, conv);", "test_moddown_merged_vs_bigint"),
     ("            C0[n] = orc_addmod(C0[n], orc_mulmod(Pm, d0, m), m);", "            C0[n] = orc_addmod(C0[n], d0, m);", "test_hmult_relin_rescale_merged"),
     ("            C1[n] = orc_addmod(C1[n], orc_mulmod(Pm, d1, m), m);", "            C1[n] = orc_addmod(C1[n], orc_mulmod(Pm, d0, m), m);", "test_hmult_relin_rescale_merged"),
+    ("                dst[n] = orc_addmod(dst[n], orc_mulmod(Pm, orc_mulmod(ptr[n], sb[n], m), m), m);", "                dst[n] = orc_addmod(dst[n], orc_mulmod(ptr[n], sb[n], m), m);", "test_double_hoisted_mac_rescale_merged"),
 ]
 
 
