@@ -250,7 +250,16 @@ def main():
         extra["double_hoisted_rot_mac_per_s"] = round(len(rots) / dt, 1)
         # bytes that must come from HBM per rotation: the key (2*dnum*(L+K) limbs) and the plaintext (L+K limbs)
         extra["double_hoisted_key_stream_GBps"] = round(len(rots) * (2 * dnum + 1) * D * 8 * N / dt / 1e9, 1)
-        del rks, pt, ptx
+        # baby-step giant-step transform with 8 x 4 = 32 diagonals: 8 baby rotations computed once in the extended
+        # basis and shared by 4 giant steps, each followed by its own rotation
+        n1, n2 = 8, 4
+        bg = [synth.galois_element(r, ps.logN) for r in range(n1)]
+        gg = [synth.galois_element(r * n1, ps.logN) for r in range(n2)]
+        ptb = torch.stack([torch.roll(evk[0, 0], shifts=i, dims=-1) for i in range(n1 * n2)]).reshape(n2, n1, D, N).contiguous()
+        dt = timed(lambda: ctx.lintrans_bsgs_at(L, ct, bg, rks[:n1], gg, rks[n1:n1 + n2], ptb, o), reps, "lintrans_bsgs_8x4")
+        extra["bsgs_8x4_transforms_per_s"] = round(1.0 / dt, 1)
+        extra["bsgs_8x4_diagonals_per_s"] = round(n1 * n2 / dt, 1)
+        del rks, pt, ptx, ptb
 
     if "levels" in groups:
         # levels below L: rescale of the batch at level 24, and the HMult+relin -> rescale pair a CNN layer

@@ -261,6 +261,24 @@ int ckks_hrot_dh_mac_rescale_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d
                                 uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * Baby-step giant-step linear transform (the shape of the CoeffToSlot / SlotToCoeff stages of the
+ * bootstrapping the paper adopts, Table 1 "Boot"; diagonals are given as ready plaintext polynomials):
+ *   inner_g = double-hoisted rotate-multiply-accumulate of ct over the n1 baby rotations with the
+ *             plaintexts pt[g][0..n1)                         (the definition of ckks_hrot_dh_mac_at),
+ *   out     = sum_g HRot(inner_g, giant rotation g)           (the definition of ckks_hrot_at; limb-wise sum).
+ * Every rotation, identities (Galois element 1) included, is a key switch with the key given for it.
+ *   d_ct : [2][level][N];  d_pt : [n2][n1][level+K][N] on the level's extended basis;  d_out : [2][level][N];
+ *   h_*_galois / h_*_rk_ptrs : host arrays (n1 baby, n2 giant) of Galois elements and device key pointers;
+ *   1 <= n1, n2 <= 64.  The baby rotations are computed once, kept in the extended basis and shared by all
+ *   giant steps; results are identical to composing the two calls above.
+ */
+int ckks_lintrans_bsgs_workspace_bytes(const ckks_ctx* ctx, uint32_t level, uint32_t n1, uint32_t n2, size_t* bytes);
+int ckks_lintrans_bsgs_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n1, const uint32_t* h_baby_galois,
+                          const uint64_t* const* h_baby_rk_ptrs, uint32_t n2, const uint32_t* h_giant_galois,
+                          const uint64_t* const* h_giant_rk_ptrs, const uint64_t* d_pt, uint64_t* d_out, void* d_ws,
+                          size_t ws_bytes, void* stream);
+
+/*
  * Optional two-stream execution inside one call.  Off by default: every kernel of a call runs on the
  * caller's stream in order.  With on != 0 the key-switch entry points run the launches that work on
  * integer-arithmetic limbs (primes of 50 bits and more, normally the special limbs) on a second stream

@@ -393,6 +393,27 @@ def hrot_dh_mac_rescale_level(ct: np.ndarray, galois: Sequence[int], rks: Sequen
     return out
 
 
+def lintrans_bsgs_level(ct: np.ndarray, baby_galois: Sequence[int], baby_rks: Sequence[np.ndarray],
+                        giant_galois: Sequence[int], giant_rks: Sequence[np.ndarray], pt: np.ndarray,
+                        P: Params) -> np.ndarray:
+    """Baby-step giant-step linear transform as the composition of two defined operations:
+         inner_g = double-hoisted rotate-MAC of ct over the baby rotations with plaintexts pt[g][:]
+         out     = sum_g HRot(inner_g, giant rotation g)            (limb-wise sum)
+    ct [2][ell][N]; pt [n2][n1][ell+K][N]; every rotation, identities included, is a key switch."""
+    ct = np.ascontiguousarray(ct, dtype=np.uint64)
+    ell = ct.shape[1]
+    n1, n2 = len(baby_galois), len(giant_galois)
+    assert pt.shape == (n2, n1, ell + P.K, P.N) and len(baby_rks) == n1 and len(giant_rks) == n2
+    q = P.primes[:ell]
+    out = np.zeros((2, ell, P.N), dtype=np.uint64)
+    for g in range(n2):
+        inner = hrot_dh_mac_level(ct, baby_galois, baby_rks, np.ascontiguousarray(pt[g]), P)
+        rot = hrot_level(inner, giant_galois[g], giant_rks[g], P)
+        for t in range(2):
+            out[t] = pointwise("add", out[t], rot[t], q)
+    return out
+
+
 # ------------------------------------------------------------- harness helpers
 def lift_signed(v: np.ndarray, primes: Sequence[int]) -> np.ndarray:
     """Small signed coefficients [N] -> canonical residues [len(primes)][N]."""

@@ -28,6 +28,7 @@ EXPORTS = (
     "ckks_workspace_bytes_at", "ckks_keyswitch_at", "ckks_hmult_relin_at", "ckks_hrot_at",
     "ckks_hrot_hoisted_mac_at", "ckks_rescale", "ckks_hrot_dh_mac", "ckks_hrot_dh_mac_at",
     "ckks_hmult_relin_rescale_at", "ckks_hrot_dh_mac_rescale_at",
+    "ckks_lintrans_bsgs_workspace_bytes", "ckks_lintrans_bsgs_at",
 )
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
@@ -78,6 +79,8 @@ def load() -> ctypes.CDLL:
     lib.ckks_hrot_dh_mac_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_hmult_relin_rescale_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_dh_mac_rescale_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.ckks_lintrans_bsgs_workspace_bytes.argtypes = [_vp, _u32, _u32, _u32, ctypes.POINTER(_sz)]
+    lib.ckks_lintrans_bsgs_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_profile_enable.argtypes = [_vp, _int]
     lib.ckks_profile_read.argtypes = [_vp, _u32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(_u64),
                                       ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_u64)]
@@ -354,4 +357,28 @@ class Context:
         self._check(load().ckks_hrot_dh_mac_rescale_at(self.handle, level, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
                                                        ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out),
                                                        ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def lintrans_bsgs_at(self, level: int, ct: torch.Tensor, baby_galois: Sequence[int], baby_rks: Sequence[torch.Tensor],
+                         giant_galois: Sequence[int], giant_rks: Sequence[torch.Tensor], pt: torch.Tensor,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """pt [n2][n1][level+K][N]; out = sum_g HRot_g(sum_b pt[g][b] * HRot_b(ct)), baby steps double-hoisted."""
+        n1, n2 = len(baby_galois), len(giant_galois)
+        if len(baby_rks) != n1 or len(giant_rks) != n2 or pt.numel() != n1 * n2 * (level + self.K) * self.N:
+            raise ValueError("one key per rotation and one extended-basis plaintext per (giant, baby) pair")
+        if out is None:
+            out = torch.empty_like(ct)
+        need = _sz()
+        self._check(load().ckks_lintrans_bsgs_workspace_bytes(self.handle, level, n1, n2, ctypes.byref(need)))
+        if self._ws is None or self._ws.numel() < need.value:
+            self._ws = None
+            self._ws = torch.empty(need.value, dtype=torch.uint8, device=self.device)
+        bg = (ctypes.c_uint32 * n1)(*[int(x) for x in baby_galois])
+        gg = (ctypes.c_uint32 * n2)(*[int(x) for x in giant_galois])
+        bk = (ctypes.c_void_p * n1)(*[_dev_ptr(k) for k in baby_rks])
+        gk = (ctypes.c_void_p * n2)(*[_dev_ptr(k) for k in giant_rks])
+        self._check(load().ckks_lintrans_bsgs_at(self.handle, level, _dev_ptr(ct), n1, ctypes.cast(bg, _vp),
+                                                 ctypes.cast(bk, _vp), n2, ctypes.cast(gg, _vp), ctypes.cast(gk, _vp),
+                                                 _dev_ptr(pt), _dev_ptr(out), self._ws.data_ptr(), self._ws.numel(),
+                                                 _stream()))
         return out

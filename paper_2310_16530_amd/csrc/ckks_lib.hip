@@ -919,6 +919,28 @@ struct DhAccumL {
     }
 };
 
+struct BsgsMacL {
+    template <class AR, int A>
+    static void go(dim3 g, hipStream_t s, const BsgsMacArgs& a, const Tables& tb, LimbRun run) {
+        hipLaunchKernelGGL((bsgs_mac_kernel<AR, CKKS_DH_EPT>), g, dim3(256), 0, s, a, tb, run);
+    }
+    static std::string name(const char* ar, int) {
+        return std::string("bsgs_mac_kernel<") + ar + ", " + std::to_string(CKKS_DH_EPT) + ">";
+    }
+};
+
+static void launch_bsgs_mac(const View* c, const BsgsMacArgs& a, hipStream_t s) {
+    const u32 chunks = (1u << c->logN) / (256 * CKKS_DH_EPT);
+    for (const ClassRun& cr : class_runs(c, 0, c->D)) {
+        const LimbRun run = {cr.first, cr.count};
+        hipStream_t rs = (!cr.fp && c->sh->side.active) ? c->sh->side.stream : s;
+        // per limb and giant step: n1 rotations (2 components) and n1 plaintexts read, 2 components written
+        ProfScope ps(c, c->sh->prof.on ? BsgsMacL::name(cr.fp ? "FpAr" : "IntAr", 0) : std::string(),
+                     (u64)cr.count * a.n2 * (3 * (u64)a.n1 + 2), rs);
+        dispatch_kernel<BsgsMacL>(c, cr.fp, dim3(xcd_grid(cr.count * chunks, a.n2)), rs, a, run);
+    }
+}
+
 // one workgroup per 256 * CKKS_DH_EPT slots of a limb, all limbs of the extended basis
 static void launch_dh_accum(const View* c, const DhInnerArgs& a, hipStream_t s) {
     const u64 n_rot = a.n_rot, acc = a.accumulate ? 2 : 0, dnum = c->dnum;
@@ -1080,7 +1102,7 @@ static int ntt_entry(ckks_ctx* ctx, uint64_t* d_x, uint32_t prime_first, uint32_
         FwdContigArgs a2 = {d_x, sel};
         launch_fwd_contig(c, a2, s);
     } else {
-        InvContigArgs a1 = {d_x, nullptr, d_x, sel, sel, 1};
+        InvContigArgs a1 = {d_x, nullptr, d_x, sel, sel, {1}, 0};
         launch_inv_contig<INV_PLAIN>(c, a1, s);
         InvStridedArgs a2 = {d_x, sel, SC_PLAIN, 0};
         launch_inv_strided(c, a2, s);
@@ -1197,9 +1219,11 @@ static void moddown_convert(const View* c, const Workspace& w, u32 cg, hipStream
 
 // cm: the view whose ModDown ends the pipeline: c itself, or the merged view of c's level (the ModDown then
 // also divides by the last q-limb: limb c->L - 1 joins the special limbs and the output has c->L - 1 limbs)
+// multi_galois / multi_keys (rotations only, batch <= CKKS_ROT_CHUNK): one Galois element and key per instance.
 template <int LOAD, int OWN, int FIN>
 static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, const u64* in2, const u64* key, u64* out,
-                               u32 batch, u32 galois, void* ws, hipStream_t s) {
+                               u32 batch, u32 galois, void* ws, hipStream_t s, const u32* multi_galois = nullptr,
+                               const u64* const* multi_keys = nullptr) {
     Workspace w = carve(c, ws, batch, batch, batch);
     if (cm != c) {  // cq and cv shrink by one limb per component, cp grows by one: still inside the level's workspace
         const size_t N = (size_t)1 << c->logN;
@@ -1207,18 +1231,26 @@ static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, co
         w.cv = w.cp + (size_t)batch * 2 * cm->K * N;
     }
     const LimbSel sel = {c->L, batch, c->L, 0, 0, 0};
-    InvContigArgs a1 = {in1, in2, w.x, sel, sel, galois};
-    launch_inv_contig<LOAD>(c, a1, s);
-    decompose_extend(c, w, batch, s);
+    InvContigArgs a1;
+    memset(&a1, 0, sizeof(a1));
+    a1.src = in1, a1.src2 = in2, a1.dst = w.x, a1.sel = sel, a1.dsel = sel, a1.galois[0] = galois;
     InnerArgs ia;
     memset(&ia, 0, sizeof(ia));
-    ia.dt = w.dt, ia.own = in1, ia.own2 = in2, ia.key[0] = key, ia.galois[0] = galois;
+    FinalArgs fa;
+    memset(&fa, 0, sizeof(fa));
+    ia.key[0] = key, ia.galois[0] = galois, fa.galois[0] = galois;
+    if (multi_galois) {
+        a1.per_inst = ia.per_inst = fa.per_inst = 1;
+        for (u32 b = 0; b < batch; b++)
+            a1.galois[b] = ia.galois[b] = fa.galois[b] = multi_galois[b], ia.key[b] = multi_keys[b];
+    }
+    launch_inv_contig<LOAD>(c, a1, s);
+    decompose_extend(c, w, batch, s);
+    ia.dt = w.dt, ia.own = in1, ia.own2 = in2;
     ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = batch, ia.split = cm->L, ia.add_tensor = cm != c;
     launch_ks_inner<OWN, false>(c, ia, s);
     moddown_convert(cm, w, batch, s);
-    FinalArgs fa;
-    memset(&fa, 0, sizeof(fa));
-    fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = in1, fa.ct2 = in2, fa.out = out, fa.galois[0] = galois, fa.n_inst = batch;
+    fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = in1, fa.ct2 = in2, fa.out = out, fa.n_inst = batch;
     fa.cq_L = cm->L, fa.in_L = c->L;
     launch_ks_final<FIN>(cm, fa, s);
 }
@@ -1316,7 +1348,7 @@ extern "C" int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct,
     w.cv = w.cp + (size_t)batch * 2 * N;  // [b][2][level-1][N]
     const LimbSel src = {1, batch * 2, level, level - 1, level - 1, 0};  // limb level-1 of every component
     const LimbSel dst = {1, batch * 2, 1, 0, level - 1, 0};
-    InvContigArgs a1 = {d_ct, nullptr, w.cp, src, dst, 1};
+    InvContigArgs a1 = {d_ct, nullptr, w.cp, src, dst, {1}, 0};
     launch_inv_contig<INV_PLAIN>(c, a1, s);
     moddown_convert(c, w, batch, s);
     FinalArgs fa;
@@ -1354,7 +1386,7 @@ extern "C" int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uin
     {
         const LimbSel src = {c->L, 1, c->L, c->L, 0, 0};  // limbs L .. 2L-1 of ct, primes 0 .. L-1
         const LimbSel dst = {c->L, 1, c->L, 0, 0, 0};
-        InvContigArgs a1 = {d_ct, nullptr, w.x, src, dst, 1};
+        InvContigArgs a1 = {d_ct, nullptr, w.x, src, dst, {1}, 0};
         launch_inv_contig<INV_PLAIN>(c, a1, s);
         decompose_extend(c, w, 1, s);
         if (c->dnum > 1) {
@@ -1431,7 +1463,7 @@ static int dh_mac_impl(ckks_ctx* ctx, uint32_t level, bool rescale, const uint64
     {  // hoisted part, as in ckks_hrot_hoisted_mac
         const LimbSel src = {c->L, 1, c->L, c->L, 0, 0};
         const LimbSel dst = {c->L, 1, c->L, 0, 0, 0};
-        InvContigArgs a1 = {d_ct, nullptr, w.x, src, dst, 1};
+        InvContigArgs a1 = {d_ct, nullptr, w.x, src, dst, {1}, 0};
         launch_inv_contig<INV_PLAIN>(c, a1, s);
         decompose_extend(c, w, 1, s);
         if (c->dnum > 1) {
@@ -1453,7 +1485,7 @@ static int dh_mac_impl(ckks_ctx* ctx, uint32_t level, bool rescale, const uint64
     }
     {  // ModDown of the sum: first inverse pass of its source limbs, then the shared tail
         const LimbSel sel = {cm->K, 2, cm->K, 0, cm->L, 0};
-        InvContigArgs ic = {w.cp, nullptr, w.cp, sel, sel, 1};
+        InvContigArgs ic = {w.cp, nullptr, w.cp, sel, sel, {1}, 0};
         launch_inv_contig<INV_PLAIN>(cm, ic, s);
     }
     moddown_convert(cm, w, 1, s);
@@ -1482,4 +1514,111 @@ extern "C" int ckks_hrot_dh_mac(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t n_
                                 size_t ws_bytes, void* stream) {
     if (!ctx) return CKKS_EINVAL;
     return ckks_hrot_dh_mac_at(ctx, ctx->L, d_ct, n_rot, h_galois, h_rk_ptrs, d_pt, d_out, d_ws, ws_bytes, stream);
+}
+
+// ---------------------------------------------------------------- baby-step giant-step transform
+static size_t bsgs_workspace_words(const View* c, u32 n1, u32 n2) {
+    const size_t N = (size_t)1 << c->logN;
+    const u32 nc = n2 < CKKS_ROT_CHUNK ? n2 : CKKS_ROT_CHUNK;
+    const size_t limbs = (size_t)c->L + (size_t)c->dnum * c->D                      // x, dt of the input
+                         + (size_t)n1 * 2 * c->D                                     // baby rotations, extended basis
+                         + (size_t)n2 * 2 * (2 * (size_t)c->L + c->K)                // C on q / special limbs, converted part
+                         + (size_t)n2 * 2 * c->L * 2;                                // inner sums, rotated inner sums
+    return limbs * N + ks_workspace_words(c, nc, nc, nc);
+}
+
+extern "C" int ckks_lintrans_bsgs_workspace_bytes(const ckks_ctx* ctx, uint32_t level, uint32_t n1, uint32_t n2,
+                                                  size_t* bytes) {
+    if (!ctx || !bytes) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    if (c->K == 0) return fail(c, CKKS_EUNSUPPORTED, "context has no special primes");
+    if (n1 == 0 || n1 > 64 || n2 == 0 || n2 > 64) return fail(c, CKKS_EINVAL, "n1 and n2 must be between 1 and 64");
+    *bytes = bsgs_workspace_words(c, n1, n2) * sizeof(u64);
+    return CKKS_OK;
+}
+
+extern "C" int ckks_lintrans_bsgs_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n1,
+                                     const uint32_t* h_baby_galois, const uint64_t* const* h_baby_rk_ptrs, uint32_t n2,
+                                     const uint32_t* h_giant_galois, const uint64_t* const* h_giant_rk_ptrs,
+                                     const uint64_t* d_pt, uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    if (!h_baby_galois || !h_baby_rk_ptrs || !h_giant_galois || !h_giant_rk_ptrs) return fail(c, CKKS_EINVAL, "null host array");
+    if (!d_ct || !d_pt || !d_out || misaligned(d_ct, 16) || misaligned(d_pt, 16) || misaligned(d_out, 16))
+        return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    if (!d_ws || misaligned(d_ws, 256)) return fail(c, CKKS_EINVAL, "workspace is null or not 256-byte aligned");
+    size_t need = 0;
+    int rc = ckks_lintrans_bsgs_workspace_bytes(ctx, level, n1, n2, &need);
+    if (rc) return rc;
+    if (ws_bytes < need) return fail(c, CKKS_ENOMEM, "workspace too small");
+    for (u32 r = 0; r < n1 + n2; r++) {
+        const uint64_t* k = r < n1 ? h_baby_rk_ptrs[r] : h_giant_rk_ptrs[r - n1];
+        if (!k || misaligned(k, 16)) return fail(c, CKKS_EINVAL, "null or misaligned key");
+        rc = check_galois(c, r < n1 ? h_baby_galois[r] : h_giant_galois[r - n1]);
+        if (rc) return rc;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const size_t N = (size_t)1 << c->logN, LN = (size_t)c->L * N, KN = (size_t)c->K * N;
+    // workspace: x | dt | Rq | Rp | Cq | Cp | Cv | inner | rot | key-switch workspace of the giant rotations
+    Workspace w;
+    w.x = (u64*)d_ws;
+    w.dt = w.x + LN;
+    u64* rq = w.dt + (size_t)c->dnum * c->D * N;
+    u64* rp = rq + (size_t)n1 * 2 * LN;
+    w.cq = rp + (size_t)n1 * 2 * KN;
+    w.cp = w.cq + (size_t)n2 * 2 * LN;
+    w.cv = w.cp + (size_t)n2 * 2 * KN;
+    u64* inner = w.cv + (size_t)n2 * 2 * LN;
+    u64* rot = inner + (size_t)n2 * 2 * LN;
+    void* ks_ws = rot + (size_t)n2 * 2 * LN;
+    {  // decomposition of the input, shared by every baby step
+        const LimbSel src = {c->L, 1, c->L, c->L, 0, 0};
+        const LimbSel dst = {c->L, 1, c->L, 0, 0, 0};
+        InvContigArgs a1 = {d_ct, nullptr, w.x, src, dst, {1}, 0};
+        launch_inv_contig<INV_PLAIN>(c, a1, s);
+        decompose_extend(c, w, 1, s);
+        if (c->dnum > 1) {
+            FwdContigArgs q = {w.dt, LimbSel{c->L, c->dnum - 1, c->D, 0, 0, c->alpha}};
+            launch_fwd_contig(c, q, s);
+        }
+        FwdContigArgs p = {w.dt, LimbSel{c->K, c->dnum, c->D, c->L, c->L, 0}};
+        launch_fwd_contig(c, p, s);
+    }
+    // baby steps: R_b = P * Rot_b(ct) in the extended basis (inner product with the key, plus P * sigma_b(b))
+    for (u32 b = 0; b < n1; b++) {
+        DhInnerArgs ia;
+        memset(&ia, 0, sizeof(ia));
+        ia.key[0] = h_baby_rk_ptrs[b], ia.galois[0] = h_baby_galois[b];
+        ia.dt = w.dt, ia.ct = d_ct, ia.pt = nullptr, ia.cq = rq + (size_t)b * 2 * LN, ia.cp = rp + (size_t)b * 2 * KN;
+        ia.n_rot = 1, ia.accumulate = 0, ia.split = c->L;
+        launch_dh_accum(c, ia, s);
+    }
+    // giant-step combinations in the extended basis, then one ModDown per giant step (as a batch)
+    BsgsMacArgs ma = {rq, rp, d_pt, w.cq, w.cp, n1, n2};
+    launch_bsgs_mac(c, ma, s);
+    {
+        const LimbSel sel = {c->K, n2 * 2, c->K, 0, c->L, 0};
+        InvContigArgs ic = {w.cp, nullptr, w.cp, sel, sel, {1}, 0};
+        launch_inv_contig<INV_PLAIN>(c, ic, s);
+    }
+    moddown_convert(c, w, n2, s);
+    FinalArgs fa;
+    memset(&fa, 0, sizeof(fa));
+    fa.cq = w.cq, fa.cq_L = c->L, fa.in_L = c->L, fa.cv = w.cv, fa.out = inner, fa.n_inst = n2;
+    launch_ks_final<FIN_KS>(c, fa, s);
+    // giant rotations, each inner sum with its own key, then the sum
+    for (u32 g0 = 0; g0 < n2; g0 += CKKS_ROT_CHUNK) {
+        const u32 ng = (n2 - g0) < CKKS_ROT_CHUNK ? (n2 - g0) : CKKS_ROT_CHUNK;
+        keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, c, inner + (size_t)g0 * 2 * LN, nullptr, nullptr,
+                                                       rot + (size_t)g0 * 2 * LN, ng, 1, ks_ws, s, h_giant_galois + g0,
+                                                       h_giant_rk_ptrs + g0);
+    }
+    {
+        ProfScope ps(c, std::string("sum_instances_kernel"), (u64)(n2 + 1) * 2 * c->L, s);
+        hipLaunchKernelGGL(sum_instances_kernel, dim3((1u << c->logN) / 256, 2 * c->L), dim3(256), 0, s, rot, d_out,
+                           c->tb.pc, c->logN, c->L, 2 * c->L, n2);
+    }
+    return hip_check(c, "ckks_lintrans_bsgs");
 }

@@ -73,6 +73,9 @@ __device__ __forceinline__ size_t limb_offset(const LimbSel& s, u32 inst, u32 l)
     return (size_t)inst * s.gs + s.first + l;
 }
 
+// most rotations (each with its own key and Galois element) one launch can be given
+#define CKKS_ROT_CHUNK 8
+
 // ============================================================ inverse transform, first pass
 enum InvLoad { INV_PLAIN = 0, INV_TENSOR = 1, INV_ROT = 2 };
 struct InvContigArgs {
@@ -80,7 +83,8 @@ struct InvContigArgs {
     const u64* src2;  // TENSOR: ct2
     u64* dst;         // raw inverse-lazy words, addressed by dsel
     LimbSel sel, dsel;
-    u32 galois;
+    u32 galois[CKKS_ROT_CHUNK];  // ROT: [0], or one per instance when per_inst is set
+    u32 per_inst;
 };
 
 template <class AR, int A, int LOAD>
@@ -106,10 +110,11 @@ __device__ __forceinline__ void inv_contig_body(const InvContigArgs& a, const Ta
             x[k] = AR::round_reduce(AR::mul_canon(__builtin_nontemporal_load(&a.src[off + k * 16 + e0]), __builtin_nontemporal_load(&a.src2[off + k * 16 + e0]), pc, m), m);
         }
     } else {  // sigma_g(a) on limb l of ciphertext `inst`
+        const u32 gal = a.galois[a.per_inst ? inst : 0];
         const u64* p = a.src + (((size_t)inst * 2 + 1) * tb.L + l) * N;
 #pragma unroll
         for (int k = 0; k < 16; k++)
-            x[k] = AR::round_reduce(AR::from_canon(p[eval_perm(r * 256 + k * 16 + e0, a.galois, tb.logN)], m), m);
+            x[k] = AR::round_reduce(AR::from_canon(p[eval_perm(r * 256 + k * 16 + e0, gal, tb.logN)], m), m);
     }
     exchange_ca_to_cb<AR>(x, lrow, e0);
     NttCore<AR, A>::inv_contig(x, lrow, e0, r, ti, tf, N, m);
@@ -464,7 +469,6 @@ __global__ __launch_bounds__(256) void fwd_contig_kernel(FwdContigArgs a, Tables
 // digit's own limbs, the switched polynomial itself (copy | a1*a2 | sigma_g(a)) -- multiplied by
 // the two key components and accumulated.  q-limbs: c' is stored canonical.  Special limbs: the
 // first inverse pass of ModDown runs on the accumulators and raw words are stored.
-#define CKKS_ROT_CHUNK 8
 enum OwnLoad { OWN_COPY = 0, OWN_TENSOR = 1, OWN_ROT = 2 };
 struct InnerArgs {
     const u64* dt;    // [inst or 1][dnum][D][N]: raw forward-lazy (NTT_INSIDE) or canonical eval (hoisted)
@@ -478,6 +482,7 @@ struct InnerArgs {
     u32 split;    // limbs below split are stored to cq ([inst][2][split][N]), the others continue to cp: the number
                   // of q-limbs, or one less when the ModDown that follows also divides by the last q-limb
     u32 add_tensor;  // OWN_TENSOR with split < L: add P * (b1*b2, a1*b2 + a2*b1) on limb `split` before its inverse pass
+    u32 per_inst;    // not hoisted: every instance has its own key and Galois element (at most CKKS_ROT_CHUNK instances)
 };
 
 template <class AR, int A, int OWN, bool HOISTED>
@@ -493,8 +498,9 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
     const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
     u64* lrow = lds + ch * 272;
     const u32 row_off = r * 256;
-    const u64* key = a.key[HOISTED ? inst : 0] + (size_t)pi * N + row_off;
-    const u32 gal = HOISTED ? a.galois[inst] : a.galois[0];
+    const u32 kidx = (HOISTED || a.per_inst) ? inst : 0;
+    const u64* key = a.key[kidx] + (size_t)pi * N + row_off;
+    const u32 gal = a.galois[kidx];
     const u32 own_digit = i < L ? i / tb.alpha : 0xffffffffu;
     T acc0[16], acc1[16];
 #pragma unroll
@@ -610,7 +616,7 @@ __global__ __launch_bounds__(256) void ks_inner_kernel(InnerArgs a, Tables tb, L
 struct DhInnerArgs {
     const u64* dt;   // [dnum][D][N] canonical evaluation form
     const u64* ct;   // [2][L][N]
-    const u64* pt;   // [n_rot][D][N] canonical evaluation form, extended basis
+    const u64* pt;   // [n_rot][D][N] canonical evaluation form, extended basis; null = the constant 1
     const u64* key[CKKS_DH_CHUNK];
     u32 galois[CKKS_DH_CHUNK];
     u64* cq;         // [2][L][N]
@@ -649,7 +655,7 @@ __global__ __launch_bounds__(256) void dh_accum_kernel(DhInnerArgs a, Tables tb,
         u32 idx[EPT];
 #pragma unroll
         for (int k = 0; k < EPT; k++) {
-            ptv[k] = __builtin_nontemporal_load(&ptp[k * 256]);
+            ptv[k] = a.pt ? __builtin_nontemporal_load(&ptp[k * 256]) : 1;
             idx[k] = eval_perm(base + k * 256, gal, tb.logN);
         }
         for (u32 j = 0; j < tb.dnum; j++) {
@@ -695,6 +701,82 @@ __global__ __launch_bounds__(256) void dh_accum_kernel(DhInnerArgs a, Tables tb,
     }
 }
 
+// ==================================================== baby-step giant-step accumulation and sums
+// C[g][t][i] = sum_b pt[g][b][i] * R[b][t][i] on every limb i of the extended basis: the giant-step
+// combinations of the baby-step rotations R_b (kept in the extended basis, times P).  Element-parallel;
+// one workgroup per 256 * EPT slots of (limb, giant step).
+struct BsgsMacArgs {
+    const u64* rq;  // [n1][2][L][N]  q-limbs of R_b
+    const u64* rp;  // [n1][2][K][N]  special limbs of R_b
+    const u64* pt;  // [n2][n1][D][N]
+    u64* cq;        // [n2][2][L][N]
+    u64* cp;        // [n2][2][K][N]
+    u32 n1, n2;
+};
+
+template <class AR, int EPT>
+__global__ __launch_bounds__(256) void bsgs_mac_kernel(BsgsMacArgs a, Tables tb, LimbRun run) {
+    typedef typename AR::T T;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x, L = tb.L, K = tb.K, D = tb.D;
+    const u32 chunks = N / (256 * EPT);
+    // the giant steps of one (limb, slot range) share the R_b they read: adjacent on one XCD
+    u32 rest, g;
+    if (!xcd_decode(blockIdx.x, a.n2, run.count * chunks, rest, g)) return;
+    const u32 i = run.first + rest / chunks, base = (rest % chunks) * (256 * EPT) + tid;
+    const PrimeConst pc = tb.pc[tb.phys(i)];
+    const typename AR::Mod m = AR::mod(pc);
+    const bool is_q = i < L;
+    T acc0[EPT], acc1[EPT];
+    u128w w0[EPT], w1[EPT];
+#pragma unroll
+    for (int k = 0; k < EPT; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero(), w0[k] = u128w{0, 0}, w1[k] = u128w{0, 0};
+    for (u32 b = 0; b < a.n1; b++) {
+        const u64* r0 = (is_q ? a.rq + (((size_t)b * 2 + 0) * L + i) * N : a.rp + (((size_t)b * 2 + 0) * K + (i - L)) * N) + base;
+        const u64* r1 = (is_q ? a.rq + (((size_t)b * 2 + 1) * L + i) * N : a.rp + (((size_t)b * 2 + 1) * K + (i - L)) * N) + base;
+        const u64* pp = a.pt + (((size_t)g * a.n1 + b) * D + i) * N + base;
+#pragma unroll
+        for (int k = 0; k < EPT; k++) {
+            const u64 pv = __builtin_nontemporal_load(&pp[k * 256]);
+            if constexpr (AR::is_fp) {
+                acc0[k] += AR::premul(r0[k * 256], pv, m);
+                acc1[k] += AR::premul(r1[k * 256], pv, m);
+            } else {  // at most 64 products below 2^122 fit the 128-bit accumulator
+                mac128(w0[k], r0[k * 256], pv);
+                mac128(w1[k], r1[k * 256], pv);
+            }
+        }
+        if constexpr (AR::is_fp) {
+            if ((b & 7) == 7) {
+#pragma unroll
+                for (int k = 0; k < EPT; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
+            }
+        }
+    }
+    u64* o0 = (is_q ? a.cq + (((size_t)g * 2 + 0) * L + i) * N : a.cp + (((size_t)g * 2 + 0) * K + (i - L)) * N) + base;
+    u64* o1 = (is_q ? a.cq + (((size_t)g * 2 + 1) * L + i) * N : a.cp + (((size_t)g * 2 + 1) * K + (i - L)) * N) + base;
+#pragma unroll
+    for (int k = 0; k < EPT; k++) {
+        if constexpr (AR::is_fp) {
+            o0[k * 256] = AR::acc_canon(AR::acc_finish(acc0[k], m), m);
+            o1[k * 256] = AR::acc_canon(AR::acc_finish(acc1[k], m), m);
+        } else {
+            o0[k * 256] = reduce128(w0[k], pc.q, pc.qneg, pc.r2);
+            o1[k * 256] = reduce128(w1[k], pc.q, pc.qneg, pc.r2);
+        }
+    }
+}
+
+// out[l][n] = sum_g in[g][l][n] mod q_l over n_limbs limbs per item (limb l uses prime l % L).
+__global__ __launch_bounds__(256) void sum_instances_kernel(const u64* __restrict__ in, u64* __restrict__ out,
+                                                            const PrimeConst* pcs, u32 logN, u32 L, u32 n_limbs, u32 n_g) {
+    const u32 N = 1u << logN;
+    const u32 n = blockIdx.x * 256 + threadIdx.x, l = blockIdx.y;
+    const u64 q = pcs[l % L].q;
+    u64 acc = 0;
+    for (u32 g = 0; g < n_g; g++) acc = addmod(acc, in[((size_t)g * n_limbs + l) * N + n], q);
+    out[(size_t)l * N + n] = acc;
+}
+
 // ======================================================================== final combine
 // ks_t[i] = (c'_t[i] - NTT(conv_t)[i]) * P^-1 mod q_i, the NTT's second pass done here, then
 //   FIN_KS     : out[inst][t][i] = ks
@@ -717,6 +799,7 @@ struct FinalArgs {
     u32 accumulate;  // HOISTED: add to what out already holds
     u32 cq_L;        // limbs per component of cq (L, or L + 1 when cq is a ciphertext about to lose its last limb)
     u32 in_L;        // limbs per component of ct1 / ct2 (L, or L + 1 for FIN_HMULT_RS)
+    u32 per_inst;    // FIN_HROT: one Galois element per instance
 };
 
 template <class AR, int A, int MODE>
@@ -795,7 +878,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                     }
                     ks += MODE == FIN_HMULT_RS ? FpAr::mulmod_lazy(d, tb.qlinv[i].d, fm) : d;  // |d| <= 1.75 q
                 } else if (MODE == FIN_HROT) {
-                    if (t == 0) ks += u64_to_f64(a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[0], tb.logN)]);
+                    if (t == 0) ks += u64_to_f64(a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[a.per_inst ? inst : 0], tb.logN)]);
                 }
                 __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[e]);
             }
@@ -860,7 +943,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                 if (MODE == FIN_HMULT_RS) d = mul_shoup(d, tb.qlinv[i].w, tb.qlinv[i].wp, q);
                 ks = addmod(ks, d, q);
             } else if (MODE == FIN_HROT) {
-                if (t == 0) ks = addmod(ks, a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[0], tb.logN)], q);
+                if (t == 0) ks = addmod(ks, a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[a.per_inst ? inst : 0], tb.logN)], q);
             }
             o[e] = ks;
         }

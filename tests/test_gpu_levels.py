@@ -340,3 +340,48 @@ def test_two_stream_overlap_on_level_and_merged_entry_points(orc):
                 assert np.array_equal(a, b)
     finally:
         ctx.set_overlap(False)
+
+
+# ------------------------------------------------ baby-step giant-step linear transform
+@pytest.mark.parametrize("shape,n1,n2", [((12, 6, 2, 3, 49, 59), 3, 2), ((13, 6, 3, 2, 49, 59), 4, 3),
+                                         ((12, 4, 2, 2, 55, 59), 2, 2), ((12, 3, 1, 3, 35, 36), 9, 10)])
+def test_bsgs_linear_transform_parity(orc, shape, n1, n2):
+    """Includes identity rotations (Galois element 1) and more giant steps than one launch takes (10 > 8)."""
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(11000 + sum(shape))
+    baby = [synth.galois_element(r, ps.logN) for r in range(n1)]
+    giant = [synth.galois_element(r * n1, ps.logN) for r in range(n2)]
+    assert baby[0] == 1 and giant[0] == 1
+    baby_rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in baby]
+    giant_rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in giant]
+    d_baby, d_giant = [dev(k) for k in baby_rks], [dev(k) for k in giant_rks]
+    for ell in sorted({ps.L, max(ps.alpha + 1, 2) if ps.L > 2 else ps.L, 1}, reverse=True):
+        _say("bsgs", shape, "level", ell)
+        basis = list(ps.q_primes[:ell]) + list(ps.p_primes)
+        ct = synth.uniform_residues(rng, basis[:ell], ps.N, lead=(2,))
+        pt = synth.uniform_residues(rng, basis, ps.N, lead=(n2, n1))
+        want = orc.lintrans_bsgs_level(ct, baby, baby_rks, giant, giant_rks, pt, P)
+        got = host(ctx.lintrans_bsgs_at(ell, dev(ct), baby, d_baby, giant, d_giant, dev(pt)))
+        assert np.array_equal(got, want), ell
+
+
+@pytest.mark.timeout(900)
+def test_bsgs_linear_transform_full_size(orc):
+    """N = 2^16, L = 24, K = 6, dnum = 4: 8 baby steps x 4 giant steps (32 diagonals) at level 24."""
+    ps = synth.CFG2
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(4, 11)
+    n1, n2 = 8, 4
+    baby = [synth.galois_element(r, ps.logN) for r in range(n1)]
+    giant = [synth.galois_element(r * n1, ps.logN) for r in range(n2)]
+    base = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    baby_rks = [np.roll(base, i + 1, axis=-1) for i in range(n1)]
+    giant_rks = [np.roll(base, 100 + i, axis=-1) for i in range(n2)]
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    pt = synth.uniform_residues(rng, ps.primes, ps.N, lead=(n2, n1))
+    _say("bsgs full size: gpu")
+    got = host(ctx.lintrans_bsgs_at(ps.L, dev(ct), baby, [dev(k) for k in baby_rks], giant, [dev(k) for k in giant_rks],
+                                    dev(pt)))
+    _say("bsgs full size: oracle")
+    assert np.array_equal(got, orc.lintrans_bsgs_level(ct, baby, baby_rks, giant, giant_rks, pt, P))

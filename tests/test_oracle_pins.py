@@ -770,3 +770,45 @@ def test_double_hoisted_mac_rescale_merged_stays_next_to_the_two_step_result(orc
             assert -ps.K <= diff.min() and diff.max() <= 1
         seen_different |= not np.array_equal(merged, two_step)
     assert seen_different
+
+
+# ------------------------------------------------- baby-step giant-step transform
+def test_bsgs_linear_transform_decrypts_to_the_sum_of_rotated_products(orc):
+    """Dec(out) = sum_g sum_b sigma_G(pt[g][b]) * sigma_{G*g_b}(m) up to the noise of n2 double-hoisted sums
+    (each rotated once more) and n2 key switches."""
+    ps = _small_set(6, 6, 2, 3, 20, 22)
+    P, rng, s, s_hat = _setup(orc, ps, 101)
+    h = int(np.abs(s).sum())
+    baby = [synth.galois_element(r, ps.logN) for r in (0, 1, 2)]
+    giant = [synth.galois_element(r, ps.logN) for r in (0, 3)]
+    baby_rks = [_keys(orc, ps, P, rng, orc.automorph_limbs(s_hat, P, 0, g, True), s_hat)[0] for g in baby]
+    giant_rks = [_keys(orc, ps, P, rng, orc.automorph_limbs(s_hat, P, 0, g, True), s_hat)[0] for g in giant]
+    for ell in (ps.L, 3):
+        q = list(ps.q_primes[:ell])
+        sq = s_hat[:ell]
+
+        def dec(c):
+            return orc.pointwise("add", c[0], orc.pointwise("mul", c[1], sq, q), q)
+
+        ct = synth.uniform_residues(rng, q, ps.N, lead=(2,))
+        pts, l1s = [], []
+        for g in giant:
+            ptg, l1 = _small_plaintexts(orc, rng, P, len(baby), ell, amp=2)
+            pts.append(ptg)
+            l1s.append(sum(l1))
+        pt = np.stack(pts)
+        out = orc.lintrans_bsgs_level(ct, baby, baby_rks, giant, giant_rks, pt, P)
+        want = np.zeros((ell, ps.N), dtype=np.uint64)
+        m = dec(ct)
+        for gi, G in enumerate(giant):
+            for bi, gb in enumerate(baby):
+                term = orc.pointwise("mul", pt[gi, bi, :ell], orc.automorph_limbs(m, P, 0, gb, True), q)
+                want = orc.pointwise("add", want, orc.automorph_limbs(term, P, 0, G, True), q)
+        E = orc.centred_small(orc.pointwise("sub", dec(out), want, q), P, ell)
+        bound = sum(orc.dh_mac_noise_bound(P, h, l1, level=ell) for l1 in l1s) \
+            + len(giant) * orc.keyswitch_noise_bound(P, h, level=ell)
+        assert 0 < np.abs(E).max() <= bound < min(q) // 4
+        # a single giant step with the identity-free structure reduces to its parts
+        one = orc.lintrans_bsgs_level(ct, baby, baby_rks, giant[1:], giant_rks[1:], pt[1:], P)
+        inner = orc.hrot_dh_mac_level(ct, baby, baby_rks, pt[1], P)
+        assert np.array_equal(one, orc.hrot_level(inner, giant[1], giant_rks[1], P))
