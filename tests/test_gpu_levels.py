@@ -385,3 +385,45 @@ def test_bsgs_linear_transform_full_size(orc):
                                     dev(pt)))
     _say("bsgs full size: oracle")
     assert np.array_equal(got, orc.lintrans_bsgs_level(ct, baby, baby_rks, giant, giant_rks, pt, P))
+
+
+def test_entry_points_can_be_captured_in_a_graph_and_replayed(orc):
+    """The library allocates nothing and issues only kernel launches, so a caller may capture its calls in a
+    HIP graph.  Every replay (with eager work and synchronisations in between) must reproduce the eager result."""
+    import torch
+    ps = synth.small_params(13, 6, 3, 2)
+    ctx = gpu_ctx(ps)
+    rng = np.random.default_rng(31)
+    ell = 5
+    q = ps.q_primes[:ell]
+    ct1 = dev(synth.uniform_residues(rng, q, ps.N, lead=(2, 2)))
+    ct2 = dev(synth.uniform_residues(rng, q, ps.N, lead=(2, 2)))
+    key = dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)))
+    gs = [synth.galois_element(r, ps.logN) for r in range(1, 4)]
+    rks = [dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))) for _ in gs]
+    pt = dev(synth.uniform_residues(rng, list(q) + list(ps.p_primes), ps.N, lead=(len(gs),)))
+    one = ct1[0].contiguous()
+    o_mult, o_low, o_rot = torch.empty_like(ct1), torch.empty_like(ct1[:, :, :ell - 1]).contiguous(), torch.empty_like(ct1)
+    o_dh = torch.empty_like(one)
+    # size the shared workspace for the largest call before capturing (no allocation may happen inside)
+    for _ in range(2):
+        ctx.hmult_relin_at(ell, ct1, ct2, key, o_mult)
+        ctx.rescale(ell, o_mult, o_low)
+        ctx.hrot_at(ell, ct1, gs[0], key, o_rot)
+        ctx.hrot_dh_mac(one, gs, rks, pt, o_dh, level=ell)
+    torch.cuda.synchronize()
+    want = [host(o_mult).copy(), host(o_low).copy(), host(o_rot).copy(), host(o_dh).copy()]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.hmult_relin_at(ell, ct1, ct2, key, o_mult)
+        ctx.rescale(ell, o_mult, o_low)
+        ctx.hrot_at(ell, ct1, gs[0], key, o_rot)
+        ctx.hrot_dh_mac(one, gs, rks, pt, o_dh, level=ell)
+    for rep in range(3):
+        for o in (o_mult, o_low, o_rot, o_dh):
+            o.fill_(rep + 7)                      # eager work between replays; also destroys the previous result
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(want, (o_mult, o_low, o_rot, o_dh)):
+            assert np.array_equal(a, host(b)), rep
