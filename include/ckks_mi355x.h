@@ -92,7 +92,9 @@ int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint3
                     const uint64_t* h_primes, const uint64_t* h_psi, void* d_tables, size_t table_bytes,
                     void* stream);
 
-/* Frees host state only. NULL is allowed. */
+/* Frees host state only. NULL is allowed.  A context (its error string, profiling state, optional second
+ * stream) is not synchronised: use it from one host thread at a time; device work of different calls on
+ * different streams may overlap only if they use different workspaces. */
 void ckks_ctx_destroy(ckks_ctx* ctx);
 
 /* Message of the last error on this context (owned by the context; "" if none). */
@@ -259,6 +261,15 @@ int ckks_hmult_relin_rescale_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d
 int ckks_hrot_dh_mac_rescale_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
                                 const uint32_t* h_galois, const uint64_t* const* h_rk_ptrs, const uint64_t* d_pt,
                                 uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Rotations of a batch of ciphertexts, instance b by the Galois element h_galois[b] with the key h_rk_ptrs[b]
+ * (host arrays of `batch` entries): out[b] = ckks_hrot_at(level, ct[b], h_galois[b], rk_b).  Issued in chunks of
+ * 8 instances; the workspace of CKKS_OP_HROT for min(batch, 8) at that level suffices.
+ */
+int ckks_hrot_multi_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, const uint32_t* h_galois,
+                       const uint64_t* const* h_rk_ptrs, uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes,
+                       void* stream);
 
 /*
  * Baby-step giant-step linear transform (the shape of the CoeffToSlot / SlotToCoeff stages of the

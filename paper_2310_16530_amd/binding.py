@@ -28,7 +28,7 @@ EXPORTS = (
     "ckks_workspace_bytes_at", "ckks_keyswitch_at", "ckks_hmult_relin_at", "ckks_hrot_at",
     "ckks_hrot_hoisted_mac_at", "ckks_rescale", "ckks_hrot_dh_mac", "ckks_hrot_dh_mac_at",
     "ckks_hmult_relin_rescale_at", "ckks_hrot_dh_mac_rescale_at",
-    "ckks_lintrans_bsgs_workspace_bytes", "ckks_lintrans_bsgs_at",
+    "ckks_lintrans_bsgs_workspace_bytes", "ckks_lintrans_bsgs_at", "ckks_hrot_multi_at",
 )
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
@@ -79,6 +79,7 @@ def load() -> ctypes.CDLL:
     lib.ckks_hrot_dh_mac_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_hmult_relin_rescale_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_dh_mac_rescale_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.ckks_hrot_multi_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_lintrans_bsgs_workspace_bytes.argtypes = [_vp, _u32, _u32, _u32, ctypes.POINTER(_sz)]
     lib.ckks_lintrans_bsgs_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_profile_enable.argtypes = [_vp, _int]
@@ -381,4 +382,19 @@ class Context:
                                                  ctypes.cast(bk, _vp), n2, ctypes.cast(gg, _vp), ctypes.cast(gk, _vp),
                                                  _dev_ptr(pt), _dev_ptr(out), self._ws.data_ptr(), self._ws.numel(),
                                                  _stream()))
+        return out
+
+    def hrot_multi_at(self, level: int, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor],
+                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """ct [batch][2][level][N]; instance b is rotated by galois[b] with key rks[b]."""
+        batch = len(galois)
+        if len(rks) != batch or ct.numel() != batch * 2 * level * self.N:
+            raise ValueError("one Galois element and one key per ciphertext")
+        if out is None:
+            out = torch.empty_like(ct)
+        g = (ctypes.c_uint32 * batch)(*[int(x) for x in galois])
+        ptrs = (ctypes.c_void_p * batch)(*[_dev_ptr(k) for k in rks])
+        ws = self.workspace(OP_HROT, min(batch, 8), level)
+        self._check(load().ckks_hrot_multi_at(self.handle, level, _dev_ptr(ct), ctypes.cast(g, _vp), ctypes.cast(ptrs, _vp),
+                                              _dev_ptr(out), batch, ws.data_ptr(), ws.numel(), _stream()))
         return out

@@ -1622,3 +1622,31 @@ extern "C" int ckks_lintrans_bsgs_at(ckks_ctx* ctx, uint32_t level, const uint64
     }
     return hip_check(c, "ckks_lintrans_bsgs");
 }
+
+// Rotations of a batch of ciphertexts, each by its own Galois element with its own key (the giant steps of a
+// linear transform, or the independent rotations of several activations): chunks of CKKS_ROT_CHUNK instances.
+extern "C" int ckks_hrot_multi_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, const uint32_t* h_galois,
+                                  const uint64_t* const* h_rk_ptrs, uint64_t* d_out, uint32_t batch, void* d_ws,
+                                  size_t ws_bytes, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = view_at(ctx, level);
+    if (!c) return CKKS_EINVAL;
+    if (!h_galois || !h_rk_ptrs) return fail(c, CKKS_EINVAL, "null host array");
+    if (batch == 0) return fail(c, CKKS_EINVAL, "batch out of range");
+    const u32 chunk = batch < CKKS_ROT_CHUNK ? batch : CKKS_ROT_CHUNK;
+    int rc = check_ks_args(c, d_ct, h_rk_ptrs[0], d_out, chunk, CKKS_OP_HROT, d_ws, ws_bytes);
+    if (rc) return rc;
+    if (batch > 4096) return fail(c, CKKS_EINVAL, "batch out of range");
+    for (u32 b = 0; b < batch; b++) {
+        if (!h_rk_ptrs[b] || misaligned(h_rk_ptrs[b], 16)) return fail(c, CKKS_EINVAL, "null or misaligned key");
+        rc = check_galois(c, h_galois[b]);
+        if (rc) return rc;
+    }
+    const size_t ct_words = ((size_t)2 * c->L) << c->logN;
+    for (u32 b0 = 0; b0 < batch; b0 += CKKS_ROT_CHUNK) {
+        const u32 nb = (batch - b0) < CKKS_ROT_CHUNK ? (batch - b0) : CKKS_ROT_CHUNK;
+        keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, c, d_ct + b0 * ct_words, nullptr, nullptr, d_out + b0 * ct_words, nb,
+                                                       1, d_ws, (hipStream_t)stream, h_galois + b0, h_rk_ptrs + b0);
+    }
+    return hip_check(c, "ckks_hrot_multi");
+}

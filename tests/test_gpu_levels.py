@@ -427,3 +427,19 @@ def test_entry_points_can_be_captured_in_a_graph_and_replayed(orc):
         torch.cuda.synchronize()
         for a, b in zip(want, (o_mult, o_low, o_rot, o_dh)):
             assert np.array_equal(a, host(b)), rep
+
+
+def test_hrot_multi_parity(orc):
+    """11 ciphertexts, each rotated by its own element with its own key (two launches: 8 + 3 instances)."""
+    ps = synth.small_params(12, 6, 2, 3)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(41)
+    B = 11
+    gs = [synth.galois_element(r, ps.logN) for r in (0, 1, -1, 2, 3, 5, 8, 13, 21, 34, 55)]
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    d_rks = [dev(k) for k in rks]
+    for ell in (ps.L, 3):
+        ct = synth.uniform_residues(rng, ps.q_primes[:ell], ps.N, lead=(B, 2))
+        got = host(ctx.hrot_multi_at(ell, dev(ct), gs, d_rks))
+        for b in range(B):
+            assert np.array_equal(got[b], orc.hrot_level(ct[b], gs[b], rks[b], P)), (ell, b)
