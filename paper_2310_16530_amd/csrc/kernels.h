@@ -301,64 +301,68 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
     const u32 rot = ns ? (inst + tile) % ns : 0;  // workgroups sharing sources walk them in different orders
     T x[TB][16];
     if (all_fp) {
-        // FP64 pipe: every product reduced lazily (|.| <= 1.25 q), at most 16 of them accumulated
-        double acc[TB][16];
+        // FP64 pipe: every product reduced lazily (|.| <= 1.25 q), at most 18 of them accumulated.  The 16
+        // words of a lane are converted in two halves so that accumulators and staged sources stay small.
         FpAr::Mod fm[TB];
 #pragma unroll
-        for (int t = 0; t < TB; t++) {
-            fm[t] = FpAr::mod(tb.pc[tb.phys(pi[t])]);
+        for (int t = 0; t < TB; t++) fm[t] = FpAr::mod(tb.pc[tb.phys(pi[t])]);
 #pragma unroll
-            for (int k = 0; k < 16; k++) acc[t][k] = 0.0;
-        }
-        // the loads of source i+1 are issued before the arithmetic on source i (software pipeline)
-        u64 cur[16], nxt[16];
-        {
-            const u64* s0 = src + (size_t)rot * N;
+        for (int hf = 0; hf < 2; hf++) {
+            double acc[TB][8];
 #pragma unroll
-            for (int k = 0; k < 16; k++) cur[k] = s0[(size_t)(k * C::RB + r0) * 256 + col];
-        }
-        for (u32 i0 = 0; i0 < ns; i0++) {
-            const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
-            if (i0 + 1 < ns) {
-                const u32 in = i0 + 1 + rot < ns ? i0 + 1 + rot : i0 + 1 + rot - ns;
-                const u64* sn = src + (size_t)in * N;
+            for (int t = 0; t < TB; t++)
 #pragma unroll
-                for (int k = 0; k < 16; k++) nxt[k] = sn[(size_t)(k * C::RB + r0) * 256 + col];
+                for (int k = 0; k < 8; k++) acc[t][k] = 0.0;
+            // the loads of source i+1 are issued before the arithmetic on source i (software pipeline)
+            u64 cur[8], nxt[8];
+            {
+                const u64* s0 = src + (size_t)rot * N;
+#pragma unroll
+                for (int k = 0; k < 8; k++) cur[k] = s0[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
             }
-            if (DIR == CONV_UP) {  // sources are doubles holding canonical residues of ~the targets' size
-                double cf[TB];
+            for (u32 i0 = 0; i0 < ns; i0++) {
+                const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
+                if (i0 + 1 < ns) {
+                    const u32 in = i0 + 1 + rot < ns ? i0 + 1 + rot : i0 + 1 + rot - ns;
+                    const u64* sn = src + (size_t)in * N;
 #pragma unroll
-                for (int t = 0; t < TB; t++) cf[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
-#pragma unroll
-                for (int k = 0; k < 16; k++) {
-                    const double y = FpAr::from_raw(cur[k]);
-#pragma unroll
-                    for (int t = 0; t < TB; t++) acc[t][k] += FpAr::mulmod_lazy(y, cf[t], fm[t]);
+                    for (int k = 0; k < 8; k++) nxt[k] = sn[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
                 }
-            } else {  // sources are words below 2^61: y = yh * 2^30 + yl, y*c = yh * (c * 2^30) + yl * c (mod q)
-                double cl[TB], ch[TB];
+                if (DIR == CONV_UP) {  // sources are doubles holding canonical residues of ~the targets' size
+                    double cf[TB];
 #pragma unroll
-                for (int t = 0; t < TB; t++) {
-                    cl[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2];
-                    ch[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2 + 1];
+                    for (int t = 0; t < TB; t++) cf[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
+#pragma unroll
+                    for (int k = 0; k < 8; k++) {
+                        const double y = FpAr::from_raw(cur[k]);
+#pragma unroll
+                        for (int t = 0; t < TB; t++) acc[t][k] += FpAr::mulmod_lazy(y, cf[t], fm[t]);
+                    }
+                } else {  // sources are words below 2^61: y = yh * 2^30 + yl, y*c = yh * (c * 2^30) + yl * c (mod q)
+                    double cl[TB], ch[TB];
+#pragma unroll
+                    for (int t = 0; t < TB; t++) {
+                        cl[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2];
+                        ch[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2 + 1];
+                    }
+#pragma unroll
+                    for (int k = 0; k < 8; k++) {
+                        const u64 y = cur[k];
+                        const double yh = (double)(u32)(y >> 30), yl = (double)(u32)(y & 0x3fffffffu);
+#pragma unroll
+                        for (int t = 0; t < TB; t++)
+                            acc[t][k] += FpAr::mulmod_lazy(yh, ch[t], fm[t]) + FpAr::mulmod_lazy(yl, cl[t], fm[t]);
+                    }
                 }
 #pragma unroll
-                for (int k = 0; k < 16; k++) {
-                    const u64 y = cur[k];
-                    const double yh = (double)(u32)(y >> 30), yl = (double)(u32)(y & 0x3fffffffu);
-#pragma unroll
-                    for (int t = 0; t < TB; t++)
-                        acc[t][k] += FpAr::mulmod_lazy(yh, ch[t], fm[t]) + FpAr::mulmod_lazy(yl, cl[t], fm[t]);
-                }
+                for (int k = 0; k < 8; k++) cur[k] = nxt[k];
             }
 #pragma unroll
-            for (int k = 0; k < 16; k++) cur[k] = nxt[k];
-        }
+            for (int t = 0; t < TB; t++) {
+                const typename AR::Mod m = AR::mod(tb.pc[tb.phys(pi[t])]);
 #pragma unroll
-        for (int t = 0; t < TB; t++) {
-            const typename AR::Mod m = AR::mod(tb.pc[tb.phys(pi[t])]);
-#pragma unroll
-            for (int k = 0; k < 16; k++) x[t][k] = AR::from_f64_lazy(acc[t][k], m);
+                for (int k = 0; k < 8; k++) x[t][hf * 8 + k] = AR::from_f64_lazy(acc[t][k], m);
+            }
         }
     } else if (!AR::is_fp) {
         // integer pipe: 128-bit accumulation against Montgomery-form constants, one reduction per target
