@@ -99,3 +99,57 @@ def test_largest_supported_chain(orc):
         dh = host(ctx.hrot_dh_mac(dev(ct1[0]), [g, 1], [d_key, d_key], dev(pt), level=ell))
         assert np.array_equal(dh, orc.hrot_dh_mac_level(ct1[0], [g, 1], [key, key], pt, P)), ell
         assert np.array_equal(host(ctx.rescale(ell, dev(ct1))), orc.rescale(ct1, P)), ell
+
+
+def _random_case(seed):
+    rng = np.random.default_rng(seed)
+    logN = int(rng.choice([12, 12, 13]))
+    L = int(rng.integers(1, 11))
+    dnum = int(rng.choice([d for d in range(1, L + 1) if L % d == 0 and L // d <= 8]))
+    K = int(rng.integers(1, 9))
+    bits = [30, 36, 44, 49, 55, 59]
+    qf = [int(rng.choice(bits)) for _ in range(L)]
+    pf = [int(rng.choice([36, 49, 59, 60])) for _ in range(K)]
+    return logN, qf, pf, dnum
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_chains_levels_and_operations(orc, seed):
+    """Seeded random parameter sets (1..10 limbs of 30..60 bits in any order, 1..8 special limbs, any digit
+    count), a random level, every composed operation once."""
+    logN, qf, pf, dnum = _random_case(500 + seed)
+    ps = synth.mixed_params(logN, qf, pf, dnum, "random%d" % seed)
+    _say("seed", seed, "logN", logN, "q bits", qf, "p bits", pf, "dnum", dnum)
+    from paper_2310_16530_amd import binding
+    ctx = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)     # not cached: twelve different chains
+    P = orc.Params(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+    rng = np.random.default_rng(900 + seed)
+    N = ps.N
+    ell = int(rng.integers(1, ps.L + 1))
+    q = ps.q_primes[:ell]
+    key = synth.uniform_residues(rng, ps.primes, N, lead=(ps.dnum, 2))
+    d_key = dev(key)
+    ct1 = synth.uniform_residues(rng, q, N, lead=(2, 2))
+    ct2 = synth.uniform_residues(rng, q, N, lead=(2, 2))
+    g = synth.galois_element(int(rng.integers(1, 100)), logN)
+    hm = host(ctx.hmult_relin_at(ell, dev(ct1), dev(ct2), d_key))
+    hr = host(ctx.hrot_at(ell, dev(ct1), g, d_key))
+    for b in range(2):
+        assert np.array_equal(hm[b], orc.hmult_relin_level(ct1[b], ct2[b], key, P)), ("hmult", ell, b)
+        assert np.array_equal(hr[b], orc.hrot_level(ct1[b], g, key, P)), ("hrot", ell, b)
+    gs = [g, 1, synth.galois_element(-1, logN)]
+    basis = list(q) + list(ps.p_primes)
+    pt = synth.uniform_residues(rng, basis, N, lead=(len(gs),))
+    d_keys = [d_key] * len(gs)
+    keys = [key] * len(gs)
+    assert np.array_equal(host(ctx.hrot_hoisted_mac_at(ell, dev(ct1[0]), gs, d_keys, dev(pt[:, :ell]))),
+                          orc.hrot_hoisted_mac_level(ct1[0], gs, keys, np.ascontiguousarray(pt[:, :ell]), P)), ("hoisted", ell)
+    assert np.array_equal(host(ctx.hrot_dh_mac(dev(ct1[0]), gs, d_keys, dev(pt), level=ell)),
+                          orc.hrot_dh_mac_level(ct1[0], gs, keys, pt, P)), ("double hoisted", ell)
+    if ell >= 2:
+        assert np.array_equal(host(ctx.rescale(ell, dev(ct1))), orc.rescale(ct1, P)), ("rescale", ell)
+        mr = host(ctx.hmult_relin_rescale_at(ell, dev(ct1), dev(ct2), d_key))
+        for b in range(2):
+            assert np.array_equal(mr[b], orc.hmult_relin_rescale_level(ct1[b], ct2[b], key, P)), ("merged", ell, b)
+        assert np.array_equal(host(ctx.hrot_dh_mac_rescale_at(ell, dev(ct1[0]), gs, d_keys, dev(pt))),
+                              orc.hrot_dh_mac_rescale_level(ct1[0], gs, keys, pt, P)), ("merged dh", ell)
