@@ -33,7 +33,11 @@
  *     buffers sized by ckks_table_bytes / ckks_workspace_bytes, 256-byte aligned.
  *   - return value: CKKS_OK or a negative error code; nothing throws or aborts.
  *     ckks_last_error() gives a message for the last failing call on a context.
- *   - only full-level operands are supported (all L limbs present, dnum | L).
+ *   - dnum must divide L.  The calls without a level work on full-level operands (all L limbs
+ *     present); the calls ending in _at, ckks_rescale and the merged-rescale calls take the number
+ *     of active limbs as `level` and use the same context, tables and full-level keys.
+ *   - the calls may be captured in a HIP graph: they only launch kernels (no allocation, no
+ *     memset), provided profiling is off.
  */
 #ifndef CKKS_MI355X_H
 #define CKKS_MI355X_H

@@ -10,7 +10,11 @@
 //                       the digits in registers -> (special limbs) first inverse pass of ModDown
 //   ks_final_kernel     second forward pass of the converted special part -> (c' - .) * P^-1 + operand
 //                       (HMult tensor terms, sigma_g(b), or plaintext multiply-accumulate over rotations)
+//   dh_accum_kernel     double hoisting: plaintext products of all rotations accumulated in the extended basis
+//   bsgs_mac_kernel     giant-step combinations of baby-step rotations kept in the extended basis
 //   modup_kernel / moddown_kernel / automorph kernels: the stand-alone coefficient-form entry points.
+//
+// Levels below L, rescale and the ModDown merged with a rescale reuse these kernels on per-level tables.
 //
 // Every kernel picks its arithmetic per limb: FpAr for primes below 3*2^48, IntAr otherwise.
 #pragma once
