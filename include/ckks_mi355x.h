@@ -73,6 +73,7 @@ extern "C" {
 #define CKKS_MAX_PRIMES 64 /* L + K */
 #define CKKS_MAX_DIGIT 8   /* alpha and K */
 #define CKKS_MAX_PRIME_BITS 61
+#define CKKS_ROTATIONS_PER_LAUNCH 16 /* instances with their own key that one launch takes (chunking of rotation batches) */
 
 typedef struct ckks_ctx ckks_ctx;
 
@@ -269,7 +270,8 @@ int ckks_hrot_dh_mac_rescale_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d
 /*
  * Rotations of a batch of ciphertexts, instance b by the Galois element h_galois[b] with the key h_rk_ptrs[b]
  * (host arrays of `batch` entries): out[b] = ckks_hrot_at(level, ct[b], h_galois[b], rk_b).  Issued in chunks of
- * 8 instances; the workspace of CKKS_OP_HROT for min(batch, 8) at that level suffices.
+ * CKKS_ROTATIONS_PER_LAUNCH instances; the workspace of CKKS_OP_HROT for min(batch, CKKS_ROTATIONS_PER_LAUNCH) at that
+ * level suffices.
  */
 int ckks_hrot_multi_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, const uint32_t* h_galois,
                        const uint64_t* const* h_rk_ptrs, uint64_t* d_out, uint32_t batch, void* d_ws, size_t ws_bytes,

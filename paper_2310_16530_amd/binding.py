@@ -17,6 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libckks_mi355x.so")
 
 CKKS_OK, CKKS_EINVAL, CKKS_EUNSUPPORTED, CKKS_EHIP, CKKS_ENOMEM = 0, -1, -2, -3, -4
+ROTATIONS_PER_LAUNCH = 16
 (OP_NTT, OP_MODUP, OP_MODDOWN, OP_AUTOMORPH, OP_KEYSWITCH, OP_HMULT_RELIN, OP_HROT, OP_HROT_HOISTED_MAC,
  OP_RESCALE, OP_HROT_DH_MAC) = range(10)
 
@@ -394,7 +395,7 @@ class Context:
             out = torch.empty_like(ct)
         g = (ctypes.c_uint32 * batch)(*[int(x) for x in galois])
         ptrs = (ctypes.c_void_p * batch)(*[_dev_ptr(k) for k in rks])
-        ws = self.workspace(OP_HROT, min(batch, 8), level)
+        ws = self.workspace(OP_HROT, min(batch, ROTATIONS_PER_LAUNCH), level)
         self._check(load().ckks_hrot_multi_at(self.handle, level, _dev_ptr(ct), ctypes.cast(g, _vp), ctypes.cast(ptrs, _vp),
                                               _dev_ptr(out), batch, ws.data_ptr(), ws.numel(), _stream()))
         return out

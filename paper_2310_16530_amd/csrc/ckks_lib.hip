@@ -13,6 +13,7 @@
 #include "kernels.h"
 
 typedef unsigned __int128 u128;
+static_assert(CKKS_ROT_CHUNK == CKKS_ROTATIONS_PER_LAUNCH, "the public constant must match the kernels' argument arrays");
 
 // ------------------------------------------------------------------ host modular helpers
 static inline u64 h_mulmod(u64 a, u64 b, u64 m) { return (u64)(((u128)a * b) % m); }

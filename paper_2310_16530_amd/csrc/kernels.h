@@ -78,7 +78,7 @@ __device__ __forceinline__ size_t limb_offset(const LimbSel& s, u32 inst, u32 l)
 }
 
 // most rotations (each with its own key and Galois element) one launch can be given
-#define CKKS_ROT_CHUNK 8
+#define CKKS_ROT_CHUNK 16
 
 // ============================================================ inverse transform, first pass
 enum InvLoad { INV_PLAIN = 0, INV_TENSOR = 1, INV_ROT = 2 };
@@ -846,8 +846,12 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
                 for (int k = 0; k < 16; k++) {
                     double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[k * 16 + e0])) - v[k], pinv.d, fm);
                     if (t == 0) ks += u64_to_f64(bp[eval_perm(row_off + k * 16 + e0, a.galois[rr], tb.logN)]);
-                    // reduced to <= q/2 so that the at most 8 accumulated products stay below 5.5 q
+                    // reduced to <= q/2 so that the at most 8 products accumulated between folds stay below 6 q
                     acc[k] += FpAr::mulmod_lazy(FpAr::reduce(ks, fm), u64_to_f64(__builtin_nontemporal_load(&ptp[k * 16 + e0])), fm);
+                }
+                if ((rr & 7) == 7) {
+#pragma unroll
+                    for (int k = 0; k < 16; k++) acc[k] = FpAr::reduce(acc[k], fm);
                 }
             }
             u64* o = a.out + ((size_t)t * L + i) * N + row_off;

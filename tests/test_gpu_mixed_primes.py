@@ -153,3 +153,24 @@ def test_random_chains_levels_and_operations(orc, seed):
             assert np.array_equal(mr[b], orc.hmult_relin_rescale_level(ct1[b], ct2[b], key, P)), ("merged", ell, b)
         assert np.array_equal(host(ctx.hrot_dh_mac_rescale_at(ell, dev(ct1[0]), gs, d_keys, dev(pt))),
                               orc.hrot_dh_mac_rescale_level(ct1[0], gs, keys, pt, P)), ("merged dh", ell)
+
+
+def test_sixteen_rotations_in_one_launch_near_the_fp64_prime_limit(orc):
+    """A full chunk of rotations accumulated in the final kernel with primes just below 3*2^48: the FP64
+    accumulators must be folded often enough to stay exact."""
+    ps = synth.mixed_params(12, [FP_LIMIT - (1 << 24)] * 4, [59, 59], 2, "fp_limit")
+    assert all(p < FP_LIMIT for p in ps.q_primes)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(77)
+    n_rot = 16
+    gs = [synth.galois_element(r, ps.logN) for r in range(1, n_rot + 1)]
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    pt = synth.uniform_residues(rng, ps.primes, ps.N, lead=(n_rot,))
+    for p_i, p in enumerate(ps.primes):          # worst case for the accumulators: operands at the top of the range
+        pt[:, p_i, :64] = p - 1
+    d_rks = [dev(k) for k in rks]
+    got = host(ctx.hrot_hoisted_mac(dev(ct), gs, d_rks, dev(np.ascontiguousarray(pt[:, :ps.L]))))
+    assert np.array_equal(got, orc.hrot_hoisted_mac(ct, gs, rks, np.ascontiguousarray(pt[:, :ps.L]), P))
+    got = host(ctx.hrot_dh_mac(dev(ct), gs, d_rks, dev(pt)))
+    assert np.array_equal(got, orc.hrot_dh_mac_level(ct, gs, rks, pt, P))
