@@ -794,7 +794,7 @@ struct FwdStridedL {
 // target limbs converted per workgroup, per direction and arithmetic (measured optimum: more targets save L2
 // reads of the sources but cost registers, which the integer kernels do not have)
 #ifndef CKKS_CONV_TB_UP_FP
-#define CKKS_CONV_TB_UP_FP 2
+#define CKKS_CONV_TB_UP_FP 3
 #endif
 #ifndef CKKS_CONV_TB_DN_FP
 #define CKKS_CONV_TB_DN_FP 3
