@@ -792,16 +792,19 @@ struct FwdStridedL {
     static std::string name(const char* ar, int A) { return kname("fwd_strided_kernel", ar, A, ""); }
 };
 // target limbs converted per workgroup, per direction and arithmetic (measured optimum: more targets save L2
-// reads of the sources but cost registers, which the integer kernels do not have)
+// reads and conversions of the sources but cost registers; 4 FP64 or 3 integer targets are slower again)
 #ifndef CKKS_CONV_TB_UP_FP
 #define CKKS_CONV_TB_UP_FP 3
 #endif
 #ifndef CKKS_CONV_TB_DN_FP
 #define CKKS_CONV_TB_DN_FP 3
 #endif
+#ifndef CKKS_CONV_TB_INT
+#define CKKS_CONV_TB_INT 2
+#endif
 template <int DIR, bool FP>
 struct ConvTB {
-    static constexpr int value = FP ? (DIR == CONV_UP ? CKKS_CONV_TB_UP_FP : CKKS_CONV_TB_DN_FP) : 1;
+    static constexpr int value = FP ? (DIR == CONV_UP ? CKKS_CONV_TB_UP_FP : CKKS_CONV_TB_DN_FP) : CKKS_CONV_TB_INT;
 };
 template <int DIR>
 struct ConvL {

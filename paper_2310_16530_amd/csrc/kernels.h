@@ -369,33 +369,37 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
             }
         }
     } else if (!AR::is_fp) {
-        // integer pipe: 128-bit accumulation against Montgomery-form constants, one reduction per target
-        u128w acc[TB][16];
+        // integer pipe: 128-bit accumulation against Montgomery-form constants, one reduction per target;
+        // in two halves of eight words like the FP64 path
 #pragma unroll
-        for (int t = 0; t < TB; t++)
+        for (int hf = 0; hf < 2; hf++) {
+            u128w acc[TB][8];
 #pragma unroll
-            for (int k = 0; k < 16; k++) acc[t][k] = u128w{0, 0};
-        for (u32 i0 = 0; i0 < ns; i0++) {
-            const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
-            const u64* si = src + (size_t)i * N;
-            const bool src_fp = DIR == CONV_UP && tb.pc[tb.phys(src_prime + i)].fp;
-            u64 cc[TB];
+            for (int t = 0; t < TB; t++)
 #pragma unroll
-            for (int t = 0; t < TB; t++) cc[t] = chat[(size_t)i * chat_stride + pi[t]];
+                for (int k = 0; k < 8; k++) acc[t][k] = u128w{0, 0};
+            for (u32 i0 = 0; i0 < ns; i0++) {
+                const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
+                const u64* si = src + (size_t)i * N;
+                const bool src_fp = DIR == CONV_UP && tb.pc[tb.phys(src_prime + i)].fp;
+                u64 cc[TB];
 #pragma unroll
-            for (int k = 0; k < 16; k++) {
-                u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
-                if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+                for (int t = 0; t < TB; t++) cc[t] = chat[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
-                for (int t = 0; t < TB; t++) mac128(acc[t][k], y, cc[t]);
+                for (int k = 0; k < 8; k++) {
+                    u64 y = si[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
+                    if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+#pragma unroll
+                    for (int t = 0; t < TB; t++) mac128(acc[t][k], y, cc[t]);
+                }
             }
-        }
 #pragma unroll
-        for (int t = 0; t < TB; t++) {
-            const PrimeConst pc = tb.pc[tb.phys(pi[t])];
-            const typename AR::Mod m = AR::mod(pc);
+            for (int t = 0; t < TB; t++) {
+                const PrimeConst pc = tb.pc[tb.phys(pi[t])];
+                const typename AR::Mod m = AR::mod(pc);
 #pragma unroll
-            for (int k = 0; k < 16; k++) x[t][k] = AR::from_canon(redc(acc[t][k], pc.q, pc.qneg), m);
+                for (int k = 0; k < 8; k++) x[t][hf * 8 + k] = AR::from_canon(redc(acc[t][k], pc.q, pc.qneg), m);
+            }
         }
     } else {
         // FpAr targets whose sources do not fit the FP64 bounds: integer conversion, one target at a time
