@@ -518,13 +518,20 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
 #pragma unroll
     for (int k = 0; k < 16; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
     for (u32 j = 0; j < tb.dnum; j++) {
-        // issue the key loads first so that they are in flight while the digit is transformed
         const u64* k0 = key + ((size_t)j * 2 + 0) * Dkey * N;
         const u64* k1 = key + ((size_t)j * 2 + 1) * Dkey * N;
         u64 kv0[16], kv1[16];
-        if constexpr (AR::is_fp) {  // IntAr has no registers to spare: it loads the key at its use
+        // FpAr issues key loads before the transform so that they are in flight meanwhile: both components
+        // where the registers allow it (measured per variant), else the first one only; IntAr has no
+        // registers to spare and loads the key at its use
+        constexpr bool EARLY0 = AR::is_fp, EARLY1 = AR::is_fp && OWN == OWN_TENSOR;
+        if constexpr (EARLY0) {
 #pragma unroll
-            for (int k = 0; k < 16; k++) kv0[k] = k0[k * 16 + e0], kv1[k] = k1[k * 16 + e0];
+            for (int k = 0; k < 16; k++) kv0[k] = k0[k * 16 + e0];
+        }
+        if constexpr (EARLY1) {
+#pragma unroll
+            for (int k = 0; k < 16; k++) kv1[k] = k1[k * 16 + e0];
         }
         T v[16];
         if (j == own_digit) {
@@ -565,7 +572,8 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
         }
 #pragma unroll
         for (int k = 0; k < 16; k++) {
-            if constexpr (!AR::is_fp) kv0[k] = k0[k * 16 + e0], kv1[k] = k1[k * 16 + e0];
+            if constexpr (!EARLY0) kv0[k] = k0[k * 16 + e0];
+            if constexpr (!EARLY1) kv1[k] = k1[k * 16 + e0];
             AR::acc_mac(acc0[k], v[k], kv0[k], m);
             AR::acc_mac(acc1[k], v[k], kv1[k], m);
         }
