@@ -2,7 +2,7 @@
 """Benchmark of the RNS-CKKS key-switch hot path on one MI355X.
 
 One "step" is one pass of the whole path over one batch of synthetic input at N=2^16, L=24, K=6,
-dnum=4 (BASELINE config 2's shape): a batch of 8 HMult+relinearisations (shared evaluation key)
+dnum=4 (the shape of workload 2): a batch of 8 HMult+relinearisations (shared evaluation key)
 followed by a batch of 8 rotations (shared Galois key) -- 16 key switches.  `value` is key
 switches per second with every operand resident in HBM.  Extras report the other quantities the
 metric names: NTT limbs/s on config 1 (16 x 24 limbs) and hoisted rotations/s on config 3.

@@ -153,7 +153,7 @@ def mixed_params(logN: int, q_floors: Sequence[int], p_floors: Sequence[int], dn
     return ExplicitParamSet(name, logN, dnum, q, pp)
 
 
-# The five workload shapes (BASELINE configs 0..4).
+# The five workload shapes (workloads 0..4 of the benchmark definition).
 CFG0 = ParamSet("cfg0_hmult_n12", 12, 3, 1, 3, 35, 36)
 CFG1 = ParamSet("cfg1_ntt_n16_l24", 16, 24, 0, 1, 49, 59)
 CFG2 = ParamSet("cfg2_hmult_n16_l24_d4", 16, 24, 6, 4, 49, 59)

@@ -209,7 +209,7 @@ def test_double_hoisted_mac_parity(orc, shape, n_rot):
 
 @pytest.mark.timeout(900)
 def test_config3_double_hoisted_full_size(orc):
-    """BASELINE config 3's shape (17 rotations, N = 2^16, L = 24, dnum = 4) through the double-hoisted call."""
+    """the shape of workload 3 (17 rotations, N = 2^16, L = 24, dnum = 4) through the double-hoisted call."""
     ps = synth.CFG3
     ctx, P = gpu_ctx(ps), orc_params(orc, ps)
     rng = synth.rng_for(3, 5)

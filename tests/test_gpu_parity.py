@@ -2,7 +2,7 @@
 
 Every comparison is exact (integer work): `np.array_equal` on the uint64 words.
 Sizes: reduced shapes of the same family that the oracle finishes in seconds (several
-workgroup tiles, every supported ring degree, digit sizes 1..7), then the full BASELINE
+workgroup tiles, every supported ring degree, digit sizes 1..7), then the full workload
 shapes in the launch configuration the benchmark times.
 """
 import numpy as np
@@ -86,7 +86,7 @@ def test_ntt_intt_parity_all_ring_degrees(orc, logN):
 
 @pytest.mark.timeout(900)
 def test_ntt_config1_full_size(orc):
-    """BASELINE config 1: 16 polynomials x 24 fifty-bit limbs at N = 2^16, forward, inverse, round trip."""
+    """workload 1: 16 polynomials x 24 fifty-bit limbs at N = 2^16, forward, inverse, round trip."""
     ps = synth.CFG1
     ctx, P = gpu_ctx(ps), orc_params(orc, ps)
     x = synth.uniform_residues(synth.rng_for(1, 0), ps.primes, ps.N, lead=(synth.CFG1_BATCH,))
@@ -232,7 +232,7 @@ def test_hoisted_mac_parity_reduced(orc, shape, n_rot):
     assert np.abs(E).max() <= orc.keyswitch_noise_bound(P, int(np.abs(s).sum()))
 
 
-# ------------------------------------------------------------- full BASELINE shapes
+# ------------------------------------------------------------- full workload shapes
 def test_config0_hmult_exact_shape(orc):
     ps = synth.CFG0
     ctx, P = gpu_ctx(ps), orc_params(orc, ps)
@@ -257,7 +257,7 @@ def test_config0_hmult_exact_shape(orc):
 
 @pytest.mark.timeout(900)
 def test_config2_hmult_batch8_full_size(orc):
-    """BASELINE config 2 in the benchmark's launch configuration (batch 8, shared evk).  The oracle
+    """workload 2 in the benchmark's launch configuration (batch 8, shared evk).  The oracle
     recomputes two of the eight products in full; all eight are checked by decrypt-and-bound."""
     ps = synth.CFG2
     ctx, P = gpu_ctx(ps), orc_params(orc, ps)
@@ -305,7 +305,7 @@ def test_config2_hrot_and_keyswitch_full_size(orc):
 
 @pytest.mark.timeout(900)
 def test_config3_rotate_and_sum_full_size(orc):
-    """BASELINE config 3: one ciphertext, the 17 listed offsets, hoisted ModUp, plaintext MAC."""
+    """workload 3: one ciphertext, the 17 listed offsets, hoisted ModUp, plaintext MAC."""
     ps = synth.CFG3
     ctx, P = gpu_ctx(ps), orc_params(orc, ps)
     rng = synth.rng_for(3, 0)
@@ -321,7 +321,7 @@ def test_config3_rotate_and_sum_full_size(orc):
 
 @pytest.mark.timeout(900)
 def test_config4_coeff_to_slot_shape_full_size(orc):
-    """BASELINE config 4: L=35, K=7, dnum=5, 32 rotations +-2^i.  The oracle recomputes a 5-rotation
+    """workload 4: L=35, K=7, dnum=5, 32 rotations +-2^i.  The oracle recomputes a 5-rotation
     subset in full (including the identity element g = 1 from +-2^15); the 32-rotation call is then
     checked by linearity: it must equal the sum of four 8-rotation calls."""
     ps = synth.CFG4

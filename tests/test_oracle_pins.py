@@ -438,7 +438,7 @@ def test_hoisted_mac_per_rotation_and_linearity(orc, shape):
 
 
 def test_config0_exact_shape_hmult(orc):
-    """BASELINE config 0: N=2^12, 3 q-limbs above 2^35, one special prime above 2^36, dnum=3."""
+    """workload 0: N=2^12, 3 q-limbs above 2^35, one special prime above 2^36, dnum=3."""
     ps = synth.CFG0
     P, rng, s, s_hat = _setup(orc, ps, 0)
     q = ps.q_primes
