@@ -41,8 +41,8 @@ MEASURED = {
     "inv_contig_kernel<FpAr, 8, 2>": (108.1, 96.0, 11071488),
     "inv_strided_kernel<FpAr, 8>": (96.6, 96.0, 9891840),
     "inv_strided_kernel<IntAr, 8>": (48.5, 48.0, 13221888),
-    "ks_final_kernel<FpAr, 8, 1>": (982.6, 192.0, 27979776),
-    "ks_final_kernel<FpAr, 8, 2>": (500.6, 192.0, 24293376),
+    "ks_final_kernel<FpAr, 8, 1>": (982.3, 192.0, 27979776),
+    "ks_final_kernel<FpAr, 8, 2>": (500.1, 192.0, 24293376),
     "ks_inner_kernel<FpAr, 8, 1, false>": (588.2, 192.0, 43929600),
     "ks_inner_kernel<FpAr, 8, 2, false>": (492.2, 192.0, 44457984),
     "ks_inner_kernel<IntAr, 8, 1, false>": (132.9, 48.0, 49920000),
