@@ -443,3 +443,27 @@ def test_hrot_multi_parity(orc):
         got = host(ctx.hrot_multi_at(ell, dev(ct), gs, d_rks))
         for b in range(B):
             assert np.array_equal(got[b], orc.hrot_level(ct[b], gs[b], rks[b], P)), (ell, b)
+
+
+def test_large_batches(orc):
+    """Batches well above the benchmark's 8 (37 and 300 ciphertexts): every entry checked for the small one,
+    sampled entries for the large one."""
+    ps = synth.small_params(12, 4, 2, 2)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(53)
+    key = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    d_key = dev(key)
+    g = synth.galois_element(9, ps.logN)
+    for B, check in ((37, range(37)), (300, (0, 1, 149, 298, 299))):
+        _say("batch", B)
+        ct1 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
+        ct2 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
+        hm = host(ctx.hmult_relin(dev(ct1), dev(ct2), d_key))
+        hr = host(ctx.hrot(dev(ct1), g, d_key))
+        rs = host(ctx.rescale(ps.L, dev(ct1)))
+        mr = host(ctx.hmult_relin_rescale_at(ps.L, dev(ct1), dev(ct2), d_key))
+        for b in check:
+            assert np.array_equal(hm[b], orc.hmult_relin(ct1[b], ct2[b], key, P)), (B, b)
+            assert np.array_equal(hr[b], orc.hrot(ct1[b], g, key, P)), (B, b)
+            assert np.array_equal(rs[b], orc.rescale(ct1[b], P)), (B, b)
+            assert np.array_equal(mr[b], orc.hmult_relin_rescale_level(ct1[b], ct2[b], key, P)), (B, b)
