@@ -36,15 +36,15 @@ MEASURED = {
     # kernel: (read MiB, write MiB, VALU wave-instructions)
     "conv_fwd_strided_kernel<FpAr, 8, 1, 3>": (96.9, 288.0, 52559872),
     "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": (49.6, 193.9, 54706176),
-    "conv_fwd_strided_kernel<IntAr, 8, 1, 2>": (98.7, 96.0, 50184192),
+    "conv_fwd_strided_kernel<IntAr, 8, 1, 2>": (98.6, 96.0, 50184192),
     "inv_contig_kernel<FpAr, 8, 1>": (204.1, 96.0, 10543104),
     "inv_contig_kernel<FpAr, 8, 2>": (108.1, 96.0, 11071488),
     "inv_strided_kernel<FpAr, 8>": (96.6, 96.0, 9891840),
     "inv_strided_kernel<IntAr, 8>": (48.5, 48.0, 13221888),
-    "ks_final_kernel<FpAr, 8, 1>": (982.3, 192.0, 27979776),
-    "ks_final_kernel<FpAr, 8, 2>": (500.1, 192.0, 24293376),
+    "ks_final_kernel<FpAr, 8, 1>": (982.7, 192.0, 27979776),
+    "ks_final_kernel<FpAr, 8, 2>": (500.6, 192.0, 24293376),
     "ks_inner_kernel<FpAr, 8, 1, false>": (588.2, 192.0, 43929600),
-    "ks_inner_kernel<FpAr, 8, 2, false>": (492.2, 192.0, 44457984),
+    "ks_inner_kernel<FpAr, 8, 2, false>": (492.3, 192.0, 44457984),
     "ks_inner_kernel<IntAr, 8, 1, false>": (132.9, 48.0, 49920000),
     "ks_inner_kernel<IntAr, 8, 2, false>": (132.8, 48.0, 50445312),
 }
@@ -53,8 +53,8 @@ MEASURED = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-extras", action="store_true", help="skip every extra measurement")
     ap.add_argument("--extras", default="overlap,concurrent,ntt,hoisted,levels",
                     help="comma-separated extra measurements: overlap (two streams inside each call), concurrent "
