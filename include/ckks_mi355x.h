@@ -109,7 +109,9 @@ const char* ckks_last_error(const ckks_ctx* ctx);
 uint64_t ckks_ctx_psi(const ckks_ctx* ctx, uint32_t i);
 
 /* Bytes of workspace the given op needs for `batch_or_nrot` (batch size; number of rotations
- * for CKKS_OP_HROT_HOISTED_MAC).  0 for ops that need none. */
+ * for CKKS_OP_HROT_HOISTED_MAC and CKKS_OP_HROT_DH_MAC).  0 for ops that need none.  The merged-rescale
+ * calls use the size of their un-merged counterpart; ckks_hrot_multi_at that of CKKS_OP_HROT for
+ * min(batch, CKKS_ROTATIONS_PER_LAUNCH); ckks_lintrans_bsgs_at has its own query. */
 int ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t batch_or_nrot, size_t* bytes);
 
 /* The same for an operation at `level` active q-limbs (1 <= level <= L; for CKKS_OP_RESCALE the level of
