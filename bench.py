@@ -284,6 +284,16 @@ def main():
         o13 = torch.empty_like(a13)
         extra["hmult_relin_level13_per_s"] = round(B / timed(lambda: ctx.hmult_relin_at(lv, a13, b13, evk, o13)), 1)
         extra["hrot_level13_per_s"] = round(B / timed(lambda: ctx.hrot_at(lv, a13, g, rk, o13)), 1)
+        # limb-wise arithmetic on the batch (HAdd and ciphertext x plaintext): 2 polynomials x L limbs per ciphertext
+        pw_out = torch.empty_like(ct1)
+        ptw = evk[0, 0, :L].contiguous().reshape(1, L, N)
+        dt = timed(lambda: ctx.pointwise(binding.PW_ADD, ct1, ct2, pw_out), label="pointwise_add")
+        extra["hadd_per_s"] = round(B / dt, 1)
+        extra["hadd_effective_GBps"] = round(B * 6 * L * 8 * N / dt / 1e9, 1)
+        dt = timed(lambda: ctx.pointwise(binding.PW_MUL, ct1, ptw, pw_out), label="pointwise_mul")
+        extra["pmult_per_s"] = round(B / dt, 1)
+        extra["pmult_effective_GBps"] = round((B * 4 + 1) * L * 8 * N / dt / 1e9, 1)
+        del pw_out, ptw
         del a13, b13, o13, rs_out
 
     cpu = None

@@ -67,6 +67,12 @@ extern "C" {
 #define CKKS_OP_RESCALE 8
 #define CKKS_OP_HROT_DH_MAC 9
 
+/* operations of ckks_pointwise */
+#define CKKS_PW_ADD 0 /* out = a + b */
+#define CKKS_PW_SUB 1 /* out = a - b */
+#define CKKS_PW_MUL 2 /* out = a * b */
+#define CKKS_PW_MAC 3 /* out = out + a * b */
+
 /* limits of this build */
 #define CKKS_MIN_LOGN 12
 #define CKKS_MAX_LOGN 16
@@ -156,6 +162,20 @@ int ckks_moddown(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, uint32_t 
  */
 int ckks_automorph(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_out, uint32_t prime_first, uint32_t n_limbs,
                    uint32_t galois, int eval_domain, uint32_t batch, void* stream);
+
+/*
+ * Limb-wise arithmetic on residue matrices: the L x N element-parallel operations of Section 3 (addition of
+ * polynomials), and in evaluation form the products behind the multiplication of a ciphertext by a plaintext
+ * that the convolutions of Section 5 accumulate.
+ *   d_a, d_out : [batch][n_limbs][N]      d_b : [b_period][n_limbs][N], 1 <= b_period <= batch
+ *   out[g][l][n] = a[g][l][n] (op) b[g % b_period][l][n]  mod prime (prime_first + l),
+ *   op = CKKS_PW_ADD | CKKS_PW_SUB | CKKS_PW_MUL, or CKKS_PW_MAC: out = out + a * b.
+ *   b_period = batch pairs the operands one to one; b_period = 1 applies one plaintext to every polynomial
+ *   of a (both components of every ciphertext of a batch).  Residues canonical on entry and exit.  d_out may be
+ *   d_a or d_b themselves (same address), but may not overlap them otherwise.  No workspace.
+ */
+int ckks_pointwise(ckks_ctx* ctx, int op, const uint64_t* d_a, const uint64_t* d_b, uint64_t* d_out,
+                   uint32_t prime_first, uint32_t n_limbs, uint32_t batch, uint32_t b_period, void* stream);
 
 /*
  * Hybrid key switch (the step inside HMult and rotation; Table 1 measures HMult):

@@ -20,6 +20,7 @@ CKKS_OK, CKKS_EINVAL, CKKS_EUNSUPPORTED, CKKS_EHIP, CKKS_ENOMEM = 0, -1, -2, -3,
 ROTATIONS_PER_LAUNCH = 16
 (OP_NTT, OP_MODUP, OP_MODDOWN, OP_AUTOMORPH, OP_KEYSWITCH, OP_HMULT_RELIN, OP_HROT, OP_HROT_HOISTED_MAC,
  OP_RESCALE, OP_HROT_DH_MAC) = range(10)
+PW_ADD, PW_SUB, PW_MUL, PW_MAC = range(4)  # CKKS_PW_* of ckks_pointwise
 
 EXPORTS = (
     "ckks_table_bytes", "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error", "ckks_ctx_psi",
@@ -29,7 +30,7 @@ EXPORTS = (
     "ckks_workspace_bytes_at", "ckks_keyswitch_at", "ckks_hmult_relin_at", "ckks_hrot_at",
     "ckks_hrot_hoisted_mac_at", "ckks_rescale", "ckks_hrot_dh_mac", "ckks_hrot_dh_mac_at",
     "ckks_hmult_relin_rescale_at", "ckks_hrot_dh_mac_rescale_at",
-    "ckks_lintrans_bsgs_workspace_bytes", "ckks_lintrans_bsgs_at", "ckks_hrot_multi_at",
+    "ckks_lintrans_bsgs_workspace_bytes", "ckks_lintrans_bsgs_at", "ckks_hrot_multi_at", "ckks_pointwise",
 )
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
@@ -81,6 +82,7 @@ def load() -> ctypes.CDLL:
     lib.ckks_hmult_relin_rescale_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_dh_mac_rescale_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_hrot_multi_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
+    lib.ckks_pointwise.argtypes = [_vp, _int, _vp, _vp, _vp, _u32, _u32, _u32, _u32, _vp]
     lib.ckks_lintrans_bsgs_workspace_bytes.argtypes = [_vp, _u32, _u32, _u32, ctypes.POINTER(_sz)]
     lib.ckks_lintrans_bsgs_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_profile_enable.argtypes = [_vp, _int]
@@ -212,6 +214,23 @@ class Context:
         out = torch.empty_like(x)
         self._check(load().ckks_automorph(self.handle, _dev_ptr(x), _dev_ptr(out), prime_first, n_limbs, galois,
                                           1 if eval_domain else 0, batch, _stream()))
+        return out
+
+    def pointwise(self, op: int, a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] = None,
+                  prime_first: int = 0) -> torch.Tensor:
+        """a (op) b limb by limb; a [..][n_limbs][N], b the same or fewer leading groups (applied cyclically).
+        PW_MAC accumulates into `out`, which may be `a` or `b` for the other operations."""
+        n_limbs = a.shape[-2]
+        batch = a.numel() // (n_limbs * self.N)
+        b_period = b.numel() // (n_limbs * self.N)
+        if out is None:
+            if op == PW_MAC:
+                raise ValueError("PW_MAC accumulates into out")
+            out = torch.empty_like(a)
+        if b.shape[-2] != n_limbs or out.shape != a.shape:
+            raise ValueError("operand shapes do not match")
+        self._check(load().ckks_pointwise(self.handle, op, _dev_ptr(a), _dev_ptr(b), _dev_ptr(out), prime_first,
+                                          n_limbs, batch, b_period, _stream()))
         return out
 
     def keyswitch(self, d: torch.Tensor, key: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -1185,6 +1185,43 @@ extern "C" int ckks_automorph(ckks_ctx* ctx, const uint64_t* d_in, uint64_t* d_o
     return hip_check(c, "ckks_automorph");
 }
 
+extern "C" int ckks_pointwise(ckks_ctx* ctx, int op, const uint64_t* d_a, const uint64_t* d_b, uint64_t* d_out,
+                              uint32_t prime_first, uint32_t n_limbs, uint32_t batch, uint32_t b_period, void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    const View* c = ctx->full();
+    if (!d_a || !d_b || !d_out || misaligned(d_a, 16) || misaligned(d_b, 16) || misaligned(d_out, 16))
+        return fail(c, CKKS_EINVAL, "null or misaligned buffer");
+    if (op < CKKS_PW_ADD || op > CKKS_PW_MAC) return fail(c, CKKS_EINVAL, "unknown limb-wise operation");
+    int rc = check_limb_range(c, prime_first, n_limbs, batch);
+    if (rc) return rc;
+    if (batch > 65535) return fail(c, CKKS_EINVAL, "batch too large");
+    if (b_period == 0 || b_period > batch) return fail(c, CKKS_EINVAL, "b_period must be in 1..batch");
+    const dim3 grid((1u << c->logN) / 512, n_limbs, batch), block(256);
+    hipStream_t s = (hipStream_t)stream;
+    static const char* const names[4] = {"pointwise_kernel<add>", "pointwise_kernel<sub>", "pointwise_kernel<mul>",
+                                         "pointwise_kernel<mac>"};
+    ProfScope ps(c, std::string(names[op]), (u64)batch * n_limbs * (op == CKKS_PW_MAC ? 3 : 2) + (u64)b_period * n_limbs, s);
+    switch (op) {
+        case CKKS_PW_ADD:
+            hipLaunchKernelGGL(pointwise_kernel<PW_ADD>, grid, block, 0, s, d_a, d_b, d_out, c->tb.pc, c->logN, n_limbs,
+                               prime_first, b_period);
+            break;
+        case CKKS_PW_SUB:
+            hipLaunchKernelGGL(pointwise_kernel<PW_SUB>, grid, block, 0, s, d_a, d_b, d_out, c->tb.pc, c->logN, n_limbs,
+                               prime_first, b_period);
+            break;
+        case CKKS_PW_MUL:
+            hipLaunchKernelGGL(pointwise_kernel<PW_MUL>, grid, block, 0, s, d_a, d_b, d_out, c->tb.pc, c->logN, n_limbs,
+                               prime_first, b_period);
+            break;
+        default:
+            hipLaunchKernelGGL(pointwise_kernel<PW_MAC>, grid, block, 0, s, d_a, d_b, d_out, c->tb.pc, c->logN, n_limbs,
+                               prime_first, b_period);
+            break;
+    }
+    return hip_check(c, "ckks_pointwise");
+}
+
 static int check_ks_args(const View* c, const void* a, const void* b, const void* out, u32 batch, int op,
                          const void* ws, size_t ws_bytes) {
     if (!a || !b || !out || misaligned(a, 16) || misaligned(b, 16) || misaligned(out, 16))

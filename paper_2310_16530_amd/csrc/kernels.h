@@ -1059,3 +1059,32 @@ __global__ __launch_bounds__(256) void automorph_coeff_kernel(const u64* __restr
     }
     out[limb + u] = v;
 }
+
+// -------------------------------------------------------------------- limb-wise arithmetic
+// out[g][l][n] = a[g][l][n] (op) b[g % b_period][l][n] mod prime (prime_first + l); two words per lane
+// (16-byte accesses).  out may be a or b themselves: every lane reads its words before it writes them.
+enum PointwiseOp { PW_ADD = 0, PW_SUB = 1, PW_MUL = 2, PW_MAC = 3 };
+template <int OP>
+__global__ __launch_bounds__(256) void pointwise_kernel(const u64* a, const u64* b, u64* out, const PrimeConst* pcs,
+                                                        u32 logN, u32 n_limbs, u32 prime_first, u32 b_period) {
+    const u32 N = 1u << logN;
+    const u32 n = (blockIdx.x * 256 + threadIdx.x) * 2;
+    const size_t la = ((size_t)blockIdx.z * n_limbs + blockIdx.y) * N + n;
+    const size_t lb = ((size_t)(blockIdx.z % b_period) * n_limbs + blockIdx.y) * N + n;
+    const PrimeConst pc = pcs[prime_first + blockIdx.y];
+    const ulonglong2 av = *reinterpret_cast<const ulonglong2*>(a + la);
+    const ulonglong2 bv = *reinterpret_cast<const ulonglong2*>(b + lb);
+    ulonglong2 r;
+    if (OP == PW_ADD) {
+        r.x = addmod(av.x, bv.x, pc.q), r.y = addmod(av.y, bv.y, pc.q);
+    } else if (OP == PW_SUB) {
+        r.x = submod(av.x, bv.x, pc.q), r.y = submod(av.y, bv.y, pc.q);
+    } else {
+        r.x = mulmod_var(av.x, bv.x, pc.q, pc.qneg, pc.r2), r.y = mulmod_var(av.y, bv.y, pc.q, pc.qneg, pc.r2);
+        if (OP == PW_MAC) {
+            const ulonglong2 ov = *reinterpret_cast<const ulonglong2*>(out + la);
+            r.x = addmod(r.x, ov.x, pc.q), r.y = addmod(r.y, ov.y, pc.q);
+        }
+    }
+    *reinterpret_cast<ulonglong2*>(out + la) = r;
+}

@@ -467,3 +467,35 @@ def test_large_batches(orc):
             assert np.array_equal(hr[b], orc.hrot(ct1[b], g, key, P)), (B, b)
             assert np.array_equal(rs[b], orc.rescale(ct1[b], P)), (B, b)
             assert np.array_equal(mr[b], orc.hmult_relin_rescale_level(ct1[b], ct2[b], key, P)), (B, b)
+
+
+@pytest.mark.parametrize("shape", [(12, 6, 2, 3, 49, 59), (13, 6, 3, 2, 49, 59), (12, 4, 2, 2, 55, 59)])
+def test_quadratic_activation_composed_from_library_calls(orc, shape):
+    """w2 * x^2 + w1 * x on a batch of ciphertexts (the shape of a polynomial activation): square with merged
+    rescale, two plaintext products, two rescales, a limb drop and a sum, every step through the library and
+    mirrored call by call with the oracle."""
+    from paper_2310_16530_amd import binding
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(9500 + sum(shape))
+    evk = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    d_evk = dev(evk)
+    B, ell = 3, ps.L
+    q = ps.q_primes
+    x = synth.uniform_residues(rng, q[:ell], ps.N, lead=(B, 2))
+    w1 = synth.uniform_residues(rng, q[:ell], ps.N, lead=(1,))
+    w2 = synth.uniform_residues(rng, q[:ell - 1], ps.N, lead=(1,))
+    dx = dev(x)
+    # GPU
+    sq = ctx.hmult_relin_rescale_at(ell, dx, dx, d_evk)                               # level ell - 1
+    a = ctx.rescale(ell - 1, ctx.pointwise(binding.PW_MUL, sq, dev(w2)))               # level ell - 2
+    b = ctx.rescale(ell, ctx.pointwise(binding.PW_MUL, dx, dev(w1)))                   # level ell - 1
+    b = b[:, :, :ell - 2].contiguous()                                                 # drop a limb
+    got = host(ctx.pointwise(binding.PW_ADD, a, b))
+    # oracle
+    for i in range(B):
+        o_sq = orc.hmult_relin_rescale_level(x[i], x[i], evk, P)
+        o_a = orc.rescale(np.stack([orc.pointwise("mul", o_sq[t], w2[0], q[:ell - 1]) for t in range(2)]), P)
+        o_b = orc.rescale(np.stack([orc.pointwise("mul", x[i, t], w1[0], q[:ell]) for t in range(2)]), P)
+        want = np.stack([orc.pointwise("add", o_a[t], o_b[t, :ell - 2], q[:ell - 2]) for t in range(2)])
+        assert np.array_equal(got[i], want), i

@@ -161,6 +161,44 @@ def make_keys(orc, ps, P, rng, s_hat, sp_hat):
     return orc.make_switch_key(s_hat, sp_hat, a, e, P)
 
 
+def _orc_pointwise(orc, op, a, b, primes):
+    """a [batch][n][N], b [period][n][N] -> [batch][n][N]; MAC is expressed by the caller (mul then add)."""
+    return np.stack([orc.pointwise(op, a[g], b[g % b.shape[0]], primes) for g in range(a.shape[0])])
+
+
+@pytest.mark.parametrize("shape,prime_first,n_limbs", [((12, 4, 2, 2), 0, 6), ((13, 6, 3, 2), 2, 5), ((16, 3, 1, 3), 1, 3)])
+def test_pointwise_parity(orc, shape, prime_first, n_limbs):
+    from paper_2310_16530_amd import binding
+    ps = synth.small_params(*shape)
+    ctx = gpu_ctx(ps)
+    primes = ps.primes[prime_first:prime_first + n_limbs]
+    rng = np.random.default_rng(77 + sum(shape) + prime_first)
+    a = synth.uniform_residues(rng, primes, ps.N, lead=(6,))
+    b = synth.uniform_residues(rng, primes, ps.N, lead=(6,))
+    c = synth.uniform_residues(rng, primes, ps.N, lead=(6,))
+    for i, q in enumerate(primes):  # corners: 0, 1, q-1 against each other
+        a[0, i, :9] = [0, 0, 0, 1, 1, q - 1, q - 1, q - 1, q - 2]
+        b[0, i, :9] = [0, 1, q - 1, 1, q - 1, q - 1, 1, 0, q - 2]
+    da, db, dc = dev(a), dev(b), dev(c)
+    for period in (6, 1, 2, 3):
+        bb = b[:period]
+        dbb = db[:period].contiguous()
+        for op, name in ((binding.PW_ADD, "add"), (binding.PW_SUB, "sub"), (binding.PW_MUL, "mul")):
+            want = _orc_pointwise(orc, name, a, bb, primes)
+            assert np.array_equal(host(ctx.pointwise(op, da, dbb, prime_first=prime_first)), want), (name, period)
+        acc = dc.clone()
+        ctx.pointwise(binding.PW_MAC, da, dbb, out=acc, prime_first=prime_first)
+        want = _orc_pointwise(orc, "add", _orc_pointwise(orc, "mul", a, bb, primes), c, primes)
+        assert np.array_equal(host(acc), want), ("mac", period)
+    # in place on the first operand, and on the second when the operands pair one to one
+    x = da.clone()
+    ctx.pointwise(binding.PW_MUL, x, db, out=x, prime_first=prime_first)
+    assert np.array_equal(host(x), _orc_pointwise(orc, "mul", a, b, primes))
+    y = db.clone()
+    ctx.pointwise(binding.PW_SUB, da, y, out=y, prime_first=prime_first)
+    assert np.array_equal(host(y), _orc_pointwise(orc, "sub", a, b, primes))
+
+
 KS_SHAPES = [(12, 4, 2, 2), (12, 3, 1, 3), (13, 6, 3, 2), (12, 6, 6, 1), (14, 4, 2, 2), (12, 14, 7, 2), (12, 8, 8, 1),
              (12, 20, 1, 20), (15, 2, 2, 1)]
 
@@ -372,6 +410,13 @@ def test_error_paths_return_codes_without_launching(orc):
     assert lib.ckks_hrot(h, p, 5, key.data_ptr(), out.data_ptr(), 1, ws.data_ptr(), 1024, None) == binding.CKKS_ENOMEM
     assert lib.ckks_hrot(h, p, 5, key.data_ptr(), out.data_ptr(), 1, None, 1 << 40, None) == binding.CKKS_EINVAL
     assert lib.ckks_hrot(h, p, 5, key.data_ptr(), out.data_ptr(), 0, ws.data_ptr(), ws.numel(), None) == binding.CKKS_EINVAL
+    o = out.data_ptr()
+    assert lib.ckks_pointwise(h, 4, p, p, o, 0, 1, 1, 1, None) == binding.CKKS_EINVAL                # unknown op
+    assert lib.ckks_pointwise(h, -1, p, p, o, 0, 1, 1, 1, None) == binding.CKKS_EINVAL
+    assert lib.ckks_pointwise(h, binding.PW_ADD, p, p, o, 0, 1, 2, 3, None) == binding.CKKS_EINVAL   # period > batch
+    assert lib.ckks_pointwise(h, binding.PW_ADD, p, p, o, 0, 1, 2, 0, None) == binding.CKKS_EINVAL
+    assert lib.ckks_pointwise(h, binding.PW_ADD, p, None, o, 0, 1, 1, 1, None) == binding.CKKS_EINVAL
+    assert lib.ckks_pointwise(h, binding.PW_ADD, p, p, o, 5, 2, 1, 1, None) == binding.CKKS_EINVAL   # beyond the chain
     n = ctypes.c_size_t()
     assert lib.ckks_workspace_bytes(h, 99, 1, ctypes.byref(n)) == binding.CKKS_EINVAL
     # transform-only context: key-switch entry points are unsupported, transforms work
