@@ -56,10 +56,12 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-extras", action="store_true", help="skip every extra measurement")
-    ap.add_argument("--extras", default="overlap,concurrent,ntt,hoisted,levels",
+    ap.add_argument("--extras", default="overlap,concurrent,ntt,hoisted,config4,latency,levels",
                     help="comma-separated extra measurements: overlap (two streams inside each call), concurrent "
                          "(HMult and HRot batches on two caller streams), ntt (config 1), hoisted "
-                         "(config 3 rotations, singly and doubly hoisted), levels (rescale, level-13 operations)")
+                         "(config 3 rotations, singly and doubly hoisted), config4 (32 rotations at L = 35, dnum = 5), latency (one "
+                         "ciphertext at a time), levels (rescale, "
+                         "merged rescale, level-13 operations, limb-wise arithmetic)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -162,7 +164,7 @@ def main():
         torch.cuda.synchronize()
         extra[name] = round(B * args.steps / (time.perf_counter() - a), 1)
 
-    EXTRA_GROUPS = ("overlap", "concurrent", "ntt", "hoisted", "levels")
+    EXTRA_GROUPS = ("overlap", "concurrent", "ntt", "hoisted", "config4", "latency", "levels")
     groups = () if args.no_extras else tuple(g for g in args.extras.split(",") if g)
     for gname in groups:
         if gname not in EXTRA_GROUPS:
@@ -170,7 +172,7 @@ def main():
             sys.exit(2)
     extra_kernels = {}
 
-    def timed(fn, reps=None, label=None):
+    def timed(fn, reps=None, label=None, pctx=None):
         """Seconds per call over `reps` calls after 2 warm-up calls; with a label, a second event-timed pass
         records the per-kernel averages of that operation."""
         reps = reps or args.steps
@@ -183,12 +185,13 @@ def main():
         torch.cuda.synchronize()
         per = (time.perf_counter() - a0) / reps
         if label:
-            ctx.profile_enable(True)
+            pctx = pctx or ctx
+            pctx.profile_enable(True)
             for _ in range(reps):
                 fn()
             torch.cuda.synchronize()
-            pr = ctx.profile_read()
-            ctx.profile_enable(False)
+            pr = pctx.profile_read()
+            pctx.profile_enable(False)
             extra_kernels[label] = {k: {"launches_per_call": n / reps, "avg_us": round(1e3 * ms / n, 2),
                                         "alg_GBps": round(nb / ms / 1e6, 1)} for k, (n, ms, nb) in pr.items() if n}
         return per
@@ -261,6 +264,42 @@ def main():
         extra["bsgs_8x4_diagonals_per_s"] = round(n1 * n2 / dt, 1)
         del rks, pt, ptx, ptb
 
+    if "config4" in groups:
+        # config 4: N = 2^16, L = 35, K = 7, dnum = 5; 32 rotations by +-2^i of one ciphertext with plaintext MAC
+        # (a CoeffToSlot-shaped stage), singly and doubly hoisted.  32 keys of 210 MiB: rolled copies of one.
+        ps4 = synth.CFG4
+        ctx4 = binding.Context(ps4.logN, ps4.L, ps4.K, ps4.dnum, ps4.primes)
+        rng4 = synth.rng_for(4, 100)
+        rots4 = synth.CFG4_ROTATIONS
+        gs4 = [synth.galois_element(r, ps4.logN) for r in rots4]
+        key4 = dev(synth.uniform_residues(rng4, ps4.primes, N, lead=(ps4.dnum, 2)))
+        rks4 = [torch.roll(key4, shifts=i + 1, dims=-1).contiguous() for i in range(len(rots4))]
+        ct4 = dev(synth.uniform_residues(rng4, ps4.q_primes, N, lead=(2,)))
+        ptx4 = torch.stack([torch.roll(key4[0, 0], shifts=i, dims=-1) for i in range(len(rots4))]).contiguous()
+        pt4 = ptx4[:, :ps4.L].contiguous()
+        o4 = torch.empty_like(ct4)
+        reps = max(1, args.steps // 10)
+        dt = timed(lambda: ctx4.hrot_hoisted_mac(ct4, gs4, rks4, pt4, o4), reps, "config4_hoisted_rot_mac", ctx4)
+        extra["config4_hoisted_rot_mac_per_s"] = round(len(rots4) / dt, 1)
+        dt = timed(lambda: ctx4.hrot_dh_mac(ct4, gs4, rks4, ptx4, o4), reps, "config4_double_hoisted_rot_mac", ctx4)
+        extra["config4_double_hoisted_rot_mac_per_s"] = round(len(rots4) / dt, 1)
+        extra["config4_double_hoisted_key_stream_GBps"] = round(
+            len(rots4) * (2 * ps4.dnum + 1) * (ps4.L + ps4.K) * 8 * N / dt / 1e9, 1)
+        del ctx4, key4, rks4, ct4, ptx4, pt4, o4
+
+    if "latency" in groups:
+        # one ciphertext at a time (the latency a single HMult or rotation sees, launch gaps included)
+        a1, b1, o1 = ct1[:1].contiguous(), ct2[:1].contiguous(), torch.empty_like(ct1[:1])
+        extra["hmult_relin_batch1_latency_us"] = round(1e6 * timed(lambda: ctx.hmult_relin(a1, b1, evk, o1), label="hmult_relin_batch1"), 1)
+        extra["hrot_batch1_latency_us"] = round(1e6 * timed(lambda: ctx.hrot(a1, g, rk, o1)), 1)
+        ctx.set_overlap(True)
+        extra["hmult_relin_batch1_latency_us_with_overlap"] = round(1e6 * timed(lambda: ctx.hmult_relin(a1, b1, evk, o1)), 1)
+        extra["hrot_batch1_latency_us_with_overlap"] = round(1e6 * timed(lambda: ctx.hrot(a1, g, rk, o1)), 1)
+        ctx.set_overlap(False)
+        r1 = torch.empty((1, 2, L - 1, N), dtype=ct1.dtype, device=ct1.device)
+        extra["hmult_relin_rescale_batch1_latency_us"] = round(1e6 * timed(lambda: ctx.hmult_relin_rescale_at(L, a1, b1, evk, r1)), 1)
+        del a1, b1, o1, r1
+
     if "levels" in groups:
         # levels below L: rescale of the batch at level 24, and the HMult+relin -> rescale pair a CNN layer
         # issues; then HMult+relin at level 13 (digits of 6, 6 and 1 limbs) with the same full-level key
@@ -310,10 +349,18 @@ def main():
             oracle.hrot(h1, g, hr, P)
             n_each += 1
         dt = time.perf_counter() - a
-        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        threads = oracle.threads()
+        # the same pair once more on a single thread
+        oracle.set_threads(1)
+        a1 = time.perf_counter()
+        oracle.hmult_relin(h1, h2, hk, P)
+        oracle.hrot(h1, g, hr, P)
+        dt1 = time.perf_counter() - a1
+        oracle.set_threads(threads)
         cpu = {"value": round(2 * n_each / dt, 3), "unit": "key-switches/s", "cores": threads, "kind": "oracle",
                "sample": "%d HMult+relin and %d HRot of the same shape (1 ciphertext each, not the batch of 8), "
-                         "OpenMP over limbs" % (n_each, n_each)}
+                         "OpenMP over limbs" % (n_each, n_each),
+               "single_thread_value": round(2 / dt1, 3)}
 
     line = {
         "metric": "key-switches/sec (HMult+relin, HRot) at N=2^16,L=24",

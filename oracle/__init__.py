@@ -54,6 +54,16 @@ def lib():
     return _lib
 
 
+def threads() -> int:
+    """OpenMP threads the limb loops run on."""
+    return int(lib().orc_threads())
+
+
+def set_threads(n: int) -> None:
+    """Pin the number of OpenMP threads (timing only; results do not depend on it)."""
+    lib().orc_set_threads(ctypes.c_int(n))
+
+
 def _ptr(a: np.ndarray):
     assert a.flags["C_CONTIGUOUS"], "oracle buffers must be contiguous"
     return ctypes.c_void_p(a.ctypes.data)

@@ -25,6 +25,18 @@
 
 typedef unsigned __int128 u128;
 
+/* ------------------------------------------------------------------ threads */
+/* Timing aid for the benchmark's CPU baseline: how many OpenMP threads the limb loops use, and a way to pin
+ * that number (1 = single thread).  No effect on any result. */
+#ifdef _OPENMP
+#include <omp.h>
+int orc_threads(void) { return omp_get_max_threads(); }
+void orc_set_threads(int n) { if (n > 0) omp_set_num_threads(n); }
+#else
+int orc_threads(void) { return 1; }
+void orc_set_threads(int n) { (void)n; }
+#endif
+
 /* ------------------------------------------------------------------ scalars */
 uint64_t orc_mulmod(uint64_t a, uint64_t b, uint64_t m) { return (uint64_t)(((u128)a * b) % m); }
 uint64_t orc_addmod(uint64_t a, uint64_t b, uint64_t m) { return (uint64_t)(((u128)a + b) % m); }
