@@ -983,6 +983,14 @@ static void launch_modup(const View* c, const u64* in, u64* out, u32 batch, hipS
         case 6: launch_modup_a<6>(c, in, out, batch, s); break;
         case 7: launch_modup_a<7>(c, in, out, batch, s); break;
         case 8: launch_modup_a<8>(c, in, out, batch, s); break;
+        case 9: launch_modup_a<9>(c, in, out, batch, s); break;
+        case 10: launch_modup_a<10>(c, in, out, batch, s); break;
+        case 11: launch_modup_a<11>(c, in, out, batch, s); break;
+        case 12: launch_modup_a<12>(c, in, out, batch, s); break;
+        case 13: launch_modup_a<13>(c, in, out, batch, s); break;
+        case 14: launch_modup_a<14>(c, in, out, batch, s); break;
+        case 15: launch_modup_a<15>(c, in, out, batch, s); break;
+        case 16: launch_modup_a<16>(c, in, out, batch, s); break;
     }
 }
 
@@ -1002,6 +1010,14 @@ static void launch_moddown(const View* c, const u64* in, u64* out, u32 groups, h
         case 6: launch_moddown_k<6>(c, in, out, groups, s); break;
         case 7: launch_moddown_k<7>(c, in, out, groups, s); break;
         case 8: launch_moddown_k<8>(c, in, out, groups, s); break;
+        case 9: launch_moddown_k<9>(c, in, out, groups, s); break;
+        case 10: launch_moddown_k<10>(c, in, out, groups, s); break;
+        case 11: launch_moddown_k<11>(c, in, out, groups, s); break;
+        case 12: launch_moddown_k<12>(c, in, out, groups, s); break;
+        case 13: launch_moddown_k<13>(c, in, out, groups, s); break;
+        case 14: launch_moddown_k<14>(c, in, out, groups, s); break;
+        case 15: launch_moddown_k<15>(c, in, out, groups, s); break;
+        case 16: launch_moddown_k<16>(c, in, out, groups, s); break;
     }
 }
 

@@ -305,7 +305,8 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
     const u32 rot = ns ? (inst + tile) % ns : 0;  // workgroups sharing sources walk them in different orders
     T x[TB][16];
     if (all_fp) {
-        // FP64 pipe: every product reduced lazily (|.| <= 1.25 q), at most 18 of them accumulated.  The 16
+        // FP64 pipe: every product reduced lazily (|.| <= 1.25 q), at most 18 of them accumulated between two
+        // reductions of the accumulator (8 sources; ModDown sources count twice).  The 16
         // words of a lane are converted in two halves so that accumulators and staged sources stay small.
         FpAr::Mod fm[TB];
 #pragma unroll
@@ -324,42 +325,52 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
 #pragma unroll
                 for (int k = 0; k < 8; k++) cur[k] = s0[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
             }
-            for (u32 i0 = 0; i0 < ns; i0++) {
-                const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
-                if (i0 + 1 < ns) {
-                    const u32 in = i0 + 1 + rot < ns ? i0 + 1 + rot : i0 + 1 + rot - ns;
-                    const u64* sn = src + (size_t)in * N;
+            // rounds of 8 sources: with more than 8, the accumulators go back to |acc| <= q/2 between rounds
+            for (u32 g0 = 0; g0 < ns; g0 += 8) {
+                const u32 ge = g0 + 8 < ns ? g0 + 8 : ns;
+                for (u32 i0 = g0; i0 < ge; i0++) {
+                    const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
+                    if (i0 + 1 < ns) {
+                        const u32 in = i0 + 1 + rot < ns ? i0 + 1 + rot : i0 + 1 + rot - ns;
+                        const u64* sn = src + (size_t)in * N;
 #pragma unroll
-                    for (int k = 0; k < 8; k++) nxt[k] = sn[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
+                        for (int k = 0; k < 8; k++) nxt[k] = sn[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
+                    }
+                    if (DIR == CONV_UP) {  // sources are doubles holding canonical residues of ~the targets' size
+                        double cf[TB];
+#pragma unroll
+                        for (int t = 0; t < TB; t++) cf[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
+#pragma unroll
+                        for (int k = 0; k < 8; k++) {
+                            const double y = FpAr::from_raw(cur[k]);
+#pragma unroll
+                            for (int t = 0; t < TB; t++) acc[t][k] += FpAr::mulmod_lazy(y, cf[t], fm[t]);
+                        }
+                    } else {  // sources are words below 2^61: y = yh * 2^30 + yl, y*c = yh * (c * 2^30) + yl * c (mod q)
+                        double cl[TB], ch[TB];
+#pragma unroll
+                        for (int t = 0; t < TB; t++) {
+                            cl[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2];
+                            ch[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2 + 1];
+                        }
+#pragma unroll
+                        for (int k = 0; k < 8; k++) {
+                            const u64 y = cur[k];
+                            const double yh = (double)(u32)(y >> 30), yl = (double)(u32)(y & 0x3fffffffu);
+#pragma unroll
+                            for (int t = 0; t < TB; t++)
+                                acc[t][k] += FpAr::mulmod_lazy(yh, ch[t], fm[t]) + FpAr::mulmod_lazy(yl, cl[t], fm[t]);
+                        }
+                    }
+#pragma unroll
+                    for (int k = 0; k < 8; k++) cur[k] = nxt[k];
                 }
-                if (DIR == CONV_UP) {  // sources are doubles holding canonical residues of ~the targets' size
-                    double cf[TB];
+                if (ge < ns) {
 #pragma unroll
-                    for (int t = 0; t < TB; t++) cf[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
+                    for (int t = 0; t < TB; t++)
 #pragma unroll
-                    for (int k = 0; k < 8; k++) {
-                        const double y = FpAr::from_raw(cur[k]);
-#pragma unroll
-                        for (int t = 0; t < TB; t++) acc[t][k] += FpAr::mulmod_lazy(y, cf[t], fm[t]);
-                    }
-                } else {  // sources are words below 2^61: y = yh * 2^30 + yl, y*c = yh * (c * 2^30) + yl * c (mod q)
-                    double cl[TB], ch[TB];
-#pragma unroll
-                    for (int t = 0; t < TB; t++) {
-                        cl[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2];
-                        ch[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2 + 1];
-                    }
-#pragma unroll
-                    for (int k = 0; k < 8; k++) {
-                        const u64 y = cur[k];
-                        const double yh = (double)(u32)(y >> 30), yl = (double)(u32)(y & 0x3fffffffu);
-#pragma unroll
-                        for (int t = 0; t < TB; t++)
-                            acc[t][k] += FpAr::mulmod_lazy(yh, ch[t], fm[t]) + FpAr::mulmod_lazy(yl, cl[t], fm[t]);
-                    }
+                        for (int k = 0; k < 8; k++) acc[t][k] = FpAr::reduce(acc[t][k], fm[t]);
                 }
-#pragma unroll
-                for (int k = 0; k < 8; k++) cur[k] = nxt[k];
             }
 #pragma unroll
             for (int t = 0; t < TB; t++) {
@@ -378,19 +389,32 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
             for (int t = 0; t < TB; t++)
 #pragma unroll
                 for (int k = 0; k < 8; k++) acc[t][k] = u128w{0, 0};
-            for (u32 i0 = 0; i0 < ns; i0++) {
-                const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
-                const u64* si = src + (size_t)i * N;
-                const bool src_fp = DIR == CONV_UP && tb.pc[tb.phys(src_prime + i)].fp;
-                u64 cc[TB];
+            // 8 terms (each below 2^61 * q) stay below q * 2^64, the bound of the reduction: with more sources,
+            // q * 2^64 is taken off after every round of 8 terms
+            for (u32 g0 = 0; g0 < ns; g0 += 8) {
+                const u32 ge = g0 + 8 < ns ? g0 + 8 : ns;
+                for (u32 i0 = g0; i0 < ge; i0++) {
+                    const u32 i = i0 + rot < ns ? i0 + rot : i0 + rot - ns;
+                    const u64* si = src + (size_t)i * N;
+                    const bool src_fp = DIR == CONV_UP && tb.pc[tb.phys(src_prime + i)].fp;
+                    u64 cc[TB];
 #pragma unroll
-                for (int t = 0; t < TB; t++) cc[t] = chat[(size_t)i * chat_stride + pi[t]];
+                    for (int t = 0; t < TB; t++) cc[t] = chat[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
-                for (int k = 0; k < 8; k++) {
-                    u64 y = si[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
-                    if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+                    for (int k = 0; k < 8; k++) {
+                        u64 y = si[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
+                        if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
 #pragma unroll
-                    for (int t = 0; t < TB; t++) mac128(acc[t][k], y, cc[t]);
+                        for (int t = 0; t < TB; t++) mac128(acc[t][k], y, cc[t]);
+                    }
+                }
+                if (ns > 8) {
+#pragma unroll
+                    for (int t = 0; t < TB; t++) {
+                        const u64 qt = tb.pc[tb.phys(pi[t])].q;
+#pragma unroll
+                        for (int k = 0; k < 8; k++) acc[t][k].hi = csub(acc[t][k].hi, qt);
+                    }
                 }
             }
 #pragma unroll
@@ -418,6 +442,10 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
                     u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
                     if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
                     mac128(acc[k], y, cc);
+                }
+                if (ns > 8 && ((i & 7) == 7 || i + 1 == ns)) {
+#pragma unroll
+                    for (int k = 0; k < 16; k++) acc[k].hi = csub(acc[k].hi, pc.q);
                 }
             }
 #pragma unroll
@@ -1003,9 +1031,12 @@ __global__ __launch_bounds__(256) void modup_kernel(const u64* __restrict__ in, 
     for (u32 t = 0; t < D; t++) {
         if (t >= j * ALPHA && t < (j + 1) * ALPHA) continue;
         u128w acc = {0, 0};
-#pragma unroll
-        for (int ii = 0; ii < ALPHA; ii++) mac128(acc, y[ii], chat[(size_t)ii * D + t]);
         const PrimeConst pc = tb.pc[t];
+#pragma unroll
+        for (int ii = 0; ii < ALPHA; ii++) {
+            mac128(acc, y[ii], chat[(size_t)ii * D + t]);
+            if (ALPHA > 8 && ((ii & 7) == 7 || ii + 1 == ALPHA)) acc.hi = csub(acc.hi, pc.q);  // keeps acc < q * 2^64
+        }
         dst[(size_t)t * N] = redc(acc, pc.q, pc.qneg);
     }
 }
@@ -1023,9 +1054,12 @@ __global__ __launch_bounds__(256) void moddown_kernel(const u64* __restrict__ in
         y[k] = mul_shoup(src[(size_t)(L + k) * N], tb.dn_hatinv[2 * k], tb.dn_hatinv[2 * k + 1], tb.pc[L + k].q);
     for (u32 i = 0; i < L; i++) {
         u128w acc = {0, 0};
-#pragma unroll
-        for (int k = 0; k < KK; k++) mac128(acc, y[k], tb.dn_chat[(size_t)k * L + i]);
         const PrimeConst pc = tb.pc[i];
+#pragma unroll
+        for (int k = 0; k < KK; k++) {
+            mac128(acc, y[k], tb.dn_chat[(size_t)k * L + i]);
+            if (KK > 8 && ((k & 7) == 7 || k + 1 == KK)) acc.hi = csub(acc.hi, pc.q);  // keeps acc < q * 2^64
+        }
         const u64 conv = redc(acc, pc.q, pc.qneg);
         const PinvConst pi = tb.pinv[i];
         dst[(size_t)i * N] = mul_shoup(submod(src[(size_t)i * N], conv, pc.q), pi.w, pi.wp, pc.q);

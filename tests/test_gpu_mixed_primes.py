@@ -21,6 +21,8 @@ CHAINS = {
     "big_small": (13, [60, 28, 49, 49], [36, 36, 60], 2),
     "class_boundary": (12, [FP_LIMIT - (1 << 20), FP_LIMIT - (1 << 20), FP_LIMIT, FP_LIMIT], [FP_LIMIT - (1 << 22), 59], 2),
     "small_special": (14, [50, 50, 50], [30, 31, 32], 1),
+    # digits of 10 limbs (more than one accumulation round in the conversions), both classes among sources and targets
+    "wide_digits": (12, [50, 36, 55, 49, 60, 50, 30, 49, 50, 58] * 2, [59, 40, 60, 50, 59, 36, 60, 49, 59, 45], 2),
 }
 
 
@@ -105,7 +107,7 @@ def _random_case(seed):
     rng = np.random.default_rng(seed)
     logN = int(rng.choice([12, 12, 13]))
     L = int(rng.integers(1, 11))
-    dnum = int(rng.choice([d for d in range(1, L + 1) if L % d == 0 and L // d <= 8]))
+    dnum = int(rng.choice([d for d in range(1, L + 1) if L % d == 0 and L // d <= 16]))
     K = int(rng.integers(1, 9))
     bits = [30, 36, 44, 49, 55, 59]
     qf = [int(rng.choice(bits)) for _ in range(L)]

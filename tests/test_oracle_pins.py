@@ -197,7 +197,7 @@ def _small_set(logn=5, L=4, K=2, dnum=2, qb=20, pb=24):
 
 
 @pytest.mark.parametrize("shape", [(5, 4, 2, 2, 20, 24), (4, 6, 3, 2, 20, 22), (4, 3, 1, 3, 35, 36),
-                                   (3, 6, 6, 1, 30, 31), (4, 8, 2, 4, 49, 59)])
+                                   (3, 6, 6, 1, 30, 31), (4, 8, 2, 4, 49, 59), (4, 12, 3, 1, 49, 59), (3, 20, 10, 2, 30, 31)])
 def test_modup_vs_bigint_crt(orc, shape):
     ps = _small_set(*shape)
     P = orc.Params.from_set(ps)
@@ -245,7 +245,8 @@ def test_conv_matches_termwise_bigint(orc):
         assert int(got[n]) == want % b
 
 
-@pytest.mark.parametrize("shape", [(5, 4, 2, 2, 20, 24), (4, 6, 3, 2, 20, 22), (4, 3, 1, 3, 35, 36), (4, 8, 2, 4, 49, 59)])
+@pytest.mark.parametrize("shape", [(5, 4, 2, 2, 20, 24), (4, 6, 3, 2, 20, 22), (4, 3, 1, 3, 35, 36), (4, 8, 2, 4, 49, 59),
+                                   (4, 3, 12, 1, 49, 59)])
 def test_moddown_vs_bigint(orc, shape):
     ps = _small_set(*shape)
     P = orc.Params.from_set(ps)
