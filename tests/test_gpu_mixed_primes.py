@@ -103,23 +103,24 @@ def test_largest_supported_chain(orc):
         assert np.array_equal(host(ctx.rescale(ell, dev(ct1))), orc.rescale(ct1, P)), ell
 
 
-def _random_case(seed):
+def _random_case(seed, max_L=10, max_K=8):
     rng = np.random.default_rng(seed)
     logN = int(rng.choice([12, 12, 13]))
-    L = int(rng.integers(1, 11))
+    L = int(rng.integers(1, max_L + 1))
     dnum = int(rng.choice([d for d in range(1, L + 1) if L % d == 0 and L // d <= 16]))
-    K = int(rng.integers(1, 9))
+    K = int(rng.integers(1, max_K + 1))
     bits = [30, 36, 44, 49, 55, 59]
     qf = [int(rng.choice(bits)) for _ in range(L)]
     pf = [int(rng.choice([36, 49, 59, 60])) for _ in range(K)]
     return logN, qf, pf, dnum
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", list(range(12)) + [100 + i for i in range(8)])
 def test_random_chains_levels_and_operations(orc, seed):
     """Seeded random parameter sets (1..10 limbs of 30..60 bits in any order, 1..8 special limbs, any digit
-    count), a random level, every composed operation once."""
-    logN, qf, pf, dnum = _random_case(500 + seed)
+    count; seeds from 100 on: up to 32 limbs and 16 special limbs, digits of up to 16 limbs), a random level,
+    every composed operation once."""
+    logN, qf, pf, dnum = _random_case(500 + seed) if seed < 100 else _random_case(500 + seed, 32, 16)
     ps = synth.mixed_params(logN, qf, pf, dnum, "random%d" % seed)
     _say("seed", seed, "logN", logN, "q bits", qf, "p bits", pf, "dnum", dnum)
     from paper_2310_16530_amd import binding
@@ -176,3 +177,31 @@ def test_sixteen_rotations_in_one_launch_near_the_fp64_prime_limit(orc):
     assert np.array_equal(got, orc.hrot_hoisted_mac(ct, gs, rks, np.ascontiguousarray(pt[:, :ps.L]), P))
     got = host(ctx.hrot_dh_mac(dev(ct), gs, d_rks, dev(pt)))
     assert np.array_equal(got, orc.hrot_dh_mac_level(ct, gs, rks, pt, P))
+
+
+def test_wide_digits_at_the_top_of_the_fp64_range(orc):
+    """Digits and a special basis of 16 limbs with q-limbs just below 3*2^48, and coefficients chosen so that
+    every pre-multiplied source of the ModUp conversion is q_i - 1: the FP64 accumulators of the fused conversions
+    see the largest terms their bounds allow, over two rounds of 8 sources."""
+    ps = synth.mixed_params(12, [FP_LIMIT - (1 << 24)] * 16, [60] * 16, 1, "wide_fp_limit")
+    assert all(p < FP_LIMIT for p in ps.q_primes) and ps.L // ps.dnum == 16
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(78)
+    N, L = ps.N, ps.L
+    x = synth.uniform_residues(rng, ps.q_primes, N, lead=())
+    Q = 1
+    for q in ps.q_primes:
+        Q *= q
+    for i, q in enumerate(ps.q_primes):
+        qhat = (Q // q) % q
+        x[i, :64] = (q - 1) * qhat % q          # y_i = x_i * qhat^-1 = q_i - 1
+        x[i, 64:128] = qhat                      # y_i = 1
+    d = np.stack([orc.ntt(x[i], ps.logN, ps.q_primes[i], P.psi[i]) for i in range(L)])
+    key = synth.uniform_residues(rng, ps.primes, N, lead=(ps.dnum, 2))
+    for p_i, p in enumerate(ps.primes):
+        key[:, :, p_i, :32] = p - 1
+    got = host(ctx.keyswitch_at(L, dev(d[None]), dev(key)))[0]
+    assert np.array_equal(got, orc.keyswitch_level(d, key, P))
+    ct = np.stack([d, d])
+    assert np.array_equal(host(ctx.hmult_relin_rescale_at(L, dev(ct[None]), dev(ct[None]), dev(key)))[0],
+                          orc.hmult_relin_rescale_level(ct, ct, key, P))
