@@ -96,6 +96,10 @@ int ckks_table_bytes(uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum, size_
  *              psi with psi^N = -1 for every prime.
  *   K may be 0 (transform-only context; key-switch calls then return
  *   CKKS_EUNSUPPORTED).  Returns after the copy has completed.
+ *   Shape limits: CKKS_MIN_LOGN <= logN <= CKKS_MAX_LOGN, L + K <= CKKS_MAX_PRIMES, dnum divides L,
+ *   L / dnum <= CKKS_MAX_DIGIT and K <= CKKS_MAX_DIGIT (else CKKS_EUNSUPPORTED).  A chain whose length is
+ *   not a multiple of the digit size is served by a context on the chain padded to the next multiple,
+ *   worked at the levels below it through the *_at calls (their last digit may be partial).
  * Ownership: the context keeps d_tables in use until ckks_ctx_destroy; the
  * caller frees it afterwards.
  */
