@@ -315,7 +315,31 @@ def main():
         extra["config4_double_hoisted_rot_mac_per_s"] = round(len(rots4) / dt, 1)
         extra["config4_double_hoisted_key_stream_GBps"] = round(
             len(rots4) * (2 * ps4.dnum + 1) * (ps4.L + ps4.K) * 8 * N / dt / 1e9, 1)
-        del ctx4, key4, rks4, ct4, ptx4, pt4, o4
+        # a factorised slot transform of the same shape: three baby-step giant-step stages of 8 x 4 diagonals at
+        # levels 35, 34, 33, each followed by a rescale (ready plaintext diagonals, keys shared by the stages)
+        n1, n2 = 8, 4
+        stage_args = []
+        stride = 1
+        for s_ in range(3):
+            ell = ps4.L - s_
+            bg = [synth.galois_element(b * stride, ps4.logN) for b in range(n1)]
+            gg = [synth.galois_element(g_ * n1 * stride, ps4.logN) for g_ in range(n2)]
+            ptb = ptx4[:, :ell + ps4.K].reshape(n2, n1, ell + ps4.K, N).contiguous()
+            stage_args.append((ell, bg, gg, ptb, torch.empty((2, ell, N), dtype=ct4.dtype, device=ct4.device),
+                               torch.empty((1, 2, ell - 1, N), dtype=ct4.dtype, device=ct4.device)))
+            stride *= n1 * n2
+
+        def chain():
+            x = ct4
+            for ell, bg, gg, ptb, mid, low in stage_args:
+                ctx4.lintrans_bsgs_at(ell, x, bg, rks4[:n1], gg, rks4[n1:n1 + n2], ptb, mid)
+                ctx4.rescale(ell, mid.reshape(1, 2, ell, N), low)
+                x = low[0]
+
+        dt = timed(chain, reps, "config4_transform_chain_3x32", ctx4)
+        extra["config4_transform_chain_3x32_per_s"] = round(1.0 / dt, 1)
+        extra["config4_transform_chain_diagonals_per_s"] = round(3 * n1 * n2 / dt, 1)
+        del ctx4, key4, rks4, ct4, ptx4, pt4, o4, stage_args
 
     if "latency" in groups:
         # one ciphertext at a time (the latency a single HMult or rotation sees, launch gaps included)

@@ -499,3 +499,38 @@ def test_quadratic_activation_composed_from_library_calls(orc, shape):
         o_b = orc.rescale(np.stack([orc.pointwise("mul", x[i, t], w1[0], q[:ell]) for t in range(2)]), P)
         want = np.stack([orc.pointwise("add", o_a[t], o_b[t, :ell - 2], q[:ell - 2]) for t in range(2)])
         assert np.array_equal(got[i], want), i
+
+
+@pytest.mark.parametrize("shape", [(12, 6, 2, 3, 49, 59), (13, 6, 3, 2, 49, 59)])
+def test_factorised_transform_chain(orc, shape):
+    """Three baby-step giant-step stages with growing rotation strides and a rescale after each one (the shape
+    of a factorised slot transform): stage s works at level L - s on ready plaintext diagonals; every stage and
+    every rescale goes through the library and is mirrored call by call with the oracle."""
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(12000 + sum(shape))
+    stages = [(4, 2), (2, 2), (3, 1)]           # (baby steps, giant steps)
+    keys, d_keys = {}, {}
+
+    def key_for(g):                              # one key per Galois element, shared by the stages
+        if g not in keys:
+            keys[g] = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+            d_keys[g] = dev(keys[g])
+        return g
+
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    d_ct, o_ct = dev(ct), ct
+    stride = 1
+    for s, (n1, n2) in enumerate(stages):
+        ell = ps.L - s
+        _say("transform chain", shape, "stage", s, "level", ell)
+        baby = [key_for(synth.galois_element(b * stride, ps.logN)) for b in range(n1)]
+        giant = [key_for(synth.galois_element(g * n1 * stride, ps.logN)) for g in range(n2)]
+        basis = list(ps.q_primes[:ell]) + list(ps.p_primes)
+        pt = synth.uniform_residues(rng, basis, ps.N, lead=(n2, n1))
+        d_ct = ctx.rescale(ell, ctx.lintrans_bsgs_at(ell, d_ct, baby, [d_keys[g] for g in baby], giant,
+                                                     [d_keys[g] for g in giant], dev(pt))[None])[0]
+        o_ct = orc.rescale(orc.lintrans_bsgs_level(o_ct, baby, [keys[g] for g in baby], giant, [keys[g] for g in giant],
+                                                   pt, P), P)
+        assert np.array_equal(host(d_ct), o_ct), s
+        stride *= n1 * n2
