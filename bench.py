@@ -35,7 +35,7 @@ _MIB = 1 << 20
 MEASURED = {
     # kernel: (read MiB, write MiB, VALU wave-instructions)
     "conv_fwd_strided_kernel<FpAr, 8, 1, 3>": (97.0, 288.0, 52756480),
-    "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": (49.7, 193.9, 54837248),
+    "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": (49.6, 193.9, 48545792),
     "conv_fwd_strided_kernel<IntAr, 8, 1, 2>": (98.7, 96.0, 50319360),
     "inv_contig_kernel<FpAr, 8, 1>": (204.1, 96.0, 10543104),
     "inv_contig_kernel<FpAr, 8, 2>": (108.1, 96.0, 11071488),
@@ -134,15 +134,15 @@ def main():
     # issue binds), from operation counts and the shortest exact FP64 sequences: a modular product of two
     # residues below 2^50 is 6 instructions (mul, fma for the low part, mul by 1/q, round, fma, add), a
     # multiply-accumulate 7, a butterfly 8 (product, add, sub), the reduction of an accumulator 3; a 60-bit source
-    # enters as two 30-bit halves (two multiply-accumulates).  Every converted word then takes (log2 N - 8) / 2
-    # butterflies of the first forward pass.
+    # is first brought below the target prime (4: mul by 1/q, round, fma, add of the low half) and then takes one
+    # multiply-accumulate.  Every converted word then takes (log2 N - 8) / 2 butterflies of the first forward pass.
     bfly = 8 * (ps.logN - 8) // 2
     n_fp_q = sum(1 for q in ps.q_primes if q < 3 << 48)
     alg_lane_ops = {
         # ModUp: per ciphertext and coefficient, every digit writes the FP64 q-limbs it does not own
         "conv_fwd_strided_kernel<FpAr, 8, 1, 3>": B * N * dnum * (n_fp_q - ps.L // dnum) * (7 * (ps.L // dnum) + 3 + bfly),
-        # ModDown: both components, every FP64 q-limb, K sources of two halves each
-        "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": B * 2 * N * n_fp_q * (14 * ps.K + 3 + bfly),
+        # ModDown: both components, every FP64 q-limb, K sources of 60 bits
+        "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": B * 2 * N * n_fp_q * (11 * ps.K + 3 + bfly),
     }
     for kname_, ops in alg_lane_ops.items():
         if kname_ in kernels:

@@ -132,7 +132,7 @@ static LevelLayout level_layout(size_t base, u32 ell, u32 K, u32 alpha) {
     l.up_chat_fp = t.take(ell * D * sizeof(double));
     l.up_fp_ok = t.take(beta * D * sizeof(u32));
     l.dn_chat = t.take(K1 * ell * sizeof(u64));
-    l.dn_chat_fp = t.take(K1 * ell * 2 * sizeof(double));
+    l.dn_chat_fp = t.take(K1 * ell * sizeof(double));
     l.dn_fp_ok = t.take(ell * sizeof(u32));
     l.pinv = t.take(ell * sizeof(PinvConst));
     l.pmod = t.take(ell * sizeof(u64));
@@ -147,7 +147,7 @@ static RescaleLayout rescale_layout(size_t base, u32 ell) {
     RescaleLayout l;
     l.sc_dn = t.take(sizeof(InvScale));
     l.dn_chat = t.take(T * sizeof(u64));
-    l.dn_chat_fp = t.take(T * 2 * sizeof(double));
+    l.dn_chat_fp = t.take(T * sizeof(double));
     l.dn_fp_ok = t.take(T * sizeof(u32));
     l.pinv = t.take(T * sizeof(PinvConst));
     l.end = t.o;
@@ -164,7 +164,7 @@ static MergedLayout merged_layout(size_t base, u32 ell, u32 K) {
     MergedLayout l;
     l.sc_dn = t.take(S * sizeof(InvScale));
     l.dn_chat = t.take(S * T * sizeof(u64));
-    l.dn_chat_fp = t.take(S * T * 2 * sizeof(double));
+    l.dn_chat_fp = t.take(S * T * sizeof(double));
     l.dn_fp_ok = t.take(T * sizeof(u32));
     l.pinv = t.take(T * sizeof(PinvConst));
     l.qlinv = t.take(T * sizeof(PinvConst));
@@ -520,8 +520,7 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
                 const u64 hatb = prod_except(specials, k, qi);
                 dn_chat[(size_t)k * ell + i] = h_mont(hatb, qi);
                 // the conversion kernel strides by ell entries, i.e. 2*ell doubles: index (k*ell + i)*2
-                dn_chat_fp[((size_t)k * ell + i) * 2] = pc[i].fp ? (double)hatb : 0.0;
-                dn_chat_fp[((size_t)k * ell + i) * 2 + 1] = pc[i].fp ? (double)h_mulmod(hatb, (1ull << 30) % qi, qi) : 0.0;
+                dn_chat_fp[(size_t)k * ell + i] = pc[i].fp ? (double)hatb : 0.0;
             }
             dn_fp_ok[i] = (pc[i].fp && qi >= (1ull << 28)) ? 1 : 0;
             pmod[i] = prod_except(specials, specials.size(), qi);
@@ -564,8 +563,7 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         for (u32 i = 0; i < T; i++) {
             const u64 qi = c->primes[i];
             dn_chat[i] = h_mont(1, qi);
-            dn_chat_fp[2 * i] = pc[i].fp ? 1.0 : 0.0;
-            dn_chat_fp[2 * i + 1] = pc[i].fp ? (double)((1ull << 30) % qi) : 0.0;
+            dn_chat_fp[i] = pc[i].fp ? 1.0 : 0.0;
             dn_fp_ok[i] = (pc[i].fp && qi >= (1ull << 28)) ? 1 : 0;
             const u64 pi = h_invmod(ql % qi, qi);
             pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
@@ -610,8 +608,7 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
             for (u32 k = 0; k < S; k++) {
                 const u64 hatb = prod_except(src, k, qi);
                 dn_chat[(size_t)k * T + i] = h_mont(hatb, qi);
-                dn_chat_fp[((size_t)k * T + i) * 2] = pc[i].fp ? (double)hatb : 0.0;
-                dn_chat_fp[((size_t)k * T + i) * 2 + 1] = pc[i].fp ? (double)h_mulmod(hatb, (1ull << 30) % qi, qi) : 0.0;
+                dn_chat_fp[(size_t)k * T + i] = pc[i].fp ? (double)hatb : 0.0;
             }
             dn_fp_ok[i] = (pc[i].fp && qi >= (1ull << 28)) ? 1 : 0;
             const u64 pi = h_invmod(prod_except(src, src.size(), qi), qi);

@@ -39,7 +39,7 @@ struct Tables {
     const u32* up_fp_ok;       // [dnum][D] 1 if target t of digit j may convert on the FP64 pipe: target and
                                //           all sources FpAr primes, largest source <= 2 * target
     const u64* dn_chat;        // [K][L]  (P/p_k) * 2^64 mod q_i
-    const double* dn_chat_fp;  // [K][L][2]  (P/p_k) mod q_i and (P/p_k) * 2^30 mod q_i as doubles
+    const double* dn_chat_fp;  // [K][L]  (P/p_k) mod q_i as a double (FpAr targets)
     const u32* dn_fp_ok;       // [L]  1 if q_i may convert on the FP64 pipe (FpAr prime, at least 2^28)
     const PinvConst* pinv;     // [L]     P^-1 mod q_i
     const u64* pmod;           // [L]     P mod q_i
@@ -346,20 +346,17 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
 #pragma unroll
                             for (int t = 0; t < TB; t++) acc[t][k] += FpAr::mulmod_lazy(y, cf[t], fm[t]);
                         }
-                    } else {  // sources are words below 2^61: y = yh * 2^30 + yl, y*c = yh * (c * 2^30) + yl * c (mod q)
-                        double cl[TB], ch[TB];
+                    } else {  // sources are words below 2^61: brought below the target first, then one product each
+                        double cl[TB];
 #pragma unroll
-                        for (int t = 0; t < TB; t++) {
-                            cl[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2];
-                            ch[t] = chat_fp[((size_t)i * chat_stride + pi[t]) * 2 + 1];
-                        }
+                        for (int t = 0; t < TB; t++) cl[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
                         for (int k = 0; k < 8; k++) {
                             const u64 y = cur[k];
-                            const double yh = (double)(u32)(y >> 30), yl = (double)(u32)(y & 0x3fffffffu);
+                            const double ya = (double)(u32)(y >> 30) * 1073741824.0, yl = (double)(u32)(y & 0x3fffffffu);
 #pragma unroll
                             for (int t = 0; t < TB; t++)
-                                acc[t][k] += FpAr::mulmod_lazy(yh, ch[t], fm[t]) + FpAr::mulmod_lazy(yl, cl[t], fm[t]);
+                                acc[t][k] += FpAr::mulmod_lazy(FpAr::reduce_split(ya, yl, fm[t]), cl[t], fm[t]);
                         }
                     }
 #pragma unroll

@@ -199,6 +199,14 @@ struct FpAr {
         double c = __builtin_rint(x * m.qinv);
         return __builtin_fma(-c, m.q, x);
     }
+    // A word y < 2^61 given as ya + yl with ya = (y >> 30) * 2^30 (31 significant bits, an exact double) and
+    // yl = y mod 2^30: an integer-valued double congruent to y modulo q with |result| <= (0.5 + 2^-19) q + 2^30.
+    // The quotient ya / q is below 2^33 for q >= 2^28, so its estimate is off by less than 2^-19 before
+    // rounding; ya - c*q is an integer below 2^50 in magnitude, hence the fma and the sum are exact.
+    static HD T reduce_split(double ya, double yl, const Mod& m) {
+        double c = __builtin_rint(ya * m.qinv);
+        return __builtin_fma(-c, m.q, ya) + yl;
+    }
     static HD T from_canon(u64 v, const Mod&) { return u64_to_f64(v); }
     static HD T from_raw(u64 v) { return __builtin_bit_cast(double, v); }
     static HD u64 to_raw(T v) { return __builtin_bit_cast(u64, v); }

@@ -3,6 +3,7 @@
 // exactness shown here is exactness on the GPU.  Compares against 128-bit integer arithmetic:
 //   * mulmod_lazy(a, w): congruent to a*w mod q, |r| <= (0.5 + 3A/8) q + 2^49 for |a| <= A q, A <= 8
 //   * reduce / canon / conversions
+//   * reduce_split: a 61-bit word brought below the modulus, and its product with a constant
 //   * four forward and four inverse butterfly stages from the documented start ranges stay exact
 // Prints "OK <count>" or the first failure.
 #include <stdio.h>
@@ -95,6 +96,32 @@ static int check_prime(u64 q, unsigned long long* count) {
                 printf("stage mismatch q=%llu k=%d\n", (unsigned long long)q, k); return 1; }
         }
         (*count)++;
+    }
+    // a word below 2^61 brought below the modulus (ModDown sources) and then multiplied by a constant:
+    // reduce_split needs q >= 2^28; eight such products (the most one accumulation round holds) stay exact
+    if (q >= (1ull << 28)) {
+        for (int it = 0; it < 200000; it++) {
+            u64 y;
+            switch (it & 7) {
+                case 0: y = (1ull << 61) - 1; break;
+                case 1: y = (1ull << 61) - (1ull << 30); break;
+                case 2: y = (it >> 3) % 64 < 61 ? (1ull << ((it >> 3) % 61)) : 0; break;
+                case 3: y = q * (rnd() % ((1ull << 61) / q)) + (q - 1) / 2 + (it & 8 ? 1 : 0); break;  // near half-way quotients
+                default: y = rnd() >> 3; break;
+            }
+            const double ya = (double)(u32)(y >> 30) * 1073741824.0, yl = (double)(u32)(y & 0x3fffffffu);
+            const double sred = FpAr::reduce_split(ya, yl, m);
+            if (sred != floor(sred) || imod((i128)(long long)sred, (long long)q) != (long long)(y % q) ||
+                fabs(sred) > (0.5 + 1.0 / 524288.0) * (double)q + 1073741824.0) {
+                printf("reduce_split failed q=%llu y=%llu s=%.0f\n", (unsigned long long)q, (unsigned long long)y, sred); return 1; }
+            const u64 w = (it & 16) ? q - 1 : rnd() % q;
+            const double r = FpAr::mulmod_lazy(sred, (double)w, m);
+            if (r != floor(r) || imod((i128)(long long)r, (long long)q) != imod((i128)(y % q) * (i128)w, (long long)q)) {
+                printf("reduce_split product failed q=%llu y=%llu w=%llu\n", (unsigned long long)q, (unsigned long long)y, (unsigned long long)w); return 1; }
+            if (8.0 * fabs(r) + 0.5 * (double)q >= 9007199254740992.0) {
+                printf("eight reduce_split products do not fit q=%llu r=%.0f\n", (unsigned long long)q, r); return 1; }
+            (*count)++;
+        }
     }
     return 0;
 }
