@@ -33,8 +33,9 @@
  *     buffers sized by ckks_table_bytes / ckks_workspace_bytes, 256-byte aligned.
  *   - return value: CKKS_OK or a negative error code; nothing throws or aborts.
  *     ckks_last_error() gives a message for the last failing call on a context.
- *   - dnum must divide L.  The calls without a level work on full-level operands (all L limbs
- *     present); the calls ending in _at, ckks_rescale and the merged-rescale calls take the number
+ *   - digits hold alpha = ceil(L / dnum) consecutive limbs; the last digit is shorter when dnum does not
+ *     divide L (dnum must be the digit count that this size gives: ceil(L / alpha) = dnum).  The calls
+ *     without a level work on full-level operands (all L limbs present); the calls ending in _at, ckks_rescale and the merged-rescale calls take the number
  *     of active limbs as `level` and use the same context, tables and full-level keys.
  *   - the calls may be captured in a HIP graph: they only launch kernels (no allocation, no
  *     memset), provided profiling is off.
@@ -96,10 +97,9 @@ int ckks_table_bytes(uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum, size_
  *              psi with psi^N = -1 for every prime.
  *   K may be 0 (transform-only context; key-switch calls then return
  *   CKKS_EUNSUPPORTED).  Returns after the copy has completed.
- *   Shape limits: CKKS_MIN_LOGN <= logN <= CKKS_MAX_LOGN, L + K <= CKKS_MAX_PRIMES, dnum divides L,
- *   L / dnum <= CKKS_MAX_DIGIT and K <= CKKS_MAX_DIGIT (else CKKS_EUNSUPPORTED).  A chain whose length is
- *   not a multiple of the digit size is served by a context on the chain padded to the next multiple,
- *   worked at the levels below it through the *_at calls (their last digit may be partial).
+ *   Shape limits: CKKS_MIN_LOGN <= logN <= CKKS_MAX_LOGN, L + K <= CKKS_MAX_PRIMES,
+ *   alpha = ceil(L / dnum) <= CKKS_MAX_DIGIT with ceil(L / alpha) = dnum, and K <= CKKS_MAX_DIGIT
+ *   (else CKKS_EUNSUPPORTED).
  * Ownership: the context keeps d_tables in use until ckks_ctx_destroy; the
  * caller frees it afterwards.
  */

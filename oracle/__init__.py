@@ -80,10 +80,13 @@ class Params:
     def __init__(self, logN: int, L: int, K: int, dnum: int, primes: Sequence[int],
                  psi: Optional[Sequence[int]] = None):
         assert len(primes) == L + K
-        assert dnum >= 1 and L % dnum == 0
+        # digits of alpha = ceil(L/dnum) limbs, the last one shorter when dnum does not divide L; dnum must be
+        # the number of digits this gives
+        assert dnum >= 1 and -(-L // -(-L // dnum)) == dnum
         self.logN, self.L, self.K, self.dnum = logN, L, K, dnum
         self.N = 1 << logN
-        self.alpha = L // dnum
+        self.alpha = -(-L // dnum)
+        self.even = L % dnum == 0   # the full-level C functions are written for digits of equal size
         self.primes = [int(p) for p in primes]
         self.psi = [int(x) for x in psi] if psi is not None else [min_psi(p, logN) for p in self.primes]
         self._primes = _arr_u64(self.primes)
@@ -165,6 +168,8 @@ def conv(x: np.ndarray, src: Sequence[int], b: int) -> np.ndarray:
 def modup(x: np.ndarray, P: Params) -> np.ndarray:
     """[L][N] coefficient form -> [dnum][L+K][N] coefficient form."""
     x = np.ascontiguousarray(x, dtype=np.uint64)
+    if not P.even:
+        return modup_level(x, P)
     out = np.empty((P.dnum, P.L + P.K, P.N), dtype=np.uint64)
     lib().orc_modup(_ptr(x), _ptr(out), _u32(P.logN), _u32(P.L), _u32(P.K), _u32(P.dnum), _ptr(P._primes))
     return out
@@ -213,6 +218,8 @@ def keyswitch(d: np.ndarray, key: np.ndarray, P: Params) -> np.ndarray:
     d = np.ascontiguousarray(d, dtype=np.uint64)
     key = np.ascontiguousarray(key, dtype=np.uint64)
     assert d.shape == (P.L, P.N) and key.shape == (P.dnum, 2, P.L + P.K, P.N)
+    if not P.even:
+        return keyswitch_level(d, key, P)
     out = np.empty((2, P.L, P.N), dtype=np.uint64)
     lib().orc_keyswitch(_ptr(d), _ptr(key), _ptr(out), *P._tail())
     return out
@@ -223,6 +230,8 @@ def hmult_relin(ct1: np.ndarray, ct2: np.ndarray, evk: np.ndarray, P: Params) ->
     ct2 = np.ascontiguousarray(ct2, dtype=np.uint64)
     evk = np.ascontiguousarray(evk, dtype=np.uint64)
     assert ct1.shape == ct2.shape == (2, P.L, P.N) and evk.shape == (P.dnum, 2, P.L + P.K, P.N)
+    if not P.even:
+        return hmult_relin_level(ct1, ct2, evk, P)
     out = np.empty((2, P.L, P.N), dtype=np.uint64)
     lib().orc_hmult_relin(_ptr(ct1), _ptr(ct2), _ptr(evk), _ptr(out), *P._tail())
     return out
@@ -232,6 +241,8 @@ def hrot(ct: np.ndarray, g: int, rk: np.ndarray, P: Params) -> np.ndarray:
     ct = np.ascontiguousarray(ct, dtype=np.uint64)
     rk = np.ascontiguousarray(rk, dtype=np.uint64)
     assert ct.shape == (2, P.L, P.N) and rk.shape == (P.dnum, 2, P.L + P.K, P.N)
+    if not P.even:
+        return hrot_level(ct, g, rk, P)
     out = np.empty((2, P.L, P.N), dtype=np.uint64)
     lib().orc_hrot(_ptr(ct), _u32(g), _ptr(rk), _ptr(out), *P._tail())
     return out
@@ -244,6 +255,9 @@ def hrot_hoisted_mac(ct: np.ndarray, galois: Sequence[int], rks: Sequence[np.nda
     pt = np.ascontiguousarray(pt, dtype=np.uint64)
     n_rot = len(galois)
     assert len(rks) == n_rot and pt.shape == (n_rot, P.L, P.N)
+    if not P.even and not want_per_rotation:
+        return hrot_hoisted_mac_level(ct, galois, rks, pt, P)
+    assert P.even, "per-rotation outputs are provided for digits of equal size only"
     rks = [np.ascontiguousarray(k, dtype=np.uint64) for k in rks]
     ptrs = (ctypes.c_void_p * n_rot)(*[k.ctypes.data for k in rks])
     g = np.ascontiguousarray(np.array(galois, dtype=np.uint32))

@@ -15,7 +15,9 @@
  * (it defers to the full-RNS CKKS scheme it cites), so each function states
  * the definition it evaluates.  Conventions: prime order q_0..q_{L-1},
  * p_0..p_{K-1}; residues canonical in [0, prime); ciphertext = (c0, c1) with
- * decryption c0 + c1*s; digit j = limbs j*alpha .. (j+1)*alpha-1, alpha = L/dnum.
+ * decryption c0 + c1*s; digit j = limbs j*alpha .. (j+1)*alpha-1, alpha = L/dnum
+ * (the level functions and the key generator take alpha = ceil(L/dnum) and a shorter last digit
+ * when dnum does not divide L; the full-level functions are written for digits of equal size).
  *
  * Parallelism: OpenMP over independent limbs only.
  */
@@ -491,7 +493,7 @@ typedef struct {
 static void level_open(orc_level* v, uint32_t ell, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
                        const uint64_t* primes, const uint64_t* psi) {
     uint32_t D = ell + K;
-    v->alpha = L / dnum;
+    v->alpha = (L + dnum - 1) / dnum; /* digits of ceil(L/dnum) limbs; the last one is shorter when dnum does not divide L */
     v->vprimes = (uint64_t*)malloc(sizeof(uint64_t) * D);
     v->vpsi = (uint64_t*)malloc(sizeof(uint64_t) * D);
     for (uint32_t i = 0; i < D; i++) {
@@ -829,7 +831,7 @@ void orc_make_switch_key(const uint64_t* s_hat, const uint64_t* sp_hat, const ui
                          uint64_t* key, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
                          const uint64_t* primes, const uint64_t* psi) {
     size_t N = (size_t)1 << logN;
-    uint32_t D = L + K, alpha = L / dnum;
+    uint32_t D = L + K, alpha = (L + dnum - 1) / dnum; /* as in the level functions */
     long total = (long)dnum * D;
 #pragma omp parallel for schedule(dynamic)
     for (long id = 0; id < total; id++) {

@@ -174,7 +174,7 @@ static MergedLayout merged_layout(size_t base, u32 ell, u32 K) {
 
 static size_t table_total(u32 logN, u32 L, u32 K, u32 dnum) {
     size_t o = shared_layout(logN, L, K).end;
-    for (u32 ell = 1; ell <= L; ell++) o = level_layout(o, ell, K, L / dnum).end;
+    for (u32 ell = 1; ell <= L; ell++) o = level_layout(o, ell, K, (L + dnum - 1) / dnum).end;
     for (u32 ell = 2; ell <= L; ell++) o = rescale_layout(o, ell).end;
     if (K)
         for (u32 ell = 2; ell <= L; ell++) o = merged_layout(o, ell, K).end;
@@ -344,9 +344,11 @@ static int check_shape(u32 logN, u32 L, u32 K, u32 dnum) {
     if (logN < CKKS_MIN_LOGN || logN > CKKS_MAX_LOGN) return CKKS_EUNSUPPORTED;
     if (L == 0 || dnum == 0) return CKKS_EINVAL;
     if (L + K > CKKS_MAX_PRIMES) return CKKS_EUNSUPPORTED;
-    if (L % dnum) return CKKS_EUNSUPPORTED;
+    if (dnum > L) return CKKS_EINVAL;
+    const u32 alpha = (L + dnum - 1) / dnum;  // limbs per digit; the last digit is shorter if dnum does not divide L
+    if ((L + alpha - 1) / alpha != dnum) return CKKS_EUNSUPPORTED;  // dnum is not the digit count this size gives
     if (K > CKKS_MAX_DIGIT) return CKKS_EUNSUPPORTED;
-    if (K > 0 && L / dnum > CKKS_MAX_DIGIT) return CKKS_EUNSUPPORTED;
+    if (K > 0 && alpha > CKKS_MAX_DIGIT) return CKKS_EUNSUPPORTED;
     return CKKS_OK;
 }
 
@@ -389,7 +391,7 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     const size_t total = table_total(logN, L, K, dnum);
     if (table_bytes < total) return CKKS_ENOMEM;
     const SharedLayout lay = shared_layout(logN, L, K);
-    const u32 D = L + K, alpha = L / dnum;
+    const u32 D = L + K, alpha = (L + dnum - 1) / dnum;
     const size_t N = (size_t)1 << logN;
     for (u32 i = 0; i < D; i++) {
         const u64 m = h_primes[i];

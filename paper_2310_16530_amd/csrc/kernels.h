@@ -1016,22 +1016,26 @@ __global__ __launch_bounds__(256) void modup_kernel(const u64* __restrict__ in, 
     const u32 n = blockIdx.x * 256 + threadIdx.x, j = blockIdx.y, b = blockIdx.z;
     const u64* src = in + ((size_t)b * L + (size_t)j * ALPHA) * N + n;
     u64* dst = out + ((size_t)b * tb.dnum + j) * D * N + n;
+    const u32 ns = (j + 1) * ALPHA <= L ? ALPHA : L - j * ALPHA;  // the last digit may be shorter
     u64 y[ALPHA];
 #pragma unroll
     for (int ii = 0; ii < ALPHA; ii++) {
-        const u32 i = j * ALPHA + ii;
-        const u64 x = src[(size_t)ii * N];
-        dst[(size_t)i * N] = x;
-        y[ii] = mul_shoup(x, tb.up_hatinv[2 * i], tb.up_hatinv[2 * i + 1], tb.pc[i].q);
+        y[ii] = 0;
+        if ((u32)ii < ns) {
+            const u32 i = j * ALPHA + ii;
+            const u64 x = src[(size_t)ii * N];
+            dst[(size_t)i * N] = x;
+            y[ii] = mul_shoup(x, tb.up_hatinv[2 * i], tb.up_hatinv[2 * i + 1], tb.pc[i].q);
+        }
     }
     const u64* chat = tb.up_chat + (size_t)j * ALPHA * D;
     for (u32 t = 0; t < D; t++) {
-        if (t >= j * ALPHA && t < (j + 1) * ALPHA) continue;
+        if (t >= j * ALPHA && t < j * ALPHA + ns) continue;
         u128w acc = {0, 0};
         const PrimeConst pc = tb.pc[t];
 #pragma unroll
         for (int ii = 0; ii < ALPHA; ii++) {
-            mac128(acc, y[ii], chat[(size_t)ii * D + t]);
+            if ((u32)ii < ns) mac128(acc, y[ii], chat[(size_t)ii * D + t]);
             if (ALPHA > 8 && ((ii & 7) == 7 || ii + 1 == ALPHA)) acc.hi = csub(acc.hi, pc.q);  // keeps acc < q * 2^64
         }
         dst[(size_t)t * N] = redc(acc, pc.q, pc.qneg);

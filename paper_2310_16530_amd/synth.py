@@ -85,7 +85,7 @@ class ParamSet:
 
     @property
     def alpha(self) -> int:
-        return self.L // self.dnum
+        return -(-self.L // self.dnum)  # the last digit is shorter when dnum does not divide L
 
     @property
     def q_primes(self) -> Tuple[int, ...]:
@@ -126,7 +126,7 @@ class ExplicitParamSet:
 
     @property
     def alpha(self) -> int:
-        return self.L // self.dnum
+        return -(-self.L // self.dnum)  # the last digit is shorter when dnum does not divide L
 
     @property
     def primes(self) -> Tuple[int, ...]:

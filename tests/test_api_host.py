@@ -42,7 +42,9 @@ def test_table_bytes_and_shape_validation(lib):
     assert lib.ckks_table_bytes(16, 24, 6, 4, None) == -1
     assert lib.ckks_table_bytes(11, 24, 6, 4, ctypes.byref(n)) == -2      # ring too small
     assert lib.ckks_table_bytes(17, 24, 6, 4, ctypes.byref(n)) == -2      # ring too large
-    assert lib.ckks_table_bytes(16, 24, 6, 5, ctypes.byref(n)) == -2      # dnum does not divide L
+    assert lib.ckks_table_bytes(16, 24, 6, 5, ctypes.byref(n)) == 0       # digits of 5, 5, 5, 5, 4 limbs
+    assert lib.ckks_table_bytes(16, 9, 3, 4, ctypes.byref(n)) == -2       # digits of 3 limbs make 3 digits, not 4
+    assert lib.ckks_table_bytes(16, 3, 3, 4, ctypes.byref(n)) == -1       # more digits than limbs
     assert lib.ckks_table_bytes(16, 0, 6, 1, ctypes.byref(n)) == -1
     assert lib.ckks_table_bytes(16, 24, 6, 0, ctypes.byref(n)) == -1
     assert lib.ckks_table_bytes(16, 60, 6, 4, ctypes.byref(n)) == -2      # too many primes
@@ -63,7 +65,8 @@ def test_ctx_create_rejects_bad_arguments_on_the_host(lib):
     assert lib.ckks_ctx_create(ctypes.byref(h), 12, 3, 1, 3, pr, None, None, big, None) == -1
     assert lib.ckks_ctx_create(ctypes.byref(h), 12, 3, 1, 3, pr, None, ctypes.c_void_p((1 << 20) + 8), big, None) == -1
     assert lib.ckks_ctx_create(ctypes.byref(h), 12, 3, 1, 3, pr, None, fake, 1024, None) == -4
-    assert lib.ckks_ctx_create(ctypes.byref(h), 12, 3, 1, 2, pr, None, fake, big, None) == -2
+    assert lib.ckks_ctx_create(ctypes.byref(h), 11, 3, 1, 3, pr, None, fake, big, None) == -2   # ring too small
+    assert lib.ckks_ctx_create(ctypes.byref(h), 12, 3, 1, 4, pr, None, fake, big, None) == -1   # more digits than limbs
     bad = (ctypes.c_uint64 * 4)(ps.primes[0], ps.primes[1], ps.primes[1], ps.primes[3])      # duplicate
     assert lib.ckks_ctx_create(ctypes.byref(h), 12, 3, 1, 3, bad, None, fake, big, None) == -1
     bad = (ctypes.c_uint64 * 4)(ps.primes[0], ps.primes[1], ps.primes[2] + 2 * 8192, ps.primes[3])  # composite

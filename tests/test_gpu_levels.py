@@ -43,7 +43,8 @@ def test_rescale_parity_every_level(orc, shape):
 
 
 LEVEL_SHAPES = [(12, 6, 2, 3, 49, 59), (13, 6, 3, 2, 49, 59), (12, 8, 8, 1, 49, 59), (12, 3, 1, 3, 35, 36),
-                (12, 6, 3, 2, 55, 59), (12, 14, 7, 2, 49, 59), (12, 24, 12, 2, 49, 59), (12, 11, 11, 1, 55, 59)]
+                (12, 6, 3, 2, 55, 59), (12, 14, 7, 2, 49, 59), (12, 24, 12, 2, 49, 59), (12, 11, 11, 1, 55, 59),
+                (12, 7, 3, 3, 49, 59), (12, 10, 4, 4, 55, 59)]   # last two: dnum does not divide L
 
 
 @pytest.mark.parametrize("shape", LEVEL_SHAPES)
@@ -225,7 +226,8 @@ def test_config3_double_hoisted_full_size(orc):
 
 # ------------------------------------------- ModDown merged with the following rescale
 MERGED_SHAPES = [(12, 6, 2, 3, 49, 59), (13, 6, 3, 2, 49, 59), (12, 3, 1, 3, 35, 36), (12, 6, 3, 2, 55, 59),
-                 (12, 8, 8, 1, 49, 59), (14, 4, 2, 2, 49, 59), (12, 10, 10, 1, 49, 59), (12, 18, 16, 2, 49, 59)]
+                 (12, 8, 8, 1, 49, 59), (14, 4, 2, 2, 49, 59), (12, 10, 10, 1, 49, 59), (12, 18, 16, 2, 49, 59),
+                 (12, 7, 3, 3, 49, 59)]
 
 
 @pytest.mark.parametrize("shape", MERGED_SHAPES)

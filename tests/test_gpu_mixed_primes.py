@@ -107,7 +107,7 @@ def _random_case(seed, max_L=10, max_K=8):
     rng = np.random.default_rng(seed)
     logN = int(rng.choice([12, 12, 13]))
     L = int(rng.integers(1, max_L + 1))
-    dnum = int(rng.choice([d for d in range(1, L + 1) if L % d == 0 and L // d <= 16]))
+    dnum = int(rng.choice([d for d in range(1, L + 1) if -(-L // -(-L // d)) == d and -(-L // d) <= 16]))
     K = int(rng.integers(1, max_K + 1))
     bits = [30, 36, 44, 49, 55, 59]
     qf = [int(rng.choice(bits)) for _ in range(L)]

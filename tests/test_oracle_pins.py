@@ -197,7 +197,8 @@ def _small_set(logn=5, L=4, K=2, dnum=2, qb=20, pb=24):
 
 
 @pytest.mark.parametrize("shape", [(5, 4, 2, 2, 20, 24), (4, 6, 3, 2, 20, 22), (4, 3, 1, 3, 35, 36),
-                                   (3, 6, 6, 1, 30, 31), (4, 8, 2, 4, 49, 59), (4, 12, 3, 1, 49, 59), (3, 20, 10, 2, 30, 31)])
+                                   (3, 6, 6, 1, 30, 31), (4, 8, 2, 4, 49, 59), (4, 12, 3, 1, 49, 59), (3, 20, 10, 2, 30, 31),
+                                   (4, 5, 2, 2, 20, 24), (4, 7, 3, 3, 35, 36), (3, 10, 4, 4, 49, 59)])
 def test_modup_vs_bigint_crt(orc, shape):
     ps = _small_set(*shape)
     P = orc.Params.from_set(ps)
@@ -211,19 +212,20 @@ def test_modup_vs_bigint_crt(orc, shape):
     assert out.shape == (ps.dnum, ps.L + ps.K, ps.N)
     a = ps.alpha
     for j in range(ps.dnum):
-        digit = list(ps.q_primes[j * a:(j + 1) * a])
+        digit = list(ps.q_primes[j * a:(j + 1) * a])              # the last digit is shorter when dnum does not divide L
+        assert 1 <= len(digit) <= a
         for n in range(ps.N):
-            xi, Qj = crt([x[j * a + i, n] for i in range(a)], digit)
+            xi, Qj = crt([x[j * a + i, n] for i in range(len(digit))], digit)
             us = set()
             for t, b in enumerate(ps.primes):
-                if j * a <= t < (j + 1) * a:
+                if j * a <= t < j * a + len(digit):
                     assert out[j, t, n] == x[t, n]              # own limbs copied
                     continue
                 diff = (int(out[j, t, n]) - xi) % b
                 u = diff * pow(Qj, -1, b) % b
                 us.add(u)
-            assert len(us) == 1 and 0 <= us.pop() < a           # one common overflow u < alpha
-            if a == 1:
+            assert len(us) == 1 and 0 <= us.pop() < len(digit)  # one common overflow u < digit size
+            if len(digit) == 1:
                 for t, b in enumerate(ps.primes):
                     assert int(out[j, t, n]) == xi % b           # alpha = 1: plain reduction
 
@@ -322,7 +324,8 @@ def _setup(orc, ps, seed, hamming=None):
     return P, rng, s, s_hat
 
 
-SHAPES = [(6, 4, 2, 2, 20, 24), (5, 6, 2, 3, 20, 22), (7, 4, 4, 1, 30, 31), (5, 3, 1, 3, 35, 36)]
+SHAPES = [(6, 4, 2, 2, 20, 24), (5, 6, 2, 3, 20, 22), (7, 4, 4, 1, 30, 31), (5, 3, 1, 3, 35, 36),
+          (5, 5, 3, 2, 20, 24), (5, 7, 3, 3, 20, 22)]   # the last two: dnum does not divide L (digits 3+2 and 3+3+1)
 
 
 @pytest.mark.parametrize("shape", SHAPES)
@@ -338,7 +341,7 @@ def test_switch_key_structure(orc, shape):
         # key0 + key1*s - gadget_j*s' must be the small error e_j on every limb
         t = orc.pointwise("add", key[j, 0], orc.pointwise("mul", key[j, 1], s_hat, ps.primes), ps.primes)
         gad = np.zeros_like(s2_hat)
-        for i in range(j * ps.alpha, (j + 1) * ps.alpha):
+        for i in range(j * ps.alpha, min((j + 1) * ps.alpha, ps.L)):
             gad[i] = orc.pointwise("mul", np.full((1, ps.N), Pp % ps.primes[i], dtype=np.uint64), s2_hat[i:i + 1], [ps.primes[i]])[0]
         t = orc.pointwise("sub", t, gad, ps.primes)
         got = orc.centred_small(t, P, ps.L + ps.K)
@@ -813,3 +816,23 @@ def test_bsgs_linear_transform_decrypts_to_the_sum_of_rotated_products(orc):
         one = orc.lintrans_bsgs_level(ct, baby, baby_rks, giant[1:], giant_rks[1:], pt[1:], P)
         inner = orc.hrot_dh_mac_level(ct, baby, baby_rks, pt[1], P)
         assert np.array_equal(one, orc.hrot_level(inner, giant[1], giant_rks[1], P))
+
+
+def test_level_functions_at_the_full_level_equal_the_full_level_functions(orc):
+    """The level functions (digits of ceil(L/dnum) limbs, last digit possibly shorter) are the definition used when
+    dnum does not divide L; with equal digits they must reproduce the full-level functions word for word."""
+    ps = _small_set(5, 6, 2, 3, 20, 22)
+    P = orc.Params.from_set(ps)
+    rng = np.random.default_rng(91)
+    key = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    ct1 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    ct2 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    g = synth.galois_element(3, ps.logN)
+    assert np.array_equal(orc.keyswitch_level(ct1[0], key, P), orc.keyswitch(ct1[0], key, P))
+    assert np.array_equal(orc.hmult_relin_level(ct1, ct2, key, P), orc.hmult_relin(ct1, ct2, key, P))
+    assert np.array_equal(orc.hrot_level(ct1, g, key, P), orc.hrot(ct1, g, key, P))
+    x = synth.uniform_residues(rng, ps.q_primes, ps.N)
+    assert np.array_equal(orc.modup_level(x, P), orc.modup(x, P))
+    gs = [g, synth.galois_element(-1, ps.logN)]
+    pt = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    assert np.array_equal(orc.hrot_hoisted_mac_level(ct1, gs, [key, key], pt, P), orc.hrot_hoisted_mac(ct1, gs, [key, key], pt, P))
