@@ -77,7 +77,7 @@ extern "C" {
 /* limits of this build */
 #define CKKS_MIN_LOGN 12
 #define CKKS_MAX_LOGN 16
-#define CKKS_MAX_PRIMES 64 /* L + K */
+#define CKKS_MAX_PRIMES 128 /* L + K */
 #define CKKS_MAX_DIGIT 16  /* alpha and K */
 #define CKKS_MAX_PRIME_BITS 61
 #define CKKS_ROTATIONS_PER_LAUNCH 16 /* instances with their own key that one launch takes (chunking of rotation batches) */

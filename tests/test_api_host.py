@@ -47,7 +47,8 @@ def test_table_bytes_and_shape_validation(lib):
     assert lib.ckks_table_bytes(16, 3, 3, 4, ctypes.byref(n)) == -1       # more digits than limbs
     assert lib.ckks_table_bytes(16, 0, 6, 1, ctypes.byref(n)) == -1
     assert lib.ckks_table_bytes(16, 24, 6, 0, ctypes.byref(n)) == -1
-    assert lib.ckks_table_bytes(16, 60, 6, 4, ctypes.byref(n)) == -2      # too many primes
+    assert lib.ckks_table_bytes(16, 60, 15, 4, ctypes.byref(n)) == 0      # L = 60 in four digits of 15 limbs
+    assert lib.ckks_table_bytes(16, 120, 9, 8, ctypes.byref(n)) == -2     # too many primes
     assert lib.ckks_table_bytes(16, 24, 17, 4, ctypes.byref(n)) == -2     # K too large
     assert lib.ckks_table_bytes(16, 34, 3, 2, ctypes.byref(n)) == -2      # alpha = 17 too large
     assert lib.ckks_table_bytes(16, 32, 16, 2, ctypes.byref(n)) == 0      # the widest digits

@@ -79,16 +79,19 @@ def test_every_entry_point_on_a_mixed_chain(orc, name):
             assert np.array_equal(host(ctx.rescale(ell, dev(ct1))), orc.rescale(ct1, P)), ell
 
 
-def test_largest_supported_chain(orc):
-    """L + K = 64 primes (the limit), digits of 8 limbs and 8 special limbs (both limits), N = 2^12."""
-    ps = synth.small_params(12, 56, 8, 7)
+@pytest.mark.parametrize("shape,levels", [((12, 56, 8, 7), (56, 51, 9)), ((12, 60, 15, 4), (60, 46, 16)),
+                                          ((12, 112, 16, 7), (112, 33))])
+def test_long_chains(orc, shape, levels):
+    """Long chains at N = 2^12: 64 primes in digits of 8, the paper's upper end L = 60 in four digits of 15, and
+    L + K = 128 primes (the limit) with digits and a special basis of 16 limbs (both limits)."""
+    ps = synth.small_params(*shape)
     ctx, P = gpu_ctx(ps), orc_params(orc, ps)
     rng = np.random.default_rng(64)
     key = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
     d_key = dev(key)
     g = synth.galois_element(3, ps.logN)
-    for ell in (56, 51, 9):
-        _say("largest chain, level", ell)
+    for ell in levels:
+        _say("long chain", shape, "level", ell)
         q = ps.q_primes[:ell]
         ct1 = synth.uniform_residues(rng, q, ps.N, lead=(2, 2))
         ct2 = synth.uniform_residues(rng, q, ps.N, lead=(2, 2))
