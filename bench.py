@@ -34,19 +34,19 @@ VALU_PEAK_TINSTR = 256 * 64 * 2.4e9 / 1e12
 _MIB = 1 << 20
 MEASURED = {
     # kernel: (read MiB, write MiB, VALU wave-instructions)
-    "conv_fwd_strided_kernel<FpAr, 8, 1, 3>": (96.9, 288.0, 52756480),
+    "conv_fwd_strided_kernel<FpAr, 8, 1, 3>": (97.0, 288.0, 52756480),
     "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": (49.6, 193.9, 48545792),
-    "conv_fwd_strided_kernel<IntAr, 8, 1, 2>": (98.7, 96.0, 50319360),
+    "conv_fwd_strided_kernel<IntAr, 8, 1, 2>": (98.6, 96.0, 47861760),
     "inv_contig_kernel<FpAr, 8, 1>": (204.1, 96.0, 10543104),
     "inv_contig_kernel<FpAr, 8, 2>": (108.1, 96.0, 11071488),
     "inv_strided_kernel<FpAr, 8>": (96.6, 96.0, 9891840),
     "inv_strided_kernel<IntAr, 8>": (48.5, 48.0, 13221888),
-    "ks_final_kernel<FpAr, 8, 1>": (982.8, 192.0, 27979776),
-    "ks_final_kernel<FpAr, 8, 2>": (500.0, 192.0, 24293376),
+    "ks_final_kernel<FpAr, 8, 1>": (982.6, 192.0, 27979776),
+    "ks_final_kernel<FpAr, 8, 2>": (500.7, 192.0, 24293376),
     "ks_inner_kernel<FpAr, 8, 1, false>": (588.2, 192.0, 43929600),
-    "ks_inner_kernel<FpAr, 8, 2, false>": (492.2, 192.0, 44457984),
-    "ks_inner_kernel<IntAr, 8, 1, false>": (132.9, 48.0, 49920000),
-    "ks_inner_kernel<IntAr, 8, 2, false>": (132.8, 48.0, 50445312),
+    "ks_inner_kernel<FpAr, 8, 2, false>": (492.3, 192.0, 44457984),
+    "ks_inner_kernel<IntAr, 8, 1, false>": (132.8, 48.0, 47953920),
+    "ks_inner_kernel<IntAr, 8, 2, false>": (132.8, 48.0, 48479232),
 }
 
 

@@ -116,9 +116,16 @@ struct IntAr {
     static HD T from_f64_lazy(double, const Mod&) { return 0; }  // FP64 conversion path is FpAr-only
     // product of two canonical residues, as a value the transforms accept
     static HD T mul_canon(u64 a, u64 b, const PrimeConst& p, const Mod&) { return mulmod_var(a, b, p.q, p.qneg, p.r2); }
-    // forward: values in [0, 4q)
+    // forward: values in [0, 8q) (8q < 2^64 for primes below 2^61).  A stage adds less than 2q to its inputs
+    // (the product is in [0, 2q) for any 64-bit Y), so inputs below 6q need no reduction; RED takes 4q off
+    // inputs that may have reached 6q..8q first.  NttCore fixes per stage which of the two applies.
+    template <bool RED>
     static HD void bfly_fwd(T& X, T& Y, const Tw& t, const Mod& m) {
-        u64 x = X >= m.q2 ? X - m.q2 : X;
+        u64 x = X;
+        if (RED) {
+            const u64 q4 = m.q2 + m.q2;
+            x = x >= q4 ? x - q4 : x;
+        }
         u64 r = mul_shoup_lazy(Y, t.w, t.wp, m.q);
         X = x + r;
         Y = x - r + m.q2;
@@ -131,7 +138,7 @@ struct IntAr {
         Y = mul_shoup_lazy(d, t.w, t.wp, m.q);
     }
     static HD T round_reduce(T v, const Mod&) { return v; }  // lazy ranges are invariants: nothing to do
-    static HD u64 canon_fwd(T v, const Mod& m) { return csub(csub(v, m.q2), m.q); }
+    static HD u64 canon_fwd(T v, const Mod& m) { return csub(csub(csub(v, m.q2 + m.q2), m.q2), m.q); }  // from [0, 8q)
     static HD u64 canon_inv(T v, const Mod& m) { return csub(v, m.q); }
     // last inverse stage with scaling, canonical results
     static HD void bfly_inv_last(T& X, T& Y, const InvScale& s, const Mod& m, bool, u64& ox, u64& oy) {
@@ -139,11 +146,11 @@ struct IntAr {
         ox = mul_shoup(a, s.sx, s.sx_p, m.q);
         oy = mul_shoup(d, s.sy, s.sy_p, m.q);
     }
-    // inner-product accumulation: acc holds sum of v*k*2^-64 in [0, 2q); v canonical or lazy < 2^64/q... (v < 4q)
+    // inner-product accumulation: acc holds sum of v*k*2^-64 in [0, 2q); v canonical or forward-lazy (any 64-bit word)
     static HD T acc_zero() { return 0; }
     static HD void acc_mac(T& acc, T v, u64 key, const Mod& m) {
         u128w p = {0, 0};
-        mac128(p, v, key);  // v < 4q < 2^63, key < q: v*key < q*2^64
+        mac128(p, v, key);  // v < 2^64, key < q: v*key < q*2^64
         u64 r = redc_lazy(p, m.q, m.qneg);
         u64 s = acc + r;
         acc = s >= m.q2 ? s - m.q2 : s;
@@ -214,6 +221,7 @@ struct FpAr {
     static HD T mul_canon(u64 a, u64 b, const PrimeConst&, const Mod& m) {
         return mulmod_lazy(u64_to_f64(a), u64_to_f64(b), m);  // |result| <= 0.875 q
     }
+    template <bool RED>  // the reduction schedule of the integer arithmetic does not apply: ranges are restored per round
     static HD void bfly_fwd(T& X, T& Y, const Tw& t, const Mod& m) {
         double r = mulmod_lazy(Y, t.w, m);
         double x = X;

@@ -48,7 +48,9 @@ struct NttCore {
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 if (k & d) continue;
-                AR::bfly_fwd(x[k], x[k + d], AR::tw(ti, tf, (1u << s) + (k >> (4 - s)), N, false), m);
+                // inputs are canonical: below 3q, 5q, 7q before stages 1, 2, 3, so only stage 3 reduces first
+                if (s == 3) AR::template bfly_fwd<true>(x[k], x[k + d], AR::tw(ti, tf, (1u << s) + (k >> (4 - s)), N, false), m);
+                else AR::template bfly_fwd<false>(x[k], x[k + d], AR::tw(ti, tf, (1u << s) + (k >> (4 - s)), N, false), m);
             }
         }
         if constexpr (A > 4) {
@@ -64,7 +66,9 @@ struct NttCore {
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
                     if (k & d) continue;
-                    AR::bfly_fwd(x[k], x[k + d], AR::tw(ti, tf, (1u << s) + ((r1 * 16 + k) >> (A - s)), N, false), m);
+                    // below 6q after stage 3: from here odd stages reduce, even stages run on inputs below 6q
+                    if (s & 1) AR::template bfly_fwd<true>(x[k], x[k + d], AR::tw(ti, tf, (1u << s) + ((r1 * 16 + k) >> (A - s)), N, false), m);
+                    else AR::template bfly_fwd<false>(x[k], x[k + d], AR::tw(ti, tf, (1u << s) + ((r1 * 16 + k) >> (A - s)), N, false), m);
                 }
             }
         }
@@ -79,7 +83,9 @@ struct NttCore {
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 if (k & d) continue;
-                AR::bfly_fwd(x[k], x[k + d], AR::tw(ti, tf, (1u << (A + u)) + (r << u) + (k >> (4 - u)), N, false), m);
+                // the strided pass leaves values below 8q: even stages reduce, odd stages run on inputs below 6q
+                if (u & 1) AR::template bfly_fwd<false>(x[k], x[k + d], AR::tw(ti, tf, (1u << (A + u)) + (r << u) + (k >> (4 - u)), N, false), m);
+                else AR::template bfly_fwd<true>(x[k], x[k + d], AR::tw(ti, tf, (1u << (A + u)) + (r << u) + (k >> (4 - u)), N, false), m);
             }
         }
 #pragma unroll
@@ -93,7 +99,9 @@ struct NttCore {
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 if (k & d) continue;
-                AR::bfly_fwd(x[k], x[k + d],
+                if (u & 1) AR::template bfly_fwd<false>(x[k], x[k + d],
+                             AR::tw(ti, tf, (1u << (A + u)) + (r << u) + ((e0 * 16 + k) >> (8 - u)), N, false), m);
+                else AR::template bfly_fwd<true>(x[k], x[k + d],
                              AR::tw(ti, tf, (1u << (A + u)) + (r << u) + ((e0 * 16 + k) >> (8 - u)), N, false), m);
             }
         }

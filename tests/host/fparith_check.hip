@@ -71,7 +71,7 @@ static int check_prime(u64 q, unsigned long long* count) {
             for (int k = 0; k < 16; k++) {
                 if (k & d) continue;
                 const FpAr::Tw tw = {(double)w[(1 << s) - 1 + (k >> (4 - s))]};
-                FpAr::bfly_fwd(x[k], x[k + d], tw, m);
+                FpAr::bfly_fwd<false>(x[k], x[k + d], tw, m);
                 const long long t = imod((i128)ref[k + d] * (i128)(u64)tw.w, (long long)q);
                 const long long X = ref[k];
                 ref[k] = imod((i128)X + t, (long long)q); ref[k + d] = imod((i128)X - t, (long long)q);
