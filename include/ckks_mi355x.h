@@ -28,7 +28,11 @@
  *     of unity modulo prime i; coefficient form is natural order.
  *   - all work is enqueued on `stream` (a hipStream_t passed as void*; NULL =
  *     the default stream) and is asynchronous; the caller synchronises.
- *   - input and output buffers must not overlap unless "in place" is stated.
+ *   - input and output buffers must not overlap unless "in place" is stated.  The calls that take a
+ *     workspace check this on the host and return CKKS_EINVAL, launching nothing, when an output shares
+ *     bytes with a ciphertext / plaintext input or when the workspace shares bytes with either (the
+ *     kernels re-read inputs after the first output words are written, so such a call would return
+ *     wrong words without any error); keys are read-only and are not part of that check.
  *   - the library allocates no device memory: tables and workspace are caller
  *     buffers sized by ckks_table_bytes / ckks_workspace_bytes, 256-byte aligned.
  *   - return value: CKKS_OK or a negative error code; nothing throws or aborts.

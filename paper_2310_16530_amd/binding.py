@@ -106,15 +106,51 @@ def _dev_ptr(t: torch.Tensor) -> int:
     return t.data_ptr()
 
 
+def check_operand(t: torch.Tensor, words: int, what: str, device: Optional[torch.device] = None) -> int:
+    """The C ABI takes raw pointers and cannot see buffer lengths, so every operand is checked here before any
+    launch: 64-bit elements, contiguous, exactly `words` of them, on `device`.  Returns the device pointer."""
+    if not isinstance(t, torch.Tensor) or t.element_size() != 8 or t.is_floating_point():
+        raise ValueError(f"{what}: expected a tensor of 64-bit integers")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: tensor is not contiguous")
+    if t.numel() != words:
+        raise ValueError(f"{what}: expected {words} words, got {t.numel()} (shape {tuple(t.shape)})")
+    if not t.is_cuda or (device is not None and t.device != device):
+        raise ValueError(f"{what}: tensor is on {t.device}, the context is on {device}")
+    return t.data_ptr()
+
+
+def check_batch(t: torch.Tensor, words_per_item: int, what: str) -> int:
+    """Number of items in t when each takes words_per_item words; rejects sizes that are no whole multiple."""
+    n = t.numel()
+    if words_per_item <= 0 or n == 0 or n % words_per_item:
+        raise ValueError(f"{what}: {n} words is not a positive multiple of {words_per_item}")
+    return n // words_per_item
+
+
+def check_chain(L: int, K: int, primes: Sequence[int], psi: Optional[Sequence[int]]) -> None:
+    """The library reads L + K primes (and roots) from the host arrays it is handed."""
+    if len(primes) != L + K:
+        raise ValueError(f"expected L + K = {L + K} primes, got {len(primes)}")
+    if psi is not None and len(psi) != L + K:
+        raise ValueError(f"expected L + K = {L + K} roots, got {len(psi)}")
+
+
 class Context:
-    """Owns the opaque ckks_ctx, its device tables and a workspace tensor (all allocated through torch)."""
+    """Owns the opaque ckks_ctx, its device tables and one workspace tensor per torch stream (all allocated
+    through torch).  Calls made under different current streams get different workspaces, so they may overlap;
+    calls on one stream share a workspace and are ordered by the stream.  Every tensor argument is checked for
+    dtype, contiguity, exact size and device before the library is called (ValueError, nothing launched)."""
 
     def __init__(self, logN: int, L: int, K: int, dnum: int, primes: Sequence[int],
                  psi: Optional[Sequence[int]] = None, device: str = "cuda:0"):
+        check_chain(L, K, primes, psi)
         lib = load()
         self.logN, self.L, self.K, self.dnum = logN, L, K, dnum
         self.N, self.D = 1 << logN, L + K
         self.device = torch.device(device)
+        if self.device.index is None:
+            self.device = torch.device(self.device.type, torch.cuda.current_device())
         nbytes = _sz()
         rc = lib.ckks_table_bytes(logN, L, K, dnum, ctypes.byref(nbytes))
         if rc:
@@ -130,7 +166,7 @@ class Context:
         if rc:
             raise CkksError(rc, "ckks_ctx_create failed")
         self.handle = handle
-        self._ws = None
+        self._ws = {}
 
     def __del__(self):
         h = getattr(self, "handle", None)
@@ -156,13 +192,46 @@ class Context:
         self._check(load().ckks_workspace_bytes_at(self.handle, op, level, batch_or_nrot, ctypes.byref(n)))
         return n.value
 
+    def _ws_for(self, need: int) -> torch.Tensor:
+        """Workspace of the current torch stream.  A tensor that is replaced by a larger one goes back to torch's
+        caching allocator, which hands it out again only in stream order of the stream it was allocated on -- the
+        same stream every earlier use of it was enqueued on."""
+        key = _stream()
+        ws = self._ws.get(key)
+        if ws is None or ws.numel() < need:
+            self._ws.pop(key, None)
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+            self._ws[key] = ws
+        return ws
+
     def workspace(self, op: int, batch_or_nrot: int, level: Optional[int] = None) -> torch.Tensor:
         need = (self.workspace_bytes(op, batch_or_nrot) if level is None
                 else self.workspace_bytes_at(op, level, batch_or_nrot))
-        if self._ws is None or self._ws.numel() < need:
-            self._ws = None
-            self._ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
-        return self._ws
+        return self._ws_for(need)
+
+    # -- operand checks --------------------------------------------------------------
+    def _level(self, level: Optional[int]) -> int:
+        ell = self.L if level is None else int(level)
+        if not 1 <= ell <= self.L:
+            raise ValueError(f"level must be between 1 and L = {self.L}")
+        return ell
+
+    def _op(self, t: torch.Tensor, words: int, what: str) -> int:
+        return check_operand(t, words, what, self.device)
+
+    def _key(self, k: torch.Tensor, what: str = "key") -> int:
+        """Switching keys are always laid out over the whole chain: [dnum][2][L+K][N], also below level L."""
+        return self._op(k, self.dnum * 2 * self.D * self.N, what)
+
+    def _keys(self, ks: Sequence[torch.Tensor], n: int, galois: Sequence[int]):
+        if len(ks) != n or len(galois) != n or n == 0:
+            raise ValueError("one Galois element and one key per rotation, at least one rotation")
+        g = (ctypes.c_uint32 * n)(*[int(x) for x in galois])
+        ptrs = (ctypes.c_void_p * n)(*[self._key(k, f"key {i}") for i, k in enumerate(ks)])
+        return g, ptrs
+
+    def _out(self, out: Optional[torch.Tensor], shape, like: torch.Tensor) -> torch.Tensor:
+        return torch.empty(tuple(shape), dtype=like.dtype, device=like.device) if out is None else out
 
     def set_overlap(self, on: bool) -> None:
         self._check(load().ckks_set_overlap(self.handle, 1 if on else 0))
@@ -187,196 +256,198 @@ class Context:
     # -- entry points (same names as the C ABI, minus the prefix) ----------------------
     def ntt(self, x: torch.Tensor, prime_first: int = 0, inverse: bool = False) -> torch.Tensor:
         """In place on x = [batch...][n_limbs][N]."""
+        if x.dim() < 2 or x.shape[-1] != self.N:
+            raise ValueError("x: expected [...][n_limbs][N]")
         n_limbs = x.shape[-2]
-        batch = x.numel() // (n_limbs * self.N)
+        if prime_first < 0 or prime_first + n_limbs > self.D:
+            raise ValueError("limb range exceeds the prime chain")
+        batch = check_batch(x, n_limbs * self.N, "x")
         f = load().ckks_intt if inverse else load().ckks_ntt
-        self._check(f(self.handle, _dev_ptr(x), prime_first, n_limbs, batch, _stream()))
+        self._check(f(self.handle, self._op(x, batch * n_limbs * self.N, "x"), prime_first, n_limbs, batch, _stream()))
         return x
 
     def intt(self, x: torch.Tensor, prime_first: int = 0) -> torch.Tensor:
         return self.ntt(x, prime_first, inverse=True)
 
-    def modup(self, x: torch.Tensor) -> torch.Tensor:
-        batch = x.numel() // (self.L * self.N)
-        out = torch.empty(tuple(x.shape[:-2]) + (self.dnum, self.D, self.N), dtype=x.dtype, device=x.device)
-        self._check(load().ckks_modup(self.handle, _dev_ptr(x), _dev_ptr(out), batch, _stream()))
+    def modup(self, x: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        batch = check_batch(x, self.L * self.N, "x")
+        out = self._out(out, tuple(x.shape[:-2]) + (self.dnum, self.D, self.N), x)
+        self._check(load().ckks_modup(self.handle, self._op(x, batch * self.L * self.N, "x"),
+                                      self._op(out, batch * self.dnum * self.D * self.N, "out"), batch, _stream()))
         return out
 
-    def moddown(self, x: torch.Tensor) -> torch.Tensor:
-        batch = x.numel() // (self.D * self.N)
-        out = torch.empty(tuple(x.shape[:-2]) + (self.L, self.N), dtype=x.dtype, device=x.device)
-        self._check(load().ckks_moddown(self.handle, _dev_ptr(x), _dev_ptr(out), batch, _stream()))
+    def moddown(self, x: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        batch = check_batch(x, self.D * self.N, "x")
+        out = self._out(out, tuple(x.shape[:-2]) + (self.L, self.N), x)
+        self._check(load().ckks_moddown(self.handle, self._op(x, batch * self.D * self.N, "x"),
+                                        self._op(out, batch * self.L * self.N, "out"), batch, _stream()))
         return out
 
-    def automorph(self, x: torch.Tensor, galois: int, eval_domain: bool, prime_first: int = 0) -> torch.Tensor:
+    def automorph(self, x: torch.Tensor, galois: int, eval_domain: bool, prime_first: int = 0,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if x.dim() < 2 or x.shape[-1] != self.N:
+            raise ValueError("x: expected [...][n_limbs][N]")
         n_limbs = x.shape[-2]
-        batch = x.numel() // (n_limbs * self.N)
-        out = torch.empty_like(x)
-        self._check(load().ckks_automorph(self.handle, _dev_ptr(x), _dev_ptr(out), prime_first, n_limbs, galois,
-                                          1 if eval_domain else 0, batch, _stream()))
+        batch = check_batch(x, n_limbs * self.N, "x")
+        out = self._out(out, x.shape, x)
+        self._check(load().ckks_automorph(self.handle, self._op(x, x.numel(), "x"), self._op(out, x.numel(), "out"),
+                                          prime_first, n_limbs, galois, 1 if eval_domain else 0, batch, _stream()))
         return out
 
     def pointwise(self, op: int, a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] = None,
                   prime_first: int = 0) -> torch.Tensor:
         """a (op) b limb by limb; a [..][n_limbs][N], b the same or fewer leading groups (applied cyclically).
         PW_MAC accumulates into `out`, which may be `a` or `b` for the other operations."""
+        if a.dim() < 2 or b.dim() < 2 or a.shape[-1] != self.N or b.shape[-1] != self.N:
+            raise ValueError("operands: expected [...][n_limbs][N]")
         n_limbs = a.shape[-2]
-        batch = a.numel() // (n_limbs * self.N)
-        b_period = b.numel() // (n_limbs * self.N)
+        batch = check_batch(a, n_limbs * self.N, "a")
+        b_period = check_batch(b, n_limbs * self.N, "b")
         if out is None:
             if op == PW_MAC:
                 raise ValueError("PW_MAC accumulates into out")
             out = torch.empty_like(a)
         if b.shape[-2] != n_limbs or out.shape != a.shape:
             raise ValueError("operand shapes do not match")
-        self._check(load().ckks_pointwise(self.handle, op, _dev_ptr(a), _dev_ptr(b), _dev_ptr(out), prime_first,
-                                          n_limbs, batch, b_period, _stream()))
+        self._check(load().ckks_pointwise(self.handle, op, self._op(a, a.numel(), "a"), self._op(b, b.numel(), "b"),
+                                          self._op(out, a.numel(), "out"), prime_first, n_limbs, batch, b_period,
+                                          _stream()))
         return out
 
-    def keyswitch(self, d: torch.Tensor, key: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        batch = d.numel() // (self.L * self.N)
-        if out is None:
-            out = torch.empty(tuple(d.shape[:-2]) + (2, self.L, self.N), dtype=d.dtype, device=d.device)
-        ws = self.workspace(OP_KEYSWITCH, batch)
-        self._check(load().ckks_keyswitch(self.handle, _dev_ptr(d), _dev_ptr(key), _dev_ptr(out), batch,
-                                          ws.data_ptr(), ws.numel(), _stream()))
+    def keyswitch(self, d: torch.Tensor, key: torch.Tensor, out: Optional[torch.Tensor] = None,
+                  level: Optional[int] = None) -> torch.Tensor:
+        ell = self._level(level)
+        batch = check_batch(d, ell * self.N, "d")
+        out = self._out(out, tuple(d.shape[:-2]) + (2, ell, self.N), d)
+        ws = self.workspace(OP_KEYSWITCH, batch, ell)
+        args = (self._op(d, batch * ell * self.N, "d"), self._key(key), self._op(out, batch * 2 * ell * self.N, "out"),
+                batch, ws.data_ptr(), ws.numel(), _stream())
+        lib = load()
+        self._check(lib.ckks_keyswitch(self.handle, *args) if level is None else lib.ckks_keyswitch_at(self.handle, ell, *args))
         return out
 
     def hmult_relin(self, ct1: torch.Tensor, ct2: torch.Tensor, evk: torch.Tensor,
-                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        batch = ct1.numel() // (2 * self.L * self.N)
-        if out is None:
-            out = torch.empty_like(ct1)
-        ws = self.workspace(OP_HMULT_RELIN, batch)
-        self._check(load().ckks_hmult_relin(self.handle, _dev_ptr(ct1), _dev_ptr(ct2), _dev_ptr(evk), _dev_ptr(out),
-                                            batch, ws.data_ptr(), ws.numel(), _stream()))
+                    out: Optional[torch.Tensor] = None, level: Optional[int] = None) -> torch.Tensor:
+        ell = self._level(level)
+        batch = check_batch(ct1, 2 * ell * self.N, "ct1")
+        words = batch * 2 * ell * self.N
+        out = self._out(out, ct1.shape, ct1)
+        ws = self.workspace(OP_HMULT_RELIN, batch, ell)
+        args = (self._op(ct1, words, "ct1"), self._op(ct2, words, "ct2"), self._key(evk, "evk"), self._op(out, words, "out"),
+                batch, ws.data_ptr(), ws.numel(), _stream())
+        lib = load()
+        self._check(lib.ckks_hmult_relin(self.handle, *args) if level is None
+                    else lib.ckks_hmult_relin_at(self.handle, ell, *args))
         return out
 
-    def hrot(self, ct: torch.Tensor, galois: int, rk: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        batch = ct.numel() // (2 * self.L * self.N)
-        if out is None:
-            out = torch.empty_like(ct)
-        ws = self.workspace(OP_HROT, batch)
-        self._check(load().ckks_hrot(self.handle, _dev_ptr(ct), galois, _dev_ptr(rk), _dev_ptr(out), batch,
-                                     ws.data_ptr(), ws.numel(), _stream()))
+    def hrot(self, ct: torch.Tensor, galois: int, rk: torch.Tensor, out: Optional[torch.Tensor] = None,
+             level: Optional[int] = None) -> torch.Tensor:
+        ell = self._level(level)
+        batch = check_batch(ct, 2 * ell * self.N, "ct")
+        words = batch * 2 * ell * self.N
+        out = self._out(out, ct.shape, ct)
+        ws = self.workspace(OP_HROT, batch, ell)
+        args = (self._op(ct, words, "ct"), galois, self._key(rk, "rk"), self._op(out, words, "out"), batch,
+                ws.data_ptr(), ws.numel(), _stream())
+        lib = load()
+        self._check(lib.ckks_hrot(self.handle, *args) if level is None else lib.ckks_hrot_at(self.handle, ell, *args))
         return out
 
     def hrot_hoisted_mac(self, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor],
-                         pt: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                         pt: torch.Tensor, out: Optional[torch.Tensor] = None,
+                         level: Optional[int] = None) -> torch.Tensor:
+        """ct [2][level][N], pt [n_rot][level][N]; out = sum_r pt_r * HRot_r(ct) with the decomposition hoisted."""
+        ell = self._level(level)
         n_rot = len(galois)
-        if len(rks) != n_rot or pt.numel() != n_rot * self.L * self.N:
-            raise ValueError("one key and one plaintext per rotation")
-        if out is None:
-            out = torch.empty_like(ct)
-        g = (ctypes.c_uint32 * n_rot)(*[int(x) for x in galois])
-        ptrs = (ctypes.c_void_p * n_rot)(*[_dev_ptr(k) for k in rks])
-        ws = self.workspace(OP_HROT_HOISTED_MAC, n_rot)
-        self._check(load().ckks_hrot_hoisted_mac(self.handle, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
-                                                 ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out),
-                                                 ws.data_ptr(), ws.numel(), _stream()))
+        g, ptrs = self._keys(rks, n_rot, galois)
+        words = 2 * ell * self.N
+        out = self._out(out, ct.shape, ct)
+        ws = self.workspace(OP_HROT_HOISTED_MAC, n_rot, ell)
+        args = (self._op(ct, words, "ct"), n_rot, ctypes.cast(g, _vp), ctypes.cast(ptrs, _vp),
+                self._op(pt, n_rot * ell * self.N, "pt"), self._op(out, words, "out"), ws.data_ptr(), ws.numel(), _stream())
+        lib = load()
+        self._check(lib.ckks_hrot_hoisted_mac(self.handle, *args) if level is None
+                    else lib.ckks_hrot_hoisted_mac_at(self.handle, ell, *args))
         return out
 
     # -- levels below L: tensors carry `level` limbs instead of L; keys stay full-level ----------
     def keyswitch_at(self, level: int, d: torch.Tensor, key: torch.Tensor,
                      out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        batch = d.numel() // (level * self.N)
-        if out is None:
-            out = torch.empty(tuple(d.shape[:-2]) + (2, level, self.N), dtype=d.dtype, device=d.device)
-        ws = self.workspace(OP_KEYSWITCH, batch, level)
-        self._check(load().ckks_keyswitch_at(self.handle, level, _dev_ptr(d), _dev_ptr(key), _dev_ptr(out), batch,
-                                             ws.data_ptr(), ws.numel(), _stream()))
-        return out
+        return self.keyswitch(d, key, out, level)
 
     def hmult_relin_at(self, level: int, ct1: torch.Tensor, ct2: torch.Tensor, evk: torch.Tensor,
                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        batch = ct1.numel() // (2 * level * self.N)
-        if out is None:
-            out = torch.empty_like(ct1)
-        ws = self.workspace(OP_HMULT_RELIN, batch, level)
-        self._check(load().ckks_hmult_relin_at(self.handle, level, _dev_ptr(ct1), _dev_ptr(ct2), _dev_ptr(evk),
-                                               _dev_ptr(out), batch, ws.data_ptr(), ws.numel(), _stream()))
-        return out
+        return self.hmult_relin(ct1, ct2, evk, out, level)
 
     def hrot_at(self, level: int, ct: torch.Tensor, galois: int, rk: torch.Tensor,
                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        batch = ct.numel() // (2 * level * self.N)
-        if out is None:
-            out = torch.empty_like(ct)
-        ws = self.workspace(OP_HROT, batch, level)
-        self._check(load().ckks_hrot_at(self.handle, level, _dev_ptr(ct), galois, _dev_ptr(rk), _dev_ptr(out), batch,
-                                        ws.data_ptr(), ws.numel(), _stream()))
-        return out
+        return self.hrot(ct, galois, rk, out, level)
 
     def hrot_hoisted_mac_at(self, level: int, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor],
                             pt: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        n_rot = len(galois)
-        if len(rks) != n_rot or pt.numel() != n_rot * level * self.N:
-            raise ValueError("one key and one plaintext per rotation")
-        if out is None:
-            out = torch.empty_like(ct)
-        g = (ctypes.c_uint32 * n_rot)(*[int(x) for x in galois])
-        ptrs = (ctypes.c_void_p * n_rot)(*[_dev_ptr(k) for k in rks])
-        ws = self.workspace(OP_HROT_HOISTED_MAC, n_rot, level)
-        self._check(load().ckks_hrot_hoisted_mac_at(self.handle, level, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
-                                                    ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out),
-                                                    ws.data_ptr(), ws.numel(), _stream()))
-        return out
+        return self.hrot_hoisted_mac(ct, galois, rks, pt, out, level)
 
     def rescale(self, level: int, ct: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         """ct [batch...][2][level][N] -> [batch...][2][level-1][N]."""
-        batch = ct.numel() // (2 * level * self.N)
-        if out is None:
-            out = torch.empty(tuple(ct.shape[:-2]) + (level - 1, self.N), dtype=ct.dtype, device=ct.device)
-        ws = self.workspace(OP_RESCALE, batch, level)
-        self._check(load().ckks_rescale(self.handle, level, _dev_ptr(ct), _dev_ptr(out), batch,
+        ell = self._level(level)
+        if ell < 2:
+            raise ValueError("rescale needs at least two limbs")
+        batch = check_batch(ct, 2 * ell * self.N, "ct")
+        out = self._out(out, tuple(ct.shape[:-2]) + (ell - 1, self.N), ct)
+        ws = self.workspace(OP_RESCALE, batch, ell)
+        self._check(load().ckks_rescale(self.handle, ell, self._op(ct, batch * 2 * ell * self.N, "ct"),
+                                        self._op(out, batch * 2 * (ell - 1) * self.N, "out"), batch,
                                         ws.data_ptr(), ws.numel(), _stream()))
         return out
 
     def hrot_dh_mac(self, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor], pt: torch.Tensor,
                     out: Optional[torch.Tensor] = None, level: Optional[int] = None) -> torch.Tensor:
         """Double-hoisted rotate-MAC; pt [n_rot][level+K][N] on the level's extended basis."""
-        ell = self.L if level is None else level
+        ell = self._level(level)
         n_rot = len(galois)
-        if len(rks) != n_rot or pt.numel() != n_rot * (ell + self.K) * self.N:
-            raise ValueError("one key and one extended-basis plaintext per rotation")
-        if out is None:
-            out = torch.empty_like(ct)
-        g = (ctypes.c_uint32 * n_rot)(*[int(x) for x in galois])
-        ptrs = (ctypes.c_void_p * n_rot)(*[_dev_ptr(k) for k in rks])
+        g, ptrs = self._keys(rks, n_rot, galois)
+        words = 2 * ell * self.N
+        out = self._out(out, ct.shape, ct)
         ws = self.workspace(OP_HROT_DH_MAC, n_rot, ell)
+        args = (self._op(ct, words, "ct"), n_rot, ctypes.cast(g, _vp), ctypes.cast(ptrs, _vp),
+                self._op(pt, n_rot * (ell + self.K) * self.N, "pt"), self._op(out, words, "out"),
+                ws.data_ptr(), ws.numel(), _stream())
         if level is None:
-            rc = load().ckks_hrot_dh_mac(self.handle, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp), ctypes.cast(ptrs, _vp),
-                                         _dev_ptr(pt), _dev_ptr(out), ws.data_ptr(), ws.numel(), _stream())
+            rc = load().ckks_hrot_dh_mac(self.handle, *args)
         else:
-            rc = load().ckks_hrot_dh_mac_at(self.handle, ell, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
-                                            ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out), ws.data_ptr(),
-                                            ws.numel(), _stream())
+            rc = load().ckks_hrot_dh_mac_at(self.handle, ell, *args)
         self._check(rc)
         return out
 
     # -- ModDown merged with the following rescale: outputs carry level - 1 limbs -----------------
     def hmult_relin_rescale_at(self, level: int, ct1: torch.Tensor, ct2: torch.Tensor, evk: torch.Tensor,
                                out: Optional[torch.Tensor] = None) -> torch.Tensor:
-        batch = ct1.numel() // (2 * level * self.N)
-        if out is None:
-            out = torch.empty(tuple(ct1.shape[:-2]) + (level - 1, self.N), dtype=ct1.dtype, device=ct1.device)
-        ws = self.workspace(OP_HMULT_RELIN, batch, level)
-        self._check(load().ckks_hmult_relin_rescale_at(self.handle, level, _dev_ptr(ct1), _dev_ptr(ct2), _dev_ptr(evk),
-                                                       _dev_ptr(out), batch, ws.data_ptr(), ws.numel(), _stream()))
+        ell = self._level(level)
+        if ell < 2:
+            raise ValueError("rescale needs at least two limbs")
+        batch = check_batch(ct1, 2 * ell * self.N, "ct1")
+        words = batch * 2 * ell * self.N
+        out = self._out(out, tuple(ct1.shape[:-2]) + (ell - 1, self.N), ct1)
+        ws = self.workspace(OP_HMULT_RELIN, batch, ell)
+        self._check(load().ckks_hmult_relin_rescale_at(self.handle, ell, self._op(ct1, words, "ct1"),
+                                                       self._op(ct2, words, "ct2"), self._key(evk, "evk"),
+                                                       self._op(out, batch * 2 * (ell - 1) * self.N, "out"), batch,
+                                                       ws.data_ptr(), ws.numel(), _stream()))
         return out
 
     def hrot_dh_mac_rescale_at(self, level: int, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor],
                                pt: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        ell = self._level(level)
+        if ell < 2:
+            raise ValueError("rescale needs at least two limbs")
         n_rot = len(galois)
-        if len(rks) != n_rot or pt.numel() != n_rot * (level + self.K) * self.N:
-            raise ValueError("one key and one extended-basis plaintext per rotation")
-        if out is None:
-            out = torch.empty((2, level - 1, self.N), dtype=ct.dtype, device=ct.device)
-        g = (ctypes.c_uint32 * n_rot)(*[int(x) for x in galois])
-        ptrs = (ctypes.c_void_p * n_rot)(*[_dev_ptr(k) for k in rks])
-        ws = self.workspace(OP_HROT_DH_MAC, n_rot, level)
-        self._check(load().ckks_hrot_dh_mac_rescale_at(self.handle, level, _dev_ptr(ct), n_rot, ctypes.cast(g, _vp),
-                                                       ctypes.cast(ptrs, _vp), _dev_ptr(pt), _dev_ptr(out),
+        g, ptrs = self._keys(rks, n_rot, galois)
+        out = self._out(out, (2, ell - 1, self.N), ct)
+        ws = self.workspace(OP_HROT_DH_MAC, n_rot, ell)
+        self._check(load().ckks_hrot_dh_mac_rescale_at(self.handle, ell, self._op(ct, 2 * ell * self.N, "ct"), n_rot,
+                                                       ctypes.cast(g, _vp), ctypes.cast(ptrs, _vp),
+                                                       self._op(pt, n_rot * (ell + self.K) * self.N, "pt"),
+                                                       self._op(out, 2 * (ell - 1) * self.N, "out"),
                                                        ws.data_ptr(), ws.numel(), _stream()))
         return out
 
@@ -384,37 +455,31 @@ class Context:
                          giant_galois: Sequence[int], giant_rks: Sequence[torch.Tensor], pt: torch.Tensor,
                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
         """pt [n2][n1][level+K][N]; out = sum_g HRot_g(sum_b pt[g][b] * HRot_b(ct)), baby steps double-hoisted."""
+        ell = self._level(level)
         n1, n2 = len(baby_galois), len(giant_galois)
-        if len(baby_rks) != n1 or len(giant_rks) != n2 or pt.numel() != n1 * n2 * (level + self.K) * self.N:
-            raise ValueError("one key per rotation and one extended-basis plaintext per (giant, baby) pair")
-        if out is None:
-            out = torch.empty_like(ct)
+        bg, bk = self._keys(baby_rks, n1, baby_galois)
+        gg, gk = self._keys(giant_rks, n2, giant_galois)
+        words = 2 * ell * self.N
+        out = self._out(out, ct.shape, ct)
         need = _sz()
-        self._check(load().ckks_lintrans_bsgs_workspace_bytes(self.handle, level, n1, n2, ctypes.byref(need)))
-        if self._ws is None or self._ws.numel() < need.value:
-            self._ws = None
-            self._ws = torch.empty(need.value, dtype=torch.uint8, device=self.device)
-        bg = (ctypes.c_uint32 * n1)(*[int(x) for x in baby_galois])
-        gg = (ctypes.c_uint32 * n2)(*[int(x) for x in giant_galois])
-        bk = (ctypes.c_void_p * n1)(*[_dev_ptr(k) for k in baby_rks])
-        gk = (ctypes.c_void_p * n2)(*[_dev_ptr(k) for k in giant_rks])
-        self._check(load().ckks_lintrans_bsgs_at(self.handle, level, _dev_ptr(ct), n1, ctypes.cast(bg, _vp),
+        self._check(load().ckks_lintrans_bsgs_workspace_bytes(self.handle, ell, n1, n2, ctypes.byref(need)))
+        ws = self._ws_for(need.value)
+        self._check(load().ckks_lintrans_bsgs_at(self.handle, ell, self._op(ct, words, "ct"), n1, ctypes.cast(bg, _vp),
                                                  ctypes.cast(bk, _vp), n2, ctypes.cast(gg, _vp), ctypes.cast(gk, _vp),
-                                                 _dev_ptr(pt), _dev_ptr(out), self._ws.data_ptr(), self._ws.numel(),
-                                                 _stream()))
+                                                 self._op(pt, n1 * n2 * (ell + self.K) * self.N, "pt"),
+                                                 self._op(out, words, "out"), ws.data_ptr(), ws.numel(), _stream()))
         return out
 
     def hrot_multi_at(self, level: int, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor],
                       out: Optional[torch.Tensor] = None) -> torch.Tensor:
         """ct [batch][2][level][N]; instance b is rotated by galois[b] with key rks[b]."""
+        ell = self._level(level)
         batch = len(galois)
-        if len(rks) != batch or ct.numel() != batch * 2 * level * self.N:
-            raise ValueError("one Galois element and one key per ciphertext")
-        if out is None:
-            out = torch.empty_like(ct)
-        g = (ctypes.c_uint32 * batch)(*[int(x) for x in galois])
-        ptrs = (ctypes.c_void_p * batch)(*[_dev_ptr(k) for k in rks])
-        ws = self.workspace(OP_HROT, min(batch, ROTATIONS_PER_LAUNCH), level)
-        self._check(load().ckks_hrot_multi_at(self.handle, level, _dev_ptr(ct), ctypes.cast(g, _vp), ctypes.cast(ptrs, _vp),
-                                              _dev_ptr(out), batch, ws.data_ptr(), ws.numel(), _stream()))
+        g, ptrs = self._keys(rks, batch, galois)
+        words = batch * 2 * ell * self.N
+        out = self._out(out, ct.shape, ct)
+        ws = self.workspace(OP_HROT, min(batch, ROTATIONS_PER_LAUNCH), ell)
+        self._check(load().ckks_hrot_multi_at(self.handle, ell, self._op(ct, words, "ct"), ctypes.cast(g, _vp),
+                                              ctypes.cast(ptrs, _vp), self._op(out, words, "out"), batch,
+                                              ws.data_ptr(), ws.numel(), _stream()))
         return out

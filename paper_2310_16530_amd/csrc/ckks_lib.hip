@@ -1237,6 +1237,25 @@ extern "C" int ckks_pointwise(ckks_ctx* ctx, int op, const uint64_t* d_a, const 
     return hip_check(c, "ckks_pointwise");
 }
 
+// [p, p + bytes) ranges that share at least one byte
+static inline bool ranges_overlap(const void* a, size_t a_bytes, const void* b, size_t b_bytes) {
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a && b && a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+// The kernels of a call read the inputs (permuted gathers, tensor terms, later chunks of rotations) after the
+// first words of the output have been written, so an output that shares memory with an input, or an output or
+// input that shares memory with the workspace, gives wrong words without any error: rejected here.
+static int check_no_alias(const View* c, const void* out, size_t out_bytes, const void* in1, size_t in1_bytes,
+                          const void* in2, size_t in2_bytes, const void* ws, size_t ws_bytes) {
+    if (ranges_overlap(out, out_bytes, in1, in1_bytes) || ranges_overlap(out, out_bytes, in2, in2_bytes))
+        return fail(c, CKKS_EINVAL, "output overlaps an input");
+    if (ranges_overlap(out, out_bytes, ws, ws_bytes) || ranges_overlap(in1, in1_bytes, ws, ws_bytes) ||
+        ranges_overlap(in2, in2_bytes, ws, ws_bytes))
+        return fail(c, CKKS_EINVAL, "workspace overlaps an operand");
+    return CKKS_OK;
+}
+static inline size_t limb_bytes(const View* c, size_t limbs) { return (limbs * sizeof(u64)) << c->logN; }
+
 static int check_ks_args(const View* c, const void* a, const void* b, const void* out, u32 batch, int op,
                          const void* ws, size_t ws_bytes) {
     if (!a || !b || !out || misaligned(a, 16) || misaligned(b, 16) || misaligned(out, 16))
@@ -1318,6 +1337,9 @@ extern "C" int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* 
     if (!c) return CKKS_EINVAL;
     int rc = check_ks_args(c, d_d, d_key, d_out, batch, CKKS_OP_KEYSWITCH, d_ws, ws_bytes);
     if (rc) return rc;
+    rc = check_no_alias(c, d_out, limb_bytes(c, (size_t)batch * 2 * c->L), d_d, limb_bytes(c, (size_t)batch * c->L), nullptr, 0,
+                        d_ws, ws_bytes);
+    if (rc) return rc;
     keyswitch_pipeline<INV_PLAIN, OWN_COPY, FIN_KS>(c, c, d_d, nullptr, d_key, d_out, batch, 1, d_ws, (hipStream_t)stream);
     return hip_check(c, "ckks_keyswitch");
 }
@@ -1330,6 +1352,9 @@ extern "C" int ckks_hmult_relin_at(ckks_ctx* ctx, uint32_t level, const uint64_t
     if (!c) return CKKS_EINVAL;
     if (!d_ct2 || misaligned(d_ct2, 16)) return fail(c, CKKS_EINVAL, "null or misaligned buffer");
     int rc = check_ks_args(c, d_ct1, d_evk, d_out, batch, CKKS_OP_HMULT_RELIN, d_ws, ws_bytes);
+    if (rc) return rc;
+    const size_t ctb = limb_bytes(c, (size_t)batch * 2 * c->L);
+    rc = check_no_alias(c, d_out, ctb, d_ct1, ctb, d_ct2, ctb, d_ws, ws_bytes);
     if (rc) return rc;
     keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT>(c, c, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
                                                           (hipStream_t)stream);
@@ -1346,6 +1371,9 @@ extern "C" int ckks_hmult_relin_rescale_at(ckks_ctx* ctx, uint32_t level, const 
     if (!d_ct2 || misaligned(d_ct2, 16)) return fail(c, CKKS_EINVAL, "null or misaligned buffer");
     int rc = check_ks_args(c, d_ct1, d_evk, d_out, batch, CKKS_OP_HMULT_RELIN, d_ws, ws_bytes);
     if (rc) return rc;
+    const size_t ctb = limb_bytes(c, (size_t)batch * 2 * c->L);
+    rc = check_no_alias(c, d_out, limb_bytes(c, (size_t)batch * 2 * (c->L - 1)), d_ct1, ctb, d_ct2, ctb, d_ws, ws_bytes);
+    if (rc) return rc;
     keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT_RS>(c, &ctx->merged[level], d_ct1, d_ct2, d_evk, d_out, batch, 1,
                                                              d_ws, (hipStream_t)stream);
     return hip_check(c, "ckks_hmult_relin_rescale");
@@ -1359,6 +1387,9 @@ extern "C" int ckks_hrot_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct,
     int rc = check_ks_args(c, d_ct, d_rk, d_out, batch, CKKS_OP_HROT, d_ws, ws_bytes);
     if (rc) return rc;
     rc = check_galois(c, galois);
+    if (rc) return rc;
+    const size_t ctb = limb_bytes(c, (size_t)batch * 2 * c->L);
+    rc = check_no_alias(c, d_out, ctb, d_ct, ctb, nullptr, 0, d_ws, ws_bytes);
     if (rc) return rc;
     keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, c, d_ct, nullptr, d_rk, d_out, batch, galois, d_ws,
                                                    (hipStream_t)stream);
@@ -1386,8 +1417,8 @@ extern "C" int ckks_hrot(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t galois, c
 // Rescale = a ModDown whose only special prime is the last active limb: inverse transform of that
 // limb, reduction modulo every remaining prime fused into their first forward pass, second forward
 // pass fused with (c_i - .) * q_last^-1.
-extern "C" int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch,
-                            void* d_ws, size_t ws_bytes, void* stream) {
+static int rescale_impl(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch,
+                        void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx) return CKKS_EINVAL;
     if (level < 2 || level > ctx->L) return fail(ctx, CKKS_EINVAL, "rescale needs a level between 2 and L");
     const View* c = &ctx->rescale[level];  // c->L = level - 1 targets, c->K = 1
@@ -1396,7 +1427,11 @@ extern "C" int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct,
     if (batch == 0 || batch > 4096) return fail(c, CKKS_EINVAL, "batch out of range");
     if (!d_ws || misaligned(d_ws, 256)) return fail(c, CKKS_EINVAL, "workspace is null or not 256-byte aligned");
     const size_t N = (size_t)1 << c->logN;
-    if (ws_bytes < (size_t)batch * 2 * level * N * sizeof(u64)) return fail(c, CKKS_ENOMEM, "workspace too small");
+    if (ws_bytes < (size_t)batch * 2 * level * N * sizeof(u64))
+        return fail(c, CKKS_ENOMEM, "workspace too small");
+    int rc = check_no_alias(c, d_out, limb_bytes(c, (size_t)batch * 2 * (level - 1)), d_ct, limb_bytes(c, (size_t)batch * 2 * level),
+                            nullptr, 0, d_ws, ws_bytes);
+    if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     Workspace w;
     w.x = w.dt = w.cq = nullptr;
@@ -1412,6 +1447,11 @@ extern "C" int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct,
     fa.cq = d_ct, fa.cq_L = level, fa.in_L = c->L, fa.cv = w.cv, fa.out = d_out, fa.n_inst = batch;
     launch_ks_final<FIN_KS>(c, fa, s);
     return hip_check(c, "ckks_rescale");
+}
+
+extern "C" int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch,
+                            void* d_ws, size_t ws_bytes, void* stream) {
+    return rescale_impl(ctx, level, d_ct, d_out, batch, d_ws, ws_bytes, stream);
 }
 
 extern "C" int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
@@ -1434,6 +1474,9 @@ extern "C" int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uin
         rc = check_galois(c, h_galois[r]);
         if (rc) return rc;
     }
+    rc = check_no_alias(c, d_out, limb_bytes(c, 2 * (size_t)c->L), d_ct, limb_bytes(c, 2 * (size_t)c->L), d_pt,
+                        limb_bytes(c, (size_t)n_rot * c->L), d_ws, ws_bytes);
+    if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     const size_t N = (size_t)1 << c->logN;
     const u32 chunk_max = n_rot < CKKS_ROT_CHUNK ? n_rot : CKKS_ROT_CHUNK;
@@ -1507,6 +1550,9 @@ static int dh_mac_impl(ckks_ctx* ctx, uint32_t level, bool rescale, const uint64
         rc = check_galois(c, h_galois[r]);
         if (rc) return rc;
     }
+    rc = check_no_alias(c, d_out, limb_bytes(c, 2 * (size_t)(rescale ? c->L - 1 : c->L)), d_ct, limb_bytes(c, 2 * (size_t)c->L),
+                        d_pt, limb_bytes(c, (size_t)n_rot * c->D), d_ws, ws_bytes);
+    if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     const size_t N = (size_t)1 << c->logN;
     // cm: the view whose ModDown ends the call (the merged one also divides by the last q-limb)
@@ -1615,6 +1661,9 @@ extern "C" int ckks_lintrans_bsgs_at(ckks_ctx* ctx, uint32_t level, const uint64
         rc = check_galois(c, r < n1 ? h_baby_galois[r] : h_giant_galois[r - n1]);
         if (rc) return rc;
     }
+    rc = check_no_alias(c, d_out, limb_bytes(c, 2 * (size_t)c->L), d_ct, limb_bytes(c, 2 * (size_t)c->L), d_pt,
+                        limb_bytes(c, (size_t)n1 * n2 * c->D), d_ws, ws_bytes);
+    if (rc) return rc;
     hipStream_t s = (hipStream_t)stream;
     const size_t N = (size_t)1 << c->logN, LN = (size_t)c->L * N, KN = (size_t)c->K * N;
     // workspace: x | dt | Rq | Rp | Cq | Cp | Cv | inner | rot | key-switch workspace of the giant rotations
@@ -1699,6 +1748,8 @@ extern "C" int ckks_hrot_multi_at(ckks_ctx* ctx, uint32_t level, const uint64_t*
         if (rc) return rc;
     }
     const size_t ct_words = ((size_t)2 * c->L) << c->logN;
+    rc = check_no_alias(c, d_out, ct_words * batch * sizeof(u64), d_ct, ct_words * batch * sizeof(u64), nullptr, 0, d_ws, ws_bytes);
+    if (rc) return rc;
     for (u32 b0 = 0; b0 < batch; b0 += CKKS_ROT_CHUNK) {
         const u32 nb = (batch - b0) < CKKS_ROT_CHUNK ? (batch - b0) : CKKS_ROT_CHUNK;
         keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, c, d_ct + b0 * ct_words, nullptr, nullptr, d_out + b0 * ct_words, nb,

@@ -107,3 +107,36 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_binding_operand_checks_reject_before_any_launch():
+    """The binding checks what the C ABI cannot see (buffer lengths, dtype, layout, device); the checks run on
+    the host, so CPU tensors exercise every branch: a wrong size is reported before the device is looked at."""
+    import torch
+    from paper_2310_16530_amd import binding
+    N, L, K, dnum = 4096, 3, 1, 3
+    good = torch.zeros((2, L, N), dtype=torch.int64)
+    with pytest.raises(ValueError, match="64-bit"):
+        binding.check_operand(torch.zeros(8, dtype=torch.int32), 8, "x")
+    with pytest.raises(ValueError, match="64-bit"):
+        binding.check_operand(torch.zeros(8, dtype=torch.float64), 8, "x")
+    with pytest.raises(ValueError, match="contiguous"):
+        binding.check_operand(good.transpose(0, 1), good.numel(), "ct")
+    with pytest.raises(ValueError, match="expected"):
+        binding.check_operand(good, good.numel() - N, "ct")            # one limb short
+    with pytest.raises(ValueError, match="expected"):
+        binding.check_operand(torch.zeros((dnum, 2, L, N), dtype=torch.int64), dnum * 2 * (L + K) * N, "key")  # key without special limbs
+    with pytest.raises(ValueError, match="is on cpu"):
+        binding.check_operand(good, good.numel(), "ct", torch.device("cuda:0"))   # right size, wrong device
+    assert binding.check_batch(good, L * N, "x") == 2
+    with pytest.raises(ValueError, match="multiple"):
+        binding.check_batch(good, 4 * N, "x")
+    with pytest.raises(ValueError, match="multiple"):
+        binding.check_batch(torch.zeros(0, dtype=torch.int64), N, "x")
+    with pytest.raises(ValueError, match="primes"):
+        binding.check_chain(3, 1, synth.CFG0.primes[:3], None)
+    with pytest.raises(ValueError, match="roots"):
+        binding.check_chain(3, 1, synth.CFG0.primes, [1, 2, 3])
+    with pytest.raises(ValueError, match="primes"):
+        binding.Context(12, 3, 1, 3, synth.CFG0.primes[:3])          # rejected before the library is touched
+    binding.check_chain(3, 1, synth.CFG0.primes, None)

@@ -139,7 +139,7 @@ def test_config2_shape_at_a_partial_level_full_size(orc):
     _say("cfg2 level 13: hmult")
     hm_d = ctx.hmult_relin_at(ell, dev(ct1), dev(ct2), d_evk)
     hm = host(hm_d)
-    for b in (0, B - 1):
+    for b in range(B):
         assert np.array_equal(hm[b], orc.hmult_relin_level(ct1[b], ct2[b], evk, P)), b
     _say("cfg2 level 13: rescale")
     rs = host(ctx.rescale(ell, hm_d))
@@ -147,7 +147,8 @@ def test_config2_shape_at_a_partial_level_full_size(orc):
     _say("cfg2 level 13: hrot")
     g = synth.galois_element(5, ps.logN)
     hr = host(ctx.hrot_at(ell, dev(ct1), g, d_evk))
-    assert np.array_equal(hr[3], orc.hrot_level(ct1[3], g, evk, P))
+    for b in range(B):
+        assert np.array_equal(hr[b], orc.hrot_level(ct1[b], g, evk, P)), b
 
 
 def test_level_error_paths(orc):
@@ -276,7 +277,7 @@ def test_config2_shape_merged_rescale_full_size(orc):
     B = synth.CFG2_BATCH
     evk = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
     d_evk = dev(evk)
-    for ell, check in ((24, (0, 5)), (13, (7,))):
+    for ell, check in ((24, range(B)), (13, range(B))):
         q = ps.q_primes[:ell]
         ct1 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))
         ct2 = synth.uniform_residues(rng, q, ps.N, lead=(B, 2))

@@ -27,6 +27,11 @@ def host(t):
     return t.cpu().numpy().view(np.uint64)
 
 
+def say(*a):
+    """progress line, flushed: names the case before each long step"""
+    print(*a, flush=True)
+
+
 _CTX = {}
 
 
@@ -302,8 +307,8 @@ def test_config0_hmult_exact_shape(orc):
 
 @pytest.mark.timeout(900)
 def test_config2_hmult_batch8_full_size(orc):
-    """workload 2 in the benchmark's launch configuration (batch 8, shared evk).  The oracle
-    recomputes two of the eight products in full; all eight are checked by decrypt-and-bound."""
+    """workload 2 in the benchmark's launch configuration (batch 8, shared evk): all eight products are
+    compared with the oracle word for word and checked by decrypt-and-bound."""
     ps = synth.CFG2
     ctx, P = gpu_ctx(ps), orc_params(orc, ps)
     rng = synth.rng_for(2, 0)
@@ -315,7 +320,8 @@ def test_config2_hmult_batch8_full_size(orc):
     ct1 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
     ct2 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
     got = host(ctx.hmult_relin(dev(ct1), dev(ct2), dev(evk)))
-    for b in (0, B - 1):
+    for b in range(B):
+        say("cfg2 hmult: oracle pair", b)
         assert np.array_equal(got[b], orc.hmult_relin(ct1[b], ct2[b], evk, P)), b
     q = ps.q_primes
     sq = s_hat[:ps.L]
@@ -341,11 +347,13 @@ def test_config2_hrot_and_keyswitch_full_size(orc):
     ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2))
     g = synth.galois_element(1, ps.logN)
     got = host(ctx.hrot(dev(ct), g, dev(rk)))
-    for b in (1, B - 2):
+    for b in range(B):
+        say("cfg2 hrot: oracle ciphertext", b)
         assert np.array_equal(got[b], orc.hrot(ct[b], g, rk, P)), b
     d = np.ascontiguousarray(ct[:2, 1])
     ks = host(ctx.keyswitch(dev(d), dev(rk)))
-    assert np.array_equal(ks[1], orc.keyswitch(d[1], rk, P))
+    for b in range(2):
+        assert np.array_equal(ks[b], orc.keyswitch(d[b], rk, P)), b
 
 
 @pytest.mark.timeout(900)
@@ -366,9 +374,10 @@ def test_config3_rotate_and_sum_full_size(orc):
 
 @pytest.mark.timeout(900)
 def test_config4_coeff_to_slot_shape_full_size(orc):
-    """workload 4: L=35, K=7, dnum=5, 32 rotations +-2^i.  The oracle recomputes a 5-rotation
-    subset in full (including the identity element g = 1 from +-2^15); the 32-rotation call is then
-    checked by linearity: it must equal the sum of four 8-rotation calls."""
+    """workload 4: L=35, K=7, dnum=5, 32 rotations +-2^i (the identity element g = 1 from +-2^15 included):
+    the 32-rotation call (two launches' worth of rotations) is compared with the oracle word for word.
+    Extra, not the parity evidence: a sub-list gives the oracle's result too, and the call is linear in
+    the rotation list."""
     ps = synth.CFG4
     ctx, P = gpu_ctx(ps), orc_params(orc, ps)
     rng = synth.rng_for(4, 0)
@@ -380,6 +389,8 @@ def test_config4_coeff_to_slot_shape_full_size(orc):
     pt = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(32,))
     d_pt = dev(pt)
     full = host(ctx.hrot_hoisted_mac(d_ct, gs, rks, d_pt))
+    say("cfg4: oracle, 32 rotations")
+    assert np.array_equal(full, orc.hrot_hoisted_mac(ct, gs, [host(k) for k in rks], pt, P))
     sub = [0, 1, 29, 30, 31]
     want = orc.hrot_hoisted_mac(ct, [gs[i] for i in sub], [host(rks[i]) for i in sub], np.ascontiguousarray(pt[sub]), P)
     got_sub = host(ctx.hrot_hoisted_mac(d_ct, [gs[i] for i in sub], [rks[i] for i in sub], dev(np.ascontiguousarray(pt[sub]))))
@@ -390,6 +401,22 @@ def test_config4_coeff_to_slot_shape_full_size(orc):
         for t in range(2):
             acc[t] = orc.pointwise("add", acc[t], part[t], ps.q_primes)
     assert np.array_equal(full, acc)
+
+
+@pytest.mark.timeout(900)
+def test_config4_double_hoisted_full_size(orc):
+    """workload 4's shape through the double-hoisted call: all 32 rotations against the oracle, word for word."""
+    ps = synth.CFG4
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = synth.rng_for(4, 3)
+    gs = [synth.galois_element(r, ps.logN) for r in synth.CFG4_ROTATIONS]
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    pt = synth.uniform_residues(rng, ps.primes, ps.N, lead=(32,))
+    say("cfg4 double hoisting: gpu")
+    got = host(ctx.hrot_dh_mac(dev(ct), gs, [dev(k) for k in rks], dev(pt)))
+    say("cfg4 double hoisting: oracle")
+    assert np.array_equal(got, orc.hrot_dh_mac_level(ct, gs, rks, pt, P))
 
 
 # ------------------------------------------------------------ error paths on a live context
@@ -417,6 +444,36 @@ def test_error_paths_return_codes_without_launching(orc):
     assert lib.ckks_hrot(h, p, 5, key.data_ptr(), out.data_ptr(), 1, ws.data_ptr(), 1024, None) == binding.CKKS_ENOMEM
     assert lib.ckks_hrot(h, p, 5, key.data_ptr(), out.data_ptr(), 1, None, 1 << 40, None) == binding.CKKS_EINVAL
     assert lib.ckks_hrot(h, p, 5, key.data_ptr(), out.data_ptr(), 0, ws.data_ptr(), ws.numel(), None) == binding.CKKS_EINVAL
+    # outputs that share memory with an input, or a workspace that shares memory with an operand, are rejected
+    ct = torch.zeros((2, 2, ps.L, ps.N), dtype=torch.int64, device="cuda:0")
+    c0, c1, k, w, wn = ct[0].data_ptr(), ct[1].data_ptr(), key.data_ptr(), ws.data_ptr(), ws.numel()
+    limb = ps.N * 8
+    assert lib.ckks_hrot(h, c0, 5, k, c0, 1, w, wn, None) == binding.CKKS_EINVAL
+    assert b"overlaps" in lib.ckks_last_error(h)
+    assert lib.ckks_hrot(h, c0, 5, k, c0 + limb, 1, w, wn, None) == binding.CKKS_EINVAL           # partial overlap
+    assert lib.ckks_hrot(h, c0, 5, k, c1, 1, w, wn, None) == binding.CKKS_OK                      # adjacent is fine
+    assert lib.ckks_hmult_relin(h, c0, c1, k, c1, 1, w, wn, None) == binding.CKKS_EINVAL          # out is ct2
+    assert lib.ckks_hmult_relin(h, c0, c1, k, c0, 1, w, wn, None) == binding.CKKS_EINVAL          # out is ct1
+    assert lib.ckks_keyswitch(h, c0, k, c0, 1, w, wn, None) == binding.CKKS_EINVAL
+    assert lib.ckks_hrot(h, w, 5, k, c1, 1, w, wn, None) == binding.CKKS_EINVAL                   # input inside the workspace
+    assert lib.ckks_rescale(h, ps.L, c0, c0, 1, w, wn, None) == binding.CKKS_EINVAL
+    gal = (ctypes.c_uint32 * 1)(5)
+    kp = (ctypes.c_void_p * 1)(k)
+    ptx = torch.zeros((1, ps.L + ps.K, ps.N), dtype=torch.int64, device="cuda:0")
+    assert lib.ckks_hrot_hoisted_mac(h, c0, 1, gal, kp, ptx.data_ptr(), c0, w, wn, None) == binding.CKKS_EINVAL
+    assert lib.ckks_hrot_hoisted_mac(h, c0, 1, gal, kp, c1, c1, w, wn, None) == binding.CKKS_EINVAL   # out is the plaintext
+    assert lib.ckks_hrot_dh_mac(h, c0, 1, gal, kp, ptx.data_ptr(), c0, w, wn, None) == binding.CKKS_EINVAL
+    assert lib.ckks_hrot_multi_at(h, ps.L, c0, gal, kp, c0, 1, w, wn, None) == binding.CKKS_EINVAL
+    # the binding checks sizes the C ABI cannot see: a key without its special limbs, a short output
+    short_key = torch.zeros((ps.dnum, 2, ps.L, ps.N), dtype=torch.int64, device="cuda:0")
+    with pytest.raises(ValueError, match="rk: expected"):
+        ctx.hrot(ct[0], 5, short_key)
+    with pytest.raises(ValueError, match="out"):
+        ctx.hrot(ct[0], 5, key, out=torch.zeros((2, ps.L - 1, ps.N), dtype=torch.int64, device="cuda:0"))
+    with pytest.raises(ValueError, match="ct2"):
+        ctx.hmult_relin(ct[0], ct[1][:1], key)
+    with pytest.raises(ValueError, match="level"):
+        ctx.hrot(ct[0], 5, key, level=ps.L + 1)
     o = out.data_ptr()
     assert lib.ckks_pointwise(h, 4, p, p, o, 0, 1, 1, 1, None) == binding.CKKS_EINVAL                # unknown op
     assert lib.ckks_pointwise(h, -1, p, p, o, 0, 1, 1, 1, None) == binding.CKKS_EINVAL

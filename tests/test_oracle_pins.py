@@ -91,6 +91,47 @@ def test_prime_chains_match_golden():
             assert P > Qj
 
 
+def test_n16_chains_against_an_independent_primality_test():
+    """The N = 2^16 chains are 'the smallest primes above 2^49 / 2^59 congruent to 1 mod 2^17': every member is
+    prime and every smaller candidate of that form is composite, by sympy's primality test (not the generator's
+    own Miller-Rabin, which also wrote the golden file)."""
+    sympy = pytest.importorskip("sympy")
+    step = 1 << 17
+    for chain, floor in ((synth.CFG4.q_primes, 1 << 49), (synth.CFG4.p_primes, 1 << 59)):
+        chain = [int(p) for p in chain]
+        assert chain == sorted(chain) and len(set(chain)) == len(chain)
+        members = set(chain)
+        c = floor + 1
+        while c <= chain[-1]:
+            assert sympy.isprime(c) == (c in members), c
+            c += step
+    for p in synth.CFG0.primes:
+        assert sympy.isprime(int(p))
+
+
+def test_ntt_batch_maps_row_to_prime_and_matches_the_definition(orc):
+    """Batched transform, batch 3 x 5 limbs (limb l of every polynomial uses prime l of the chain): every row
+    against the big-integer definition, both directions."""
+    logn, n = 5, 32
+    ps = synth.small_params(logn, 3, 2, 3, 30, 31)
+    P = orc.Params.from_set(ps)
+    rng = np.random.default_rng(77)
+    x = synth.uniform_residues(rng, ps.primes, n, lead=(3,))
+    assert x.shape == (3, 5, n)
+    fwd = orc.ntt_batch(x, P, 0)
+    inv = orc.ntt_batch(fwd, P, 0, inverse=True)
+    assert np.array_equal(inv, x)
+    for b in range(3):
+        for l in range(5):
+            m, psi = int(ps.primes[l]), int(P.psi[l])
+            row = [int(v) for v in x[b, l]]
+            want = [sum(row[t] * pow(psi, t * (2 * brev(j, logn) + 1), m) for t in range(n)) % m for j in range(n)]
+            assert fwd[b, l].tolist() == want, (b, l)
+    # a sub-range of the chain: limbs 2..4 with prime_first = 2
+    sub = np.ascontiguousarray(x[:, 2:5])
+    assert np.array_equal(orc.ntt_batch(sub, P, 2), fwd[:, 2:5])
+
+
 def test_min_psi_matches_golden_and_is_minimal(orc):
     for line in open(os.path.join(GOLD, "min_psi.txt")):
         if line.startswith("#") or not line.strip():
