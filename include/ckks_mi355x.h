@@ -84,6 +84,7 @@ extern "C" {
 #define CKKS_MAX_PRIMES 128 /* L + K */
 #define CKKS_MAX_DIGIT 16  /* alpha and K */
 #define CKKS_MAX_PRIME_BITS 61
+#define CKKS_STATIC_SCRATCH_BYTES (32u << 20) /* per-GPU scratch of ckks_rescale_static */
 #define CKKS_ROTATIONS_PER_LAUNCH 16 /* instances with their own key that one launch takes (chunking of rotation batches) */
 
 typedef struct ckks_ctx ckks_ctx;
@@ -258,6 +259,22 @@ int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct
  */
 int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch, void* d_ws,
                  size_t ws_bytes, void* stream);
+
+/*
+ * ckks_rescale for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same operands, same result words as
+ * ckks_rescale; the workspace is a static device array inside the library, CKKS_STATIC_SCRATCH_BYTES
+ * (32 MiB) on every GPU the library is loaded on, held until the process ends.  The call allocates nothing
+ * (no hipMalloc / hipFree, no allocating library routine) and only launches kernels.
+ *   Limit: batch * 2 * level * N * 8 bytes <= CKKS_STATIC_SCRATCH_BYTES (N = 2^16: batch * level <= 32, e.g. one
+ *   ciphertext at level 32, two at level 16); larger requests return CKKS_ENOMEM and launch nothing.
+ *   The device current at the call must be the one the context was created on (else CKKS_EINVAL).
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different streams,
+ *   different contexts, different threads) race on it and must be ordered by the caller.  Nothing needs
+ *   clearing between calls: every scratch word a call reads it has written first.
+ */
+int ckks_rescale_static(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch,
+                        void* stream);
 
 /*
  * Double-hoisted rotate-multiply-accumulate (the linear-transform evaluation of the bootstrapping

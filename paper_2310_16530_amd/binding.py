@@ -31,7 +31,9 @@ EXPORTS = (
     "ckks_hrot_hoisted_mac_at", "ckks_rescale", "ckks_hrot_dh_mac", "ckks_hrot_dh_mac_at",
     "ckks_hmult_relin_rescale_at", "ckks_hrot_dh_mac_rescale_at",
     "ckks_lintrans_bsgs_workspace_bytes", "ckks_lintrans_bsgs_at", "ckks_hrot_multi_at", "ckks_pointwise",
+    "ckks_rescale_static",
 )
+STATIC_SCRATCH_BYTES = 32 << 20
 
 _u32, _u64, _int, _sz, _vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_int, ctypes.c_size_t, ctypes.c_void_p
 _lib = None
@@ -77,6 +79,7 @@ def load() -> ctypes.CDLL:
     lib.ckks_hrot_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
     lib.ckks_hrot_hoisted_mac_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_rescale.argtypes = [_vp, _u32, _vp, _vp, _u32, _vp, _sz, _vp]
+    lib.ckks_rescale_static.argtypes = [_vp, _u32, _vp, _vp, _u32, _vp]
     lib.ckks_hrot_dh_mac.argtypes = [_vp, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_hrot_dh_mac_at.argtypes = [_vp, _u32, _vp, _u32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     lib.ckks_hmult_relin_rescale_at.argtypes = [_vp, _u32, _vp, _vp, _vp, _vp, _u32, _vp, _sz, _vp]
@@ -398,6 +401,16 @@ class Context:
         self._check(load().ckks_rescale(self.handle, ell, self._op(ct, batch * 2 * ell * self.N, "ct"),
                                         self._op(out, batch * 2 * (ell - 1) * self.N, "out"), batch,
                                         ws.data_ptr(), ws.numel(), _stream()))
+        return out
+
+    def rescale_static(self, level: int, ct: torch.Tensor, out: torch.Tensor) -> torch.Tensor:
+        """ckks_rescale with the library's static scratch as workspace; the caller brings `out` (nothing is allocated)."""
+        ell = self._level(level)
+        if ell < 2:
+            raise ValueError("rescale needs at least two limbs")
+        batch = check_batch(ct, 2 * ell * self.N, "ct")
+        self._check(load().ckks_rescale_static(self.handle, ell, self._op(ct, batch * 2 * ell * self.N, "ct"),
+                                               self._op(out, batch * 2 * (ell - 1) * self.N, "out"), batch, _stream()))
         return out
 
     def hrot_dh_mac(self, ct: torch.Tensor, galois: Sequence[int], rks: Sequence[torch.Tensor], pt: torch.Tensor,

@@ -233,7 +233,15 @@ struct View {
     Shared* sh = nullptr;
 };
 
+// Scratch memory of ckks_rescale_static, the entry point for callers that cannot allocate or bring a
+// workspace: one array per GPU, held from the moment the code object is loaded on that GPU until the process
+// ends.  In host code the name `scratch` is only a handle for hipGetSymbolAddress: the address a kernel may
+// use is looked up once per device (at context creation, with that device current) and kept in the context.
+static __device__ __align__(256) unsigned char scratch[CKKS_STATIC_SCRATCH_BYTES];
+
 struct ckks_ctx {
+    int device = -1;               // the device that was current at creation: tables and scratch live there
+    void* scratch_ptr = nullptr;   // device address of `scratch` on that device
     u32 logN, L, K, dnum, alpha, D;
     std::vector<u64> primes, psi;
     std::vector<View> level;    // [ell], 1 <= ell <= L: key switching at ell active q-limbs; level[L] is the full one
@@ -638,7 +646,11 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipMemcpyAsync(d_tables, host.data(), total, hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
-    if (e != hipSuccess) {
+    // this device's copy of the static scratch array (every GPU has its own, at its own address)
+    if (e == hipSuccess) e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipGetSymbolAddress(&c->scratch_ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !c->scratch_ptr) {
+        (void)hipGetLastError();
         delete c;
         return CKKS_EHIP;
     }
@@ -1418,7 +1430,7 @@ extern "C" int ckks_hrot(ckks_ctx* ctx, const uint64_t* d_ct, uint32_t galois, c
 // limb, reduction modulo every remaining prime fused into their first forward pass, second forward
 // pass fused with (c_i - .) * q_last^-1.
 static int rescale_impl(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch,
-                        void* d_ws, size_t ws_bytes, void* stream) {
+                        void* d_ws, size_t ws_bytes, void* stream, bool static_scratch) {
     if (!ctx) return CKKS_EINVAL;
     if (level < 2 || level > ctx->L) return fail(ctx, CKKS_EINVAL, "rescale needs a level between 2 and L");
     const View* c = &ctx->rescale[level];  // c->L = level - 1 targets, c->K = 1
@@ -1428,7 +1440,8 @@ static int rescale_impl(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uin
     if (!d_ws || misaligned(d_ws, 256)) return fail(c, CKKS_EINVAL, "workspace is null or not 256-byte aligned");
     const size_t N = (size_t)1 << c->logN;
     if (ws_bytes < (size_t)batch * 2 * level * N * sizeof(u64))
-        return fail(c, CKKS_ENOMEM, "workspace too small");
+        return fail(c, CKKS_ENOMEM, static_scratch ? "batch * 2 * level * N words exceed CKKS_STATIC_SCRATCH_BYTES"
+                                                   : "workspace too small");
     int rc = check_no_alias(c, d_out, limb_bytes(c, (size_t)batch * 2 * (level - 1)), d_ct, limb_bytes(c, (size_t)batch * 2 * level),
                             nullptr, 0, d_ws, ws_bytes);
     if (rc) return rc;
@@ -1451,7 +1464,19 @@ static int rescale_impl(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uin
 
 extern "C" int ckks_rescale(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch,
                             void* d_ws, size_t ws_bytes, void* stream) {
-    return rescale_impl(ctx, level, d_ct, d_out, batch, d_ws, ws_bytes, stream);
+    return rescale_impl(ctx, level, d_ct, d_out, batch, d_ws, ws_bytes, stream, false);
+}
+
+// The same launches with the workspace in this GPU's static scratch array: no allocation of any kind, no
+// workspace argument.  Every word of the scratch that the kernels read has been written earlier in the same
+// call (last-limb coefficients, then the converted part), so nothing has to be cleared between calls.
+extern "C" int ckks_rescale_static(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint64_t* d_out, uint32_t batch,
+                                   void* stream) {
+    if (!ctx) return CKKS_EINVAL;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device)
+        return fail(ctx, CKKS_EINVAL, "the current device is not the one the context was created on");
+    return rescale_impl(ctx, level, d_ct, d_out, batch, ctx->scratch_ptr, CKKS_STATIC_SCRATCH_BYTES, stream, true);
 }
 
 extern "C" int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uint32_t n_rot,
