@@ -83,6 +83,8 @@ static u64 h_min_root(u64 m, u32 logN) {
     return best;
 }
 
+static inline u32 u8_of(u64 z, u32 k) { return (u32)(z >> (8 * k)) & 0xffu; }
+
 // ------------------------------------------------------------------------------ context
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -93,8 +95,26 @@ struct SharedLayout {
     size_t tw_int, tw_fp, pc, sc_plain, sc_dn, dn_hatinv, end;
 };
 struct LevelLayout {
-    size_t sc_up, up_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, dn_chat_fp, dn_fp_ok, pinv, pmod, end;
+    size_t sc_up, up_hatinv, up_chat, up_chat_fp, up_fp_ok, dn_chat, dn_chat_fp, dn_fp_ok, pinv, pmod, up_tiles, up_aop,
+        dn_tiles, dn_aop, end;
 };
+
+// Conversion on the matrix cores: targets per tile and the bound on tiles for a basis of `targets` limbs; ks = products
+// per coefficient group = ceil(sources / 4), used for 2..8 sources only
+// CKKS_MFMA_NTT: targets per lane half of a tile.  2 halves the matrix-core work per output but needs 128 registers
+// for the converted words alone and spills (1.1 KB per lane); 1 is what runs.
+// CKKS_MFMA_UP: the ModUp conversion (6 sources of 50 bits at the benchmark shape) measured the same on the matrix
+// cores as on the FP64 pipe (125 vs 124 us), so only the ModDown direction (60-bit sources: 11 FP64 instructions per
+// source and output against 19 in total) uses them by default.
+#ifndef CKKS_MFMA_NTT
+#define CKKS_MFMA_NTT 1
+#endif
+#ifndef CKKS_MFMA_UP
+#define CKKS_MFMA_UP 0
+#endif
+static inline u32 mfma_ks(u32 sources) { return (sources >= 2 && sources <= 8) ? (sources + 3) / 4 : 0; }
+static inline u32 mfma_ks_up(u32 sources) { return CKKS_MFMA_UP ? mfma_ks(sources) : 0; }
+static inline u32 mfma_tile_bound(u32 targets) { return (targets + 2 * CKKS_MFMA_NTT - 1) / (2 * CKKS_MFMA_NTT) + 1; }
 struct RescaleLayout {
     size_t sc_dn, dn_chat, dn_chat_fp, dn_fp_ok, pinv, end;
 };
@@ -136,6 +156,10 @@ static LevelLayout level_layout(size_t base, u32 ell, u32 K, u32 alpha) {
     l.dn_fp_ok = t.take(ell * sizeof(u32));
     l.pinv = t.take(ell * sizeof(PinvConst));
     l.pmod = t.take(ell * sizeof(u64));
+    l.up_tiles = t.take((mfma_ks_up(alpha) ? beta * mfma_tile_bound(D) : 0) * sizeof(ConvTile));
+    l.up_aop = t.take(beta * mfma_tile_bound(D) * mfma_ks_up(alpha) * 128 * sizeof(u64));
+    l.dn_tiles = t.take(mfma_tile_bound(ell) * sizeof(ConvTile));
+    l.dn_aop = t.take(mfma_tile_bound(ell) * mfma_ks(K) * 128 * sizeof(u64));
     l.end = t.o;
     return l;
 }
@@ -156,7 +180,7 @@ static RescaleLayout rescale_layout(size_t base, u32 ell) {
 
 // ModDown merged with the rescale after it, from level ell: sources q_{ell-1}, p_0..p_{K-1}; targets q_0..q_{ell-2}
 struct MergedLayout {
-    size_t sc_dn, dn_chat, dn_chat_fp, dn_fp_ok, pinv, qlinv, end;
+    size_t sc_dn, dn_chat, dn_chat_fp, dn_fp_ok, pinv, qlinv, dn_tiles, dn_aop, end;
 };
 static MergedLayout merged_layout(size_t base, u32 ell, u32 K) {
     const size_t T = ell - 1, S = K + 1;
@@ -168,6 +192,8 @@ static MergedLayout merged_layout(size_t base, u32 ell, u32 K) {
     l.dn_fp_ok = t.take(T * sizeof(u32));
     l.pinv = t.take(T * sizeof(PinvConst));
     l.qlinv = t.take(T * sizeof(PinvConst));
+    l.dn_tiles = t.take(mfma_tile_bound(T) * sizeof(ConvTile));
+    l.dn_aop = t.take(mfma_tile_bound(T) * mfma_ks(S) * 128 * sizeof(u64));
     l.end = t.o;
     return l;
 }
@@ -387,6 +413,46 @@ static u64 prod_except(const std::vector<u64>& src, size_t skip, u64 m) {
     return r;
 }
 
+// Tiles and constant operands of the matrix-core conversion for one digit (conv_mfma_kernel states the layout).
+// targets: limb indices of the FpAr targets, in order; mod_of(t): their primes; hat(i, t): (product of the other
+// sources) mod that prime, for source i < ns.  Returns the number of tiles written (at most `bound`).
+template <class ModFn, class HatFn>
+static u32 build_conv_tiles(ConvTile* tiles, u64* aop, u32 bound, u32 ks_n, u32 ns, const std::vector<u32>& targets,
+                            ModFn mod_of, HatFn hat) {
+    u32 n_tiles = 0;
+    for (size_t first = 0; first < targets.size() && n_tiles < bound; n_tiles++) {
+        const u32 left = (u32)(targets.size() - first);
+        ConvTile& ct = tiles[n_tiles];
+        memset(&ct, 0, sizeof(ct));
+        ct.ntt = (left > 2 && CKKS_MFMA_NTT == 2) ? 2 : 1;
+        const u32 take = left < 2 * ct.ntt ? left : 2 * ct.ntt;
+        for (u32 tl = 0; tl < 4; tl++) ct.target[tl] = tl < take ? targets[first + tl] : 0xffffffffu;
+        first += take;
+        for (u32 ks = 0; ks < ks_n; ks++) {
+            for (u32 lane = 0; lane < 64; lane++) {
+                const u32 m_row = lane % 32, hk = lane / 32, hrow = (m_row / 4) % 2, a = (m_row / 8) * 4 + m_row % 4;
+                const u32 slot = hrow * ct.ntt + a / 8, dg = a % 8;
+                for (u32 half = 0; half < 2; half++) {  // the two sources this lane half carries in product ks
+                    const u32 i = 4 * ks + 2 * hk + half;
+                    u64 word = 0;
+                    if (a / 8 < ct.ntt && slot < 4 && ct.target[slot] != 0xffffffffu && i < ns) {
+                        const u64 m = mod_of(ct.target[slot]);
+                        u64 c = hat(i, ct.target[slot]) % m;  // times 256^bb below
+                        for (u32 bb = 0; bb < 8; bb++) {
+                            const int64_t centred = c > m / 2 ? (int64_t)c - (int64_t)m : (int64_t)c;
+                            const u64 z = (u64)centred + CKKS_DIGIT_BIAS;
+                            word |= (u64)((u8_of(z, dg)) ^ 0x80u) << (8 * bb);
+                            c = h_mulmod(c, 256 % m, m);
+                        }
+                    }
+                    aop[(((size_t)n_tiles * ks_n + ks) * 64 + lane) * 2 + half] = word;
+                }
+            }
+        }
+    }
+    return n_tiles;
+}
+
 extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32_t K, uint32_t dnum,
                                const uint64_t* h_primes, const uint64_t* h_psi, void* d_tables, size_t table_bytes,
                                void* stream) {
@@ -537,6 +603,31 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
             const u64 pi = h_invmod(pmod[i], qi);
             pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
         }
+        // matrix-core conversion: ModUp tiles per digit (FpAr targets outside the digit), ModDown tiles (FpAr q-limbs)
+        u32 up_nt = 0, dn_nt = 0;
+        const u32 up_ks = mfma_ks_up(alpha), dn_ks = mfma_ks(K), up_bound = mfma_tile_bound(Dl), dn_bound = mfma_tile_bound(ell);
+        if (up_ks) {
+            for (u32 j = 0; j < beta; j++) {
+                const u32 lo = j * alpha, hi = (j + 1) * alpha < ell ? (j + 1) * alpha : ell;
+                const std::vector<u64> digit(c->primes.begin() + lo, c->primes.begin() + hi);
+                std::vector<u32> tg;
+                for (u32 t = 0; t < Dl; t++)
+                    if (!(t >= lo && t < hi) && pc[ph(t)].fp) tg.push_back(t);
+                const u32 nt = build_conv_tiles((ConvTile*)(hb + ll.up_tiles) + (size_t)j * up_bound,
+                                                (u64*)(hb + ll.up_aop) + (size_t)j * up_bound * up_ks * 128, up_bound, up_ks,
+                                                hi - lo, tg, [&](u32 t) { return c->primes[ph(t)]; },
+                                                [&](u32 i, u32 t) { return prod_except(digit, i, c->primes[ph(t)]); });
+                if (nt > up_nt) up_nt = nt;
+            }
+        }
+        if (dn_ks) {
+            std::vector<u32> tg;
+            for (u32 i = 0; i < ell; i++)
+                if (pc[i].fp) tg.push_back(i);
+            dn_nt = build_conv_tiles((ConvTile*)(hb + ll.dn_tiles), (u64*)(hb + ll.dn_aop), dn_bound, dn_ks, K, tg,
+                                     [&](u32 t) { return c->primes[t]; },
+                                     [&](u32 k, u32 t) { return prod_except(specials, k, c->primes[t]); });
+        }
         View& v = c->level[ell];
         v.logN = logN, v.L = ell, v.K = K, v.dnum = beta, v.alpha = alpha, v.D = Dl, v.sh = &c->sh;
         v.primes.resize(Dl);
@@ -555,6 +646,9 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         tb.pinv = (const PinvConst*)(dbase + ll.pinv);
         tb.pmod = (const u64*)(dbase + ll.pmod);
         tb.qlinv = nullptr;
+        tb.up_tiles = (const ConvTile*)(dbase + ll.up_tiles), tb.up_aop = (const u64*)(dbase + ll.up_aop);
+        tb.dn_tiles = (const ConvTile*)(dbase + ll.dn_tiles), tb.dn_aop = (const u64*)(dbase + ll.dn_aop);
+        tb.up_ntiles = up_nt, tb.up_tstride = up_bound, tb.up_ks = up_ks, tb.dn_ntiles = dn_nt, tb.dn_ks = dn_ks;
         tb.L = ell, tb.K = K, tb.dnum = beta, tb.alpha = alpha, tb.D = Dl, tb.Lfull = L, tb.Lq = ell;
     }
     // ---- one block per rescale step: a ModDown whose only "special" prime is q_{ell-1}
@@ -626,6 +720,16 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
             const u64 ql = h_invmod(src[0] % qi, qi);
             qlinv[i] = PinvConst{ql, h_shoup(ql, qi), (double)ql};
         }
+        u32 dn_nt = 0;
+        const u32 dn_ks = mfma_ks(S);
+        if (dn_ks) {
+            std::vector<u32> tg;
+            for (u32 i = 0; i < T; i++)
+                if (pc[i].fp) tg.push_back(i);
+            dn_nt = build_conv_tiles((ConvTile*)(hb + ml.dn_tiles), (u64*)(hb + ml.dn_aop), mfma_tile_bound(T), dn_ks, S, tg,
+                                     [&](u32 t) { return c->primes[t]; },
+                                     [&](u32 k, u32 t) { return prod_except(src, k, c->primes[t]); });
+        }
         View& v = c->merged[ell];
         v.logN = logN, v.L = T, v.K = S, v.dnum = 1, v.alpha = T, v.D = ell + K, v.sh = &c->sh;
         v.primes = c->level[ell].primes;  // same limb order as the level: q_0..q_{ell-1}, p_0..p_{K-1}
@@ -640,6 +744,8 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         tb.dn_fp_ok = (const u32*)(dbase + ml.dn_fp_ok);
         tb.pinv = (const PinvConst*)(dbase + ml.pinv);
         tb.qlinv = (const PinvConst*)(dbase + ml.qlinv);
+        tb.dn_tiles = (const ConvTile*)(dbase + ml.dn_tiles), tb.dn_aop = (const u64*)(dbase + ml.dn_aop);
+        tb.dn_ntiles = dn_nt, tb.dn_ks = dn_ks;
         tb.L = T, tb.K = S, tb.dnum = 1, tb.alpha = T, tb.D = ell + K, tb.Lfull = L, tb.Lq = ell;
     }
 
@@ -761,10 +867,12 @@ static std::string kname(const char* base, const char* ar, int A, const char* ta
 // kernel's limb index.  by_limb: groups = run limbs x groups_n, instances = inst_n; otherwise
 // (conversion targets): groups = groups_n, instances = the run's limbs in blocks of inst_n.  alg(first, count) gives
 // the algorithmic limbs (read + written once) of the launch covering primes [first, first+count).
+// only: -1 = every run, 0 = IntAr runs only, 1 = FpAr runs only.
 template <class L, class ArgT, class AlgFn>
 static void launch_runs(const View* c, u32 lo, u32 hi, u32 limb_base, bool by_limb, u32 groups_n, u32 inst_n,
-                        const ArgT& a, hipStream_t s, AlgFn alg) {
+                        const ArgT& a, hipStream_t s, AlgFn alg, int only = -1) {
     for (const ClassRun& cr : class_runs(c, lo, hi)) {
+        if (only >= 0 && (int)cr.fp != only) continue;
         const LimbRun run = {cr.first - limb_base, cr.count};
         // conversion launches: inst_n holds the targets per workgroup of FpAr runs in its low half and of
         // IntAr runs in its high half
@@ -821,6 +929,14 @@ template <int DIR>
 struct ConvL {
     template <class AR, int A>
     static void go(dim3 g, hipStream_t s, const ConvArgs& a, const Tables& tb, LimbRun run) {
+        // digit-format sources exist only where the FpAr targets go to the matrix-core kernel: integer targets only
+        if constexpr (!AR::is_fp) {
+            if (a.src_fmt == SRC_DIGITS) {
+                hipLaunchKernelGGL((conv_fwd_strided_kernel<AR, A, DIR, ConvTB<DIR, false>::value, true>), g, dim3(256), 0, s, a,
+                                   tb, run);
+                return;
+            }
+        }
         hipLaunchKernelGGL((conv_fwd_strided_kernel<AR, A, DIR, ConvTB<DIR, AR::is_fp>::value>), g, dim3(256), 0, s, a, tb,
                            run);
     }
@@ -881,9 +997,56 @@ static void launch_fwd_strided(const View* c, const FwdStridedArgs& a, hipStream
                              [per](u32, u32 n) { return per * n; });
 }
 
+template <int A, int DIR>
+static void launch_conv_mfma_ks(const View* c, u32 ks, dim3 grid, hipStream_t s, const MfmaConvArgs& a) {
+    switch (ks) {
+        case 1: hipLaunchKernelGGL((conv_mfma_kernel<A, 1, DIR, CKKS_MFMA_NTT>), grid, dim3(256), 0, s, a, c->tb); break;
+        case 2: hipLaunchKernelGGL((conv_mfma_kernel<A, 2, DIR, CKKS_MFMA_NTT>), grid, dim3(256), 0, s, a, c->tb); break;
+    }
+}
+
+// conversion of every FpAr target on the matrix cores (the view's tile tables say which targets those are)
+template <int DIR>
+static void launch_conv_mfma(const View* c, const ConvArgs& a, hipStream_t s) {
+    const Tables& tb = c->tb;
+    MfmaConvArgs m;
+    m.src = a.src, m.dst = a.dst, m.groups_outer = a.groups_outer;
+    m.tiles = DIR == CONV_UP ? tb.up_tiles : tb.dn_tiles;
+    m.aop = DIR == CONV_UP ? tb.up_aop : tb.dn_aop;
+    m.n_tiles = DIR == CONV_UP ? tb.up_ntiles : tb.dn_ntiles;
+    m.tile_stride = DIR == CONV_UP ? tb.up_tstride : tb.dn_ntiles;
+    const u32 ks = DIR == CONV_UP ? tb.up_ks : tb.dn_ks;
+    const u32 groups = a.groups_outer * (DIR == CONV_UP ? c->dnum : 1) * tiles_of(c);
+    const dim3 grid(xcd_grid(groups, m.n_tiles));
+    u64 limbs = 0;  // FpAr targets written (per digit that does not own them) plus the sources, read once
+    if (c->sh->prof.on) {
+        const u32 hi = DIR == CONV_UP ? c->D : c->L;
+        for (u32 t = 0; t < hi; t++)
+            if (c->primes[t] < CKKS_FP_PRIME_LIMIT) limbs += DIR == CONV_UP ? c->dnum - (t < c->L ? 1 : 0) : 1;
+        limbs = (u64)a.groups_outer * (limbs + (DIR == CONV_UP ? c->L : c->K));
+    }
+    ProfScope ps(c, c->sh->prof.on ? std::string("conv_mfma_kernel<") + std::to_string((int)c->logN - 8) + ", " + std::to_string(ks) +
+                                         ", " + std::to_string(DIR) + ", " + std::to_string(CKKS_MFMA_NTT) + ">"
+                                   : std::string(),
+                 limbs, s);
+    switch (c->logN - 8) {
+        case 4: launch_conv_mfma_ks<4, DIR>(c, ks, grid, s, m); break;
+        case 5: launch_conv_mfma_ks<5, DIR>(c, ks, grid, s, m); break;
+        case 6: launch_conv_mfma_ks<6, DIR>(c, ks, grid, s, m); break;
+        case 7: launch_conv_mfma_ks<7, DIR>(c, ks, grid, s, m); break;
+        case 8: launch_conv_mfma_ks<8, DIR>(c, ks, grid, s, m); break;
+    }
+}
+
+static inline bool conv_on_matrix_cores(const View* c, int dir) {
+    return dir == CONV_UP ? c->tb.up_ntiles != 0 : c->tb.dn_ntiles != 0;
+}
+
 template <int DIR>
 static void launch_conv(const View* c, const ConvArgs& a, hipStream_t s) {
     const u64 outer = a.groups_outer;
+    const int only = conv_on_matrix_cores(c, DIR) ? 0 : -1;  // FpAr targets go to the matrix-core kernel when the view has tiles
+    if (only == 0) launch_conv_mfma<DIR>(c, a, s);
     if (DIR == CONV_UP) {  // groups = (batch, digit, tile); instances = blocks of the run's target primes
         launch_runs<ConvL<DIR>>(c, 0, c->D, 0, false, a.groups_outer * c->dnum * tiles_of(c),
                                 ConvTB<DIR, true>::value | (ConvTB<DIR, false>::value << 16), a, s,
@@ -891,11 +1054,11 @@ static void launch_conv(const View* c, const ConvArgs& a, hipStream_t s) {
                                     u64 w = 0;  // every target limb is written for each digit that does not own it
                                     for (u32 t = first; t < first + n; t++) w += c->dnum - (t < c->L ? 1 : 0);
                                     return outer * (w + c->L);  // plus the source coefficients, read once
-                                });
+                                }, only);
     } else {  // groups = (g, tile); instances = blocks of the run's target q-limbs
         launch_runs<ConvL<DIR>>(c, 0, c->L, 0, false, a.groups_outer * tiles_of(c),
                                 ConvTB<DIR, true>::value | (ConvTB<DIR, false>::value << 16), a, s,
-                                [c, outer](u32, u32 n) { return outer * (n + (u64)c->K); });
+                                [c, outer](u32, u32 n) { return outer * (n + (u64)c->K); }, only);
     }
 }
 
@@ -1287,20 +1450,22 @@ static int check_ks_args(const View* c, const void* a, const void* b, const void
 // first forward pass of every extended limb.
 static void decompose_extend(const View* c, const Workspace& w, u32 groups, hipStream_t s) {
     const LimbSel sel = {c->L, groups, c->L, 0, 0, 0};
-    InvStridedArgs a2 = {w.x, sel, SC_UP, 1};
+    const u32 fmt = conv_on_matrix_cores(c, CONV_UP) ? SRC_DIGITS : SRC_F64;
+    InvStridedArgs a2 = {w.x, sel, SC_UP, fmt};
     launch_inv_strided(c, a2, s);
     fork_side(c, s);  // from here the special-limb (IntAr) chain runs beside the q-limb chain
-    ConvArgs a3 = {w.x, w.dt, groups};
+    ConvArgs a3 = {w.x, w.dt, groups, fmt};
     launch_conv<CONV_UP>(c, a3, s);
 }
 
 // ModDown side: w.cp holds the first inverse pass of c' on the special limbs.
 static void moddown_convert(const View* c, const Workspace& w, u32 cg, hipStream_t s) {
     const LimbSel sel = {c->K, cg * 2, c->K, 0, c->L, 0};
-    InvStridedArgs a6 = {w.cp, sel, SC_DN, 0};
+    const u32 fmt = conv_on_matrix_cores(c, CONV_DN) ? SRC_DIGITS : SRC_CANON;
+    InvStridedArgs a6 = {w.cp, sel, SC_DN, fmt};
     launch_inv_strided(c, a6, s);
     join_side(c, s);  // the conversion reads every special limb
-    ConvArgs a7 = {w.cp, w.cv, cg * 2};
+    ConvArgs a7 = {w.cp, w.cv, cg * 2, fmt};
     launch_conv<CONV_DN>(c, a7, s);
 }
 

@@ -44,6 +44,13 @@ struct Tables {
     const PinvConst* pinv;     // [L]     P^-1 mod q_i
     const u64* pmod;           // [L]     P mod q_i
     const PinvConst* qlinv;    // [L]     q_L^-1 mod q_i where limb L is the first source of a merged ModDown
+    // conversion on the matrix cores (conv_mfma_kernel): target tiles and constant operands per digit; n_tiles = 0
+    // when the view does not use it (fewer than 2 or more than 8 sources, or no FpAr target)
+    const struct ConvTile* up_tiles;  // [dnum][up_tstride]
+    const u64* up_aop;                // [dnum][up_tstride][up_ks][64]
+    const struct ConvTile* dn_tiles;  // [dn_ntiles]
+    const u64* dn_aop;                // [dn_ntiles][dn_ks][64]
+    u32 up_ntiles, up_tstride, up_ks, dn_ntiles, dn_ks;  // tiles in use (most over the digits), tiles stored per digit
     u32 logN, L, K, dnum, alpha, D;
     u32 Lfull;  // q-limbs of the whole prime chain
     u32 Lq;     // limbs 0 .. Lq-1 of this basis are q-limbs of the chain, the rest its special limbs
@@ -148,7 +155,7 @@ struct InvStridedArgs {
     u64* data;  // in place: raw inverse-lazy words in, canonical coefficients (times the scale) out
     LimbSel sel;
     u32 scale;   // InvScaleSel
-    u32 fp_out;  // 1: limbs of FpAr primes are stored as doubles (same canonical integer values)
+    u32 out_fmt;  // SrcFormat of the stored words: SRC_F64 applies to limbs of FpAr primes only (others stay canonical)
 };
 
 template <class AR, int A>
@@ -176,7 +183,7 @@ __device__ __forceinline__ void inv_strided_body(const InvStridedArgs& a, const 
 #pragma unroll
     for (int k = 0; k < 8; k++) {
         u64 ox, oy;
-        AR::bfly_inv_last(x[k], x[k + 8], sc, m, a.fp_out != 0, ox, oy);
+        AR::bfly_inv_last(x[k], x[k + 8], sc, m, a.out_fmt, ox, oy);
         base[(size_t)(k * C::RB + r0) * 256 + col] = ox;
         base[(size_t)((k + 8) * C::RB + r0) * 256 + col] = oy;
     }
@@ -250,9 +257,16 @@ struct ConvArgs {
     const u64* src;
     u64* dst;
     u32 groups_outer;  // CONV_UP: batch; CONV_DN: number of g
+    u32 src_fmt;       // SrcFormat of the source words: SRC_DIGITS, or the natural format (the launcher picks the instantiation)
 };
+// a source word as a canonical integer; DG: the sources are SRC_DIGITS words, else they are in their natural
+// format (FpAr-prime sources of ModUp as doubles, everything else canonical)
+template <bool DG>
+__device__ __forceinline__ u64 conv_src_int(u64 w, bool f64_word) {
+    return DG ? digits_decode(w) : f64_word ? f64_to_u64(FpAr::from_raw(w)) : w;
+}
 
-template <class AR, int A, int DIR, int TB>
+template <class AR, int A, int DIR, int TB, bool DG = false>
 __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kernel(ConvArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[4096];
     typedef NttCore<AR, A> C;
@@ -342,7 +356,7 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
                         for (int t = 0; t < TB; t++) cf[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
                         for (int k = 0; k < 8; k++) {
-                            const double y = FpAr::from_raw(cur[k]);
+                            const double y = DG ? u64_to_f64(digits_decode(cur[k])) : FpAr::from_raw(cur[k]);
 #pragma unroll
                             for (int t = 0; t < TB; t++) acc[t][k] += FpAr::mulmod_lazy(y, cf[t], fm[t]);
                         }
@@ -352,7 +366,7 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
                         for (int t = 0; t < TB; t++) cl[t] = chat_fp[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
                         for (int k = 0; k < 8; k++) {
-                            const u64 y = cur[k];
+                            const u64 y = DG ? digits_decode(cur[k]) : cur[k];
                             const double ya = (double)(u32)(y >> 30) * 1073741824.0, yl = (double)(u32)(y & 0x3fffffffu);
 #pragma unroll
                             for (int t = 0; t < TB; t++)
@@ -399,8 +413,7 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
                     for (int t = 0; t < TB; t++) cc[t] = chat[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
                     for (int k = 0; k < 8; k++) {
-                        u64 y = si[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col];
-                        if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+                        const u64 y = conv_src_int<DG>(si[(size_t)((hf * 8 + k) * C::RB + r0) * 256 + col], src_fp);
 #pragma unroll
                         for (int t = 0; t < TB; t++) mac128(acc[t][k], y, cc[t]);
                     }
@@ -436,8 +449,7 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
                 const u64 cc = chat[(size_t)i * chat_stride + pi[t]];
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
-                    u64 y = si[(size_t)(k * C::RB + r0) * 256 + col];
-                    if (src_fp) y = f64_to_u64(FpAr::from_raw(y));
+                    const u64 y = conv_src_int<DG>(si[(size_t)(k * C::RB + r0) * 256 + col], src_fp);
                     mac128(acc[k], y, cc);
                 }
                 if (ns > 8 && ((i & 7) == 7 || i + 1 == ns)) {
@@ -458,6 +470,208 @@ __global__ __launch_bounds__(256, AR::is_fp ? 3 : 2) void conv_fwd_strided_kerne
         if (t) __syncthreads();  // the previous target's exchange must have been read
         if (valid[t]) fwd_strided_finish<AR, A>(x[t], tb, lds, pi[t], dst0 + (size_t)pi[t] * N, tile);
         else if (A > 4) __syncthreads();  // keep barrier counts equal (fwd_strided holds one barrier)
+    }
+}
+
+
+// ===================== base conversion on the matrix cores, fused into the first forward pass of FpAr targets
+// out_t = sum_i y_i * chat_{i,t} mod m_t as an 8-bit integer matrix product.  Every source word arrives as eight
+// signed base-256 digits (SRC_DIGITS), y_i = sum_b d_{i,b} 256^b; the digit weight is folded into the constant,
+// C_{(i,b),t} = centred (chat_{i,t} * 256^b mod m_t), itself cut into seven signed digits C = sum_g c_g 256^g.  Then
+//   S_{t,g}[n] = sum_{(i,b)} c_g(C_{(i,b),t}) * d_{i,b}(y_i[n])          (v_mfma_i32_32x32x32_i8, |S| < 2^21)
+//   out_t[n]  == sum_g 256^g S_{t,g}[n]  (mod m_t),
+// recombined exactly in FP64 (conv_recombine).  One 32x32x32 product handles 32 coefficients (columns) and 32
+// rows = up to 4 targets x 8 digit rows, over 32 values of (i,b) = four sources (lane half h holds the digit words
+// of sources 4*ks + 2*h and 4*ks + 2*h + 1 in its 16 operand bytes, the constant operand the matching bytes);
+// ceil(ns/4) products accumulate all sources.  Row m of the constant tile sits in accumulator a = (m/8)*4 + m%4 of lane half (m/4)%2, so a lane
+// holds all digits of its targets: target slot tl = h * ntt + a/8, digit a%8 (ntt = targets per lane, 1 or 2).
+//
+// A lane converts, for s = 0, 1 and every k < 16, coefficient (row k*RB + r0, column c) of the tile, with
+// (r0, c) from pp = wave*64 + s*32 + lane%32 exactly as tid maps to (r0, c) in layout SA: the 16 values k of one
+// (s, target) are the inputs of the first four forward stages, which therefore run in the lane that converted
+// them; the exchange for the remaining stages goes through LDS target by target.
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+struct ConvTile {
+    u32 target[4];  // limb index of target slot tl within the destination group; 0xffffffff = unused slot
+    u32 ntt;        // targets per lane half (1 or 2); 0 = unused tile
+    u32 pad[3];
+};
+struct MfmaConvArgs {
+    const u64* src;         // SRC_DIGITS words: CONV_UP [b][L][N], CONV_DN [g][K][N]
+    u64* dst;               // raw forward-lazy words after the first pass: CONV_UP dt [b][dnum][D][N], CONV_DN cv [g][L][N]
+    const ConvTile* tiles;  // [digits][n_tiles]
+    const u64* aop;         // [digits][n_tiles][KS][64][2] constant operands, one 16-byte row fragment per lane
+    u32 groups_outer;       // CONV_UP: batch; CONV_DN: number of g
+    u32 n_tiles;            // tiles launched per digit
+    u32 tile_stride;        // tiles stored per digit
+};
+
+// sum_g 256^g S_g reduced to |.| <= (0.5 + 2^-15) m, exactly: lo = digits 0..3 (below 2^46), hi = digits 4..6 times
+// 2^32 (an integer multiple of 2^32 with 38 significant bits: exact); the quotient estimate of (hi + lo) / m is off
+// by less than 2^-15 before rounding, hi - c*m is an integer below 2^53 in magnitude, so the fma and the sum are exact.
+// (Summing the digits with 64-bit integer multiply-adds onto the bit pattern of a double, which avoids the half-rate
+// i32 -> f64 conversions, was measured 5 % slower on the kernel.)
+__device__ __forceinline__ double conv_recombine(const v16i& s, int b, const FpAr::Mod& m) {
+    const double lo = __builtin_fma((double)s[b + 3], 16777216.0,
+                                    __builtin_fma((double)s[b + 2], 65536.0, __builtin_fma((double)s[b + 1], 256.0, (double)s[b])));
+    const double hi = __builtin_fma((double)s[b + 6], 281474976710656.0,
+                                    __builtin_fma((double)s[b + 5], 1099511627776.0, (double)s[b + 4] * 4294967296.0));
+    const double c = __builtin_rint((hi + lo) * m.qinv);
+    return __builtin_fma(-c, m.q, hi) + lo;
+}
+
+template <int A, int KS, int DIR, int NTT>
+__global__ __launch_bounds__(256, NTT == 1 ? 3 : 2) void conv_mfma_kernel(MfmaConvArgs a, Tables tb) {
+    __shared__ u64 lds[4096];
+    typedef NttCore<FpAr, A> C;
+    constexpr u32 TILES = (1u << A) / 16;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 31, h = lane >> 5;
+    const u32 n_dig = DIR == CONV_UP ? tb.dnum : 1;
+    u32 group, inst;
+    if (!xcd_decode(blockIdx.x, a.n_tiles, a.groups_outer * n_dig * TILES, group, inst)) return;
+    const u32 tile = group % TILES;
+    u32 j = 0, ns;
+    const u64* src;
+    u64* dst0;
+    if (DIR == CONV_UP) {
+        const u32 bj = group / TILES, b = bj / tb.dnum;
+        j = bj % tb.dnum;
+        const u32 own_lo = j * tb.alpha, own_hi = (j + 1) * tb.alpha < tb.L ? (j + 1) * tb.alpha : tb.L;
+        ns = own_hi - own_lo;
+        src = a.src + ((size_t)b * tb.L + own_lo) * N;
+        dst0 = a.dst + ((size_t)b * tb.dnum + j) * tb.D * N;
+    } else {
+        const u32 g = group / TILES;
+        ns = tb.K;
+        src = a.src + (size_t)g * tb.K * N;
+        dst0 = a.dst + (size_t)g * tb.L * N;
+    }
+    const ConvTile ct = a.tiles[j * a.tile_stride + inst];
+    if (ct.ntt == 0) return;  // digits with fewer targets leave their last tiles unused (uniform per workgroup)
+    auto slot_target = [&](u32 tl) { return tl == 0 ? ct.target[0] : tl == 1 ? ct.target[1] : tl == 2 ? ct.target[2] : ct.target[3]; };
+    v4i aop[KS];
+    {
+        const v4i* ap = reinterpret_cast<const v4i*>(a.aop) + (size_t)(j * a.tile_stride + inst) * KS * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) aop[ks] = ap[ks * 64];
+    }
+    // this lane's targets: slots h * ntt + tt
+    u32 vi[NTT];
+    FpAr::Mod fm[NTT];
+#pragma unroll
+    for (int tt = 0; tt < NTT; tt++) {
+        vi[tt] = (u32)tt < ct.ntt ? slot_target(h * ct.ntt + tt) : 0xffffffffu;
+        fm[tt] = FpAr::mod(tb.pc[tb.phys(vi[tt] != 0xffffffffu ? vi[tt] : 0)]);
+    }
+    double x[2][NTT][16];
+    // 32 coefficient groups g = s*16 + k per lane.  The source words of group g + PF are requested before the products
+    // of group g are issued; scheduling barriers keep the compiler from hoisting every load of the unrolled loop
+    // (which would spill).
+    constexpr int PF = 2;  // deeper prefetch (4, 6, 8 groups) changes nothing: the words come from L2
+    // this lane half supplies the digits of sources 4*ks + 2*h and the next one; beyond the last source any valid word
+    // will do (the constant rows of those sources are zero)
+    const u64* sp[2 * KS];
+#pragma unroll
+    for (int q = 0; q < 2 * KS; q++) {
+        const u32 i = 4 * (q >> 1) + 2 * h + (q & 1);
+        sp[q] = src + (size_t)(i < ns ? i : ns - 1) * N + tile * C::TC;
+    }
+    auto src_off = [&](int g) {
+        const u32 pp = wave * 64 + (g >> 4) * 32 + n;
+        return (u32)(((g & 15) * C::RB + pp / C::TC) * 256 + pp % C::TC);
+    };
+    u64 bw[PF + 1][2 * KS];
+#pragma unroll
+    for (int g = 0; g < PF; g++) {
+#pragma unroll
+        for (int q = 0; q < 2 * KS; q++) bw[g][q] = sp[q][src_off(g)];
+    }
+#pragma unroll
+    for (int g = 0; g < 32; g++) {
+        if (g + PF < 32) {
+#pragma unroll
+            for (int q = 0; q < 2 * KS; q++) bw[(g + PF) % (PF + 1)][q] = sp[q][src_off(g + PF)];
+        }
+        v16i acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+            const u64 w0 = bw[g % (PF + 1)][2 * ks], w1 = bw[g % (PF + 1)][2 * ks + 1];
+            const v4i bop = {(int)(u32)w0, (int)(u32)(w0 >> 32), (int)(u32)w1, (int)(u32)(w1 >> 32)};
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(aop[ks], bop, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int tt = 0; tt < NTT; tt++) x[g >> 4][tt][g & 15] = conv_recombine(acc, tt * 8, fm[tt]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    // first four forward stages of every (s, target) set, in place (|x| <= 0.51 q on entry, below 7 q after)
+#pragma unroll
+    for (int tt = 0; tt < NTT; tt++) {
+        if (vi[tt] == 0xffffffffu) continue;
+        const double* tf = tb.tw_fp + (size_t)tb.phys(vi[tt]) * 2 * N;
+#pragma unroll
+        for (int st = 0; st < 4; st++) {
+            const int d = 8 >> st;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                if (k & d) continue;
+                const FpAr::Tw w = FpAr::tw(nullptr, tf, (1u << st) + (k >> (4 - st)), N, false);
+#pragma unroll
+                for (int s = 0; s < 2; s++) FpAr::bfly_fwd<false>(x[s][tt][k], x[s][tt][k + d], w, fm[tt]);
+            }
+        }
+    }
+    // remaining stages and store, one target at a time
+#pragma unroll
+    for (int tt = 0; tt < NTT; tt++) {
+#pragma unroll
+        for (int hh = 0; hh < 2; hh++) {
+            if ((u32)tt >= ct.ntt) continue;
+            const u32 t_vi = slot_target(hh * ct.ntt + tt);  // uniform over the workgroup
+            if (t_vi == 0xffffffffu) continue;
+            const u32 pi = tb.phys(t_vi);
+            const FpAr::Mod m = FpAr::mod(tb.pc[pi]);
+            u64* dst = dst0 + (size_t)t_vi * N;
+            if constexpr (A > 4) {
+                __syncthreads();  // the previous target's exchange has been read
+                if (h == (u32)hh) {
+#pragma unroll
+                    for (int s = 0; s < 2; s++) {
+                        const u32 pp = wave * 64 + s * 32 + n;
+#pragma unroll
+                        for (int k = 0; k < 16; k++) lds[k * 256 + pp] = FpAr::to_raw(FpAr::reduce(x[s][tt][k], m));
+                    }
+                }
+                __syncthreads();
+                const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
+                const u32 c = tid % C::TC, r1 = tid / C::TC, col = tile * C::TC + c;
+                double y[16];
+#pragma unroll
+                for (int k = 0; k < 16; k++) y[k] = FpAr::from_raw(lds[(r1 * 16 + k) * C::TC + c]);
+#pragma unroll
+                for (int st = 4; st < A; st++) {
+                    const int d = 1 << (A - st - 1);
+#pragma unroll
+                    for (int k = 0; k < 16; k++) {
+                        if (k & d) continue;
+                        FpAr::bfly_fwd<false>(y[k], y[k + d], FpAr::tw(nullptr, tf, (1u << st) + ((r1 * 16 + k) >> (A - st)), N, false), m);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < 16; k++)
+                    __builtin_nontemporal_store(FpAr::to_raw(FpAr::reduce(y[k], m)), &dst[(size_t)(r1 * 16 + k) * 256 + col]);
+            } else {
+                if (h == (u32)hh) {
+#pragma unroll
+                    for (int s = 0; s < 2; s++) {
+                        const u32 pp = wave * 64 + s * 32 + n, c = pp % C::TC, r0 = pp / C::TC, col = tile * C::TC + c;
+#pragma unroll
+                        for (int k = 0; k < 16; k++)
+                            dst[(size_t)(k * C::RB + r0) * 256 + col] = FpAr::to_raw(FpAr::reduce(x[s][tt][k], m));
+                    }
+                }
+            }
+        }
     }
 }
 

@@ -73,6 +73,17 @@ HD u64 mulmod_var(u64 a, u64 b, u64 q, u64 qneg, u64 r2) {
     return reduce128(p, q, qneg, r2);
 }
 
+// Word formats of base-conversion sources (the coefficients times the conversion pre-factor that the last
+// inverse stage leaves for the conversion kernels):
+//   SRC_CANON  canonical integer            SRC_F64  canonical integer as a double (FpAr primes only)
+//   SRC_DIGITS eight signed base-256 digits d_k in [-128, 127], y = sum d_k 256^k, digit k stored in byte k as
+//              d_k + 128 with the top bit flipped, i.e. as the two's-complement byte the matrix cores read:
+//              word = (y + B) ^ B with B = 0x80 in every byte (y < 2^63 - B, here y < 2^61).
+enum SrcFormat { SRC_CANON = 0, SRC_F64 = 1, SRC_DIGITS = 2 };
+#define CKKS_DIGIT_BIAS 0x8080808080808080ull
+HD u64 digits_encode(u64 y) { return (y + CKKS_DIGIT_BIAS) ^ CKKS_DIGIT_BIAS; }
+HD u64 digits_decode(u64 w) { return (w ^ CKKS_DIGIT_BIAS) - CKKS_DIGIT_BIAS; }
+
 // ------------------------------------------------------------------ per-prime constants
 struct PrimeConst {
     u64 q;        // the prime
@@ -140,11 +151,12 @@ struct IntAr {
     static HD T round_reduce(T v, const Mod&) { return v; }  // lazy ranges are invariants: nothing to do
     static HD u64 canon_fwd(T v, const Mod& m) { return csub(csub(csub(v, m.q2 + m.q2), m.q2), m.q); }  // from [0, 8q)
     static HD u64 canon_inv(T v, const Mod& m) { return csub(v, m.q); }
-    // last inverse stage with scaling, canonical results
-    static HD void bfly_inv_last(T& X, T& Y, const InvScale& s, const Mod& m, bool, u64& ox, u64& oy) {
+    // last inverse stage with scaling, canonical results (fmt: SRC_CANON or SRC_DIGITS; SRC_F64 does not apply)
+    static HD void bfly_inv_last(T& X, T& Y, const InvScale& s, const Mod& m, u32 fmt, u64& ox, u64& oy) {
         u64 a = X + Y, d = X - Y + m.q2;
         ox = mul_shoup(a, s.sx, s.sx_p, m.q);
         oy = mul_shoup(d, s.sy, s.sy_p, m.q);
+        if (fmt == SRC_DIGITS) ox = digits_encode(ox), oy = digits_encode(oy);
     }
     // inner-product accumulation: acc holds sum of v*k*2^-64 in [0, 2q); v canonical or forward-lazy (any 64-bit word)
     static HD T acc_zero() { return 0; }
@@ -245,12 +257,13 @@ struct FpAr {
         double r = reduce(v, m);
         return r < 0.0 ? r + m.q : r;
     }
-    // as_double: store the canonical value as a double's bit pattern instead of an integer word
-    static HD void bfly_inv_last(T& X, T& Y, const InvScale& s, const Mod& m, bool as_double, u64& ox, u64& oy) {
+    // fmt: SRC_F64 stores the canonical value as a double's bit pattern, SRC_DIGITS as signed digits
+    static HD void bfly_inv_last(T& X, T& Y, const InvScale& s, const Mod& m, u32 fmt, u64& ox, u64& oy) {
         double a = X + Y, d = X - Y;
         double rx = canon_f64(mulmod_lazy(a, s.sxd, m), m), ry = canon_f64(mulmod_lazy(d, s.syd, m), m);
-        ox = as_double ? to_raw(rx) : f64_to_u64(rx);
-        oy = as_double ? to_raw(ry) : f64_to_u64(ry);
+        ox = fmt == SRC_F64 ? to_raw(rx) : f64_to_u64(rx);
+        oy = fmt == SRC_F64 ? to_raw(ry) : f64_to_u64(ry);
+        if (fmt == SRC_DIGITS) ox = digits_encode(ox), oy = digits_encode(oy);
     }
     static HD T acc_zero() { return 0.0; }
     static HD void acc_mac(T& acc, T v, u64 key, const Mod& m) { acc += mulmod_lazy(v, u64_to_f64(key), m); }
