@@ -8,9 +8,12 @@ switches per second with every operand resident in HBM.  Extras report the other
 metric names: NTT limbs/s on config 1 (16 x 24 limbs) and hoisted rotations/s on config 3.
 
 The line also carries
-  roofline     : the kernel with the largest share of the timed region, its algorithmic bytes per
+  roofline     : the kernel with the largest share of the timed region: its algorithmic bytes per
                  launch over its mean launch duration (HIP events recorded by the library on the
-                 launch stream, in a second pass of the same K steps) against 8 TB/s;
+                 launch stream, in a further pass of the same K steps) against 8 TB/s, with the
+                 binding resource decided by the counters of the committed profile;
+  step_roofline: compulsory bytes and HBM-side counter bytes of the whole step over ms_per_step
+                 against 8 TB/s (the figure the 60 % target speaks of);
   cpu_baseline : the CPU oracle, as it stands, on a bounded sample of the same workload.
 """
 import argparse
@@ -27,27 +30,30 @@ HBM_PEAK_GBS = 8000.0
 # (the same units and clock that give the published 78.6 TFLOP/s fp64 figure, an FMA counting two flops).
 VALU_PEAK_TINSTR = 256 * 64 * 2.4e9 / 1e12
 
-# Per-launch counters of the default workload from rocprofv3 --pmc, copied from
-# profiles/keyswitch_step_n16_l24_d4_hbm_traffic.txt: HBM bytes (FETCH_SIZE scaled by 2, the factor a plain copy
-# of known size shows, plus WRITE_SIZE) and wave-level VALU instructions (SQ_INSTS_VALU).  Kernels or workloads
-# that were not measured report null.
+# Per-launch counters of the default workload come from the committed rocprofv3 --pmc summary (they are lab numbers of
+# the run that wrote that file, not something this run observes): HBM-side bytes (FETCH_SIZE scaled by 2, the factor a
+# plain copy of known size shows, plus WRITE_SIZE) and wave-level VALU instructions (SQ_INSTS_VALU).  Kernels that the
+# file does not list report null.
 _MIB = 1 << 20
-MEASURED = {
-    # kernel: (read MiB, write MiB, VALU wave-instructions)
-    "conv_fwd_strided_kernel<FpAr, 8, 1, 3>": (97.0, 288.0, 52756480),
-    "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": (49.6, 193.9, 48545792),
-    "conv_fwd_strided_kernel<IntAr, 8, 1, 2>": (98.6, 96.0, 47861760),
-    "inv_contig_kernel<FpAr, 8, 1>": (204.1, 96.0, 10543104),
-    "inv_contig_kernel<FpAr, 8, 2>": (108.1, 96.0, 11071488),
-    "inv_strided_kernel<FpAr, 8>": (96.6, 96.0, 9891840),
-    "inv_strided_kernel<IntAr, 8>": (48.5, 48.0, 13221888),
-    "ks_final_kernel<FpAr, 8, 1>": (982.6, 192.0, 27979776),
-    "ks_final_kernel<FpAr, 8, 2>": (500.7, 192.0, 24293376),
-    "ks_inner_kernel<FpAr, 8, 1, false>": (588.2, 192.0, 43929600),
-    "ks_inner_kernel<FpAr, 8, 2, false>": (492.3, 192.0, 44457984),
-    "ks_inner_kernel<IntAr, 8, 1, false>": (132.8, 48.0, 47953920),
-    "ks_inner_kernel<IntAr, 8, 2, false>": (132.8, 48.0, 48479232),
-}
+TRAFFIC_SOURCE = "profiles/keyswitch_step_n16_l24_d4_hbm_traffic.txt"
+
+
+def load_counter_table(path=None):
+    """{kernel: (read MiB, write MiB, VALU wave-instructions)} parsed from the committed counter summary."""
+    import re
+    rows = {}
+    try:
+        with open(path or os.path.join(ROOT, TRAFFIC_SOURCE)) as f:
+            for ln in f:
+                m = re.match(r"^(\S.*?>)\s+([\d.]+)\s+([\d.]+)\s+(\d+)\s+(\d+)(?:\s+\d+)*\s*$", ln)
+                if m:
+                    rows[m.group(1)] = (float(m.group(2)), float(m.group(3)), int(m.group(5)))
+    except OSError:
+        pass
+    return rows
+
+
+MEASURED = load_counter_table()
 
 
 def main():
@@ -56,7 +62,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-extras", action="store_true", help="skip every extra measurement")
-    ap.add_argument("--extras", default="overlap,concurrent,ntt,hoisted,config4,latency,levels",
+    ap.add_argument("--extras", default="overlap,concurrent,ntt,hoisted,config4,latency,levels,standalone",
                     help="comma-separated extra measurements: overlap (two streams inside each call), concurrent "
                          "(HMult and HRot batches on two caller streams), ntt (config 1), hoisted "
                          "(config 3 rotations, singly and doubly hoisted), config4 (32 rotations at L = 35, dnum = 5), latency (one "
@@ -100,7 +106,10 @@ def main():
         ctx.hmult_relin(ct1, ct2, evk, out1)
         ctx.hrot(ct1, g, rk, out2)
 
-    for _ in range(args.warmup):
+    # untimed: STARTUP steps that take the device from idle to its running clocks (the first steps after start-up are
+    # 5-9 % slower), then the W warm-up steps asked for
+    STARTUP = 30
+    for _ in range(STARTUP + args.warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -111,6 +120,15 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     ks_per_step = 2 * B
     value = ks_per_step / (ms_per_step * 1e-3)
+    # the same K steps once more, each bracketed by two events on the launch stream: median beside the mean
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    ms_median = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
 
     # ---- per-kernel pass: the same K steps with HIP events around every launch
     ctx.profile_enable(True)
@@ -140,48 +158,58 @@ def main():
     n_fp_q = sum(1 for q in ps.q_primes if q < 3 << 48)
     alg_lane_ops = {
         # ModUp: per ciphertext and coefficient, every digit writes the FP64 q-limbs it does not own
-        "conv_fwd_strided_kernel<FpAr, 8, 1, 3>": B * N * dnum * (n_fp_q - ps.L // dnum) * (7 * (ps.L // dnum) + 3 + bfly),
+        "conv_fwd_strided_kernel<FpAr, 8, 1, 3, false>": B * N * dnum * (n_fp_q - ps.L // dnum) * (7 * (ps.L // dnum) + 3 + bfly),
         # ModDown: both components, every FP64 q-limb, K sources of 60 bits
-        "conv_fwd_strided_kernel<FpAr, 8, 2, 3>": B * 2 * N * n_fp_q * (11 * ps.K + 3 + bfly),
+        # ModDown on the matrix cores: 7 conversions + 12 FP64 operations recombine an output, then the butterflies
+        "conv_mfma_kernel<8, 2, 2, 1>": B * 2 * N * n_fp_q * (19 + bfly),
     }
     for kname_, ops in alg_lane_ops.items():
         if kname_ in kernels:
             t = kernels[kname_]["avg_us"] * 1e-6
             kernels[kname_]["alg_lane_ops_frac"] = round(ops / t / 1e12 / VALU_PEAK_TINSTR, 3)
+    # ---- roofline of the kernel with the largest share of the timed region.  The headline figure is the HBM one:
+    # algorithmic bytes per launch (limbs the launch must read plus write once, tables excluded) over the mean launch
+    # duration from HIP events, against 8 TB/s.  Which resource binds the kernel is decided by the counters of the
+    # committed profile, evaluated at this run's duration: VALU issue fraction against HBM-traffic fraction.
     dom = max(prof.items(), key=lambda kv: kv[1][1])
     dname, (dn, dms, dbytes) = dom
     dur_s = dms / dn * 1e-3
     hbm_gbs = dbytes / dms / 1e6
     meas = MEASURED.get(dname) if B == synth.CFG2_BATCH else None
     traffic = int((meas[0] + meas[1]) * _MIB) if meas else None
-    valu_tinstr = meas[2] * 64 / dur_s / 1e12 if meas else None
-    hbm_frac = hbm_gbs / HBM_PEAK_GBS
-    alu_frac = valu_tinstr / VALU_PEAK_TINSTR if meas else None
-    roofline = {"kernel": dname, "traffic": traffic, "alg_bytes_per_launch": dbytes // dn,
-                "avg_launch_us": round(1e6 * dur_s, 2), "share_of_step": round(dms / total_ms, 3),
-                "hbm": {"achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(hbm_frac, 4)},
-                "alu": None if alu_frac is None else {
-                    "achieved": round(valu_tinstr, 2), "peak": round(VALU_PEAK_TINSTR, 2),
-                    "unit": "T VALU lane-instructions/s (peak = 256 CU x 64 lanes x 2.4 GHz = fp64 78.6 TFLOP/s / 2)",
-                    "frac": round(alu_frac, 4)}}
-    if alu_frac is not None and alu_frac > hbm_frac:
-        if dname in alg_lane_ops:
-            # the reported fraction is the algorithmic one; the issue-slot utilisation measured by the counter
-            # (which also holds address arithmetic, conversions and LDS traffic) stays beside it in "alu"
-            alg_t = alg_lane_ops[dname] / dur_s / 1e12
-            roofline["alu"]["issued"] = roofline["alu"].pop("achieved")
-            roofline["alu"]["issue_frac"] = roofline["alu"].pop("frac")
-            roofline["alu"]["alg_lane_ops_per_launch"] = alg_lane_ops[dname]
-            roofline["alu"]["achieved"] = round(alg_t, 2)
-            roofline["alu"]["frac"] = round(alg_t / VALU_PEAK_TINSTR, 4)
-            roofline.update({"bound": "alu", "achieved": round(alg_t, 2), "peak": round(VALU_PEAK_TINSTR, 2),
-                             "unit": "T lane-ops/s", "frac": round(alg_t / VALU_PEAK_TINSTR, 4)})
-        else:
-            roofline.update({"bound": "alu", "achieved": round(valu_tinstr, 2), "peak": round(VALU_PEAK_TINSTR, 2),
-                             "unit": "Tinstr/s", "frac": round(alu_frac, 4)})
-    else:
-        roofline.update({"bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                         "frac": round(hbm_frac, 4)})
+    roofline = {"kernel": dname, "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": TRAFFIC_SOURCE if meas else None,
+                "alg_bytes_per_launch": dbytes // dn, "avg_launch_us": round(1e6 * dur_s, 2),
+                "share_of_step": round(dms / total_ms, 3)}
+    if meas:
+        traffic_frac = traffic / dur_s / 1e9 / HBM_PEAK_GBS
+        issue_frac = meas[2] * 64 / dur_s / 1e12 / VALU_PEAK_TINSTR
+        roofline["hbm_counter_traffic"] = {"GBps": round(traffic / dur_s / 1e9, 1), "frac": round(traffic_frac, 4)}
+        roofline["valu_issue"] = {"wave_instructions_per_launch": meas[2], "frac": round(issue_frac, 4),
+                                  "peak": "256 CU x 4 SIMD x one wave64 instruction per 4 cycles x 2.4 GHz"}
+        roofline["bound"] = "alu" if issue_frac > traffic_frac else "hbm"
+        roofline["bound_decided_by"] = "valu_issue.frac vs hbm_counter_traffic.frac of the same kernel"
+    if dname in alg_lane_ops:  # secondary: the method's own FP64 operation count against the VALU issue peak
+        alg_t = alg_lane_ops[dname] / dur_s / 1e12
+        roofline["alu_algorithmic"] = {"lane_ops_per_launch": alg_lane_ops[dname], "achieved_T_per_s": round(alg_t, 2),
+                                       "peak_T_per_s": round(VALU_PEAK_TINSTR, 2), "frac": round(alg_t / VALU_PEAK_TINSTR, 4),
+                                       "note": "shortest exact FP64 sequences counted by hand; not a hardware counter"}
+
+    # ---- the whole step against the HBM roofline: compulsory bytes (operands, keys and results moved once: 6L limbs
+    # per HMult, 4L per HRot, one key of 2*dnum*(L+K) limbs per batch) and the HBM-side counter bytes of every launch
+    limb = 8 * N
+    compulsory = (B * 6 * L + 2 * dnum * D + B * 4 * L + 2 * dnum * D) * limb
+    step_roofline = {"compulsory_bytes_per_step": compulsory,
+                     "compulsory_GBps": round(compulsory / ms_per_step / 1e6, 1),
+                     "compulsory_frac": round(compulsory / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
+                     "counter_bytes_per_step": None, "counter_GBps": None, "counter_frac": None,
+                     "target_frac": 0.6, "traffic_source": None}
+    if B == synth.CFG2_BATCH and all(k in MEASURED for k in prof):
+        cb = sum((MEASURED[k][0] + MEASURED[k][1]) * _MIB * n / args.steps for k, (n, _ms, _b) in prof.items())
+        step_roofline.update({"counter_bytes_per_step": int(cb), "counter_GBps": round(cb / ms_per_step / 1e6, 1),
+                              "counter_frac": round(cb / ms_per_step / 1e6 / HBM_PEAK_GBS, 4),
+                              "traffic_source": TRAFFIC_SOURCE})
 
     extra = {"hmult_relin_per_s": None, "hrot_per_s": None}
     # split of the step (separately timed, same launch configuration)
@@ -194,7 +222,7 @@ def main():
         torch.cuda.synchronize()
         extra[name] = round(B * args.steps / (time.perf_counter() - a), 1)
 
-    EXTRA_GROUPS = ("overlap", "concurrent", "ntt", "hoisted", "config4", "latency", "levels")
+    EXTRA_GROUPS = ("overlap", "concurrent", "ntt", "hoisted", "config4", "latency", "levels", "standalone")
     groups = () if args.no_extras else tuple(g for g in args.extras.split(",") if g)
     for gname in groups:
         if gname not in EXTRA_GROUPS:
@@ -389,6 +417,25 @@ def main():
         del pw_out, ptw
         del a13, b13, o13, rs_out
 
+    if "standalone" in groups:
+        # the coefficient-form entry points as calls of their own (one element-parallel kernel each), on the batch
+        xin = ct1[:, 0].contiguous()                                  # [B][L][N]
+        up_out = torch.empty((B, dnum, D, N), dtype=ct1.dtype, device=ct1.device)
+        dt = timed(lambda: ctx.modup(xin, up_out), label="modup")
+        extra["modup_per_s"] = round(B / dt, 1)
+        extra["modup_effective_GBps"] = round(B * (L + dnum * D) * 8 * N / dt / 1e9, 1)   # L limbs read, dnum*(L+K) written
+        yin = up_out[:, :2].contiguous().reshape(B * 2, D, N)          # any residues below the primes will do
+        dn_out = torch.empty((B * 2, L, N), dtype=ct1.dtype, device=ct1.device)
+        dt = timed(lambda: ctx.moddown(yin, dn_out), label="moddown")
+        extra["moddown_per_s"] = round(B * 2 / dt, 1)
+        extra["moddown_effective_GBps"] = round(B * 2 * (D + L) * 8 * N / dt / 1e9, 1)
+        am_out = torch.empty_like(ct1)
+        for name, ev in (("automorph_eval", True), ("automorph_coeff", False)):
+            dt = timed(lambda: ctx.automorph(ct1, g, ev, 0, am_out), label=name)
+            extra[name + "_limbs_per_s"] = round(B * 2 * L / dt, 1)
+            extra[name + "_effective_GBps"] = round(B * 2 * L * 2 * 8 * N / dt / 1e9, 1)
+        del xin, up_out, yin, dn_out, am_out
+
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -415,6 +462,39 @@ def main():
                "sample": "%d HMult+relin and %d HRot of the same shape (1 ciphertext each, not the batch of 8), "
                          "OpenMP over limbs" % (n_each, n_each),
                "single_thread_value": round(2 / dt1, 3)}
+        # the other workload shapes, a few seconds each (same oracle, all cores): transforms of workload 1, hoisted
+        # rotations of workloads 3 and 4 (3 rotations each; the rate is per rotation), HMult of workload 0
+        other = {}
+        xs = h1[0][:16] if h1.shape[1] >= 16 else h1[0]
+        a2 = time.perf_counter()
+        oracle.ntt_batch(xs, P, 0)
+        oracle.ntt_batch(xs, P, 0, inverse=True)
+        other["ntt_limbs_per_s (workload 1 shape, %d limbs forward + inverse)" % xs.shape[0]] = round(2 * xs.shape[0] / (time.perf_counter() - a2), 1)
+        gs3 = [synth.galois_element(r_, ps.logN) for r_ in synth.CFG3_ROTATIONS[:3]]
+        a2 = time.perf_counter()
+        oracle.hrot_hoisted_mac(h1, gs3, [hr, hk, hr], np.ascontiguousarray(h2[0][None].repeat(3, 0)), P)
+        other["hoisted_rot_mac_per_s (workload 3 shape, 3 rotations)"] = round(3 / (time.perf_counter() - a2), 3)
+        ps0 = synth.CFG0
+        P0 = oracle.Params.from_set(ps0)
+        r0 = synth.rng_for(0, 100)
+        c0a = synth.uniform_residues(r0, ps0.q_primes, ps0.N, lead=(2,))
+        c0b = synth.uniform_residues(r0, ps0.q_primes, ps0.N, lead=(2,))
+        k0_ = synth.uniform_residues(r0, ps0.primes, ps0.N, lead=(ps0.dnum, 2))
+        a2 = time.perf_counter()
+        for _ in range(20):
+            oracle.hmult_relin(c0a, c0b, k0_, P0)
+        other["hmult_relin_per_s (workload 0 shape, N=2^12)"] = round(20 / (time.perf_counter() - a2), 1)
+        ps4 = synth.CFG4
+        P4 = oracle.Params.from_set(ps4)
+        r4 = synth.rng_for(4, 101)
+        c4 = synth.uniform_residues(r4, ps4.q_primes, ps4.N, lead=(2,))
+        k4 = synth.uniform_residues(r4, ps4.primes, ps4.N, lead=(ps4.dnum, 2))
+        p4 = synth.uniform_residues(r4, ps4.q_primes, ps4.N, lead=(2,))
+        gs4_ = [synth.galois_element(r_, ps4.logN) for r_ in synth.CFG4_ROTATIONS[:2]]
+        a2 = time.perf_counter()
+        oracle.hrot_hoisted_mac(c4, gs4_, [k4, k4], p4, P4)
+        other["hoisted_rot_mac_per_s (workload 4 shape, 2 rotations)"] = round(2 / (time.perf_counter() - a2), 3)
+        cpu["other_workloads"] = other
 
     line = {
         "metric": "key-switches/sec (HMult+relin, HRot) at N=2^16,L=24",
@@ -424,6 +504,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(ms_median, 4),
+        "startup_steps": STARTUP,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -433,6 +515,7 @@ def main():
                                "one step = batch of 8 HMult+relin + batch of 8 HRot (16 key switches)",
                    "batch": B, "key_switches_per_step": ks_per_step},
         "roofline": roofline,
+        "step_roofline": step_roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
         "extra": extra,

@@ -925,25 +925,20 @@ template <int DIR, bool FP>
 struct ConvTB {
     static constexpr int value = FP ? (DIR == CONV_UP ? CKKS_CONV_TB_UP_FP : CKKS_CONV_TB_DN_FP) : CKKS_CONV_TB_INT;
 };
-template <int DIR>
+// DG: the sources are digit-format words (only where the FpAr targets of the view go to the matrix-core kernel, so
+// only integer-arithmetic runs are launched with it)
+template <int DIR, bool DG>
 struct ConvL {
     template <class AR, int A>
     static void go(dim3 g, hipStream_t s, const ConvArgs& a, const Tables& tb, LimbRun run) {
-        // digit-format sources exist only where the FpAr targets go to the matrix-core kernel: integer targets only
-        if constexpr (!AR::is_fp) {
-            if (a.src_fmt == SRC_DIGITS) {
-                hipLaunchKernelGGL((conv_fwd_strided_kernel<AR, A, DIR, ConvTB<DIR, false>::value, true>), g, dim3(256), 0, s, a,
-                                   tb, run);
-                return;
-            }
-        }
-        hipLaunchKernelGGL((conv_fwd_strided_kernel<AR, A, DIR, ConvTB<DIR, AR::is_fp>::value>), g, dim3(256), 0, s, a, tb,
-                           run);
+        if constexpr (!(AR::is_fp && DG))
+            hipLaunchKernelGGL((conv_fwd_strided_kernel<AR, A, DIR, ConvTB<DIR, AR::is_fp>::value, DG>), g, dim3(256), 0, s, a, tb,
+                               run);
     }
     static std::string name(const char* ar, int A) {
         const int tbv = ar[0] == 'F' ? ConvTB<DIR, true>::value : ConvTB<DIR, false>::value;
         return kname("conv_fwd_strided_kernel", ar, A,
-                     (std::string(", ") + std::to_string(DIR) + ", " + std::to_string(tbv)).c_str());
+                     (std::string(", ") + std::to_string(DIR) + ", " + std::to_string(tbv) + (DG ? ", true" : ", false")).c_str());
     }
 };
 struct FwdContigL {
@@ -1047,18 +1042,21 @@ static void launch_conv(const View* c, const ConvArgs& a, hipStream_t s) {
     const u64 outer = a.groups_outer;
     const int only = conv_on_matrix_cores(c, DIR) ? 0 : -1;  // FpAr targets go to the matrix-core kernel when the view has tiles
     if (only == 0) launch_conv_mfma<DIR>(c, a, s);
+    const u32 tbs = ConvTB<DIR, true>::value | (ConvTB<DIR, false>::value << 16);
     if (DIR == CONV_UP) {  // groups = (batch, digit, tile); instances = blocks of the run's target primes
-        launch_runs<ConvL<DIR>>(c, 0, c->D, 0, false, a.groups_outer * c->dnum * tiles_of(c),
-                                ConvTB<DIR, true>::value | (ConvTB<DIR, false>::value << 16), a, s,
-                                [c, outer](u32 first, u32 n) {
-                                    u64 w = 0;  // every target limb is written for each digit that does not own it
-                                    for (u32 t = first; t < first + n; t++) w += c->dnum - (t < c->L ? 1 : 0);
-                                    return outer * (w + c->L);  // plus the source coefficients, read once
-                                }, only);
+        auto alg = [c, outer](u32 first, u32 n) {
+            u64 w = 0;  // every target limb is written for each digit that does not own it
+            for (u32 t = first; t < first + n; t++) w += c->dnum - (t < c->L ? 1 : 0);
+            return outer * (w + c->L);  // plus the source coefficients, read once
+        };
+        const u32 groups = a.groups_outer * c->dnum * tiles_of(c);
+        if (a.src_fmt == SRC_DIGITS) launch_runs<ConvL<DIR, true>>(c, 0, c->D, 0, false, groups, tbs, a, s, alg, only);
+        else launch_runs<ConvL<DIR, false>>(c, 0, c->D, 0, false, groups, tbs, a, s, alg, only);
     } else {  // groups = (g, tile); instances = blocks of the run's target q-limbs
-        launch_runs<ConvL<DIR>>(c, 0, c->L, 0, false, a.groups_outer * tiles_of(c),
-                                ConvTB<DIR, true>::value | (ConvTB<DIR, false>::value << 16), a, s,
-                                [c, outer](u32, u32 n) { return outer * (n + (u64)c->K); }, only);
+        auto alg = [c, outer](u32, u32 n) { return outer * (n + (u64)c->K); };
+        const u32 groups = a.groups_outer * tiles_of(c);
+        if (a.src_fmt == SRC_DIGITS) launch_runs<ConvL<DIR, true>>(c, 0, c->L, 0, false, groups, tbs, a, s, alg, only);
+        else launch_runs<ConvL<DIR, false>>(c, 0, c->L, 0, false, groups, tbs, a, s, alg, only);
     }
 }
 

@@ -509,7 +509,7 @@ def test_repeat_runs_are_bit_identical_and_profile_counts_launches(orc):
     # the ModDown conversion (2..8 sources) of FP64 targets runs on the matrix cores: <log2 N - 8, products, direction, ..>
     hits = [v for k, v in prof.items() if k.startswith("conv_mfma_kernel<5, ") and k.split(", ")[2] == "2"]
     assert len(hits) == 1 and hits[0][0] == 3
-    assert prof["conv_fwd_strided_kernel<FpAr, 5, 1, 3>"][0] == 3 and prof["conv_fwd_strided_kernel<IntAr, 5, 1, 2>"][0] == 3
+    assert prof["conv_fwd_strided_kernel<FpAr, 5, 1, 3, false>"][0] == 3 and prof["conv_fwd_strided_kernel<IntAr, 5, 1, 2, false>"][0] == 3
     assert not any(k.startswith("conv_fwd_strided_kernel<FpAr, 5, 2") for k in prof)
     assert all(n > 0 and ms > 0 and b > 0 for n, ms, b in prof.values())
 

@@ -1,5 +1,5 @@
-"""The per-launch counters that bench.py uses for `roofline.traffic` and the issue fractions are copies of the
-committed rocprofv3 summary: this keeps the two from drifting apart."""
+"""bench.py takes the per-launch counters behind `roofline.traffic`, the issue fractions and `step_roofline` from the
+committed rocprofv3 summary; these checks keep the parser, the two summaries and the kernel names in step."""
 import importlib.util
 import os
 import re
@@ -14,18 +14,19 @@ def _bench_module():
     return mod
 
 
-def test_measured_table_matches_the_committed_counter_summary():
+def test_counter_table_is_read_from_the_committed_summary():
     bench = _bench_module()
-    rows = {}
-    with open(os.path.join(ROOT, "profiles", "keyswitch_step_n16_l24_d4_hbm_traffic.txt")) as f:
-        for line in f:
-            m = re.match(r"^(\S.*?>)\s+([\d.]+)\s+([\d.]+)\s+(\d+)\s+(\d+)\s+(\d+)\s*$", line)
-            if m:
-                rows[m.group(1)] = (float(m.group(2)), float(m.group(3)), int(m.group(5)))
-    assert set(rows) == set(bench.MEASURED), "kernel lists differ"
-    for name, (rd, wr, insts) in bench.MEASURED.items():
-        prd, pwr, pinsts = rows[name]
-        assert abs(rd - prd) < 0.05 and abs(wr - pwr) < 0.05 and insts == pinsts, name
+    rows = bench.load_counter_table()
+    assert rows and rows == bench.MEASURED
+    assert os.path.exists(os.path.join(ROOT, bench.TRAFFIC_SOURCE))
+    for name, (rd, wr, insts) in rows.items():
+        assert re.match(r"^[a-z_]+<.*>$", name), name
+        assert 0 < rd < 4096 and 0 < wr < 4096 and insts > 100000, name
+    # the kernels of the default step: both conversions, both inner products, both final combines
+    for frag in ("conv_fwd_strided_kernel<FpAr, 8, 1", "conv_mfma_kernel<8,", "ks_inner_kernel<FpAr, 8, 1", "ks_inner_kernel<IntAr, 8, 2",
+                 "ks_final_kernel<FpAr, 8, 1", "ks_final_kernel<FpAr, 8, 2", "inv_contig_kernel<FpAr, 8, 1", "inv_strided_kernel<IntAr, 8"):
+        assert any(k.startswith(frag) for k in rows), frag
+    assert bench.load_counter_table(os.path.join(ROOT, "no_such_file")) == {}
 
 
 def test_kernel_stats_summary_lists_the_same_kernels():
