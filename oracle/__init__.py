@@ -5,7 +5,9 @@ package; the HIP library and its binding never do.  Besides thin wrappers of the
 functions it holds the harness-side steps the key-switch path itself does not
 export: lifting a small signed polynomial to RNS limbs, switching-key
 generation (from random draws handed in by the caller) and the
-decrypt-and-bound noise check.
+decrypt-and-bound noise check; and the canonical-embedding encoding of slot vectors and of the
+diagonals of a matrix, which turns the baby-step giant-step call into a matrix-vector product on the
+slots (the shape of the CoeffToSlot / SlotToCoeff stages behind the paper's Table 1 "Boot" rows).
 """
 from __future__ import annotations
 
@@ -495,6 +497,22 @@ def centred_small(x_eval: np.ndarray, P: Params, n_limbs: int) -> np.ndarray:
     return ref
 
 
+def crt_centred(x_eval: np.ndarray, P: Params, n_limbs: int) -> list:
+    """INTT the first n_limbs limbs and reconstruct every coefficient modulo their product with big integers,
+    centred to (-Q/2, Q/2]: for values that are small against the product but not against a single limb."""
+    c = ntt_batch(np.ascontiguousarray(x_eval[:n_limbs]), P, 0, inverse=True)
+    primes = [int(p) for p in P.primes[:n_limbs]]
+    Q = 1
+    for p in primes:
+        Q *= p
+    lift = [(Q // p) * pow(Q // p, -1, p) for p in primes]
+    out = []
+    for k in range(c.shape[1]):
+        v = sum(int(c[i, k]) * lift[i] for i in range(n_limbs)) % Q
+        out.append(v - Q if v > Q // 2 else v)
+    return out
+
+
 def keyswitch_noise(d: np.ndarray, ks: np.ndarray, s_hat: np.ndarray, sp_hat: np.ndarray, P: Params,
                     level: Optional[int] = None) -> np.ndarray:
     """E = ks0 + ks1*s - d*s'  over the (active) q-limbs, as centred integer coefficients (must be small)."""
@@ -521,3 +539,69 @@ def keyswitch_noise_bound(P: Params, s_l1: int, level: Optional[int] = None) -> 
         maxQ = max(maxQ, Qj)
     first = -((-(beta * P.N * P.alpha * maxQ * 19)) // Pprod)
     return first + P.K * (1 + s_l1) + 1
+
+
+# ------------------------------------------------- canonical embedding (encoding of slot vectors)
+# The CKKS plaintext space (the scheme of the paper's Section 2): a real polynomial m of degree < N is
+# identified with its values at zeta_j = exp(i*pi*5^j / N), j < N/2 (one of each conjugate pair of roots
+# of X^N + 1) -- the "slots".  X -> X^(5^r) permutes these roots, zeta_j -> zeta_(j+r), so the automorphism
+# with Galois element 5^r rotates the slot vector by r places.  Plain O(N^2) definitions in complex128;
+# nothing here is shared with the HIP library, which never encodes.
+def slot_roots(logN: int) -> np.ndarray:
+    """zeta_j = exp(i*pi*(5^j mod 2N)/N) for j < N/2."""
+    n = 1 << logN
+    e = np.array([pow(5, j, 2 * n) for j in range(n // 2)], dtype=np.float64)
+    return np.exp(1j * np.pi * e / n)
+
+
+def encode(z: np.ndarray, scale: float, logN: int) -> np.ndarray:
+    """Slot vector z [N/2] complex -> integer coefficients [N] (int64) of the real polynomial with
+    m(zeta_j) = scale * z_j, rounded to nearest: m_k = round(scale * (2/N) * Re(sum_j z_j * conj(zeta_j)^k))."""
+    n = 1 << logN
+    z = np.asarray(z, dtype=np.complex128)
+    assert z.shape == (n // 2,)
+    zeta = slot_roots(logN)
+    k = np.arange(n, dtype=np.float64)
+    # conj(zeta_j)^k, as exp(-i * k * angle_j) to avoid the error growth of repeated products
+    ang = np.angle(zeta)
+    w = np.exp(-1j * np.outer(k, ang))            # [N][N/2]
+    m = (2.0 / n) * np.real(w @ z) * scale
+    return np.rint(m).astype(np.int64)
+
+
+def decode(coeffs: np.ndarray, scale: float, logN: int) -> np.ndarray:
+    """Integer coefficients [N] -> slot vector [N/2]: z_j = m(zeta_j) / scale."""
+    n = 1 << logN
+    c = np.asarray(coeffs, dtype=np.float64)
+    ang = np.angle(slot_roots(logN))
+    w = np.exp(1j * np.outer(ang, np.arange(n, dtype=np.float64)))   # zeta_j^k, [N/2][N]
+    return (w @ c) / scale
+
+
+def encode_limbs(z: np.ndarray, scale: float, P: Params, limb_primes: Sequence[int], limb_psi: Sequence[int]) -> np.ndarray:
+    """encode(), lifted to the given RNS limbs and transformed to evaluation form: [len(limb_primes)][N]."""
+    lifted = lift_signed(encode(z, scale, P.logN), limb_primes)
+    return np.stack([ntt(lifted[i], P.logN, int(m), int(w)) for i, (m, w) in enumerate(zip(limb_primes, limb_psi))])
+
+
+def matrix_diagonal(M: np.ndarray, d: int) -> np.ndarray:
+    """Generalised diagonal d of an n x n matrix: diag_d[j] = M[j][(j + d) mod n], so that
+    M z = sum_d diag_d * rot_d(z) with rot_d(z)[j] = z[(j + d) mod n]."""
+    n = M.shape[0]
+    j = np.arange(n)
+    return M[j, (j + d) % n]
+
+
+def bsgs_diagonal_plaintexts(M: np.ndarray, n1: int, n2: int, scale: float, P: Params, level: int) -> np.ndarray:
+    """Plaintexts [n2][n1][level+K][N] that make lintrans_bsgs_level (baby rotations 0..n1-1, giant rotations
+    0, n1, .., (n2-1)*n1) evaluate z -> M z on the slots, for a matrix whose non-zero diagonals are 0 .. n1*n2-1:
+      M z = sum_g rot_{g*n1}( sum_b rot_{-g*n1}(diag_{g*n1+b}) * rot_b(z) ),
+    so plaintext (g, b) encodes diagonal g*n1 + b rotated by -g*n1."""
+    basis = list(P.primes[:level]) + list(P.primes[P.L:])
+    psis = list(P.psi[:level]) + list(P.psi[P.L:])
+    out = np.empty((n2, n1, len(basis), P.N), dtype=np.uint64)
+    for g in range(n2):
+        for b in range(n1):
+            diag = np.roll(matrix_diagonal(M, g * n1 + b), g * n1)   # rot_{-g*n1}: entry j takes entry j - g*n1
+            out[g, b] = encode_limbs(diag, scale, P, basis, psis)
+    return out

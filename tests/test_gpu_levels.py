@@ -369,6 +369,56 @@ def test_bsgs_linear_transform_parity(orc, shape, n1, n2):
         assert np.array_equal(got, want), ell
 
 
+@pytest.mark.timeout(600)
+def test_bsgs_with_encoded_diagonals_is_a_matrix_vector_product(orc):
+    """Real diagonals instead of random residues: a band matrix with 32 non-zero (generalised) diagonals on the 2048
+    slots of N = 4096, encoded by the oracle's canonical embedding, true rotation keys, a fresh encryption of z.
+    The library's baby-step giant-step call equals the oracle's word for word, and what it returns decrypts and
+    decodes to M z."""
+    ps = synth.small_params(12, 4, 2, 2, 49, 59)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(4242)
+    N, n, ell = ps.N, ps.N // 2, ps.L
+    n1, n2 = 8, 4
+    scale = scale_pt = float(1 << 30)
+    s = synth.ternary_hamming(rng, N, 64)
+    s_hat = orc.secret_eval(s, P)
+    diags = (rng.uniform(-1, 1, (n1 * n2, n)) + 1j * rng.uniform(-1, 1, (n1 * n2, n))) / np.sqrt(2)
+    M = np.zeros((n, n), dtype=np.complex128)
+    j = np.arange(n)
+    for d in range(n1 * n2):
+        M[j, (j + d) % n] = diags[d]
+    z = (rng.uniform(-1, 1, n) + 1j * rng.uniform(-1, 1, n)) / np.sqrt(2)
+    baby = [synth.galois_element(b, ps.logN) for b in range(n1)]
+    giant = [synth.galois_element(g * n1, ps.logN) for g in range(n2)]
+    _say("encoded diagonals: keys")
+    baby_rks = [make_keys(orc, ps, P, rng, s_hat, orc.automorph_limbs(s_hat, P, 0, g, True)) for g in baby]
+    giant_rks = [make_keys(orc, ps, P, rng, s_hat, orc.automorph_limbs(s_hat, P, 0, g, True)) for g in giant]
+    q = list(ps.q_primes)
+    sq = s_hat[:ell]
+    _say("encoded diagonals: encode")
+    m_hat = orc.encode_limbs(z, scale, P, q, P.psi[:ell])
+    a = synth.uniform_residues(rng, q, N)
+    e_hat = orc.ntt_batch(orc.lift_signed(synth.gaussian_error(rng, (N,)), q), P, 0)
+    b = orc.pointwise("add", orc.pointwise("sub", m_hat, orc.pointwise("mul", a, sq, q), q), e_hat, q)
+    ct = np.stack([b, a])
+    pt = orc.bsgs_diagonal_plaintexts(M, n1, n2, scale_pt, P, ell)
+    _say("encoded diagonals: gpu")
+    got = host(ctx.lintrans_bsgs_at(ell, dev(ct), baby, [dev(k) for k in baby_rks], giant, [dev(k) for k in giant_rks], dev(pt)))
+    _say("encoded diagonals: oracle")
+    assert np.array_equal(got, orc.lintrans_bsgs_level(ct, baby, baby_rks, giant, giant_rks, pt, P))
+    dec = orc.pointwise("add", got[0], orc.pointwise("mul", got[1], sq, q), q)
+    slots = orc.decode(np.array(orc.crt_centred(dec, P, ell), dtype=np.float64), scale * scale_pt, ps.logN)
+    # worst-case slot error, as in the CPU pin of the oracle: a coefficient error c moves a slot by at most N * c; every
+    # slot sums 32 products of values of modulus <= 1 (message rounding 1/2 and encryption error <= 19 per coefficient,
+    # diagonal rounding 1/2), plus the key-switch noise of the call
+    h = int(np.abs(s).sum())
+    l1 = [sum(int(np.abs(orc.centred_small(pt[g, bb], P, ell)).sum()) for bb in range(n1)) for g in range(n2)]
+    noise = sum(orc.dh_mac_noise_bound(P, h, t, level=ell) for t in l1) + n2 * orc.keyswitch_noise_bound(P, h, level=ell)
+    tol = n1 * n2 * (N / 2 + 19 * N) / scale + n1 * n2 * (N / 2) / scale_pt + N * noise / (scale * scale_pt)
+    assert np.abs(slots - M @ z).max() <= tol < 0.01
+
+
 @pytest.mark.timeout(900)
 def test_bsgs_linear_transform_full_size(orc):
     """N = 2^16, L = 24, K = 6, dnum = 4: 8 baby steps x 4 giant steps (32 diagonals) at level 24."""

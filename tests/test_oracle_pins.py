@@ -877,3 +877,93 @@ def test_level_functions_at_the_full_level_equal_the_full_level_functions(orc):
     gs = [g, synth.galois_element(-1, ps.logN)]
     pt = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2,))
     assert np.array_equal(orc.hrot_hoisted_mac_level(ct1, gs, [key, key], pt, P), orc.hrot_hoisted_mac(ct1, gs, [key, key], pt, P))
+
+
+# --------------------------------------------------- encoded diagonals: matrix-vector products on the slots
+def _centred(limb, q):
+    v = limb.astype(np.int64)
+    return np.where(limb > np.uint64(q // 2), v - q, v)
+
+
+def test_canonical_embedding_pins(orc):
+    """encode/decode against what fixes them: the evaluation points are roots of X^N + 1, a constant slot vector is
+    a constant polynomial, decode inverts encode within the rounding bound, the embedding is multiplicative
+    (big-integer negacyclic product), and the automorphism with Galois element 5^r rotates the slots by r
+    (2N - 1 conjugates them) -- the convention every rotation key and diagonal below relies on."""
+    logN, scale = 5, float(1 << 30)
+    n = 1 << logN
+    zeta = orc.slot_roots(logN)
+    assert np.abs(zeta ** n + 1).max() < 1e-12 and len(set(np.round(zeta, 9))) == n // 2
+    assert np.abs(np.abs(np.subtract.outer(zeta, np.conj(zeta)))).min() > 1e-3          # one of each conjugate pair
+    m = orc.encode(np.full(n // 2, 0.75), scale, logN)
+    assert m[0] == int(0.75 * scale) and not m[1:].any()
+    rng = np.random.default_rng(11)
+    z = rng.uniform(-1, 1, n // 2) + 1j * rng.uniform(-1, 1, n // 2)
+    w = rng.uniform(-1, 1, n // 2) + 1j * rng.uniform(-1, 1, n // 2)
+    mz, mw = orc.encode(z, scale, logN), orc.encode(w, scale, logN)
+    # rounding moves every coefficient by at most 1/2, a slot by at most N/2
+    assert np.abs(orc.decode(mz, scale, logN) - z).max() <= n / 2 / scale
+    prod = negacyclic_schoolbook([int(v) for v in mz], [int(v) for v in mw], 1 << 200)
+    prod = [v - (1 << 200) if v >> 199 else v for v in prod]
+    got = orc.decode(np.array(prod, dtype=np.float64), scale * scale, logN)
+    assert np.abs(got - z * w).max() <= 4 * n / scale
+    q = synth.primes_above(1 << 49, 2 * n, 1)[0]
+    lifted = orc.lift_signed(mz, [q])[0]
+    for r in (1, 3, -1, n // 4):
+        rot = _centred(orc.automorph_coeff(lifted, logN, q, synth.galois_element(r, logN)), q)
+        assert np.abs(orc.decode(rot, scale, logN) - np.roll(z, -r)).max() <= n / scale, r
+    conj = _centred(orc.automorph_coeff(lifted, logN, q, 2 * n - 1), q)
+    assert np.abs(orc.decode(conj, scale, logN) - np.conj(z)).max() <= n / scale
+    # diagonals: M z = sum_d diag_d * rot_d(z)
+    M = rng.uniform(-1, 1, (n // 2, n // 2))
+    acc = sum(orc.matrix_diagonal(M, d) * np.roll(z, -d) for d in range(n // 2))
+    assert np.abs(acc - M @ z).max() < 1e-12
+
+
+def test_bsgs_with_encoded_diagonals_is_the_matrix_vector_product(orc):
+    """A dense 32 x 32 complex matrix on the 32 slots of N = 64, cut into 8 x 4 diagonals and encoded: the baby-step
+    giant-step call on an encryption of z decrypts and decodes to M z within the stated error (rounding of the two
+    encodings, the fresh encryption error, and the key-switch noise bound of the call)."""
+    ps = _small_set(6, 4, 2, 2, 49, 59)
+    P, rng, s, s_hat = _setup(orc, ps, 77)
+    h = int(np.abs(s).sum())
+    N, n = ps.N, ps.N // 2
+    n1, n2 = 8, 4
+    scale = scale_pt = float(1 << 25)
+    M = (rng.uniform(-1, 1, (n, n)) + 1j * rng.uniform(-1, 1, (n, n))) / np.sqrt(2)      # entries of modulus <= 1
+    z = (rng.uniform(-1, 1, n) + 1j * rng.uniform(-1, 1, n)) / np.sqrt(2)
+    baby = [synth.galois_element(b, ps.logN) for b in range(n1)]
+    giant = [synth.galois_element(g * n1, ps.logN) for g in range(n2)]
+    baby_rks = [_keys(orc, ps, P, rng, orc.automorph_limbs(s_hat, P, 0, g, True), s_hat)[0] for g in baby]
+    giant_rks = [_keys(orc, ps, P, rng, orc.automorph_limbs(s_hat, P, 0, g, True), s_hat)[0] for g in giant]
+    for ell in (ps.L, 3):
+        q = list(ps.q_primes[:ell])
+        sq = s_hat[:ell]
+        # fresh encryption of encode(z): b = -a*s + m + e
+        m_hat = orc.encode_limbs(z, scale, P, q, P.psi[:ell])
+        a = synth.uniform_residues(rng, q, N)
+        e = synth.gaussian_error(rng, (N,))
+        e_hat = orc.ntt_batch(orc.lift_signed(e, q), P, 0)
+        b = orc.pointwise("add", orc.pointwise("sub", m_hat, orc.pointwise("mul", a, sq, q), q), e_hat, q)
+        ct = np.stack([b, a])
+        pt = orc.bsgs_diagonal_plaintexts(M, n1, n2, scale_pt, P, ell)
+        out = orc.lintrans_bsgs_level(ct, baby, baby_rks, giant, giant_rks, pt, P)
+        dec = orc.pointwise("add", out[0], orc.pointwise("mul", out[1], sq, q), q)
+        coeffs = orc.crt_centred(dec, P, ell)                    # about 2^55: small against Q, not against one limb
+        assert max(abs(v) for v in coeffs) < (1 << 60)
+        got = orc.decode(np.array(coeffs, dtype=np.float64), scale * scale_pt, ps.logN)
+        # l1 norms of the encoded diagonals, per giant step, for the noise bound of the double-hoisted sums
+        basis = q + list(ps.p_primes)
+        l1 = []
+        for g in range(n2):
+            tot = 0
+            for bb in range(n1):
+                tot += int(np.abs(orc.centred_small(pt[g, bb], P, ell)).sum())
+            l1.append(tot)
+        noise = sum(orc.dh_mac_noise_bound(P, h, t, level=ell) for t in l1) + n2 * orc.keyswitch_noise_bound(P, h, level=ell)
+        # slot-domain error: a coefficient error c moves a slot by at most N*c; every slot sums n products
+        tol = n * (N / 2 + 19 * N) / scale + n * (N / 2) / scale_pt + N * noise / (scale * scale_pt)
+        err = np.abs(got - M @ z).max()
+        assert err <= tol < 0.01, (ell, err, tol)
+        assert err > 0
+        del basis
