@@ -180,7 +180,7 @@ static RescaleLayout rescale_layout(size_t base, u32 ell) {
 
 // ModDown merged with the rescale after it, from level ell: sources q_{ell-1}, p_0..p_{K-1}; targets q_0..q_{ell-2}
 struct MergedLayout {
-    size_t sc_dn, dn_chat, dn_chat_fp, dn_fp_ok, pinv, qlinv, dn_tiles, dn_aop, end;
+    size_t sc_dn, dn_chat, dn_chat_fp, dn_fp_ok, pinv, dn_tiles, dn_aop, end;
 };
 static MergedLayout merged_layout(size_t base, u32 ell, u32 K) {
     const size_t T = ell - 1, S = K + 1;
@@ -191,7 +191,6 @@ static MergedLayout merged_layout(size_t base, u32 ell, u32 K) {
     l.dn_chat_fp = t.take(S * T * sizeof(double));
     l.dn_fp_ok = t.take(T * sizeof(u32));
     l.pinv = t.take(T * sizeof(PinvConst));
-    l.qlinv = t.take(T * sizeof(PinvConst));
     l.dn_tiles = t.take(mfma_tile_bound(T) * sizeof(ConvTile));
     l.dn_aop = t.take(mfma_tile_bound(T) * mfma_ks(S) * 128 * sizeof(u64));
     l.end = t.o;
@@ -645,7 +644,6 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         tb.dn_fp_ok = (const u32*)(dbase + ll.dn_fp_ok);
         tb.pinv = (const PinvConst*)(dbase + ll.pinv);
         tb.pmod = (const u64*)(dbase + ll.pmod);
-        tb.qlinv = nullptr;
         tb.up_tiles = (const ConvTile*)(dbase + ll.up_tiles), tb.up_aop = (const u64*)(dbase + ll.up_aop);
         tb.dn_tiles = (const ConvTile*)(dbase + ll.dn_tiles), tb.dn_aop = (const u64*)(dbase + ll.dn_aop);
         tb.up_ntiles = up_nt, tb.up_tstride = up_bound, tb.up_ks = up_ks, tb.dn_ntiles = dn_nt, tb.dn_ks = dn_ks;
@@ -701,7 +699,6 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         double* dn_chat_fp = (double*)(hb + ml.dn_chat_fp);
         u32* dn_fp_ok = (u32*)(hb + ml.dn_fp_ok);
         PinvConst* pinv = (PinvConst*)(hb + ml.pinv);
-        PinvConst* qlinv = (PinvConst*)(hb + ml.qlinv);
         for (u32 k = 0; k < S; k++) {
             const u64 sk = src[k];
             const u64 hinv = h_invmod(prod_except(src, k, sk), sk);
@@ -717,8 +714,6 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
             dn_fp_ok[i] = (pc[i].fp && qi >= (1ull << 28)) ? 1 : 0;
             const u64 pi = h_invmod(prod_except(src, src.size(), qi), qi);
             pinv[i] = PinvConst{pi, h_shoup(pi, qi), (double)pi};
-            const u64 ql = h_invmod(src[0] % qi, qi);
-            qlinv[i] = PinvConst{ql, h_shoup(ql, qi), (double)ql};
         }
         u32 dn_nt = 0;
         const u32 dn_ks = mfma_ks(S);
@@ -743,7 +738,6 @@ extern "C" int ckks_ctx_create(ckks_ctx** out, uint32_t logN, uint32_t L, uint32
         tb.dn_chat_fp = (const double*)(dbase + ml.dn_chat_fp);
         tb.dn_fp_ok = (const u32*)(dbase + ml.dn_fp_ok);
         tb.pinv = (const PinvConst*)(dbase + ml.pinv);
-        tb.qlinv = (const PinvConst*)(dbase + ml.qlinv);
         tb.dn_tiles = (const ConvTile*)(dbase + ml.dn_tiles), tb.dn_aop = (const u64*)(dbase + ml.dn_aop);
         tb.dn_ntiles = dn_nt, tb.dn_ks = dn_ks;
         tb.L = T, tb.K = S, tb.dnum = 1, tb.alpha = T, tb.D = ell + K, tb.Lfull = L, tb.Lq = ell;
@@ -948,15 +942,16 @@ struct FwdContigL {
     }
     static std::string name(const char* ar, int A) { return kname("fwd_contig_kernel", ar, A, ""); }
 };
-template <int OWN, bool HOISTED>
+template <int OWN, bool HOISTED, bool FUSED>
 struct KsInnerL {
     template <class AR, int A>
     static void go(dim3 g, hipStream_t s, const InnerArgs& a, const Tables& tb, LimbRun run) {
-        hipLaunchKernelGGL((ks_inner_kernel<AR, A, OWN, HOISTED>), g, dim3(256), 0, s, a, tb, run);
+        hipLaunchKernelGGL((ks_inner_kernel<AR, A, OWN, HOISTED, FUSED>), g, dim3(256), 0, s, a, tb, run);
     }
     static std::string name(const char* ar, int A) {
         return kname("ks_inner_kernel", ar, A,
-                     (std::string(", ") + std::to_string(OWN) + (HOISTED ? ", true" : ", false")).c_str());
+                     (std::string(", ") + std::to_string(OWN) + (HOISTED ? ", true" : ", false") + (FUSED ? ", true" : ", false"))
+                         .c_str());
     }
 };
 template <int MODE>
@@ -1067,21 +1062,28 @@ static void launch_fwd_contig(const View* c, const FwdContigArgs& a, hipStream_t
                             [per](u32, u32 n) { return per * n; });
 }
 
-template <int OWN, bool HOISTED>
-static void launch_ks_inner(const View* c, const InnerArgs& a, hipStream_t s) {
+// limbs [lo, hi) of the extended basis.  FUSED: the launch also ends the ModDown on its limbs (all below
+// a.split, after the conversion of the special part) and writes the result instead of c'.
+template <int OWN, bool HOISTED, bool FUSED = false>
+static void launch_ks_inner(const View* c, const InnerArgs& a, hipStream_t s, u32 lo, u32 hi) {
     const u64 n_inst = a.n_inst;
-    launch_runs<KsInnerL<OWN, HOISTED>>(
-        c, 0, c->D, 0, true, tiles_of(c), a.n_inst, a, s, [c, n_inst](u32 first, u32 n) {
+    launch_runs<KsInnerL<OWN, HOISTED, FUSED>>(
+        c, lo, hi, 0, true, tiles_of(c), a.n_inst, a, s, [c, n_inst](u32 first, u32 n) {
             u64 limbs = 0;
             for (u32 i = first; i < first + n; i++) {
                 const bool q = i < c->L;
                 limbs += n_inst * ((u64)c->dnum - (q ? 1 : 0)            // extended digits outside their own limbs
-                                   + (q ? (OWN == OWN_TENSOR ? 2 : 1) : 0)  // the switched polynomial on its own limb
-                                   + 2)                                    // c' written
+                                   + (q ? (OWN == OWN_TENSOR ? 4 : 1) : 0)  // the switched polynomial (HMult: both inputs) on its own limb
+                                   + 2                                     // c' (or the result) written
+                                   + (FUSED ? 2 + (OWN == OWN_ROT ? 1 : 0) : 0))  // converted special part (+ sigma_g(b))
                          + (HOISTED ? n_inst : 1) * 2 * (u64)c->dnum;      // key limbs
             }
             return limbs;
         });
+}
+template <int OWN, bool HOISTED>
+static void launch_ks_inner(const View* c, const InnerArgs& a, hipStream_t s) {
+    launch_ks_inner<OWN, HOISTED, false>(c, a, s, 0, c->D);
 }
 
 #define CKKS_DH_EPT 4
@@ -1135,7 +1137,7 @@ template <int MODE>
 static void launch_ks_final(const View* c, const FinalArgs& a, hipStream_t s) {
     u64 per;  // algorithmic limbs per q-limb
     if (MODE == FIN_HOISTED) per = (u64)a.n_rot * (2 + 2 + 1 + 1) + (2 + (a.accumulate ? 2 : 0));
-    else per = (u64)a.n_inst * (6 + (MODE == FIN_HMULT ? 4 : MODE == FIN_HROT ? 1 : 0));
+    else per = (u64)a.n_inst * (6 + (MODE == FIN_HROT ? 1 : 0));
     launch_runs<KsFinalL<MODE>>(c, 0, c->L, 0, true, tiles_of(c), a.n_inst, a, s, [per](u32, u32 n) { return per * n; });
 }
 
@@ -1470,6 +1472,9 @@ static void moddown_convert(const View* c, const Workspace& w, u32 cg, hipStream
 // cm: the view whose ModDown ends the pipeline: c itself, or the merged view of c's level (the ModDown then
 // also divides by the last q-limb: limb c->L - 1 joins the special limbs and the output has c->L - 1 limbs)
 // multi_galois / multi_keys (rotations only, batch <= CKKS_ROT_CHUNK): one Galois element and key per instance.
+#ifndef CKKS_FUSED_FINAL
+#define CKKS_FUSED_FINAL 1
+#endif
 template <int LOAD, int OWN, int FIN>
 static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, const u64* in2, const u64* key, u64* out,
                                u32 batch, u32 galois, void* ws, hipStream_t s, const u32* multi_galois = nullptr,
@@ -1497,12 +1502,21 @@ static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, co
     launch_inv_contig<LOAD>(c, a1, s);
     decompose_extend(c, w, batch, s);
     ia.dt = w.dt, ia.own = in1, ia.own2 = in2;
-    ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = batch, ia.split = cm->L, ia.add_tensor = cm != c;
+    ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = batch, ia.split = cm->L;
+#if CKKS_FUSED_FINAL
+    // the limbs that feed the ModDown conversion first; the q-limbs then finish in one kernel, c' in registers
+    launch_ks_inner<OWN, false, false>(c, ia, s, cm->L, c->D);
+    moddown_convert(cm, w, batch, s);
+    ia.cv = w.cv, ia.out = out, ia.fin_pinv = cm->tb.pinv;
+    launch_ks_inner<OWN, false, true>(c, ia, s, 0, cm->L);
+    (void)fa;
+#else
     launch_ks_inner<OWN, false>(c, ia, s);
     moddown_convert(cm, w, batch, s);
-    fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = in1, fa.ct2 = in2, fa.out = out, fa.n_inst = batch;
+    fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = in1, fa.out = out, fa.n_inst = batch;
     fa.cq_L = cm->L, fa.in_L = c->L;
     launch_ks_final<FIN>(cm, fa, s);
+#endif
 }
 
 extern "C" int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_d, const uint64_t* d_key,
@@ -1531,7 +1545,7 @@ extern "C" int ckks_hmult_relin_at(ckks_ctx* ctx, uint32_t level, const uint64_t
     const size_t ctb = limb_bytes(c, (size_t)batch * 2 * c->L);
     rc = check_no_alias(c, d_out, ctb, d_ct1, ctb, d_ct2, ctb, d_ws, ws_bytes);
     if (rc) return rc;
-    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT>(c, c, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
+    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_KS>(c, c, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
                                                           (hipStream_t)stream);
     return hip_check(c, "ckks_hmult_relin");
 }
@@ -1549,7 +1563,7 @@ extern "C" int ckks_hmult_relin_rescale_at(ckks_ctx* ctx, uint32_t level, const 
     const size_t ctb = limb_bytes(c, (size_t)batch * 2 * c->L);
     rc = check_no_alias(c, d_out, limb_bytes(c, (size_t)batch * 2 * (c->L - 1)), d_ct1, ctb, d_ct2, ctb, d_ws, ws_bytes);
     if (rc) return rc;
-    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_HMULT_RS>(c, &ctx->merged[level], d_ct1, d_ct2, d_evk, d_out, batch, 1,
+    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_KS>(c, &ctx->merged[level], d_ct1, d_ct2, d_evk, d_out, batch, 1,
                                                              d_ws, (hipStream_t)stream);
     return hip_check(c, "ckks_hmult_relin_rescale");
 }

@@ -43,7 +43,6 @@ struct Tables {
     const u32* dn_fp_ok;       // [L]  1 if q_i may convert on the FP64 pipe (FpAr prime, at least 2^28)
     const PinvConst* pinv;     // [L]     P^-1 mod q_i
     const u64* pmod;           // [L]     P mod q_i
-    const PinvConst* qlinv;    // [L]     q_L^-1 mod q_i where limb L is the first source of a merged ModDown
     // conversion on the matrix cores (conv_mfma_kernel): target tiles and constant operands per digit; n_tiles = 0
     // when the view does not use it (fewer than 2 or more than 8 sources, or no FpAr target)
     const struct ConvTile* up_tiles;  // [dnum][up_tstride]
@@ -210,7 +209,8 @@ template <class AR, int A>
 __device__ __forceinline__ void fwd_strided_finish(typename AR::T (&x)[16], const Tables& tb, u64* lds, u32 vi,
                                                    u64* dst, u32 tile) {
     typedef NttCore<AR, A> C;
-    const u32 N = 1u << tb.logN, tid = threadIdx.x, pi = tb.phys(vi);
+    const u32 N = 1u << tb.logN, pi = tb.phys(vi);
+    const u32 tid = threadIdx.x;
     const typename AR::Mod m = AR::mod(tb.pc[pi]);
     const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
     const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
@@ -732,11 +732,14 @@ struct InnerArgs {
     u32 n_inst;
     u32 split;    // limbs below split are stored to cq ([inst][2][split][N]), the others continue to cp: the number
                   // of q-limbs, or one less when the ModDown that follows also divides by the last q-limb
-    u32 add_tensor;  // OWN_TENSOR with split < L: add P * (b1*b2, a1*b2 + a2*b1) on limb `split` before its inverse pass
     u32 per_inst;    // not hoisted: every instance has its own key and Galois element (at most CKKS_ROT_CHUNK instances)
+    // FUSED (limbs below split only, launched after the ModDown conversion): the kernel also ends the ModDown
+    const u64* cv;              // [inst][2][split][N] converted special part, first forward pass done
+    u64* out;                   // [inst][2][split][N]
+    const PinvConst* fin_pinv;  // [split] inverse of the product of the ModDown's source primes
 };
 
-template <class AR, int A, int OWN, bool HOISTED>
+template <class AR, int A, int OWN, bool HOISTED, bool FUSED>
 __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile,
                                               u32 inst) {
     typedef typename AR::T T;
@@ -785,9 +788,20 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
                 for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(AR::from_canon(p[k * 16 + e0], m), m);
             } else if (OWN == OWN_TENSOR) {
                 const size_t off = (((size_t)inst * 2 + 1) * L + i) * N + row_off;
+                // the tensor terms d0 = b1*b2 and d1 = a1*b2 + a2*b1 join c' here as P * d, where a1 and a2 are
+                // loaded anyway: (c' + P*d - conv) * P^-1 = (c' - conv) * P^-1 + d, so the kernel that ends the
+                // ModDown adds nothing, also when it divides by the last q-limb as well.  One more product
+                // between folds: at most 9 * 0.69 q < 2^53, still exact.
+                const size_t offb = off - (size_t)L * N;
+                const u64 pmod = tb.pmod[i];
 #pragma unroll
                 for (int k = 0; k < 16; k++) {
-                    v[k] = AR::round_reduce(AR::mul_canon(__builtin_nontemporal_load(&a.own[off + k * 16 + e0]), __builtin_nontemporal_load(&a.own2[off + k * 16 + e0]), pc, m), m);
+                    const u32 e = k * 16 + e0;
+                    const u64 a1 = __builtin_nontemporal_load(&a.own[off + e]), a2 = __builtin_nontemporal_load(&a.own2[off + e]);
+                    const u64 b1 = __builtin_nontemporal_load(&a.own[offb + e]), b2 = __builtin_nontemporal_load(&a.own2[offb + e]);
+                    v[k] = AR::round_reduce(AR::mul_canon(a1, a2, pc, m), m);
+                    AR::acc_mac(acc0[k], AR::mul_canon(b1, b2, pc, m), pmod, m);
+                    AR::acc_mac(acc1[k], AR::mul_canon(a1, b2, pc, m) + AR::mul_canon(a2, b1, pc, m), pmod, m);
                 }
             } else {
                 const u64* p = a.own + (((size_t)inst * 2 + 1) * L + i) * N;
@@ -821,18 +835,44 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             for (int k = 0; k < 16; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
         }
     }
-    if (OWN == OWN_TENSOR && a.add_tensor && i == a.split) {
-        const size_t o0 = (((size_t)inst * 2 + 0) * L + i) * N + row_off, o1 = o0 + (size_t)L * N;
-        const u64 pmod = tb.pmod[i];
+    if (FUSED) {
+        // c' stays in registers: out = (c' - second forward pass of the converted special part) * P^-1
+        // (+ sigma_g(b) on the first component of a rotation).  FP64 magnitudes in units of q: c' <= 0.5,
+        // v <= 5.2, the product with P^-1 <= 2.9; canonicalised before the store.
+        // Opaque copies of the lane coordinates: every address of this part is derived from them, so none of
+        // it is computed before the accumulation loop, which has no registers to spare.
+        u32 e0f = e0, chf = ch, gal_fin = gal;
+        asm volatile("" : "+v"(e0f), "+v"(chf), "+s"(gal_fin));
+        const u32 rf = tile * 16 + chf, row_off_f = rf * 256;
+        u64* lrow_f = lds + chf * 272;
+        const PinvConst pinv = a.fin_pinv[i];
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            const u32 e = k * 16 + e0;
-            const u64 b1 = a.own[o0 + e], b2 = a.own2[o0 + e], a1 = a.own[o1 + e], a2 = a.own2[o1 + e];
-            AR::acc_mac(acc0[k], AR::mul_canon(b1, b2, pc, m), pmod, m);
-            AR::acc_mac(acc1[k], AR::mul_canon(a1, b2, pc, m) + AR::mul_canon(a2, b1, pc, m), pmod, m);
+        for (int t = 0; t < 2; t++) {
+            T v[16];
+            const u64* p = a.cv + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
+#pragma unroll
+            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0f]));
+            NttCore<AR, A>::fwd_contig(v, lrow_f, e0f, rf, ti, tf, N, m);
+            exchange_cb_to_ca<AR>(v, lrow_f, e0f);
+            u64* o = a.out + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
+            const u64* bp = a.own + ((size_t)inst * 2 * L + i) * N;
+#pragma unroll
+            for (int k = 0; k < 16; k++) {
+                const u32 e = k * 16 + e0f;
+                const T fin = AR::acc_finish(t ? acc1[k] : acc0[k], m);
+                if constexpr (AR::is_fp) {
+                    const FpAr::Mod fm = FpAr::mod(pc);
+                    double ks = FpAr::mulmod_lazy(fin - v[k], pinv.d, fm);
+                    if (OWN == OWN_ROT && t == 0) ks += u64_to_f64(bp[eval_perm(row_off_f + e, gal_fin, tb.logN)]);
+                    __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[e]);
+                } else {
+                    u64 ks = mul_shoup(submod(AR::acc_canon(fin, m), AR::canon_fwd(v[k], m), pc.q), pinv.w, pinv.wp, pc.q);
+                    if (OWN == OWN_ROT && t == 0) ks = addmod(ks, bp[eval_perm(row_off_f + e, gal_fin, tb.logN)], pc.q);
+                    o[e] = ks;
+                }
+            }
         }
-    }
-    if (i < a.split) {
+    } else if (i < a.split) {
         u64* o0 = a.cq + (((size_t)inst * 2 + 0) * a.split + i) * N + row_off;
         u64* o1 = a.cq + (((size_t)inst * 2 + 1) * a.split + i) * N + row_off;
 #pragma unroll
@@ -855,13 +895,13 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
     }
 }
 
-template <class AR, int A, int OWN, bool HOISTED>
-__global__ __launch_bounds__(256) void ks_inner_kernel(InnerArgs a, Tables tb, LimbRun run) {
+template <class AR, int A, int OWN, bool HOISTED, bool FUSED>
+__global__ __launch_bounds__(256, 2) void ks_inner_kernel(InnerArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[NTT_LDS_WORDS];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;
     if (!xcd_decode(blockIdx.x, a.n_inst, run.count * TILES, group, inst)) return;
-    ks_inner_body<AR, A, OWN, HOISTED>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
+    ks_inner_body<AR, A, OWN, HOISTED, FUSED>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
 }
 
 // ===================================================== double-hoisted rotate-multiply-accumulate
@@ -1039,17 +1079,15 @@ __global__ __launch_bounds__(256) void sum_instances_kernel(const u64* __restric
 // ======================================================================== final combine
 // ks_t[i] = (c'_t[i] - NTT(conv_t)[i]) * P^-1 mod q_i, the NTT's second pass done here, then
 //   FIN_KS     : out[inst][t][i] = ks
-//   FIN_HMULT  : out = ks + (t == 0 ? b1*b2 : a1*b2 + a2*b1)
 //   FIN_HROT   : out = ks + (t == 0 ? sigma_g(b) : 0)
 //   FIN_HOISTED: out[t][i] (+)= sum_r pt_r[i] * (ks_r + (t == 0 ? sigma_{g_r}(b) : 0)); work item (i, tile, t)
-//   FIN_HMULT_RS: the ModDown also divides by the last q-limb of the inputs (merged rescale): out has L limbs,
-//                 ct1 / ct2 have in_L = L + 1, and the tensor terms enter divided by that limb's prime
-enum FinalMode { FIN_KS = 0, FIN_HMULT = 1, FIN_HROT = 2, FIN_HOISTED = 3, FIN_HMULT_RS = 4 };
+// HMult ends in FIN_KS: its tensor terms were added to c' by the inner-product kernel.  The numbering keeps
+// the kernel names of the profiles stable.
+enum FinalMode { FIN_KS = 0, FIN_HROT = 2, FIN_HOISTED = 3 };
 struct FinalArgs {
     const u64* cq;   // [g][2][L][N] canonical
     const u64* cv;   // [g][2][L][N] raw forward-lazy (first pass done)
-    const u64* ct1;  // HMULT: ct1; HROT / HOISTED: ct
-    const u64* ct2;  // HMULT: ct2
+    const u64* ct1;  // HROT / HOISTED: ct
     const u64* pt;   // HOISTED: plaintexts of this chunk [n_rot][L][N]
     u64* out;
     u32 galois[CKKS_ROT_CHUNK];
@@ -1057,7 +1095,7 @@ struct FinalArgs {
     u32 n_rot;       // HOISTED
     u32 accumulate;  // HOISTED: add to what out already holds
     u32 cq_L;        // limbs per component of cq (L, or L + 1 when cq is a ciphertext about to lose its last limb)
-    u32 in_L;        // limbs per component of ct1 / ct2 (L, or L + 1 for FIN_HMULT_RS)
+    u32 in_L;        // limbs per component of ct1
     u32 per_inst;    // FIN_HROT: one Galois element per instance
 };
 
@@ -1129,18 +1167,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             for (int k = 0; k < 16; k++) {
                 const u32 e = k * 16 + e0;
                 double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[e])) - v[k], pinv.d, fm);
-                if (MODE == FIN_HMULT || MODE == FIN_HMULT_RS) {
-                    // b1, b2 are read again for t = 1 (from L2): holding them would cost a wave of occupancy
-                    const double b1 = u64_to_f64(a.ct1[o0 + e]), b2 = u64_to_f64(a.ct2[o0 + e]);
-                    double d;
-                    if (t == 0) {
-                        d = FpAr::mulmod_lazy(b1, b2, fm);
-                    } else {
-                        d = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct1[o1 + e])), b2, fm) +
-                            FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&a.ct2[o1 + e])), b1, fm);
-                    }
-                    ks += MODE == FIN_HMULT_RS ? FpAr::mulmod_lazy(d, tb.qlinv[i].d, fm) : d;  // |d| <= 1.75 q
-                } else if (MODE == FIN_HROT) {
+                if (MODE == FIN_HROT) {
                     if (t == 0) ks += u64_to_f64(a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[a.per_inst ? inst : 0], tb.logN)]);
                 }
                 __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[e]);
@@ -1194,18 +1221,7 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
         for (int k = 0; k < 16; k++) {
             const u32 e = k * 16 + e0;
             u64 ks = mul_shoup(submod(c[e], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
-            if (MODE == FIN_HMULT || MODE == FIN_HMULT_RS) {
-                u128w s = {0, 0};
-                if (t == 0) {
-                    mac128(s, a.ct1[o0 + e], a.ct2[o0 + e]);
-                } else {
-                    mac128(s, a.ct1[o1 + e], a.ct2[o0 + e]);
-                    mac128(s, a.ct2[o1 + e], a.ct1[o0 + e]);
-                }
-                u64 d = reduce128(s, q, pc.qneg, pc.r2);
-                if (MODE == FIN_HMULT_RS) d = mul_shoup(d, tb.qlinv[i].w, tb.qlinv[i].wp, q);
-                ks = addmod(ks, d, q);
-            } else if (MODE == FIN_HROT) {
+            if (MODE == FIN_HROT) {
                 if (t == 0) ks = addmod(ks, a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[a.per_inst ? inst : 0], tb.logN)], q);
             }
             o[e] = ks;
