@@ -238,6 +238,7 @@ struct ProfState {
 struct SideStream {
     bool enabled = false;  // off by default; ckks_set_overlap switches it
     bool active = false;
+    bool fp_pending = false;  // an FpAr conversion is running on the side stream (see decompose_extend)
     hipStream_t stream = nullptr;
     std::vector<hipEvent_t> events;
     size_t next = 0;
@@ -286,16 +287,21 @@ static hipEvent_t side_event(SideStream& sd) {
     return sd.events[sd.next++ % sd.events.size()];
 }
 
-// From here on IntAr launches go to the side stream, ordered after everything enqueued on s so far.
-static void fork_side(const View* c, hipStream_t s) {
-    SideStream& sd = c->sh->side;
-    if (!sd.enabled || !c->mixed_classes || sd.active) return;
+static bool side_stream_ready(SideStream& sd) {
     if (!sd.stream && hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking) != hipSuccess) {
         sd.stream = nullptr;
         sd.enabled = false;
         (void)hipGetLastError();
-        return;
+        return false;
     }
+    return true;
+}
+
+// From here on IntAr launches go to the side stream, ordered after everything enqueued on s so far.
+static void fork_side(const View* c, hipStream_t s) {
+    SideStream& sd = c->sh->side;
+    if (!sd.enabled || !c->mixed_classes || sd.active) return;
+    if (!side_stream_ready(sd)) return;
     hipEvent_t e = side_event(sd);
     if (!e || hipEventRecord(e, s) != hipSuccess || hipStreamWaitEvent(sd.stream, e, 0) != hipSuccess) {
         (void)hipGetLastError();
@@ -1032,11 +1038,14 @@ static inline bool conv_on_matrix_cores(const View* c, int dir) {
     return dir == CONV_UP ? c->tb.up_ntiles != 0 : c->tb.dn_ntiles != 0;
 }
 
+// cls: -1 = every target, 0 = IntAr targets only, 1 = FpAr targets only
 template <int DIR>
-static void launch_conv(const View* c, const ConvArgs& a, hipStream_t s) {
+static void launch_conv(const View* c, const ConvArgs& a, hipStream_t s, int cls = -1) {
     const u64 outer = a.groups_outer;
-    const int only = conv_on_matrix_cores(c, DIR) ? 0 : -1;  // FpAr targets go to the matrix-core kernel when the view has tiles
-    if (only == 0) launch_conv_mfma<DIR>(c, a, s);
+    const bool mfma = conv_on_matrix_cores(c, DIR);  // FpAr targets go to the matrix-core kernel when the view has tiles
+    if (mfma && cls != 0) launch_conv_mfma<DIR>(c, a, s);
+    if (mfma && cls == 1) return;
+    const int only = mfma ? 0 : cls;
     const u32 tbs = ConvTB<DIR, true>::value | (ConvTB<DIR, false>::value << 16);
     if (DIR == CONV_UP) {  // groups = (batch, digit, tile); instances = blocks of the run's target primes
         auto alg = [c, outer](u32 first, u32 n) {
@@ -1137,7 +1146,7 @@ template <int MODE>
 static void launch_ks_final(const View* c, const FinalArgs& a, hipStream_t s) {
     u64 per;  // algorithmic limbs per q-limb
     if (MODE == FIN_HOISTED) per = (u64)a.n_rot * (2 + 2 + 1 + 1) + (2 + (a.accumulate ? 2 : 0));
-    else per = (u64)a.n_inst * (6 + (MODE == FIN_HROT ? 1 : 0));
+    else per = (u64)a.n_inst * 6;
     launch_runs<KsFinalL<MODE>>(c, 0, c->L, 0, true, tiles_of(c), a.n_inst, a, s, [per](u32, u32 n) { return per * n; });
 }
 
@@ -1448,14 +1457,41 @@ static int check_ks_args(const View* c, const void* a, const void* b, const void
 // ModUp side shared by every key switch: w.x holds the first inverse pass of the polynomial(s).
 // Second inverse pass (scaled by the conversion pre-factor), then conversion fused into the
 // first forward pass of every extended limb.
-static void decompose_extend(const View* c, const Workspace& w, u32 groups, hipStream_t s) {
+static void decompose_extend(const View* c, const Workspace& w, u32 groups, hipStream_t s, bool fp_beside = false) {
     const LimbSel sel = {c->L, groups, c->L, 0, 0, 0};
     const u32 fmt = conv_on_matrix_cores(c, CONV_UP) ? SRC_DIGITS : SRC_F64;
     InvStridedArgs a2 = {w.x, sel, SC_UP, fmt};
     launch_inv_strided(c, a2, s);
-    fork_side(c, s);  // from here the special-limb (IntAr) chain runs beside the q-limb chain
     ConvArgs a3 = {w.x, w.dt, groups, fmt};
+    SideStream& sd = c->sh->side;
+    if (fp_beside && sd.enabled && c->mixed_classes && !sd.active && side_stream_ready(sd)) {
+        // the IntAr targets first, on s; the FpAr targets on the side stream from the moment those are done, beside
+        // whatever s runs next (the caller joins before it reads the FpAr limbs of dt)
+        launch_conv<CONV_UP>(c, a3, s, 0);
+        hipEvent_t e = side_event(sd);
+        if (e && hipEventRecord(e, s) == hipSuccess && hipStreamWaitEvent(sd.stream, e, 0) == hipSuccess) {
+            launch_conv<CONV_UP>(c, a3, sd.stream, 1);
+            sd.fp_pending = true;
+            return;
+        }
+        (void)hipGetLastError();
+        launch_conv<CONV_UP>(c, a3, s, 1);
+        return;
+    }
+    fork_side(c, s);  // from here the special-limb (IntAr) chain runs beside the q-limb chain
     launch_conv<CONV_UP>(c, a3, s);
+}
+
+// s waits for the FpAr conversion that decompose_extend put on the side stream
+static void join_fp_beside(const View* c, hipStream_t s) {
+    SideStream& sd = c->sh->side;
+    if (!sd.fp_pending) return;
+    sd.fp_pending = false;
+    hipEvent_t e = side_event(sd);
+    if (!e || hipEventRecord(e, sd.stream) != hipSuccess || hipStreamWaitEvent(s, e, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipStreamSynchronize(sd.stream);
+    }
 }
 
 // ModDown side: w.cp holds the first inverse pass of c' on the special limbs.
@@ -1472,10 +1508,7 @@ static void moddown_convert(const View* c, const Workspace& w, u32 cg, hipStream
 // cm: the view whose ModDown ends the pipeline: c itself, or the merged view of c's level (the ModDown then
 // also divides by the last q-limb: limb c->L - 1 joins the special limbs and the output has c->L - 1 limbs)
 // multi_galois / multi_keys (rotations only, batch <= CKKS_ROT_CHUNK): one Galois element and key per instance.
-#ifndef CKKS_FUSED_FINAL
-#define CKKS_FUSED_FINAL 1
-#endif
-template <int LOAD, int OWN, int FIN>
+template <int LOAD, int OWN>
 static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, const u64* in2, const u64* key, u64* out,
                                u32 batch, u32 galois, void* ws, hipStream_t s, const u32* multi_galois = nullptr,
                                const u64* const* multi_keys = nullptr) {
@@ -1491,32 +1524,28 @@ static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, co
     a1.src = in1, a1.src2 = in2, a1.dst = w.x, a1.sel = sel, a1.dsel = sel, a1.galois[0] = galois;
     InnerArgs ia;
     memset(&ia, 0, sizeof(ia));
-    FinalArgs fa;
-    memset(&fa, 0, sizeof(fa));
-    ia.key[0] = key, ia.galois[0] = galois, fa.galois[0] = galois;
+    ia.key[0] = key, ia.galois[0] = galois;
     if (multi_galois) {
-        a1.per_inst = ia.per_inst = fa.per_inst = 1;
+        a1.per_inst = ia.per_inst = 1;
         for (u32 b = 0; b < batch; b++)
-            a1.galois[b] = ia.galois[b] = fa.galois[b] = multi_galois[b], ia.key[b] = multi_keys[b];
+            a1.galois[b] = ia.galois[b] = multi_galois[b], ia.key[b] = multi_keys[b];
     }
     launch_inv_contig<LOAD>(c, a1, s);
-    decompose_extend(c, w, batch, s);
+    decompose_extend(c, w, batch, s, true);
     ia.dt = w.dt, ia.own = in1, ia.own2 = in2;
     ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = batch, ia.split = cm->L;
-#if CKKS_FUSED_FINAL
     // the limbs that feed the ModDown conversion first; the q-limbs then finish in one kernel, c' in registers
-    launch_ks_inner<OWN, false, false>(c, ia, s, cm->L, c->D);
+    if (cm != c) {
+        join_fp_beside(c, s);  // limb cm->L is a q-limb here: its digits come from the FpAr conversion
+        launch_ks_inner<OWN, false, false>(c, ia, s, cm->L, c->D);
+    } else {
+        // special limbs belong to no digit, so every variant computes the same on them: the leanest one runs
+        launch_ks_inner<OWN_COPY, false, false>(c, ia, s, c->L, c->D);
+    }
     moddown_convert(cm, w, batch, s);
     ia.cv = w.cv, ia.out = out, ia.fin_pinv = cm->tb.pinv;
+    join_fp_beside(c, s);
     launch_ks_inner<OWN, false, true>(c, ia, s, 0, cm->L);
-    (void)fa;
-#else
-    launch_ks_inner<OWN, false>(c, ia, s);
-    moddown_convert(cm, w, batch, s);
-    fa.cq = w.cq, fa.cv = w.cv, fa.ct1 = in1, fa.out = out, fa.n_inst = batch;
-    fa.cq_L = cm->L, fa.in_L = c->L;
-    launch_ks_final<FIN>(cm, fa, s);
-#endif
 }
 
 extern "C" int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_d, const uint64_t* d_key,
@@ -1529,7 +1558,7 @@ extern "C" int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* 
     rc = check_no_alias(c, d_out, limb_bytes(c, (size_t)batch * 2 * c->L), d_d, limb_bytes(c, (size_t)batch * c->L), nullptr, 0,
                         d_ws, ws_bytes);
     if (rc) return rc;
-    keyswitch_pipeline<INV_PLAIN, OWN_COPY, FIN_KS>(c, c, d_d, nullptr, d_key, d_out, batch, 1, d_ws, (hipStream_t)stream);
+    keyswitch_pipeline<INV_PLAIN, OWN_COPY>(c, c, d_d, nullptr, d_key, d_out, batch, 1, d_ws, (hipStream_t)stream);
     return hip_check(c, "ckks_keyswitch");
 }
 
@@ -1545,7 +1574,7 @@ extern "C" int ckks_hmult_relin_at(ckks_ctx* ctx, uint32_t level, const uint64_t
     const size_t ctb = limb_bytes(c, (size_t)batch * 2 * c->L);
     rc = check_no_alias(c, d_out, ctb, d_ct1, ctb, d_ct2, ctb, d_ws, ws_bytes);
     if (rc) return rc;
-    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_KS>(c, c, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
+    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR>(c, c, d_ct1, d_ct2, d_evk, d_out, batch, 1, d_ws,
                                                           (hipStream_t)stream);
     return hip_check(c, "ckks_hmult_relin");
 }
@@ -1563,7 +1592,7 @@ extern "C" int ckks_hmult_relin_rescale_at(ckks_ctx* ctx, uint32_t level, const 
     const size_t ctb = limb_bytes(c, (size_t)batch * 2 * c->L);
     rc = check_no_alias(c, d_out, limb_bytes(c, (size_t)batch * 2 * (c->L - 1)), d_ct1, ctb, d_ct2, ctb, d_ws, ws_bytes);
     if (rc) return rc;
-    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR, FIN_KS>(c, &ctx->merged[level], d_ct1, d_ct2, d_evk, d_out, batch, 1,
+    keyswitch_pipeline<INV_TENSOR, OWN_TENSOR>(c, &ctx->merged[level], d_ct1, d_ct2, d_evk, d_out, batch, 1,
                                                              d_ws, (hipStream_t)stream);
     return hip_check(c, "ckks_hmult_relin_rescale");
 }
@@ -1580,7 +1609,7 @@ extern "C" int ckks_hrot_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct,
     const size_t ctb = limb_bytes(c, (size_t)batch * 2 * c->L);
     rc = check_no_alias(c, d_out, ctb, d_ct, ctb, nullptr, 0, d_ws, ws_bytes);
     if (rc) return rc;
-    keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, c, d_ct, nullptr, d_rk, d_out, batch, galois, d_ws,
+    keyswitch_pipeline<INV_ROT, OWN_ROT>(c, c, d_ct, nullptr, d_rk, d_out, batch, galois, d_ws,
                                                    (hipStream_t)stream);
     return hip_check(c, "ckks_hrot");
 }
@@ -1634,7 +1663,7 @@ static int rescale_impl(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, uin
     moddown_convert(c, w, batch, s);
     FinalArgs fa;
     memset(&fa, 0, sizeof(fa));
-    fa.cq = d_ct, fa.cq_L = level, fa.in_L = c->L, fa.cv = w.cv, fa.out = d_out, fa.n_inst = batch;
+    fa.cq = d_ct, fa.cq_L = level, fa.cv = w.cv, fa.out = d_out, fa.n_inst = batch;
     launch_ks_final<FIN_KS>(c, fa, s);
     return hip_check(c, "ckks_rescale");
 }
@@ -1716,7 +1745,7 @@ extern "C" int ckks_hrot_hoisted_mac_at(ckks_ctx* ctx, uint32_t level, const uin
         launch_ks_inner<OWN_COPY, true>(c, ia, s);
         moddown_convert(c, w, nr, s);
         fa.cq = w.cq, fa.cq_L = c->L, fa.cv = w.cv, fa.ct1 = d_ct, fa.pt = d_pt + (size_t)r0 * c->L * N, fa.out = d_out;
-        fa.n_inst = 2, fa.n_rot = nr, fa.accumulate = r0 ? 1 : 0, fa.in_L = c->L;
+        fa.n_inst = 2, fa.n_rot = nr, fa.accumulate = r0 ? 1 : 0;
         launch_ks_final<FIN_HOISTED>(c, fa, s);
     }
     return hip_check(c, "ckks_hrot_hoisted_mac");
@@ -1795,7 +1824,7 @@ static int dh_mac_impl(ckks_ctx* ctx, uint32_t level, bool rescale, const uint64
     moddown_convert(cm, w, 1, s);
     FinalArgs fa;
     memset(&fa, 0, sizeof(fa));
-    fa.cq = w.cq, fa.cq_L = cm->L, fa.in_L = cm->L, fa.cv = w.cv, fa.out = d_out, fa.n_inst = 1;
+    fa.cq = w.cq, fa.cq_L = cm->L, fa.cv = w.cv, fa.out = d_out, fa.n_inst = 1;
     launch_ks_final<FIN_KS>(cm, fa, s);
     return hip_check(c, "ckks_hrot_dh_mac");
 }
@@ -1913,12 +1942,12 @@ extern "C" int ckks_lintrans_bsgs_at(ckks_ctx* ctx, uint32_t level, const uint64
     moddown_convert(c, w, n2, s);
     FinalArgs fa;
     memset(&fa, 0, sizeof(fa));
-    fa.cq = w.cq, fa.cq_L = c->L, fa.in_L = c->L, fa.cv = w.cv, fa.out = inner, fa.n_inst = n2;
+    fa.cq = w.cq, fa.cq_L = c->L, fa.cv = w.cv, fa.out = inner, fa.n_inst = n2;
     launch_ks_final<FIN_KS>(c, fa, s);
     // giant rotations, each inner sum with its own key, then the sum
     for (u32 g0 = 0; g0 < n2; g0 += CKKS_ROT_CHUNK) {
         const u32 ng = (n2 - g0) < CKKS_ROT_CHUNK ? (n2 - g0) : CKKS_ROT_CHUNK;
-        keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, c, inner + (size_t)g0 * 2 * LN, nullptr, nullptr,
+        keyswitch_pipeline<INV_ROT, OWN_ROT>(c, c, inner + (size_t)g0 * 2 * LN, nullptr, nullptr,
                                                        rot + (size_t)g0 * 2 * LN, ng, 1, ks_ws, s, h_giant_galois + g0,
                                                        h_giant_rk_ptrs + g0);
     }
@@ -1954,7 +1983,7 @@ extern "C" int ckks_hrot_multi_at(ckks_ctx* ctx, uint32_t level, const uint64_t*
     if (rc) return rc;
     for (u32 b0 = 0; b0 < batch; b0 += CKKS_ROT_CHUNK) {
         const u32 nb = (batch - b0) < CKKS_ROT_CHUNK ? (batch - b0) : CKKS_ROT_CHUNK;
-        keyswitch_pipeline<INV_ROT, OWN_ROT, FIN_HROT>(c, c, d_ct + b0 * ct_words, nullptr, nullptr, d_out + b0 * ct_words, nb,
+        keyswitch_pipeline<INV_ROT, OWN_ROT>(c, c, d_ct + b0 * ct_words, nullptr, nullptr, d_out + b0 * ct_words, nb,
                                                        1, d_ws, (hipStream_t)stream, h_galois + b0, h_rk_ptrs + b0);
     }
     return hip_check(c, "ckks_hrot_multi");

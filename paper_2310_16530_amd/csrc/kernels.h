@@ -837,8 +837,9 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
     }
     if (FUSED) {
         // c' stays in registers: out = (c' - second forward pass of the converted special part) * P^-1
-        // (+ sigma_g(b) on the first component of a rotation).  FP64 magnitudes in units of q: c' <= 0.5,
-        // v <= 5.2, the product with P^-1 <= 2.9; canonicalised before the store.
+        // (+ sigma_g(b) on the first component of a rotation; adding it as P * sigma_g(b) where sigma_g(a) is
+        // gathered measured slower: the accumulation loop has no registers for it).  FP64 magnitudes in units
+        // of q: c' <= 0.5, v <= 5.2, the product with P^-1 <= 2.9; canonicalised before the store.
         // Opaque copies of the lane coordinates: every address of this part is derived from them, so none of
         // it is computed before the accumulation loop, which has no registers to spare.
         u32 e0f = e0, chf = ch, gal_fin = gal;
@@ -855,7 +856,7 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             NttCore<AR, A>::fwd_contig(v, lrow_f, e0f, rf, ti, tf, N, m);
             exchange_cb_to_ca<AR>(v, lrow_f, e0f);
             u64* o = a.out + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
-            const u64* bp = a.own + ((size_t)inst * 2 * L + i) * N;
+            const u64* bp = a.own + ((size_t)inst * 2 * L + i) * N;  // OWN_ROT: b, gathered at the rotated slots
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 const u32 e = k * 16 + e0f;
@@ -1079,15 +1080,14 @@ __global__ __launch_bounds__(256) void sum_instances_kernel(const u64* __restric
 // ======================================================================== final combine
 // ks_t[i] = (c'_t[i] - NTT(conv_t)[i]) * P^-1 mod q_i, the NTT's second pass done here, then
 //   FIN_KS     : out[inst][t][i] = ks
-//   FIN_HROT   : out = ks + (t == 0 ? sigma_g(b) : 0)
 //   FIN_HOISTED: out[t][i] (+)= sum_r pt_r[i] * (ks_r + (t == 0 ? sigma_{g_r}(b) : 0)); work item (i, tile, t)
-// HMult ends in FIN_KS: its tensor terms were added to c' by the inner-product kernel.  The numbering keeps
-// the kernel names of the profiles stable.
-enum FinalMode { FIN_KS = 0, FIN_HROT = 2, FIN_HOISTED = 3 };
+// (HMult, HRot and the plain key switch end inside the inner-product kernel, which also adds the tensor
+// terms or sigma_g(b).)  The numbering keeps kernel names stable.
+enum FinalMode { FIN_KS = 0, FIN_HOISTED = 3 };
 struct FinalArgs {
     const u64* cq;   // [g][2][L][N] canonical
     const u64* cv;   // [g][2][L][N] raw forward-lazy (first pass done)
-    const u64* ct1;  // HROT / HOISTED: ct
+    const u64* ct1;  // HOISTED: ct
     const u64* pt;   // HOISTED: plaintexts of this chunk [n_rot][L][N]
     u64* out;
     u32 galois[CKKS_ROT_CHUNK];
@@ -1095,8 +1095,6 @@ struct FinalArgs {
     u32 n_rot;       // HOISTED
     u32 accumulate;  // HOISTED: add to what out already holds
     u32 cq_L;        // limbs per component of cq (L, or L + 1 when cq is a ciphertext about to lose its last limb)
-    u32 in_L;        // limbs per component of ct1
-    u32 per_inst;    // FIN_HROT: one Galois element per instance
 };
 
 template <class AR, int A, int MODE>
@@ -1162,14 +1160,10 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
             exchange_cb_to_ca<AR>(v, lrow, e0);
             const u64* c = a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off;
             u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
-            const size_t o0 = (((size_t)inst * 2 + 0) * a.in_L + i) * N + row_off, o1 = o0 + (size_t)a.in_L * N;
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 const u32 e = k * 16 + e0;
-                double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[e])) - v[k], pinv.d, fm);
-                if (MODE == FIN_HROT) {
-                    if (t == 0) ks += u64_to_f64(a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[a.per_inst ? inst : 0], tb.logN)]);
-                }
+                const double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[e])) - v[k], pinv.d, fm);
                 __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[e]);
             }
         }
@@ -1216,15 +1210,10 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
         exchange_cb_to_ca<AR>(v, lrow, e0);
         const u64* c = a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off;
         u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
-        const size_t o0 = (((size_t)inst * 2 + 0) * a.in_L + i) * N + row_off, o1 = o0 + (size_t)a.in_L * N;
 #pragma unroll
         for (int k = 0; k < 16; k++) {
             const u32 e = k * 16 + e0;
-            u64 ks = mul_shoup(submod(c[e], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
-            if (MODE == FIN_HROT) {
-                if (t == 0) ks = addmod(ks, a.ct1[o0 - row_off + eval_perm(row_off + e, a.galois[a.per_inst ? inst : 0], tb.logN)], q);
-            }
-            o[e] = ks;
+            o[e] = mul_shoup(submod(c[e], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
         }
     }
 }
