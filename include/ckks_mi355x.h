@@ -344,11 +344,15 @@ int ckks_lintrans_bsgs_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_ct, u
 
 /*
  * Optional two-stream execution inside one call.  Off by default: every kernel of a call runs on the
- * caller's stream in order.  With on != 0 the key-switch entry points run the launches that work on
- * integer-arithmetic limbs (primes of 50 bits and more, normally the special limbs) on a second stream
- * owned by the context, beside the launches on floating-point-arithmetic limbs, ordered by events
- * (both streams at default priority).  Results are identical; the call still completes in stream order
- * on the caller's stream.  Not to be changed while a call of this context is being issued.
+ * caller's stream in order.  With on != 0 a call may put part of its launches on a second stream owned by
+ * the context, ordered by events (both streams at default priority): ckks_keyswitch, ckks_hmult_relin,
+ * ckks_hrot and their _at / _multi / _rescale forms run the ModUp conversion of the floating-point-arithmetic
+ * limbs there, beside the inner product and ModDown conversion of the integer-arithmetic limbs (primes of
+ * 50 bits and more, normally the special limbs); the hoisted, double-hoisted and baby-step giant-step calls
+ * run the launches on integer-arithmetic limbs there, beside those on floating-point-arithmetic limbs.
+ * Needs both classes of primes in the chain, otherwise nothing changes.  Results are identical; the call
+ * still completes in stream order on the caller's stream.  Not to be changed while a call of this context
+ * is being issued.
  */
 int ckks_set_overlap(ckks_ctx* ctx, int on);
 

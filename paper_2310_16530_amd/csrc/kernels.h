@@ -7,9 +7,11 @@
 //   fwd_strided_kernel  load (plain | base conversion from the digit / special limbs) -> first forward pass
 //   fwd_contig_kernel   second forward pass -> canonical store
 //   ks_inner_kernel     second forward pass of every extended digit -> key inner product accumulated over
-//                       the digits in registers -> (special limbs) first inverse pass of ModDown
-//   ks_final_kernel     second forward pass of the converted special part -> (c' - .) * P^-1 + operand
-//                       (HMult tensor terms, sigma_g(b), or plaintext multiply-accumulate over rotations)
+//                       the digits in registers (+ P * tensor terms of HMult) -> special limbs: first inverse
+//                       pass of ModDown; q-limbs, launched after the ModDown conversion: second forward pass
+//                       of the converted special part -> (c' - .) * P^-1 (+ sigma_g(b)) -> result
+//   ks_final_kernel     the same end of the ModDown from a stored c', for the calls whose inner product is
+//                       not this kernel or is followed by a plaintext multiply-accumulate over rotations
 //   dh_accum_kernel     double hoisting: plaintext products of all rotations accumulated in the extended basis
 //   bsgs_mac_kernel     giant-step combinations of baby-step rotations kept in the extended basis
 //   modup_kernel / moddown_kernel / automorph kernels: the stand-alone coefficient-form entry points.

@@ -22,10 +22,12 @@ def test_counter_table_is_read_from_the_committed_summary():
     for name, (rd, wr, insts) in rows.items():
         assert re.match(r"^[a-z_]+<.*>$", name), name
         assert 0 < rd < 4096 and 0 < wr < 4096 and insts > 100000, name
-    # the kernels of the default step: both conversions, both inner products, both final combines
-    for frag in ("conv_fwd_strided_kernel<FpAr, 8, 1", "conv_mfma_kernel<8,", "ks_inner_kernel<FpAr, 8, 1", "ks_inner_kernel<IntAr, 8, 2",
-                 "ks_final_kernel<FpAr, 8, 1", "ks_final_kernel<FpAr, 8, 2", "inv_contig_kernel<FpAr, 8, 1", "inv_strided_kernel<IntAr, 8"):
+    # the kernels of the default step: both conversions, the inner product on the special limbs and, for HMult
+    # and HRot, the q-limb inner product that also ends the ModDown (no separate final kernel)
+    for frag in ("conv_fwd_strided_kernel<FpAr, 8, 1", "conv_mfma_kernel<8,", "ks_inner_kernel<FpAr, 8, 1, false, true", "ks_inner_kernel<FpAr, 8, 2, false, true",
+                 "ks_inner_kernel<IntAr, 8, 0, false, false", "inv_contig_kernel<FpAr, 8, 1", "inv_strided_kernel<IntAr, 8"):
         assert any(k.startswith(frag) for k in rows), frag
+    assert not any(k.startswith("ks_final_kernel") for k in rows)
     assert bench.load_counter_table(os.path.join(ROOT, "no_such_file")) == {}
 
 
