@@ -741,6 +741,64 @@ struct InnerArgs {
     const PinvConst* fin_pinv;  // [split] inverse of the product of the ModDown's source primes
 };
 
+// Layout CP of the 16 words of a lane in a 256-word row (lane e0 of the row's 16): register kk holds word
+// (kk/2)*32 + e0*2 + kk%2, i.e. eight adjacent pairs: every global access of the inner product that does not feed a
+// transform directly (keys, own-digit operands, results) is a 16-byte access per lane, half the memory
+// instructions of the one-word-per-access layout CA.  The per-instruction cost of the address path, not the
+// bytes, is what the kernel's memory side was bound by.
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32 cp_word(u32 e0, int kk) { return (u32)(kk >> 1) * 32 + e0 * 2 + (u32)(kk & 1); }
+template <bool NT>
+__device__ __forceinline__ void load_row_cp(const u64* row, u32 e0, u64 (&o)[16]) {
+#pragma unroll
+    for (int k2 = 0; k2 < 8; k2++) {
+        const u64x2* p = reinterpret_cast<const u64x2*>(row + k2 * 32 + e0 * 2);
+        const u64x2 t = NT ? __builtin_nontemporal_load(p) : *p;
+        o[2 * k2] = t.x, o[2 * k2 + 1] = t.y;
+    }
+}
+__device__ __forceinline__ void store_row_cp(u64* row, u32 e0, const u64 (&v)[16]) {
+#pragma unroll
+    for (int k2 = 0; k2 < 8; k2++) {
+        u64x2 t;
+        t.x = v[2 * k2], t.y = v[2 * k2 + 1];
+        __builtin_nontemporal_store(t, reinterpret_cast<u64x2*>(row + k2 * 32 + e0 * 2));
+    }
+}
+// between the contiguous-pass layout CB (word e0*16 + k) and CP, through the row's LDS slice
+template <class AR>
+__device__ __forceinline__ void exchange_cb_to_cp(typename AR::T (&x)[16], u64* l, u32 e0) {
+    row_sync();
+#pragma unroll
+    for (int k = 0; k < 16; k++) l[pad16(e0 * 16 + k)] = AR::to_raw(x[k]);
+    row_sync();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) x[kk] = AR::from_raw(l[pad16(cp_word(e0, kk))]);
+}
+template <class AR>
+__device__ __forceinline__ void exchange_cp_to_cb(typename AR::T (&x)[16], u64* l, u32 e0) {
+    row_sync();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) l[pad16(cp_word(e0, kk))] = AR::to_raw(x[kk]);
+    row_sync();
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(e0 * 16 + k)]);
+}
+// Row `row_off/256` of sigma_g(f) in layout CP.  In evaluation order the automorphism maps a 256-word row onto one
+// source row (the row index is the bit-reversed low part of the exponent index, and multiplication by g keeps low
+// parts among themselves), so the source row is loaded whole with 16-byte accesses, staged in the row's LDS
+// slice and permuted there, instead of one scattered 8-byte global access per word.
+__device__ __forceinline__ void gather_row_cp(const u64* limb, u32 row_off, u32 gal, u32 logN, u64* l, u32 e0, u64 (&o)[16]) {
+    const u32 src_row = eval_perm(row_off, gal, logN) >> 8;
+    load_row_cp<false>(limb + (size_t)src_row * 256, e0, o);
+    row_sync();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) l[pad16(cp_word(e0, kk))] = o[kk];
+    row_sync();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) o[kk] = l[pad16(eval_perm(row_off + cp_word(e0, kk), gal, logN) & 255)];
+}
+
 template <class AR, int A, int OWN, bool HOISTED, bool FUSED>
 __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile,
                                               u32 inst) {
@@ -758,7 +816,7 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
     const u64* key = a.key[kidx] + (size_t)pi * N + row_off;
     const u32 gal = a.galois[kidx];
     const u32 own_digit = i < L ? i / tb.alpha : 0xffffffffu;
-    T acc0[16], acc1[16];
+    T acc0[16], acc1[16];  // layout CP
 #pragma unroll
     for (int k = 0; k < 16; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
     for (u32 j = 0; j < tb.dnum; j++) {
@@ -769,53 +827,53 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
         // where the registers allow it (measured per variant), else the first one only; IntAr has no
         // registers to spare and loads the key at its use
         constexpr bool EARLY0 = AR::is_fp, EARLY1 = AR::is_fp && OWN == OWN_TENSOR;
-        if constexpr (EARLY0) {
-#pragma unroll
-            for (int k = 0; k < 16; k++) kv0[k] = k0[k * 16 + e0];
-        }
-        if constexpr (EARLY1) {
-#pragma unroll
-            for (int k = 0; k < 16; k++) kv1[k] = k1[k * 16 + e0];
-        }
-        T v[16];
+        if constexpr (EARLY0) load_row_cp<false>(k0, e0, kv0);
+        if constexpr (EARLY1) load_row_cp<false>(k1, e0, kv1);
+        T v[16];  // the digit on this limb, evaluation form, layout CP
         if (j == own_digit) {
             if (HOISTED) {
-                const u64* p = a.own + ((size_t)L + i) * N;
+                u64 w[16];
+                gather_row_cp(a.own + ((size_t)L + i) * N, row_off, gal, tb.logN, lrow, e0, w);
 #pragma unroll
-                for (int k = 0; k < 16; k++)
-                    v[k] = AR::round_reduce(AR::from_canon(p[eval_perm(row_off + k * 16 + e0, gal, tb.logN)], m), m);
+                for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(AR::from_canon(w[k], m), m);
             } else if (OWN == OWN_COPY) {
-                const u64* p = a.own + ((size_t)inst * L + i) * N + row_off;
+                u64 w[16];
+                load_row_cp<false>(a.own + ((size_t)inst * L + i) * N + row_off, e0, w);
 #pragma unroll
-                for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(AR::from_canon(p[k * 16 + e0], m), m);
+                for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(AR::from_canon(w[k], m), m);
             } else if (OWN == OWN_TENSOR) {
-                const size_t off = (((size_t)inst * 2 + 1) * L + i) * N + row_off;
                 // the tensor terms d0 = b1*b2 and d1 = a1*b2 + a2*b1 join c' here as P * d, where a1 and a2 are
                 // loaded anyway: (c' + P*d - conv) * P^-1 = (c' - conv) * P^-1 + d, so the kernel that ends the
                 // ModDown adds nothing, also when it divides by the last q-limb as well.  One more product
                 // between folds: at most 9 * 0.69 q < 2^53, still exact.
-                const size_t offb = off - (size_t)L * N;
+                const size_t off = (((size_t)inst * 2 + 1) * L + i) * N + row_off, offb = off - (size_t)L * N;
                 const u64 pmod = tb.pmod[i];
 #pragma unroll
-                for (int k = 0; k < 16; k++) {
-                    const u32 e = k * 16 + e0;
-                    const u64 a1 = __builtin_nontemporal_load(&a.own[off + e]), a2 = __builtin_nontemporal_load(&a.own2[off + e]);
-                    const u64 b1 = __builtin_nontemporal_load(&a.own[offb + e]), b2 = __builtin_nontemporal_load(&a.own2[offb + e]);
-                    v[k] = AR::round_reduce(AR::mul_canon(a1, a2, pc, m), m);
-                    AR::acc_mac(acc0[k], AR::mul_canon(b1, b2, pc, m), pmod, m);
-                    AR::acc_mac(acc1[k], AR::mul_canon(a1, b2, pc, m) + AR::mul_canon(a2, b1, pc, m), pmod, m);
+                for (int k2 = 0; k2 < 8; k2++) {
+                    const u32 w = k2 * 32 + e0 * 2;
+                    const u64x2 a1 = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(a.own + off + w));
+                    const u64x2 a2 = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(a.own2 + off + w));
+                    const u64x2 b1 = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(a.own + offb + w));
+                    const u64x2 b2 = __builtin_nontemporal_load(reinterpret_cast<const u64x2*>(a.own2 + offb + w));
+#pragma unroll
+                    for (int b = 0; b < 2; b++) {
+                        const int k = 2 * k2 + b;
+                        v[k] = AR::round_reduce(AR::mul_canon(a1[b], a2[b], pc, m), m);
+                        AR::acc_mac(acc0[k], AR::mul_canon(b1[b], b2[b], pc, m), pmod, m);
+                        AR::acc_mac(acc1[k], AR::mul_canon(a1[b], b2[b], pc, m) + AR::mul_canon(a2[b], b1[b], pc, m), pmod, m);
+                    }
                 }
             } else {
-                const u64* p = a.own + (((size_t)inst * 2 + 1) * L + i) * N;
+                u64 w[16];
+                gather_row_cp(a.own + (((size_t)inst * 2 + 1) * L + i) * N, row_off, gal, tb.logN, lrow, e0, w);
 #pragma unroll
-                for (int k = 0; k < 16; k++)
-                    v[k] = AR::round_reduce(AR::from_canon(p[eval_perm(row_off + k * 16 + e0, gal, tb.logN)], m), m);
+                for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(AR::from_canon(w[k], m), m);
             }
         } else if (HOISTED) {
-            const u64* p = a.dt + ((size_t)j * D + i) * N;
+            u64 w[16];
+            gather_row_cp(a.dt + ((size_t)j * D + i) * N, row_off, gal, tb.logN, lrow, e0, w);
 #pragma unroll
-            for (int k = 0; k < 16; k++)
-                v[k] = AR::round_reduce(AR::from_canon(p[eval_perm(row_off + k * 16 + e0, gal, tb.logN)], m), m);
+            for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(AR::from_canon(w[k], m), m);
         } else {
             const u64* p = a.dt + (((size_t)inst * tb.dnum + j) * D + i) * N + row_off;
 #pragma unroll
@@ -823,15 +881,14 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
 #pragma unroll
             for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(v[k], m);
-            exchange_cb_to_ca<AR>(v, lrow, e0);
+            exchange_cb_to_cp<AR>(v, lrow, e0);
         }
+        if constexpr (!EARLY0) load_row_cp<false>(k0, e0, kv0);
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            if constexpr (!EARLY0) kv0[k] = k0[k * 16 + e0];
-            if constexpr (!EARLY1) kv1[k] = k1[k * 16 + e0];
-            AR::acc_mac(acc0[k], v[k], kv0[k], m);
-            AR::acc_mac(acc1[k], v[k], kv1[k], m);
-        }
+        for (int k = 0; k < 16; k++) AR::acc_mac(acc0[k], v[k], kv0[k], m);
+        if constexpr (!EARLY1) load_row_cp<false>(k1, e0, kv1);
+#pragma unroll
+        for (int k = 0; k < 16; k++) AR::acc_mac(acc1[k], v[k], kv1[k], m);
         if ((j & 7) == 7) {  // FpAr sums at most 8 lazily reduced products (0.69 q each) between reductions
 #pragma unroll
             for (int k = 0; k < 16; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
@@ -856,32 +913,36 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
 #pragma unroll
             for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0f]));
             NttCore<AR, A>::fwd_contig(v, lrow_f, e0f, rf, ti, tf, N, m);
-            exchange_cb_to_ca<AR>(v, lrow_f, e0f);
-            u64* o = a.out + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
-            const u64* bp = a.own + ((size_t)inst * 2 * L + i) * N;  // OWN_ROT: b, gathered at the rotated slots
+            exchange_cb_to_cp<AR>(v, lrow_f, e0f);
+            u64 res[16];
 #pragma unroll
             for (int k = 0; k < 16; k++) {
-                const u32 e = k * 16 + e0f;
                 const T fin = AR::acc_finish(t ? acc1[k] : acc0[k], m);
-                if constexpr (AR::is_fp) {
-                    const FpAr::Mod fm = FpAr::mod(pc);
-                    double ks = FpAr::mulmod_lazy(fin - v[k], pinv.d, fm);
-                    if (OWN == OWN_ROT && t == 0) ks += u64_to_f64(bp[eval_perm(row_off_f + e, gal_fin, tb.logN)]);
-                    __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[e]);
-                } else {
-                    u64 ks = mul_shoup(submod(AR::acc_canon(fin, m), AR::canon_fwd(v[k], m), pc.q), pinv.w, pinv.wp, pc.q);
-                    if (OWN == OWN_ROT && t == 0) ks = addmod(ks, bp[eval_perm(row_off_f + e, gal_fin, tb.logN)], pc.q);
-                    o[e] = ks;
+                if constexpr (AR::is_fp) res[k] = AR::to_raw(FpAr::mulmod_lazy(fin - v[k], pinv.d, FpAr::mod(pc)));
+                else res[k] = mul_shoup(submod(AR::acc_canon(fin, m), AR::canon_fwd(v[k], m), pc.q), pinv.w, pinv.wp, pc.q);
+            }
+            if (OWN == OWN_ROT && t == 0) {
+                u64 bw[16];
+                gather_row_cp(a.own + ((size_t)inst * 2 * L + i) * N, row_off_f, gal_fin, tb.logN, lrow_f, e0f, bw);
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    if constexpr (AR::is_fp) res[k] = AR::to_raw(AR::from_raw(res[k]) + u64_to_f64(bw[k]));
+                    else res[k] = addmod(res[k], bw[k], pc.q);
                 }
             }
+            if constexpr (AR::is_fp) {
+#pragma unroll
+                for (int k = 0; k < 16; k++) res[k] = FpAr::canon(AR::from_raw(res[k]), FpAr::mod(pc));
+            }
+            store_row_cp(a.out + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f, e0f, res);
         }
     } else if (i < a.split) {
-        u64* o0 = a.cq + (((size_t)inst * 2 + 0) * a.split + i) * N + row_off;
-        u64* o1 = a.cq + (((size_t)inst * 2 + 1) * a.split + i) * N + row_off;
+        u64 res[16];
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc0[k], m), m), &o0[k * 16 + e0]);
-            __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc1[k], m), m), &o1[k * 16 + e0]);
+        for (int t = 0; t < 2; t++) {
+#pragma unroll
+            for (int k = 0; k < 16; k++) res[k] = AR::acc_canon(AR::acc_finish(t ? acc1[k] : acc0[k], m), m);
+            store_row_cp(a.cq + (((size_t)inst * 2 + t) * a.split + i) * N + row_off, e0, res);
         }
     } else {
 #pragma unroll
@@ -889,7 +950,7 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             T x[16];
 #pragma unroll
             for (int k = 0; k < 16; k++) x[k] = AR::acc_finish(t ? acc1[k] : acc0[k], m);
-            exchange_ca_to_cb<AR>(x, lrow, e0);
+            exchange_cp_to_cb<AR>(x, lrow, e0);
             NttCore<AR, A>::inv_contig(x, lrow, e0, r, ti, tf, N, m);
             u64* o = a.cp + (((size_t)inst * 2 + t) * (D - a.split) + (i - a.split)) * N + row_off;
 #pragma unroll
@@ -905,6 +966,150 @@ __global__ __launch_bounds__(256, 2) void ks_inner_kernel(InnerArgs a, Tables tb
     u32 group, inst;
     if (!xcd_decode(blockIdx.x, a.n_inst, run.count * TILES, group, inst)) return;
     ks_inner_body<AR, A, OWN, HOISTED, FUSED>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
+}
+
+// ---- the same work with 32 lanes per row and 8 words per lane (NttRow8): about half the registers per lane, so
+// twice the waves per SIMD carry the same data in flight as independent instruction streams.  Not hoisted.
+// Work item = (limb i, tile of 8 rows, instance).  Both key components of a digit are requested before its
+// transform.  Everything else (own-digit loads, tensor terms, special limbs, FUSED tail) as in ks_inner_body.
+template <class AR, int A, int OWN, bool FUSED>
+__device__ __forceinline__ void ks_inner8_body(const InnerArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile, u32 inst) {
+    typedef typename AR::T T;
+    typedef NttRow8<AR, A> R8;
+    const u32 N = 1u << tb.logN, tid = threadIdx.x, e = tid % 32, ch = tid / 32, r = tile * 8 + ch;
+    const u32 L = tb.L, D = tb.D;
+    const u32 pi = tb.phys(i), Dkey = tb.Lfull + tb.K;
+    const PrimeConst pc = tb.pc[pi];
+    const typename AR::Mod m = AR::mod(pc);
+    const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
+    const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
+    u64* lrow = lds + ch * NTT8_ROW_WORDS;
+    const u32 row_off = r * 256;
+    const u32 kidx = a.per_inst ? inst : 0;
+    const u64* key = a.key[kidx] + (size_t)pi * N + row_off;
+    const u32 gal = a.galois[kidx];
+    const u32 own_digit = i < L ? i / tb.alpha : 0xffffffffu;
+    T acc0[8], acc1[8];
+#pragma unroll
+    for (int k = 0; k < 8; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
+    for (u32 j = 0; j < tb.dnum; j++) {
+        const u64* k0 = key + ((size_t)j * 2 + 0) * Dkey * N;
+        const u64* k1 = key + ((size_t)j * 2 + 1) * Dkey * N;
+        u64 kv0[8], kv1[8];
+#pragma unroll
+        for (int k = 0; k < 8; k++) kv0[k] = k0[k * 32 + e];
+#pragma unroll
+        for (int k = 0; k < 8; k++) kv1[k] = k1[k * 32 + e];
+        T v[8];
+        if (j == own_digit) {
+            if (OWN == OWN_COPY) {
+                const u64* p = a.own + ((size_t)inst * L + i) * N + row_off;
+#pragma unroll
+                for (int k = 0; k < 8; k++) v[k] = AR::round_reduce(AR::from_canon(p[k * 32 + e], m), m);
+            } else if (OWN == OWN_TENSOR) {
+                // P * (b1*b2) and P * (a1*b2 + a2*b1) join c' here (see ks_inner_body)
+                const size_t off = (((size_t)inst * 2 + 1) * L + i) * N + row_off, offb = off - (size_t)L * N;
+                const u64 pmod = tb.pmod[i];
+#pragma unroll
+                for (int k = 0; k < 8; k++) {
+                    const u32 w = k * 32 + e;
+                    const u64 a1 = __builtin_nontemporal_load(&a.own[off + w]), a2 = __builtin_nontemporal_load(&a.own2[off + w]);
+                    const u64 b1 = __builtin_nontemporal_load(&a.own[offb + w]), b2 = __builtin_nontemporal_load(&a.own2[offb + w]);
+                    v[k] = AR::round_reduce(AR::mul_canon(a1, a2, pc, m), m);
+                    AR::acc_mac(acc0[k], AR::mul_canon(b1, b2, pc, m), pmod, m);
+                    AR::acc_mac(acc1[k], AR::mul_canon(a1, b2, pc, m) + AR::mul_canon(a2, b1, pc, m), pmod, m);
+                }
+            } else {
+                const u64* p = a.own + (((size_t)inst * 2 + 1) * L + i) * N;
+#pragma unroll
+                for (int k = 0; k < 8; k++)
+                    v[k] = AR::round_reduce(AR::from_canon(p[eval_perm(row_off + k * 32 + e, gal, tb.logN)], m), m);
+            }
+        } else {
+            const u64* p = a.dt + (((size_t)inst * tb.dnum + j) * D + i) * N + row_off;
+#pragma unroll
+            for (int k = 0; k < 8; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 32 + e]));
+            R8::fwd_contig(v, lrow, e, r, ti, tf, N, m);
+            row8_exchange<AR, R8_R2, R8_R0, true>(v, lrow, e, m);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            AR::acc_mac(acc0[k], v[k], kv0[k], m);
+            AR::acc_mac(acc1[k], v[k], kv1[k], m);
+        }
+        if ((j & 7) == 7) {
+#pragma unroll
+            for (int k = 0; k < 8; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
+        }
+    }
+    if (FUSED) {
+        u32 ef = e, chf = ch, gal_fin = gal;  // opaque copies: see ks_inner_body
+        asm volatile("" : "+v"(ef), "+v"(chf), "+s"(gal_fin));
+        const u32 rf = tile * 8 + chf, row_off_f = rf * 256;
+        u64* lrow_f = lds + chf * NTT8_ROW_WORDS;
+        const PinvConst pinv = a.fin_pinv[i];
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            T v[8];
+            const u64* p = a.cv + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
+#pragma unroll
+            for (int k = 0; k < 8; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 32 + ef]));
+            R8::fwd_contig(v, lrow_f, ef, rf, ti, tf, N, m);
+            row8_exchange<AR, R8_R2, R8_R0, false>(v, lrow_f, ef, m);
+            u64* o = a.out + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
+            const u64* bp = a.own + ((size_t)inst * 2 * L + i) * N;  // OWN_ROT: b, gathered at the rotated slots
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const u32 w = k * 32 + ef;
+                const T fin = AR::acc_finish(t ? acc1[k] : acc0[k], m);
+                if constexpr (AR::is_fp) {
+                    const FpAr::Mod fm = FpAr::mod(pc);
+                    double ks = FpAr::mulmod_lazy(fin - v[k], pinv.d, fm);
+                    if (OWN == OWN_ROT && t == 0) ks += u64_to_f64(bp[eval_perm(row_off_f + w, gal_fin, tb.logN)]);
+                    __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[w]);
+                } else {
+                    u64 ks = mul_shoup(submod(AR::acc_canon(fin, m), AR::canon_fwd(v[k], m), pc.q), pinv.w, pinv.wp, pc.q);
+                    if (OWN == OWN_ROT && t == 0) ks = addmod(ks, bp[eval_perm(row_off_f + w, gal_fin, tb.logN)], pc.q);
+                    o[w] = ks;
+                }
+            }
+        }
+    } else if (i < a.split) {
+        u64* o0 = a.cq + (((size_t)inst * 2 + 0) * a.split + i) * N + row_off;
+        u64* o1 = a.cq + (((size_t)inst * 2 + 1) * a.split + i) * N + row_off;
+#pragma unroll
+        for (int k = 0; k < 8; k++) {
+            __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc0[k], m), m), &o0[k * 32 + e]);
+            __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc1[k], m), m), &o1[k * 32 + e]);
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            T x[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) x[k] = AR::acc_finish(t ? acc1[k] : acc0[k], m);
+            row8_exchange<AR, R8_R0, R8_R2, false>(x, lrow, e, m);
+            R8::inv_contig(x, lrow, e, r, ti, tf, N, m);
+            u64* o = a.cp + (((size_t)inst * 2 + t) * (D - a.split) + (i - a.split)) * N + row_off;
+#pragma unroll
+            for (int k = 0; k < 8; k++) o[k * 32 + e] = AR::to_raw(AR::round_reduce(x[k], m));
+        }
+    }
+}
+
+#ifndef CKKS_INNER8_WAVES_FP
+#define CKKS_INNER8_WAVES_FP 4
+#endif
+#ifndef CKKS_INNER8_WAVES_INT
+#define CKKS_INNER8_WAVES_INT 3
+#endif
+template <class AR, int A, int OWN, bool FUSED>
+__global__ __launch_bounds__(256, AR::is_fp ? CKKS_INNER8_WAVES_FP : CKKS_INNER8_WAVES_INT) void ks_inner8_kernel(InnerArgs a, Tables tb, LimbRun run) {
+    __shared__ u64 lds[NTT8_LDS_WORDS];
+    constexpr u32 TILES = (1u << A) / 8;
+    u32 group, inst;
+    if (!xcd_decode(blockIdx.x, a.n_inst, run.count * TILES, group, inst)) return;
+    ks_inner8_body<AR, A, OWN, FUSED>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
 }
 
 // ===================================================== double-hoisted rotate-multiply-accumulate
