@@ -85,6 +85,64 @@ __device__ __forceinline__ size_t limb_offset(const LimbSel& s, u32 inst, u32 l)
     return (size_t)inst * s.gs + s.first + l;
 }
 
+// Layout CP of the 16 words of a lane in a 256-word row (lane e0 of the row's 16): register kk holds word
+// (kk/2)*32 + e0*2 + kk%2, i.e. eight adjacent pairs: every global access of the inner product that does not feed a
+// transform directly (keys, own-digit operands, results) is a 16-byte access per lane, half the memory
+// instructions of the one-word-per-access layout CA.  The per-instruction cost of the address path, not the
+// bytes, is what the kernel's memory side was bound by.
+typedef u64 u64x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32 cp_word(u32 e0, int kk) { return (u32)(kk >> 1) * 32 + e0 * 2 + (u32)(kk & 1); }
+template <bool NT>
+__device__ __forceinline__ void load_row_cp(const u64* row, u32 e0, u64 (&o)[16]) {
+#pragma unroll
+    for (int k2 = 0; k2 < 8; k2++) {
+        const u64x2* p = reinterpret_cast<const u64x2*>(row + k2 * 32 + e0 * 2);
+        const u64x2 t = NT ? __builtin_nontemporal_load(p) : *p;
+        o[2 * k2] = t.x, o[2 * k2 + 1] = t.y;
+    }
+}
+__device__ __forceinline__ void store_row_cp(u64* row, u32 e0, const u64 (&v)[16]) {
+#pragma unroll
+    for (int k2 = 0; k2 < 8; k2++) {
+        u64x2 t;
+        t.x = v[2 * k2], t.y = v[2 * k2 + 1];
+        __builtin_nontemporal_store(t, reinterpret_cast<u64x2*>(row + k2 * 32 + e0 * 2));
+    }
+}
+// between the contiguous-pass layout CB (word e0*16 + k) and CP, through the row's LDS slice
+template <class AR>
+__device__ __forceinline__ void exchange_cb_to_cp(typename AR::T (&x)[16], u64* l, u32 e0) {
+    row_sync();
+#pragma unroll
+    for (int k = 0; k < 16; k++) l[pad16(e0 * 16 + k)] = AR::to_raw(x[k]);
+    row_sync();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) x[kk] = AR::from_raw(l[pad16(cp_word(e0, kk))]);
+}
+template <class AR>
+__device__ __forceinline__ void exchange_cp_to_cb(typename AR::T (&x)[16], u64* l, u32 e0) {
+    row_sync();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) l[pad16(cp_word(e0, kk))] = AR::to_raw(x[kk]);
+    row_sync();
+#pragma unroll
+    for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(e0 * 16 + k)]);
+}
+// Row `row_off/256` of sigma_g(f) in layout CP.  In evaluation order the automorphism maps a 256-word row onto one
+// source row (the row index is the bit-reversed low part of the exponent index, and multiplication by g keeps low
+// parts among themselves), so the source row is loaded whole with 16-byte accesses, staged in the row's LDS
+// slice and permuted there, instead of one scattered 8-byte global access per word.
+__device__ __forceinline__ void gather_row_cp(const u64* limb, u32 row_off, u32 gal, u32 logN, u64* l, u32 e0, u64 (&o)[16]) {
+    const u32 src_row = eval_perm(row_off, gal, logN) >> 8;
+    load_row_cp<false>(limb + (size_t)src_row * 256, e0, o);
+    row_sync();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) l[pad16(cp_word(e0, kk))] = o[kk];
+    row_sync();
+#pragma unroll
+    for (int kk = 0; kk < 16; kk++) o[kk] = l[pad16(eval_perm(row_off + cp_word(e0, kk), gal, logN) & 255)];
+}
+
 // most rotations (each with its own key and Galois element) one launch can be given
 #define CKKS_ROT_CHUNK 16
 
@@ -111,24 +169,36 @@ __device__ __forceinline__ void inv_contig_body(const InvContigArgs& a, const Ta
     const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
     u64* lrow = lds + ch * 272;
     T x[16];
+    // operands arrive in layout CP (16-byte accesses) and are brought into the pass's layout CB by the exchange
+    // that the pass needs anyway; a rotation applies its permutation in that exchange
     if (LOAD == INV_PLAIN) {
-        const u64* p = a.src + limb_offset(a.sel, inst, l) * N + (size_t)r * 256;
+        u64 w[16];
+        load_row_cp<true>(a.src + limb_offset(a.sel, inst, l) * N + (size_t)r * 256, e0, w);
 #pragma unroll
-        for (int k = 0; k < 16; k++) x[k] = AR::round_reduce(AR::from_canon(__builtin_nontemporal_load(&p[k * 16 + e0]), m), m);
+        for (int k = 0; k < 16; k++) x[k] = AR::round_reduce(AR::from_canon(w[k], m), m);
+        exchange_cp_to_cb<AR>(x, lrow, e0);
     } else if (LOAD == INV_TENSOR) {  // d2 = a1 * a2 on limb l of pair `inst`
         const size_t off = (((size_t)inst * 2 + 1) * tb.L + l) * N + (size_t)r * 256;
+        u64 w1[16], w2[16];
+        load_row_cp<true>(a.src + off, e0, w1);
+        load_row_cp<true>(a.src2 + off, e0, w2);
 #pragma unroll
-        for (int k = 0; k < 16; k++) {
-            x[k] = AR::round_reduce(AR::mul_canon(__builtin_nontemporal_load(&a.src[off + k * 16 + e0]), __builtin_nontemporal_load(&a.src2[off + k * 16 + e0]), pc, m), m);
-        }
-    } else {  // sigma_g(a) on limb l of ciphertext `inst`
+        for (int k = 0; k < 16; k++) x[k] = AR::round_reduce(AR::mul_canon(w1[k], w2[k], pc, m), m);
+        exchange_cp_to_cb<AR>(x, lrow, e0);
+    } else {  // sigma_g(a) on limb l of ciphertext `inst`: the source row, whole, permuted on its way through LDS
         const u32 gal = a.galois[a.per_inst ? inst : 0];
         const u64* p = a.src + (((size_t)inst * 2 + 1) * tb.L + l) * N;
+        const u32 src_row = eval_perm(r * 256, gal, tb.logN) >> 8;
+        u64 w[16];
+        load_row_cp<false>(p + (size_t)src_row * 256, e0, w);
+        row_sync();
+#pragma unroll
+        for (int kk = 0; kk < 16; kk++) lrow[pad16(cp_word(e0, kk))] = w[kk];
+        row_sync();
 #pragma unroll
         for (int k = 0; k < 16; k++)
-            x[k] = AR::round_reduce(AR::from_canon(p[eval_perm(r * 256 + k * 16 + e0, gal, tb.logN)], m), m);
+            x[k] = AR::round_reduce(AR::from_canon(lrow[pad16(eval_perm(r * 256 + e0 * 16 + k, gal, tb.logN) & 255)], m), m);
     }
-    exchange_ca_to_cb<AR>(x, lrow, e0);
     NttCore<AR, A>::inv_contig(x, lrow, e0, r, ti, tf, N, m);
     u64* o = a.dst + limb_offset(a.dsel, inst, l) * N + (size_t)r * 256;
 #pragma unroll
@@ -702,8 +772,10 @@ __device__ __forceinline__ void fwd_contig_body(const FwdContigArgs& a, const Ta
 #pragma unroll
     for (int k = 0; k < 16; k++) lrow[pad16(e0 * 16 + k)] = AR::canon_fwd(x[k], m);
     row_sync();
+    u64 res[16];  // stored in layout CP: 16 bytes per access
 #pragma unroll
-    for (int k = 0; k < 16; k++) p[k * 16 + e0] = lrow[pad16(k * 16 + e0)];
+    for (int kk = 0; kk < 16; kk++) res[kk] = lrow[pad16(cp_word(e0, kk))];
+    store_row_cp(p, e0, res);
 }
 
 template <class AR, int A>
@@ -740,64 +812,6 @@ struct InnerArgs {
     u64* out;                   // [inst][2][split][N]
     const PinvConst* fin_pinv;  // [split] inverse of the product of the ModDown's source primes
 };
-
-// Layout CP of the 16 words of a lane in a 256-word row (lane e0 of the row's 16): register kk holds word
-// (kk/2)*32 + e0*2 + kk%2, i.e. eight adjacent pairs: every global access of the inner product that does not feed a
-// transform directly (keys, own-digit operands, results) is a 16-byte access per lane, half the memory
-// instructions of the one-word-per-access layout CA.  The per-instruction cost of the address path, not the
-// bytes, is what the kernel's memory side was bound by.
-typedef u64 u64x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ u32 cp_word(u32 e0, int kk) { return (u32)(kk >> 1) * 32 + e0 * 2 + (u32)(kk & 1); }
-template <bool NT>
-__device__ __forceinline__ void load_row_cp(const u64* row, u32 e0, u64 (&o)[16]) {
-#pragma unroll
-    for (int k2 = 0; k2 < 8; k2++) {
-        const u64x2* p = reinterpret_cast<const u64x2*>(row + k2 * 32 + e0 * 2);
-        const u64x2 t = NT ? __builtin_nontemporal_load(p) : *p;
-        o[2 * k2] = t.x, o[2 * k2 + 1] = t.y;
-    }
-}
-__device__ __forceinline__ void store_row_cp(u64* row, u32 e0, const u64 (&v)[16]) {
-#pragma unroll
-    for (int k2 = 0; k2 < 8; k2++) {
-        u64x2 t;
-        t.x = v[2 * k2], t.y = v[2 * k2 + 1];
-        __builtin_nontemporal_store(t, reinterpret_cast<u64x2*>(row + k2 * 32 + e0 * 2));
-    }
-}
-// between the contiguous-pass layout CB (word e0*16 + k) and CP, through the row's LDS slice
-template <class AR>
-__device__ __forceinline__ void exchange_cb_to_cp(typename AR::T (&x)[16], u64* l, u32 e0) {
-    row_sync();
-#pragma unroll
-    for (int k = 0; k < 16; k++) l[pad16(e0 * 16 + k)] = AR::to_raw(x[k]);
-    row_sync();
-#pragma unroll
-    for (int kk = 0; kk < 16; kk++) x[kk] = AR::from_raw(l[pad16(cp_word(e0, kk))]);
-}
-template <class AR>
-__device__ __forceinline__ void exchange_cp_to_cb(typename AR::T (&x)[16], u64* l, u32 e0) {
-    row_sync();
-#pragma unroll
-    for (int kk = 0; kk < 16; kk++) l[pad16(cp_word(e0, kk))] = AR::to_raw(x[kk]);
-    row_sync();
-#pragma unroll
-    for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(e0 * 16 + k)]);
-}
-// Row `row_off/256` of sigma_g(f) in layout CP.  In evaluation order the automorphism maps a 256-word row onto one
-// source row (the row index is the bit-reversed low part of the exponent index, and multiplication by g keeps low
-// parts among themselves), so the source row is loaded whole with 16-byte accesses, staged in the row's LDS
-// slice and permuted there, instead of one scattered 8-byte global access per word.
-__device__ __forceinline__ void gather_row_cp(const u64* limb, u32 row_off, u32 gal, u32 logN, u64* l, u32 e0, u64 (&o)[16]) {
-    const u32 src_row = eval_perm(row_off, gal, logN) >> 8;
-    load_row_cp<false>(limb + (size_t)src_row * 256, e0, o);
-    row_sync();
-#pragma unroll
-    for (int kk = 0; kk < 16; kk++) l[pad16(cp_word(e0, kk))] = o[kk];
-    row_sync();
-#pragma unroll
-    for (int kk = 0; kk < 16; kk++) o[kk] = l[pad16(eval_perm(row_off + cp_word(e0, kk), gal, logN) & 255)];
-}
 
 template <class AR, int A, int OWN, bool HOISTED, bool FUSED>
 __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile,
@@ -1317,94 +1331,78 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
     u64* lrow = lds + ch * 272;
     const u32 row_off = r * 256;
     const u64 q = pc.q;
-    if constexpr (AR::is_fp) {
-        // FP64 pipe (magnitudes in units of q): v <= 5.2, c' - v <= 6.2, ks = (c' - v) * P^-1 <= 2.9,
-        // every added product of canonical operands <= 0.875; everything is canonicalised before the store.
-        const FpAr::Mod fm = FpAr::mod(pc);
-        if (MODE == FIN_HOISTED) {
-            const u32 t = inst;
-            double acc[16];
-#pragma unroll
-            for (int k = 0; k < 16; k++) acc[k] = 0.0;
-            for (u32 rr = 0; rr < a.n_rot; rr++) {
-                T v[16];
-                const u64* p = a.cv + (((size_t)rr * 2 + t) * L + i) * N + row_off;
-#pragma unroll
-                for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
-                NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
-                exchange_cb_to_ca<AR>(v, lrow, e0);
-                const u64* c = a.cq + (((size_t)rr * 2 + t) * L + i) * N + row_off;
-                const u64* ptp = a.pt + ((size_t)rr * L + i) * N + row_off;
-                const u64* bp = a.ct1 + (size_t)i * N;
-#pragma unroll
-                for (int k = 0; k < 16; k++) {
-                    double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[k * 16 + e0])) - v[k], pinv.d, fm);
-                    if (t == 0) ks += u64_to_f64(bp[eval_perm(row_off + k * 16 + e0, a.galois[rr], tb.logN)]);
-                    // reduced to <= q/2 so that the at most 8 products accumulated between folds stay below 6 q
-                    acc[k] += FpAr::mulmod_lazy(FpAr::reduce(ks, fm), u64_to_f64(__builtin_nontemporal_load(&ptp[k * 16 + e0])), fm);
-                }
-                if ((rr & 7) == 7) {
-#pragma unroll
-                    for (int k = 0; k < 16; k++) acc[k] = FpAr::reduce(acc[k], fm);
-                }
-            }
-            u64* o = a.out + ((size_t)t * L + i) * N + row_off;
-#pragma unroll
-            for (int k = 0; k < 16; k++) {
-                double res = acc[k];
-                if (a.accumulate) res += u64_to_f64(o[k * 16 + e0]);
-                __builtin_nontemporal_store(FpAr::canon(res, fm), &o[k * 16 + e0]);
-            }
-            return;
-        }
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-            T v[16];
-            const u64* p = a.cv + (((size_t)inst * 2 + t) * L + i) * N + row_off;
-#pragma unroll
-            for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
-            NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
-            exchange_cb_to_ca<AR>(v, lrow, e0);
-            const u64* c = a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off;
-            u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
-#pragma unroll
-            for (int k = 0; k < 16; k++) {
-                const u32 e = k * 16 + e0;
-                const double ks = FpAr::mulmod_lazy(u64_to_f64(__builtin_nontemporal_load(&c[e])) - v[k], pinv.d, fm);
-                __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[e]);
-            }
-        }
-        return;
-    }
+    // The converted part leaves its second forward pass in layout CP: c', plaintexts and results move with 16-byte
+    // accesses, and sigma_g(b) comes as a whole source row permuted in LDS (gather_row_cp).
+    // FP64 pipe (magnitudes in units of q): v <= 5.2, c' - v <= 6.2, ks = (c' - v) * P^-1 <= 2.9,
+    // every added product of canonical operands <= 0.875; everything is canonicalised before the store.
     if (MODE == FIN_HOISTED) {
         const u32 t = inst;
-        u128w acc[16];
+        double facc[AR::is_fp ? 16 : 1];
+        u128w iacc[AR::is_fp ? 1 : 16];
 #pragma unroll
-        for (int k = 0; k < 16; k++) acc[k] = u128w{0, 0};
+        for (int k = 0; k < 16; k++) {
+            if constexpr (AR::is_fp) facc[k] = 0.0;
+            else iacc[k] = u128w{0, 0};
+        }
         for (u32 rr = 0; rr < a.n_rot; rr++) {
             T v[16];
             const u64* p = a.cv + (((size_t)rr * 2 + t) * L + i) * N + row_off;
 #pragma unroll
             for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
             NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
-            exchange_cb_to_ca<AR>(v, lrow, e0);
-            const u64* c = a.cq + (((size_t)rr * 2 + t) * L + i) * N + row_off;
-            const u64* ptp = a.pt + ((size_t)rr * L + i) * N + row_off;
-            const u64* bp = a.ct1 + (size_t)i * N;
+            exchange_cb_to_cp<AR>(v, lrow, e0);
+            // one operand stream at a time: c', then sigma_g(b), then the plaintext (16 words each)
+            T ks[16];
+            {
+                u64 c[16];
+                load_row_cp<true>(a.cq + (((size_t)rr * 2 + t) * L + i) * N + row_off, e0, c);
 #pragma unroll
-            for (int k = 0; k < 16; k++) {
-                u64 ks = mul_shoup(submod(c[k * 16 + e0], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
-                if (t == 0) ks = addmod(ks, bp[eval_perm(row_off + k * 16 + e0, a.galois[rr], tb.logN)], q);
-                mac128(acc[k], ks, ptp[k * 16 + e0]);
+                for (int k = 0; k < 16; k++) {
+                    if constexpr (AR::is_fp) ks[k] = FpAr::mulmod_lazy(u64_to_f64(c[k]) - v[k], pinv.d, FpAr::mod(pc));
+                    else ks[k] = mul_shoup(submod(c[k], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
+                }
+            }
+            if (t == 0) {
+                u64 bw[16];
+                gather_row_cp(a.ct1 + (size_t)i * N, row_off, a.galois[rr], tb.logN, lrow, e0, bw);
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    if constexpr (AR::is_fp) ks[k] += u64_to_f64(bw[k]);
+                    else ks[k] = addmod(ks[k], bw[k], q);
+                }
+            }
+            {
+                u64 ptw[16];
+                load_row_cp<true>(a.pt + ((size_t)rr * L + i) * N + row_off, e0, ptw);
+#pragma unroll
+                for (int k = 0; k < 16; k++) {
+                    // FP64: reduced to <= q/2 so that the at most 8 products accumulated between folds stay below 6 q
+                    if constexpr (AR::is_fp) facc[k] += FpAr::mulmod_lazy(FpAr::reduce(ks[k], FpAr::mod(pc)), u64_to_f64(ptw[k]), FpAr::mod(pc));
+                    else mac128(iacc[k], ks[k], ptw[k]);
+                }
+            }
+            if constexpr (AR::is_fp) {
+                if ((rr & 7) == 7) {
+#pragma unroll
+                    for (int k = 0; k < 16; k++) facc[k] = FpAr::reduce(facc[k], FpAr::mod(pc));
+                }
             }
         }
         u64* o = a.out + ((size_t)t * L + i) * N + row_off;
+        u64 prev[16], res[16];
+        if (a.accumulate) load_row_cp<false>(o, e0, prev);
 #pragma unroll
         for (int k = 0; k < 16; k++) {
-            u64 res = reduce128(acc[k], q, pc.qneg, pc.r2);
-            if (a.accumulate) res = addmod(res, o[k * 16 + e0], q);
-            o[k * 16 + e0] = res;
+            if constexpr (AR::is_fp) {
+                double x = facc[k];
+                if (a.accumulate) x += u64_to_f64(prev[k]);
+                res[k] = FpAr::canon(x, FpAr::mod(pc));
+            } else {
+                res[k] = reduce128(iacc[k], q, pc.qneg, pc.r2);
+                if (a.accumulate) res[k] = addmod(res[k], prev[k], q);
+            }
         }
+        store_row_cp(o, e0, res);
         return;
     }
 #pragma unroll
@@ -1414,19 +1412,24 @@ __device__ __forceinline__ void ks_final_body(const FinalArgs& a, const Tables& 
 #pragma unroll
         for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
         NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
-        exchange_cb_to_ca<AR>(v, lrow, e0);
-        const u64* c = a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off;
-        u64* o = a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off;
+        exchange_cb_to_cp<AR>(v, lrow, e0);
+        u64 c[16], res[16];
+        load_row_cp<true>(a.cq + (((size_t)inst * 2 + t) * a.cq_L + i) * N + row_off, e0, c);
 #pragma unroll
         for (int k = 0; k < 16; k++) {
-            const u32 e = k * 16 + e0;
-            o[e] = mul_shoup(submod(c[e], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
+            if constexpr (AR::is_fp) {
+                const FpAr::Mod fm = FpAr::mod(pc);
+                res[k] = FpAr::canon(FpAr::mulmod_lazy(u64_to_f64(c[k]) - v[k], pinv.d, fm), fm);
+            } else {
+                res[k] = mul_shoup(submod(c[k], AR::canon_fwd(v[k], m), q), pinv.w, pinv.wp, q);
+            }
         }
+        store_row_cp(a.out + (((size_t)inst * 2 + t) * L + i) * N + row_off, e0, res);
     }
 }
 
 template <class AR, int A, int MODE>
-__global__ __launch_bounds__(256) void ks_final_kernel(FinalArgs a, Tables tb, LimbRun run) {
+__global__ __launch_bounds__(256, MODE == FIN_HOISTED ? (AR::is_fp ? 3 : 2) : 4) void ks_final_kernel(FinalArgs a, Tables tb, LimbRun run) {
     __shared__ u64 lds[NTT_LDS_WORDS];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;

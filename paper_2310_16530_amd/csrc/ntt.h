@@ -170,26 +170,6 @@ struct NttCore {
     }
 };
 
-// exchange between the two contiguous-pass layouts through the row's LDS slice
-template <class AR>
-__device__ __forceinline__ void exchange_cb_to_ca(typename AR::T (&x)[16], u64* l, u32 e0) {
-    row_sync();
-#pragma unroll
-    for (int k = 0; k < 16; k++) l[pad16(e0 * 16 + k)] = AR::to_raw(x[k]);
-    row_sync();
-#pragma unroll
-    for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(k * 16 + e0)]);
-}
-template <class AR>
-__device__ __forceinline__ void exchange_ca_to_cb(typename AR::T (&x)[16], u64* l, u32 e0) {
-    row_sync();
-#pragma unroll
-    for (int k = 0; k < 16; k++) l[pad16(k * 16 + e0)] = AR::to_raw(x[k]);
-    row_sync();
-#pragma unroll
-    for (int k = 0; k < 16; k++) x[k] = AR::from_raw(l[pad16(e0 * 16 + k)]);
-}
-
 // ---------------------------------------------------------------------------------------------
 // Contiguous pass with 32 lanes per 256-word row and 8 words per lane: half the registers per lane of the
 // 16-word form above, for kernels that keep accumulators across several transforms (the key inner product)
