@@ -7,7 +7,6 @@
 #include <string.h>
 
 #include <string>
-#include <type_traits>
 #include <vector>
 
 #include "../../include/ckks_mi355x.h"
@@ -1072,28 +1071,13 @@ static void launch_fwd_contig(const View* c, const FwdContigArgs& a, hipStream_t
                             [per](u32, u32 n) { return per * n; });
 }
 
-// the inner product with 32 lanes per row (ks_inner8_kernel): tiles of 8 rows
-template <int OWN, bool FUSED>
-struct KsInner8L {
-    template <class AR, int A>
-    static void go(dim3 g, hipStream_t s, const InnerArgs& a, const Tables& tb, LimbRun run) {
-        hipLaunchKernelGGL((ks_inner8_kernel<AR, A, OWN, FUSED>), g, dim3(256), 0, s, a, tb, run);
-    }
-    static std::string name(const char* ar, int A) {
-        return kname("ks_inner8_kernel", ar, A, (std::string(", ") + std::to_string(OWN) + (FUSED ? ", true" : ", false")).c_str());
-    }
-};
 // limbs [lo, hi) of the extended basis.  FUSED: the launch also ends the ModDown on its limbs (all below
 // a.split, after the conversion of the special part) and writes the result instead of c'.
-#ifndef CKKS_INNER8
-#define CKKS_INNER8 0
-#endif
-template <int OWN, bool HOISTED, bool FUSED = false, bool ROW32 = false>
+template <int OWN, bool HOISTED, bool FUSED = false>
 static void launch_ks_inner(const View* c, const InnerArgs& a, hipStream_t s, u32 lo, u32 hi) {
     const u64 n_inst = a.n_inst;
-    typedef typename std::conditional<ROW32 && !HOISTED, KsInner8L<OWN, FUSED>, KsInnerL<OWN, HOISTED, FUSED>>::type Launcher;
-    launch_runs<Launcher>(
-        c, lo, hi, 0, true, tiles_of(c) * (ROW32 && !HOISTED ? 2 : 1), a.n_inst, a, s, [c, n_inst](u32 first, u32 n) {
+    launch_runs<KsInnerL<OWN, HOISTED, FUSED>>(
+        c, lo, hi, 0, true, tiles_of(c), a.n_inst, a, s, [c, n_inst](u32 first, u32 n) {
             u64 limbs = 0;
             for (u32 i = first; i < first + n; i++) {
                 const bool q = i < c->L;
@@ -1553,15 +1537,15 @@ static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, co
     // the limbs that feed the ModDown conversion first; the q-limbs then finish in one kernel, c' in registers
     if (cm != c) {
         join_fp_beside(c, s);  // limb cm->L is a q-limb here: its digits come from the FpAr conversion
-        launch_ks_inner<OWN, false, false, (CKKS_INNER8 & 2) != 0>(c, ia, s, cm->L, c->D);
+        launch_ks_inner<OWN, false, false>(c, ia, s, cm->L, c->D);
     } else {
         // special limbs belong to no digit, so every variant computes the same on them: the leanest one runs
-        launch_ks_inner<OWN_COPY, false, false, (CKKS_INNER8 & 2) != 0>(c, ia, s, c->L, c->D);
+        launch_ks_inner<OWN_COPY, false, false>(c, ia, s, c->L, c->D);
     }
     moddown_convert(cm, w, batch, s);
     ia.cv = w.cv, ia.out = out, ia.fin_pinv = cm->tb.pinv;
     join_fp_beside(c, s);
-    launch_ks_inner<OWN, false, true, (CKKS_INNER8 & 1) != 0>(c, ia, s, 0, cm->L);
+    launch_ks_inner<OWN, false, true>(c, ia, s, 0, cm->L);
 }
 
 extern "C" int ckks_keyswitch_at(ckks_ctx* ctx, uint32_t level, const uint64_t* d_d, const uint64_t* d_key,

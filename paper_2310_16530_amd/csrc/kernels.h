@@ -101,12 +101,15 @@ __device__ __forceinline__ void load_row_cp(const u64* row, u32 e0, u64 (&o)[16]
         o[2 * k2] = t.x, o[2 * k2 + 1] = t.y;
     }
 }
+template <bool NT = true>
 __device__ __forceinline__ void store_row_cp(u64* row, u32 e0, const u64 (&v)[16]) {
 #pragma unroll
     for (int k2 = 0; k2 < 8; k2++) {
         u64x2 t;
         t.x = v[2 * k2], t.y = v[2 * k2 + 1];
-        __builtin_nontemporal_store(t, reinterpret_cast<u64x2*>(row + k2 * 32 + e0 * 2));
+        u64x2* p = reinterpret_cast<u64x2*>(row + k2 * 32 + e0 * 2);
+        if (NT) __builtin_nontemporal_store(t, p);
+        else *p = t;
     }
 }
 // between the contiguous-pass layout CB (word e0*16 + k) and CP, through the row's LDS slice
@@ -772,10 +775,10 @@ __device__ __forceinline__ void fwd_contig_body(const FwdContigArgs& a, const Ta
 #pragma unroll
     for (int k = 0; k < 16; k++) lrow[pad16(e0 * 16 + k)] = AR::canon_fwd(x[k], m);
     row_sync();
-    u64 res[16];  // stored in layout CP: 16 bytes per access
+    u64 res[16];  // stored in layout CP: 16 bytes per access; cacheable, the caller's next call reads it
 #pragma unroll
     for (int kk = 0; kk < 16; kk++) res[kk] = lrow[pad16(cp_word(e0, kk))];
-    store_row_cp(p, e0, res);
+    store_row_cp<false>(p, e0, res);
 }
 
 template <class AR, int A>
@@ -980,150 +983,6 @@ __global__ __launch_bounds__(256, 2) void ks_inner_kernel(InnerArgs a, Tables tb
     u32 group, inst;
     if (!xcd_decode(blockIdx.x, a.n_inst, run.count * TILES, group, inst)) return;
     ks_inner_body<AR, A, OWN, HOISTED, FUSED>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
-}
-
-// ---- the same work with 32 lanes per row and 8 words per lane (NttRow8): about half the registers per lane, so
-// twice the waves per SIMD carry the same data in flight as independent instruction streams.  Not hoisted.
-// Work item = (limb i, tile of 8 rows, instance).  Both key components of a digit are requested before its
-// transform.  Everything else (own-digit loads, tensor terms, special limbs, FUSED tail) as in ks_inner_body.
-template <class AR, int A, int OWN, bool FUSED>
-__device__ __forceinline__ void ks_inner8_body(const InnerArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile, u32 inst) {
-    typedef typename AR::T T;
-    typedef NttRow8<AR, A> R8;
-    const u32 N = 1u << tb.logN, tid = threadIdx.x, e = tid % 32, ch = tid / 32, r = tile * 8 + ch;
-    const u32 L = tb.L, D = tb.D;
-    const u32 pi = tb.phys(i), Dkey = tb.Lfull + tb.K;
-    const PrimeConst pc = tb.pc[pi];
-    const typename AR::Mod m = AR::mod(pc);
-    const u64* ti = tb.tw_int + (size_t)pi * 4 * N;
-    const double* tf = tb.tw_fp + (size_t)pi * 2 * N;
-    u64* lrow = lds + ch * NTT8_ROW_WORDS;
-    const u32 row_off = r * 256;
-    const u32 kidx = a.per_inst ? inst : 0;
-    const u64* key = a.key[kidx] + (size_t)pi * N + row_off;
-    const u32 gal = a.galois[kidx];
-    const u32 own_digit = i < L ? i / tb.alpha : 0xffffffffu;
-    T acc0[8], acc1[8];
-#pragma unroll
-    for (int k = 0; k < 8; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
-    for (u32 j = 0; j < tb.dnum; j++) {
-        const u64* k0 = key + ((size_t)j * 2 + 0) * Dkey * N;
-        const u64* k1 = key + ((size_t)j * 2 + 1) * Dkey * N;
-        u64 kv0[8], kv1[8];
-#pragma unroll
-        for (int k = 0; k < 8; k++) kv0[k] = k0[k * 32 + e];
-#pragma unroll
-        for (int k = 0; k < 8; k++) kv1[k] = k1[k * 32 + e];
-        T v[8];
-        if (j == own_digit) {
-            if (OWN == OWN_COPY) {
-                const u64* p = a.own + ((size_t)inst * L + i) * N + row_off;
-#pragma unroll
-                for (int k = 0; k < 8; k++) v[k] = AR::round_reduce(AR::from_canon(p[k * 32 + e], m), m);
-            } else if (OWN == OWN_TENSOR) {
-                // P * (b1*b2) and P * (a1*b2 + a2*b1) join c' here (see ks_inner_body)
-                const size_t off = (((size_t)inst * 2 + 1) * L + i) * N + row_off, offb = off - (size_t)L * N;
-                const u64 pmod = tb.pmod[i];
-#pragma unroll
-                for (int k = 0; k < 8; k++) {
-                    const u32 w = k * 32 + e;
-                    const u64 a1 = __builtin_nontemporal_load(&a.own[off + w]), a2 = __builtin_nontemporal_load(&a.own2[off + w]);
-                    const u64 b1 = __builtin_nontemporal_load(&a.own[offb + w]), b2 = __builtin_nontemporal_load(&a.own2[offb + w]);
-                    v[k] = AR::round_reduce(AR::mul_canon(a1, a2, pc, m), m);
-                    AR::acc_mac(acc0[k], AR::mul_canon(b1, b2, pc, m), pmod, m);
-                    AR::acc_mac(acc1[k], AR::mul_canon(a1, b2, pc, m) + AR::mul_canon(a2, b1, pc, m), pmod, m);
-                }
-            } else {
-                const u64* p = a.own + (((size_t)inst * 2 + 1) * L + i) * N;
-#pragma unroll
-                for (int k = 0; k < 8; k++)
-                    v[k] = AR::round_reduce(AR::from_canon(p[eval_perm(row_off + k * 32 + e, gal, tb.logN)], m), m);
-            }
-        } else {
-            const u64* p = a.dt + (((size_t)inst * tb.dnum + j) * D + i) * N + row_off;
-#pragma unroll
-            for (int k = 0; k < 8; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 32 + e]));
-            R8::fwd_contig(v, lrow, e, r, ti, tf, N, m);
-            row8_exchange<AR, R8_R2, R8_R0, true>(v, lrow, e, m);
-        }
-#pragma unroll
-        for (int k = 0; k < 8; k++) {
-            AR::acc_mac(acc0[k], v[k], kv0[k], m);
-            AR::acc_mac(acc1[k], v[k], kv1[k], m);
-        }
-        if ((j & 7) == 7) {
-#pragma unroll
-            for (int k = 0; k < 8; k++) acc0[k] = AR::acc_fold(acc0[k], m), acc1[k] = AR::acc_fold(acc1[k], m);
-        }
-    }
-    if (FUSED) {
-        u32 ef = e, chf = ch, gal_fin = gal;  // opaque copies: see ks_inner_body
-        asm volatile("" : "+v"(ef), "+v"(chf), "+s"(gal_fin));
-        const u32 rf = tile * 8 + chf, row_off_f = rf * 256;
-        u64* lrow_f = lds + chf * NTT8_ROW_WORDS;
-        const PinvConst pinv = a.fin_pinv[i];
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-            T v[8];
-            const u64* p = a.cv + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
-#pragma unroll
-            for (int k = 0; k < 8; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 32 + ef]));
-            R8::fwd_contig(v, lrow_f, ef, rf, ti, tf, N, m);
-            row8_exchange<AR, R8_R2, R8_R0, false>(v, lrow_f, ef, m);
-            u64* o = a.out + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
-            const u64* bp = a.own + ((size_t)inst * 2 * L + i) * N;  // OWN_ROT: b, gathered at the rotated slots
-#pragma unroll
-            for (int k = 0; k < 8; k++) {
-                const u32 w = k * 32 + ef;
-                const T fin = AR::acc_finish(t ? acc1[k] : acc0[k], m);
-                if constexpr (AR::is_fp) {
-                    const FpAr::Mod fm = FpAr::mod(pc);
-                    double ks = FpAr::mulmod_lazy(fin - v[k], pinv.d, fm);
-                    if (OWN == OWN_ROT && t == 0) ks += u64_to_f64(bp[eval_perm(row_off_f + w, gal_fin, tb.logN)]);
-                    __builtin_nontemporal_store(FpAr::canon(ks, fm), &o[w]);
-                } else {
-                    u64 ks = mul_shoup(submod(AR::acc_canon(fin, m), AR::canon_fwd(v[k], m), pc.q), pinv.w, pinv.wp, pc.q);
-                    if (OWN == OWN_ROT && t == 0) ks = addmod(ks, bp[eval_perm(row_off_f + w, gal_fin, tb.logN)], pc.q);
-                    o[w] = ks;
-                }
-            }
-        }
-    } else if (i < a.split) {
-        u64* o0 = a.cq + (((size_t)inst * 2 + 0) * a.split + i) * N + row_off;
-        u64* o1 = a.cq + (((size_t)inst * 2 + 1) * a.split + i) * N + row_off;
-#pragma unroll
-        for (int k = 0; k < 8; k++) {
-            __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc0[k], m), m), &o0[k * 32 + e]);
-            __builtin_nontemporal_store(AR::acc_canon(AR::acc_finish(acc1[k], m), m), &o1[k * 32 + e]);
-        }
-    } else {
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-            T x[8];
-#pragma unroll
-            for (int k = 0; k < 8; k++) x[k] = AR::acc_finish(t ? acc1[k] : acc0[k], m);
-            row8_exchange<AR, R8_R0, R8_R2, false>(x, lrow, e, m);
-            R8::inv_contig(x, lrow, e, r, ti, tf, N, m);
-            u64* o = a.cp + (((size_t)inst * 2 + t) * (D - a.split) + (i - a.split)) * N + row_off;
-#pragma unroll
-            for (int k = 0; k < 8; k++) o[k * 32 + e] = AR::to_raw(AR::round_reduce(x[k], m));
-        }
-    }
-}
-
-#ifndef CKKS_INNER8_WAVES_FP
-#define CKKS_INNER8_WAVES_FP 4
-#endif
-#ifndef CKKS_INNER8_WAVES_INT
-#define CKKS_INNER8_WAVES_INT 3
-#endif
-template <class AR, int A, int OWN, bool FUSED>
-__global__ __launch_bounds__(256, AR::is_fp ? CKKS_INNER8_WAVES_FP : CKKS_INNER8_WAVES_INT) void ks_inner8_kernel(InnerArgs a, Tables tb, LimbRun run) {
-    __shared__ u64 lds[NTT8_LDS_WORDS];
-    constexpr u32 TILES = (1u << A) / 8;
-    u32 group, inst;
-    if (!xcd_decode(blockIdx.x, a.n_inst, run.count * TILES, group, inst)) return;
-    ks_inner8_body<AR, A, OWN, FUSED>(a, tb, lds, run.first + group / TILES, group % TILES, inst);
 }
 
 // ===================================================== double-hoisted rotate-multiply-accumulate

@@ -170,105 +170,6 @@ struct NttCore {
     }
 };
 
-// ---------------------------------------------------------------------------------------------
-// Contiguous pass with 32 lanes per 256-word row and 8 words per lane: half the registers per lane of the
-// 16-word form above, for kernels that keep accumulators across several transforms (the key inner product)
-// and are limited by the waves their registers allow.  A wavefront owns two rows; a 256-thread workgroup a
-// tile of 8 rows.  The 8 stages run as 3 + 3 + 2 in-lane stages with two exchanges through the row's LDS
-// slice (wave-local, row_sync).  Register layouts of the 8 words x[k] of lane e (word index w in the row):
-//   R0: w = k*32 + e                              coalesced global access; in-lane bits 7,6,5
-//   RF: w = (e/4)*32 + k*4 + e%4                  forward middle round;    in-lane bits 4,3,2
-//   R2: w = e*8 + k                               in-lane bits 2,1,0
-//   RI: w = (e/8)*64 + k*8 + e%8                  inverse middle round;    in-lane bits 5,4,3
-// forward: R0 (stages 0-2) -> RF (stages 3-5) -> R2 (stages 6,7); inverse: R2 (0-2) -> RI (3-5) -> R0 (6,7).
-// Twiddles: forward stage u of the pass uses W[2^(A+u) + r*2^u + (w >> (8-u))], inverse stage v uses
-// Winv[(N >> (v+1)) + ((r*256 + w) >> (v+1))], w = row index of the pair's first word (as in NttCore).
-#define NTT8_ROW_WORDS 288  // 256 words + one pad word per 8
-#define NTT8_LDS_WORDS (8 * NTT8_ROW_WORDS)
-__device__ __forceinline__ u32 pad8(u32 w) { return w + (w >> 3); }
-__device__ __forceinline__ u32 w_r0(u32 e, u32 k) { return k * 32 + e; }
-__device__ __forceinline__ u32 w_rf(u32 e, u32 k) { return ((e >> 2) << 5) | (k << 2) | (e & 3); }
-__device__ __forceinline__ u32 w_r2(u32 e, u32 k) { return e * 8 + k; }
-__device__ __forceinline__ u32 w_ri(u32 e, u32 k) { return ((e >> 3) << 6) | (k << 3) | (e & 7); }
-
-enum Row8Layout { R8_R0 = 0, R8_RF = 1, R8_R2 = 2, R8_RI = 3 };
-template <int LAY>
-__device__ __forceinline__ u32 w_of(u32 e, u32 k) {
-    return LAY == R8_R0 ? w_r0(e, k) : LAY == R8_RF ? w_rf(e, k) : LAY == R8_R2 ? w_r2(e, k) : w_ri(e, k);
-}
-
-// x from layout FROM to layout TO through the row's LDS slice; REDUCE applies the arithmetic's range
-// reduction to what is written (the rounds of the transforms rely on it)
-template <class AR, int FROM, int TO, bool REDUCE>
-__device__ __forceinline__ void row8_exchange(typename AR::T (&x)[8], u64* l, u32 e, const typename AR::Mod& m) {
-    row_sync();
-#pragma unroll
-    for (int k = 0; k < 8; k++) l[pad8(w_of<FROM>(e, k))] = AR::to_raw(REDUCE ? AR::round_reduce(x[k], m) : x[k]);
-    row_sync();
-#pragma unroll
-    for (int k = 0; k < 8; k++) x[k] = AR::from_raw(l[pad8(w_of<TO>(e, k))]);
-}
-
-template <class AR, int A>
-struct NttRow8 {
-    typedef typename AR::T T;
-    typedef typename AR::Mod Mod;
-
-    // three (or NS) in-lane forward stages starting at pass stage U0 on layout LAY
-    template <int LAY, int U0, int NS>
-    static __device__ __forceinline__ void fwd_round(T (&x)[8], u32 e, u32 r, const u64* ti, const double* tf, u32 N,
-                                                     const Mod& m) {
-#pragma unroll
-        for (int s = 0; s < NS; s++) {
-            const int u = U0 + s;
-            const int d = (NS == 3 ? 4 : 2) >> s;  // in-lane distance of the pair
-#pragma unroll
-            for (int k = 0; k < 8; k++) {
-                if (k & d) continue;
-                const u32 w = w_of<LAY>(e, k);
-                const typename AR::Tw t = AR::tw(ti, tf, (1u << (A + u)) + (r << u) + (w >> (8 - u)), N, false);
-                // values below 8q enter the pass: even stages take 4q off first, odd stages run on inputs below 6q
-                if (u & 1) AR::template bfly_fwd<false>(x[k], x[k + d], t, m);
-                else AR::template bfly_fwd<true>(x[k], x[k + d], t, m);
-            }
-        }
-    }
-    // x in layout R0 (row r of the limb, values as the strided pass leaves them) -> 8 stages -> layout R2
-    static __device__ __forceinline__ void fwd_contig(T (&x)[8], u64* l, u32 e, u32 r, const u64* ti, const double* tf,
-                                                      u32 N, const Mod& m) {
-        fwd_round<R8_R0, 0, 3>(x, e, r, ti, tf, N, m);
-        row8_exchange<AR, R8_R0, R8_RF, true>(x, l, e, m);
-        fwd_round<R8_RF, 3, 3>(x, e, r, ti, tf, N, m);
-        row8_exchange<AR, R8_RF, R8_R2, true>(x, l, e, m);
-        fwd_round<R8_R2, 6, 2>(x, e, r, ti, tf, N, m);
-    }
-
-    template <int LAY, int V0, int NS, int D0>
-    static __device__ __forceinline__ void inv_round(T (&x)[8], u32 e, u32 r, const u64* ti, const double* tf, u32 N,
-                                                     const Mod& m) {
-#pragma unroll
-        for (int s = 0; s < NS; s++) {
-            const int v = V0 + s;
-            const int d = D0 << s;  // in-lane distance of the pair
-#pragma unroll
-            for (int k = 0; k < 8; k++) {
-                if (k & d) continue;
-                const u32 w = w_of<LAY>(e, k);
-                AR::bfly_inv(x[k], x[k + d], AR::tw(ti, tf, (N >> (v + 1)) + ((r * 256 + w) >> (v + 1)), N, true), m);
-            }
-        }
-    }
-    // x in layout R2 (inverse-lazy range) -> 8 stages -> layout R0
-    static __device__ __forceinline__ void inv_contig(T (&x)[8], u64* l, u32 e, u32 r, const u64* ti, const double* tf,
-                                                      u32 N, const Mod& m) {
-        inv_round<R8_R2, 0, 3, 1>(x, e, r, ti, tf, N, m);
-        row8_exchange<AR, R8_R2, R8_RI, true>(x, l, e, m);
-        inv_round<R8_RI, 3, 3, 1>(x, e, r, ti, tf, N, m);
-        row8_exchange<AR, R8_RI, R8_R0, true>(x, l, e, m);
-        inv_round<R8_R0, 6, 2, 2>(x, e, r, ti, tf, N, m);  // bits 6 and 7 of w are bits 1 and 2 of k
-    }
-};
-
 // XCD-aware decode of a linear workgroup id.  Workgroups are handed to the 8 XCDs round-robin,
 // so ids congruent modulo 8 share an L2.  Work is organised as `groups` groups of `S` instances
 // that read the same tables / sources; all instances of a group get ids on one XCD, adjacent
