@@ -1214,19 +1214,22 @@ struct Workspace {
     u64 *x, *dt, *cq, *cp, *cv;
 };
 
-static size_t ks_workspace_words(const View* c, u32 xg, u32 dg, u32 cg) {
+// with_cq = false: the plain key-switch pipeline, whose c' on the q-limbs never leaves the registers of the kernel
+// that accumulates it: no cq (a fifth of the workspace at (24,6,4))
+static size_t ks_workspace_words(const View* c, u32 xg, u32 dg, u32 cg, bool with_cq = true) {
     const size_t N = (size_t)1 << c->logN;
-    return ((size_t)xg * c->L + (size_t)dg * c->dnum * c->D + (size_t)cg * 2 * (2 * (size_t)c->L + c->K)) * N;
+    return ((size_t)xg * c->L + (size_t)dg * c->dnum * c->D + (size_t)cg * 2 * ((with_cq ? 2 : 1) * (size_t)c->L + c->K)) * N;
 }
 
-static Workspace carve(const View* c, void* ws, u32 xg, u32 dg, u32 cg) {
+static Workspace carve(const View* c, void* ws, u32 xg, u32 dg, u32 cg, bool with_cq = true) {
     const size_t N = (size_t)1 << c->logN;
     Workspace w;
     w.x = (u64*)ws;
     w.dt = w.x + (size_t)xg * c->L * N;
     w.cq = w.dt + (size_t)dg * c->dnum * c->D * N;
-    w.cp = w.cq + (size_t)cg * 2 * c->L * N;
+    w.cp = w.cq + (with_cq ? (size_t)cg * 2 * c->L * N : 0);
     w.cv = w.cp + (size_t)cg * 2 * c->K * N;
+    if (!with_cq) w.cq = nullptr;
     return w;
 }
 
@@ -1241,7 +1244,7 @@ static int view_workspace_bytes(const View* v, int op, uint32_t batch_or_nrot, s
         case CKKS_OP_HMULT_RELIN:
         case CKKS_OP_HROT:
             if (v->K == 0) return fail(v, CKKS_EUNSUPPORTED, "context has no special primes");
-            *bytes = ks_workspace_words(v, batch_or_nrot, batch_or_nrot, batch_or_nrot) * sizeof(u64);
+            *bytes = ks_workspace_words(v, batch_or_nrot, batch_or_nrot, batch_or_nrot, false) * sizeof(u64);
             return CKKS_OK;
         case CKKS_OP_HROT_HOISTED_MAC: {
             if (v->K == 0) return fail(v, CKKS_EUNSUPPORTED, "context has no special primes");
@@ -1512,12 +1515,9 @@ template <int LOAD, int OWN>
 static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, const u64* in2, const u64* key, u64* out,
                                u32 batch, u32 galois, void* ws, hipStream_t s, const u32* multi_galois = nullptr,
                                const u64* const* multi_keys = nullptr) {
-    Workspace w = carve(c, ws, batch, batch, batch);
-    if (cm != c) {  // cq and cv shrink by one limb per component, cp grows by one: still inside the level's workspace
-        const size_t N = (size_t)1 << c->logN;
-        w.cp = w.cq + (size_t)batch * 2 * cm->L * N;
-        w.cv = w.cp + (size_t)batch * 2 * cm->K * N;
-    }
+    Workspace w = carve(c, ws, batch, batch, batch, false);
+    if (cm != c)  // cv shrinks by one limb per component, cp grows by one: still inside the level's workspace
+        w.cv = w.cp + ((size_t)batch * 2 * cm->K << c->logN);
     const LimbSel sel = {c->L, batch, c->L, 0, 0, 0};
     InvContigArgs a1;
     memset(&a1, 0, sizeof(a1));
@@ -1857,7 +1857,7 @@ static size_t bsgs_workspace_words(const View* c, u32 n1, u32 n2) {
                          + (size_t)n1 * 2 * c->D                                     // baby rotations, extended basis
                          + (size_t)n2 * 2 * (2 * (size_t)c->L + c->K)                // C on q / special limbs, converted part
                          + (size_t)n2 * 2 * c->L * 2;                                // inner sums, rotated inner sums
-    return limbs * N + ks_workspace_words(c, nc, nc, nc);
+    return limbs * N + ks_workspace_words(c, nc, nc, nc, false);  // the giant rotations run the plain pipeline
 }
 
 extern "C" int ckks_lintrans_bsgs_workspace_bytes(const ckks_ctx* ctx, uint32_t level, uint32_t n1, uint32_t n2,

@@ -816,6 +816,37 @@ struct InnerArgs {
     const PinvConst* fin_pinv;  // [split] inverse of the product of the ModDown's source primes
 };
 
+// Twiddles of one row's second forward pass, kept in LDS for kernels that run that pass several times on the same
+// row of the same limb (the inner product: once per digit and twice more when it ends the ModDown).  FP64 limbs
+// only: 255 doubles per row.  Words [0, 15): stages 0-3, whose 2^u twiddles are the same for the row's 16 lanes
+// (stage u from offset 2^u - 1); then 15 words per lane: stages 4-7, 2^(u-4) twiddles each.  The lane blocks are
+// 15 words apart, so the 16 lanes of a row read 16 different bank pairs.  Loaded from the tables once per
+// workgroup: the 30 global loads per lane and pass were 14 % of the fused kernel's time.
+#define CKKS_ROW_TW_WORDS 256
+template <int A>
+__device__ __forceinline__ void fill_row_tw(u64* blk, u32 e0, u32 r, const double* tf) {
+    if (e0 < 15) {
+        const u32 u = 31 - __clz(e0 + 1), off = e0 + 1 - (1u << u);
+        blk[e0] = __builtin_bit_cast(u64, tf[(1u << (A + u)) + (r << u) + off]);
+    }
+#pragma unroll
+    for (int u = 4; u < 8; u++) {
+#pragma unroll
+        for (int t = 0; t < (1 << (u - 4)); t++)
+            blk[15 + e0 * 15 + (1 << (u - 4)) - 1 + t] = __builtin_bit_cast(u64, tf[(1u << (A + u)) + (r << u) + (e0 << (u - 4)) + t]);
+    }
+    row_sync();
+}
+struct RowTwLds {
+    const u64* blk;
+    u32 e0;
+    __device__ __forceinline__ FpAr::Tw get(int u, u32 w) const {
+        const u32 t = w >> (8 - u);
+        const u32 at = u < 4 ? (1u << u) - 1 + t : 15 + e0 * 15 + (1u << (u - 4)) - 1 + (t - (e0 << (u - 4)));
+        return FpAr::Tw{__builtin_bit_cast(double, blk[at])};
+    }
+};
+
 template <class AR, int A, int OWN, bool HOISTED, bool FUSED>
 __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& tb, u64* lds, u32 i, u32 tile,
                                               u32 inst) {
@@ -833,6 +864,9 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
     const u64* key = a.key[kidx] + (size_t)pi * N + row_off;
     const u32 gal = a.galois[kidx];
     const u32 own_digit = i < L ? i / tb.alpha : 0xffffffffu;
+    constexpr bool TWL = AR::is_fp && !HOISTED;  // the row's forward twiddles live in LDS
+    u64* twblk = lds + NTT_LDS_WORDS + ch * CKKS_ROW_TW_WORDS;
+    if constexpr (TWL) fill_row_tw<A>(twblk, e0, r, tf);
     T acc0[16], acc1[16];  // layout CP
 #pragma unroll
     for (int k = 0; k < 16; k++) acc0[k] = AR::acc_zero(), acc1[k] = AR::acc_zero();
@@ -895,7 +929,8 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             const u64* p = a.dt + (((size_t)inst * tb.dnum + j) * D + i) * N + row_off;
 #pragma unroll
             for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0]));
-            NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
+            if constexpr (TWL) NttCore<AR, A>::fwd_contig_with(v, lrow, e0, RowTwLds{twblk, e0}, m);
+            else NttCore<AR, A>::fwd_contig(v, lrow, e0, r, ti, tf, N, m);
 #pragma unroll
             for (int k = 0; k < 16; k++) v[k] = AR::round_reduce(v[k], m);
             exchange_cb_to_cp<AR>(v, lrow, e0);
@@ -929,7 +964,8 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
             const u64* p = a.cv + (((size_t)inst * 2 + t) * a.split + i) * N + row_off_f;
 #pragma unroll
             for (int k = 0; k < 16; k++) v[k] = AR::from_raw(__builtin_nontemporal_load(&p[k * 16 + e0f]));
-            NttCore<AR, A>::fwd_contig(v, lrow_f, e0f, rf, ti, tf, N, m);
+            if constexpr (TWL) NttCore<AR, A>::fwd_contig_with(v, lrow_f, e0f, RowTwLds{lds + NTT_LDS_WORDS + chf * CKKS_ROW_TW_WORDS, e0f}, m);
+            else NttCore<AR, A>::fwd_contig(v, lrow_f, e0f, rf, ti, tf, N, m);
             exchange_cb_to_cp<AR>(v, lrow_f, e0f);
             u64 res[16];
 #pragma unroll
@@ -978,7 +1014,7 @@ __device__ __forceinline__ void ks_inner_body(const InnerArgs& a, const Tables& 
 
 template <class AR, int A, int OWN, bool HOISTED, bool FUSED>
 __global__ __launch_bounds__(256, 2) void ks_inner_kernel(InnerArgs a, Tables tb, LimbRun run) {
-    __shared__ u64 lds[NTT_LDS_WORDS];
+    __shared__ u64 lds[NTT_LDS_WORDS + (AR::is_fp && !HOISTED ? 16 * CKKS_ROW_TW_WORDS : 0)];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;
     if (!xcd_decode(blockIdx.x, a.n_inst, run.count * TILES, group, inst)) return;

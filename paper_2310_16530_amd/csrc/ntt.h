@@ -74,9 +74,10 @@ struct NttCore {
         }
     }
 
-    // ---- forward contiguous pass: x in layout CA (row r of the limb) -> 8 stages -> layout CB
-    static __device__ __forceinline__ void fwd_contig(T (&x)[16], u64* l, u32 e0, u32 r, const u64* ti,
-                                                      const double* tf, u32 N, const Mod& m) {
+    // ---- forward contiguous pass: x in layout CA (row r of the limb) -> 8 stages -> layout CB.
+    // TW supplies the twiddle of stage u for the pair whose first word has index w in the row: get(u, w).
+    template <class TW>
+    static __device__ __forceinline__ void fwd_contig_with(T (&x)[16], u64* l, u32 e0, const TW& tw, const Mod& m) {
 #pragma unroll
         for (int u = 0; u < 4; u++) {
             const int d = 8 >> u;
@@ -84,8 +85,8 @@ struct NttCore {
             for (int k = 0; k < 16; k++) {
                 if (k & d) continue;
                 // the strided pass leaves values below 8q: even stages reduce, odd stages run on inputs below 6q
-                if (u & 1) AR::template bfly_fwd<false>(x[k], x[k + d], AR::tw(ti, tf, (1u << (A + u)) + (r << u) + (k >> (4 - u)), N, false), m);
-                else AR::template bfly_fwd<true>(x[k], x[k + d], AR::tw(ti, tf, (1u << (A + u)) + (r << u) + (k >> (4 - u)), N, false), m);
+                if (u & 1) AR::template bfly_fwd<false>(x[k], x[k + d], tw.get(u, (u32)k * 16 + e0), m);
+                else AR::template bfly_fwd<true>(x[k], x[k + d], tw.get(u, (u32)k * 16 + e0), m);
             }
         }
 #pragma unroll
@@ -99,12 +100,23 @@ struct NttCore {
 #pragma unroll
             for (int k = 0; k < 16; k++) {
                 if (k & d) continue;
-                if (u & 1) AR::template bfly_fwd<false>(x[k], x[k + d],
-                             AR::tw(ti, tf, (1u << (A + u)) + (r << u) + ((e0 * 16 + k) >> (8 - u)), N, false), m);
-                else AR::template bfly_fwd<true>(x[k], x[k + d],
-                             AR::tw(ti, tf, (1u << (A + u)) + (r << u) + ((e0 * 16 + k) >> (8 - u)), N, false), m);
+                if (u & 1) AR::template bfly_fwd<false>(x[k], x[k + d], tw.get(u, e0 * 16 + (u32)k), m);
+                else AR::template bfly_fwd<true>(x[k], x[k + d], tw.get(u, e0 * 16 + (u32)k), m);
             }
         }
+    }
+    // twiddles from the tables in global memory: stage u of the pass uses W[2^(A+u) + r*2^u + (w >> (8-u))]
+    struct GlobalTw {
+        const u64* ti;
+        const double* tf;
+        u32 r, N;
+        __device__ __forceinline__ typename AR::Tw get(int u, u32 w) const {
+            return AR::tw(ti, tf, (1u << (A + u)) + (r << u) + (w >> (8 - u)), N, false);
+        }
+    };
+    static __device__ __forceinline__ void fwd_contig(T (&x)[16], u64* l, u32 e0, u32 r, const u64* ti,
+                                                      const double* tf, u32 N, const Mod& m) {
+        fwd_contig_with(x, l, e0, GlobalTw{ti, tf, r, N}, m);
     }
 
     // ---- inverse contiguous pass: x in layout CB (inverse-lazy range) -> 8 stages -> layout CA
