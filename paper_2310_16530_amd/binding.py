@@ -174,8 +174,11 @@ class Context:
     def __del__(self):
         h = getattr(self, "handle", None)
         if h:
-            load().ckks_ctx_destroy(h)
             self.handle = None
+            try:
+                load().ckks_ctx_destroy(h)
+            except Exception:  # interpreter shutdown: module globals may already be gone
+                pass
 
     # -- helpers ---------------------------------------------------------------------
     def _check(self, rc: int):

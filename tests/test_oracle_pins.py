@@ -967,3 +967,21 @@ def test_bsgs_with_encoded_diagonals_is_the_matrix_vector_product(orc):
         assert err <= tol < 0.01, (ell, err, tol)
         assert err > 0
         del basis
+
+def test_eval_automorphism_maps_256_slot_rows_onto_rows(orc):
+    """In evaluation (bit-reversed) order sigma_g sends every aligned block of 256 slots to one aligned source
+    block: the block index is the bit-reversed low part of the exponent index, and multiplying the odd exponent by
+    an odd g keeps low parts among themselves.  The kernels rely on it when they fetch a rotation's source row
+    whole and permute it on chip; here it is read off the oracle's own permutation (independent code), for
+    rotations, their inverses and the conjugation, at every ring degree the library accepts."""
+    for logn in (12, 13, 16):
+        n = 1 << logn
+        ident = np.arange(n, dtype=np.uint64)
+        gs = [synth.galois_element(r, logn) for r in (1, 2, 3, 7, 64, 1000, -1, -5)] + [2 * n - 1, 3, 2 * n - 3]
+        for g in gs:
+            assert g % 2 == 1
+            src = orc.automorph_eval(ident, logn, g)          # out[j] = in[src[j]]
+            assert sorted(src.tolist()) == list(range(n))     # a permutation
+            rows = (src >> np.uint64(8)).reshape(n // 256, 256)
+            assert (rows == rows[:, :1]).all(), (logn, g)     # one source row per destination row
+            assert sorted(rows[:, 0].tolist()) == list(range(n // 256))
