@@ -263,9 +263,12 @@ __device__ __forceinline__ void inv_strided_body(const InvStridedArgs& a, const 
     }
 }
 
+#ifndef CKKS_INV_STRIDED_WAVES
+#define CKKS_INV_STRIDED_WAVES 6
+#endif
 template <class AR, int A>
-__global__ __launch_bounds__(256) void inv_strided_kernel(InvStridedArgs a, Tables tb, LimbRun run) {
-    __shared__ u64 lds[4096];
+__global__ __launch_bounds__(256, (A == 8 && INV_STRIDED_HALF_EXCHANGE) ? CKKS_INV_STRIDED_WAVES : 4) void inv_strided_kernel(InvStridedArgs a, Tables tb, LimbRun run) {
+    __shared__ u64 lds[(A == 8 && INV_STRIDED_HALF_EXCHANGE) ? 2048 : 4096];
     constexpr u32 TILES = (1u << A) / 16;
     u32 group, inst;
     if (!xcd_decode(blockIdx.x, a.sel.n_inst, run.count * TILES, group, inst)) return;

@@ -23,6 +23,9 @@
 #include "modarith.h"
 
 #define NTT_LDS_WORDS (16 * 272)  // 16 rows of 256 words + one pad word per 16
+#ifndef INV_STRIDED_HALF_EXCHANGE
+#define INV_STRIDED_HALF_EXCHANGE 1
+#endif
 __device__ __forceinline__ u32 pad16(u32 e) { return e + (e >> 4); }
 
 // In the contiguous pass the 16 lanes that own a row are part of one wavefront and no other
@@ -164,11 +167,36 @@ struct NttCore {
                     AR::bfly_inv(x[k], x[k + d], AR::tw(ti, tf, (N >> (9 + w)) + ((r1 * 16 + k) >> (w + 1)), N, true), m);
                 }
             }
+            if constexpr (A == 8 && INV_STRIDED_HALF_EXCHANGE) {
+                // N = 2^16: the exchange is a 16 x 16 transpose between the 16 lanes of a column (lane r1 register k <->
+                // lane k register r1), done in two halves of eight registers through a buffer of half the size: the
+                // lanes with r1 < 8 find all their words in the first half, the others in the second.  16 KiB of LDS
+                // per workgroup instead of 32 lets the registers, not the LDS, set the number of resident workgroups.
+                T y[16];
 #pragma unroll
-            for (int k = 0; k < 16; k++) lds[(r1 * 16 + k) * TC + c] = AR::to_raw(AR::round_reduce(x[k], m));
-            __syncthreads();
+                for (int k = 0; k < 8; k++) lds[(r1 * 8 + k) * 16 + c] = AR::to_raw(AR::round_reduce(x[k], m));
+                __syncthreads();
+                if (r1 < 8) {
 #pragma unroll
-            for (int k = 0; k < 16; k++) x[k] = AR::from_raw(lds[k * 256 + tid]);
+                    for (int k = 0; k < 16; k++) y[k] = AR::from_raw(lds[(k * 8 + r1) * 16 + c]);
+                }
+                __syncthreads();
+#pragma unroll
+                for (int k = 0; k < 8; k++) lds[(r1 * 8 + k) * 16 + c] = AR::to_raw(AR::round_reduce(x[k + 8], m));
+                __syncthreads();
+                if (r1 >= 8) {
+#pragma unroll
+                    for (int k = 0; k < 16; k++) y[k] = AR::from_raw(lds[(k * 8 + r1 - 8) * 16 + c]);
+                }
+#pragma unroll
+                for (int k = 0; k < 16; k++) x[k] = y[k];
+            } else {
+#pragma unroll
+                for (int k = 0; k < 16; k++) lds[(r1 * 16 + k) * TC + c] = AR::to_raw(AR::round_reduce(x[k], m));
+                __syncthreads();
+#pragma unroll
+                for (int k = 0; k < 16; k++) x[k] = AR::from_raw(lds[k * 256 + tid]);
+            }
         }
 #pragma unroll
         for (int w = A - 4; w < A - 1; w++) {
