@@ -245,6 +245,28 @@ def test_keyswitch_hmult_hrot_parity_reduced(orc, shape):
             assert np.array_equal(hr[b], orc.hrot(ct1[b], g, rk, P)), (rot, b)
 
 
+@pytest.mark.parametrize("shape", [(13, 4, 2, 2), (16, 3, 1, 3)])
+def test_hrot_other_galois_elements(orc, shape):
+    """Rotations gather their source rows whole and permute them on chip; the row-to-row property that rests on holds for
+    every odd Galois element, so the conjugation, 3 (neither a power of 5 times a sign we use elsewhere) and far
+    rotations are compared with the oracle too, singly and inside a hoisted rotate-MAC."""
+    ps = synth.small_params(*shape)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    rng = np.random.default_rng(4242 + sum(shape))
+    ct = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2, 2))
+    gs = [2 * ps.N - 1, 3, 2 * ps.N - 3, synth.galois_element(ps.N // 2 - 1, ps.logN), synth.galois_element(1000, ps.logN)]
+    rks = [synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)) for _ in gs]
+    d_ct = dev(ct)
+    for g, rk in zip(gs, rks):
+        say("hrot with Galois element", g)
+        got = host(ctx.hrot(d_ct, g, dev(rk)))
+        for b in range(2):
+            assert np.array_equal(got[b], orc.hrot(ct[b], g, rk, P)), (g, b)
+    pt = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(len(gs),))
+    got = host(ctx.hrot_hoisted_mac(dev(ct[0]), gs, [dev(r) for r in rks], dev(pt)))
+    assert np.array_equal(got, orc.hrot_hoisted_mac(ct[0], gs, rks, pt, P))
+
+
 @pytest.mark.parametrize("shape,n_rot", [((12, 4, 2, 2), 3), ((13, 6, 3, 2), 11), ((12, 3, 1, 3), 8), ((12, 6, 6, 1), 9),
                                          ((12, 7, 3, 3), 5)])
 def test_hoisted_mac_parity_reduced(orc, shape, n_rot):
