@@ -8,10 +8,13 @@ switches per second with every operand resident in HBM.  Extras report the other
 metric names: NTT limbs/s on config 1 (16 x 24 limbs) and hoisted rotations/s on config 3.
 
 The line also carries
-  roofline     : the kernel with the largest share of the timed region: its algorithmic bytes per
-                 launch over its mean launch duration (HIP events recorded by the library on the
-                 launch stream, in a further pass of the same K steps) against 8 TB/s, with the
-                 binding resource decided by the counters of the committed profile;
+  roofline     : the kernel with the largest share of the timed region (instantiations of one
+                 kernel template that differ only in an operand mode count as that kernel and
+                 are listed as `members`): its algorithmic bytes per launch over its mean launch
+                 duration (HIP events recorded by the library on the launch stream, in a further
+                 pass of the same K steps) against 8 TB/s, with the binding resource decided by
+                 the counters of the committed profile; `largest_instantiation` gives the same
+                 for the single instantiation with the largest share when that is another kernel;
   step_roofline: compulsory bytes and HBM-side counter bytes of the whole step over ms_per_step
                  against 8 TB/s (the figure the 60 % target speaks of);
   cpu_baseline : the CPU oracle, as it stands, on a bounded sample of the same workload.
@@ -19,6 +22,7 @@ The line also carries
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -180,30 +184,59 @@ def main():
     # algorithmic bytes per launch (limbs the launch must read plus write once, tables excluded) over the mean launch
     # duration from HIP events, against 8 TB/s.  Which resource binds the kernel is decided by the counters of the
     # committed profile, evaluated at this run's duration: VALU issue fraction against HBM-traffic fraction.
-    dom = max(prof.items(), key=lambda kv: kv[1][1])
-    dname, (dn, dms, dbytes) = dom
-    dur_s = dms / dn * 1e-3
-    hbm_gbs = dbytes / dms / 1e6
-    meas = MEASURED.get(dname) if B == synth.CFG2_BATCH else None
-    traffic = int((meas[0] + meas[1]) * _MIB) if meas else None
-    roofline = {"kernel": dname, "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "traffic_source": TRAFFIC_SOURCE if meas else None,
-                "alg_bytes_per_launch": dbytes // dn, "avg_launch_us": round(1e6 * dur_s, 2),
-                "share_of_step": round(dms / total_ms, 3)}
-    if meas:
-        traffic_frac = traffic / dur_s / 1e9 / HBM_PEAK_GBS
-        issue_frac = meas[2] * 64 / dur_s / 1e12 / VALU_PEAK_TINSTR
-        roofline["hbm_counter_traffic"] = {"GBps": round(traffic / dur_s / 1e9, 1), "frac": round(traffic_frac, 4)}
-        roofline["valu_issue"] = {"wave_instructions_per_launch": meas[2], "frac": round(issue_frac, 4),
-                                  "peak": "256 CU x 4 SIMD x one wave64 instruction per 4 cycles x 2.4 GHz"}
-        roofline["bound"] = "alu" if issue_frac > traffic_frac else "hbm"
-        roofline["bound_decided_by"] = "valu_issue.frac vs hbm_counter_traffic.frac of the same kernel"
-    if dname in alg_lane_ops:  # secondary: the method's own FP64 operation count against the VALU issue peak
-        alg_t = alg_lane_ops[dname] / dur_s / 1e12
-        roofline["alu_algorithmic"] = {"lane_ops_per_launch": alg_lane_ops[dname], "achieved_T_per_s": round(alg_t, 2),
-                                       "peak_T_per_s": round(VALU_PEAK_TINSTR, 2), "frac": round(alg_t / VALU_PEAK_TINSTR, 4),
-                                       "note": "shortest exact FP64 sequences counted by hand; not a hardware counter"}
+    # A kernel is one __global__ template; instantiations that differ only in how an operand is formed (the own-digit
+    # mode of the inner product, the gather mode of the first inverse pass) are launches of the same kernel, listed
+    # under `members` with their own durations.  `largest_instantiation` carries the same figures for the single
+    # instantiation with the largest share, when that is a different kernel.
+    def family(name):
+        m = re.match(r"^(ks_inner_kernel<\w+, \d+, )\d+(, \w+, \w+>)$", name) or \
+            re.match(r"^(inv_contig_kernel<\w+, \d+, )\d+(>)$", name)
+        return m.group(1) + "*" + m.group(2) if m else name
+
+    def roofline_of(label, names):
+        dn = sum(prof[k][0] for k in names)
+        dms = sum(prof[k][1] for k in names)
+        dbytes = sum(prof[k][2] for k in names)
+        dur_s = dms / dn * 1e-3
+        hbm_gbs = dbytes / dms / 1e6
+        have = B == synth.CFG2_BATCH and all(k in MEASURED for k in names)
+        # counters: mean per launch over the launches of this run
+        traffic = int(sum((MEASURED[k][0] + MEASURED[k][1]) * _MIB * prof[k][0] for k in names) / dn) if have else None
+        r = {"kernel": label, "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+             "frac": round(hbm_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+             "traffic_source": TRAFFIC_SOURCE if have else None,
+             "alg_bytes_per_launch": dbytes // dn, "avg_launch_us": round(1e6 * dur_s, 2),
+             "share_of_step": round(dms / total_ms, 3)}
+        if len(names) > 1:
+            r["members"] = {k: {"launches_per_step": prof[k][0] / args.steps,
+                                "alg_bytes_per_launch": prof[k][2] // prof[k][0],
+                                "avg_launch_us": round(1e3 * prof[k][1] / prof[k][0], 2),
+                                "frac": round(prof[k][2] / prof[k][1] / 1e6 / HBM_PEAK_GBS, 4)} for k in names}
+        if have:
+            valu = sum(MEASURED[k][2] * prof[k][0] for k in names) / dn
+            traffic_frac = traffic / dur_s / 1e9 / HBM_PEAK_GBS
+            issue_frac = valu * 64 / dur_s / 1e12 / VALU_PEAK_TINSTR
+            r["hbm_counter_traffic"] = {"GBps": round(traffic / dur_s / 1e9, 1), "frac": round(traffic_frac, 4)}
+            r["valu_issue"] = {"wave_instructions_per_launch": int(valu), "frac": round(issue_frac, 4),
+                               "peak": "256 CU x 4 SIMD x one wave64 instruction per 4 cycles x 2.4 GHz"}
+            r["bound"] = "alu" if issue_frac > traffic_frac else "hbm"
+            r["bound_decided_by"] = "valu_issue.frac vs hbm_counter_traffic.frac of the same kernel"
+        if len(names) == 1 and names[0] in alg_lane_ops:  # secondary: the method's own FP64 operation count
+            alg_t = alg_lane_ops[names[0]] / dur_s / 1e12
+            r["alu_algorithmic"] = {"lane_ops_per_launch": alg_lane_ops[names[0]], "achieved_T_per_s": round(alg_t, 2),
+                                    "peak_T_per_s": round(VALU_PEAK_TINSTR, 2), "frac": round(alg_t / VALU_PEAK_TINSTR, 4),
+                                    "note": "shortest exact FP64 sequences counted by hand; not a hardware counter"}
+        return r
+
+    launched = [k for k, v in prof.items() if v[0]]
+    fams = {}
+    for k in launched:
+        fams.setdefault(family(k), []).append(k)
+    dfam = max(fams, key=lambda f: sum(prof[k][1] for k in fams[f]))
+    roofline = roofline_of(dfam, sorted(fams[dfam]))
+    dinst = max(launched, key=lambda k: prof[k][1])
+    if [dinst] != fams[dfam]:
+        roofline["largest_instantiation"] = roofline_of(dinst, [dinst])
 
     # ---- the whole step against the HBM roofline: compulsory bytes (operands, keys and results moved once: 6L limbs
     # per HMult, 4L per HRot, one key of 2*dnum*(L+K) limbs per batch) and the HBM-side counter bytes of every launch
