@@ -1485,6 +1485,12 @@ static void decompose_extend(const View* c, const Workspace& w, u32 groups, hipS
     launch_conv<CONV_UP>(c, a3, s);
 }
 
+static bool any_fp_prime(const View* c, u32 lo, u32 hi) {
+    for (u32 i = lo; i < hi; i++)
+        if (c->primes[i] < CKKS_FP_PRIME_LIMIT) return true;
+    return false;
+}
+
 // s waits for the FpAr conversion that decompose_extend put on the side stream
 static void join_fp_beside(const View* c, hipStream_t s) {
     SideStream& sd = c->sh->side;
@@ -1534,9 +1540,11 @@ static void keyswitch_pipeline(const View* c, const View* cm, const u64* in1, co
     decompose_extend(c, w, batch, s, true);
     ia.dt = w.dt, ia.own = in1, ia.own2 = in2;
     ia.cq = w.cq, ia.cp = w.cp, ia.n_inst = batch, ia.split = cm->L;
-    // the limbs that feed the ModDown conversion first; the q-limbs then finish in one kernel, c' in registers
+    // the limbs that feed the ModDown conversion first; the q-limbs then finish in one kernel, c' in registers.
+    // Those of them that are FpAr primes (special primes below the FP64 limit; limb cm->L of the merged rescale) take
+    // their digits from the FpAr conversion, which may still be running on the side stream.
+    if (any_fp_prime(c, cm->L, c->D)) join_fp_beside(c, s);
     if (cm != c) {
-        join_fp_beside(c, s);  // limb cm->L is a q-limb here: its digits come from the FpAr conversion
         launch_ks_inner<OWN, false, false>(c, ia, s, cm->L, c->D);
     } else {
         // special limbs belong to no digit, so every variant computes the same on them: the leanest one runs

@@ -208,3 +208,39 @@ def test_wide_digits_at_the_top_of_the_fp64_range(orc):
     ct = np.stack([d, d])
     assert np.array_equal(host(ctx.hmult_relin_rescale_at(L, dev(ct[None]), dev(ct[None]), dev(key)))[0],
                           orc.hmult_relin_rescale_level(ct, ct, key, P))
+
+
+@pytest.mark.parametrize("name,shape", [("fp64_special", (12, [44, 36, 55, 30, 55, 59, 30, 55], [49, 49, 49, 36], 4)),
+                                        ("mixed_special", (13, [50, 58, 44, 59], [59, 49, 36], 2))])
+def test_second_stream_with_fp64_special_limbs(orc, name, shape):
+    """With the library's second stream on, the FP64 ModUp conversion runs beside the inner product on the limbs that
+    feed the ModDown.  When some of those limbs are FP64 primes themselves (special primes below 3*2^48) the inner
+    product needs that conversion's output and has to wait for it: every key-switch entry point, several times in a
+    row, against the oracle."""
+    logN, qf, pf, dnum = shape
+    ps = synth.mixed_params(logN, qf, pf, dnum, name)
+    assert any(p < FP_LIMIT for p in ps.p_primes) and any(p >= FP_LIMIT for p in ps.q_primes)
+    from paper_2310_16530_amd import binding
+    ctx = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+    ctx.set_overlap(True)
+    P = orc.Params(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+    rng = np.random.default_rng(77 + logN)
+    N = ps.N
+    key = synth.uniform_residues(rng, ps.primes, N, lead=(ps.dnum, 2))
+    d_key = dev(key)
+    g = synth.galois_element(3, logN)
+    for ell in (ps.L, ps.L - 1):
+        q = ps.q_primes[:ell]
+        ct1 = synth.uniform_residues(rng, q, N, lead=(4, 2))
+        ct2 = synth.uniform_residues(rng, q, N, lead=(4, 2))
+        want = [np.stack([orc.keyswitch_level(ct1[b, 0], key, P) for b in range(4)]),
+                np.stack([orc.hmult_relin_level(ct1[b], ct2[b], key, P) for b in range(4)]),
+                np.stack([orc.hrot_level(ct1[b], g, key, P) for b in range(4)]),
+                np.stack([orc.hmult_relin_rescale_level(ct1[b], ct2[b], key, P) for b in range(4)])]
+        d1, d2, d0 = dev(ct1), dev(ct2), dev(ct1[:, 0])
+        for rep in range(3):
+            _say(name, "level", ell, "repetition", rep)
+            got = [host(ctx.keyswitch_at(ell, d0, d_key)), host(ctx.hmult_relin_at(ell, d1, d2, d_key)),
+                   host(ctx.hrot_at(ell, d1, g, d_key)), host(ctx.hmult_relin_rescale_at(ell, d1, d2, d_key))]
+            for what, a, b in zip(("keyswitch", "hmult", "hrot", "merged"), got, want):
+                assert np.array_equal(a, b), (what, ell, rep)
