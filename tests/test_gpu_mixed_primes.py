@@ -118,16 +118,17 @@ def _random_case(seed, max_L=10, max_K=8):
     return logN, qf, pf, dnum
 
 
-@pytest.mark.parametrize("seed", list(range(12)) + [100 + i for i in range(8)])
+@pytest.mark.parametrize("seed", list(range(40)) + [100 + i for i in range(8)])
 def test_random_chains_levels_and_operations(orc, seed):
     """Seeded random parameter sets (1..10 limbs of 30..60 bits in any order, 1..8 special limbs, any digit
     count; seeds from 100 on: up to 32 limbs and 16 special limbs, digits of up to 16 limbs), a random level,
-    every composed operation once."""
+    every composed operation once; odd seeds with the library's second stream on."""
     logN, qf, pf, dnum = _random_case(500 + seed) if seed < 100 else _random_case(500 + seed, 32, 16)
     ps = synth.mixed_params(logN, qf, pf, dnum, "random%d" % seed)
     _say("seed", seed, "logN", logN, "q bits", qf, "p bits", pf, "dnum", dnum)
     from paper_2310_16530_amd import binding
-    ctx = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)     # not cached: twelve different chains
+    ctx = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)     # not cached: every seed has its own chain
+    ctx.set_overlap(seed % 2 == 1)
     P = orc.Params(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
     rng = np.random.default_rng(900 + seed)
     N = ps.N
