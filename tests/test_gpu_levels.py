@@ -440,12 +440,15 @@ def test_bsgs_linear_transform_full_size(orc):
     assert np.array_equal(got, orc.lintrans_bsgs_level(ct, baby, baby_rks, giant, giant_rks, pt, P))
 
 
-def test_entry_points_can_be_captured_in_a_graph_and_replayed(orc):
+@pytest.mark.parametrize("overlap", [False, True])
+def test_entry_points_can_be_captured_in_a_graph_and_replayed(orc, overlap):
     """The library allocates nothing and issues only kernel launches, so a caller may capture its calls in a
-    HIP graph.  Every replay (with eager work and synchronisations in between) must reproduce the eager result."""
+    HIP graph.  Every replay (with eager work and synchronisations in between) must reproduce the eager result.
+    With the library's second stream on, its fork and join by events are captured with the rest."""
     import torch
+    from paper_2310_16530_amd import binding
     ps = synth.small_params(13, 6, 3, 2)
-    ctx = gpu_ctx(ps)
+    ctx = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
     rng = np.random.default_rng(31)
     ell = 5
     q = ps.q_primes[:ell]
@@ -466,6 +469,7 @@ def test_entry_points_can_be_captured_in_a_graph_and_replayed(orc):
         ctx.hrot_dh_mac(one, gs, rks, pt, o_dh, level=ell)
     torch.cuda.synchronize()
     want = [host(o_mult).copy(), host(o_low).copy(), host(o_rot).copy(), host(o_dh).copy()]
+    ctx.set_overlap(overlap)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
         ctx.hmult_relin_at(ell, ct1, ct2, key, o_mult)
