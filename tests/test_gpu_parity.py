@@ -574,3 +574,35 @@ def test_two_stream_overlap_gives_identical_results(orc):
                 assert np.array_equal(a, b)
     finally:
         ctx.set_overlap(False)
+
+
+def test_caller_supplied_roots(orc):
+    """A context created with the caller's own primitive 2N-th roots (odd powers of the minimal ones) transforms,
+    rotates and switches keys with those roots, like the oracle given the same ones; a root of the wrong order is
+    rejected on the host."""
+    from paper_2310_16530_amd import binding
+    ps = synth.small_params(13, 4, 2, 2)
+    base = orc.Params(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+    rng = np.random.default_rng(515)
+    psi = [pow(r, int(2 * rng.integers(1, ps.N) + 1), p) for r, p in zip(base.psi, ps.primes)]
+    assert psi != base.psi
+    P = orc.Params(ps.logN, ps.L, ps.K, ps.dnum, ps.primes, psi)
+    ctx = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes, psi=psi)
+    assert [ctx.psi(i) for i in range(ps.L + ps.K)] == psi
+    x = synth.uniform_residues(rng, ps.primes, ps.N, lead=(2,))
+    assert np.array_equal(host(ctx.ntt(dev(x))), orc.ntt_batch(x, P, 0))
+    assert not np.array_equal(host(ctx.ntt(dev(x))), orc.ntt_batch(x, base, 0))
+    assert np.array_equal(host(ctx.intt(dev(x))), orc.ntt_batch(x, P, 0, inverse=True))
+    key = synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2))
+    ct1 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2, 2))
+    ct2 = synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(2, 2))
+    g = synth.galois_element(5, ps.logN)
+    hm = host(ctx.hmult_relin(dev(ct1), dev(ct2), dev(key)))
+    hr = host(ctx.hrot(dev(ct1), g, dev(key)))
+    for b in range(2):
+        assert np.array_equal(hm[b], orc.hmult_relin(ct1[b], ct2[b], key, P)), b
+        assert np.array_equal(hr[b], orc.hrot(ct1[b], g, key, P)), b
+    bad = list(psi)
+    bad[1] = pow(psi[1], 2, ps.primes[1])       # order N, not 2N
+    with pytest.raises(binding.CkksError):
+        binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes, psi=bad)
