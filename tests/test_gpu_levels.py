@@ -591,3 +591,46 @@ def test_factorised_transform_chain(orc, shape):
                                                    pt, P), P)
         assert np.array_equal(host(d_ct), o_ct), s
         stride *= n1 * n2
+
+
+def test_operands_and_workspace_beyond_4_gib(orc):
+    """1100 ciphertexts at N = 2^16: every operand, result and workspace part is larger than 4 GiB, so word offsets
+    that were computed in 32 bits would wrap.  Inputs are drawn on the device; first, middle and last entries are
+    compared with the oracle, with and without the library's second stream."""
+    import torch
+    ps = synth.small_params(16, 4, 2, 2)
+    ctx, P = gpu_ctx(ps), orc_params(orc, ps)
+    B, N, L = 1100, ps.N, ps.L
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+
+    def draw():
+        x = torch.empty((B, 2, L, N), dtype=torch.int64, device="cuda")
+        for i, q in enumerate(ps.q_primes):
+            x[:, :, i, :] = torch.randint(0, q, (B, 2, N), generator=gen, device="cuda", dtype=torch.int64)
+        return x
+
+    ct1, ct2 = draw(), draw()
+    assert ct1.numel() * 8 > 1 << 32
+    key = synth.uniform_residues(np.random.default_rng(3), ps.primes, N, lead=(ps.dnum, 2))
+    d_key = dev(key)
+    g = synth.galois_element(11, ps.logN)
+    try:
+        for overlap in (False, True):
+            _say("1100 ciphertexts, second stream", overlap)
+            ctx.set_overlap(overlap)
+            hm = ctx.hmult_relin(ct1, ct2, d_key)
+            hr = ctx.hrot(ct1, g, d_key)
+            ks = ctx.keyswitch_at(L, ct1[:, 0].contiguous(), d_key)
+            rs = ctx.rescale(L, ct1)
+            for b in (0, 549, 1099):
+                a1, a2 = host(ct1[b]), host(ct2[b])
+                assert np.array_equal(host(hm[b]), orc.hmult_relin(a1, a2, key, P)), ("hmult", b)
+                assert np.array_equal(host(hr[b]), orc.hrot(a1, g, key, P)), ("hrot", b)
+                assert np.array_equal(host(ks[b]), orc.keyswitch_level(a1[0], key, P)), ("keyswitch", b)
+                assert np.array_equal(host(rs[b]), orc.rescale(a1[None], P)[0]), ("rescale", b)
+            del hm, hr, ks, rs
+    finally:
+        ctx.set_overlap(False)
+        ctx._ws.clear()          # the cached context of the test module should not keep tens of GiB of workspace
+        torch.cuda.empty_cache()
