@@ -126,6 +126,36 @@ def test_random_chains_levels_and_operations(orc, seed):
     logN, qf, pf, dnum = _random_case(500 + seed) if seed < 100 else _random_case(500 + seed, 32, 16)
     ps = synth.mixed_params(logN, qf, pf, dnum, "random%d" % seed)
     _say("seed", seed, "logN", logN, "q bits", qf, "p bits", pf, "dnum", dnum)
+    _every_composed_operation_once(orc, ps, seed)
+
+
+def _edge_case(seed):
+    """Primes drawn from the edges of what a context accepts: the smallest = 1 mod 2N, either side of 2^28 (below it
+    a conversion target is converted with integers), either side of 3*2^48 (the FP64 / integer bound), 53-54 bits,
+    and just below 2^61."""
+    rng = np.random.default_rng(47000 + seed)
+    logN = int(rng.choice([12, 12, 13, 14]))
+    floors = [logN + 1, logN + 2, 17, 20, 24, (1 << 28) - (1 << 20), (1 << 28) + 1, 31, 32, 33, 40,
+              FP_LIMIT - (1 << 24), FP_LIMIT - (1 << 40), FP_LIMIT, FP_LIMIT + (1 << 30), 50, 52, 53, 54, 60,
+              (1 << 61) - (1 << 26), (1 << 61) - (1 << 40)]
+    L, K = int(rng.integers(1, 9)), int(rng.integers(1, 6))
+    dnum = int(rng.choice([d for d in range(1, L + 1) if -(-L // -(-L // d)) == d]))
+    qf = [int(floors[i]) for i in rng.integers(0, len(floors), size=L)]
+    pf = [int(floors[i]) for i in rng.integers(0, len(floors), size=K)]
+    return logN, qf, pf, dnum
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_primes_at_the_edges_of_the_accepted_range(orc, seed):
+    logN, qf, pf, dnum = _edge_case(seed)
+    ps = synth.mixed_params(logN, qf, pf, dnum, "edge%d" % seed)
+    assert all(p < 1 << 61 for p in ps.primes)
+    _say("seed", seed, "logN", logN, "prime bits", [p.bit_length() for p in ps.primes], "dnum", dnum)
+    _every_composed_operation_once(orc, ps, seed, corners=True)
+
+
+def _every_composed_operation_once(orc, ps, seed, corners=False):
+    logN = ps.logN
     from paper_2310_16530_amd import binding
     ctx = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)     # not cached: every seed has its own chain
     ctx.set_overlap(seed % 2 == 1)
@@ -138,6 +168,13 @@ def test_random_chains_levels_and_operations(orc, seed):
     d_key = dev(key)
     ct1 = synth.uniform_residues(rng, q, N, lead=(2, 2))
     ct2 = synth.uniform_residues(rng, q, N, lead=(2, 2))
+    if corners:  # extreme residues against each other in every limb, also in the key
+        for i, p in enumerate(q):
+            ct1[0, :, i, :6] = [0, 1, p - 1, p - 2, p // 2, p // 2 + 1]
+            ct2[0, :, i, :6] = [p - 1, p - 1, p - 1, 0, p // 2, 1]
+        for i, p in enumerate(ps.primes):
+            key[:, :, i, :3] = [p - 1, 0, 1]
+        d_key = dev(key)
     g = synth.galois_element(int(rng.integers(1, 100)), logN)
     hm = host(ctx.hmult_relin_at(ell, dev(ct1), dev(ct2), d_key))
     hr = host(ctx.hrot_at(ell, dev(ct1), g, d_key))
