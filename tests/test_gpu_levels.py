@@ -634,3 +634,37 @@ def test_operands_and_workspace_beyond_4_gib(orc):
         ctx.set_overlap(False)
         ctx._ws.clear()          # the cached context of the test module should not keep tens of GiB of workspace
         torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("overlap", [False, True])
+def test_calls_on_two_caller_streams_at_once(orc, overlap):
+    """One context used under two torch streams: the binding keeps one workspace per stream, so an HMult batch and
+    a rotation batch may run at the same time (the library's own second stream, when on, is shared by both)."""
+    import torch
+    from paper_2310_16530_amd import binding
+    ps = synth.small_params(14, 6, 3, 2)
+    ctx = binding.Context(ps.logN, ps.L, ps.K, ps.dnum, ps.primes)
+    rng = np.random.default_rng(61)
+    B = 6
+    ct1 = dev(synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2)))
+    ct2 = dev(synth.uniform_residues(rng, ps.q_primes, ps.N, lead=(B, 2)))
+    evk = dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)))
+    rk = dev(synth.uniform_residues(rng, ps.primes, ps.N, lead=(ps.dnum, 2)))
+    g = synth.galois_element(3, ps.logN)
+    want1, want2 = host(ctx.hmult_relin(ct1, ct2, evk)).copy(), host(ctx.hrot(ct1, g, rk)).copy()
+    P = orc_params(orc, ps)
+    assert np.array_equal(want1[B - 1], orc.hmult_relin(host(ct1[B - 1]), host(ct2[B - 1]), host(evk), P))
+    ctx.set_overlap(overlap)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    o1, o2 = torch.empty_like(ct1), torch.empty_like(ct1)
+    for rep in range(5):
+        o1.fill_(1)
+        o2.fill_(2)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s1):
+            ctx.hmult_relin(ct1, ct2, evk, o1)
+        with torch.cuda.stream(s2):
+            ctx.hrot(ct1, g, rk, o2)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(o1), want1), ("hmult", rep)
+        assert np.array_equal(host(o2), want2), ("hrot", rep)
