@@ -588,7 +588,7 @@ struct MfmaConvArgs {
 // sum_g 256^g S_g reduced to |.| <= (0.5 + 2^-15) m, exactly: lo = digits 0..3 (below 2^46), hi = digits 4..6 times
 // 2^32 (an integer multiple of 2^32 with 38 significant bits: exact); the quotient estimate of (hi + lo) / m is off
 // by less than 2^-15 before rounding, hi - c*m is an integer below 2^53 in magnitude, so the fma and the sum are exact.
-// (Summing the digits with 64-bit integer multiply-adds onto the bit pattern of a double, which avoids the half-rate
+// (Summing the digits with 64-bit integer multiply-adds onto the bit pattern of a double, which avoids the
 // i32 -> f64 conversions, was measured 5 % slower on the kernel.)
 __device__ __forceinline__ double conv_recombine(const v16i& s, int b, const FpAr::Mod& m) {
     const double lo = __builtin_fma((double)s[b + 3], 16777216.0,

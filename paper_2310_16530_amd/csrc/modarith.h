@@ -7,8 +7,9 @@
 //   * Montgomery reduction of a 128-bit accumulator: acc * 2^-64 mod q in [0, 2q) for acc < q*2^64.
 //
 // FpAr   -- residues held as integer-valued doubles (possibly negative), primes below 3*2^48.
-//   CDNA4 issues FP64 FMA at full rate while 32-bit integer multiplies are several times slower,
-//   so for the ~50-bit ciphertext primes the butterflies run on the FP64 pipe.  Everything is
+//   On CDNA4 an FP64 FMA issues at the rate of one 32-bit integer multiply (four cycles per wave), and a Shoup
+//   product of 64-bit words needs ten of those, so for the ~50-bit ciphertext primes the butterflies run on the
+//   FP64 pipe.  Everything is
 //   exact: for integers a, w with |a| <= A*q (A <= 8), 0 <= w < q < 3*2^48,
 //       h = fl(a*w), l = fma(a, w, -h)          (a*w = h + l exactly)
 //       c = rint(fl(h * fl(1/q)))               (|c - a*w/q| <= 0.5 + 3A/8)
